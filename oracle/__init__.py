@@ -1,0 +1,232 @@
+"""CPU oracle of the Spark-FFN sparse decode path -- TEST INFRASTRUCTURE ONLY.
+
+Thin ctypes access to ``spark_oracle.c`` (plain C, double precision, written from the
+paper's definitions: Eq.2, Eq.9-11 of arXiv 2506.06644) plus the two set-level steps that
+need no arithmetic (union of per-token active sets, batching = one token at a time).
+
+Nothing in the product imports this package; only tests/, the smoke check and the
+benchmark's ``cpu_baseline`` leg do.  It imports nothing from the HIP library or its
+binding.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+import subprocess
+from dataclasses import dataclass
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "spark_oracle.c")
+_LIB = os.path.join(_HERE, "libspark_oracle.so")
+
+FILL_ZERO, FILL_NEG_INF = 0, 1
+GELU_ERF, GELU_TANH = 0, 1
+
+_lib = None
+
+
+def build(force: bool = False) -> str:
+    """Compile the oracle with gcc (``-O2 -fopenmp``); returns the library path."""
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+        cmd = ["gcc", "-O2", "-std=c11", "-fPIC", "-shared", "-fopenmp", "-Wall", "-Wextra",
+               "-o", _LIB, _SRC, "-lm"]
+        subprocess.run(cmd, check=True)
+    return _LIB
+
+
+def _load():
+    global _lib
+    if _lib is not None:
+        return _lib
+    build()
+    lib = ctypes.CDLL(_LIB)
+    c_d, c_i64, c_int = ctypes.c_double, ctypes.c_int64, ctypes.c_int
+    vp = ctypes.c_void_p
+    lib.spark_ref_max_threads.restype = c_int
+    lib.spark_ref_normal_cdf.restype = c_d
+    lib.spark_ref_normal_cdf.argtypes = [c_d]
+    lib.spark_ref_normal_quantile.restype = c_d
+    lib.spark_ref_normal_quantile.argtypes = [c_d]
+    lib.spark_ref_gelu.restype = c_d
+    lib.spark_ref_gelu.argtypes = [c_d, c_int]
+    lib.spark_ref_stat_topk.restype = c_int
+    lib.spark_ref_stat_topk.argtypes = [vp, c_i64, c_i64, c_int, vp, vp, vp, vp]
+    lib.spark_ref_stat_topk_rows.restype = c_int
+    lib.spark_ref_stat_topk_rows.argtypes = [vp, c_i64, c_i64, c_i64, c_i64, c_int, vp, c_i64,
+                                             vp, vp, vp, vp, c_i64, c_int]
+    lib.spark_ref_exact_topk.restype = c_int
+    lib.spark_ref_exact_topk.argtypes = [vp, c_i64, c_i64, vp]
+    lib.spark_ref_exact_topk_rows.restype = c_int
+    lib.spark_ref_exact_topk_rows.argtypes = [vp, c_i64, c_i64, c_i64, c_i64, vp, c_int]
+    lib.spark_ref_spark_ffn.restype = c_int
+    lib.spark_ref_spark_ffn.argtypes = [vp, vp, vp, vp, c_i64, c_i64, c_i64, c_i64, c_int, c_int,
+                                        vp, vp, vp, vp, vp, vp, vp, vp, c_int]
+    _lib = lib
+    return lib
+
+
+def _ptr(a):
+    return None if a is None else a.ctypes.data_as(ctypes.c_void_p)
+
+
+def _check(rc: int, what: str):
+    if rc != 0:
+        names = {1: "null pointer", 2: "bad shape", 3: "k out of range"}
+        raise ValueError(f"{what}: {names.get(rc, rc)}")
+
+
+def max_threads() -> int:
+    return int(_load().spark_ref_max_threads())
+
+
+def normal_cdf(z: float) -> float:
+    return float(_load().spark_ref_normal_cdf(float(z)))
+
+
+def normal_quantile(p: float) -> float:
+    """Q(p) of the standard Gaussian (text after Eq.11)."""
+    return float(_load().spark_ref_normal_quantile(float(p)))
+
+
+def gelu(x: float, kind: int = GELU_ERF) -> float:
+    return float(_load().spark_ref_gelu(float(x), int(kind)))
+
+
+@dataclass
+class StatTopK:
+    y: np.ndarray        # [d] float64, Eq.10 output
+    mean: float
+    std: float
+    z: float             # Q(1 - k/d)
+    theta: float         # Eq.11
+    idx: np.ndarray      # ascending active indices, int32
+    count: int
+
+
+def stat_topk(x, k: int, fill: int = FILL_ZERO) -> StatTopK:
+    """Statistical top-k of one vector (Eq.9-11)."""
+    x = np.ascontiguousarray(x, dtype=np.float64)
+    if x.ndim != 1:
+        raise ValueError("stat_topk takes one vector")
+    d = x.shape[0]
+    y = np.empty(d, np.float64)
+    stats = np.empty(4, np.float64)
+    idx = np.empty(max(d, 1), np.int32)
+    cnt = np.zeros(1, np.int64)
+    rc = _load().spark_ref_stat_topk(_ptr(x), d, int(k), int(fill), _ptr(y), _ptr(stats),
+                                     _ptr(idx), _ptr(cnt))
+    _check(rc, "stat_topk")
+    m = int(cnt[0])
+    return StatTopK(y, float(stats[0]), float(stats[1]), float(stats[2]), float(stats[3]),
+                    idx[:m].copy(), m)
+
+
+@dataclass
+class StatTopKRows:
+    y: np.ndarray | None      # [rows, d] float64
+    theta: np.ndarray         # [rows] float64
+    std: np.ndarray           # [rows] float64
+    count: np.ndarray         # [rows] int64
+    idx: np.ndarray | None    # [rows, d] int32, first count[row] entries valid
+
+
+def stat_topk_rows(x, k: int, fill: int = FILL_ZERO, want_y: bool = True, want_idx: bool = True,
+                   threads: int = 0) -> StatTopKRows:
+    """Row-wise statistical top-k over x[rows, d]."""
+    x = np.ascontiguousarray(x, dtype=np.float64)
+    if x.ndim != 2:
+        raise ValueError("stat_topk_rows takes a matrix")
+    rows, d = x.shape
+    y = np.empty((rows, d), np.float64) if want_y else None
+    theta = np.empty(rows, np.float64)
+    std = np.empty(rows, np.float64)
+    count = np.zeros(rows, np.int64)
+    idx = np.full((rows, d), -1, np.int32) if want_idx else None
+    rc = _load().spark_ref_stat_topk_rows(_ptr(x), rows, d, d, int(k), int(fill), _ptr(y), d,
+                                          _ptr(theta), _ptr(std), _ptr(count), _ptr(idx), d,
+                                          int(threads))
+    _check(rc, "stat_topk_rows")
+    return StatTopKRows(y, theta, std, count, idx)
+
+
+def exact_topk(x, k: int) -> np.ndarray:
+    """Indices of the k largest entries by sorting (ties: lower index), ascending."""
+    x = np.ascontiguousarray(x, dtype=np.float64)
+    idx = np.empty(max(int(k), 1), np.int32)
+    rc = _load().spark_ref_exact_topk(_ptr(x), x.shape[0], int(k), _ptr(idx))
+    _check(rc, "exact_topk")
+    return idx[: int(k)].copy()
+
+
+def exact_topk_rows(x, k: int, threads: int = 0) -> np.ndarray:
+    x = np.ascontiguousarray(x, dtype=np.float64)
+    rows, d = x.shape
+    idx = np.empty((rows, int(k)), np.int32)
+    rc = _load().spark_ref_exact_topk_rows(_ptr(x), rows, d, d, int(k), _ptr(idx), int(threads))
+    _check(rc, "exact_topk_rows")
+    return idx
+
+
+@dataclass
+class SparkFFN:
+    y: np.ndarray        # [d_model] float64
+    s: np.ndarray        # [d_ff] predictor scores
+    a: np.ndarray        # [d_ff] StatTop_k(s)
+    u: np.ndarray        # [d_ff] GELU(a) * (K2^T q[r:])
+    mean: float
+    std: float
+    z: float
+    theta: float
+    idx: np.ndarray      # ascending active set
+    count: int
+    macs: tuple          # multiply-adds spent on (K1, K2, V)
+
+
+def spark_ffn(k1n, k2n, vn, q, k: int, gelu_kind: int = GELU_ERF, skip_inactive: bool = False,
+              threads: int = 0) -> SparkFFN:
+    """One Spark-FFN layer for one token (Eq.2); weights neuron-major float32 arrays."""
+    k1n = np.ascontiguousarray(k1n, dtype=np.float32)
+    k2n = np.ascontiguousarray(k2n, dtype=np.float32)
+    vn = np.ascontiguousarray(vn, dtype=np.float32)
+    q = np.ascontiguousarray(q, dtype=np.float32)
+    d_ff, r = k1n.shape
+    d_model = vn.shape[1]
+    if k2n.shape != (d_ff, d_model - r) or vn.shape[0] != d_ff or q.shape != (d_model,):
+        raise ValueError("spark_ffn: inconsistent shapes")
+    y = np.empty(d_model, np.float64)
+    s = np.empty(d_ff, np.float64)
+    a = np.empty(d_ff, np.float64)
+    u = np.empty(d_ff, np.float64)
+    stats = np.empty(4, np.float64)
+    idx = np.empty(d_ff, np.int32)
+    cnt = np.zeros(1, np.int64)
+    macs = np.zeros(3, np.int64)
+    rc = _load().spark_ref_spark_ffn(_ptr(k1n), _ptr(k2n), _ptr(vn), _ptr(q), d_model, d_ff, r,
+                                     int(k), int(gelu_kind), int(bool(skip_inactive)), _ptr(y),
+                                     _ptr(s), _ptr(a), _ptr(u), _ptr(stats), _ptr(idx),
+                                     _ptr(cnt), _ptr(macs), int(threads))
+    _check(rc, "spark_ffn")
+    m = int(cnt[0])
+    return SparkFFN(y, s, a, u, float(stats[0]), float(stats[1]), float(stats[2]),
+                    float(stats[3]), idx[:m].copy(), m, tuple(int(v) for v in macs))
+
+
+def spark_ffn_batch(k1n, k2n, vn, q, k: int, gelu_kind: int = GELU_ERF,
+                    skip_inactive: bool = True, threads: int = 0):
+    """Batch of tokens: every token is evaluated on its own (Appendix B: individual masks
+    decide the computation); the union of the active sets only says which rows a batched
+    kernel has to load and never changes any y_b.  Returns (list of SparkFFN, union idx)."""
+    q = np.asarray(q, dtype=np.float32)
+    outs = [spark_ffn(k1n, k2n, vn, q[b], k, gelu_kind, skip_inactive, threads)
+            for b in range(q.shape[0])]
+    return outs, union_of([o.idx for o in outs])
+
+
+def union_of(index_sets) -> np.ndarray:
+    """Ascending union of active index sets."""
+    u = set()
+    for s in index_sets:
+        u.update(int(i) for i in s)
+    return np.array(sorted(u), dtype=np.int32)

@@ -1,0 +1,321 @@
+/*
+ * CPU oracle for the Spark-FFN sparse decode path (Spark Transformer, arXiv 2506.06644).
+ *
+ * TEST INFRASTRUCTURE ONLY.  This file is the plain, slow, double-precision statement of
+ * what the path computes, written from the paper's definitions.  It shares no code, header,
+ * table or helper with the HIP library, and the product never calls it: only tests/, the
+ * smoke check and the benchmark's cpu_baseline leg may load it.
+ *
+ * Every sum below is a straight loop in double precision in the order the definition
+ * states; there is no blocking, fusion or reordering.  OpenMP is used only across
+ * independent outputs (rows / neurons / output columns), never inside a sum, so the value
+ * of every output is the same for any thread count.
+ *
+ * Parity pins (tests/test_oracle_pins.py): quantile vs. textbook values and two library
+ * routines; count ~ k on Gaussian rows; nesting with the sort-based top-m set by brute
+ * force; zero/shift structure; affine and permutation equivariance; variational optimality;
+ * GEMV / gathered-sum steps vs. float64 matmul; sparse == dense; the FLOP identities of
+ * Eq.3/Eq.4.  The numeric values of y for the Gemma-shaped layers have no printed example
+ * in the paper: they are pinned only through the composition of these steps.
+ */
+#include <math.h>
+#include <stdint.h>
+#include <stdlib.h>
+#include <string.h>
+#ifdef _OPENMP
+#include <omp.h>
+#endif
+
+#define REF_OK 0
+#define REF_ERR_NULL 1
+#define REF_ERR_SHAPE 2
+#define REF_ERR_K 3
+
+#define REF_FILL_ZERO 0
+#define REF_FILL_NEG_INF 1
+
+#define REF_GELU_ERF 0
+#define REF_GELU_TANH 1
+
+int spark_ref_max_threads(void) {
+#ifdef _OPENMP
+  return omp_get_max_threads();
+#else
+  return 1;
+#endif
+}
+
+/* Standard normal CDF, Phi(z) = erfc(-z / sqrt 2) / 2. */
+double spark_ref_normal_cdf(double z) { return 0.5 * erfc(-z / sqrt(2.0)); }
+
+/*
+ * Q(p): quantile of the standard Gaussian (Section 3, text after Eq.11).  The paper
+ * leaves the evaluation method open, so the oracle solves Phi(z) = p directly: bisection on a
+ * bracket that certainly contains the root, run until the bracket stops shrinking in
+ * double precision.  For p > 1/2 the symmetric problem is solved so the tail keeps its
+ * relative accuracy.
+ */
+double spark_ref_normal_quantile(double p) {
+  if (!(p > 0.0) || !(p < 1.0)) {
+    if (p == 0.0) return -INFINITY;
+    if (p == 1.0) return INFINITY;
+    return NAN;
+  }
+  if (p == 0.5) return 0.0;
+  if (p > 0.5) return -spark_ref_normal_quantile(1.0 - p);
+  double lo = -40.0, hi = 0.0; /* Phi(-40) underflows to 0 < p < 1/2 = Phi(0) */
+  for (int it = 0; it < 400; ++it) {
+    double mid = 0.5 * (lo + hi);
+    if (mid <= lo || mid >= hi) break;
+    if (spark_ref_normal_cdf(mid) < p)
+      lo = mid;
+    else
+      hi = mid;
+  }
+  return 0.5 * (lo + hi);
+}
+
+/* GELU(x) = x * Phi(x) (exact form); the tanh form is the common approximation of it. */
+double spark_ref_gelu(double x, int kind) {
+  if (kind == REF_GELU_TANH) {
+    const double c = sqrt(2.0 / acos(-1.0));
+    return 0.5 * x * (1.0 + tanh(c * (x + 0.044715 * x * x * x)));
+  }
+  return 0.5 * x * (1.0 + erf(x / sqrt(2.0)));
+}
+
+/*
+ * Statistical top-k of one vector (Eq.9, Eq.10, Eq.11).
+ *   mean  = (1/d) sum x_i
+ *   std   = sqrt( (1/(d-1)) sum (x_i - mean)^2 )
+ *   theta = mean + std * Q(1 - k/d)
+ *   y_i   = x_i - theta  if x_i > theta, else 0   (or -inf for the Top_k^(-inf) variant)
+ * Active set = { i : x_i > theta } (strict, as counted in Theorem 1), ascending.
+ * stats[4] = { mean, std, Q(1-k/d), theta }.  y, idx, count may be NULL.
+ */
+int spark_ref_stat_topk(const double* x, int64_t d, int64_t k, int fill, double* y,
+                        double* stats, int32_t* idx, int64_t* count) {
+  if (!x) return REF_ERR_NULL;
+  if (d < 2) return REF_ERR_SHAPE;
+  if (k < 1 || k > d - 1) return REF_ERR_K;
+  double sum = 0.0;
+  for (int64_t i = 0; i < d; ++i) sum += x[i];
+  const double mean = sum / (double)d;
+  double ss = 0.0;
+  for (int64_t i = 0; i < d; ++i) {
+    const double c = x[i] - mean;
+    ss += c * c;
+  }
+  const double std = sqrt(ss / (double)(d - 1));
+  const double z = spark_ref_normal_quantile(1.0 - (double)k / (double)d);
+  const double theta = mean + std * z;
+  int64_t m = 0;
+  for (int64_t i = 0; i < d; ++i) {
+    const int active = x[i] > theta;
+    if (y) y[i] = active ? x[i] - theta : (fill == REF_FILL_NEG_INF ? -INFINITY : 0.0);
+    if (active) {
+      if (idx) idx[m] = (int32_t)i;
+      ++m;
+    }
+  }
+  if (stats) {
+    stats[0] = mean;
+    stats[1] = std;
+    stats[2] = z;
+    stats[3] = theta;
+  }
+  if (count) *count = m;
+  return REF_OK;
+}
+
+/* Row-wise statistical top-k over x[rows][d] (the training / prefill shape). */
+int spark_ref_stat_topk_rows(const double* x, int64_t rows, int64_t d, int64_t ldx, int64_t k,
+                             int fill, double* y, int64_t ldy, double* theta, double* std,
+                             int64_t* count, int32_t* idx, int64_t ldidx, int threads) {
+  if (!x) return REF_ERR_NULL;
+  if (rows < 0 || d < 2 || ldx < d || (y && ldy < d) || (idx && ldidx < d)) return REF_ERR_SHAPE;
+  if (k < 1 || k > d - 1) return REF_ERR_K;
+#ifdef _OPENMP
+  if (threads <= 0) threads = omp_get_max_threads();
+#endif
+  (void)threads;
+#pragma omp parallel for num_threads(threads) schedule(static)
+  for (int64_t row = 0; row < rows; ++row) {
+    double st[4];
+    int64_t m = 0;
+    spark_ref_stat_topk(x + row * ldx, d, k, fill, y ? y + row * ldy : NULL, st,
+                        idx ? idx + row * ldidx : NULL, &m);
+    if (theta) theta[row] = st[3];
+    if (std) std[row] = st[1];
+    if (count) count[row] = m;
+  }
+  return REF_OK;
+}
+
+/*
+ * Exact top-k by sorting: indices of the k largest entries (ties: lower index first),
+ * returned ascending by index.  Used to measure how far the statistical set is from the
+ * sort-based one, and as the brute-force side of the nesting pin.
+ */
+typedef struct {
+  double v;
+  int32_t i;
+} ref_pair;
+
+static int ref_pair_desc(const void* a, const void* b) {
+  const ref_pair* pa = (const ref_pair*)a;
+  const ref_pair* pb = (const ref_pair*)b;
+  if (pa->v > pb->v) return -1;
+  if (pa->v < pb->v) return 1;
+  return (pa->i > pb->i) - (pa->i < pb->i);
+}
+
+static int ref_i32_asc(const void* a, const void* b) {
+  const int32_t ia = *(const int32_t*)a, ib = *(const int32_t*)b;
+  return (ia > ib) - (ia < ib);
+}
+
+int spark_ref_exact_topk(const double* x, int64_t d, int64_t k, int32_t* idx) {
+  if (!x || !idx) return REF_ERR_NULL;
+  if (d < 1) return REF_ERR_SHAPE;
+  if (k < 0 || k > d) return REF_ERR_K;
+  ref_pair* p = (ref_pair*)malloc((size_t)d * sizeof(ref_pair));
+  if (!p) return REF_ERR_SHAPE;
+  for (int64_t i = 0; i < d; ++i) {
+    p[i].v = x[i];
+    p[i].i = (int32_t)i;
+  }
+  qsort(p, (size_t)d, sizeof(ref_pair), ref_pair_desc);
+  for (int64_t i = 0; i < k; ++i) idx[i] = p[i].i;
+  qsort(idx, (size_t)k, sizeof(int32_t), ref_i32_asc);
+  free(p);
+  return REF_OK;
+}
+
+int spark_ref_exact_topk_rows(const double* x, int64_t rows, int64_t d, int64_t ldx, int64_t k,
+                              int32_t* idx, int threads) {
+  if (!x || !idx) return REF_ERR_NULL;
+#ifdef _OPENMP
+  if (threads <= 0) threads = omp_get_max_threads();
+#endif
+  (void)threads;
+  int rc = REF_OK;
+#pragma omp parallel for num_threads(threads) schedule(static)
+  for (int64_t row = 0; row < rows; ++row) {
+    int e = spark_ref_exact_topk(x + row * ldx, d, k, idx + row * k);
+    if (e != REF_OK) rc = e;
+  }
+  return rc;
+}
+
+/*
+ * One Spark-FFN layer for one token (Eq.2), weights neuron-major (row j = column j of the
+ * paper's K1 / K2 / V):
+ *   s_j = sum_{i<r} K1n[j][i] * q[i]                          predictor, all j
+ *   a   = StatTop_k(s)                                        Eq.10
+ *   g_j = sum_{i<d_model-r} K2n[j][i] * q[r+i]
+ *   u_j = GELU(a_j) * g_j                                     sigma = GELU on the shifted value
+ *   y_c = sum_j u_j * Vn[j][c]
+ * skip_inactive = 0: the dense definition (every j in every sum).
+ * skip_inactive = 1: g and the y-sum run over the active set only; the skipped terms are
+ *                    exact zeros (GELU(0) = 0), so both give the same y.
+ * Weights and q arrive as float (the exact widening of their bf16 / fp32 storage).
+ * Outputs (any may be NULL): y[d_model], s[d_ff], a[d_ff], u[d_ff], stats[4], idx[d_ff],
+ * count, macs[3] = multiply-adds spent on K1, K2, V.
+ */
+int spark_ref_spark_ffn(const float* k1n, const float* k2n, const float* vn, const float* q,
+                        int64_t d_model, int64_t d_ff, int64_t r, int64_t k, int gelu_kind,
+                        int skip_inactive, double* y, double* s_out, double* a_out,
+                        double* u_out, double* stats, int32_t* idx_out, int64_t* count_out,
+                        int64_t* macs, int threads) {
+  if (!k1n || !k2n || !vn || !q) return REF_ERR_NULL;
+  if (d_ff < 2 || d_model < 2 || r < 1 || r > d_model - 1) return REF_ERR_SHAPE;
+  if (k < 1 || k > d_ff - 1) return REF_ERR_K;
+#ifdef _OPENMP
+  if (threads <= 0) threads = omp_get_max_threads();
+#endif
+  (void)threads;
+  const int64_t r2 = d_model - r;
+  double* s = (double*)malloc((size_t)d_ff * sizeof(double));
+  double* a = (double*)malloc((size_t)d_ff * sizeof(double));
+  double* u = (double*)malloc((size_t)d_ff * sizeof(double));
+  int32_t* idx = (int32_t*)malloc((size_t)d_ff * sizeof(int32_t));
+  if (!s || !a || !u || !idx) {
+    free(s); free(a); free(u); free(idx);
+    return REF_ERR_SHAPE;
+  }
+  int64_t mac1 = 0, mac2 = 0, mac3 = 0;
+
+#pragma omp parallel for num_threads(threads) schedule(static)
+  for (int64_t j = 0; j < d_ff; ++j) {
+    double acc = 0.0;
+    for (int64_t i = 0; i < r; ++i) acc += (double)k1n[j * r + i] * (double)q[i];
+    s[j] = acc;
+  }
+  mac1 = d_ff * r;
+
+  double st[4];
+  int64_t m = 0;
+  int rc = spark_ref_stat_topk(s, d_ff, k, REF_FILL_ZERO, a, st, idx, &m);
+  if (rc != REF_OK) {
+    free(s); free(a); free(u); free(idx);
+    return rc;
+  }
+
+  if (skip_inactive) {
+    for (int64_t j = 0; j < d_ff; ++j) u[j] = 0.0;
+#pragma omp parallel for num_threads(threads) schedule(static)
+    for (int64_t t = 0; t < m; ++t) {
+      const int64_t j = idx[t];
+      double g = 0.0;
+      for (int64_t i = 0; i < r2; ++i) g += (double)k2n[j * r2 + i] * (double)q[r + i];
+      u[j] = spark_ref_gelu(a[j], gelu_kind) * g;
+    }
+    mac2 = m * r2;
+  } else {
+#pragma omp parallel for num_threads(threads) schedule(static)
+    for (int64_t j = 0; j < d_ff; ++j) {
+      double g = 0.0;
+      for (int64_t i = 0; i < r2; ++i) g += (double)k2n[j * r2 + i] * (double)q[r + i];
+      u[j] = spark_ref_gelu(a[j], gelu_kind) * g;
+    }
+    mac2 = d_ff * r2;
+  }
+
+  if (y) {
+    if (skip_inactive) {
+#pragma omp parallel for num_threads(threads) schedule(static)
+      for (int64_t c = 0; c < d_model; ++c) {
+        double acc = 0.0;
+        for (int64_t t = 0; t < m; ++t) {
+          const int64_t j = idx[t];
+          acc += u[j] * (double)vn[j * d_model + c];
+        }
+        y[c] = acc;
+      }
+      mac3 = m * d_model;
+    } else {
+#pragma omp parallel for num_threads(threads) schedule(static)
+      for (int64_t c = 0; c < d_model; ++c) {
+        double acc = 0.0;
+        for (int64_t j = 0; j < d_ff; ++j) acc += u[j] * (double)vn[j * d_model + c];
+        y[c] = acc;
+      }
+      mac3 = d_ff * d_model;
+    }
+  }
+
+  if (s_out) memcpy(s_out, s, (size_t)d_ff * sizeof(double));
+  if (a_out) memcpy(a_out, a, (size_t)d_ff * sizeof(double));
+  if (u_out) memcpy(u_out, u, (size_t)d_ff * sizeof(double));
+  if (idx_out) memcpy(idx_out, idx, (size_t)m * sizeof(int32_t));
+  if (stats) memcpy(stats, st, sizeof(st));
+  if (count_out) *count_out = m;
+  if (macs) {
+    macs[0] = mac1;
+    macs[1] = mac2;
+    macs[2] = mac3;
+  }
+  free(s); free(a); free(u); free(idx);
+  return REF_OK;
+}
