@@ -1,0 +1,169 @@
+/*
+ * spark.h -- C ABI of the MI355X (gfx950) Spark-FFN sparse decode library.
+ *
+ * The library evaluates the sparse feed-forward layer of the Spark Transformer
+ * (arXiv 2506.06644):
+ *
+ *   Spark-FFN(q; K1, K2, V, k, r) = V * ( GELU( StatTop_k(K1^T q[:r]) ) (.) (K2^T q[r:]) )     Eq.2
+ *   StatTop_k(x)   = max(x - theta, 0)                                                       Eq.9-10
+ *   theta(x, k)    = mean(x) + std(x) * Q(1 - k/d),  std with 1/(d-1)                        Eq.11
+ *
+ * as the decode pipeline of Section 2.1 / Appendix B: predictor GEMV over the first r input
+ * dimensions, statistical top-k, compaction of the active neurons, gathered GEMVs over only
+ * the active rows of K2 and V.
+ *
+ * General conventions
+ *   - All array arguments are DEVICE pointers (HIP global memory of the current device)
+ *     unless the comment says "host".  The library never allocates or frees device memory
+ *     and keeps no state between calls: every buffer, including the workspace, is owned by
+ *     the caller.
+ *   - Calls enqueue work on `hip_stream` (a hipStream_t passed as void*; NULL = the default
+ *     stream) and return without synchronising.  Outputs are valid once the stream has
+ *     been synchronised by the caller.  Two calls that share a workspace must be ordered
+ *     on one stream.
+ *   - Arguments are validated on the host before anything is launched; an invalid call
+ *     returns an error code and touches no memory.  Nothing throws or aborts across the ABI.
+ *   - Weights are "neuron-major": row j of K1n / K2n / Vn is column j of the paper's
+ *     K1 / K2 / V, so the data of one neuron is one contiguous burst.
+ *   - Base pointers of weights, q and x must be 16-byte aligned and every row must span a
+ *     multiple of 16 bytes (SPARK_ERR_ALIGN otherwise).
+ */
+#ifndef SPARK_H_
+#define SPARK_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define SPARK_VERSION 100
+#define SPARK_MAX_BATCH 64 /* tokens per spark_ffn_decode call (the paper's prefill chunk) */
+
+typedef enum {
+  SPARK_OK = 0,
+  SPARK_ERR_NULL = 1,      /* a required pointer is NULL                                    */
+  SPARK_ERR_SHAPE = 2,     /* a dimension / stride / batch is out of range                  */
+  SPARK_ERR_K = 3,         /* k outside [1, d-1] (the range of Theorem 1)                   */
+  SPARK_ERR_DTYPE = 4,     /* unknown or unsupported dtype combination                      */
+  SPARK_ERR_ALIGN = 5,     /* pointer or row pitch not 16-byte aligned                      */
+  SPARK_ERR_WORKSPACE = 6, /* workspace NULL or smaller than the matching *_workspace_bytes */
+  SPARK_ERR_DEVICE = 7     /* the HIP runtime refused a launch or a query                   */
+} spark_status;
+
+typedef enum { SPARK_F32 = 0, SPARK_BF16 = 1 } spark_dtype;
+
+/* What StatTop_k writes for entries at or below theta: 0 (Eq.10) or -inf (the Top_k^(-inf)
+ * variant used in front of a softmax, Section 3 after Eq.11). */
+typedef enum { SPARK_FILL_ZERO = 0, SPARK_FILL_NEG_INF = 1 } spark_fill;
+
+/* GELU form: exact x*Phi(x) (default) or its tanh approximation. */
+typedef enum { SPARK_GELU_ERF = 0, SPARK_GELU_TANH = 1 } spark_gelu;
+
+/* Host. Static string for a status code. */
+const char* spark_status_string(spark_status s);
+
+/* Host. Library version (SPARK_VERSION it was built with). */
+int spark_version(void);
+
+/* Host. Q(p): quantile of the standard Gaussian (Section 3, text after Eq.11), accurate to
+ * a few ulp in double.  Q(0) = -inf, Q(1) = +inf, NaN outside [0, 1]. */
+double spark_normal_quantile(double p);
+
+/* ------------------------------------------------------------------------------------------
+ * Row-wise statistical top-k (Eq.9-11), the operator applied to the [tokens x d_ff]
+ * pre-activation tensor in training / prefill and to the predictor scores in decode.
+ *
+ *   x      [rows][n] of `dt`, row pitch ldx elements (ldx >= n)                    in
+ *   k      target number of survivors per row, 1 <= k <= n-1
+ *   y      [rows][n] of `dt`, row pitch ldy; y = x - theta where x > theta,        out, optional
+ *          else the fill value.  Computed in fp32, rounded to nearest-even on
+ *          store for bf16.  May alias x exactly (in place).
+ *   theta  [rows] fp32 threshold of each row                                       out, optional
+ *   count  [rows] int32, #{i : x_i > theta} (strict), exact even if idx is capped  out, optional
+ *   idx    [rows][idx_cap] int32, ascending active indices; entries past           out, optional
+ *          min(count, idx_cap) are left untouched
+ *
+ * Statistics are accumulated in fp32 (mean first, then centred squares) whatever `dt` is.
+ * A constant row has std = 0, theta = mean and no survivor.  n >= 2 is required.
+ * Needs no workspace.  Errors: NULL x; rows < 0, n < 2, n > 2^31-1 or a pitch < n -> SHAPE;
+ * k out of range -> K; dt -> DTYPE; alignment -> ALIGN.
+ */
+spark_status spark_stat_topk(const void* x, spark_dtype dt, int64_t rows, int64_t n, int64_t ldx,
+                             int64_t k, spark_fill fill, void* y, int64_t ldy, float* theta,
+                             int32_t* count, int32_t* idx, int64_t idx_cap, void* hip_stream);
+
+/* ------------------------------------------------------------------------------------------
+ * One Spark-FFN layer (Eq.2).  Host struct holding device pointers.
+ */
+typedef struct {
+  int32_t d_model;    /* input / output width                                   */
+  int32_t d_ff;       /* number of neurons, >= 2                                */
+  int32_t r;          /* predictor width, 1 <= r <= d_model-1                   */
+  int32_t k;          /* sparsity level, 1 <= k <= d_ff-1                       */
+  int32_t wdtype;     /* spark_dtype of the three weight arrays                 */
+  int32_t gelu;       /* spark_gelu                                             */
+  const void* k1n;    /* [d_ff][r]            predictor half of the first layer */
+  const void* k2n;    /* [d_ff][d_model - r]  gated half of the first layer     */
+  const void* vn;     /* [d_ff][d_model]      second layer                      */
+} spark_ffn_layer;
+
+/* Host. Bytes of device workspace spark_ffn_decode / spark_ffn_decode_layers /
+ * spark_ffn_dense_decode need for this layer shape and batch (0 on invalid arguments). */
+size_t spark_ffn_workspace_bytes(int32_t d_model, int32_t d_ff, int32_t batch);
+
+/*
+ * Decode `batch` tokens through one layer (Section 2.1; batching as in Appendix B: each
+ * token has its own threshold and mask, the union of the masks decides which weight rows
+ * are fetched, and y[b] does not depend on the other tokens of the batch).
+ *
+ *   q             [batch][d_model] of `qdtype`, row pitch ldq elements             in
+ *   y             [batch][d_model] fp32, overwritten                               out
+ *   theta         [batch] fp32                                                     out, optional
+ *   active_count  [batch] int32, #{j : s_bj > theta_b}                             out, optional
+ *   active_idx    [batch][d_ff] int32, ascending active neurons of each token      out, optional
+ *   union_count   [1] int32, size of the union of the active sets                  out, optional
+ *   union_idx     [d_ff] int32, ascending union                                    out, optional
+ *   workspace     >= spark_ffn_workspace_bytes(d_model, d_ff, batch), 256-byte aligned
+ *
+ * Arithmetic: weights and q are widened exactly to fp32; all products and sums are fp32
+ * (bf16 x bf16 products are exact in fp32); q is never rounded by the library.
+ * 1 <= batch <= SPARK_MAX_BATCH.
+ */
+spark_status spark_ffn_decode(const spark_ffn_layer* layer, const void* q, spark_dtype qdtype,
+                              int32_t batch, int64_t ldq, float* y, float* theta,
+                              int32_t* active_count, int32_t* active_idx, int32_t* union_count,
+                              int32_t* union_idx, void* workspace, size_t workspace_bytes,
+                              void* hip_stream);
+
+/*
+ * n_layers independent layers of one shape, evaluated in order l = 0 .. n_layers-1 on the
+ * same q (host array `layers`; every layer must agree in d_model, d_ff, r, k, wdtype, gelu).
+ * Output arrays carry a leading n_layers dimension:
+ *   y [n_layers][batch][d_model], theta [n_layers][batch], active_count [n_layers][batch],
+ *   active_idx [n_layers][batch][d_ff], union_count [n_layers], union_idx [n_layers][d_ff].
+ * For batch == 1 and supported shapes this is one persistent launch that keeps the next
+ * layer's predictor rows in flight while the current layer's gather runs; results are the
+ * same as n_layers calls of spark_ffn_decode.
+ */
+spark_status spark_ffn_decode_layers(const spark_ffn_layer* layers, int32_t n_layers,
+                                     const void* q, spark_dtype qdtype, int32_t batch,
+                                     int64_t ldq, float* y, float* theta, int32_t* active_count,
+                                     int32_t* active_idx, int32_t* union_count,
+                                     int32_t* union_idx, void* workspace,
+                                     size_t workspace_bytes, void* hip_stream);
+
+/*
+ * Dense evaluation of the same layer (every neuron's K2 and V row is read; the result
+ * equals spark_ffn_decode's because inactive neurons contribute exact zeros).  It exists as
+ * the same-GPU comparison point for the sparse path (Eq.3 vs Eq.4).
+ */
+spark_status spark_ffn_dense_decode(const spark_ffn_layer* layer, const void* q,
+                                    spark_dtype qdtype, int32_t batch, int64_t ldq, float* y,
+                                    void* workspace, size_t workspace_bytes, void* hip_stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SPARK_H_ */

@@ -1,0 +1,167 @@
+"""ctypes binding of the C ABI declared in ``include/spark.h``.
+
+Argument marshalling only: tensors are PyTorch device tensors used as plain device memory
+(``data_ptr()``), the stream is the current HIP stream, and all arithmetic happens in the
+library's kernels.  There is no fallback: if ``libspark_hip.so`` has not been built the
+import of the library fails with an error that says how to build it.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Optional, Sequence
+
+import torch
+
+_PKG = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_PKG, "libspark_hip.so")
+
+F32, BF16 = 0, 1
+FILL_ZERO, FILL_NEG_INF = 0, 1
+GELU_ERF, GELU_TANH = 0, 1
+MAX_BATCH = 64
+
+EXPORTS = (
+    "spark_status_string", "spark_version", "spark_normal_quantile", "spark_stat_topk",
+    "spark_ffn_workspace_bytes", "spark_ffn_decode", "spark_ffn_decode_layers",
+    "spark_ffn_dense_decode",
+)
+
+
+class SparkError(RuntimeError):
+    def __init__(self, code: int, what: str):
+        self.code = code
+        super().__init__(f"{what}: spark_status {code} ({status_string(code)})")
+
+
+class _Layer(ctypes.Structure):
+    _fields_ = [
+        ("d_model", ctypes.c_int32), ("d_ff", ctypes.c_int32), ("r", ctypes.c_int32),
+        ("k", ctypes.c_int32), ("wdtype", ctypes.c_int32), ("gelu", ctypes.c_int32),
+        ("k1n", ctypes.c_void_p), ("k2n", ctypes.c_void_p), ("vn", ctypes.c_void_p),
+    ]
+
+
+_lib = None
+
+
+def load_library():
+    """Loads ``libspark_hip.so``; raises if it has not been built."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise ImportError(
+            f"{LIB_PATH} is missing: build it with `python -m paper_2506_06644_amd.build` "
+            "(there is no CPU or PyTorch fallback)")
+    lib = ctypes.CDLL(LIB_PATH)
+    vp, i32, i64, sz, c_int = ctypes.c_void_p, ctypes.c_int32, ctypes.c_int64, ctypes.c_size_t, ctypes.c_int
+    lib.spark_status_string.restype = ctypes.c_char_p
+    lib.spark_status_string.argtypes = [c_int]
+    lib.spark_version.restype = c_int
+    lib.spark_normal_quantile.restype = ctypes.c_double
+    lib.spark_normal_quantile.argtypes = [ctypes.c_double]
+    lib.spark_stat_topk.restype = c_int
+    lib.spark_stat_topk.argtypes = [vp, c_int, i64, i64, i64, i64, c_int, vp, i64, vp, vp, vp, i64, vp]
+    lib.spark_ffn_workspace_bytes.restype = sz
+    lib.spark_ffn_workspace_bytes.argtypes = [i32, i32, i32]
+    lib.spark_ffn_decode.restype = c_int
+    lib.spark_ffn_decode.argtypes = [ctypes.POINTER(_Layer), vp, c_int, i32, i64, vp, vp, vp, vp, vp, vp,
+                                     vp, sz, vp]
+    lib.spark_ffn_decode_layers.restype = c_int
+    lib.spark_ffn_decode_layers.argtypes = [ctypes.POINTER(_Layer), i32, vp, c_int, i32, i64, vp, vp, vp,
+                                            vp, vp, vp, vp, sz, vp]
+    lib.spark_ffn_dense_decode.restype = c_int
+    lib.spark_ffn_dense_decode.argtypes = [ctypes.POINTER(_Layer), vp, c_int, i32, i64, vp, vp, sz, vp]
+    _lib = lib
+    return lib
+
+
+def status_string(code: int) -> str:
+    return load_library().spark_status_string(int(code)).decode()
+
+
+def normal_quantile(p: float) -> float:
+    return float(load_library().spark_normal_quantile(float(p)))
+
+
+def ffn_workspace_bytes(d_model: int, d_ff: int, batch: int) -> int:
+    return int(load_library().spark_ffn_workspace_bytes(int(d_model), int(d_ff), int(batch)))
+
+
+def _dt(t: torch.Tensor) -> int:
+    if t.dtype == torch.float32:
+        return F32
+    if t.dtype == torch.bfloat16:
+        return BF16
+    return -1
+
+
+def _p(t: Optional[torch.Tensor]):
+    return None if t is None else ctypes.c_void_p(t.data_ptr())
+
+
+def _stream():
+    return ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+def _check(rc: int, what: str):
+    if rc != 0:
+        raise SparkError(rc, what)
+
+
+def spark_stat_topk(x: torch.Tensor, k: int, fill: int = FILL_ZERO, y: Optional[torch.Tensor] = None,
+                    theta: Optional[torch.Tensor] = None, count: Optional[torch.Tensor] = None,
+                    idx: Optional[torch.Tensor] = None):
+    """Row-wise statistical top-k of ``x[rows, n]`` (device tensor, fp32 or bf16)."""
+    rows, n = x.shape
+    idx_cap = 0 if idx is None else idx.shape[1]
+    rc = load_library().spark_stat_topk(
+        _p(x), _dt(x), rows, n, x.stride(0), int(k), int(fill), _p(y),
+        0 if y is None else y.stride(0), _p(theta), _p(count), _p(idx), idx_cap, _stream())
+    _check(rc, "spark_stat_topk")
+
+
+def make_layer(k1n: torch.Tensor, k2n: torch.Tensor, vn: torch.Tensor, k: int, gelu: int = GELU_ERF) -> _Layer:
+    d_ff, r = k1n.shape
+    d_model = vn.shape[1]
+    if k2n.shape != (d_ff, d_model - r) or vn.shape[0] != d_ff:
+        raise ValueError("inconsistent weight shapes")
+    if not (k1n.is_contiguous() and k2n.is_contiguous() and vn.is_contiguous()):
+        raise ValueError("weights must be contiguous neuron-major arrays")
+    if not (k1n.dtype == k2n.dtype == vn.dtype):
+        raise ValueError("the three weight arrays must share a dtype")
+    return _Layer(d_model, d_ff, r, int(k), _dt(k1n), int(gelu), k1n.data_ptr(), k2n.data_ptr(),
+                  vn.data_ptr())
+
+
+def make_workspace(d_model: int, d_ff: int, batch: int, device) -> torch.Tensor:
+    return torch.empty(ffn_workspace_bytes(d_model, d_ff, batch), dtype=torch.uint8, device=device)
+
+
+def spark_ffn_decode(layer: _Layer, q: torch.Tensor, y: torch.Tensor, workspace: torch.Tensor,
+                     theta=None, active_count=None, active_idx=None, union_count=None, union_idx=None):
+    """One Spark-FFN layer over ``q[batch, d_model]``; ``y[batch, d_model]`` fp32 is overwritten."""
+    rc = load_library().spark_ffn_decode(
+        ctypes.byref(layer), _p(q), _dt(q), q.shape[0], q.stride(0), _p(y), _p(theta), _p(active_count),
+        _p(active_idx), _p(union_count), _p(union_idx), _p(workspace), workspace.numel(), _stream())
+    _check(rc, "spark_ffn_decode")
+
+
+def spark_ffn_decode_layers(layers: Sequence[_Layer], q: torch.Tensor, y: torch.Tensor,
+                            workspace: torch.Tensor, theta=None, active_count=None, active_idx=None,
+                            union_count=None, union_idx=None):
+    """``len(layers)`` independent layers on the same ``q``; outputs carry a leading layer dim."""
+    arr = (_Layer * len(layers))(*layers)
+    rc = load_library().spark_ffn_decode_layers(
+        arr, len(layers), _p(q), _dt(q), q.shape[0], q.stride(0), _p(y), _p(theta), _p(active_count),
+        _p(active_idx), _p(union_count), _p(union_idx), _p(workspace), workspace.numel(), _stream())
+    _check(rc, "spark_ffn_decode_layers")
+
+
+def spark_ffn_dense_decode(layer: _Layer, q: torch.Tensor, y: torch.Tensor, workspace: torch.Tensor):
+    """Same layer with every K2 / V row read (the dense comparison point)."""
+    rc = load_library().spark_ffn_dense_decode(
+        ctypes.byref(layer), _p(q), _dt(q), q.shape[0], q.stride(0), _p(y), _p(workspace),
+        workspace.numel(), _stream())
+    _check(rc, "spark_ffn_dense_decode")

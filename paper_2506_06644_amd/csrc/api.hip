@@ -1,0 +1,200 @@
+// C ABI of the Spark-FFN library: host-side validation and dispatch.  See include/spark.h.
+#include "../../include/spark.h"
+
+#include <cmath>
+#include <limits>
+
+#include "spark_internal.h"
+
+namespace {
+
+bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+size_t dtype_size(int dt) { return dt == SPARK_BF16 ? 2 : 4; }
+bool dtype_ok(int dt) { return dt == SPARK_F32 || dt == SPARK_BF16; }
+
+double normal_cdf(double z) { return 0.5 * std::erfc(-z * 0.70710678118654752440); }
+
+spark_status validate_layer(const spark_ffn_layer* L) {
+  if (!L) return SPARK_ERR_NULL;
+  if (!L->k1n || !L->k2n || !L->vn) return SPARK_ERR_NULL;
+  if (!dtype_ok(L->wdtype)) return SPARK_ERR_DTYPE;
+  if (L->gelu != SPARK_GELU_ERF && L->gelu != SPARK_GELU_TANH) return SPARK_ERR_DTYPE;
+  if (L->d_ff < 2 || L->d_model < 2) return SPARK_ERR_SHAPE;
+  if (L->r < 1 || L->r > L->d_model - 1) return SPARK_ERR_SHAPE;
+  if (L->k < 1 || L->k > L->d_ff - 1) return SPARK_ERR_K;
+  const size_t ws = dtype_size(L->wdtype);
+  if ((L->r * ws) % 16 || ((L->d_model - L->r) * ws) % 16 || (L->d_model * ws) % 16) return SPARK_ERR_ALIGN;
+  if (!aligned16(L->k1n) || !aligned16(L->k2n) || !aligned16(L->vn)) return SPARK_ERR_ALIGN;
+  return SPARK_OK;
+}
+
+spark_status validate_decode(const spark_ffn_layer* L, const void* q, int qdtype, int32_t batch, int64_t ldq,
+                             const float* y, const void* workspace, size_t workspace_bytes) {
+  spark_status s = validate_layer(L);
+  if (s != SPARK_OK) return s;
+  if (!q || !y) return SPARK_ERR_NULL;
+  if (!dtype_ok(qdtype)) return SPARK_ERR_DTYPE;
+  if (batch < 1 || batch > SPARK_MAX_BATCH) return SPARK_ERR_SHAPE;
+  if (ldq < L->d_model) return SPARK_ERR_SHAPE;
+  const size_t qs = dtype_size(qdtype);
+  // the split point r and every token row must fall on a 16-byte boundary of q as well
+  if (!aligned16(q) || (ldq * qs) % 16 || (L->r * qs) % 16 || (L->d_model * qs) % 16) return SPARK_ERR_ALIGN;
+  if (!workspace) return SPARK_ERR_WORKSPACE;
+  if (reinterpret_cast<uintptr_t>(workspace) & 255u) return SPARK_ERR_WORKSPACE;
+  if (workspace_bytes < spark_ffn_workspace_bytes(L->d_model, L->d_ff, batch)) return SPARK_ERR_WORKSPACE;
+  return SPARK_OK;
+}
+
+spark::FfnProblem make_problem(const spark_ffn_layer* L, const void* q, int qdtype, int32_t batch, int64_t ldq,
+                               float* y, float* theta, int32_t* active_count, int32_t* active_idx,
+                               int32_t* union_count, int32_t* union_idx) {
+  spark::FfnProblem p;
+  p.d_model = L->d_model;
+  p.d_ff = L->d_ff;
+  p.r = L->r;
+  p.k = L->k;
+  p.w_bf16 = L->wdtype == SPARK_BF16;
+  p.q_bf16 = qdtype == SPARK_BF16;
+  p.gelu = L->gelu;
+  p.k1n = L->k1n;
+  p.k2n = L->k2n;
+  p.vn = L->vn;
+  p.q = q;
+  p.ldq = ldq;
+  p.batch = batch;
+  p.z = (float)spark_normal_quantile(1.0 - (double)L->k / (double)L->d_ff);
+  p.y = y;
+  p.theta = theta;
+  p.active_count = active_count;
+  p.active_idx = active_idx;
+  p.union_count = union_count;
+  p.union_idx = union_idx;
+  return p;
+}
+
+}  // namespace
+
+extern "C" {
+
+const char* spark_status_string(spark_status s) {
+  switch (s) {
+    case SPARK_OK: return "ok";
+    case SPARK_ERR_NULL: return "required pointer is null";
+    case SPARK_ERR_SHAPE: return "dimension, stride or batch out of range";
+    case SPARK_ERR_K: return "k outside [1, d-1]";
+    case SPARK_ERR_DTYPE: return "unsupported dtype or activation kind";
+    case SPARK_ERR_ALIGN: return "pointer or row pitch not 16-byte aligned";
+    case SPARK_ERR_WORKSPACE: return "workspace missing, misaligned or too small";
+    case SPARK_ERR_DEVICE: return "HIP runtime error";
+  }
+  return "unknown status";
+}
+
+int spark_version(void) { return SPARK_VERSION; }
+
+// Q(p) by a rational starting guess for the tail (Hastings' approximation, A&S 26.2.23)
+// polished with Halley steps on Phi(z) - p, where Phi is evaluated through erfc so the lower
+// tail keeps its relative accuracy.
+double spark_normal_quantile(double p) {
+  if (std::isnan(p) || p < 0.0 || p > 1.0) return std::numeric_limits<double>::quiet_NaN();
+  if (p == 0.0) return -std::numeric_limits<double>::infinity();
+  if (p == 1.0) return std::numeric_limits<double>::infinity();
+  if (p == 0.5) return 0.0;
+  const bool upper = p > 0.5;
+  const double pl = upper ? 1.0 - p : p;  // lower-tail mass, in (0, 1/2)
+  const double t = std::sqrt(-2.0 * std::log(pl));
+  double z = -(t - (2.515517 + t * (0.802853 + t * 0.010328)) /
+                       (1.0 + t * (1.432788 + t * (0.189269 + t * 0.001308))));
+  const double inv_sqrt_2pi = 0.39894228040143267794;
+  for (int it = 0; it < 8; ++it) {
+    const double f = normal_cdf(z) - pl;
+    const double pdf = inv_sqrt_2pi * std::exp(-0.5 * z * z);
+    if (pdf == 0.0) break;
+    const double u = f / pdf;
+    const double step = u / (1.0 + 0.5 * z * u);
+    z -= step;
+    if (std::fabs(step) <= 1e-16 * std::fabs(z)) break;
+  }
+  return upper ? -z : z;
+}
+
+spark_status spark_stat_topk(const void* x, spark_dtype dt, int64_t rows, int64_t n, int64_t ldx, int64_t k,
+                             spark_fill fill, void* y, int64_t ldy, float* theta, int32_t* count,
+                             int32_t* idx, int64_t idx_cap, void* hip_stream) {
+  if (!x) return SPARK_ERR_NULL;
+  if (!dtype_ok(dt)) return SPARK_ERR_DTYPE;
+  if (fill != SPARK_FILL_ZERO && fill != SPARK_FILL_NEG_INF) return SPARK_ERR_DTYPE;
+  if (rows < 0 || rows > 2147483647LL || n < 2 || n > 2147483647LL || ldx < n) return SPARK_ERR_SHAPE;
+  if (y && ldy < n) return SPARK_ERR_SHAPE;
+  if (idx && idx_cap < 0) return SPARK_ERR_SHAPE;
+  if (k < 1 || k > n - 1) return SPARK_ERR_K;
+  const size_t es = dtype_size(dt);
+  if (!aligned16(x) || (ldx * es) % 16) return SPARK_ERR_ALIGN;
+  if (y && (!aligned16(y) || (ldy * es) % 16)) return SPARK_ERR_ALIGN;
+  const float z = (float)spark_normal_quantile(1.0 - (double)k / (double)n);
+  const hipError_t e = spark::launch_stat_topk(x, dt == SPARK_BF16, rows, n, ldx, z, fill == SPARK_FILL_NEG_INF,
+                                               y, ldy, theta, count, idx, idx_cap, nullptr,
+                                               static_cast<hipStream_t>(hip_stream));
+  return e == hipSuccess ? SPARK_OK : SPARK_ERR_DEVICE;
+}
+
+size_t spark_ffn_workspace_bytes(int32_t d_model, int32_t d_ff, int32_t batch) {
+  if (d_model < 2 || d_ff < 2 || batch < 1 || batch > SPARK_MAX_BATCH) return 0;
+  return spark::ffn_workspace_bytes(d_model, d_ff, batch);
+}
+
+spark_status spark_ffn_decode(const spark_ffn_layer* layer, const void* q, spark_dtype qdtype, int32_t batch,
+                              int64_t ldq, float* y, float* theta, int32_t* active_count,
+                              int32_t* active_idx, int32_t* union_count, int32_t* union_idx,
+                              void* workspace, size_t workspace_bytes, void* hip_stream) {
+  const spark_status s = validate_decode(layer, q, qdtype, batch, ldq, y, workspace, workspace_bytes);
+  if (s != SPARK_OK) return s;
+  const spark::FfnProblem p = make_problem(layer, q, qdtype, batch, ldq, y, theta, active_count, active_idx,
+                                           union_count, union_idx);
+  const spark::FfnWorkspace ws = spark::carve_workspace(workspace, layer->d_model, layer->d_ff, batch);
+  const hipError_t e = spark::launch_ffn_general(p, ws, 0, static_cast<hipStream_t>(hip_stream));
+  return e == hipSuccess ? SPARK_OK : SPARK_ERR_DEVICE;
+}
+
+spark_status spark_ffn_decode_layers(const spark_ffn_layer* layers, int32_t n_layers, const void* q,
+                                     spark_dtype qdtype, int32_t batch, int64_t ldq, float* y, float* theta,
+                                     int32_t* active_count, int32_t* active_idx, int32_t* union_count,
+                                     int32_t* union_idx, void* workspace, size_t workspace_bytes,
+                                     void* hip_stream) {
+  if (!layers) return SPARK_ERR_NULL;
+  if (n_layers < 1) return SPARK_ERR_SHAPE;
+  for (int32_t l = 0; l < n_layers; ++l) {
+    const spark_status s = validate_decode(&layers[l], q, qdtype, batch, ldq, y, workspace, workspace_bytes);
+    if (s != SPARK_OK) return s;
+    if (layers[l].d_model != layers[0].d_model || layers[l].d_ff != layers[0].d_ff ||
+        layers[l].r != layers[0].r || layers[l].k != layers[0].k || layers[l].wdtype != layers[0].wdtype ||
+        layers[l].gelu != layers[0].gelu)
+      return SPARK_ERR_SHAPE;
+  }
+  const int64_t d_model = layers[0].d_model, d_ff = layers[0].d_ff;
+  const spark::FfnWorkspace ws = spark::carve_workspace(workspace, layers[0].d_model, layers[0].d_ff, batch);
+  for (int32_t l = 0; l < n_layers; ++l) {
+    const spark::FfnProblem p = make_problem(
+        &layers[l], q, qdtype, batch, ldq, y + (int64_t)l * batch * d_model,
+        theta ? theta + (int64_t)l * batch : nullptr, active_count ? active_count + (int64_t)l * batch : nullptr,
+        active_idx ? active_idx + (int64_t)l * batch * d_ff : nullptr, union_count ? union_count + l : nullptr,
+        union_idx ? union_idx + (int64_t)l * d_ff : nullptr);
+    const hipError_t e = spark::launch_ffn_general(p, ws, 0, static_cast<hipStream_t>(hip_stream));
+    if (e != hipSuccess) return SPARK_ERR_DEVICE;
+  }
+  return SPARK_OK;
+}
+
+spark_status spark_ffn_dense_decode(const spark_ffn_layer* layer, const void* q, spark_dtype qdtype,
+                                    int32_t batch, int64_t ldq, float* y, void* workspace,
+                                    size_t workspace_bytes, void* hip_stream) {
+  const spark_status s = validate_decode(layer, q, qdtype, batch, ldq, y, workspace, workspace_bytes);
+  if (s != SPARK_OK) return s;
+  const spark::FfnProblem p =
+      make_problem(layer, q, qdtype, batch, ldq, y, nullptr, nullptr, nullptr, nullptr, nullptr);
+  const spark::FfnWorkspace ws = spark::carve_workspace(workspace, layer->d_model, layer->d_ff, batch);
+  const hipError_t e = spark::launch_ffn_general(p, ws, 1, static_cast<hipStream_t>(hip_stream));
+  return e == hipSuccess ? SPARK_OK : SPARK_ERR_DEVICE;
+}
+
+}  // extern "C"

@@ -1,0 +1,157 @@
+// Device-side helpers shared by the Spark-FFN kernels (gfx950, wave64).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace spark {
+
+constexpr int kWave = 64;
+
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+
+struct bf16_t {
+  uint16_t bits;
+};
+
+__device__ __forceinline__ float bf16_bits_to_float(uint32_t b) { return __uint_as_float(b << 16); }
+__device__ __forceinline__ float bf16_lo(uint32_t w) { return __uint_as_float(w << 16); }
+__device__ __forceinline__ float bf16_hi(uint32_t w) { return __uint_as_float(w & 0xffff0000u); }
+
+// fp32 -> bf16, round to nearest even; NaN stays NaN, +-inf stays +-inf.
+__device__ __forceinline__ uint16_t float_to_bf16_rne(float f) {
+  uint32_t u = __float_as_uint(f);
+  if ((u & 0x7fffffffu) > 0x7f800000u) return (uint16_t)((u >> 16) | 0x0040u);
+  u += 0x7fffu + ((u >> 16) & 1u);
+  return (uint16_t)(u >> 16);
+}
+
+// One 16-byte vector of storage type T seen as VEC floats.
+template <typename T>
+struct Vec16;
+
+template <>
+struct Vec16<float> {
+  static constexpr int N = 4;
+  f32x4 raw;
+  __device__ __forceinline__ float get(int i) const { return raw[i]; }
+  __device__ __forceinline__ void set(int i, float v) { raw[i] = v; }
+  __device__ __forceinline__ static float load1(const float* p) { return *p; }
+  __device__ __forceinline__ static void store1(float* p, float v) { *p = v; }
+};
+
+template <>
+struct Vec16<bf16_t> {
+  static constexpr int N = 8;
+  u32x4 raw;
+  __device__ __forceinline__ float get(int i) const {
+    const uint32_t w = raw[i >> 1];
+    return (i & 1) ? bf16_hi(w) : bf16_lo(w);
+  }
+  __device__ __forceinline__ void set(int i, float v) {
+    const uint32_t h = float_to_bf16_rne(v);
+    uint32_t w = raw[i >> 1];
+    w = (i & 1) ? ((w & 0x0000ffffu) | (h << 16)) : ((w & 0xffff0000u) | h);
+    raw[i >> 1] = w;
+  }
+  __device__ __forceinline__ static float load1(const bf16_t* p) { return bf16_bits_to_float(p->bits); }
+  __device__ __forceinline__ static void store1(bf16_t* p, float v) { p->bits = float_to_bf16_rne(v); }
+};
+
+template <typename T>
+__device__ __forceinline__ Vec16<T> load_vec16(const T* p) {
+  Vec16<T> v;
+  v.raw = *reinterpret_cast<const decltype(v.raw)*>(p);
+  return v;
+}
+
+template <typename T>
+__device__ __forceinline__ void store_vec16(T* p, const Vec16<T>& v) {
+  *reinterpret_cast<decltype(v.raw)*>(p) = v.raw;
+}
+
+// Token vectors may be fp32 or bf16 whatever the weights are: read element i as float.
+__device__ __forceinline__ float load_q(const void* q, int q_is_bf16, int64_t i) {
+  return q_is_bf16 ? bf16_bits_to_float(static_cast<const uint16_t*>(q)[i])
+                   : static_cast<const float*>(q)[i];
+}
+
+// N consecutive token elements starting at element i (i is a multiple of N, N = 4 or 8).
+template <int N>
+__device__ __forceinline__ void load_q_vec(const void* q, int q_is_bf16, int64_t i, float* out) {
+  if (q_is_bf16) {
+    const uint16_t* p = static_cast<const uint16_t*>(q) + i;
+    if (N == 8) {
+      const u32x4 w = *reinterpret_cast<const u32x4*>(p);
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        out[2 * e] = bf16_lo(w[e]);
+        out[2 * e + 1] = bf16_hi(w[e]);
+      }
+    } else {
+      const u32x2 w = *reinterpret_cast<const u32x2*>(p);
+#pragma unroll
+      for (int e = 0; e < 2; ++e) {
+        out[2 * e] = bf16_lo(w[e]);
+        out[2 * e + 1] = bf16_hi(w[e]);
+      }
+    }
+  } else {
+    const float* p = static_cast<const float*>(q) + i;
+#pragma unroll
+    for (int e = 0; e < N; e += 4) {
+      const f32x4 w = *reinterpret_cast<const f32x4*>(p + e);
+      out[e] = w[0];
+      out[e + 1] = w[1];
+      out[e + 2] = w[2];
+      out[e + 3] = w[3];
+    }
+  }
+}
+
+// Butterfly sum over the 64 lanes of a wavefront; every lane ends with the total, and the
+// order of additions is fixed, so the result is reproducible.
+__device__ __forceinline__ float wave_sum(float v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, kWave);
+  return v;
+}
+
+__device__ __forceinline__ int wave_sum_int(int v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, kWave);
+  return v;
+}
+
+// Number of set bits of `mask` in lanes below the calling lane.
+__device__ __forceinline__ int lanes_below(uint64_t mask) {
+  return __builtin_amdgcn_mbcnt_hi((uint32_t)(mask >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)mask, 0));
+}
+
+// Sum over a thread block (THREADS a multiple of 64, <= 1024).  `red` is THREADS/64 floats
+// of LDS.  All threads receive the total; the combination order is fixed.
+template <int THREADS>
+__device__ __forceinline__ float block_sum(float v, float* red) {
+  constexpr int NW = THREADS / kWave;
+  v = wave_sum(v);
+  if (NW == 1) return v;
+  const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
+  __syncthreads();  // protects `red` against the previous use
+  if (lane == 0) red[wave] = v;
+  __syncthreads();
+  float t = 0.f;
+#pragma unroll
+  for (int w = 0; w < NW; ++w) t += red[w];
+  return t;
+}
+
+__device__ __forceinline__ float gelu_erf(float x) { return 0.5f * x * (1.0f + erff(x * 0.70710678118654752440f)); }
+__device__ __forceinline__ float gelu_tanh(float x) {
+  const float c = 0.79788456080286535588f;  // sqrt(2/pi)
+  return 0.5f * x * (1.0f + tanhf(c * (x + 0.044715f * x * x * x)));
+}
+__device__ __forceinline__ float gelu(float x, int kind) { return kind ? gelu_tanh(x) : gelu_erf(x); }
+
+}  // namespace spark

@@ -1,0 +1,53 @@
+// Host-side launchers of the Spark-FFN kernels (internal to the library).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+namespace spark {
+
+// Row-wise statistical top-k.  dt: 0 = fp32, 1 = bf16.  `flags`, when given, receives a 1 at
+// every active column (used to form the union of the active sets of a batch).
+hipError_t launch_stat_topk(const void* x, int dt, int64_t rows, int64_t n, int64_t ldx, float z,
+                            int fill, void* y, int64_t ldy, float* theta, int32_t* count,
+                            int32_t* idx, int64_t idx_cap, int32_t* flags, hipStream_t st);
+
+struct FfnProblem {
+  int d_model, d_ff, r, k;
+  int w_bf16, q_bf16, gelu;
+  const void *k1n, *k2n, *vn;
+  const void* q;
+  int64_t ldq;
+  int batch;
+  float z;  // Q(1 - k/d_ff)
+  // outputs (optional ones may be null)
+  float* y;
+  float* theta;
+  int32_t* active_count;
+  int32_t* active_idx;
+  int32_t* union_count;
+  int32_t* union_idx;
+};
+
+// Carving of the caller's workspace.
+struct FfnWorkspace {
+  float* S;          // [batch][d_ff] predictor scores
+  float* A;          // [batch][d_ff] StatTop_k(S)
+  int32_t* flags;    // [d_ff] union membership
+  int32_t* uidx;     // [d_ff] ascending union
+  int32_t* ucount;   // [16]
+  float* uact;       // [d_ff][batch] GELU(a) * g per union row
+  float* part;       // [ksplit][batch][d_model] split partial sums of y
+  int ksplit;
+  void* fused;       // scratch of the persistent batch-1 kernel
+  size_t fused_bytes;
+};
+
+size_t ffn_workspace_bytes(int d_model, int d_ff, int batch);
+FfnWorkspace carve_workspace(void* base, int d_model, int d_ff, int batch);
+
+// General path: separate kernels, any batch <= 64.  dense != 0 reads every K2 / V row.
+hipError_t launch_ffn_general(const FfnProblem& p, const FfnWorkspace& ws, int dense, hipStream_t st);
+
+}  // namespace spark

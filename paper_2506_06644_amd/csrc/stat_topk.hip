@@ -1,0 +1,278 @@
+// Row-wise statistical top-k (Eq.9-11 of arXiv 2506.06644) for gfx950.
+//
+// One workgroup owns one row.  The row is read from HBM once into registers (striped
+// 16-byte vectors, fully coalesced), the mean and the centred sum of squares are reduced
+// with wavefront butterflies plus a small LDS combine, theta = mean + std * Q(1 - k/n) is
+// formed, and the soft-thresholded row is written once.  Active indices are compacted in
+// ascending order with wave ballots and an LDS prefix table.  Rows too long for the
+// register file fall back to a kernel that re-reads the row for each pass.
+#include "spark_device.h"
+#include "spark_internal.h"
+
+namespace spark {
+
+namespace {
+
+// Exclusive scan, in place, of `n` ints in LDS by the first wavefront; returns nothing,
+// the grand total is left in tab[n].  Caller synchronises before and after.
+__device__ __forceinline__ void wave0_exclusive_scan(int* tab, int n) {
+  if (threadIdx.x < kWave) {
+    const int lane = threadIdx.x;
+    int carry = 0;
+    for (int base = 0; base < n; base += kWave) {
+      const int i = base + lane;
+      const int v = i < n ? tab[i] : 0;
+      int incl = v;
+#pragma unroll
+      for (int o = 1; o < kWave; o <<= 1) {
+        const int t = __shfl_up(incl, o, kWave);
+        if (lane >= o) incl += t;
+      }
+      if (i < n) tab[i] = carry + incl - v;
+      carry += __shfl(incl, kWave - 1, kWave);
+    }
+    if (lane == 0) tab[n] = carry;
+  }
+}
+
+template <typename T, int THREADS, int ITEMS>
+__global__ __launch_bounds__(THREADS) void stat_topk_cached_kernel(
+    const T* x, int64_t ldx, int n, float z, int fill_neg_inf, T* y, int64_t ldy,
+    float* __restrict__ theta_out, int32_t* __restrict__ count_out, int32_t* __restrict__ idx_out,
+    int64_t idx_cap, int32_t* __restrict__ flags) {
+  constexpr int VEC = Vec16<T>::N;
+  constexpr int NW = THREADS / kWave;
+  __shared__ float red[NW];
+  __shared__ int tab[ITEMS * NW + 1];
+
+  const int tid = threadIdx.x;
+  const int lane = tid & (kWave - 1), wave = tid / kWave;
+  const int64_t row = blockIdx.x;
+  const T* xr = x + row * ldx;
+  const int nfull = n / VEC, tail = n - nfull * VEC;
+
+  Vec16<T> v[ITEMS];
+  int nv[ITEMS];  // valid elements of each held vector
+#pragma unroll
+  for (int i = 0; i < ITEMS; ++i) {
+    const int vi = i * THREADS + tid;
+    nv[i] = vi < nfull ? VEC : (vi == nfull ? tail : 0);
+    if (vi < nfull) {
+      v[i] = load_vec16<T>(xr + (int64_t)vi * VEC);
+    } else {
+      v[i].raw = (decltype(v[i].raw))(0);
+      if (vi == nfull) {
+#pragma unroll
+        for (int e = 0; e < VEC; ++e)
+          if (e < tail) v[i].set(e, Vec16<T>::load1(xr + (int64_t)vi * VEC + e));
+      }
+    }
+  }
+
+  float s = 0.f;
+#pragma unroll
+  for (int i = 0; i < ITEMS; ++i)
+#pragma unroll
+    for (int e = 0; e < VEC; ++e) s += (e < nv[i]) ? v[i].get(e) : 0.f;
+  const float mean = block_sum<THREADS>(s, red) / (float)n;
+
+  float ss = 0.f;
+#pragma unroll
+  for (int i = 0; i < ITEMS; ++i)
+#pragma unroll
+    for (int e = 0; e < VEC; ++e) {
+      const float c = v[i].get(e) - mean;
+      ss += (e < nv[i]) ? c * c : 0.f;
+    }
+  const float m2 = block_sum<THREADS>(ss, red);
+  const float sd = sqrtf(m2 / (float)(n - 1));
+  const float theta = mean + sd * z;
+  if (tid == 0 && theta_out) theta_out[row] = theta;
+
+  const float fillv = fill_neg_inf ? -__builtin_inff() : 0.f;
+  uint32_t act[ITEMS];
+  int cnt = 0;
+#pragma unroll
+  for (int i = 0; i < ITEMS; ++i) {
+    uint32_t m = 0;
+#pragma unroll
+    for (int e = 0; e < VEC; ++e) {
+      const float xv = v[i].get(e);
+      const bool a = (e < nv[i]) && (xv > theta);
+      m |= a ? (1u << e) : 0u;
+    }
+    act[i] = m;
+    cnt += __popc(m);
+  }
+
+  if (y) {
+    T* yr = y + row * ldy;
+#pragma unroll
+    for (int i = 0; i < ITEMS; ++i) {
+      const int vi = i * THREADS + tid;
+      if (nv[i] == 0) continue;
+      Vec16<T> o;
+#pragma unroll
+      for (int e = 0; e < VEC; ++e) o.set(e, ((act[i] >> e) & 1u) ? v[i].get(e) - theta : fillv);
+      if (nv[i] == VEC) {
+        store_vec16<T>(yr + (int64_t)vi * VEC, o);
+      } else {
+#pragma unroll
+        for (int e = 0; e < VEC; ++e)
+          if (e < nv[i]) Vec16<T>::store1(yr + (int64_t)vi * VEC + e, o.get(e));
+      }
+    }
+  }
+
+  if (flags) {
+#pragma unroll
+    for (int i = 0; i < ITEMS; ++i) {
+      const int vi = i * THREADS + tid;
+#pragma unroll
+      for (int e = 0; e < VEC; ++e)
+        if ((act[i] >> e) & 1u) flags[vi * VEC + e] = 1;
+    }
+  }
+
+  if (idx_out) {
+    int pre[ITEMS];
+#pragma unroll
+    for (int i = 0; i < ITEMS; ++i) {
+      int below = 0, total = 0;
+#pragma unroll
+      for (int e = 0; e < VEC; ++e) {
+        const uint64_t b = __ballot((act[i] >> e) & 1u);
+        below += lanes_below(b);
+        total += __popcll(b);
+      }
+      pre[i] = below;
+      if (lane == 0) tab[i * NW + wave] = total;
+    }
+    __syncthreads();
+    wave0_exclusive_scan(tab, ITEMS * NW);
+    __syncthreads();
+    int32_t* ir = idx_out + row * idx_cap;
+#pragma unroll
+    for (int i = 0; i < ITEMS; ++i) {
+      const int vi = i * THREADS + tid;
+      int pos = tab[i * NW + wave] + pre[i];
+#pragma unroll
+      for (int e = 0; e < VEC; ++e) {
+        if ((act[i] >> e) & 1u) {
+          if (pos < idx_cap) ir[pos] = vi * VEC + e;
+          ++pos;
+        }
+      }
+    }
+    if (tid == 0 && count_out) count_out[row] = tab[ITEMS * NW];
+  } else if (count_out) {
+    const float total = block_sum<THREADS>((float)cnt, red);  // exact: counts < 2^24
+    if (tid == 0) count_out[row] = (int32_t)total;
+  }
+}
+
+// Fallback for rows that do not fit the register file: three reads of the row.
+template <typename T, int THREADS>
+__global__ __launch_bounds__(THREADS) void stat_topk_stream_kernel(
+    const T* x, int64_t ldx, int n, float z, int fill_neg_inf, T* y, int64_t ldy,
+    float* __restrict__ theta_out, int32_t* __restrict__ count_out, int32_t* __restrict__ idx_out,
+    int64_t idx_cap, int32_t* __restrict__ flags) {
+  constexpr int NW = THREADS / kWave;
+  __shared__ float red[NW];
+  __shared__ int tab[NW + 1];
+  __shared__ int running;
+  const int tid = threadIdx.x;
+  const int lane = tid & (kWave - 1), wave = tid / kWave;
+  const int64_t row = blockIdx.x;
+  const T* xr = x + row * ldx;
+
+  float s = 0.f;
+  for (int i = tid; i < n; i += THREADS) s += Vec16<T>::load1(xr + i);
+  const float mean = block_sum<THREADS>(s, red) / (float)n;
+  float ss = 0.f;
+  for (int i = tid; i < n; i += THREADS) {
+    const float c = Vec16<T>::load1(xr + i) - mean;
+    ss += c * c;
+  }
+  const float m2 = block_sum<THREADS>(ss, red);
+  const float theta = mean + sqrtf(m2 / (float)(n - 1)) * z;
+  if (tid == 0 && theta_out) theta_out[row] = theta;
+  const float fillv = fill_neg_inf ? -__builtin_inff() : 0.f;
+  if (tid == 0) running = 0;
+  __syncthreads();
+  int cnt = 0;
+  const int rounds = (n + THREADS - 1) / THREADS;
+  for (int rd = 0; rd < rounds; ++rd) {
+    const int i = rd * THREADS + tid;
+    float xv = 0.f;
+    bool a = false;
+    if (i < n) {
+      xv = Vec16<T>::load1(xr + i);
+      a = xv > theta;
+      if (y) Vec16<T>::store1(y + row * ldy + i, a ? xv - theta : fillv);
+      if (a && flags) flags[i] = 1;
+    }
+    cnt += a;
+    if (idx_out) {
+      const uint64_t b = __ballot(a);
+      if (lane == 0) tab[wave] = __popcll(b);
+      __syncthreads();
+      int base = running;
+      for (int w = 0; w < wave; ++w) base += tab[w];
+      const int pos = base + lanes_below(b);
+      if (a && pos < idx_cap) idx_out[row * idx_cap + pos] = i;
+      __syncthreads();
+      if (tid == 0) {
+        int t = running;
+        for (int w = 0; w < NW; ++w) t += tab[w];
+        running = t;
+      }
+      __syncthreads();
+    }
+  }
+  if (count_out) {
+    const float total = block_sum<THREADS>((float)cnt, red);
+    if (tid == 0) count_out[row] = (int32_t)total;
+  }
+}
+
+template <typename T>
+hipError_t launch_stat_topk_t(const T* x, int64_t rows, int64_t n, int64_t ldx, float z, int fill,
+                              T* y, int64_t ldy, float* theta, int32_t* count, int32_t* idx,
+                              int64_t idx_cap, int32_t* flags, hipStream_t st) {
+  if (rows == 0) return hipSuccess;
+  constexpr int VEC = Vec16<T>::N;
+  const int64_t nvec = (n + VEC - 1) / VEC;
+  const dim3 grid((unsigned)rows);
+#define SPARK_LAUNCH_CACHED(THREADS, ITEMS)                                                        \
+  hipLaunchKernelGGL((stat_topk_cached_kernel<T, THREADS, ITEMS>), grid, dim3(THREADS), 0, st, x, \
+                     ldx, (int)n, z, fill, y, ldy, theta, count, idx, idx_cap, flags)
+  if (nvec <= 256 * 1) SPARK_LAUNCH_CACHED(256, 1);
+  else if (nvec <= 256 * 2) SPARK_LAUNCH_CACHED(256, 2);
+  else if (nvec <= 256 * 5) SPARK_LAUNCH_CACHED(256, 5);
+  else if (nvec <= 256 * 9) SPARK_LAUNCH_CACHED(256, 9);
+  else if (nvec <= 256 * 14) SPARK_LAUNCH_CACHED(256, 14);
+  else if (nvec <= 1024 * 8) SPARK_LAUNCH_CACHED(1024, 8);
+  else if (sizeof(T) == 4 && nvec <= 1024 * 16) {
+    // 16 vectors per lane fit the 128-VGPR budget of a 1024-thread workgroup only for fp32
+    if constexpr (sizeof(T) == 4) SPARK_LAUNCH_CACHED(1024, 16);
+  } else
+    hipLaunchKernelGGL((stat_topk_stream_kernel<T, 1024>), grid, dim3(1024), 0, st, x, ldx, (int)n,
+                       z, fill, y, ldy, theta, count, idx, idx_cap, flags);
+#undef SPARK_LAUNCH_CACHED
+  return hipGetLastError();
+}
+
+}  // namespace
+
+hipError_t launch_stat_topk(const void* x, int dt, int64_t rows, int64_t n, int64_t ldx, float z,
+                            int fill, void* y, int64_t ldy, float* theta, int32_t* count,
+                            int32_t* idx, int64_t idx_cap, int32_t* flags, hipStream_t st) {
+  if (dt == 0)
+    return launch_stat_topk_t<float>(static_cast<const float*>(x), rows, n, ldx, z, fill,
+                                     static_cast<float*>(y), ldy, theta, count, idx, idx_cap, flags, st);
+  return launch_stat_topk_t<bf16_t>(static_cast<const bf16_t*>(x), rows, n, ldx, z, fill,
+                                    static_cast<bf16_t*>(y), ldy, theta, count, idx, idx_cap, flags, st);
+}
+
+}  // namespace spark

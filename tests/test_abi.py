@@ -1,0 +1,100 @@
+"""The C-ABI library loads, exports every symbol include/spark.h declares, and rejects
+invalid calls on the host before anything is launched (no GPU needed)."""
+import ctypes
+import os
+import re
+
+import pytest
+
+from paper_2506_06644_amd import binding
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def test_library_exports_every_declared_symbol():
+    header = open(os.path.join(ROOT, "include", "spark.h")).read()
+    declared = set(re.findall(r"\b(spark_[a-z_0-9]+)\s*\(", header))
+    declared -= {"spark_status", "spark_dtype", "spark_fill", "spark_gelu", "spark_ffn_layer"}
+    assert declared == set(binding.EXPORTS)
+    lib = binding.load_library()
+    for name in declared:
+        assert hasattr(lib, name), name
+    assert lib.spark_version() == 100
+
+
+def test_status_strings():
+    for code in range(8):
+        assert binding.status_string(code) not in ("", "unknown status")
+    assert binding.status_string(99) == "unknown status"
+
+
+def test_library_quantile_agrees_with_statistics_module():
+    import statistics
+    nd = statistics.NormalDist()
+    for p in [1e-9, 0.001, 0.08, 0.5, 0.7, 1 - 737 / 9216, 0.999999]:
+        assert binding.normal_quantile(p) == pytest.approx(nd.inv_cdf(p), rel=1e-12, abs=1e-13)
+    assert binding.normal_quantile(0.0) == float("-inf") and binding.normal_quantile(1.0) == float("inf")
+    assert binding.normal_quantile(2.0) != binding.normal_quantile(2.0)
+
+
+def _layer(d_model=256, d_ff=1024, r=128, k=82, wd=binding.BF16, gelu=0, k1=0x1000, k2=0x2000, v=0x3000):
+    return binding._Layer(d_model, d_ff, r, k, wd, gelu, k1, k2, v)
+
+
+def _decode(layer, q=0x4000, qd=binding.BF16, batch=1, ldq=256, y=0x5000, ws=0x10000, ws_bytes=None):
+    lib = binding.load_library()
+    if ws_bytes is None:
+        ws_bytes = binding.ffn_workspace_bytes(layer.d_model, layer.d_ff, max(1, min(batch, 64)))
+    vp = ctypes.c_void_p
+    return lib.spark_ffn_decode(ctypes.byref(layer), vp(q), qd, batch, ldq, vp(y), None, None, None, None,
+                                None, vp(ws), ws_bytes, None)
+
+
+def test_decode_rejects_bad_arguments_before_launch():
+    # every call below carries fake (never dereferenced) device addresses
+    assert _decode(_layer(k1=0)) == 1                        # NULL weights
+    assert _decode(_layer(), q=0) == 1
+    assert _decode(_layer(), y=0) == 1
+    assert _decode(_layer(d_ff=1)) == 2
+    assert _decode(_layer(r=0)) == 2
+    assert _decode(_layer(r=256)) == 2
+    assert _decode(_layer(), batch=0) == 2
+    assert _decode(_layer(), batch=65) == 2
+    assert _decode(_layer(), ldq=128) == 2
+    assert _decode(_layer(k=0)) == 3
+    assert _decode(_layer(k=1024)) == 3
+    assert _decode(_layer(wd=7)) == 4
+    assert _decode(_layer(gelu=5)) == 4
+    assert _decode(_layer(), qd=9) == 4
+    assert _decode(_layer(r=100)) == 5                       # 200-byte rows
+    assert _decode(_layer(k1=0x1004)) == 5
+    assert _decode(_layer(), q=0x4002) == 5
+    assert _decode(_layer(), ws=0) == 6
+    assert _decode(_layer(), ws=0x10010) == 6
+    assert _decode(_layer(), ws_bytes=1024) == 6
+
+
+def test_stat_topk_rejects_bad_arguments_before_launch():
+    lib = binding.load_library()
+    vp = ctypes.c_void_p
+
+    def call(x=0x1000, dt=0, rows=4, n=64, ldx=64, k=5, fill=0, y=0x2000, ldy=64, cap=0):
+        return lib.spark_stat_topk(vp(x), dt, rows, n, ldx, k, fill, vp(y), ldy, None, None, None, cap, None)
+
+    assert call(x=0) == 1
+    assert call(n=1) == 2
+    assert call(rows=-1) == 2
+    assert call(ldx=60) == 2
+    assert call(ldy=32) == 2
+    assert call(k=0) == 3 and call(k=64) == 3
+    assert call(dt=3) == 4 and call(fill=2) == 4
+    assert call(x=0x1008) == 5
+    assert call(ldx=66, ldy=66) == 5
+    assert call(rows=0) == 0                                  # empty input: nothing to do
+
+
+def test_workspace_query():
+    assert binding.ffn_workspace_bytes(2304, 9216, 1) > 9216 * 4 * 4
+    assert binding.ffn_workspace_bytes(2304, 9216, 64) > binding.ffn_workspace_bytes(2304, 9216, 1)
+    assert binding.ffn_workspace_bytes(2304, 9216, 0) == 0
+    assert binding.ffn_workspace_bytes(2304, 9216, 65) == 0

@@ -1,0 +1,194 @@
+"""GPU parity: the HIP path, called through the C ABI, against the CPU oracle."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2506_06644_amd import binding, synth
+
+from parity_util import (TOL_BF16, TOL_BF16_TIGHT, TOL_F32, assert_active_set, check_ffn_against_oracle,
+                         rel_l2, run_gpu_ffn)
+
+pytestmark = pytest.mark.gpu
+
+DEV = "cuda:0"
+
+
+# ------------------------------------------------------------------------------- stat top-k
+def _topk_case(rows, n, k, dtype, fill=binding.FILL_ZERO, seed=4242, ld=None, with_idx=True):
+    x = synth.topk_rows(rows, n, seed=seed, dtype=dtype)
+    ld = ld or (n + 7) // 8 * 8
+    xd = torch.zeros(rows, ld, dtype=dtype, device=DEV)
+    xd[:, :n] = x.to(DEV)
+    xv = xd[:, :n]
+    y = torch.full((rows, ld), 7.0, dtype=dtype, device=DEV)[:, :n]
+    theta = torch.zeros(rows, dtype=torch.float32, device=DEV)
+    count = torch.zeros(rows, dtype=torch.int32, device=DEV)
+    idx = torch.full((rows, n), -1, dtype=torch.int32, device=DEV) if with_idx else None
+    binding.spark_stat_topk(xv, k, fill, y, theta, count, idx)
+    torch.cuda.synchronize()
+    ref = oracle.stat_topk_rows(synth.to_oracle(x).astype(np.float64), k, fill)
+    yg = y.float().cpu().numpy().astype(np.float64)
+    tg, cg = theta.cpu().numpy(), count.cpu().numpy()
+    xs = synth.to_oracle(x).astype(np.float64)
+    ulp = 2.0 ** -8 if dtype == torch.bfloat16 else 2.0 ** -22
+    for r in range(rows):
+        assert abs(tg[r] - ref.theta[r]) <= 2e-6 * (ref.std[r] + abs(ref.theta[r])), f"row {r} theta"
+        act_g = xs[r] > tg[r]          # what the GPU decided, re-derived from its own theta
+        if with_idx:
+            gi = idx[r].cpu().numpy()
+            m = int(cg[r])
+            assert np.all(np.diff(gi[:m]) > 0) and np.all(gi[m:] == -1)
+            ndiff = assert_active_set(gi[:m], xs[r], ref.theta[r], ref.std[r], f"row {r}")
+            act_g = np.zeros(n, bool)
+            act_g[gi[:m]] = True
+        else:
+            ndiff = int((act_g != (xs[r] > ref.theta[r])).sum())
+        assert abs(int(cg[r]) - int(ref.count[r])) <= ndiff
+        both = act_g & (xs[r] > ref.theta[r])
+        # survivors: x - theta (rounded once to the storage type)
+        assert np.all(np.abs(yg[r][both] - ref.y[r][both]) <= ulp * np.abs(ref.y[r][both])
+                      + 4e-6 * (ref.std[r] + abs(ref.theta[r]))), f"row {r} values"
+        dropped = ~act_g
+        if fill == binding.FILL_ZERO:
+            assert np.all(yg[r][dropped] == 0.0)
+        else:
+            assert np.all(np.isneginf(yg[r][dropped]))
+    return ref
+
+
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
+@pytest.mark.parametrize("rows,n,k", [(5, 1024, 82), (33, 9216, 737), (7, 1000, 77), (3, 14336, 1147),
+                                      (4, 13824, 1106), (2, 40000, 900), (2, 70000, 5000), (3, 8, 2),
+                                      (2, 2, 1)])
+def test_stat_topk_matches_oracle(rows, n, k, dtype):
+    _topk_case(rows, n, k, dtype)
+
+
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
+def test_stat_topk_ragged_pitch_neg_inf_and_optional_outputs(dtype):
+    _topk_case(6, 1003, 80, dtype, fill=binding.FILL_NEG_INF, ld=1016)
+    _topk_case(6, 9216, 737, dtype, with_idx=False)
+    # stats only, idx capped
+    x = synth.topk_rows(4, 2048, seed=9, dtype=dtype).to(DEV)
+    count = torch.zeros(4, dtype=torch.int32, device=DEV)
+    idx = torch.full((4, 16), -1, dtype=torch.int32, device=DEV)
+    binding.spark_stat_topk(x, 200, count=count, idx=idx)
+    torch.cuda.synchronize()
+    ref = oracle.stat_topk_rows(synth.to_oracle(x).astype(np.float64), 200)
+    assert np.all(np.abs(count.cpu().numpy() - ref.count) <= 2)
+    for r in range(4):
+        assert np.array_equal(idx[r].cpu().numpy(), ref.idx[r, :16])
+
+
+def test_stat_topk_in_place_and_degenerate_rows():
+    x = synth.topk_rows(9, 4096, seed=3, dtype=torch.float32)
+    x[4] = 2.5                                  # constant row: std = 0, nothing survives
+    xd = x.to(DEV)
+    theta = torch.zeros(9, device=DEV)
+    count = torch.zeros(9, dtype=torch.int32, device=DEV)
+    binding.spark_stat_topk(xd, 300, y=xd, theta=theta, count=count)
+    torch.cuda.synchronize()
+    ref = oracle.stat_topk_rows(x.numpy().astype(np.float64), 300)
+    assert count[4].item() == 0 and theta[4].item() == 2.5 and not xd[4].any()
+    assert rel_l2(xd.cpu().numpy(), ref.y) < 1e-5
+
+
+def test_stat_topk_full_prefill_shape_sampled_rows():
+    """8192 x 9216 (the prefill / training shape), fp32 and bf16: sampled rows one by one
+    against the oracle, and count / zero-structure properties on every row."""
+    rows, n, k = 8192, 9216, 737
+    for dtype in (torch.float32, torch.bfloat16):
+        x = synth.topk_rows(rows, n, seed=4242, dtype=dtype, device=DEV)
+        y = torch.empty_like(x)
+        theta = torch.zeros(rows, device=DEV)
+        count = torch.zeros(rows, dtype=torch.int32, device=DEV)
+        binding.spark_stat_topk(x, k, y=y, theta=theta, count=count)
+        torch.cuda.synchronize()
+        # properties that hold for every row
+        nz = (y > 0).sum(1).to(torch.int32)
+        assert torch.equal(nz, count)
+        assert torch.equal(y > 0, x.float() > theta[:, None])
+        assert (y >= 0).all()
+        sample = [0, 1, 777, 4095, 8191]
+        xs = synth.to_oracle(x[sample]).astype(np.float64)
+        ref = oracle.stat_topk_rows(xs, k)
+        tg = theta[sample].cpu().numpy()
+        for i, r in enumerate(sample):
+            assert abs(tg[i] - ref.theta[i]) <= 2e-6 * (ref.std[i] + abs(ref.theta[i]))
+            gi = np.flatnonzero(y[r].float().cpu().numpy() > 0)
+            assert_active_set(gi, xs[i], ref.theta[i], ref.std[i], f"row {r}")
+        del x, y
+
+
+# ------------------------------------------------------------------------------- Spark-FFN decode
+def _ffn_case(shape, wdtype, qdtype, batch, n_layers=1, gelu=binding.GELU_ERF, via_layers=False, seed=1234):
+    weights = synth.ffn_stack(shape, n_layers, base_seed=seed, dtype=wdtype)
+    q = synth.tokens(shape, batch, seed + 4444, dtype=qdtype)
+    out = run_gpu_ffn(shape, weights, q, gelu=gelu, via_layers=via_layers)
+    tol = TOL_F32 if wdtype == torch.float32 else TOL_BF16
+    worst = check_ffn_against_oracle(shape, weights, q, out, tol, gelu=gelu,
+                                     what=f"{shape.name} {wdtype} B={batch}")
+    if wdtype == torch.bfloat16:
+        assert worst <= TOL_BF16_TIGHT
+    return out
+
+
+@pytest.mark.parametrize("batch", [1, 3, 16])
+@pytest.mark.parametrize("wdtype,qdtype", [(torch.float32, torch.float32), (torch.bfloat16, torch.bfloat16),
+                                           (torch.bfloat16, torch.float32), (torch.float32, torch.bfloat16)])
+def test_tiny_layer(wdtype, qdtype, batch):
+    _ffn_case(synth.TINY, wdtype, qdtype, batch)
+
+
+@pytest.mark.parametrize("wdtype", [torch.float32, torch.bfloat16])
+@pytest.mark.parametrize("batch", [1, 5, 64])
+def test_ragged_shape(wdtype, batch):
+    _ffn_case(synth.RAGGED, wdtype, wdtype, batch)
+
+
+def test_tanh_gelu_variant():
+    _ffn_case(synth.TINY, torch.float32, torch.float32, 2, gelu=binding.GELU_TANH)
+
+
+@pytest.mark.parametrize("batch", [1, 4])
+def test_gemma2_2b_layer(batch):
+    out = _ffn_case(synth.GEMMA2_2B, torch.bfloat16, torch.bfloat16, batch, seed=1000)
+    assert np.all(np.abs(out["count"] - 737) < 6 * 26)
+
+
+def test_gemma2_2b_fp32_weights():
+    _ffn_case(synth.GEMMA2_2B, torch.float32, torch.float32, 1, seed=1001)
+
+
+def test_layers_entry_point_matches_single_calls():
+    sh = synth.TINY
+    weights = synth.ffn_stack(sh, 5, base_seed=1000, dtype=torch.bfloat16)
+    for batch in (1, 4):
+        q = synth.tokens(sh, batch, 2000 + batch, torch.bfloat16)
+        a = run_gpu_ffn(sh, weights, q, via_layers=True)
+        b = run_gpu_ffn(sh, weights, q, via_layers=False)
+        check_ffn_against_oracle(sh, weights, q, a, TOL_BF16_TIGHT, what="layers")
+        assert np.array_equal(a["idx"], b["idx"]) and np.array_equal(a["uidx"], b["uidx"])
+        assert rel_l2(a["y"], b["y"]) < 1e-6
+
+
+def test_dense_evaluation_gives_the_same_layer():
+    sh = synth.TINY
+    weights = synth.ffn_stack(sh, 1, base_seed=77, dtype=torch.bfloat16)
+    q = synth.tokens(sh, 3, 78, torch.bfloat16)
+    dense = run_gpu_ffn(sh, weights, q, dense=True)
+    check_ffn_against_oracle(sh, weights, q, dense, TOL_BF16_TIGHT, dense=True, what="dense")
+    sparse = run_gpu_ffn(sh, weights, q)
+    assert rel_l2(dense["y"], sparse["y"]) < 1e-6
+
+
+def test_batch_members_do_not_influence_each_other():
+    sh = synth.TINY
+    weights = synth.ffn_stack(sh, 1, base_seed=5, dtype=torch.bfloat16)
+    q = synth.tokens(sh, 16, 2016, torch.bfloat16)
+    full = run_gpu_ffn(sh, weights, q)
+    for b in (0, 9, 15):
+        solo = run_gpu_ffn(sh, weights, q[b:b + 1])
+        assert np.array_equal(solo["idx"][0, 0], full["idx"][0, b])
+        assert rel_l2(solo["y"][0, 0], full["y"][0, b]) < 1e-6
