@@ -14,9 +14,10 @@
  *
  * General conventions
  *   - All array arguments are DEVICE pointers (HIP global memory of the current device)
- *     unless the comment says "host".  The library never allocates or frees device memory
- *     and keeps no state between calls: every buffer, including the workspace, is owned by
- *     the caller.
+ *     unless the comment says "host".  The library never allocates or frees device memory:
+ *     every buffer, including the workspace, is owned by the caller.  The only state kept
+ *     between calls is a process-wide launch counter (it stamps the synchronisation words
+ *     of the persistent launch, so the workspace needs no initialisation).
  *   - Calls enqueue work on `hip_stream` (a hipStream_t passed as void*; NULL = the default
  *     stream) and return without synchronising.  Outputs are valid once the stream has
  *     been synchronised by the caller.  Two calls that share a workspace must be ordered
@@ -162,6 +163,28 @@ spark_status spark_ffn_decode_layers(const spark_ffn_layer* layers, int32_t n_la
 spark_status spark_ffn_dense_decode(const spark_ffn_layer* layer, const void* q,
                                     spark_dtype qdtype, int32_t batch, int64_t ldq, float* y,
                                     void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/*
+ * Host, synchronising.  The batch-1 entry points run as one persistent launch whose
+ * wavefronts wait on each other; every such wait is bounded, and a launch that had to give
+ * up (for instance because another process held part of the GPU) leaves a non-zero status
+ * word in the workspace instead of results.  This call waits for `hip_stream`, reads that
+ * word and returns SPARK_ERR_DEVICE if the last batch-1 decode on this workspace aborted,
+ * SPARK_OK otherwise.  Arguments as for spark_ffn_workspace_bytes.
+ */
+spark_status spark_ffn_check(const void* workspace, int32_t d_model, int32_t d_ff, int32_t batch,
+                             void* hip_stream);
+
+/* Host.  Testing aid: a non-zero value routes batch-1 calls through the general multi-kernel
+ * path instead of the persistent launch (process-wide). */
+void spark_debug_force_general(int on);
+
+/* Host.  Testing aid: with profiling on, every wavefront of the persistent launch records
+ * how long it lived and how long it spent in each of its waits (100 MHz ticks);
+ * spark_debug_read_profile synchronises and copies out [256 workgroups][16 waves][8] words. */
+void spark_debug_profile(int on);
+spark_status spark_debug_read_profile(const void* workspace, int32_t d_model, int32_t d_ff, int32_t batch,
+                                      int64_t* out, int64_t n_words, void* hip_stream);
 
 #ifdef __cplusplus
 }

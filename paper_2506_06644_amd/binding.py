@@ -24,7 +24,8 @@ MAX_BATCH = 64
 EXPORTS = (
     "spark_status_string", "spark_version", "spark_normal_quantile", "spark_stat_topk",
     "spark_ffn_workspace_bytes", "spark_ffn_decode", "spark_ffn_decode_layers",
-    "spark_ffn_dense_decode",
+    "spark_ffn_dense_decode", "spark_ffn_check", "spark_debug_force_general",
+    "spark_debug_profile", "spark_debug_read_profile",
 )
 
 
@@ -73,6 +74,14 @@ def load_library():
                                             vp, vp, vp, vp, sz, vp]
     lib.spark_ffn_dense_decode.restype = c_int
     lib.spark_ffn_dense_decode.argtypes = [ctypes.POINTER(_Layer), vp, c_int, i32, i64, vp, vp, sz, vp]
+    lib.spark_ffn_check.restype = c_int
+    lib.spark_ffn_check.argtypes = [vp, i32, i32, i32, vp]
+    lib.spark_debug_profile.restype = None
+    lib.spark_debug_profile.argtypes = [c_int]
+    lib.spark_debug_read_profile.restype = c_int
+    lib.spark_debug_read_profile.argtypes = [vp, i32, i32, i32, vp, i64, vp]
+    lib.spark_debug_force_general.restype = None
+    lib.spark_debug_force_general.argtypes = [c_int]
     _lib = lib
     return lib
 
@@ -165,3 +174,28 @@ def spark_ffn_dense_decode(layer: _Layer, q: torch.Tensor, y: torch.Tensor, work
         ctypes.byref(layer), _p(q), _dt(q), q.shape[0], q.stride(0), _p(y), _p(workspace),
         workspace.numel(), _stream())
     _check(rc, "spark_ffn_dense_decode")
+
+
+def spark_ffn_check(workspace: torch.Tensor, d_model: int, d_ff: int, batch: int):
+    """Waits for the current stream and raises if the last batch-1 decode on ``workspace`` aborted."""
+    rc = load_library().spark_ffn_check(_p(workspace), int(d_model), int(d_ff), int(batch), _stream())
+    _check(rc, "spark_ffn_check")
+
+
+def spark_debug_force_general(on: bool):
+    load_library().spark_debug_force_general(1 if on else 0)
+
+
+def spark_debug_profile(on: bool):
+    load_library().spark_debug_profile(1 if on else 0)
+
+
+def spark_debug_read_profile(workspace: torch.Tensor, d_model: int, d_ff: int, batch: int):
+    """[256, 16, 8] int64 tick counters of the last profiled persistent launch."""
+    import numpy as np
+
+    out = np.zeros((256, 16, 8), np.int64)
+    rc = load_library().spark_debug_read_profile(_p(workspace), int(d_model), int(d_ff), int(batch),
+                                                 out.ctypes.data_as(ctypes.c_void_p), out.size, _stream())
+    _check(rc, "spark_debug_read_profile")
+    return out

@@ -72,6 +72,34 @@ spark::FfnProblem make_problem(const spark_ffn_layer* L, const void* q, int qdty
   return p;
 }
 
+int g_force_general = 0;
+
+// Runs layers[0..n) for one token through the persistent launch.
+hipError_t run_fused(const spark_ffn_layer* layers, int32_t n_layers, const spark::FfnProblem& p0,
+                     const spark::FfnWorkspace& ws, hipStream_t st) {
+  const void* k1n[256];
+  const void* k2n[256];
+  const void* vn[256];
+  hipError_t e = hipSuccess;
+  for (int32_t base = 0; base < n_layers && e == hipSuccess; base += 256) {
+    const int32_t n = n_layers - base < 256 ? n_layers - base : 256;
+    for (int32_t l = 0; l < n; ++l) {
+      k1n[l] = layers[base + l].k1n;
+      k2n[l] = layers[base + l].k2n;
+      vn[l] = layers[base + l].vn;
+    }
+    spark::FfnProblem p = p0;
+    p.y = p0.y + (int64_t)base * p0.d_model;
+    if (p.theta) p.theta += base;
+    if (p.active_count) p.active_count += base;
+    if (p.active_idx) p.active_idx += (int64_t)base * p0.d_ff;
+    if (p.union_count) p.union_count += base;
+    if (p.union_idx) p.union_idx += (int64_t)base * p0.d_ff;
+    e = spark::launch_ffn_fused(p, k1n, k2n, vn, n, ws.fused, st);
+  }
+  return e;
+}
+
 }  // namespace
 
 extern "C" {
@@ -152,7 +180,11 @@ spark_status spark_ffn_decode(const spark_ffn_layer* layer, const void* q, spark
   const spark::FfnProblem p = make_problem(layer, q, qdtype, batch, ldq, y, theta, active_count, active_idx,
                                            union_count, union_idx);
   const spark::FfnWorkspace ws = spark::carve_workspace(workspace, layer->d_model, layer->d_ff, batch);
-  const hipError_t e = spark::launch_ffn_general(p, ws, 0, static_cast<hipStream_t>(hip_stream));
+  hipError_t e;
+  if (!g_force_general && spark::fused_supported(p, 1))
+    e = run_fused(layer, 1, p, ws, static_cast<hipStream_t>(hip_stream));
+  else
+    e = spark::launch_ffn_general(p, ws, 0, static_cast<hipStream_t>(hip_stream));
   return e == hipSuccess ? SPARK_OK : SPARK_ERR_DEVICE;
 }
 
@@ -173,6 +205,14 @@ spark_status spark_ffn_decode_layers(const spark_ffn_layer* layers, int32_t n_la
   }
   const int64_t d_model = layers[0].d_model, d_ff = layers[0].d_ff;
   const spark::FfnWorkspace ws = spark::carve_workspace(workspace, layers[0].d_model, layers[0].d_ff, batch);
+  {
+    const spark::FfnProblem p0 = make_problem(&layers[0], q, qdtype, batch, ldq, y, theta, active_count,
+                                              active_idx, union_count, union_idx);
+    if (!g_force_general && spark::fused_supported(p0, n_layers)) {
+      const hipError_t e = run_fused(layers, n_layers, p0, ws, static_cast<hipStream_t>(hip_stream));
+      return e == hipSuccess ? SPARK_OK : SPARK_ERR_DEVICE;
+    }
+  }
   for (int32_t l = 0; l < n_layers; ++l) {
     const spark::FfnProblem p = make_problem(
         &layers[l], q, qdtype, batch, ldq, y + (int64_t)l * batch * d_model,
@@ -195,6 +235,35 @@ spark_status spark_ffn_dense_decode(const spark_ffn_layer* layer, const void* q,
   const spark::FfnWorkspace ws = spark::carve_workspace(workspace, layer->d_model, layer->d_ff, batch);
   const hipError_t e = spark::launch_ffn_general(p, ws, 1, static_cast<hipStream_t>(hip_stream));
   return e == hipSuccess ? SPARK_OK : SPARK_ERR_DEVICE;
+}
+
+spark_status spark_ffn_check(const void* workspace, int32_t d_model, int32_t d_ff, int32_t batch,
+                             void* hip_stream) {
+  if (!workspace) return SPARK_ERR_WORKSPACE;
+  if (spark_ffn_workspace_bytes(d_model, d_ff, batch) == 0) return SPARK_ERR_SHAPE;
+  const spark::FfnWorkspace ws = spark::carve_workspace(const_cast<void*>(workspace), d_model, d_ff, batch);
+  int32_t word = 0;
+  hipStream_t st = static_cast<hipStream_t>(hip_stream);
+  if (hipMemcpyAsync(&word, ws.fused, sizeof(word), hipMemcpyDeviceToHost, st) != hipSuccess) return SPARK_ERR_DEVICE;
+  if (hipStreamSynchronize(st) != hipSuccess) return SPARK_ERR_DEVICE;
+  return word == 0 ? SPARK_OK : SPARK_ERR_DEVICE;
+}
+
+void spark_debug_force_general(int on) { g_force_general = on != 0; }
+
+void spark_debug_profile(int on) { spark::fused_set_profile(on != 0); }
+
+spark_status spark_debug_read_profile(const void* workspace, int32_t d_model, int32_t d_ff, int32_t batch,
+                                      int64_t* out, int64_t n_words, void* hip_stream) {
+  if (!workspace || !out) return SPARK_ERR_NULL;
+  if (spark_ffn_workspace_bytes(d_model, d_ff, batch) == 0) return SPARK_ERR_SHAPE;
+  const spark::FfnWorkspace ws = spark::carve_workspace(const_cast<void*>(workspace), d_model, d_ff, batch);
+  size_t bytes = (size_t)n_words * 8;
+  if (bytes > spark::fused_profile_bytes()) bytes = spark::fused_profile_bytes();
+  hipStream_t st = static_cast<hipStream_t>(hip_stream);
+  const char* src = static_cast<const char*>(ws.fused) + spark::fused_profile_offset(d_model);
+  if (hipMemcpyAsync(out, src, bytes, hipMemcpyDeviceToHost, st) != hipSuccess) return SPARK_ERR_DEVICE;
+  return hipStreamSynchronize(st) == hipSuccess ? SPARK_OK : SPARK_ERR_DEVICE;
 }
 
 }  // extern "C"

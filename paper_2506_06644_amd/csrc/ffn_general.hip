@@ -21,10 +21,12 @@ template <typename WT, int TB>
 __global__ __launch_bounds__(kBlock) void predict_kernel(const WT* __restrict__ k1n, int d_ff, int r,
                                                          const void* __restrict__ q, int q_bf16,
                                                          int64_t ldq, int B, float* __restrict__ S,
-                                                         int32_t* __restrict__ flags) {
+                                                         int32_t* __restrict__ flags,
+                                                         int32_t* __restrict__ status) {
   constexpr int VEC = Vec16<WT>::N;
   const int tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid / kWave;
   for (int i = blockIdx.x * kBlock + tid; i < d_ff; i += gridDim.x * kBlock) flags[i] = 0;
+  if (blockIdx.x == 0 && tid == 0) status[0] = 0;  // this path cannot abort
   const int nvec = r / VEC;
   const int gw = blockIdx.x * kWavesPerBlock + wave, nw = gridDim.x * kWavesPerBlock;
   for (int j = gw; j < d_ff; j += nw) {
@@ -240,10 +242,10 @@ hipError_t launch_general_t(const FfnProblem& p, const FfnWorkspace& ws, int den
     const int grid = min((p.d_ff + kWavesPerBlock - 1) / kWavesPerBlock, 4096);
     if (B == 1)
       hipLaunchKernelGGL((predict_kernel<WT, 1>), dim3(grid), dim3(kBlock), 0, st, k1n, p.d_ff, p.r, p.q,
-                         p.q_bf16, p.ldq, B, ws.S, ws.flags);
+                         p.q_bf16, p.ldq, B, ws.S, ws.flags, static_cast<int32_t*>(ws.fused));
     else
       hipLaunchKernelGGL((predict_kernel<WT, 4>), dim3(grid), dim3(kBlock), 0, st, k1n, p.d_ff, p.r, p.q,
-                         p.q_bf16, p.ldq, B, ws.S, ws.flags);
+                         p.q_bf16, p.ldq, B, ws.S, ws.flags, static_cast<int32_t*>(ws.fused));
   }
   hipError_t e = launch_stat_topk(ws.S, 0, B, p.d_ff, p.d_ff, p.z, 0, ws.A, p.d_ff, p.theta, p.active_count,
                                   p.active_idx, p.d_ff, ws.flags, st);
@@ -290,7 +292,6 @@ int pick_ksplit(int d_model) {
   return ks;
 }
 
-constexpr size_t kFusedScratchBytes = (size_t)8 << 20;
 
 }  // namespace
 
@@ -304,7 +305,7 @@ size_t ffn_workspace_bytes(int d_model, int d_ff, int batch) {
   t += 256;                                            // ucount
   t += align_up(F * B * 4, 256);                       // uact
   t += align_up((size_t)pick_ksplit(d_model) * B * D * 4, 256);  // part
-  t += kFusedScratchBytes;
+  t += align_up(fused_scratch_bytes(d_model), 256);
   return t;
 }
 
@@ -321,7 +322,7 @@ FfnWorkspace carve_workspace(void* base, int d_model, int d_ff, int batch) {
   ws.ksplit = pick_ksplit(d_model);
   ws.part = reinterpret_cast<float*>(p);     p += align_up((size_t)ws.ksplit * B * D * 4, 256);
   ws.fused = p;
-  ws.fused_bytes = kFusedScratchBytes;
+  ws.fused_bytes = fused_scratch_bytes(d_model);
   return ws;
 }
 

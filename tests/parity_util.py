@@ -36,7 +36,7 @@ def assert_active_set(gpu_idx, scores, theta, std, what=""):
     return len(gpu ^ ref)
 
 
-def run_gpu_ffn(shape, weights, q, gelu=binding.GELU_ERF, dense=False, via_layers=False):
+def run_gpu_ffn(shape, weights, q, gelu=binding.GELU_ERF, dense=False, via_layers=False, force_general=False):
     """weights: list of (k1n, k2n, vn) CPU tensors (one per layer); q: CPU [B, d_model]."""
     dev = torch.device("cuda:0")
     L = len(weights)
@@ -51,6 +51,7 @@ def run_gpu_ffn(shape, weights, q, gelu=binding.GELU_ERF, dense=False, via_layer
     idx = torch.full((L, B, shape.d_ff), -1, dtype=torch.int32, device=dev)
     ucnt = torch.zeros(L, dtype=torch.int32, device=dev)
     uidx = torch.full((L, shape.d_ff), -1, dtype=torch.int32, device=dev)
+    binding.spark_debug_force_general(force_general)
     if dense:
         for l in range(L):
             binding.spark_ffn_dense_decode(layers[l], qd, y[l], ws)
@@ -60,6 +61,8 @@ def run_gpu_ffn(shape, weights, q, gelu=binding.GELU_ERF, dense=False, via_layer
         for l in range(L):
             binding.spark_ffn_decode(layers[l], qd, y[l], ws, theta[l], cnt[l], idx[l], ucnt[l:l + 1],
                                      uidx[l])
+    binding.spark_debug_force_general(False)
+    binding.spark_ffn_check(ws, shape.d_model, shape.d_ff, B)     # synchronises; raises if a launch aborted
     torch.cuda.synchronize()
     return dict(y=y.cpu().numpy(), theta=theta.cpu().numpy(), count=cnt.cpu().numpy(),
                 idx=idx.cpu().numpy(), ucount=ucnt.cpu().numpy(), uidx=uidx.cpu().numpy())
@@ -80,7 +83,8 @@ def check_ffn_against_oracle(shape, weights, q, out, tol, gelu=oracle.GELU_ERF, 
             assert err <= tol, f"{tag}: y rel L2 {err:.3e} > {tol}"
             if dense:
                 continue
-            assert abs(out["theta"][l, b] - o.theta) <= 1e-5 * o.std + 1e-6 * abs(o.theta), tag
+            assert abs(out["theta"][l, b] - o.theta) <= 1e-5 * o.std + 1e-6 * abs(o.theta), (
+                f"{tag}: theta {out['theta'][l, b]!r} vs {o.theta!r} (std {o.std!r})")
             m = int(out["count"][l, b])
             gidx = out["idx"][l, b, :m]
             assert np.all(np.diff(gidx) > 0), f"{tag}: indices not ascending"

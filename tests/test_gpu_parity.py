@@ -122,10 +122,11 @@ def test_stat_topk_full_prefill_shape_sampled_rows():
 
 
 # ------------------------------------------------------------------------------- Spark-FFN decode
-def _ffn_case(shape, wdtype, qdtype, batch, n_layers=1, gelu=binding.GELU_ERF, via_layers=False, seed=1234):
+def _ffn_case(shape, wdtype, qdtype, batch, n_layers=1, gelu=binding.GELU_ERF, via_layers=False, seed=1234,
+              force_general=False):
     weights = synth.ffn_stack(shape, n_layers, base_seed=seed, dtype=wdtype)
     q = synth.tokens(shape, batch, seed + 4444, dtype=qdtype)
-    out = run_gpu_ffn(shape, weights, q, gelu=gelu, via_layers=via_layers)
+    out = run_gpu_ffn(shape, weights, q, gelu=gelu, via_layers=via_layers, force_general=force_general)
     tol = TOL_F32 if wdtype == torch.float32 else TOL_BF16
     worst = check_ffn_against_oracle(shape, weights, q, out, tol, gelu=gelu,
                                      what=f"{shape.name} {wdtype} B={batch}")
@@ -149,6 +150,39 @@ def test_ragged_shape(wdtype, batch):
 
 def test_tanh_gelu_variant():
     _ffn_case(synth.TINY, torch.float32, torch.float32, 2, gelu=binding.GELU_TANH)
+    _ffn_case(synth.TINY, torch.float32, torch.float32, 1, gelu=binding.GELU_TANH)
+
+
+# batch 1 has two implementations (one persistent launch / separate kernels): both are held to the oracle
+@pytest.mark.parametrize("force_general", [False, True])
+@pytest.mark.parametrize("shape,wdtype,qdtype", [
+    (synth.TINY, torch.float32, torch.float32), (synth.TINY, torch.bfloat16, torch.bfloat16),
+    (synth.TINY, torch.bfloat16, torch.float32), (synth.RAGGED, torch.bfloat16, torch.bfloat16),
+    (synth.RAGGED, torch.float32, torch.float32), (synth.GEMMA2_2B, torch.bfloat16, torch.bfloat16)])
+def test_batch1_both_paths(shape, wdtype, qdtype, force_general):
+    _ffn_case(shape, wdtype, qdtype, 1, n_layers=3, via_layers=True, force_general=force_general, seed=31)
+
+
+@pytest.mark.parametrize("n_layers", [1, 2, 9, 70])
+def test_persistent_launch_layer_counts(n_layers):
+    """Stacks shorter and longer than the kernel's internal rings, and longer than one launch holds."""
+    _ffn_case(synth.TINY, torch.bfloat16, torch.bfloat16, 1, n_layers=n_layers, via_layers=True, seed=500)
+
+
+def test_persistent_launch_is_reproducible():
+    sh = synth.GEMMA2_2B
+    weights = synth.ffn_stack(sh, 4, base_seed=1000, dtype=torch.bfloat16)
+    q = synth.tokens(sh, 1, 2001, torch.bfloat16)
+    a = run_gpu_ffn(sh, weights, q, via_layers=True)
+    for _ in range(3):
+        b = run_gpu_ffn(sh, weights, q, via_layers=True)
+        assert np.array_equal(a["y"], b["y"]) and np.array_equal(a["idx"], b["idx"])
+
+
+def test_paper_layer_shape_and_9b_shape():
+    _ffn_case(synth.PAPER_2B, torch.bfloat16, torch.bfloat16, 1, n_layers=2, via_layers=True, seed=9)
+    _ffn_case(synth.GEMMA2_9B, torch.bfloat16, torch.bfloat16, 1, n_layers=2, via_layers=True, seed=10)
+    _ffn_case(synth.GEMMA2_9B, torch.bfloat16, torch.bfloat16, 8, n_layers=1, seed=11)
 
 
 @pytest.mark.parametrize("batch", [1, 4])
