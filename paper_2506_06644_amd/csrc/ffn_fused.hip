@@ -39,7 +39,9 @@ namespace spark {
 namespace {
 
 constexpr int kRing = 4;       // LDS ring depth (layers) for scores / theta / mask
-constexpr int kPartRing = 4;   // ring depth (layers) of the partial-y buffer in the workspace
+constexpr int kPartRing = 6;   // ring depth (layers) of the partial-y buffer in the workspace
+constexpr int kYRing = 3;      // LDS ring depth (layers) of the gather waves' output rows
+constexpr int kReduceLag = 3;  // layers the reduce waves may trail what an exchange allowed (< kPartRing - 1)
 constexpr int kRep = 8;        // replicas of the slot array (spreads the polling over channels)
 constexpr int kSlotStride = 2048;  // u64 words between slot replicas (16 KB)
 constexpr int kMaxG = 256;
@@ -64,7 +66,7 @@ struct FusedParams {
   long long* prof;  // optional [G][16 waves][8] tick counters (testing aid), else null
   int n_layers, d_model, d_ff, r, q_bf16, gelu;
   float z;
-  int G, R, CW;
+  int G, R, DP;  // workgroups, neurons per workgroup, d_model rounded up to 16 columns
   uint32_t epoch_base;
 };
 
@@ -74,12 +76,13 @@ struct Shared {
   unsigned long long mask_ring[kRing];
   int produced[kRing];  // stream-wave completions per ring slot (layer l complete at NS * (l / kRing + 1))
   int theta_ready;  // layers whose theta / mask are posted
-  int g_consumed;   // gather-wave reads of the rings (layer l consumed at NG * (l + 1))
-  int p_done;       // gather-wave completions of partial writes
-  int r_done;       // layers reduced by this workgroup
+  int g_consumed[kRing];  // gather-wave reads of a ring slot (layer l consumed at NG * (l / kRing + 1))
+  int y_ready[kYRing];    // gather-wave rows posted per ybuf slot (layer l complete at NG * (l / kYRing + 1))
+  int y_free;       // layers whose ybuf slot the writer wave has drained
+  int p_done;       // layers whose partial row is written and acknowledged
+  int r_cnt[4];     // layers finished by each reduce wave (wave i owns layers i, i + NR, ...)
   int pd_min;       // min over workgroups of layers with partial written (as last exchanged)
   int rd_min;       // min over workgroups of layers reduced (as last exchanged)
-  int gbar;         // gather-wave barrier counter
   int abort_flag;
 };
 
@@ -144,6 +147,20 @@ __device__ __forceinline__ void st_f32(float* p, float v) {
 __device__ __forceinline__ float ld_f32(const float* p) {
   return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
+// Raw buffer access to the ring of partial outputs: 16-byte loads / stores that bypass the
+// non-coherent L2 state (sc1), addressed by a 32-bit byte offset.
+constexpr int kAuxSc1 = 16;
+__device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void* base, uint32_t bytes) {
+  return __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(base), 0, (int)bytes, 0x00020000);
+}
+__device__ __forceinline__ f32x4 buf_load_f32x4(__amdgpu_buffer_rsrc_t r, uint32_t byte_off) {
+  const u32x4 v = __builtin_amdgcn_raw_buffer_load_b128(r, (int)byte_off, 0, kAuxSc1);
+  return f32x4{__uint_as_float(v[0]), __uint_as_float(v[1]), __uint_as_float(v[2]), __uint_as_float(v[3])};
+}
+__device__ __forceinline__ void buf_store_f32x4(__amdgpu_buffer_rsrc_t r, uint32_t byte_off, f32x4 v) {
+  const u32x4 u{__float_as_uint(v[0]), __float_as_uint(v[1]), __float_as_uint(v[2]), __float_as_uint(v[3])};
+  __builtin_amdgcn_raw_buffer_store_b128(u, r, (int)byte_off, 0, kAuxSc1);
+}
 __device__ __forceinline__ void wait_vmem() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
 
 __device__ __forceinline__ int wave_min_int(int v) {
@@ -152,16 +169,51 @@ __device__ __forceinline__ int wave_min_int(int v) {
   return v;
 }
 
-// Template: storage type, chunks (16 B) per lane of a K1n / K2n / Vn row, predictor rows per
-// stream wave, number of stream / gather waves, max output columns per workgroup.
-template <typename WT, int CPL1, int CPL2, int CPLV, int RPW, int NS, int NG, int CWMAX>
-__global__ __launch_bounds__((NS + NG + 2) * kWave) void ffn_fused_kernel(const FusedParams P) {
+// Sum over the wavefront with DPP moves only (no LDS crossbar): quad swaps, row mirrors, then
+// the two row broadcasts; lane 63 ends with the total, which is returned as a uniform value.
+// The order of additions is fixed.
+template <int CTRL, int ROW_MASK>
+__device__ __forceinline__ float dpp_add(float x) {
+  const int t = __builtin_amdgcn_update_dpp(0, __float_as_int(x), CTRL, ROW_MASK, 0xf, false);
+  return x + __int_as_float(t);
+}
+__device__ __forceinline__ float wave_sum_dpp(float x) {
+  x = dpp_add<0xB1, 0xf>(x);   // quad_perm [1,0,3,2]
+  x = dpp_add<0x4E, 0xf>(x);   // quad_perm [2,3,0,1]
+  x = dpp_add<0x141, 0xf>(x);  // row_half_mirror
+  x = dpp_add<0x140, 0xf>(x);  // row_mirror
+  x = dpp_add<0x142, 0xa>(x);  // row_bcast:15 into rows 1 and 3
+  x = dpp_add<0x143, 0xc>(x);  // row_bcast:31 into rows 2 and 3
+  return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(x), 63));
+}
+
+// Layers reduced contiguously from 0 when reduce wave i has finished r_cnt[i] of its layers.
+template <int NR>
+__device__ __forceinline__ int reduced_layers(const Shared* sh) {
+  int m = 1 << 30;
+#pragma unroll
+  for (int i = 0; i < NR; ++i) m = min(m, lds_read(&sh->r_cnt[i]) * NR + i);
+  return m;
+}
+
+// Template: storage type; 16-byte chunks per lane of a K1n / K2n / Vn row; predictor rows per
+// stream wave; number of stream / gather / reduce waves.
+// Wave roles by index: 0 control, 1..NR reduce, NR+1 writer, then NG gather, then NS stream.
+//
+// Every global load below is unconditional: lanes, rows or columns that fall outside the
+// problem read a valid dummy location of the same array (chunk 0 of the same row, row 0 of the
+// slice, slot 0) and the value is discarded by a select.  This keeps the loads free of
+// per-lane branches, so they are issued back to back and waited for only where consumed.
+template <typename WT, int CPL1, int CPL2, int CPLV, int RPW, int NS, int NG, int NR>
+__global__ __launch_bounds__((NS + NG + NR + 2) * kWave) void ffn_fused_kernel(const FusedParams P) {
   constexpr int VEC = Vec16<WT>::N;
   constexpr int DM_MAX = CPLV * kWave * VEC;
   static_assert(NS * RPW <= kWave, "a workgroup owns at most 64 neurons");
+  static_assert(NR >= 1 && NR <= 4, "one to four reduce waves");
+  static_assert(NS + NG + NR + 2 <= 16, "at most 16 waves per workgroup");
   __shared__ Shared sh;
-  __shared__ float ybuf[2][NG][DM_MAX];
-  __shared__ int g_has[2][NG];
+  __shared__ float ybuf[kYRing][NG][DM_MAX];
+  __shared__ int g_has[kYRing][NG];
 
   const int tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid / kWave;
   const int w = blockIdx.x, G = P.G, R = P.R, L = P.n_layers;
@@ -170,13 +222,16 @@ __global__ __launch_bounds__((NS + NG + 2) * kWave) void ffn_fused_kernel(const 
 
   if (tid == 0) {
     for (int i = 0; i < kRing; ++i) sh.produced[i] = 0;
-    sh.theta_ready = sh.g_consumed = sh.p_done = sh.r_done = 0;
-    sh.pd_min = sh.rd_min = sh.gbar = sh.abort_flag = 0;
+    for (int i = 0; i < 4; ++i) sh.r_cnt[i] = 0;
+    for (int i = 0; i < kRing; ++i) sh.g_consumed[i] = 0;
+    for (int i = 0; i < kYRing; ++i) sh.y_ready[i] = 0;
+    sh.theta_ready = sh.y_free = sh.p_done = 0;
+    sh.pd_min = sh.rd_min = sh.abort_flag = 0;
     if (w == 0) __hip_atomic_store(P.status, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
   }
   __syncthreads();
 
-  // optional tick counters of this wave: [0] lifetime, [1..7] time spent in its wait sites
+  // optional tick counters of this wave: [0] lifetime, [1..7] time spent in its phases
   long long pw[8] = {0, 0, 0, 0, 0, 0, 0, 0};
   const bool prof = P.prof != nullptr;
   const long long t_begin = prof ? wall_clock64() : 0;
@@ -197,18 +252,42 @@ __global__ __launch_bounds__((NS + NG + 2) * kWave) void ffn_fused_kernel(const 
       float mean_w = 0.f, m2_w = 0.f, sval = 0.f;
       if (is_layer) {
         if (!wait_ge(&sh.produced[e % kRing], NS * (e / kRing + 1), &sh, P.status, W(1))) return;
-        if (e >= kRing && !wait_ge(&sh.g_consumed, NG * (e - kRing + 1), &sh, P.status, W(2))) return;
+        if (e >= kRing && !wait_ge(&sh.g_consumed[e % kRing], NG * (e / kRing), &sh, P.status, W(2))) return;
         sval = lane < Rw ? sh.s_ring[e % kRing][lane] : 0.f;
         if (Rw > 0) {
-          mean_w = wave_sum(sval) / (float)Rw;
+          mean_w = wave_sum_dpp(sval) / (float)Rw;
           const float dv = lane < Rw ? sval - mean_w : 0.f;
-          m2_w = wave_sum(dv * dv);
+          m2_w = wave_sum_dpp(dv * dv);
         }
       }
-      // the reduce wave must have caught up with what the previous exchange allowed
-      if (!wait_ge(&sh.r_done, min(pd_known, L), &sh, P.status, W(3))) return;
+      // The reduce waves may trail what the previous exchange allowed by at most kReduceLag
+      // layers; together with kPartRing > kReduceLag + 1 this keeps the ring of partials from
+      // ever blocking the exchange.
+      {
+        const int need = min(pd_known, L) - kReduceLag;
+        if (reduced_layers<NR>(&sh) < need) {
+          const long long tw = prof ? wall_clock64() : 0;
+          long long t0 = 0;
+          int spins = 0;
+          while (reduced_layers<NR>(&sh) < need) {
+            if (lds_read(&sh.abort_flag)) return;
+            __builtin_amdgcn_s_sleep(1);
+            if ((++spins & 255) == 0) {
+              const long long t = wall_clock64();
+              if (t0 == 0) {
+                t0 = t;
+              } else if (t - t0 > kTimeoutTicks) {
+                lds_write(&sh.abort_flag, 1);
+                __hip_atomic_store(P.status, 4, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                return;
+              }
+            }
+          }
+          if (prof) pw[3] += wall_clock64() - tw;
+        }
+      }
       const int cnt_prev = __popcll(prev_mask);
-      const int pdone = lds_read(&sh.p_done) / NG, rdone = lds_read(&sh.r_done);
+      const int pdone = lds_read(&sh.p_done), rdone = min(reduced_layers<NR>(&sh), L);
       const uint32_t epoch = P.epoch_base + (uint32_t)e + 1u;
       const int parity = e & 1;
       // A slot is three 64-bit words, each carrying the full epoch next to its payload, so a
@@ -229,18 +308,15 @@ __global__ __launch_bounds__((NS + NG + 2) * kWave) void ffn_fused_kernel(const 
         long long t0 = 0;
         int spins = 0;
         for (;;) {
-          bool ok = true;
 #pragma unroll
           for (int i = 0; i < kSlotsPerLane; ++i) {
             const int s = lane + kWave * i;
-            if (s < G) {
-              v0[i] = ld_u64(rp + (size_t)s * 4);
-              v1[i] = ld_u64(rp + (size_t)s * 4 + 1);
-              v2[i] = ld_u64(rp + (size_t)s * 4 + 2);
-            } else {
-              v0[i] = v1[i] = v2[i] = (unsigned long long)epoch << 32;
-            }
+            const unsigned long long* sp = rp + (size_t)(s < G ? s : 0) * 4;
+            v0[i] = ld_u64(sp);
+            v1[i] = ld_u64(sp + 1);
+            v2[i] = ld_u64(sp + 2);
           }
+          bool ok = true;
 #pragma unroll
           for (int i = 0; i < kSlotsPerLane; ++i)
             ok = ok && ((uint32_t)(v0[i] >> 32) == epoch) && ((uint32_t)(v1[i] >> 32) == epoch) &&
@@ -285,7 +361,7 @@ __global__ __launch_bounds__((NS + NG + 2) * kWave) void ffn_fused_kernel(const 
       rmin = wave_min_int(rmin);
       unsigned long long mask = 0;
       if (is_layer) {
-        const float mean = wave_sum(s1) / (float)P.d_ff;
+        const float mean = wave_sum_dpp(s1) / (float)P.d_ff;
         float m2 = 0.f;
 #pragma unroll
         for (int i = 0; i < kSlotsPerLane; ++i) {
@@ -296,7 +372,7 @@ __global__ __launch_bounds__((NS + NG + 2) * kWave) void ffn_fused_kernel(const 
             m2 += __uint_as_float((uint32_t)v1[i]) + (float)nw * d * d;
           }
         }
-        m2 = wave_sum(m2);
+        m2 = wave_sum_dpp(m2);
         const float theta = mean + sqrtf(m2 / (float)(P.d_ff - 1)) * P.z;
         mask = __ballot(lane < Rw && sval > theta);
         if (lane == 0) {
@@ -339,55 +415,113 @@ __global__ __launch_bounds__((NS + NG + 2) * kWave) void ffn_fused_kernel(const 
   }
 
   // ------------------------------------------------------------------------------ reduce
-  if (wave == 1) {
-    const int CW = P.CW;
-    for (int l = 0; l < L; ++l) {
+  if (wave < 1 + NR) {
+    // Workgroup w < DP / 16 owns output columns [16 w, 16 w + 16): one 64-byte line of every
+    // workgroup's partial row.  The other workgroups have nothing to reduce.
+    const int ri = wave - 1;
+    const int DP = P.DP;
+    const bool reader = w * 16 < DP;
+    const __amdgpu_buffer_rsrc_t prs = make_rsrc(P.part, (uint32_t)kPartRing * G * DP * 4u);
+    int done = 0;
+    for (int l = ri; reader && l < L; l += NR) {
       if (!wait_ge(&sh.pd_min, l + 1, &sh, P.status, W(1))) return;
-      // all loads of the layer are issued before the first use (one round trip, not G/64)
-      float pv[kSlotsPerLane][CWMAX];
+      const long long tl = prof ? wall_clock64() : 0;
+      // every load of the layer is issued before the first use (one round trip)
+      f32x4 pv[kSlotsPerLane][4];
 #pragma unroll
       for (int k = 0; k < kSlotsPerLane; ++k) {
         const int t = lane + kWave * k;
-        const float* src = P.part + ((size_t)((l % kPartRing) * G + w) * G + (t < G ? t : 0)) * CW;
+        const uint32_t off = ((uint32_t)((l % kPartRing) * G + (t < G ? t : 0)) * DP + (uint32_t)w * 16u) * 4u;
 #pragma unroll
-        for (int i = 0; i < CWMAX; ++i) pv[k][i] = (t < G && i < CW) ? ld_f32(src + i) : 0.f;
+        for (int i = 0; i < 4; ++i) pv[k][i] = buf_load_f32x4(prs, off + 16u * i);
       }
-      float acc[CWMAX];
+      float acc[16];
 #pragma unroll
-      for (int i = 0; i < CWMAX; ++i) {
+      for (int i = 0; i < 16; ++i) {
         acc[i] = 0.f;
 #pragma unroll
-        for (int k = 0; k < kSlotsPerLane; ++k) acc[i] += pv[k][i];
+        for (int k = 0; k < kSlotsPerLane; ++k) acc[i] += (lane + kWave * k < G) ? pv[k][i >> 2][i & 3] : 0.f;
       }
+      if (prof) pw[2] += wall_clock64() - tl;
 #pragma unroll
-      for (int i = 0; i < CWMAX; ++i) {
-        if (i < CW) {
-          const float tot = wave_sum(acc[i]);
-          const int col = w * CW + i;
-          if (lane == 0 && col < P.d_model) P.y[(size_t)l * P.d_model + col] = tot;
+      for (int i = 0; i < 16; ++i) {
+        const float tot = wave_sum_dpp(acc[i]);
+        const int col = w * 16 + i;
+        if (lane == 0 && col < P.d_model) P.y[(size_t)l * P.d_model + col] = tot;
+      }
+      ++done;
+      if (lane == 0) lds_signal_set(&sh.r_cnt[ri], done);
+      if (prof) pw[3] += wall_clock64() - tl;
+    }
+    // a wave that owns no further layer must not hold back the contiguous count
+    if (lane == 0) lds_signal_set(&sh.r_cnt[ri], 1 << 20);
+    prof_flush();
+    return;
+  }
+
+  // ------------------------------------------------------------------------------ writer
+  if (wave == 1 + NR) {
+    const int DP = P.DP;
+    const __amdgpu_buffer_rsrc_t prs = make_rsrc(P.part, (uint32_t)kPartRing * G * DP * 4u);
+    constexpr int FPL = (DM_MAX / 4 + kWave - 1) / kWave;  // float4 columns per lane
+    for (int l = 0; l < L; ++l) {
+      const int ys = l % kYRing;
+      if (!wait_ge(&sh.y_ready[ys], NG * (l / kYRing + 1), &sh, P.status, W(1))) return;
+      // sum the gather waves' rows in wave order
+      int has[NG];
+#pragma unroll
+      for (int g2 = 0; g2 < NG; ++g2) has[g2] = g_has[ys][g2];
+      f32x4 row[FPL];
+#pragma unroll
+      for (int k = 0; k < FPL; ++k) {
+        const int f = lane + kWave * k;
+        row[k] = f32x4{0.f, 0.f, 0.f, 0.f};
+        if (f * 4 < P.d_model) {
+#pragma unroll
+          for (int g2 = 0; g2 < NG; ++g2)
+            if (has[g2]) row[k] += *reinterpret_cast<const f32x4*>(&ybuf[ys][g2][f * 4]);
         }
       }
+      lds_fence();
+      if (lane == 0) lds_signal_set(&sh.y_free, l + 1);
+      // the ring slot of the partial buffer must have been reduced everywhere
+      if (l >= kPartRing && !wait_ge(&sh.rd_min, l - kPartRing + 1, &sh, P.status, W(2))) return;
+      const long long tc = prof ? wall_clock64() : 0;
+      // the workgroup's partial row, contiguous, as 16-byte write-through stores
+      const uint32_t row_off = (uint32_t)((l % kPartRing) * G + w) * DP * 4u;
+#pragma unroll
+      for (int k = 0; k < FPL; ++k) {
+        const int f = lane + kWave * k;
+        if (f * 4 < DP) buf_store_f32x4(prs, row_off + (uint32_t)f * 16u, row[k]);
+      }
       wait_vmem();
-      if (lane == 0) lds_signal_set(&sh.r_done, l + 1);
+      if (prof) pw[3] += wall_clock64() - tc;
+      if (lane == 0) lds_signal_set(&sh.p_done, l + 1);
     }
     prof_flush();
     return;
   }
 
   // ------------------------------------------------------------------------------ gather
-  if (wave < 2 + NG) {
-    const int gw = wave - 2;
+  if (wave < 2 + NR + NG) {
+    const int gw = wave - 2 - NR;
     const int nvec2 = r2 / VEC, nvecv = P.d_model / VEC;
     float q2[CPL2][VEC];
+    uint32_t koff[CPL2], voff[CPLV];  // element offsets of this lane's chunks inside a row
 #pragma unroll
     for (int c = 0; c < CPL2; ++c) {
       const int ch = lane + kWave * c;
-      if (ch < nvec2) {
-        load_q_vec<VEC>(P.q, P.q_bf16, (int64_t)P.r + (int64_t)ch * VEC, q2[c]);
-      } else {
+      koff[c] = (uint32_t)(ch < nvec2 ? ch : 0) * VEC;
+      load_q_vec<VEC>(P.q, P.q_bf16, (int64_t)P.r + koff[c], q2[c]);
+      if (ch >= nvec2) {
 #pragma unroll
         for (int e = 0; e < VEC; ++e) q2[c][e] = 0.f;
       }
+    }
+#pragma unroll
+    for (int c = 0; c < CPLV; ++c) {
+      const int ch = lane + kWave * c;
+      voff[c] = (uint32_t)(ch < nvecv ? ch : 0) * VEC;
     }
     for (int l = 0; l < L; ++l) {
       if (!wait_ge(&sh.theta_ready, l + 1, &sh, P.status, W(1))) return;
@@ -398,7 +532,7 @@ __global__ __launch_bounds__((NS + NG + 2) * kWave) void ffn_fused_kernel(const 
       const uint32_t mhi = __builtin_amdgcn_readfirstlane((uint32_t)(mask_v >> 32));
       unsigned long long m = ((unsigned long long)mhi << 32) | mlo;
       lds_fence();  // the ring reads above have returned
-      if (lane == 0) lds_signal_add(&sh.g_consumed);
+      if (lane == 0) lds_signal_add(&sh.g_consumed[l % kRing]);
 
       float yacc[CPLV][VEC];
 #pragma unroll
@@ -408,6 +542,7 @@ __global__ __launch_bounds__((NS + NG + 2) * kWave) void ffn_fused_kernel(const 
       int mine = 0;
       const WT* k2base = static_cast<const WT*>(P.k2n[l]);
       const WT* vbase = static_cast<const WT*>(P.vn[l]);
+      const long long tn = prof ? wall_clock64() : 0;
       for (int p = 0; m != 0; ++p) {
         const int nl = __builtin_ctzll(m);
         m &= m - 1;
@@ -418,68 +553,41 @@ __global__ __launch_bounds__((NS + NG + 2) * kWave) void ffn_fused_kernel(const 
         const WT* vrow = vbase + j * P.d_model;
         Vec16<WT> kreg[CPL2], vreg[CPLV];
 #pragma unroll
-        for (int c = 0; c < CPL2; ++c) {
-          const int ch = lane + kWave * c;
-          kreg[c].raw = (decltype(kreg[c].raw))(0);
-          if (ch < nvec2) kreg[c] = load_vec16<WT>(k2row + (int64_t)ch * VEC);
-        }
+        for (int c = 0; c < CPL2; ++c) kreg[c] = load_vec16<WT>(k2row + koff[c]);
 #pragma unroll
-        for (int c = 0; c < CPLV; ++c) {
-          const int ch = lane + kWave * c;
-          vreg[c].raw = (decltype(vreg[c].raw))(0);
-          if (ch < nvecv) vreg[c] = load_vec16<WT>(vrow + (int64_t)ch * VEC);
-        }
-        const long long tl = prof ? wall_clock64() : 0;
+        for (int c = 0; c < CPLV; ++c) vreg[c] = load_vec16<WT>(vrow + voff[c]);
         float g = 0.f;
 #pragma unroll
         for (int c = 0; c < CPL2; ++c)
 #pragma unroll
           for (int e = 0; e < VEC; ++e) g += kreg[c].get(e) * q2[c][e];
-        g = wave_sum(g);
-        const float a = __shfl(a_lane, nl, kWave);
+        g = wave_sum_dpp(g);
+        const float a = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(a_lane), nl));
         const float u = gelu(a, P.gelu) * g;
 #pragma unroll
         for (int c = 0; c < CPLV; ++c)
 #pragma unroll
           for (int e = 0; e < VEC; ++e) yacc[c][e] += u * vreg[c].get(e);
-        if (prof) { pw[5] += wall_clock64() - tl; pw[6] += 1; }
       }
-      const int pb = l & 1;
+      if (prof) { pw[5] += wall_clock64() - tn; pw[6] += mine; }
+      // post this wave's row to the LDS ring; the writer wave combines and stores it
+      const int ys = l % kYRing;
+      if (l >= kYRing && !wait_ge(&sh.y_free, l - kYRing + 1, &sh, P.status, W(2))) return;
       if (mine) {
 #pragma unroll
         for (int c = 0; c < CPLV; ++c) {
           const int ch = lane + kWave * c;
           if (ch < nvecv) {
+            float* dst = &ybuf[ys][gw][ch * VEC];
 #pragma unroll
-            for (int e = 0; e < VEC; ++e) ybuf[pb][gw][ch * VEC + e] = yacc[c][e];
+            for (int e = 0; e < VEC; e += 4)
+              *reinterpret_cast<f32x4*>(dst + e) = f32x4{yacc[c][e], yacc[c][e + 1], yacc[c][e + 2], yacc[c][e + 3]};
           }
         }
       }
-      if (lane == 0) g_has[pb][gw] = mine;
+      if (lane == 0) g_has[ys][gw] = mine;
       lds_fence();
-      if (lane == 0) lds_signal_add(&sh.gbar);
-      if (!wait_ge(&sh.gbar, NG * (l + 1), &sh, P.status, W(2))) return;
-      // the ring slot of the partial buffer must have been reduced everywhere
-      if (l >= kPartRing && !wait_ge(&sh.rd_min, l - kPartRing + 1, &sh, P.status, W(3))) return;
-      int has[NG];
-#pragma unroll
-      for (int g2 = 0; g2 < NG; ++g2) has[g2] = g_has[pb][g2];
-      const int CW = P.CW;
-      float* pbase = P.part + (size_t)(l % kPartRing) * G * G * CW;
-      for (int col = gw * kWave + lane; col < P.d_model; col += NG * kWave) {
-        float s = 0.f;
-#pragma unroll
-        for (int g2 = 0; g2 < NG; ++g2)
-          if (has[g2]) s += ybuf[pb][g2][col];
-        const int reader = col / CW, i = col - reader * CW;
-        st_f32(pbase + ((size_t)reader * G + w) * CW + i, s);
-      }
-      {
-        const long long tv = prof ? wall_clock64() : 0;
-        wait_vmem();
-        if (prof) pw[4] += wall_clock64() - tv;
-      }
-      if (lane == 0) lds_signal_add(&sh.p_done);
+      if (lane == 0) lds_signal_add(&sh.y_ready[ys]);
     }
     prof_flush();
     return;
@@ -487,38 +595,44 @@ __global__ __launch_bounds__((NS + NG + 2) * kWave) void ffn_fused_kernel(const 
 
   // ------------------------------------------------------------------------------ stream
   {
-    const int sw = wave - 2 - NG;
+    const int sw = wave - 2 - NR - NG;
     const int nvec1 = P.r / VEC;
     float q1[CPL1][VEC];
+    uint32_t eoff[RPW][CPL1];  // element offset of (row, chunk) inside a layer's K1n
+    bool rvalid[RPW];
 #pragma unroll
     for (int c = 0; c < CPL1; ++c) {
       const int ch = lane + kWave * c;
-      if (ch < nvec1) {
-        load_q_vec<VEC>(P.q, P.q_bf16, (int64_t)ch * VEC, q1[c]);
-      } else {
+      const uint32_t co = (uint32_t)(ch < nvec1 ? ch : 0) * VEC;
+      load_q_vec<VEC>(P.q, P.q_bf16, (int64_t)co, q1[c]);
+      if (ch >= nvec1) {
 #pragma unroll
         for (int e = 0; e < VEC; ++e) q1[c][e] = 0.f;
       }
-    }
-    Vec16<WT> reg[RPW][CPL1];
-#pragma unroll
-    for (int i = 0; i < RPW; ++i) {
-      const int lr = sw + NS * i;
-#pragma unroll
-      for (int c = 0; c < CPL1; ++c) {
-        const int ch = lane + kWave * c;
-        reg[i][c].raw = (decltype(reg[i][c].raw))(0);
-        if (lr < Rw && ch < nvec1)
-          reg[i][c] = load_vec16<WT>(static_cast<const WT*>(P.k1n[0]) + ((int64_t)w * R + lr) * P.r + (int64_t)ch * VEC);
-      }
-    }
-    for (int l = 0; l < L; ++l) {
-      if (l >= kRing && !wait_ge(&sh.g_consumed, NG * (l - kRing + 1), &sh, P.status, W(1))) return;
-      const WT* next = static_cast<const WT*>(P.k1n[l + 1 < L ? l + 1 : l]);
-      const bool more = l + 1 < L;
 #pragma unroll
       for (int i = 0; i < RPW; ++i) {
         const int lr = sw + NS * i;
+        const int row = (Rw > 0) ? w * R + (lr < Rw ? lr : 0) : 0;
+        eoff[i][c] = (uint32_t)row * (uint32_t)P.r + co;
+      }
+    }
+#pragma unroll
+    for (int i = 0; i < RPW; ++i) rvalid[i] = sw + NS * i < Rw;
+
+    Vec16<WT> reg[RPW][CPL1];
+    {
+      const WT* base0 = static_cast<const WT*>(P.k1n[0]);
+#pragma unroll
+      for (int i = 0; i < RPW; ++i)
+#pragma unroll
+        for (int c = 0; c < CPL1; ++c) reg[i][c] = load_vec16<WT>(base0 + eoff[i][c]);
+    }
+    for (int l = 0; l < L; ++l) {
+      if (l >= kRing && !wait_ge(&sh.g_consumed[l % kRing], NG * (l / kRing), &sh, P.status, W(1))) return;
+      const bool more = l + 1 < L;
+      const WT* next = static_cast<const WT*>(P.k1n[more ? l + 1 : l]);
+#pragma unroll
+      for (int i = 0; i < RPW; ++i) {
         float acc = 0.f;
 #pragma unroll
         for (int c = 0; c < CPL1; ++c)
@@ -526,14 +640,10 @@ __global__ __launch_bounds__((NS + NG + 2) * kWave) void ffn_fused_kernel(const 
           for (int e = 0; e < VEC; ++e) acc += reg[i][c].get(e) * q1[c][e];
         if (more) {
 #pragma unroll
-          for (int c = 0; c < CPL1; ++c) {
-            const int ch = lane + kWave * c;
-            if (lr < Rw && ch < nvec1)
-              reg[i][c] = load_vec16<WT>(next + ((int64_t)w * R + lr) * P.r + (int64_t)ch * VEC);
-          }
+          for (int c = 0; c < CPL1; ++c) reg[i][c] = load_vec16<WT>(next + eoff[i][c]);
         }
-        acc = wave_sum(acc);
-        if (lane == 0 && lr < Rw) sh.s_ring[l % kRing][lr] = acc;
+        acc = wave_sum_dpp(acc);
+        if (lane == 0 && rvalid[i]) sh.s_ring[l % kRing][sw + NS * i] = acc;
       }
       if (lane == 0) lds_signal_add(&sh.produced[l % kRing]);
     }
@@ -541,11 +651,11 @@ __global__ __launch_bounds__((NS + NG + 2) * kWave) void ffn_fused_kernel(const 
   }
 }
 
-template <typename WT, int CPL1, int CPL2, int CPLV, int RPW, int NS, int NG, int CWMAX>
+template <typename WT, int CPL1, int CPL2, int CPLV, int RPW, int NS, int NG, int NR>
 hipError_t launch_variant(const FusedParams& P, hipStream_t st) {
-  auto kern = ffn_fused_kernel<WT, CPL1, CPL2, CPLV, RPW, NS, NG, CWMAX>;
+  auto kern = ffn_fused_kernel<WT, CPL1, CPL2, CPLV, RPW, NS, NG, NR>;
   void* args[] = {const_cast<FusedParams*>(&P)};
-  return hipLaunchCooperativeKernel(reinterpret_cast<const void*>(kern), dim3(P.G), dim3((NS + NG + 2) * kWave),
+  return hipLaunchCooperativeKernel(reinterpret_cast<const void*>(kern), dim3(P.G), dim3((NS + NG + NR + 2) * kWave),
                                     args, 0, st);
 }
 
@@ -566,8 +676,8 @@ size_t fused_profile_bytes() { return kProfBytes; }
 
 size_t fused_scratch_bytes(int d_model) {
   const size_t slots = (size_t)2 * kRep * kSlotStride * 8;
-  const size_t cw = ((size_t)d_model + kMaxG - 1) / kMaxG;
-  const size_t part = (size_t)kPartRing * kMaxG * kMaxG * cw * 4;
+  const size_t dp = ((size_t)d_model + 15) / 16 * 16;
+  const size_t part = (size_t)kPartRing * kMaxG * dp * 4;
   return 256 + slots + part + kProfBytes;
 }
 
@@ -577,13 +687,14 @@ int fused_variant(const FfnProblem& p) {
   const int vec = p.w_bf16 ? 8 : 4;
   const int c1 = (p.r / vec + kWave - 1) / kWave, c2 = ((p.d_model - p.r) / vec + kWave - 1) / kWave;
   const int cv = (p.d_model / vec + kWave - 1) / kWave;
-  const int R = (p.d_ff + kMaxG - 1) / kMaxG, CW = (p.d_model + kMaxG - 1) / kMaxG;
+  const int R = (p.d_ff + kMaxG - 1) / kMaxG;
+  if (p.d_model > 16 * kMaxG) return -1;  // one 16-column slice per workgroup at most
   if (p.w_bf16) {
-    if (c1 <= 2 && c2 <= 3 && cv <= 5 && R <= 36 && CW <= 9) return 0;
-    if (c1 <= 3 && c2 <= 4 && cv <= 7 && R <= 56 && CW <= 14) return 1;
+    if (c1 <= 2 && c2 <= 3 && cv <= 5 && R <= 36) return 0;
+    if (c1 <= 3 && c2 <= 4 && cv <= 7 && R <= 56) return 1;
     return -1;
   }
-  if (c1 <= 4 && c2 <= 5 && cv <= 9 && R <= 36 && CW <= 9) return 2;
+  if (c1 <= 4 && c2 <= 5 && cv <= 9 && R <= 36) return 2;
   return -1;
 }
 
@@ -625,12 +736,12 @@ hipError_t launch_ffn_fused(const FfnProblem& p0, const void* const* k1n, const 
     P.z = p0.z;
     P.G = kMaxG;
     P.R = (p0.d_ff + P.G - 1) / P.G;
-    P.CW = (p0.d_model + P.G - 1) / P.G;
+    P.DP = (p0.d_model + 15) / 16 * 16;
     P.epoch_base = next_epoch_base(L);
     switch (fused_variant(p0)) {
-      case 0: err = launch_variant<bf16_t, 2, 3, 5, 4, 9, 5, 9>(P, st); break;
-      case 1: err = launch_variant<bf16_t, 3, 4, 7, 8, 7, 3, 14>(P, st); break;
-      case 2: err = launch_variant<float, 4, 5, 9, 4, 9, 5, 9>(P, st); break;
+      case 0: err = launch_variant<bf16_t, 2, 3, 5, 4, 9, 4, 1>(P, st); break;
+      case 1: err = launch_variant<bf16_t, 3, 4, 7, 8, 7, 2, 1>(P, st); break;
+      case 2: err = launch_variant<float, 4, 5, 9, 4, 9, 4, 1>(P, st); break;
       default: err = hipErrorInvalidValue; break;
     }
   }
