@@ -261,7 +261,7 @@ spark_status spark_debug_read_profile(const void* workspace, int32_t d_model, in
   size_t bytes = (size_t)n_words * 8;
   if (bytes > spark::fused_profile_bytes()) bytes = spark::fused_profile_bytes();
   hipStream_t st = static_cast<hipStream_t>(hip_stream);
-  const char* src = static_cast<const char*>(ws.fused) + spark::fused_profile_offset(d_model);
+  const char* src = static_cast<const char*>(ws.fused) + spark::fused_profile_offset(d_model, d_ff);
   if (hipMemcpyAsync(out, src, bytes, hipMemcpyDeviceToHost, st) != hipSuccess) return SPARK_ERR_DEVICE;
   return hipStreamSynchronize(st) == hipSuccess ? SPARK_OK : SPARK_ERR_DEVICE;
 }

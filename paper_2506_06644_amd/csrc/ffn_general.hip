@@ -305,7 +305,7 @@ size_t ffn_workspace_bytes(int d_model, int d_ff, int batch) {
   t += 256;                                            // ucount
   t += align_up(F * B * 4, 256);                       // uact
   t += align_up((size_t)pick_ksplit(d_model) * B * D * 4, 256);  // part
-  t += align_up(fused_scratch_bytes(d_model), 256);
+  t += align_up(fused_scratch_bytes(d_model, d_ff), 256);
   return t;
 }
 
@@ -322,7 +322,7 @@ FfnWorkspace carve_workspace(void* base, int d_model, int d_ff, int batch) {
   ws.ksplit = pick_ksplit(d_model);
   ws.part = reinterpret_cast<float*>(p);     p += align_up((size_t)ws.ksplit * B * D * 4, 256);
   ws.fused = p;
-  ws.fused_bytes = fused_scratch_bytes(d_model);
+  ws.fused_bytes = fused_scratch_bytes(d_model, d_ff);
   return ws;
 }
 

@@ -1,0 +1,845 @@
+// Spark-FFN decode (Eq.2 of arXiv 2506.06644), batch 1, as ONE persistent launch over a
+// stack of layers for gfx950, with the compute units split into two kinds of workgroup.
+//
+// A CU's vector-memory pipeline returns data in order, so a latency-critical load issued
+// behind a deep prefetch stream waits for the whole stream.  The launch therefore gives the
+// two halves of the method to different CUs (one workgroup per CU, 256 workgroups):
+//
+//   192 STREAM workgroups own d_ff / 192 neurons each.  Their waves keep the next layer's
+//     K1n rows in flight in registers (a row is re-requested for layer l+1 as soon as it has
+//     been consumed for layer l), form the predictor scores s_j = K1n[j] . q[:r] and publish
+//     each score, and the workgroup's (mean, M2) of its scores, as 64-bit words that carry the
+//     layer's epoch.  They never wait for anybody: HBM streams at full rate throughout.
+//   64 GATHER workgroups own d_ff / 64 neurons each.  Two control waves (even / odd layers)
+//     poll the 192 statistics slots and their own scores, merge the statistics in a fixed
+//     order into the global mean / std, form theta = mean + std * Q(1 - k/d_ff) (Eq.11) and
+//     the ballot mask of the active neurons (strict s > theta).  Gather waves take one active
+//     neuron at a time: its K2n and Vn rows (one contiguous burst each), g = K2n[j] . q[r:],
+//     u = GELU(s_j - theta) * g, and add u * Vn[j][:] into the wave's own LDS row.  A writer
+//     wave sums the rows in wave order and stores the workgroup's partial output; a reduce
+//     wave sums the 64 partials of the workgroup's own d_model / 64 output columns in
+//     workgroup order and writes y, and emits the compacted ascending index list.
+//
+// Everything that crosses workgroups is either a 64-bit word stamped with a per-launch epoch
+// (written and polled with agent-scope relaxed atomics, i.e. sc1: coherent across the eight
+// XCD L2s) or bulk data ordered behind such a word.  Buffers are indexed by layer, so nothing
+// is reused inside a launch and the only waits are on strictly upstream progress
+// (stream -> control -> gather -> writer -> reduce); every wait is bounded by a wall-clock
+// timeout that raises an abort flag.  All reductions have a fixed order: results are
+// reproducible bit for bit.
+#include <atomic>
+
+#include "spark_device.h"
+#include "spark_internal.h"
+
+namespace spark {
+
+namespace {
+
+constexpr int kG = 256;            // workgroups (one per CU)
+constexpr int kGroup = 32;         // consecutive workgroups per placement group (4 per XCD)
+constexpr int kGatherPer = 8;      // gather workgroups per group (the last ones: one per XCD)
+constexpr int kGS = kG / kGroup * (kGroup - kGatherPer);  // 192 stream workgroups
+constexpr int kGG = kG / kGroup * kGatherPer;             // 64 gather workgroups
+constexpr int kRing = 4;           // LDS ring depth (layers)
+constexpr int kMaskWords = 4;      // a gather workgroup owns at most 256 neurons
+constexpr int kStatSlots = 256;    // statistics slots reserved per layer
+constexpr size_t kProfBytes = (size_t)kG * 16 * 8 * 8;
+constexpr long long kTimeoutTicks = 20000000LL;  // 0.2 s of the 100 MHz wall clock
+
+struct SpecParams {
+  const void* k1n[kFusedMaxLayers];
+  const void* k2n[kFusedMaxLayers];
+  const void* vn[kFusedMaxLayers];
+  const void* q;
+  float* y;
+  float* theta;
+  int32_t* count;
+  int32_t* idx;
+  int32_t* ucount;
+  int32_t* uidx;
+  unsigned long long* stats;   // [L][kStatSlots][2]  {mean | epoch}, {M2 | epoch}
+  unsigned long long* scores;  // [L][d_ff]           {s_j | epoch}
+  unsigned long long* gcnt;    // [L][kGG]            {active count | epoch}
+  unsigned long long* gdone;   // [kGG]               {layers written | launch tag}
+  float* part;                 // [L][kGG][DP]        partial outputs
+  int32_t* status;
+  long long* prof;
+  int n_layers, d_model, d_ff, r, q_bf16, gelu;
+  float z;
+  int RS;   // neurons per stream workgroup
+  int NPG;  // neurons per gather workgroup
+  int CWG;  // output columns per gather workgroup (multiple of 4)
+  int DP;   // CWG * kGG >= d_model
+  uint32_t epoch_base;
+};
+
+__device__ __forceinline__ int lds_read(const int* p) { return *reinterpret_cast<const volatile int*>(p); }
+__device__ __forceinline__ void lds_write(int* p, int v) { *reinterpret_cast<volatile int*>(p) = v; }
+
+// LDS hand-offs between wavefronts of one workgroup: the hardware executes one wave's LDS
+// operations in order, so ordering only has to be imposed on the compiler (the "memory"
+// clobber) and on the return of earlier LDS loads (lgkmcnt).  Outstanding global loads
+// (vmcnt) are deliberately NOT waited for: the stream waves keep theirs in flight.
+__device__ __forceinline__ void lds_fence() { asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory"); }
+__device__ __forceinline__ void lds_signal_add(int* p) {
+  lds_fence();
+  atomicAdd(p, 1);
+}
+__device__ __forceinline__ void lds_signal_set(int* p, int v) {
+  lds_fence();
+  *reinterpret_cast<volatile int*>(p) = v;
+}
+
+struct Abort {
+  int* flag;        // LDS
+  int32_t* status;  // global
+};
+
+// Wall-clock guard for a spin loop: call every iteration; returns true when the launch must
+// be abandoned (somebody raised the flag, or this wait has lasted longer than the timeout).
+struct SpinGuard {
+  long long t0 = 0;
+  int spins = 0;
+  __device__ __forceinline__ bool expired(const Abort& ab, int code) {
+    if (lds_read(ab.flag)) return true;
+    if ((++spins & 127) == 0) {
+      const long long t = wall_clock64();
+      if (t0 == 0) {
+        t0 = t;
+      } else if (t - t0 > kTimeoutTicks) {
+        lds_write(ab.flag, 1);
+        __hip_atomic_store(ab.status, code, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        return true;
+      }
+    }
+    return false;
+  }
+};
+
+// Bounded wait for an LDS counter; false means the launch is being aborted.
+__device__ __forceinline__ bool wait_ge(const int* p, int target, const Abort& ab, long long* waited = nullptr) {
+  if (lds_read(p) >= target) {
+    lds_fence();
+    return true;
+  }
+  const long long tw = waited ? wall_clock64() : 0;
+  SpinGuard g;
+  while (lds_read(p) < target) {
+    if (g.expired(ab, 1)) return false;
+    __builtin_amdgcn_s_sleep(1);
+  }
+  lds_fence();
+  if (waited) *waited += wall_clock64() - tw;
+  return true;
+}
+
+__device__ __forceinline__ void st_u64(unsigned long long* p, unsigned long long v) {
+  __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ unsigned long long ld_u64(const unsigned long long* p) {
+  return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ unsigned long long pack(float v, uint32_t epoch) {
+  return ((unsigned long long)epoch << 32) | __float_as_uint(v);
+}
+__device__ __forceinline__ uint32_t hi32(unsigned long long v) { return (uint32_t)(v >> 32); }
+__device__ __forceinline__ float lo_f32(unsigned long long v) { return __uint_as_float((uint32_t)v); }
+
+// Raw buffer access (16-byte, sc1 = coherent across XCDs) to the partial outputs.
+constexpr int kAuxSc1 = 16;
+__device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void* base, uint32_t bytes) {
+  return __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(base), 0, (int)bytes, 0x00020000);
+}
+__device__ __forceinline__ f32x4 buf_load_f32x4(__amdgpu_buffer_rsrc_t r, uint32_t byte_off) {
+  const u32x4 v = __builtin_amdgcn_raw_buffer_load_b128(r, (int)byte_off, 0, kAuxSc1);
+  return f32x4{__uint_as_float(v[0]), __uint_as_float(v[1]), __uint_as_float(v[2]), __uint_as_float(v[3])};
+}
+__device__ __forceinline__ void buf_store_f32x4(__amdgpu_buffer_rsrc_t r, uint32_t byte_off, f32x4 v) {
+  const u32x4 u{__float_as_uint(v[0]), __float_as_uint(v[1]), __float_as_uint(v[2]), __float_as_uint(v[3])};
+  __builtin_amdgcn_raw_buffer_store_b128(u, r, (int)byte_off, 0, kAuxSc1);
+}
+// 16-byte weight load through a buffer descriptor: uniform base + uniform row offset (SGPR) +
+// per-lane byte offset (VGPR); no 64-bit address arithmetic per load.
+template <typename WT>
+__device__ __forceinline__ Vec16<WT> buf_load_w(__amdgpu_buffer_rsrc_t r, uint32_t lane_off, uint32_t row_off) {
+  Vec16<WT> v;
+  const u32x4 u = __builtin_amdgcn_raw_buffer_load_b128(r, (int)lane_off, (int)row_off, 0);
+  v.raw = __builtin_bit_cast(decltype(v.raw), u);
+  return v;
+}
+__device__ __forceinline__ void wait_vmem() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
+
+// Sum over the wavefront with DPP moves only (no LDS crossbar): quad swaps, row mirrors, then
+// the two row broadcasts; lane 63 ends with the total, which is returned as a uniform value.
+// The order of additions is fixed.
+template <int CTRL, int ROW_MASK>
+__device__ __forceinline__ float dpp_add(float x) {
+  const int t = __builtin_amdgcn_update_dpp(0, __float_as_int(x), CTRL, ROW_MASK, 0xf, false);
+  return x + __int_as_float(t);
+}
+__device__ __forceinline__ float wave_sum_dpp(float x) {
+  x = dpp_add<0xB1, 0xf>(x);   // quad_perm [1,0,3,2]
+  x = dpp_add<0x4E, 0xf>(x);   // quad_perm [2,3,0,1]
+  x = dpp_add<0x141, 0xf>(x);  // row_half_mirror
+  x = dpp_add<0x140, 0xf>(x);  // row_mirror
+  x = dpp_add<0x142, 0xa>(x);  // row_bcast:15 into rows 1 and 3
+  x = dpp_add<0x143, 0xc>(x);  // row_bcast:31 into rows 2 and 3
+  return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(x), 63));
+}
+
+__device__ __forceinline__ unsigned long long uniform_u64(unsigned long long v) {
+  const uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)v);
+  const uint32_t hi = __builtin_amdgcn_readfirstlane((uint32_t)(v >> 32));
+  return ((unsigned long long)hi << 32) | lo;
+}
+
+struct StreamShared {
+  float s_ring[kRing][128];
+  int produced[kRing];  // stream-wave completions per ring slot (layer l complete at NS * (l / kRing + 1))
+  int pub_done;         // layers whose statistics have been published
+};
+
+struct GatherShared {
+  float theta_ring[kRing];
+  unsigned long long mask_ring[kRing][kMaskWords];
+  float a_ring[kRing][kMaskWords * kWave];  // s_j - theta of the workgroup's neurons
+  unsigned long long mask_hist[kFusedMaxLayers][kMaskWords];
+  int theta_ready;       // layers whose theta / mask / a are posted (in layer order)
+  int g_consumed[kRing]; // gather-wave reads of a ring slot (layer l consumed at NGW * (l / kRing + 1))
+  int row_full[16];      // per gather wave: 2 * (layers posted) + (last posted row holds data)
+  int row_free[16];      // per gather wave: layers the writer has drained
+  int q2_ready;          // the shared copy of q[r:] is in LDS
+};
+
+// Template: storage type; 16-byte chunks per lane of a K1n / K2n / Vn row; predictor rows per
+// stream wave; stream waves; gather waves; 16-byte chunks per lane of a reduce slice.
+//
+// Every global load below is unconditional: lanes, rows or columns that fall outside the
+// problem read a valid dummy location of the same array (chunk 0 of the same row, row 0,
+// slot 0) and the value is discarded by a select, so loads carry no per-lane branches and
+// are issued back to back.
+template <typename WT, int CPL1, int CPL2, int CPLV, int RPW, int NS, int NGW, int CW4>
+__global__ __launch_bounds__(1024) void ffn_spec_kernel(const SpecParams P) {
+  constexpr int VEC = Vec16<WT>::N;
+  constexpr int DM_MAX = CPLV * kWave * VEC;
+  constexpr int FPL = DM_MAX / 4 / kWave;  // float4 columns per lane of an LDS row
+  static_assert(NS * RPW <= 128, "a stream workgroup owns at most 128 neurons");
+  static_assert(NS + 1 <= 16 && NGW + 5 <= 16, "at most 16 waves per workgroup");
+  __shared__ union {
+    StreamShared s;
+    GatherShared g;
+  } sh;
+  __shared__ float rows[NGW][DM_MAX];
+  __shared__ float q2s[CPL2 * kWave * VEC];  // q[r:] for the gather waves (zero past its end)
+  __shared__ int abort_flag;
+
+  const int tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid / kWave;
+  const int w = blockIdx.x, L = P.n_layers;
+  const int grp = w / kGroup, gi = w % kGroup;
+  const bool is_gather = gi >= kGroup - kGatherPer;
+  const Abort ab{&abort_flag, P.status};
+
+  if (tid == 0) {
+    abort_flag = 0;
+    if (is_gather) {
+      sh.g.theta_ready = 0;
+      sh.g.q2_ready = 0;
+      for (int i = 0; i < kRing; ++i) sh.g.g_consumed[i] = 0;
+      for (int i = 0; i < 16; ++i) sh.g.row_full[i] = sh.g.row_free[i] = 0;
+    } else {
+      for (int i = 0; i < kRing; ++i) sh.s.produced[i] = 0;
+      sh.s.pub_done = 0;
+    }
+    if (w == 0) __hip_atomic_store(P.status, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  }
+  __syncthreads();
+
+  long long pw[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+  const bool prof = P.prof != nullptr;
+  const long long t_begin = prof ? wall_clock64() : 0;
+  auto W = [&](int i) -> long long* { return prof ? &pw[i] : nullptr; };
+  auto prof_flush = [&]() {
+    if (prof && lane == 0) {
+      pw[0] = wall_clock64() - t_begin;
+      for (int i = 0; i < 8; ++i) P.prof[((size_t)w * 16 + wave) * 8 + i] = pw[i];
+    }
+  };
+
+  if (!is_gather) {
+    // ============================================================== STREAM workgroup
+    const int s = grp * (kGroup - kGatherPer) + gi;     // index among stream workgroups
+    const int RS = P.RS;
+    const int RSw = max(0, min(RS, P.d_ff - s * RS));    // neurons owned
+    if (wave < NS) {
+      const int sw = wave;
+      const int nvec1 = P.r / VEC;
+      float q1[CPL1][VEC];
+      uint32_t eoff[RPW][CPL1];  // byte offset of (row, chunk) inside a layer's K1n
+      bool rvalid[RPW];
+#pragma unroll
+      for (int c = 0; c < CPL1; ++c) {
+        const int ch = lane + kWave * c;
+        const uint32_t co = (uint32_t)(ch < nvec1 ? ch : 0) * VEC;
+        load_q_vec<VEC>(P.q, P.q_bf16, (int64_t)co, q1[c]);
+        if (ch >= nvec1) {
+#pragma unroll
+          for (int e = 0; e < VEC; ++e) q1[c][e] = 0.f;
+        }
+#pragma unroll
+        for (int i = 0; i < RPW; ++i) {
+          const int lr = sw + NS * i;
+          const int row = (RSw > 0) ? s * RS + (lr < RSw ? lr : 0) : 0;
+          eoff[i][c] = ((uint32_t)row * (uint32_t)P.r + co) * (uint32_t)sizeof(WT);
+        }
+      }
+#pragma unroll
+      for (int i = 0; i < RPW; ++i) rvalid[i] = sw + NS * i < RSw;
+
+      const uint32_t k1_bytes = (uint32_t)P.d_ff * (uint32_t)P.r * (uint32_t)sizeof(WT);
+      Vec16<WT> reg[RPW][CPL1];
+      {
+        const __amdgpu_buffer_rsrc_t b0 = make_rsrc(P.k1n[0], k1_bytes);
+#pragma unroll
+        for (int i = 0; i < RPW; ++i)
+#pragma unroll
+          for (int c = 0; c < CPL1; ++c) reg[i][c] = buf_load_w<WT>(b0, eoff[i][c], 0);
+      }
+      for (int l = 0; l < L; ++l) {
+        if (l >= kRing && !wait_ge(&sh.s.pub_done, l - kRing + 1, ab, W(1))) return;
+        const bool more = l + 1 < L;
+        const __amdgpu_buffer_rsrc_t next = make_rsrc(P.k1n[more ? l + 1 : l], k1_bytes);
+        const uint32_t epoch = P.epoch_base + (uint32_t)l + 1u;
+        unsigned long long* srow = P.scores + (size_t)l * P.d_ff + (size_t)s * RS;
+#pragma unroll
+        for (int i = 0; i < RPW; ++i) {
+          float acc = 0.f;
+#pragma unroll
+          for (int c = 0; c < CPL1; ++c)
+#pragma unroll
+            for (int e = 0; e < VEC; ++e) acc += reg[i][c].get(e) * q1[c][e];
+          if (more) {
+#pragma unroll
+            for (int c = 0; c < CPL1; ++c) reg[i][c] = buf_load_w<WT>(next, eoff[i][c], 0);
+          }
+          acc = wave_sum_dpp(acc);
+          if (lane == 0 && rvalid[i]) {
+            sh.s.s_ring[l % kRing][sw + NS * i] = acc;
+            st_u64(srow + sw + NS * i, pack(acc, epoch));
+          }
+        }
+        if (lane == 0) lds_signal_add(&sh.s.produced[l % kRing]);
+      }
+      prof_flush();
+    } else if (wave == NS) {
+      // publisher: the workgroup's (mean, M2) of each layer's scores
+      for (int l = 0; l < L; ++l) {
+        if (!wait_ge(&sh.s.produced[l % kRing], NS * (l / kRing + 1), ab, W(1))) return;
+        const float v0 = lane < RSw ? sh.s.s_ring[l % kRing][lane] : 0.f;
+        const float v1 = lane + kWave < RSw ? sh.s.s_ring[l % kRing][lane + kWave] : 0.f;
+        float mean_w = 0.f, m2_w = 0.f;
+        if (RSw > 0) {
+          mean_w = wave_sum_dpp(v0 + v1) / (float)RSw;
+          const float d0 = lane < RSw ? v0 - mean_w : 0.f;
+          const float d1 = lane + kWave < RSw ? v1 - mean_w : 0.f;
+          m2_w = wave_sum_dpp(d0 * d0 + d1 * d1);
+        }
+        const uint32_t epoch = P.epoch_base + (uint32_t)l + 1u;
+        if (lane == 0) {
+          unsigned long long* p = P.stats + ((size_t)l * kStatSlots + s) * 2;
+          st_u64(p, pack(mean_w, epoch));
+          st_u64(p + 1, pack(m2_w, epoch));
+          lds_signal_set(&sh.s.pub_done, l + 1);
+        }
+      }
+      prof_flush();
+    }
+    return;
+  }
+
+  // ================================================================ GATHER workgroup
+  const int g = grp * kGatherPer + (gi - (kGroup - kGatherPer));  // index among gather workgroups
+  const int NPG = P.NPG;
+  const int NPGg = max(0, min(NPG, P.d_ff - g * NPG));  // neurons owned
+  const int r2 = P.d_model - P.r;
+
+  // ------------------------------------------------------------------------------ control
+  if (wave < 2) {
+    for (int l = wave; l < L; l += 2) {
+      if (l >= kRing && !wait_ge(&sh.g.g_consumed[l % kRing], NGW * (l / kRing), ab, W(1))) return;
+      const uint32_t epoch = P.epoch_base + (uint32_t)l + 1u;
+      const unsigned long long* st = P.stats + (size_t)l * kStatSlots * 2;
+      const unsigned long long* sc = P.scores + (size_t)l * P.d_ff + (NPGg > 0 ? (size_t)g * NPG : 0);
+      unsigned long long m0[3], m1[3], sv[kMaskWords];
+      {
+        const long long tp = prof ? wall_clock64() : 0;
+        SpinGuard guard;
+        for (;;) {
+#pragma unroll
+          for (int k = 0; k < 3; ++k) {
+            const int t = lane + kWave * k;
+            const unsigned long long* sp = st + (size_t)(t < kGS ? t : 0) * 2;
+            m0[k] = ld_u64(sp);
+            m1[k] = ld_u64(sp + 1);
+          }
+#pragma unroll
+          for (int k = 0; k < kMaskWords; ++k) {
+            const int n = lane + kWave * k;
+            sv[k] = ld_u64(sc + (n < NPGg ? n : 0));
+          }
+          bool ok = true;
+#pragma unroll
+          for (int k = 0; k < 3; ++k) ok = ok && hi32(m0[k]) == epoch && hi32(m1[k]) == epoch;
+#pragma unroll
+          for (int k = 0; k < kMaskWords; ++k) ok = ok && (NPGg == 0 || hi32(sv[k]) == epoch);
+          if (__all(ok)) break;
+          if (guard.expired(ab, 2)) return;
+          if (prof) pw[3] += 1;
+        }
+        if (prof) pw[2] += wall_clock64() - tp;
+      }
+      // merge (Chan et al.): mean = sum n_s mean_s / n, M2 = sum M2_s + n_s (mean_s - mean)^2
+      float s1 = 0.f;
+#pragma unroll
+      for (int k = 0; k < 3; ++k) {
+        const int t = lane + kWave * k;
+        const int ns = max(0, min(P.RS, P.d_ff - t * P.RS));
+        s1 += (float)ns * lo_f32(m0[k]);
+      }
+      const float mean = wave_sum_dpp(s1) / (float)P.d_ff;
+      float m2 = 0.f;
+#pragma unroll
+      for (int k = 0; k < 3; ++k) {
+        const int t = lane + kWave * k;
+        const int ns = max(0, min(P.RS, P.d_ff - t * P.RS));
+        const float d = lo_f32(m0[k]) - mean;
+        m2 += lo_f32(m1[k]) + (float)ns * d * d;
+      }
+      m2 = wave_sum_dpp(m2);
+      const float theta = mean + sqrtf(m2 / (float)(P.d_ff - 1)) * P.z;
+      unsigned long long mask[kMaskWords];
+      int cnt = 0;
+#pragma unroll
+      for (int k = 0; k < kMaskWords; ++k) {
+        const int n = lane + kWave * k;
+        const float sval = lo_f32(sv[k]);
+        mask[k] = __ballot(n < NPGg && sval > theta);
+        cnt += __popcll(mask[k]);
+        sh.g.a_ring[l % kRing][n] = sval - theta;
+      }
+      if (lane == 0) {
+        st_u64(P.gcnt + (size_t)l * kGG + g, ((unsigned long long)epoch << 32) | (uint32_t)cnt);
+        sh.g.theta_ring[l % kRing] = theta;
+#pragma unroll
+        for (int k = 0; k < kMaskWords; ++k) {
+          sh.g.mask_ring[l % kRing][k] = mask[k];
+          sh.g.mask_hist[l][k] = mask[k];
+        }
+        if (g == 0 && P.theta) P.theta[l] = theta;
+      }
+      lds_fence();
+      // layers are posted in order: wait for the other control wave to have posted l - 1
+      if (!wait_ge(&sh.g.theta_ready, l, ab, W(4))) return;
+      if (lane == 0) lds_signal_set(&sh.g.theta_ready, l + 1);
+    }
+    prof_flush();
+    return;
+  }
+
+  // ------------------------------------------------------------------------------ writer
+  if (wave == 2) {
+    const int DP = P.DP;
+    const __amdgpu_buffer_rsrc_t prs = make_rsrc(P.part, (uint32_t)L * kGG * DP * 4u);
+    for (int l = 0; l < L; ++l) {
+      f32x4 acc[FPL];
+#pragma unroll
+      for (int k = 0; k < FPL; ++k) acc[k] = f32x4{0.f, 0.f, 0.f, 0.f};
+      for (int i = 0; i < NGW; ++i) {
+        if (!wait_ge(&sh.g.row_full[i], 2 * (l + 1), ab, W(1))) return;
+        if (lds_read(&sh.g.row_full[i]) & 1) {
+#pragma unroll
+          for (int k = 0; k < FPL; ++k) acc[k] += *reinterpret_cast<const f32x4*>(&rows[i][(lane + kWave * k) * 4]);
+        }
+        lds_fence();
+        if (lane == 0) lds_signal_set(&sh.g.row_free[i], l + 1);
+      }
+      const long long tc = prof ? wall_clock64() : 0;
+      const uint32_t row_off = (uint32_t)(l * kGG + g) * DP * 4u;
+#pragma unroll
+      for (int k = 0; k < FPL; ++k) {
+        const int f = lane + kWave * k;
+        if (f * 4 < DP) buf_store_f32x4(prs, row_off + (uint32_t)f * 16u, f * 4 < P.d_model ? acc[k] : f32x4{0.f, 0.f, 0.f, 0.f});
+      }
+      wait_vmem();
+      if (lane == 0) st_u64(P.gdone + g, ((unsigned long long)P.epoch_base << 32) | (uint32_t)(l + 1));
+      if (prof) pw[2] += wall_clock64() - tc;
+    }
+    prof_flush();
+    return;
+  }
+
+  // ------------------------------------------------------------------------------ reduce
+  if (wave < 5) {
+    const int DP = P.DP, CWG = P.CWG;
+    const __amdgpu_buffer_rsrc_t prs = make_rsrc(P.part, (uint32_t)L * kGG * DP * 4u);
+    for (int l = wave - 3; l < L; l += 2) {
+      // every gather workgroup has written layer l
+      {
+        const long long tp = prof ? wall_clock64() : 0;
+        SpinGuard guard;
+        for (;;) {
+          const unsigned long long v = ld_u64(P.gdone + (lane < kGG ? lane : 0));
+          if (__all(hi32(v) == P.epoch_base && (int)(uint32_t)v >= l + 1)) break;
+          if (guard.expired(ab, 3)) return;
+          __builtin_amdgcn_s_sleep(2);
+        }
+        if (prof) pw[1] += wall_clock64() - tp;
+      }
+      const long long tl = prof ? wall_clock64() : 0;
+      f32x4 pv[CW4];
+      const uint32_t off = ((uint32_t)(l * kGG + (lane < kGG ? lane : 0)) * DP + (uint32_t)g * CWG) * 4u;
+#pragma unroll
+      for (int i = 0; i < CW4; ++i) pv[i] = buf_load_f32x4(prs, off + 16u * (i * 4 < CWG ? i : 0));
+      const unsigned long long cv = ld_u64(P.gcnt + (size_t)l * kGG + (lane < kGG ? lane : 0));
+#pragma unroll
+      for (int i = 0; i < CW4; ++i) {
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          const float tot = wave_sum_dpp(lane < kGG ? pv[i][e] : 0.f);
+          const int col = g * CWG + i * 4 + e;
+          if (lane == 0 && i * 4 + e < CWG && col < P.d_model) P.y[(size_t)l * P.d_model + col] = tot;
+        }
+      }
+      if (prof) pw[2] += wall_clock64() - tl;
+      // compacted ascending index list: counts of all gather workgroups were published long ago
+      unsigned long long c = cv;
+      {
+        SpinGuard guard;
+        const uint32_t epoch = P.epoch_base + (uint32_t)l + 1u;
+        while (!__all(hi32(c) == epoch)) {
+          if (guard.expired(ab, 4)) return;
+          c = ld_u64(P.gcnt + (size_t)l * kGG + (lane < kGG ? lane : 0));
+        }
+      }
+      const int cn = lane < kGG ? (int)(uint32_t)c : 0;
+      const int off_g = wave_sum_int(lane < g ? cn : 0);
+      const int total = wave_sum_int(cn);
+      int below = off_g;
+#pragma unroll
+      for (int k = 0; k < kMaskWords; ++k) {
+        const unsigned long long mk = sh.g.mask_hist[l][k];
+        if ((mk >> lane) & 1ull) {
+          const int pos = below + lanes_below(mk);
+          const int j = g * NPG + lane + kWave * k;
+          if (P.idx) P.idx[(size_t)l * P.d_ff + pos] = j;
+          if (P.uidx) P.uidx[(size_t)l * P.d_ff + pos] = j;
+        }
+        below += __popcll(mk);
+      }
+      if (g == 0 && lane == 0) {
+        if (P.count) P.count[l] = total;
+        if (P.ucount) P.ucount[l] = total;
+      }
+    }
+    prof_flush();
+    return;
+  }
+
+  // ------------------------------------------------------------------------------ gather
+  // Each gather wave walks the layers' masks and takes every NGW-th active neuron (in neuron
+  // order).  Two neurons are kept in flight: the rows of the next one are requested before
+  // the current one is consumed, across layer boundaries as well, so the wave always has a
+  // load outstanding while it computes, waits for the writer, or waits for the next theta.
+  if (wave < 5 + NGW) {
+    const int gw = wave - 5;
+    const int nvec2 = r2 / VEC, nvecv = P.d_model / VEC;
+    uint32_t koff[CPL2], voff[CPLV];  // byte offsets of this lane's chunks inside a row
+#pragma unroll
+    for (int c = 0; c < CPL2; ++c) {
+      const int ch = lane + kWave * c;
+      koff[c] = (uint32_t)(ch < nvec2 ? ch : 0) * VEC * (uint32_t)sizeof(WT);
+      if (gw == 0) {  // one wave fills the shared copy of q[r:]
+        float qv[VEC];
+        load_q_vec<VEC>(P.q, P.q_bf16, (int64_t)P.r + (int64_t)(ch < nvec2 ? ch : 0) * VEC, qv);
+#pragma unroll
+        for (int e = 0; e < VEC; ++e) q2s[ch * VEC + e] = ch < nvec2 ? qv[e] : 0.f;
+      }
+    }
+#pragma unroll
+    for (int c = 0; c < CPLV; ++c) {
+      const int ch = lane + kWave * c;
+      voff[c] = (uint32_t)(ch < nvecv ? ch : 0) * VEC * (uint32_t)sizeof(WT);
+    }
+    if (gw == 0) {
+      lds_fence();
+      if (lane == 0) lds_signal_set(&sh.g.q2_ready, 1);
+    }
+    if (!wait_ge(&sh.g.q2_ready, 1, ab)) return;
+    const uint32_t k2_bytes = (uint32_t)P.d_ff * (uint32_t)r2 * (uint32_t)sizeof(WT);
+    const uint32_t v_bytes = (uint32_t)P.d_ff * (uint32_t)P.d_model * (uint32_t)sizeof(WT);
+    float* myrow = rows[gw];
+
+    // iterator over this wave's neurons (uniform state)
+    int il = 0, ik = 0, ip = 0;
+    bool have_layer = false;
+    unsigned long long mk = 0;
+    // processor state
+    int pl = 0, mine = 0;
+
+    struct Meta {
+      int valid, l;
+      float a;
+    };
+    // Closes layer pl: tells the writer whether this wave's row holds data for it.
+    auto finish_layer = [&]() -> bool {
+      if (mine == 0 && !wait_ge(&sh.g.row_free[gw], pl, ab, W(2))) return false;
+      lds_fence();
+      if (lane == 0) lds_signal_set(&sh.g.row_full[gw], 2 * (pl + 1) + (mine ? 1 : 0));
+      ++pl;
+      mine = 0;
+      return true;
+    };
+    // Finds the wave's next neuron.  valid = 0 with il < L means "theta of the next layer is
+    // not posted yet" (only when !blocking).  Returns false on abort.
+    auto next_task = [&](bool blocking, Meta& mt, int& jn) -> bool {
+      mt.valid = 0;
+      for (;;) {
+        // A blocking call is only made with no neuron in flight, so every layer the iterator
+        // has left is complete for this wave: close those layers BEFORE any wait, or the
+        // writer (and through it the other waves, the rings and the control waves) would wait
+        // for a wave that is itself waiting for a later theta.
+        if (blocking) {
+          while (pl < il)
+            if (!finish_layer()) return false;
+        }
+        if (il >= L) return true;
+        if (!have_layer) {
+          if (lds_read(&sh.g.theta_ready) < il + 1) {
+            if (!blocking) return true;
+            if (!wait_ge(&sh.g.theta_ready, il + 1, ab, W(1))) return false;
+          }
+          lds_fence();
+          have_layer = true;
+          ik = 0;
+          ip = 0;
+          mk = uniform_u64(sh.g.mask_ring[il % kRing][0]);
+        }
+        while (mk == 0 && ik < kMaskWords - 1) {
+          ++ik;
+          mk = uniform_u64(sh.g.mask_ring[il % kRing][ik]);
+        }
+        if (mk == 0) {  // layer exhausted: its ring slot has been read completely
+          lds_fence();
+          if (lane == 0) lds_signal_add(&sh.g.g_consumed[il % kRing]);
+          ++il;
+          have_layer = false;
+          continue;
+        }
+        const int nl = __builtin_ctzll(mk);
+        mk &= mk - 1;
+        const bool take = ip % NGW == gw;
+        ++ip;
+        if (!take) continue;
+        const int n = kWave * ik + nl;
+        mt.valid = 1;
+        mt.l = il;
+        mt.a = sh.g.a_ring[il % kRing][n];
+        jn = g * NPG + n;
+        return true;
+      }
+    };
+    auto issue = [&](Vec16<WT>(&kr)[CPL2], Vec16<WT>(&vr)[CPLV], const Meta& mt, int jn) {
+      const __amdgpu_buffer_rsrc_t kb = make_rsrc(P.k2n[mt.l], k2_bytes);
+      const __amdgpu_buffer_rsrc_t vb = make_rsrc(P.vn[mt.l], v_bytes);
+      const uint32_t krow = (uint32_t)jn * (uint32_t)r2 * (uint32_t)sizeof(WT);
+      const uint32_t vrow = (uint32_t)jn * (uint32_t)P.d_model * (uint32_t)sizeof(WT);
+#pragma unroll
+      for (int c = 0; c < CPL2; ++c) kr[c] = buf_load_w<WT>(kb, koff[c], krow);
+#pragma unroll
+      for (int c = 0; c < CPLV; ++c) vr[c] = buf_load_w<WT>(vb, voff[c], vrow);
+    };
+    auto process = [&](Vec16<WT>(&kr)[CPL2], Vec16<WT>(&vr)[CPLV], const Meta& mt) -> bool {
+      while (pl < mt.l)
+        if (!finish_layer()) return false;
+      float gdot = 0.f;
+#pragma unroll
+      for (int c = 0; c < CPL2; ++c) {
+        const float* qp = &q2s[(lane + kWave * c) * VEC];
+#pragma unroll
+        for (int e = 0; e < VEC; ++e) gdot += kr[c].get(e) * qp[e];
+      }
+      gdot = wave_sum_dpp(gdot);
+      const float u = gelu(mt.a, P.gelu) * gdot;
+      // the wave's LDS row: the first neuron of a layer overwrites it (once the writer has
+      // drained the previous layer), later ones add to it
+      if (mine == 0 && !wait_ge(&sh.g.row_free[gw], pl, ab, W(2))) return false;
+#pragma unroll
+      for (int c = 0; c < CPLV; ++c) {
+        const int ch = lane + kWave * c;
+        float* dst = myrow + (size_t)ch * VEC;
+        if (ch < nvecv) {
+#pragma unroll
+          for (int e = 0; e < VEC; e += 4) {
+            f32x4 t{u * vr[c].get(e), u * vr[c].get(e + 1), u * vr[c].get(e + 2), u * vr[c].get(e + 3)};
+            if (mine) t += *reinterpret_cast<const f32x4*>(dst + e);
+            *reinterpret_cast<f32x4*>(dst + e) = t;
+          }
+        }
+      }
+      ++mine;
+      if (prof) pw[6] += 1;
+      return true;
+    };
+
+    Vec16<WT> kA[CPL2], vA[CPLV], kB[CPL2], vB[CPLV];
+    Meta mA, mB;
+    int jA = 0, jB = 0;
+    if (!next_task(true, mA, jA)) return;
+    if (mA.valid) issue(kA, vA, mA, jA);
+    while (mA.valid) {
+      // B <- next (do not block while A is waiting to be consumed)
+      if (!next_task(false, mB, jB)) return;
+      if (mB.valid) issue(kB, vB, mB, jB);
+      if (!process(kA, vA, mA)) return;
+      if (!mB.valid) {  // nothing was prefetched: now block for the next one
+        if (!next_task(true, mB, jB)) return;
+        if (mB.valid) issue(kB, vB, mB, jB);
+      }
+      if (!mB.valid) break;
+      // A <- next
+      if (!next_task(false, mA, jA)) return;
+      if (mA.valid) issue(kA, vA, mA, jA);
+      if (!process(kB, vB, mB)) return;
+      if (!mA.valid) {
+        if (!next_task(true, mA, jA)) return;
+        if (mA.valid) issue(kA, vA, mA, jA);
+      }
+    }
+    while (pl < L)
+      if (!finish_layer()) return;
+    prof_flush();
+  }
+}
+
+template <typename WT, int CPL1, int CPL2, int CPLV, int RPW, int NS, int NGW, int CW4>
+hipError_t launch_variant(const SpecParams& P, hipStream_t st) {
+  auto kern = ffn_spec_kernel<WT, CPL1, CPL2, CPLV, RPW, NS, NGW, CW4>;
+  void* args[] = {const_cast<SpecParams*>(&P)};
+  constexpr int waves = (NS + 1 > NGW + 5) ? NS + 1 : NGW + 5;
+  return hipLaunchCooperativeKernel(reinterpret_cast<const void*>(kern), dim3(kG), dim3(waves * kWave), args, 0, st);
+}
+
+uint32_t next_epoch_base(int n_layers) {
+  // Process-wide counter: every launch gets epochs no earlier launch has written into a
+  // workspace, so stale words can never be mistaken for fresh ones.
+  static std::atomic<uint32_t> counter{1u};
+  uint32_t b = counter.fetch_add((uint32_t)n_layers + 64u);
+  if (b == 0) b = counter.fetch_add((uint32_t)n_layers + 64u);  // the tag 0 is never used
+  return b;
+}
+
+int g_fused_profile = 0;
+
+size_t align256(size_t v) { return (v + 255) / 256 * 256; }
+
+struct ScratchLayout {
+  size_t status, stats, scores, gcnt, gdone, part, prof, total;
+  int CWG, DP;
+};
+
+ScratchLayout scratch_layout(int d_model, int d_ff) {
+  ScratchLayout s;
+  s.CWG = ((d_model + kGG - 1) / kGG + 3) / 4 * 4;
+  s.DP = s.CWG * kGG;
+  size_t o = 0;
+  s.status = o; o += 256;
+  s.stats = o;  o += align256((size_t)kFusedMaxLayers * kStatSlots * 2 * 8);
+  s.scores = o; o += align256((size_t)kFusedMaxLayers * (size_t)d_ff * 8);
+  s.gcnt = o;   o += align256((size_t)kFusedMaxLayers * kGG * 8);
+  s.gdone = o;  o += align256((size_t)kGG * 8);
+  s.part = o;   o += align256((size_t)kFusedMaxLayers * kGG * (size_t)s.DP * 4);
+  s.prof = o;   o += kProfBytes;
+  s.total = o;
+  return s;
+}
+
+// Shape limits of the compiled variants.  Returns -1 when no variant fits.
+int spec_variant(const FfnProblem& p) {
+  const int vec = p.w_bf16 ? 8 : 4;
+  const int c1 = (p.r / vec + kWave - 1) / kWave, c2 = ((p.d_model - p.r) / vec + kWave - 1) / kWave;
+  const int cv = (p.d_model / vec + kWave - 1) / kWave;
+  const int RS = (p.d_ff + kGS - 1) / kGS, NPG = (p.d_ff + kGG - 1) / kGG;
+  const int cw4 = (((p.d_model + kGG - 1) / kGG + 3) / 4);
+  if (NPG > kMaskWords * kWave) return -1;
+  if (p.w_bf16) {
+    if (c1 <= 2 && c2 <= 3 && cv <= 5 && RS <= 48 && cw4 <= 9) return 0;
+    if (c1 <= 3 && c2 <= 4 && cv <= 7 && RS <= 75 && cw4 <= 14) return 1;
+    return -1;
+  }
+  if (c1 <= 4 && c2 <= 5 && cv <= 9 && RS <= 48 && cw4 <= 9) return 2;
+  return -1;
+}
+
+}  // namespace
+
+void fused_set_profile(int on) { g_fused_profile = on; }
+size_t fused_profile_offset(int d_model, int d_ff) { return scratch_layout(d_model, d_ff).prof; }
+size_t fused_profile_bytes() { return kProfBytes; }
+size_t fused_scratch_bytes(int d_model, int d_ff) { return scratch_layout(d_model, d_ff).total; }
+
+bool fused_supported(const FfnProblem& p, int n_layers) {
+  return p.batch == 1 && n_layers >= 1 && spec_variant(p) >= 0;
+}
+
+// layers: n_layers problems that differ only in weights and outputs' leading index.
+hipError_t launch_ffn_fused(const FfnProblem& p0, const void* const* k1n, const void* const* k2n,
+                            const void* const* vn, int n_layers, void* scratch, hipStream_t st) {
+  hipError_t err = hipSuccess;
+  const ScratchLayout lay = scratch_layout(p0.d_model, p0.d_ff);
+  char* s = static_cast<char*>(scratch);
+  for (int base = 0; base < n_layers && err == hipSuccess; base += kFusedMaxLayers) {
+    const int L = min(kFusedMaxLayers, n_layers - base);
+    SpecParams P;
+    for (int l = 0; l < L; ++l) {
+      P.k1n[l] = k1n[base + l];
+      P.k2n[l] = k2n[base + l];
+      P.vn[l] = vn[base + l];
+    }
+    for (int l = L; l < kFusedMaxLayers; ++l) P.k1n[l] = P.k2n[l] = P.vn[l] = nullptr;
+    P.q = p0.q;
+    P.y = p0.y + (size_t)base * p0.d_model;
+    P.theta = p0.theta ? p0.theta + base : nullptr;
+    P.count = p0.active_count ? p0.active_count + base : nullptr;
+    P.idx = p0.active_idx ? p0.active_idx + (size_t)base * p0.d_ff : nullptr;
+    P.ucount = p0.union_count ? p0.union_count + base : nullptr;
+    P.uidx = p0.union_idx ? p0.union_idx + (size_t)base * p0.d_ff : nullptr;
+    P.status = reinterpret_cast<int32_t*>(s + lay.status);
+    P.stats = reinterpret_cast<unsigned long long*>(s + lay.stats);
+    P.scores = reinterpret_cast<unsigned long long*>(s + lay.scores);
+    P.gcnt = reinterpret_cast<unsigned long long*>(s + lay.gcnt);
+    P.gdone = reinterpret_cast<unsigned long long*>(s + lay.gdone);
+    P.part = reinterpret_cast<float*>(s + lay.part);
+    P.prof = g_fused_profile ? reinterpret_cast<long long*>(s + lay.prof) : nullptr;
+    P.n_layers = L;
+    P.d_model = p0.d_model;
+    P.d_ff = p0.d_ff;
+    P.r = p0.r;
+    P.q_bf16 = p0.q_bf16;
+    P.gelu = p0.gelu;
+    P.z = p0.z;
+    P.RS = (p0.d_ff + kGS - 1) / kGS;
+    P.NPG = (p0.d_ff + kGG - 1) / kGG;
+    P.CWG = lay.CWG;
+    P.DP = lay.DP;
+    P.epoch_base = next_epoch_base(L);
+    switch (spec_variant(p0)) {
+      case 0: err = launch_variant<bf16_t, 2, 3, 5, 4, 12, 11, 9>(P, st); break;
+      case 1: err = launch_variant<bf16_t, 3, 4, 7, 5, 15, 8, 14>(P, st); break;
+      case 2: err = launch_variant<float, 4, 5, 9, 4, 12, 11, 9>(P, st); break;
+      default: err = hipErrorInvalidValue; break;
+    }
+  }
+  return err;
+}
+
+}  // namespace spark

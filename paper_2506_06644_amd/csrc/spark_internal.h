@@ -51,12 +51,12 @@ FfnWorkspace carve_workspace(void* base, int d_model, int d_ff, int batch);
 hipError_t launch_ffn_general(const FfnProblem& p, const FfnWorkspace& ws, int dense, hipStream_t st);
 
 // Persistent batch-1 path: one launch for up to kFusedMaxLayers layers (longer stacks are
-// chained).  `scratch` is ws.fused (fused_scratch_bytes(d_model) bytes, 256-byte aligned); its
+// chained).  `scratch` is ws.fused (fused_scratch_bytes(d_model, d_ff) bytes, 256-byte aligned); its
 // first int32 is a status word the launch clears and sets non-zero if it had to abort.
 constexpr int kFusedMaxLayers = 64;
-size_t fused_scratch_bytes(int d_model);
+size_t fused_scratch_bytes(int d_model, int d_ff);
 void fused_set_profile(int on);               // testing aid: per-wave wait-time counters
-size_t fused_profile_offset(int d_model);     // byte offset of the counters inside the scratch
+size_t fused_profile_offset(int d_model, int d_ff);     // byte offset of the counters inside the scratch
 size_t fused_profile_bytes();
 bool fused_supported(const FfnProblem& p, int n_layers);
 hipError_t launch_ffn_fused(const FfnProblem& p0, const void* const* k1n, const void* const* k2n,
