@@ -3,22 +3,27 @@
 //
 // A CU's vector-memory pipeline returns data in order, so a latency-critical load issued
 // behind a deep prefetch stream waits for the whole stream.  The launch therefore gives the
-// two halves of the method to different CUs (one workgroup per CU, 256 workgroups):
+// two halves of the method to different CUs (one workgroup per CU, 256 workgroups, GS + GG):
 //
-//   192 STREAM workgroups own d_ff / 192 neurons each.  Their waves keep the next layer's
+//   GS STREAM workgroups own d_ff / GS neurons each.  Their waves keep the next layer's
 //     K1n rows in flight in registers (a row is re-requested for layer l+1 as soon as it has
 //     been consumed for layer l), form the predictor scores s_j = K1n[j] . q[:r] and publish
 //     each score, and the workgroup's (mean, M2) of its scores, as 64-bit words that carry the
 //     layer's epoch.  They never wait for anybody: HBM streams at full rate throughout.
-//   64 GATHER workgroups own d_ff / 64 neurons each.  Two control waves (even / odd layers)
-//     poll the 192 statistics slots and their own scores, merge the statistics in a fixed
+//   GG GATHER workgroups own d_ff / GG neurons each.  Two control waves (even / odd layers)
+//     poll the GS statistics slots and their own scores, merge the statistics in a fixed
 //     order into the global mean / std, form theta = mean + std * Q(1 - k/d_ff) (Eq.11) and
 //     the ballot mask of the active neurons (strict s > theta).  Gather waves take one active
 //     neuron at a time: its K2n and Vn rows (one contiguous burst each), g = K2n[j] . q[r:],
 //     u = GELU(s_j - theta) * g, and add u * Vn[j][:] into the wave's own LDS row.  A writer
 //     wave sums the rows in wave order and stores the workgroup's partial output; a reduce
-//     wave sums the 64 partials of the workgroup's own d_model / 64 output columns in
+//     wave sums the GG partials of the workgroup's own d_model / GG output columns in
 //     workgroup order and writes y, and emits the compacted ascending index list.
+//
+// The split is a compile-time choice per shape class (128 + 128 for the Gemma-2 2B class:
+// 128 CUs still stream K1n at about three quarters of the HBM rate, and the row gathers,
+// which are bound by latency and not by bandwidth, need the other half of the chip to keep
+// enough rows in flight).
 //
 // Everything that crosses workgroups is either a 64-bit word stamped with a per-launch epoch
 // (written and polled with agent-scope relaxed atomics, i.e. sc1: coherent across the eight
@@ -38,12 +43,13 @@ namespace {
 
 constexpr int kG = 256;            // workgroups (one per CU)
 constexpr int kGroup = 32;         // consecutive workgroups per placement group (4 per XCD)
-constexpr int kGatherPer = 8;      // gather workgroups per group (the last ones: one per XCD)
-constexpr int kGS = kG / kGroup * (kGroup - kGatherPer);  // 192 stream workgroups
-constexpr int kGG = kG / kGroup * kGatherPer;             // 64 gather workgroups
+constexpr int kMaxGather = 128;    // most gather workgroups any variant uses
+constexpr int kLeaders = 8;        // gather workgroups that fan synchronisation words in and out
+constexpr int kCell = 64;          // 64-bit words between two leaders' words (separate 512-byte cells)
 constexpr int kRing = 4;           // LDS ring depth (layers)
-constexpr int kMaskWords = 4;      // a gather workgroup owns at most 256 neurons
 constexpr int kStatSlots = 256;    // statistics slots reserved per layer
+// 64-bit mask words of a gather workgroup's neurons (GP = gather workgroups per group of 32)
+constexpr int mask_words(int gp) { return gp >= 12 ? 2 : 4; }
 constexpr size_t kProfBytes = (size_t)kG * 16 * 8 * 8;
 constexpr long long kTimeoutTicks = 20000000LL;  // 0.2 s of the 100 MHz wall clock
 
@@ -60,9 +66,11 @@ struct SpecParams {
   int32_t* uidx;
   unsigned long long* stats;   // [L][kStatSlots][2]  {mean | epoch}, {M2 | epoch}
   unsigned long long* scores;  // [L][d_ff]           {s_j | epoch}
-  unsigned long long* gcnt;    // [L][kGG]            {active count | epoch}
-  unsigned long long* gdone;   // [kGG]               {layers written | launch tag}
-  float* part;                 // [L][kGG][DP]        partial outputs
+  unsigned long long* gcnt;    // [L][kMaxGather]     {active count | epoch}
+  unsigned long long* gdone;   // [kMaxGather]        {layers written | launch tag}
+  unsigned long long* thetaw;  // [L][kLeaders][64]   {theta | epoch} in word 0 of each 512-byte cell
+  unsigned long long* gdone2;  // [kLeaders][64]      {layers written by a whole group | launch tag}
+  float* part;                 // [L][GG][DP]         partial outputs
   int32_t* status;
   long long* prof;
   int n_layers, d_model, d_ff, r, q_bf16, gelu;
@@ -70,12 +78,18 @@ struct SpecParams {
   int RS;   // neurons per stream workgroup
   int NPG;  // neurons per gather workgroup
   int CWG;  // output columns per gather workgroup (multiple of 4)
-  int DP;   // CWG * kGG >= d_model
+  int DP;   // CWG * GG >= d_model
   uint32_t epoch_base;
 };
 
-__device__ __forceinline__ int lds_read(const int* p) { return *reinterpret_cast<const volatile int*>(p); }
-__device__ __forceinline__ void lds_write(int* p, int v) { *reinterpret_cast<volatile int*>(p) = v; }
+// Synchronisation words live in LDS and are accessed through pointers that carry the LDS
+// address space.  (A volatile access through a generic pointer would be emitted as a FLAT
+// instruction, which counts on vmcnt as well: every poll of a flag would then wait for the
+// wave's outstanding global loads, i.e. for the very prefetch it is supposed to overlap.)
+typedef __attribute__((address_space(3))) int lds_int_t;
+__device__ __forceinline__ volatile lds_int_t* as_lds(const int* p) { return (volatile lds_int_t*)p; }
+__device__ __forceinline__ int lds_read(const int* p) { return *as_lds(p); }
+__device__ __forceinline__ void lds_write(int* p, int v) { *as_lds(p) = v; }
 
 // LDS hand-offs between wavefronts of one workgroup: the hardware executes one wave's LDS
 // operations in order, so ordering only has to be imposed on the compiler (the "memory"
@@ -84,11 +98,11 @@ __device__ __forceinline__ void lds_write(int* p, int v) { *reinterpret_cast<vol
 __device__ __forceinline__ void lds_fence() { asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory"); }
 __device__ __forceinline__ void lds_signal_add(int* p) {
   lds_fence();
-  atomicAdd(p, 1);
+  __hip_atomic_fetch_add((lds_int_t*)p, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
 }
 __device__ __forceinline__ void lds_signal_set(int* p, int v) {
   lds_fence();
-  *reinterpret_cast<volatile int*>(p) = v;
+  *as_lds(p) = v;
 }
 
 struct Abort {
@@ -117,20 +131,20 @@ struct SpinGuard {
   }
 };
 
-// Bounded wait for an LDS counter; false means the launch is being aborted.
+// Bounded wait for an LDS counter; false means the launch is being aborted.  Kept inline on
+// purpose: across a call the compiler can no longer count the wave's outstanding loads and
+// would wait for all of them (vmcnt(0)) at the next use, defeating the prefetch.
 __device__ __forceinline__ bool wait_ge(const int* p, int target, const Abort& ab, long long* waited = nullptr) {
-  if (lds_read(p) >= target) {
-    lds_fence();
-    return true;
-  }
-  const long long tw = waited ? wall_clock64() : 0;
-  SpinGuard g;
-  while (lds_read(p) < target) {
-    if (g.expired(ab, 1)) return false;
-    __builtin_amdgcn_s_sleep(1);
+  if (lds_read(p) < target) {
+    const long long tw = waited ? wall_clock64() : 0;
+    SpinGuard g;
+    while (lds_read(p) < target) {
+      if (g.expired(ab, 1)) return false;
+      __builtin_amdgcn_s_sleep(1);
+    }
+    if (waited) *waited += wall_clock64() - tw;
   }
   lds_fence();
-  if (waited) *waited += wall_clock64() - tw;
   return true;
 }
 
@@ -200,53 +214,67 @@ struct StreamShared {
   int pub_done;         // layers whose statistics have been published
 };
 
+template <int MW>
 struct GatherShared {
   float theta_ring[kRing];
-  unsigned long long mask_ring[kRing][kMaskWords];
-  float a_ring[kRing][kMaskWords * kWave];  // s_j - theta of the workgroup's neurons
-  unsigned long long mask_hist[kFusedMaxLayers][kMaskWords];
+  unsigned long long mask_ring[kRing][MW];
+  float a_ring[kRing][MW * kWave];  // s_j - theta of the workgroup's neurons
+  unsigned long long mask_hist[kFusedMaxLayers][MW];
   int theta_ready;       // layers whose theta / mask / a are posted (in layer order)
+  int stats_seen;        // layers whose statistics a control wave has seen complete
+  int red_seen;          // layers a reduce wave has seen written by every gather workgroup
   int g_consumed[kRing]; // gather-wave reads of a ring slot (layer l consumed at NGW * (l / kRing + 1))
-  int row_full[16];      // per gather wave: 2 * (layers posted) + (last posted row holds data)
+  int row_full[32];      // per (gather wave, row slot): 2 * (layer posted + 1) + (the row holds data)
   int row_free[16];      // per gather wave: layers the writer has drained
   int q2_ready;          // the shared copy of q[r:] is in LDS
 };
 
-// Template: storage type; 16-byte chunks per lane of a K1n / K2n / Vn row; predictor rows per
-// stream wave; stream waves; gather waves; 16-byte chunks per lane of a reduce slice.
+// Template: storage type; gather workgroups per placement group of 32; 16-byte chunks per lane
+// of a K1n / K2n / Vn row; predictor rows per stream wave; stream waves; gather waves; LDS
+// rows per gather wave (layers a gather wave may run ahead of the writer); 16-byte chunks per
+// writer of a reduce slice.
 //
 // Every global load below is unconditional: lanes, rows or columns that fall outside the
 // problem read a valid dummy location of the same array (chunk 0 of the same row, row 0,
 // slot 0) and the value is discarded by a select, so loads carry no per-lane branches and
 // are issued back to back.
-template <typename WT, int CPL1, int CPL2, int CPLV, int RPW, int NS, int NGW, int CW4>
+template <typename WT, int GP, int CPL1, int CPL2, int CPLV, int RPW, int NS, int NGW, int RB, int CW4, bool PROF>
 __global__ __launch_bounds__(1024) void ffn_spec_kernel(const SpecParams P) {
   constexpr int VEC = Vec16<WT>::N;
-  constexpr int DM_MAX = CPLV * kWave * VEC;
-  constexpr int FPL = DM_MAX / 4 / kWave;  // float4 columns per lane of an LDS row
+  constexpr int GS = kG / kGroup * (kGroup - GP);  // stream workgroups
+  constexpr int GG = kG / kGroup * GP;             // gather workgroups
+  constexpr int SPL = (GS + kWave - 1) / kWave;    // statistics slots per lane of a control wave
+  constexpr int WPL = (GG + kWave - 1) / kWave;    // writers per lane of a reduce wave
+  constexpr int MW = mask_words(GP);
+  constexpr int FPL = CPLV * VEC / 4;              // float4 columns per lane of an LDS row
   static_assert(NS * RPW <= 128, "a stream workgroup owns at most 128 neurons");
-  static_assert(NS + 1 <= 16 && NGW + 5 <= 16, "at most 16 waves per workgroup");
+  static_assert(NS + 1 <= 16 && NGW + 6 <= 16, "at most 16 waves per workgroup");
+  static_assert(GG % kLeaders == 0 && GG / kLeaders <= kWave, "leader groups");
+  static_assert(NGW * RB <= 32, "row_full slots");
   __shared__ union {
     StreamShared s;
-    GatherShared g;
+    GatherShared<MW> g;
   } sh;
-  __shared__ float rows[NGW][DM_MAX];
   __shared__ float q2s[CPL2 * kWave * VEC];  // q[r:] for the gather waves (zero past its end)
   __shared__ int abort_flag;
+  extern __shared__ __align__(16) float rows[];  // [NGW][RB][d_model]
 
   const int tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid / kWave;
   const int w = blockIdx.x, L = P.n_layers;
   const int grp = w / kGroup, gi = w % kGroup;
-  const bool is_gather = gi >= kGroup - kGatherPer;
+  const bool is_gather = gi >= kGroup - GP;
   const Abort ab{&abort_flag, P.status};
 
   if (tid == 0) {
     abort_flag = 0;
     if (is_gather) {
       sh.g.theta_ready = 0;
+      sh.g.stats_seen = 0;
+      sh.g.red_seen = 0;
       sh.g.q2_ready = 0;
       for (int i = 0; i < kRing; ++i) sh.g.g_consumed[i] = 0;
-      for (int i = 0; i < 16; ++i) sh.g.row_full[i] = sh.g.row_free[i] = 0;
+      for (int i = 0; i < 32; ++i) sh.g.row_full[i] = 0;
+      for (int i = 0; i < 16; ++i) sh.g.row_free[i] = 0;
     } else {
       for (int i = 0; i < kRing; ++i) sh.s.produced[i] = 0;
       sh.s.pub_done = 0;
@@ -256,7 +284,7 @@ __global__ __launch_bounds__(1024) void ffn_spec_kernel(const SpecParams P) {
   __syncthreads();
 
   long long pw[8] = {0, 0, 0, 0, 0, 0, 0, 0};
-  const bool prof = P.prof != nullptr;
+  constexpr bool prof = PROF;  // compiled out of the production kernels
   const long long t_begin = prof ? wall_clock64() : 0;
   auto W = [&](int i) -> long long* { return prof ? &pw[i] : nullptr; };
   auto prof_flush = [&]() {
@@ -268,15 +296,15 @@ __global__ __launch_bounds__(1024) void ffn_spec_kernel(const SpecParams P) {
 
   if (!is_gather) {
     // ============================================================== STREAM workgroup
-    const int s = grp * (kGroup - kGatherPer) + gi;     // index among stream workgroups
+    const int s = grp * (kGroup - GP) + gi;             // index among stream workgroups
     const int RS = P.RS;
     const int RSw = max(0, min(RS, P.d_ff - s * RS));    // neurons owned
     if (wave < NS) {
       const int sw = wave;
       const int nvec1 = P.r / VEC;
       float q1[CPL1][VEC];
-      uint32_t eoff[RPW][CPL1];  // byte offset of (row, chunk) inside a layer's K1n
-      bool rvalid[RPW];
+      uint32_t loff[CPL1];  // byte offset of this lane's chunks inside a row (VGPR)
+      uint32_t roff[RPW];   // byte offset of the wave's rows inside a layer's K1n (SGPR)
 #pragma unroll
       for (int c = 0; c < CPL1; ++c) {
         const int ch = lane + kWave * c;
@@ -286,31 +314,38 @@ __global__ __launch_bounds__(1024) void ffn_spec_kernel(const SpecParams P) {
 #pragma unroll
           for (int e = 0; e < VEC; ++e) q1[c][e] = 0.f;
         }
-#pragma unroll
-        for (int i = 0; i < RPW; ++i) {
-          const int lr = sw + NS * i;
-          const int row = (RSw > 0) ? s * RS + (lr < RSw ? lr : 0) : 0;
-          eoff[i][c] = ((uint32_t)row * (uint32_t)P.r + co) * (uint32_t)sizeof(WT);
-        }
+        loff[c] = co * (uint32_t)sizeof(WT);
       }
 #pragma unroll
-      for (int i = 0; i < RPW; ++i) rvalid[i] = sw + NS * i < RSw;
+      for (int i = 0; i < RPW; ++i) {
+        const int lr = sw + NS * i;
+        const int row = (RSw > 0) ? s * RS + (lr < RSw ? lr : 0) : 0;
+        roff[i] = __builtin_amdgcn_readfirstlane((uint32_t)row * (uint32_t)P.r * (uint32_t)sizeof(WT));
+      }
 
       const uint32_t k1_bytes = (uint32_t)P.d_ff * (uint32_t)P.r * (uint32_t)sizeof(WT);
       Vec16<WT> reg[RPW][CPL1];
       {
         const __amdgpu_buffer_rsrc_t b0 = make_rsrc(P.k1n[0], k1_bytes);
 #pragma unroll
-        for (int i = 0; i < RPW; ++i)
+        for (int i = 0; i < RPW; ++i) {
 #pragma unroll
-          for (int c = 0; c < CPL1; ++c) reg[i][c] = buf_load_w<WT>(b0, eoff[i][c], 0);
+          for (int c = 0; c < CPL1; ++c) reg[i][c] = buf_load_w<WT>(b0, loff[c], roff[i]);
+          // Rows are requested in the order in which they are consumed, here and in the loop:
+          // the wait before a row's use then only has to cover that row's own loads.
+          __builtin_amdgcn_sched_barrier(0);
+        }
       }
       for (int l = 0; l < L; ++l) {
         if (l >= kRing && !wait_ge(&sh.s.pub_done, l - kRing + 1, ab, W(1))) return;
+        // The rows are re-requested for the next layer as soon as they have been consumed.
+        // After the last layer the descriptor has zero records: the loads are still issued
+        // (so the number of loads in flight stays a compile-time constant and the waits can
+        // be exact) but return zeros without touching memory.
         const bool more = l + 1 < L;
-        const __amdgpu_buffer_rsrc_t next = make_rsrc(P.k1n[more ? l + 1 : l], k1_bytes);
+        const __amdgpu_buffer_rsrc_t next = make_rsrc(P.k1n[more ? l + 1 : l], more ? k1_bytes : 0u);
         const uint32_t epoch = P.epoch_base + (uint32_t)l + 1u;
-        unsigned long long* srow = P.scores + (size_t)l * P.d_ff + (size_t)s * RS;
+        float mys = 0.f;  // lane i keeps the score of the wave's i-th row
 #pragma unroll
         for (int i = 0; i < RPW; ++i) {
           float acc = 0.f;
@@ -318,15 +353,15 @@ __global__ __launch_bounds__(1024) void ffn_spec_kernel(const SpecParams P) {
           for (int c = 0; c < CPL1; ++c)
 #pragma unroll
             for (int e = 0; e < VEC; ++e) acc += reg[i][c].get(e) * q1[c][e];
-          if (more) {
 #pragma unroll
-            for (int c = 0; c < CPL1; ++c) reg[i][c] = buf_load_w<WT>(next, eoff[i][c], 0);
-          }
+          for (int c = 0; c < CPL1; ++c) reg[i][c] = buf_load_w<WT>(next, loff[c], roff[i]);
           acc = wave_sum_dpp(acc);
-          if (lane == 0 && rvalid[i]) {
-            sh.s.s_ring[l % kRing][sw + NS * i] = acc;
-            st_u64(srow + sw + NS * i, pack(acc, epoch));
-          }
+          mys = lane == i ? acc : mys;
+          __builtin_amdgcn_sched_barrier(0);
+        }
+        if (lane < RPW && sw + NS * lane < RSw) {
+          sh.s.s_ring[l % kRing][sw + NS * lane] = mys;
+          st_u64(P.scores + (size_t)l * P.d_ff + (size_t)s * RS + sw + NS * lane, pack(mys, epoch));
         }
         if (lane == 0) lds_signal_add(&sh.s.produced[l % kRing]);
       }
@@ -358,10 +393,18 @@ __global__ __launch_bounds__(1024) void ffn_spec_kernel(const SpecParams P) {
   }
 
   // ================================================================ GATHER workgroup
-  const int g = grp * kGatherPer + (gi - (kGroup - kGatherPer));  // index among gather workgroups
+  const int g = grp * GP + (gi - (kGroup - GP));  // index among gather workgroups
   const int NPG = P.NPG;
   const int NPGg = max(0, min(NPG, P.d_ff - g * NPG));  // neurons owned
   const int r2 = P.d_model - P.r;
+  // Synchronisation words that every gather workgroup would otherwise poll (the GS statistics
+  // slots of a layer, the GG "written" words) sit in a few cache lines of one memory channel:
+  // polled by all workgroups they turn that channel into a hot spot that throttles every
+  // stream passing through it.  One leader per group of GG / 8 gather workgroups therefore
+  // does the wide poll and republishes a single word for its group.
+  constexpr int GPL = GG / kLeaders;  // gather workgroups per leader
+  const int lead = g / GPL;
+  const bool is_leader = g % GPL == 0;
 
   // ------------------------------------------------------------------------------ control
   if (wave < 2) {
@@ -370,57 +413,84 @@ __global__ __launch_bounds__(1024) void ffn_spec_kernel(const SpecParams P) {
       const uint32_t epoch = P.epoch_base + (uint32_t)l + 1u;
       const unsigned long long* st = P.stats + (size_t)l * kStatSlots * 2;
       const unsigned long long* sc = P.scores + (size_t)l * P.d_ff + (NPGg > 0 ? (size_t)g * NPG : 0);
-      unsigned long long m0[3], m1[3], sv[kMaskWords];
-      {
-        const long long tp = prof ? wall_clock64() : 0;
+      // the other control wave has seen layer l - 1 (a layer cannot complete before its
+      // predecessor, so polling earlier would only add traffic)
+      if (!wait_ge(&sh.g.stats_seen, l, ab, W(4))) return;
+      unsigned long long sv[MW];
+      float theta;
+      const long long tp = prof ? wall_clock64() : 0;
+      if (is_leader) {
+        unsigned long long m0[SPL], m1[SPL];
         SpinGuard guard;
         for (;;) {
 #pragma unroll
-          for (int k = 0; k < 3; ++k) {
+          for (int k = 0; k < SPL; ++k) {
             const int t = lane + kWave * k;
-            const unsigned long long* sp = st + (size_t)(t < kGS ? t : 0) * 2;
+            const unsigned long long* sp = st + (size_t)(t < GS ? t : 0) * 2;
             m0[k] = ld_u64(sp);
             m1[k] = ld_u64(sp + 1);
           }
+          bool ok = true;
 #pragma unroll
-          for (int k = 0; k < kMaskWords; ++k) {
+          for (int k = 0; k < SPL; ++k) ok = ok && hi32(m0[k]) == epoch && hi32(m1[k]) == epoch;
+          if (__all(ok)) break;
+          if (guard.expired(ab, 2)) return;
+          if (prof) pw[3] += 1;
+        }
+        // merge (Chan et al.): mean = sum n_s mean_s / n, M2 = sum M2_s + n_s (mean_s - mean)^2
+        float s1 = 0.f;
+#pragma unroll
+        for (int k = 0; k < SPL; ++k) {
+          const int t = lane + kWave * k;
+          const int ns = t < GS ? max(0, min(P.RS, P.d_ff - t * P.RS)) : 0;
+          s1 += (float)ns * lo_f32(m0[k]);
+        }
+        const float mean = wave_sum_dpp(s1) / (float)P.d_ff;
+        float m2 = 0.f;
+#pragma unroll
+        for (int k = 0; k < SPL; ++k) {
+          const int t = lane + kWave * k;
+          const int ns = t < GS ? max(0, min(P.RS, P.d_ff - t * P.RS)) : 0;
+          const float d = lo_f32(m0[k]) - mean;
+          m2 += (t < GS ? lo_f32(m1[k]) : 0.f) + (float)ns * d * d;
+        }
+        m2 = wave_sum_dpp(m2);
+        theta = mean + sqrtf(m2 / (float)(P.d_ff - 1)) * P.z;
+        if (lane == 0) st_u64(P.thetaw + ((size_t)l * kLeaders + lead) * kCell, pack(theta, epoch));
+      } else {
+        const unsigned long long* tw = P.thetaw + ((size_t)l * kLeaders + lead) * kCell;
+        SpinGuard guard;
+        unsigned long long v;
+        for (;;) {
+          v = ld_u64(tw);
+          if (__all(hi32(v) == epoch)) break;
+          if (guard.expired(ab, 2)) return;
+          if (prof) pw[3] += 1;
+          __builtin_amdgcn_s_sleep(2);
+        }
+        theta = lo_f32(uniform_u64(v));
+      }
+      {
+        SpinGuard guard;
+        for (;;) {
+#pragma unroll
+          for (int k = 0; k < MW; ++k) {
             const int n = lane + kWave * k;
             sv[k] = ld_u64(sc + (n < NPGg ? n : 0));
           }
           bool ok = true;
 #pragma unroll
-          for (int k = 0; k < 3; ++k) ok = ok && hi32(m0[k]) == epoch && hi32(m1[k]) == epoch;
-#pragma unroll
-          for (int k = 0; k < kMaskWords; ++k) ok = ok && (NPGg == 0 || hi32(sv[k]) == epoch);
+          for (int k = 0; k < MW; ++k) ok = ok && (NPGg == 0 || hi32(sv[k]) == epoch);
           if (__all(ok)) break;
-          if (guard.expired(ab, 2)) return;
-          if (prof) pw[3] += 1;
+          if (guard.expired(ab, 5)) return;
         }
-        if (prof) pw[2] += wall_clock64() - tp;
       }
-      // merge (Chan et al.): mean = sum n_s mean_s / n, M2 = sum M2_s + n_s (mean_s - mean)^2
-      float s1 = 0.f;
-#pragma unroll
-      for (int k = 0; k < 3; ++k) {
-        const int t = lane + kWave * k;
-        const int ns = max(0, min(P.RS, P.d_ff - t * P.RS));
-        s1 += (float)ns * lo_f32(m0[k]);
-      }
-      const float mean = wave_sum_dpp(s1) / (float)P.d_ff;
-      float m2 = 0.f;
-#pragma unroll
-      for (int k = 0; k < 3; ++k) {
-        const int t = lane + kWave * k;
-        const int ns = max(0, min(P.RS, P.d_ff - t * P.RS));
-        const float d = lo_f32(m0[k]) - mean;
-        m2 += lo_f32(m1[k]) + (float)ns * d * d;
-      }
-      m2 = wave_sum_dpp(m2);
-      const float theta = mean + sqrtf(m2 / (float)(P.d_ff - 1)) * P.z;
-      unsigned long long mask[kMaskWords];
+      if (lane == 0) lds_signal_set(&sh.g.stats_seen, l + 1);
+      if (prof) pw[2] += wall_clock64() - tp;
+      unsigned long long mask[MW];
       int cnt = 0;
 #pragma unroll
-      for (int k = 0; k < kMaskWords; ++k) {
+      for (int k = 0; k < MW; ++k) {
         const int n = lane + kWave * k;
         const float sval = lo_f32(sv[k]);
         mask[k] = __ballot(n < NPGg && sval > theta);
@@ -428,10 +498,10 @@ __global__ __launch_bounds__(1024) void ffn_spec_kernel(const SpecParams P) {
         sh.g.a_ring[l % kRing][n] = sval - theta;
       }
       if (lane == 0) {
-        st_u64(P.gcnt + (size_t)l * kGG + g, ((unsigned long long)epoch << 32) | (uint32_t)cnt);
+        st_u64(P.gcnt + (size_t)l * kMaxGather + g, ((unsigned long long)epoch << 32) | (uint32_t)cnt);
         sh.g.theta_ring[l % kRing] = theta;
 #pragma unroll
-        for (int k = 0; k < kMaskWords; ++k) {
+        for (int k = 0; k < MW; ++k) {
           sh.g.mask_ring[l % kRing][k] = mask[k];
           sh.g.mask_hist[l][k] = mask[k];
         }
@@ -439,7 +509,7 @@ __global__ __launch_bounds__(1024) void ffn_spec_kernel(const SpecParams P) {
       }
       lds_fence();
       // layers are posted in order: wait for the other control wave to have posted l - 1
-      if (!wait_ge(&sh.g.theta_ready, l, ab, W(4))) return;
+      if (!wait_ge(&sh.g.theta_ready, l, ab, W(5))) return;
       if (lane == 0) lds_signal_set(&sh.g.theta_ready, l + 1);
     }
     prof_flush();
@@ -449,26 +519,31 @@ __global__ __launch_bounds__(1024) void ffn_spec_kernel(const SpecParams P) {
   // ------------------------------------------------------------------------------ writer
   if (wave == 2) {
     const int DP = P.DP;
-    const __amdgpu_buffer_rsrc_t prs = make_rsrc(P.part, (uint32_t)L * kGG * DP * 4u);
+    const __amdgpu_buffer_rsrc_t prs = make_rsrc(P.part, (uint32_t)L * GG * DP * 4u);
     for (int l = 0; l < L; ++l) {
       f32x4 acc[FPL];
 #pragma unroll
       for (int k = 0; k < FPL; ++k) acc[k] = f32x4{0.f, 0.f, 0.f, 0.f};
       for (int i = 0; i < NGW; ++i) {
-        if (!wait_ge(&sh.g.row_full[i], 2 * (l + 1), ab, W(1))) return;
-        if (lds_read(&sh.g.row_full[i]) & 1) {
+        const int slot = i * RB + l % RB;
+        if (!wait_ge(&sh.g.row_full[slot], 2 * (l + 1), ab, W(1))) return;
+        if (lds_read(&sh.g.row_full[slot]) & 1) {
+          const float* row = rows + (size_t)slot * P.d_model;
 #pragma unroll
-          for (int k = 0; k < FPL; ++k) acc[k] += *reinterpret_cast<const f32x4*>(&rows[i][(lane + kWave * k) * 4]);
+          for (int k = 0; k < FPL; ++k) {
+            const int f = lane + kWave * k;
+            if (f * 4 < P.d_model) acc[k] += *reinterpret_cast<const f32x4*>(&row[f * 4]);
+          }
         }
         lds_fence();
         if (lane == 0) lds_signal_set(&sh.g.row_free[i], l + 1);
       }
       const long long tc = prof ? wall_clock64() : 0;
-      const uint32_t row_off = (uint32_t)(l * kGG + g) * DP * 4u;
+      const uint32_t row_off = (uint32_t)(l * GG + g) * DP * 4u;
 #pragma unroll
       for (int k = 0; k < FPL; ++k) {
         const int f = lane + kWave * k;
-        if (f * 4 < DP) buf_store_f32x4(prs, row_off + (uint32_t)f * 16u, f * 4 < P.d_model ? acc[k] : f32x4{0.f, 0.f, 0.f, 0.f});
+        if (f * 4 < DP) buf_store_f32x4(prs, row_off + (uint32_t)f * 16u, acc[k]);
       }
       wait_vmem();
       if (lane == 0) st_u64(P.gdone + g, ((unsigned long long)P.epoch_base << 32) | (uint32_t)(l + 1));
@@ -481,52 +556,78 @@ __global__ __launch_bounds__(1024) void ffn_spec_kernel(const SpecParams P) {
   // ------------------------------------------------------------------------------ reduce
   if (wave < 5) {
     const int DP = P.DP, CWG = P.CWG;
-    const __amdgpu_buffer_rsrc_t prs = make_rsrc(P.part, (uint32_t)L * kGG * DP * 4u);
+    const __amdgpu_buffer_rsrc_t prs = make_rsrc(P.part, (uint32_t)L * GG * DP * 4u);
+    const bool want_idx = P.idx || P.uidx || P.count || P.ucount;
     for (int l = wave - 3; l < L; l += 2) {
-      // every gather workgroup has written layer l
+      // every gather workgroup has written layer l: the leaders' group words say so
+      if (!wait_ge(&sh.g.red_seen, l, ab, W(3))) return;
       {
         const long long tp = prof ? wall_clock64() : 0;
         SpinGuard guard;
         for (;;) {
-          const unsigned long long v = ld_u64(P.gdone + (lane < kGG ? lane : 0));
+          const unsigned long long v = ld_u64(P.gdone2 + (size_t)(lane < kLeaders ? lane : 0) * kCell);
           if (__all(hi32(v) == P.epoch_base && (int)(uint32_t)v >= l + 1)) break;
           if (guard.expired(ab, 3)) return;
           __builtin_amdgcn_s_sleep(2);
         }
+        if (lane == 0) lds_signal_set(&sh.g.red_seen, l + 1);
         if (prof) pw[1] += wall_clock64() - tp;
       }
       const long long tl = prof ? wall_clock64() : 0;
-      f32x4 pv[CW4];
-      const uint32_t off = ((uint32_t)(l * kGG + (lane < kGG ? lane : 0)) * DP + (uint32_t)g * CWG) * 4u;
+      f32x4 pv[WPL][CW4];
+      unsigned long long cv[WPL];
 #pragma unroll
-      for (int i = 0; i < CW4; ++i) pv[i] = buf_load_f32x4(prs, off + 16u * (i * 4 < CWG ? i : 0));
-      const unsigned long long cv = ld_u64(P.gcnt + (size_t)l * kGG + (lane < kGG ? lane : 0));
+      for (int j = 0; j < WPL; ++j) {
+        const int wi = lane + kWave * j;
+        const uint32_t off = ((uint32_t)(l * GG + (wi < GG ? wi : 0)) * DP + (uint32_t)g * CWG) * 4u;
+#pragma unroll
+        for (int i = 0; i < CW4; ++i) pv[j][i] = buf_load_f32x4(prs, off + 16u * (i * 4 < CWG ? i : 0));
+        cv[j] = want_idx ? ld_u64(P.gcnt + (size_t)l * kMaxGather + (wi < GG ? wi : 0)) : 0ull;
+      }
 #pragma unroll
       for (int i = 0; i < CW4; ++i) {
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
-          const float tot = wave_sum_dpp(lane < kGG ? pv[i][e] : 0.f);
+          float mine = 0.f;  // this lane's writers, in ascending workgroup order
+#pragma unroll
+          for (int j = 0; j < WPL; ++j) mine += (lane + kWave * j < GG) ? pv[j][i][e] : 0.f;
+          const float tot = wave_sum_dpp(mine);
           const int col = g * CWG + i * 4 + e;
           if (lane == 0 && i * 4 + e < CWG && col < P.d_model) P.y[(size_t)l * P.d_model + col] = tot;
         }
       }
       if (prof) pw[2] += wall_clock64() - tl;
+      if (!want_idx) continue;
       // compacted ascending index list: counts of all gather workgroups were published long ago
-      unsigned long long c = cv;
       {
         SpinGuard guard;
         const uint32_t epoch = P.epoch_base + (uint32_t)l + 1u;
-        while (!__all(hi32(c) == epoch)) {
+        for (;;) {
+          bool ok = true;
+#pragma unroll
+          for (int j = 0; j < WPL; ++j) ok = ok && hi32(cv[j]) == epoch;
+          if (__all(ok)) break;
           if (guard.expired(ab, 4)) return;
-          c = ld_u64(P.gcnt + (size_t)l * kGG + (lane < kGG ? lane : 0));
+#pragma unroll
+          for (int j = 0; j < WPL; ++j) {
+            const int wi = lane + kWave * j;
+            cv[j] = ld_u64(P.gcnt + (size_t)l * kMaxGather + (wi < GG ? wi : 0));
+          }
         }
       }
-      const int cn = lane < kGG ? (int)(uint32_t)c : 0;
-      const int off_g = wave_sum_int(lane < g ? cn : 0);
-      const int total = wave_sum_int(cn);
+      int before = 0, all = 0;
+#pragma unroll
+      for (int j = 0; j < WPL; ++j) {
+        const int wi = lane + kWave * j;
+        const int cn = wi < GG ? (int)(uint32_t)cv[j] : 0;
+        before += wi < g ? cn : 0;
+        all += cn;
+      }
+      const int off_g = wave_sum_int(before);
+      const int total = wave_sum_int(all);
       int below = off_g;
 #pragma unroll
-      for (int k = 0; k < kMaskWords; ++k) {
+      for (int k = 0; k < MW; ++k) {
         const unsigned long long mk = sh.g.mask_hist[l][k];
         if ((mk >> lane) & 1ull) {
           const int pos = below + lanes_below(mk);
@@ -546,10 +647,10 @@ __global__ __launch_bounds__(1024) void ffn_spec_kernel(const SpecParams P) {
   }
 
   // ------------------------------------------------------------------------------ gather
-  // Each gather wave walks the layers' masks and takes every NGW-th active neuron (in neuron
-  // order).  Two neurons are kept in flight: the rows of the next one are requested before
-  // the current one is consumed, across layer boundaries as well, so the wave always has a
-  // load outstanding while it computes, waits for the writer, or waits for the next theta.
+  // The active neurons of a layer are dealt to the gather waves round-robin (rotated from
+  // layer to layer so that every wave gets its share of idle layers).  A wave handles its
+  // neurons one at a time and adds them into its LDS row of the layer; RB rows per wave let
+  // it run ahead of the writer by RB - 1 layers.
   if (wave < 5 + NGW) {
     const int gw = wave - 5;
     const int nvec2 = r2 / VEC, nvecv = P.d_model / VEC;
@@ -577,156 +678,111 @@ __global__ __launch_bounds__(1024) void ffn_spec_kernel(const SpecParams P) {
     if (!wait_ge(&sh.g.q2_ready, 1, ab)) return;
     const uint32_t k2_bytes = (uint32_t)P.d_ff * (uint32_t)r2 * (uint32_t)sizeof(WT);
     const uint32_t v_bytes = (uint32_t)P.d_ff * (uint32_t)P.d_model * (uint32_t)sizeof(WT);
-    float* myrow = rows[gw];
 
-    // iterator over this wave's neurons (uniform state)
-    int il = 0, ik = 0, ip = 0;
-    bool have_layer = false;
-    unsigned long long mk = 0;
-    // processor state
-    int pl = 0, mine = 0;
-
-    struct Meta {
-      int valid, l;
-      float a;
-    };
-    // Closes layer pl: tells the writer whether this wave's row holds data for it.
-    auto finish_layer = [&]() -> bool {
-      if (mine == 0 && !wait_ge(&sh.g.row_free[gw], pl, ab, W(2))) return false;
+    for (int l = 0; l < L; ++l) {
+      if (!wait_ge(&sh.g.theta_ready, l + 1, ab, W(1))) return;
+      const int slot = gw * RB + l % RB;
+      float* myrow = rows + (size_t)slot * P.d_model;
+      const __amdgpu_buffer_rsrc_t kb = make_rsrc(P.k2n[l], k2_bytes);
+      const __amdgpu_buffer_rsrc_t vb = make_rsrc(P.vn[l], v_bytes);
+      int ip = (l * 3) % NGW, mine = 0;
+#pragma unroll
+      for (int k = 0; k < MW; ++k) {
+        unsigned long long mk = uniform_u64(sh.g.mask_ring[l % kRing][k]);
+        while (mk) {
+          const int nl = __builtin_ctzll(mk);
+          mk &= mk - 1;
+          const bool take = ip == gw;
+          ip = ip + 1 == NGW ? 0 : ip + 1;
+          if (!take) continue;
+          const int n = kWave * k + nl;
+          const float a = sh.g.a_ring[l % kRing][n];
+          const uint32_t jn = (uint32_t)(g * NPG + n);
+          const uint32_t krow = jn * (uint32_t)r2 * (uint32_t)sizeof(WT);
+          const uint32_t vrow = jn * (uint32_t)P.d_model * (uint32_t)sizeof(WT);
+          const long long tq0 = prof ? wall_clock64() : 0;
+          Vec16<WT> kr[CPL2], vr[CPLV];
+#pragma unroll
+          for (int c = 0; c < CPL2; ++c) kr[c] = buf_load_w<WT>(kb, koff[c], krow);
+#pragma unroll
+          for (int c = 0; c < CPLV; ++c) vr[c] = buf_load_w<WT>(vb, voff[c], vrow);
+          float gdot = 0.f;
+#pragma unroll
+          for (int c = 0; c < CPL2; ++c) {
+            const float* qp = &q2s[(lane + kWave * c) * VEC];
+#pragma unroll
+            for (int e = 0; e < VEC; ++e) gdot += kr[c].get(e) * qp[e];
+          }
+          gdot = wave_sum_dpp(gdot);
+          const float u = gelu(a, P.gelu) * gdot;
+          if (prof) pw[3] += wall_clock64() - tq0;
+          // the wave's LDS row of this layer: the first neuron overwrites it (once the writer
+          // has drained the layer that used the row before), later ones add to it
+          if (mine == 0 && l >= RB && !wait_ge(&sh.g.row_free[gw], l - RB + 1, ab, W(2))) return;
+#pragma unroll
+          for (int c = 0; c < CPLV; ++c) {
+            const int ch = lane + kWave * c;
+            float* dst = myrow + (size_t)ch * VEC;
+            if (ch < nvecv) {
+#pragma unroll
+              for (int e = 0; e < VEC; e += 4) {
+                f32x4 t{u * vr[c].get(e), u * vr[c].get(e + 1), u * vr[c].get(e + 2), u * vr[c].get(e + 3)};
+                if (mine) t += *reinterpret_cast<const f32x4*>(dst + e);
+                *reinterpret_cast<f32x4*>(dst + e) = t;
+              }
+            }
+          }
+          ++mine;
+          if (prof) {
+            pw[6] += 1;
+            pw[5] += wall_clock64() - tq0;
+          }
+        }
+      }
       lds_fence();
-      if (lane == 0) lds_signal_set(&sh.g.row_full[gw], 2 * (pl + 1) + (mine ? 1 : 0));
-      ++pl;
-      mine = 0;
-      return true;
-    };
-    // Finds the wave's next neuron.  valid = 0 with il < L means "theta of the next layer is
-    // not posted yet" (only when !blocking).  Returns false on abort.
-    auto next_task = [&](bool blocking, Meta& mt, int& jn) -> bool {
-      mt.valid = 0;
-      for (;;) {
-        // A blocking call is only made with no neuron in flight, so every layer the iterator
-        // has left is complete for this wave: close those layers BEFORE any wait, or the
-        // writer (and through it the other waves, the rings and the control waves) would wait
-        // for a wave that is itself waiting for a later theta.
-        if (blocking) {
-          while (pl < il)
-            if (!finish_layer()) return false;
-        }
-        if (il >= L) return true;
-        if (!have_layer) {
-          if (lds_read(&sh.g.theta_ready) < il + 1) {
-            if (!blocking) return true;
-            if (!wait_ge(&sh.g.theta_ready, il + 1, ab, W(1))) return false;
-          }
-          lds_fence();
-          have_layer = true;
-          ik = 0;
-          ip = 0;
-          mk = uniform_u64(sh.g.mask_ring[il % kRing][0]);
-        }
-        while (mk == 0 && ik < kMaskWords - 1) {
-          ++ik;
-          mk = uniform_u64(sh.g.mask_ring[il % kRing][ik]);
-        }
-        if (mk == 0) {  // layer exhausted: its ring slot has been read completely
-          lds_fence();
-          if (lane == 0) lds_signal_add(&sh.g.g_consumed[il % kRing]);
-          ++il;
-          have_layer = false;
-          continue;
-        }
-        const int nl = __builtin_ctzll(mk);
-        mk &= mk - 1;
-        const bool take = ip % NGW == gw;
-        ++ip;
-        if (!take) continue;
-        const int n = kWave * ik + nl;
-        mt.valid = 1;
-        mt.l = il;
-        mt.a = sh.g.a_ring[il % kRing][n];
-        jn = g * NPG + n;
-        return true;
-      }
-    };
-    auto issue = [&](Vec16<WT>(&kr)[CPL2], Vec16<WT>(&vr)[CPLV], const Meta& mt, int jn) {
-      const __amdgpu_buffer_rsrc_t kb = make_rsrc(P.k2n[mt.l], k2_bytes);
-      const __amdgpu_buffer_rsrc_t vb = make_rsrc(P.vn[mt.l], v_bytes);
-      const uint32_t krow = (uint32_t)jn * (uint32_t)r2 * (uint32_t)sizeof(WT);
-      const uint32_t vrow = (uint32_t)jn * (uint32_t)P.d_model * (uint32_t)sizeof(WT);
-#pragma unroll
-      for (int c = 0; c < CPL2; ++c) kr[c] = buf_load_w<WT>(kb, koff[c], krow);
-#pragma unroll
-      for (int c = 0; c < CPLV; ++c) vr[c] = buf_load_w<WT>(vb, voff[c], vrow);
-    };
-    auto process = [&](Vec16<WT>(&kr)[CPL2], Vec16<WT>(&vr)[CPLV], const Meta& mt) -> bool {
-      while (pl < mt.l)
-        if (!finish_layer()) return false;
-      float gdot = 0.f;
-#pragma unroll
-      for (int c = 0; c < CPL2; ++c) {
-        const float* qp = &q2s[(lane + kWave * c) * VEC];
-#pragma unroll
-        for (int e = 0; e < VEC; ++e) gdot += kr[c].get(e) * qp[e];
-      }
-      gdot = wave_sum_dpp(gdot);
-      const float u = gelu(mt.a, P.gelu) * gdot;
-      // the wave's LDS row: the first neuron of a layer overwrites it (once the writer has
-      // drained the previous layer), later ones add to it
-      if (mine == 0 && !wait_ge(&sh.g.row_free[gw], pl, ab, W(2))) return false;
-#pragma unroll
-      for (int c = 0; c < CPLV; ++c) {
-        const int ch = lane + kWave * c;
-        float* dst = myrow + (size_t)ch * VEC;
-        if (ch < nvecv) {
-#pragma unroll
-          for (int e = 0; e < VEC; e += 4) {
-            f32x4 t{u * vr[c].get(e), u * vr[c].get(e + 1), u * vr[c].get(e + 2), u * vr[c].get(e + 3)};
-            if (mine) t += *reinterpret_cast<const f32x4*>(dst + e);
-            *reinterpret_cast<f32x4*>(dst + e) = t;
-          }
-        }
-      }
-      ++mine;
-      if (prof) pw[6] += 1;
-      return true;
-    };
+      if (lane == 0) lds_signal_add(&sh.g.g_consumed[l % kRing]);
+      // the slot's previous posting must have been read before it is overwritten
+      if (mine == 0 && l >= RB && !wait_ge(&sh.g.row_free[gw], l - RB + 1, ab, W(2))) return;
+      if (lane == 0) lds_signal_set(&sh.g.row_full[slot], 2 * (l + 1) + (mine ? 1 : 0));
+    }
+    prof_flush();
+    return;
+  }
 
-    Vec16<WT> kA[CPL2], vA[CPLV], kB[CPL2], vB[CPLV];
-    Meta mA, mB;
-    int jA = 0, jB = 0;
-    if (!next_task(true, mA, jA)) return;
-    if (mA.valid) issue(kA, vA, mA, jA);
-    while (mA.valid) {
-      // B <- next (do not block while A is waiting to be consumed)
-      if (!next_task(false, mB, jB)) return;
-      if (mB.valid) issue(kB, vB, mB, jB);
-      if (!process(kA, vA, mA)) return;
-      if (!mB.valid) {  // nothing was prefetched: now block for the next one
-        if (!next_task(true, mB, jB)) return;
-        if (mB.valid) issue(kB, vB, mB, jB);
-      }
-      if (!mB.valid) break;
-      // A <- next
-      if (!next_task(false, mA, jA)) return;
-      if (mA.valid) issue(kA, vA, mA, jA);
-      if (!process(kB, vB, mB)) return;
-      if (!mA.valid) {
-        if (!next_task(true, mA, jA)) return;
-        if (mA.valid) issue(kA, vA, mA, jA);
+  // ------------------------------------------------------------------------------ collector
+  // In a leader workgroup: republishes min(layers written) over the group's writers.
+  if (wave == 5 + NGW && is_leader) {
+    int published = 0;
+    SpinGuard guard;
+    while (published < L) {
+      const unsigned long long v = ld_u64(P.gdone + g + (lane < GPL ? lane : 0));
+      const int done = hi32(v) == P.epoch_base ? (int)(uint32_t)v : 0;
+      int m = done;
+#pragma unroll
+      for (int o = 32; o >= 1; o >>= 1) m = min(m, __shfl_xor(m, o));
+      if (m > published) {
+        published = m;
+        if (lane == 0) st_u64(P.gdone2 + (size_t)lead * kCell, ((unsigned long long)P.epoch_base << 32) | (uint32_t)m);
+        guard = SpinGuard();
+      } else {
+        if (guard.expired(ab, 6)) return;
+        __builtin_amdgcn_s_sleep(2);
       }
     }
-    while (pl < L)
-      if (!finish_layer()) return;
     prof_flush();
   }
 }
 
-template <typename WT, int CPL1, int CPL2, int CPLV, int RPW, int NS, int NGW, int CW4>
+template <typename WT, int GP, int CPL1, int CPL2, int CPLV, int RPW, int NS, int NGW, int RB, int CW4>
 hipError_t launch_variant(const SpecParams& P, hipStream_t st) {
-  auto kern = ffn_spec_kernel<WT, CPL1, CPL2, CPLV, RPW, NS, NGW, CW4>;
+  const void* kern = P.prof ? reinterpret_cast<const void*>(ffn_spec_kernel<WT, GP, CPL1, CPL2, CPLV, RPW, NS, NGW, RB, CW4, true>)
+                            : reinterpret_cast<const void*>(ffn_spec_kernel<WT, GP, CPL1, CPL2, CPLV, RPW, NS, NGW, RB, CW4, false>);
+  const size_t dyn = (size_t)NGW * RB * (size_t)P.d_model * sizeof(float);
+  hipError_t err = hipFuncSetAttribute(kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)dyn);
+  if (err != hipSuccess) return err;
   void* args[] = {const_cast<SpecParams*>(&P)};
-  constexpr int waves = (NS + 1 > NGW + 5) ? NS + 1 : NGW + 5;
-  return hipLaunchCooperativeKernel(reinterpret_cast<const void*>(kern), dim3(kG), dim3(waves * kWave), args, 0, st);
+  constexpr int waves = (NS + 1 > NGW + 6) ? NS + 1 : NGW + 6;
+  return hipLaunchCooperativeKernel(kern, dim3(kG), dim3(waves * kWave), args, dyn, st);
 }
 
 uint32_t next_epoch_base(int n_layers) {
@@ -743,41 +799,79 @@ int g_fused_profile = 0;
 size_t align256(size_t v) { return (v + 255) / 256 * 256; }
 
 struct ScratchLayout {
-  size_t status, stats, scores, gcnt, gdone, part, prof, total;
-  int CWG, DP;
+  size_t status, stats, scores, gcnt, gdone, thetaw, gdone2, part, prof, total;
 };
 
+// Sized for the variant with the most gather workgroups (a partial row is at most
+// d_model + 4 * kMaxGather floats long), so the size depends on the shape only.
 ScratchLayout scratch_layout(int d_model, int d_ff) {
   ScratchLayout s;
-  s.CWG = ((d_model + kGG - 1) / kGG + 3) / 4 * 4;
-  s.DP = s.CWG * kGG;
   size_t o = 0;
   s.status = o; o += 256;
   s.stats = o;  o += align256((size_t)kFusedMaxLayers * kStatSlots * 2 * 8);
   s.scores = o; o += align256((size_t)kFusedMaxLayers * (size_t)d_ff * 8);
-  s.gcnt = o;   o += align256((size_t)kFusedMaxLayers * kGG * 8);
-  s.gdone = o;  o += align256((size_t)kGG * 8);
-  s.part = o;   o += align256((size_t)kFusedMaxLayers * kGG * (size_t)s.DP * 4);
+  s.gcnt = o;   o += align256((size_t)kFusedMaxLayers * kMaxGather * 8);
+  s.gdone = o;  o += align256((size_t)kMaxGather * 8);
+  s.thetaw = o; o += align256((size_t)kFusedMaxLayers * kLeaders * kCell * 8);
+  s.gdone2 = o; o += align256((size_t)kLeaders * kCell * 8);
+  s.part = o;   o += align256((size_t)kFusedMaxLayers * kMaxGather * ((size_t)d_model + 4 * kMaxGather) * 4);
   s.prof = o;   o += kProfBytes;
   s.total = o;
   return s;
 }
 
-// Shape limits of the compiled variants.  Returns -1 when no variant fits.
+// The compiled variants and their shape limits.
+struct Variant {
+  int bf16, gp, cpl1, cpl2, cplv, rpw, ns, ngw, rb, cw4;
+};
+constexpr Variant kVariants[] = {
+    {1, 16, 2, 3, 5, 6, 12, 8, 2, 5},    // Gemma-2 2B class
+    {1, 16, 2, 3, 5, 8, 14, 8, 2, 5},    // the same with the wider d_ff of the paper's 2B model
+    {1, 8, 3, 4, 7, 5, 15, 10, 1, 14},   // Gemma-2 9B class
+    {0, 8, 4, 5, 9, 4, 12, 10, 1, 9},    // fp32 weights
+};
+constexpr int kNumVariants = sizeof(kVariants) / sizeof(kVariants[0]);
+constexpr size_t kMaxRowBytes = 148 * 1024;  // dynamic LDS left for the gather waves' rows
+
+struct Split {
+  int GS, GG, RS, NPG, CWG, DP;
+};
+Split split_for(const Variant& v, int d_model, int d_ff) {
+  Split s;
+  s.GS = kG / kGroup * (kGroup - v.gp);
+  s.GG = kG / kGroup * v.gp;
+  s.RS = (d_ff + s.GS - 1) / s.GS;
+  s.NPG = (d_ff + s.GG - 1) / s.GG;
+  s.CWG = ((d_model + s.GG - 1) / s.GG + 3) / 4 * 4;
+  s.DP = s.CWG * s.GG;
+  return s;
+}
+
+// Returns -1 when no variant fits.
 int spec_variant(const FfnProblem& p) {
   const int vec = p.w_bf16 ? 8 : 4;
   const int c1 = (p.r / vec + kWave - 1) / kWave, c2 = ((p.d_model - p.r) / vec + kWave - 1) / kWave;
   const int cv = (p.d_model / vec + kWave - 1) / kWave;
-  const int RS = (p.d_ff + kGS - 1) / kGS, NPG = (p.d_ff + kGG - 1) / kGG;
-  const int cw4 = (((p.d_model + kGG - 1) / kGG + 3) / 4);
-  if (NPG > kMaskWords * kWave) return -1;
-  if (p.w_bf16) {
-    if (c1 <= 2 && c2 <= 3 && cv <= 5 && RS <= 48 && cw4 <= 9) return 0;
-    if (c1 <= 3 && c2 <= 4 && cv <= 7 && RS <= 75 && cw4 <= 14) return 1;
-    return -1;
+  for (int i = 0; i < kNumVariants; ++i) {
+    const Variant& v = kVariants[i];
+    if (v.bf16 != (p.w_bf16 ? 1 : 0)) continue;
+    const Split s = split_for(v, p.d_model, p.d_ff);
+    if (c1 > v.cpl1 || c2 > v.cpl2 || cv > v.cplv) continue;
+    if (s.RS > v.rpw * v.ns || s.NPG > mask_words(v.gp) * kWave) continue;
+    if (s.CWG > v.cw4 * 4 || s.DP > v.cplv * vec * kWave) continue;
+    if ((size_t)v.ngw * v.rb * p.d_model * sizeof(float) > kMaxRowBytes) continue;
+    return i;
   }
-  if (c1 <= 4 && c2 <= 5 && cv <= 9 && RS <= 48 && cw4 <= 9) return 2;
   return -1;
+}
+
+template <int I>
+hipError_t launch_index(const SpecParams& P, hipStream_t st) {
+  constexpr Variant v = kVariants[I];
+  if constexpr (v.bf16)
+    return launch_variant<bf16_t, v.gp, v.cpl1, v.cpl2, v.cplv, v.rpw, v.ns, v.ngw, v.rb, v.cw4>(P, st);
+  else
+    return launch_variant<float, v.gp, v.cpl1, v.cpl2, v.cplv, v.rpw, v.ns, v.ngw, v.rb, v.cw4>(P, st);
 }
 
 }  // namespace
@@ -796,6 +890,9 @@ hipError_t launch_ffn_fused(const FfnProblem& p0, const void* const* k1n, const 
                             const void* const* vn, int n_layers, void* scratch, hipStream_t st) {
   hipError_t err = hipSuccess;
   const ScratchLayout lay = scratch_layout(p0.d_model, p0.d_ff);
+  const int vi = spec_variant(p0);
+  if (vi < 0) return hipErrorInvalidValue;
+  const Split sp = split_for(kVariants[vi], p0.d_model, p0.d_ff);
   char* s = static_cast<char*>(scratch);
   for (int base = 0; base < n_layers && err == hipSuccess; base += kFusedMaxLayers) {
     const int L = min(kFusedMaxLayers, n_layers - base);
@@ -818,6 +915,8 @@ hipError_t launch_ffn_fused(const FfnProblem& p0, const void* const* k1n, const 
     P.scores = reinterpret_cast<unsigned long long*>(s + lay.scores);
     P.gcnt = reinterpret_cast<unsigned long long*>(s + lay.gcnt);
     P.gdone = reinterpret_cast<unsigned long long*>(s + lay.gdone);
+    P.thetaw = reinterpret_cast<unsigned long long*>(s + lay.thetaw);
+    P.gdone2 = reinterpret_cast<unsigned long long*>(s + lay.gdone2);
     P.part = reinterpret_cast<float*>(s + lay.part);
     P.prof = g_fused_profile ? reinterpret_cast<long long*>(s + lay.prof) : nullptr;
     P.n_layers = L;
@@ -827,15 +926,16 @@ hipError_t launch_ffn_fused(const FfnProblem& p0, const void* const* k1n, const 
     P.q_bf16 = p0.q_bf16;
     P.gelu = p0.gelu;
     P.z = p0.z;
-    P.RS = (p0.d_ff + kGS - 1) / kGS;
-    P.NPG = (p0.d_ff + kGG - 1) / kGG;
-    P.CWG = lay.CWG;
-    P.DP = lay.DP;
+    P.RS = sp.RS;
+    P.NPG = sp.NPG;
+    P.CWG = sp.CWG;
+    P.DP = sp.DP;
     P.epoch_base = next_epoch_base(L);
-    switch (spec_variant(p0)) {
-      case 0: err = launch_variant<bf16_t, 2, 3, 5, 4, 12, 11, 9>(P, st); break;
-      case 1: err = launch_variant<bf16_t, 3, 4, 7, 5, 15, 8, 14>(P, st); break;
-      case 2: err = launch_variant<float, 4, 5, 9, 4, 12, 11, 9>(P, st); break;
+    switch (vi) {
+      case 0: err = launch_index<0>(P, st); break;
+      case 1: err = launch_index<1>(P, st); break;
+      case 2: err = launch_index<2>(P, st); break;
+      case 3: err = launch_index<3>(P, st); break;
       default: err = hipErrorInvalidValue; break;
     }
   }
