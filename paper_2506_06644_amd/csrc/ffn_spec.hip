@@ -33,6 +33,7 @@
 // timeout that raises an abort flag.  All reductions have a fixed order: results are
 // reproducible bit for bit.
 #include <atomic>
+#include <cstdlib>
 
 #include "spark_device.h"
 #include "spark_internal.h"
@@ -77,8 +78,9 @@ struct SpecParams {
   float z;
   int RS;   // neurons per stream workgroup
   int NPG;  // neurons per gather workgroup
-  int CWG;  // output columns per gather workgroup (multiple of 4)
-  int DP;   // CWG * GG >= d_model
+  int CWG;  // output columns per reducing workgroup (multiple of 16)
+  int NR;   // reducing workgroups, ceil(d_model / CWG) <= GG
+  int DP;   // CWG * NR >= d_model: floats per partial row
   uint32_t epoch_base;
 };
 
@@ -221,7 +223,6 @@ struct GatherShared {
   float a_ring[kRing][MW * kWave];  // s_j - theta of the workgroup's neurons
   unsigned long long mask_hist[kFusedMaxLayers][MW];
   int theta_ready;       // layers whose theta / mask / a are posted (in layer order)
-  int stats_seen;        // layers whose statistics a control wave has seen complete
   int red_seen;          // layers a reduce wave has seen written by every gather workgroup
   int g_consumed[kRing]; // gather-wave reads of a ring slot (layer l consumed at NGW * (l / kRing + 1))
   int row_full[32];      // per (gather wave, row slot): 2 * (layer posted + 1) + (the row holds data)
@@ -238,7 +239,7 @@ struct GatherShared {
 // problem read a valid dummy location of the same array (chunk 0 of the same row, row 0,
 // slot 0) and the value is discarded by a select, so loads carry no per-lane branches and
 // are issued back to back.
-template <typename WT, int GP, int CPL1, int CPL2, int CPLV, int RPW, int NS, int NGW, int RB, int CW4, bool PROF>
+template <typename WT, int GP, int CPL1, int CPL2, int CPLV, int RPW, int RIF, int NS, int NGW, int RB, int CW4, bool PROF>
 __global__ __launch_bounds__(1024) void ffn_spec_kernel(const SpecParams P) {
   constexpr int VEC = Vec16<WT>::N;
   constexpr int GS = kG / kGroup * (kGroup - GP);  // stream workgroups
@@ -269,7 +270,6 @@ __global__ __launch_bounds__(1024) void ffn_spec_kernel(const SpecParams P) {
     abort_flag = 0;
     if (is_gather) {
       sh.g.theta_ready = 0;
-      sh.g.stats_seen = 0;
       sh.g.red_seen = 0;
       sh.g.q2_ready = 0;
       for (int i = 0; i < kRing; ++i) sh.g.g_consumed[i] = 0;
@@ -292,6 +292,12 @@ __global__ __launch_bounds__(1024) void ffn_spec_kernel(const SpecParams P) {
       pw[0] = wall_clock64() - t_begin;
       for (int i = 0; i < 8; ++i) P.prof[((size_t)w * 16 + wave) * 8 + i] = pw[i];
     }
+  };
+
+  // profiling only: absolute time at which this wave finished layer 0 / the middle layer
+  auto mark = [&](int l) {
+    if (prof && l == 0) pw[6] = wall_clock64();
+    if (prof && l == L - 1) pw[7] = wall_clock64();
   };
 
   if (!is_gather) {
@@ -324,11 +330,16 @@ __global__ __launch_bounds__(1024) void ffn_spec_kernel(const SpecParams P) {
       }
 
       const uint32_t k1_bytes = (uint32_t)P.d_ff * (uint32_t)P.r * (uint32_t)sizeof(WT);
+      // The wave keeps RIF of its RPW rows in flight: row n + RIF (counting across layers) is
+      // requested right after row n has been consumed.  The depth is a trade: enough bytes in
+      // flight to cover the memory latency at full rate, but no more, because everything
+      // beyond that only queues in front of the gather workgroups' latency-bound loads.
+      static_assert(RIF >= 1 && RIF <= RPW, "rows in flight");
       Vec16<WT> reg[RPW][CPL1];
       {
         const __amdgpu_buffer_rsrc_t b0 = make_rsrc(P.k1n[0], k1_bytes);
 #pragma unroll
-        for (int i = 0; i < RPW; ++i) {
+        for (int i = 0; i < RIF; ++i) {
 #pragma unroll
           for (int c = 0; c < CPL1; ++c) reg[i][c] = buf_load_w<WT>(b0, loff[c], roff[i]);
           // Rows are requested in the order in which they are consumed, here and in the loop:
@@ -338,11 +349,11 @@ __global__ __launch_bounds__(1024) void ffn_spec_kernel(const SpecParams P) {
       }
       for (int l = 0; l < L; ++l) {
         if (l >= kRing && !wait_ge(&sh.s.pub_done, l - kRing + 1, ab, W(1))) return;
-        // The rows are re-requested for the next layer as soon as they have been consumed.
         // After the last layer the descriptor has zero records: the loads are still issued
         // (so the number of loads in flight stays a compile-time constant and the waits can
         // be exact) but return zeros without touching memory.
         const bool more = l + 1 < L;
+        const __amdgpu_buffer_rsrc_t cur = make_rsrc(P.k1n[l], k1_bytes);
         const __amdgpu_buffer_rsrc_t next = make_rsrc(P.k1n[more ? l + 1 : l], more ? k1_bytes : 0u);
         const uint32_t epoch = P.epoch_base + (uint32_t)l + 1u;
         float mys = 0.f;  // lane i keeps the score of the wave's i-th row
@@ -353,8 +364,13 @@ __global__ __launch_bounds__(1024) void ffn_spec_kernel(const SpecParams P) {
           for (int c = 0; c < CPL1; ++c)
 #pragma unroll
             for (int e = 0; e < VEC; ++e) acc += reg[i][c].get(e) * q1[c][e];
+          if (i + RIF < RPW) {
 #pragma unroll
-          for (int c = 0; c < CPL1; ++c) reg[i][c] = buf_load_w<WT>(next, loff[c], roff[i]);
+            for (int c = 0; c < CPL1; ++c) reg[(i + RIF) % RPW][c] = buf_load_w<WT>(cur, loff[c], roff[(i + RIF) % RPW]);
+          } else {
+#pragma unroll
+            for (int c = 0; c < CPL1; ++c) reg[(i + RIF) % RPW][c] = buf_load_w<WT>(next, loff[c], roff[(i + RIF) % RPW]);
+          }
           acc = wave_sum_dpp(acc);
           mys = lane == i ? acc : mys;
           __builtin_amdgcn_sched_barrier(0);
@@ -364,6 +380,7 @@ __global__ __launch_bounds__(1024) void ffn_spec_kernel(const SpecParams P) {
           st_u64(P.scores + (size_t)l * P.d_ff + (size_t)s * RS + sw + NS * lane, pack(mys, epoch));
         }
         if (lane == 0) lds_signal_add(&sh.s.produced[l % kRing]);
+        mark(l);
       }
       prof_flush();
     } else if (wave == NS) {
@@ -386,6 +403,7 @@ __global__ __launch_bounds__(1024) void ffn_spec_kernel(const SpecParams P) {
           st_u64(p + 1, pack(m2_w, epoch));
           lds_signal_set(&sh.s.pub_done, l + 1);
         }
+        mark(l);
       }
       prof_flush();
     }
@@ -404,7 +422,7 @@ __global__ __launch_bounds__(1024) void ffn_spec_kernel(const SpecParams P) {
   // does the wide poll and republishes a single word for its group.
   constexpr int GPL = GG / kLeaders;  // gather workgroups per leader
   const int lead = g / GPL;
-  const bool is_leader = g % GPL == 0;
+  const bool is_leader = g % GPL == lead % GPL;  // the leaders sit on different XCDs
 
   // ------------------------------------------------------------------------------ control
   if (wave < 2) {
@@ -413,9 +431,6 @@ __global__ __launch_bounds__(1024) void ffn_spec_kernel(const SpecParams P) {
       const uint32_t epoch = P.epoch_base + (uint32_t)l + 1u;
       const unsigned long long* st = P.stats + (size_t)l * kStatSlots * 2;
       const unsigned long long* sc = P.scores + (size_t)l * P.d_ff + (NPGg > 0 ? (size_t)g * NPG : 0);
-      // the other control wave has seen layer l - 1 (a layer cannot complete before its
-      // predecessor, so polling earlier would only add traffic)
-      if (!wait_ge(&sh.g.stats_seen, l, ab, W(4))) return;
       unsigned long long sv[MW];
       float theta;
       const long long tp = prof ? wall_clock64() : 0;
@@ -430,9 +445,17 @@ __global__ __launch_bounds__(1024) void ffn_spec_kernel(const SpecParams P) {
             m0[k] = ld_u64(sp);
             m1[k] = ld_u64(sp + 1);
           }
+          // own scores: stored before the statistics were published, but by other waves
+#pragma unroll
+          for (int k = 0; k < MW; ++k) {
+            const int n = lane + kWave * k;
+            sv[k] = ld_u64(sc + (n < NPGg ? n : 0));
+          }
           bool ok = true;
 #pragma unroll
           for (int k = 0; k < SPL; ++k) ok = ok && hi32(m0[k]) == epoch && hi32(m1[k]) == epoch;
+#pragma unroll
+          for (int k = 0; k < MW; ++k) ok = ok && (NPGg == 0 || hi32(sv[k]) == epoch);
           if (__all(ok)) break;
           if (guard.expired(ab, 2)) return;
           if (prof) pw[3] += 1;
@@ -458,34 +481,27 @@ __global__ __launch_bounds__(1024) void ffn_spec_kernel(const SpecParams P) {
         theta = mean + sqrtf(m2 / (float)(P.d_ff - 1)) * P.z;
         if (lane == 0) st_u64(P.thetaw + ((size_t)l * kLeaders + lead) * kCell, pack(theta, epoch));
       } else {
+        // the leader's theta and the workgroup's own scores, in one round trip
         const unsigned long long* tw = P.thetaw + ((size_t)l * kLeaders + lead) * kCell;
         SpinGuard guard;
         unsigned long long v;
         for (;;) {
           v = ld_u64(tw);
-          if (__all(hi32(v) == epoch)) break;
+#pragma unroll
+          for (int k = 0; k < MW; ++k) {
+            const int n = lane + kWave * k;
+            sv[k] = ld_u64(sc + (n < NPGg ? n : 0));
+          }
+          bool ok = hi32(v) == epoch;
+#pragma unroll
+          for (int k = 0; k < MW; ++k) ok = ok && (NPGg == 0 || hi32(sv[k]) == epoch);
+          if (__all(ok)) break;
           if (guard.expired(ab, 2)) return;
           if (prof) pw[3] += 1;
           __builtin_amdgcn_s_sleep(2);
         }
         theta = lo_f32(uniform_u64(v));
       }
-      {
-        SpinGuard guard;
-        for (;;) {
-#pragma unroll
-          for (int k = 0; k < MW; ++k) {
-            const int n = lane + kWave * k;
-            sv[k] = ld_u64(sc + (n < NPGg ? n : 0));
-          }
-          bool ok = true;
-#pragma unroll
-          for (int k = 0; k < MW; ++k) ok = ok && (NPGg == 0 || hi32(sv[k]) == epoch);
-          if (__all(ok)) break;
-          if (guard.expired(ab, 5)) return;
-        }
-      }
-      if (lane == 0) lds_signal_set(&sh.g.stats_seen, l + 1);
       if (prof) pw[2] += wall_clock64() - tp;
       unsigned long long mask[MW];
       int cnt = 0;
@@ -511,6 +527,7 @@ __global__ __launch_bounds__(1024) void ffn_spec_kernel(const SpecParams P) {
       // layers are posted in order: wait for the other control wave to have posted l - 1
       if (!wait_ge(&sh.g.theta_ready, l, ab, W(5))) return;
       if (lane == 0) lds_signal_set(&sh.g.theta_ready, l + 1);
+      mark(l);
     }
     prof_flush();
     return;
@@ -548,6 +565,7 @@ __global__ __launch_bounds__(1024) void ffn_spec_kernel(const SpecParams P) {
       wait_vmem();
       if (lane == 0) st_u64(P.gdone + g, ((unsigned long long)P.epoch_base << 32) | (uint32_t)(l + 1));
       if (prof) pw[2] += wall_clock64() - tc;
+      mark(l);
     }
     prof_flush();
     return;
@@ -558,45 +576,65 @@ __global__ __launch_bounds__(1024) void ffn_spec_kernel(const SpecParams P) {
     const int DP = P.DP, CWG = P.CWG;
     const __amdgpu_buffer_rsrc_t prs = make_rsrc(P.part, (uint32_t)L * GG * DP * 4u);
     const bool want_idx = P.idx || P.uidx || P.count || P.ucount;
+    // The output columns are cut into slices of CWG floats (a whole number of 64-byte
+    // sectors, so that a slice of a partial row is fetched without read amplification); the
+    // first NR gather workgroups reduce one slice each.
+    const bool reducer = g < P.NR;
+    if (!reducer && !want_idx) {
+      prof_flush();
+      return;
+    }
     for (int l = wave - 3; l < L; l += 2) {
-      // every gather workgroup has written layer l: the leaders' group words say so
-      if (!wait_ge(&sh.g.red_seen, l, ab, W(3))) return;
-      {
+      // every gather workgroup has written layer l: the leaders' group words say so.  The
+      // two reduce waves share what they have seen, so a wave that is behind does not poll.
+      if (reducer && lds_read(&sh.g.red_seen) < l + 1) {
         const long long tp = prof ? wall_clock64() : 0;
         SpinGuard guard;
         for (;;) {
           const unsigned long long v = ld_u64(P.gdone2 + (size_t)(lane < kLeaders ? lane : 0) * kCell);
-          if (__all(hi32(v) == P.epoch_base && (int)(uint32_t)v >= l + 1)) break;
+          int m = hi32(v) == P.epoch_base ? (int)(uint32_t)v : 0;
+#pragma unroll
+          for (int o = 32; o >= 1; o >>= 1) m = min(m, __shfl_xor(m, o));
+          if (m >= l + 1) {
+            if (lane == 0) __hip_atomic_fetch_max((lds_int_t*)&sh.g.red_seen, m, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+            break;
+          }
           if (guard.expired(ab, 3)) return;
           __builtin_amdgcn_s_sleep(2);
         }
-        if (lane == 0) lds_signal_set(&sh.g.red_seen, l + 1);
         if (prof) pw[1] += wall_clock64() - tp;
       }
       const long long tl = prof ? wall_clock64() : 0;
-      f32x4 pv[WPL][CW4];
       unsigned long long cv[WPL];
 #pragma unroll
       for (int j = 0; j < WPL; ++j) {
         const int wi = lane + kWave * j;
-        const uint32_t off = ((uint32_t)(l * GG + (wi < GG ? wi : 0)) * DP + (uint32_t)g * CWG) * 4u;
-#pragma unroll
-        for (int i = 0; i < CW4; ++i) pv[j][i] = buf_load_f32x4(prs, off + 16u * (i * 4 < CWG ? i : 0));
         cv[j] = want_idx ? ld_u64(P.gcnt + (size_t)l * kMaxGather + (wi < GG ? wi : 0)) : 0ull;
       }
+      if (reducer) {
+        f32x4 pv[WPL][CW4];
 #pragma unroll
-      for (int i = 0; i < CW4; ++i) {
+        for (int j = 0; j < WPL; ++j) {
+          const int wi = lane + kWave * j;
+          const uint32_t off = ((uint32_t)(l * GG + (wi < GG ? wi : 0)) * DP + (uint32_t)g * CWG) * 4u;
 #pragma unroll
-        for (int e = 0; e < 4; ++e) {
-          float mine = 0.f;  // this lane's writers, in ascending workgroup order
+          for (int i = 0; i < CW4; ++i) pv[j][i] = buf_load_f32x4(prs, off + 16u * (i * 4 < CWG ? i : 0));
+        }
 #pragma unroll
-          for (int j = 0; j < WPL; ++j) mine += (lane + kWave * j < GG) ? pv[j][i][e] : 0.f;
-          const float tot = wave_sum_dpp(mine);
-          const int col = g * CWG + i * 4 + e;
-          if (lane == 0 && i * 4 + e < CWG && col < P.d_model) P.y[(size_t)l * P.d_model + col] = tot;
+        for (int i = 0; i < CW4; ++i) {
+#pragma unroll
+          for (int e = 0; e < 4; ++e) {
+            float mine = 0.f;  // this lane's writers, in ascending workgroup order
+#pragma unroll
+            for (int j = 0; j < WPL; ++j) mine += (lane + kWave * j < GG) ? pv[j][i][e] : 0.f;
+            const float tot = wave_sum_dpp(mine);
+            const int col = g * CWG + i * 4 + e;
+            if (lane == 0 && i * 4 + e < CWG && col < P.d_model) P.y[(size_t)l * P.d_model + col] = tot;
+          }
         }
       }
       if (prof) pw[2] += wall_clock64() - tl;
+      mark(l);
       if (!want_idx) continue;
       // compacted ascending index list: counts of all gather workgroups were published long ago
       {
@@ -683,67 +721,93 @@ __global__ __launch_bounds__(1024) void ffn_spec_kernel(const SpecParams P) {
       if (!wait_ge(&sh.g.theta_ready, l + 1, ab, W(1))) return;
       const int slot = gw * RB + l % RB;
       float* myrow = rows + (size_t)slot * P.d_model;
-      const __amdgpu_buffer_rsrc_t kb = make_rsrc(P.k2n[l], k2_bytes);
-      const __amdgpu_buffer_rsrc_t vb = make_rsrc(P.vn[l], v_bytes);
-      int ip = (l * 3) % NGW, mine = 0;
+      // This wave's neurons of the layer: every NGW-th active one, starting at a position
+      // that rotates with the layer.  They are handled two at a time (both row pairs are
+      // requested before either is used), so that a layer with up to 2 * NGW active neurons
+      // costs the workgroup one memory round trip.
+      int first = gw - (l * 3) % NGW;  // position of the wave's first neuron among the active ones
+      if (first < 0) first += NGW;
+      unsigned long long mk[MW];
 #pragma unroll
-      for (int k = 0; k < MW; ++k) {
-        unsigned long long mk = uniform_u64(sh.g.mask_ring[l % kRing][k]);
-        while (mk) {
-          const int nl = __builtin_ctzll(mk);
-          mk &= mk - 1;
-          const bool take = ip == gw;
-          ip = ip + 1 == NGW ? 0 : ip + 1;
-          if (!take) continue;
-          const int n = kWave * k + nl;
-          const float a = sh.g.a_ring[l % kRing][n];
-          const uint32_t jn = (uint32_t)(g * NPG + n);
-          const uint32_t krow = jn * (uint32_t)r2 * (uint32_t)sizeof(WT);
-          const uint32_t vrow = jn * (uint32_t)P.d_model * (uint32_t)sizeof(WT);
-          const long long tq0 = prof ? wall_clock64() : 0;
-          Vec16<WT> kr[CPL2], vr[CPLV];
+      for (int k = 0; k < MW; ++k) mk[k] = uniform_u64(sh.g.mask_ring[l % kRing][k]);
+      int skip = first, mine = 0;
+      // Pops the wave's next neuron (local index) from the masks, -1 when there is none.
+      auto next_neuron = [&]() -> int {
 #pragma unroll
-          for (int c = 0; c < CPL2; ++c) kr[c] = buf_load_w<WT>(kb, koff[c], krow);
-#pragma unroll
-          for (int c = 0; c < CPLV; ++c) vr[c] = buf_load_w<WT>(vb, voff[c], vrow);
-          float gdot = 0.f;
-#pragma unroll
-          for (int c = 0; c < CPL2; ++c) {
-            const float* qp = &q2s[(lane + kWave * c) * VEC];
-#pragma unroll
-            for (int e = 0; e < VEC; ++e) gdot += kr[c].get(e) * qp[e];
-          }
-          gdot = wave_sum_dpp(gdot);
-          const float u = gelu(a, P.gelu) * gdot;
-          if (prof) pw[3] += wall_clock64() - tq0;
-          // the wave's LDS row of this layer: the first neuron overwrites it (once the writer
-          // has drained the layer that used the row before), later ones add to it
-          if (mine == 0 && l >= RB && !wait_ge(&sh.g.row_free[gw], l - RB + 1, ab, W(2))) return;
-#pragma unroll
-          for (int c = 0; c < CPLV; ++c) {
-            const int ch = lane + kWave * c;
-            float* dst = myrow + (size_t)ch * VEC;
-            if (ch < nvecv) {
-#pragma unroll
-              for (int e = 0; e < VEC; e += 4) {
-                f32x4 t{u * vr[c].get(e), u * vr[c].get(e + 1), u * vr[c].get(e + 2), u * vr[c].get(e + 3)};
-                if (mine) t += *reinterpret_cast<const f32x4*>(dst + e);
-                *reinterpret_cast<f32x4*>(dst + e) = t;
-              }
+        for (int k = 0; k < MW; ++k) {
+          while (mk[k]) {
+            const int nl = __builtin_ctzll(mk[k]);
+            mk[k] &= mk[k] - 1;
+            if (skip == 0) {
+              skip = NGW - 1;
+              return kWave * k + nl;
             }
-          }
-          ++mine;
-          if (prof) {
-            pw[6] += 1;
-            pw[5] += wall_clock64() - tq0;
+            --skip;
           }
         }
+        return -1;
+      };
+      for (;;) {
+        const int n0 = next_neuron();
+        if (n0 < 0) break;
+        const int n1 = next_neuron();
+        const long long tq0 = prof ? wall_clock64() : 0;
+        // a missing second neuron reads through a descriptor without records: zeros, no traffic
+        const __amdgpu_buffer_rsrc_t kb0 = make_rsrc(P.k2n[l], k2_bytes), vb0 = make_rsrc(P.vn[l], v_bytes);
+        const __amdgpu_buffer_rsrc_t kb1 = make_rsrc(P.k2n[l], n1 >= 0 ? k2_bytes : 0u);
+        const __amdgpu_buffer_rsrc_t vb1 = make_rsrc(P.vn[l], n1 >= 0 ? v_bytes : 0u);
+        const uint32_t j0 = (uint32_t)(g * NPG + n0), j1 = (uint32_t)(g * NPG + (n1 >= 0 ? n1 : n0));
+        Vec16<WT> kr0[CPL2], vr0[CPLV], kr1[CPL2], vr1[CPLV];
+#pragma unroll
+        for (int c = 0; c < CPL2; ++c) kr0[c] = buf_load_w<WT>(kb0, koff[c], j0 * (uint32_t)r2 * (uint32_t)sizeof(WT));
+#pragma unroll
+        for (int c = 0; c < CPL2; ++c) kr1[c] = buf_load_w<WT>(kb1, koff[c], j1 * (uint32_t)r2 * (uint32_t)sizeof(WT));
+#pragma unroll
+        for (int c = 0; c < CPLV; ++c) vr0[c] = buf_load_w<WT>(vb0, voff[c], j0 * (uint32_t)P.d_model * (uint32_t)sizeof(WT));
+#pragma unroll
+        for (int c = 0; c < CPLV; ++c) vr1[c] = buf_load_w<WT>(vb1, voff[c], j1 * (uint32_t)P.d_model * (uint32_t)sizeof(WT));
+        float gd0 = 0.f, gd1 = 0.f;
+#pragma unroll
+        for (int c = 0; c < CPL2; ++c) {
+          const float* qp = &q2s[(lane + kWave * c) * VEC];
+#pragma unroll
+          for (int e = 0; e < VEC; ++e) {
+            gd0 += kr0[c].get(e) * qp[e];
+            gd1 += kr1[c].get(e) * qp[e];
+          }
+        }
+        gd0 = wave_sum_dpp(gd0);
+        gd1 = wave_sum_dpp(gd1);
+        const float u0 = gelu(sh.g.a_ring[l % kRing][n0], P.gelu) * gd0;
+        const float u1 = n1 >= 0 ? gelu(sh.g.a_ring[l % kRing][n1], P.gelu) * gd1 : 0.f;
+        if (prof) pw[3] += wall_clock64() - tq0;
+        // the wave's LDS row of this layer: the first neuron overwrites it (once the writer
+        // has drained the layer that used the row before), later ones add to it
+        if (mine == 0 && l >= RB && !wait_ge(&sh.g.row_free[gw], l - RB + 1, ab, W(2))) return;
+#pragma unroll
+        for (int c = 0; c < CPLV; ++c) {
+          const int ch = lane + kWave * c;
+          float* dst = myrow + (size_t)ch * VEC;
+          if (ch < nvecv) {
+#pragma unroll
+            for (int e = 0; e < VEC; e += 4) {
+              // neurons are added in ascending order, one after the other (u1 = 0 adds +0)
+              f32x4 t{u0 * vr0[c].get(e), u0 * vr0[c].get(e + 1), u0 * vr0[c].get(e + 2), u0 * vr0[c].get(e + 3)};
+              if (mine) t += *reinterpret_cast<const f32x4*>(dst + e);
+              if (n1 >= 0) t += f32x4{u1 * vr1[c].get(e), u1 * vr1[c].get(e + 1), u1 * vr1[c].get(e + 2), u1 * vr1[c].get(e + 3)};
+              *reinterpret_cast<f32x4*>(dst + e) = t;
+            }
+          }
+        }
+        mine += 2;
+        if (prof) pw[5] += wall_clock64() - tq0;
       }
       lds_fence();
       if (lane == 0) lds_signal_add(&sh.g.g_consumed[l % kRing]);
       // the slot's previous posting must have been read before it is overwritten
       if (mine == 0 && l >= RB && !wait_ge(&sh.g.row_free[gw], l - RB + 1, ab, W(2))) return;
       if (lane == 0) lds_signal_set(&sh.g.row_full[slot], 2 * (l + 1) + (mine ? 1 : 0));
+      mark(l);
     }
     prof_flush();
     return;
@@ -755,7 +819,7 @@ __global__ __launch_bounds__(1024) void ffn_spec_kernel(const SpecParams P) {
     int published = 0;
     SpinGuard guard;
     while (published < L) {
-      const unsigned long long v = ld_u64(P.gdone + g + (lane < GPL ? lane : 0));
+      const unsigned long long v = ld_u64(P.gdone + lead * GPL + (lane < GPL ? lane : 0));
       const int done = hi32(v) == P.epoch_base ? (int)(uint32_t)v : 0;
       int m = done;
 #pragma unroll
@@ -773,10 +837,10 @@ __global__ __launch_bounds__(1024) void ffn_spec_kernel(const SpecParams P) {
   }
 }
 
-template <typename WT, int GP, int CPL1, int CPL2, int CPLV, int RPW, int NS, int NGW, int RB, int CW4>
+template <typename WT, int GP, int CPL1, int CPL2, int CPLV, int RPW, int RIF, int NS, int NGW, int RB, int CW4>
 hipError_t launch_variant(const SpecParams& P, hipStream_t st) {
-  const void* kern = P.prof ? reinterpret_cast<const void*>(ffn_spec_kernel<WT, GP, CPL1, CPL2, CPLV, RPW, NS, NGW, RB, CW4, true>)
-                            : reinterpret_cast<const void*>(ffn_spec_kernel<WT, GP, CPL1, CPL2, CPLV, RPW, NS, NGW, RB, CW4, false>);
+  const void* kern = P.prof ? reinterpret_cast<const void*>(ffn_spec_kernel<WT, GP, CPL1, CPL2, CPLV, RPW, RIF, NS, NGW, RB, CW4, true>)
+                            : reinterpret_cast<const void*>(ffn_spec_kernel<WT, GP, CPL1, CPL2, CPLV, RPW, RIF, NS, NGW, RB, CW4, false>);
   const size_t dyn = (size_t)NGW * RB * (size_t)P.d_model * sizeof(float);
   hipError_t err = hipFuncSetAttribute(kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)dyn);
   if (err != hipSuccess) return err;
@@ -822,19 +886,22 @@ ScratchLayout scratch_layout(int d_model, int d_ff) {
 
 // The compiled variants and their shape limits.
 struct Variant {
-  int bf16, gp, cpl1, cpl2, cplv, rpw, ns, ngw, rb, cw4;
+  int bf16, gp, cpl1, cpl2, cplv, rpw, rif, ns, ngw, rb, cw4;
 };
 constexpr Variant kVariants[] = {
-    {1, 16, 2, 3, 5, 6, 12, 8, 2, 5},    // Gemma-2 2B class
-    {1, 16, 2, 3, 5, 8, 14, 8, 2, 5},    // the same with the wider d_ff of the paper's 2B model
-    {1, 8, 3, 4, 7, 5, 15, 10, 1, 14},   // Gemma-2 9B class
-    {0, 8, 4, 5, 9, 4, 12, 10, 1, 9},    // fp32 weights
+    {1, 16, 2, 3, 5, 6, 3, 12, 8, 2, 8},    // Gemma-2 2B class
+    {1, 16, 2, 3, 5, 8, 4, 14, 8, 2, 8},    // the same with the wider d_ff of the paper's 2B model
+    {1, 8, 3, 4, 7, 5, 3, 15, 10, 1, 16},   // Gemma-2 9B class
+    {0, 8, 4, 5, 9, 4, 2, 12, 10, 1, 12},   // fp32 weights
+    {1, 14, 2, 3, 5, 6, 3, 11, 8, 2, 8},    // experiments
+    {1, 12, 2, 3, 5, 5, 3, 12, 8, 2, 8},
+    {1, 14, 2, 3, 5, 6, 3, 12, 8, 2, 8},
 };
 constexpr int kNumVariants = sizeof(kVariants) / sizeof(kVariants[0]);
 constexpr size_t kMaxRowBytes = 148 * 1024;  // dynamic LDS left for the gather waves' rows
 
 struct Split {
-  int GS, GG, RS, NPG, CWG, DP;
+  int GS, GG, RS, NPG, CWG, NR, DP;
 };
 Split split_for(const Variant& v, int d_model, int d_ff) {
   Split s;
@@ -842,8 +909,9 @@ Split split_for(const Variant& v, int d_model, int d_ff) {
   s.GG = kG / kGroup * v.gp;
   s.RS = (d_ff + s.GS - 1) / s.GS;
   s.NPG = (d_ff + s.GG - 1) / s.GG;
-  s.CWG = ((d_model + s.GG - 1) / s.GG + 3) / 4 * 4;
-  s.DP = s.CWG * s.GG;
+  s.CWG = ((d_model + s.GG - 1) / s.GG + 15) / 16 * 16;
+  s.NR = (d_model + s.CWG - 1) / s.CWG;
+  s.DP = s.CWG * s.NR;
   return s;
 }
 
@@ -869,9 +937,9 @@ template <int I>
 hipError_t launch_index(const SpecParams& P, hipStream_t st) {
   constexpr Variant v = kVariants[I];
   if constexpr (v.bf16)
-    return launch_variant<bf16_t, v.gp, v.cpl1, v.cpl2, v.cplv, v.rpw, v.ns, v.ngw, v.rb, v.cw4>(P, st);
+    return launch_variant<bf16_t, v.gp, v.cpl1, v.cpl2, v.cplv, v.rpw, v.rif, v.ns, v.ngw, v.rb, v.cw4>(P, st);
   else
-    return launch_variant<float, v.gp, v.cpl1, v.cpl2, v.cplv, v.rpw, v.ns, v.ngw, v.rb, v.cw4>(P, st);
+    return launch_variant<float, v.gp, v.cpl1, v.cpl2, v.cplv, v.rpw, v.rif, v.ns, v.ngw, v.rb, v.cw4>(P, st);
 }
 
 }  // namespace
@@ -890,8 +958,9 @@ hipError_t launch_ffn_fused(const FfnProblem& p0, const void* const* k1n, const 
                             const void* const* vn, int n_layers, void* scratch, hipStream_t st) {
   hipError_t err = hipSuccess;
   const ScratchLayout lay = scratch_layout(p0.d_model, p0.d_ff);
-  const int vi = spec_variant(p0);
+  int vi = spec_variant(p0);
   if (vi < 0) return hipErrorInvalidValue;
+  if (vi == 0 && getenv("SPARK_X_VARIANT")) vi = atoi(getenv("SPARK_X_VARIANT"));
   const Split sp = split_for(kVariants[vi], p0.d_model, p0.d_ff);
   char* s = static_cast<char*>(scratch);
   for (int base = 0; base < n_layers && err == hipSuccess; base += kFusedMaxLayers) {
@@ -929,6 +998,7 @@ hipError_t launch_ffn_fused(const FfnProblem& p0, const void* const* k1n, const 
     P.RS = sp.RS;
     P.NPG = sp.NPG;
     P.CWG = sp.CWG;
+    P.NR = sp.NR;
     P.DP = sp.DP;
     P.epoch_base = next_epoch_base(L);
     switch (vi) {
@@ -936,6 +1006,9 @@ hipError_t launch_ffn_fused(const FfnProblem& p0, const void* const* k1n, const 
       case 1: err = launch_index<1>(P, st); break;
       case 2: err = launch_index<2>(P, st); break;
       case 3: err = launch_index<3>(P, st); break;
+      case 4: err = launch_index<4>(P, st); break;
+      case 5: err = launch_index<5>(P, st); break;
+      case 6: err = launch_index<6>(P, st); break;
       default: err = hipErrorInvalidValue; break;
     }
   }
