@@ -33,7 +33,6 @@
 // timeout that raises an abort flag.  All reductions have a fixed order: results are
 // reproducible bit for bit.
 #include <atomic>
-#include <cstdlib>
 
 #include "spark_device.h"
 #include "spark_internal.h"
@@ -846,7 +845,13 @@ hipError_t launch_variant(const SpecParams& P, hipStream_t st) {
   if (err != hipSuccess) return err;
   void* args[] = {const_cast<SpecParams*>(&P)};
   constexpr int waves = (NS + 1 > NGW + 6) ? NS + 1 : NGW + 6;
-  return hipLaunchCooperativeKernel(kern, dim3(kG), dim3(waves * kWave), args, dyn, st);
+  // A plain launch: every workgroup needs a compute unit of its own (the LDS request makes
+  // sure of that) and all of them must be resident together, which holds when the device has
+  // kG compute units and no other kernel is running on it.  If it does not hold, the
+  // bounded waits give up and the status word reports it.  (A cooperative launch would only
+  // add the occupancy check that fused_supported() already makes, at several times the
+  // launch latency.)
+  return hipLaunchKernel(kern, dim3(kG), dim3(waves * kWave), args, dyn, st);
 }
 
 uint32_t next_epoch_base(int n_layers) {
@@ -893,9 +898,6 @@ constexpr Variant kVariants[] = {
     {1, 16, 2, 3, 5, 8, 4, 14, 8, 2, 8},    // the same with the wider d_ff of the paper's 2B model
     {1, 8, 3, 4, 7, 5, 3, 15, 10, 1, 16},   // Gemma-2 9B class
     {0, 8, 4, 5, 9, 4, 2, 12, 10, 1, 12},   // fp32 weights
-    {1, 14, 2, 3, 5, 6, 3, 11, 8, 2, 8},    // experiments
-    {1, 12, 2, 3, 5, 5, 3, 12, 8, 2, 8},
-    {1, 14, 2, 3, 5, 6, 3, 12, 8, 2, 8},
 };
 constexpr int kNumVariants = sizeof(kVariants) / sizeof(kVariants[0]);
 constexpr size_t kMaxRowBytes = 148 * 1024;  // dynamic LDS left for the gather waves' rows
@@ -949,8 +951,23 @@ size_t fused_profile_offset(int d_model, int d_ff) { return scratch_layout(d_mod
 size_t fused_profile_bytes() { return kProfBytes; }
 size_t fused_scratch_bytes(int d_model, int d_ff) { return scratch_layout(d_model, d_ff).total; }
 
+// One workgroup per compute unit: the current device must have at least kG of them.
+static bool device_has_room() {
+  static std::atomic<int> cached[64];  // per device: 0 unknown, 1 yes, 2 no
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return false;
+  int c = cached[dev].load();
+  if (c == 0) {
+    int cus = 0;
+    const bool ok = hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && cus >= kG;
+    c = ok ? 1 : 2;
+    cached[dev].store(c);
+  }
+  return c == 1;
+}
+
 bool fused_supported(const FfnProblem& p, int n_layers) {
-  return p.batch == 1 && n_layers >= 1 && spec_variant(p) >= 0;
+  return p.batch == 1 && n_layers >= 1 && spec_variant(p) >= 0 && device_has_room();
 }
 
 // layers: n_layers problems that differ only in weights and outputs' leading index.
@@ -958,9 +975,8 @@ hipError_t launch_ffn_fused(const FfnProblem& p0, const void* const* k1n, const 
                             const void* const* vn, int n_layers, void* scratch, hipStream_t st) {
   hipError_t err = hipSuccess;
   const ScratchLayout lay = scratch_layout(p0.d_model, p0.d_ff);
-  int vi = spec_variant(p0);
+  const int vi = spec_variant(p0);
   if (vi < 0) return hipErrorInvalidValue;
-  if (vi == 0 && getenv("SPARK_X_VARIANT")) vi = atoi(getenv("SPARK_X_VARIANT"));
   const Split sp = split_for(kVariants[vi], p0.d_model, p0.d_ff);
   char* s = static_cast<char*>(scratch);
   for (int base = 0; base < n_layers && err == hipSuccess; base += kFusedMaxLayers) {
@@ -1006,9 +1022,6 @@ hipError_t launch_ffn_fused(const FfnProblem& p0, const void* const* k1n, const 
       case 1: err = launch_index<1>(P, st); break;
       case 2: err = launch_index<2>(P, st); break;
       case 3: err = launch_index<3>(P, st); break;
-      case 4: err = launch_index<4>(P, st); break;
-      case 5: err = launch_index<5>(P, st); break;
-      case 6: err = launch_index<6>(P, st); break;
       default: err = hipErrorInvalidValue; break;
     }
   }
