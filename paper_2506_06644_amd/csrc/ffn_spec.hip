@@ -74,6 +74,7 @@ struct SpecParams {
   int32_t* status;
   long long* prof;
   int n_layers, d_model, d_ff, r, q_bf16, gelu;
+  int xmode;  // TEMP experiment switch
   float z;
   int RS;   // neurons per stream workgroup
   int NPG;  // neurons per gather workgroup
@@ -183,6 +184,13 @@ __device__ __forceinline__ Vec16<WT> buf_load_w(__amdgpu_buffer_rsrc_t r, uint32
   v.raw = __builtin_bit_cast(decltype(v.raw), u);
   return v;
 }
+// a.lo * b.lo + a.hi * b.hi + c on packed bf16 pairs (products of bf16 values are exact in fp32)
+typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ float dot2_bf16(uint32_t a, uint32_t b, float c) {
+  return __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2_t, a), __builtin_bit_cast(bf16x2_t, b), c, false);
+}
+__device__ __forceinline__ uint32_t raw_dword(const Vec16<bf16_t>& v, int d) { return v.raw[d]; }
+__device__ __forceinline__ uint32_t raw_dword(const Vec16<float>& v, int d) { return __float_as_uint(v.raw[d]); }
 __device__ __forceinline__ void wait_vmem() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
 
 // Sum over the wavefront with DPP moves only (no LDS crossbar): quad swaps, row mirrors, then
@@ -238,7 +246,7 @@ struct GatherShared {
 // problem read a valid dummy location of the same array (chunk 0 of the same row, row 0,
 // slot 0) and the value is discarded by a select, so loads carry no per-lane branches and
 // are issued back to back.
-template <typename WT, int GP, int CPL1, int CPL2, int CPLV, int RPW, int RIF, int NS, int NGW, int RB, int CW4, bool PROF>
+template <typename WT, bool QB, int GP, int CPL1, int CPL2, int CPLV, int RPW, int RIF, int NS, int NGW, int RB, int CW4, bool PROF>
 __global__ __launch_bounds__(1024) void ffn_spec_kernel(const SpecParams P) {
   constexpr int VEC = Vec16<WT>::N;
   constexpr int GS = kG / kGroup * (kGroup - GP);  // stream workgroups
@@ -248,7 +256,7 @@ __global__ __launch_bounds__(1024) void ffn_spec_kernel(const SpecParams P) {
   constexpr int MW = mask_words(GP);
   constexpr int FPL = CPLV * VEC / 4;              // float4 columns per lane of an LDS row
   static_assert(NS * RPW <= 128, "a stream workgroup owns at most 128 neurons");
-  static_assert(NS + 1 <= 16 && NGW + 6 <= 16, "at most 16 waves per workgroup");
+  static_assert(NS + 1 <= 16 && NGW + 7 <= 16, "at most 16 waves per workgroup");
   static_assert(GG % kLeaders == 0 && GG / kLeaders <= kWave, "leader groups");
   static_assert(NGW * RB <= 32, "row_full slots");
   __shared__ union {
@@ -307,17 +315,26 @@ __global__ __launch_bounds__(1024) void ffn_spec_kernel(const SpecParams P) {
     if (wave < NS) {
       const int sw = wave;
       const int nvec1 = P.r / VEC;
-      float q1[CPL1][VEC];
+      // q[:r]: as fp32, or (bf16 weights and a bf16 token) as the packed bf16 pairs themselves,
+      // which the two-element dot product instruction consumes directly
+      constexpr bool DOT2 = QB && VEC == 8;
+      float q1[DOT2 ? 1 : CPL1][VEC];
+      u32x4 q1p[DOT2 ? CPL1 : 1];
       uint32_t loff[CPL1];  // byte offset of this lane's chunks inside a row (VGPR)
       uint32_t roff[RPW];   // byte offset of the wave's rows inside a layer's K1n (SGPR)
 #pragma unroll
       for (int c = 0; c < CPL1; ++c) {
         const int ch = lane + kWave * c;
         const uint32_t co = (uint32_t)(ch < nvec1 ? ch : 0) * VEC;
-        load_q_vec<VEC>(P.q, P.q_bf16, (int64_t)co, q1[c]);
-        if (ch >= nvec1) {
+        if constexpr (DOT2) {
+          q1p[c] = *reinterpret_cast<const u32x4*>(static_cast<const uint16_t*>(P.q) + co);
+          if (ch >= nvec1) q1p[c] = u32x4{0u, 0u, 0u, 0u};
+        } else {
+          load_q_vec<VEC>(P.q, P.q_bf16, (int64_t)co, q1[c]);
+          if (ch >= nvec1) {
 #pragma unroll
-          for (int e = 0; e < VEC; ++e) q1[c][e] = 0.f;
+            for (int e = 0; e < VEC; ++e) q1[c][e] = 0.f;
+          }
         }
         loff[c] = co * (uint32_t)sizeof(WT);
       }
@@ -359,10 +376,23 @@ __global__ __launch_bounds__(1024) void ffn_spec_kernel(const SpecParams P) {
 #pragma unroll
         for (int i = 0; i < RPW; ++i) {
           float acc = 0.f;
+          if constexpr (DOT2) {
+            // one accumulator per chunk: independent dependency chains
+            float accc[CPL1];
 #pragma unroll
-          for (int c = 0; c < CPL1; ++c)
+            for (int c = 0; c < CPL1; ++c) {
+              accc[c] = 0.f;
 #pragma unroll
-            for (int e = 0; e < VEC; ++e) acc += reg[i][c].get(e) * q1[c][e];
+              for (int d = 0; d < 4; ++d) accc[c] = dot2_bf16(raw_dword(reg[i][c], d), q1p[c][d], accc[c]);
+            }
+#pragma unroll
+            for (int c = 0; c < CPL1; ++c) acc += accc[c];
+          } else {
+#pragma unroll
+            for (int c = 0; c < CPL1; ++c)
+#pragma unroll
+              for (int e = 0; e < VEC; ++e) acc += reg[i][c].get(e) * q1[c][e];
+          }
           if (i + RIF < RPW) {
 #pragma unroll
             for (int c = 0; c < CPL1; ++c) reg[(i + RIF) % RPW][c] = buf_load_w<WT>(cur, loff[c], roff[(i + RIF) % RPW]);
@@ -374,10 +404,11 @@ __global__ __launch_bounds__(1024) void ffn_spec_kernel(const SpecParams P) {
           mys = lane == i ? acc : mys;
           __builtin_amdgcn_sched_barrier(0);
         }
-        if (lane < RPW && sw + NS * lane < RSw) {
-          sh.s.s_ring[l % kRing][sw + NS * lane] = mys;
-          st_u64(P.scores + (size_t)l * P.d_ff + (size_t)s * RS + sw + NS * lane, pack(mys, epoch));
-        }
+        // Scores go to LDS only.  The publisher wave stores them to memory: a store issued
+        // here would sit between this wave's loads, and since the memory counter retires in
+        // order, every later load would also wait for the store's (slow, device-scope)
+        // acknowledgement.
+        if (lane < RPW && sw + NS * lane < RSw) sh.s.s_ring[l % kRing][sw + NS * lane] = mys;
         if (lane == 0) lds_signal_add(&sh.s.produced[l % kRing]);
         mark(l);
       }
@@ -396,6 +427,9 @@ __global__ __launch_bounds__(1024) void ffn_spec_kernel(const SpecParams P) {
           m2_w = wave_sum_dpp(d0 * d0 + d1 * d1);
         }
         const uint32_t epoch = P.epoch_base + (uint32_t)l + 1u;
+        unsigned long long* srow = P.scores + (size_t)l * P.d_ff + (size_t)s * RS;
+        if (lane < RSw) st_u64(srow + lane, pack(v0, epoch));
+        if (lane + kWave < RSw) st_u64(srow + lane + kWave, pack(v1, epoch));
         if (lane == 0) {
           unsigned long long* p = P.stats + ((size_t)l * kStatSlots + s) * 2;
           st_u64(p, pack(mean_w, epoch));
@@ -410,6 +444,7 @@ __global__ __launch_bounds__(1024) void ffn_spec_kernel(const SpecParams P) {
   }
 
   // ================================================================ GATHER workgroup
+  if (P.xmode == 2) return;  // TEMP: stream only
   const int g = grp * GP + (gi - (kGroup - GP));  // index among gather workgroups
   const int NPG = P.NPG;
   const int NPGg = max(0, min(NPG, P.d_ff - g * NPG));  // neurons owned
@@ -428,58 +463,11 @@ __global__ __launch_bounds__(1024) void ffn_spec_kernel(const SpecParams P) {
     for (int l = wave; l < L; l += 2) {
       if (l >= kRing && !wait_ge(&sh.g.g_consumed[l % kRing], NGW * (l / kRing), ab, W(1))) return;
       const uint32_t epoch = P.epoch_base + (uint32_t)l + 1u;
-      const unsigned long long* st = P.stats + (size_t)l * kStatSlots * 2;
       const unsigned long long* sc = P.scores + (size_t)l * P.d_ff + (NPGg > 0 ? (size_t)g * NPG : 0);
       unsigned long long sv[MW];
       float theta;
       const long long tp = prof ? wall_clock64() : 0;
-      if (is_leader) {
-        unsigned long long m0[SPL], m1[SPL];
-        SpinGuard guard;
-        for (;;) {
-#pragma unroll
-          for (int k = 0; k < SPL; ++k) {
-            const int t = lane + kWave * k;
-            const unsigned long long* sp = st + (size_t)(t < GS ? t : 0) * 2;
-            m0[k] = ld_u64(sp);
-            m1[k] = ld_u64(sp + 1);
-          }
-          // own scores: stored before the statistics were published, but by other waves
-#pragma unroll
-          for (int k = 0; k < MW; ++k) {
-            const int n = lane + kWave * k;
-            sv[k] = ld_u64(sc + (n < NPGg ? n : 0));
-          }
-          bool ok = true;
-#pragma unroll
-          for (int k = 0; k < SPL; ++k) ok = ok && hi32(m0[k]) == epoch && hi32(m1[k]) == epoch;
-#pragma unroll
-          for (int k = 0; k < MW; ++k) ok = ok && (NPGg == 0 || hi32(sv[k]) == epoch);
-          if (__all(ok)) break;
-          if (guard.expired(ab, 2)) return;
-          if (prof) pw[3] += 1;
-        }
-        // merge (Chan et al.): mean = sum n_s mean_s / n, M2 = sum M2_s + n_s (mean_s - mean)^2
-        float s1 = 0.f;
-#pragma unroll
-        for (int k = 0; k < SPL; ++k) {
-          const int t = lane + kWave * k;
-          const int ns = t < GS ? max(0, min(P.RS, P.d_ff - t * P.RS)) : 0;
-          s1 += (float)ns * lo_f32(m0[k]);
-        }
-        const float mean = wave_sum_dpp(s1) / (float)P.d_ff;
-        float m2 = 0.f;
-#pragma unroll
-        for (int k = 0; k < SPL; ++k) {
-          const int t = lane + kWave * k;
-          const int ns = t < GS ? max(0, min(P.RS, P.d_ff - t * P.RS)) : 0;
-          const float d = lo_f32(m0[k]) - mean;
-          m2 += (t < GS ? lo_f32(m1[k]) : 0.f) + (float)ns * d * d;
-        }
-        m2 = wave_sum_dpp(m2);
-        theta = mean + sqrtf(m2 / (float)(P.d_ff - 1)) * P.z;
-        if (lane == 0) st_u64(P.thetaw + ((size_t)l * kLeaders + lead) * kCell, pack(theta, epoch));
-      } else {
+      {
         // the leader's theta and the workgroup's own scores, in one round trip
         const unsigned long long* tw = P.thetaw + ((size_t)l * kLeaders + lead) * kCell;
         SpinGuard guard;
@@ -520,7 +508,6 @@ __global__ __launch_bounds__(1024) void ffn_spec_kernel(const SpecParams P) {
           sh.g.mask_ring[l % kRing][k] = mask[k];
           sh.g.mask_hist[l][k] = mask[k];
         }
-        if (g == 0 && P.theta) P.theta[l] = theta;
       }
       lds_fence();
       // layers are posted in order: wait for the other control wave to have posted l - 1
@@ -812,6 +799,60 @@ __global__ __launch_bounds__(1024) void ffn_spec_kernel(const SpecParams P) {
     return;
   }
 
+  // ------------------------------------------------------------------------------ leader
+  // In a leader workgroup: merges the stream workgroups' statistics of every layer into
+  // theta and publishes it for the group, as fast as the stream delivers (it depends on
+  // nothing downstream, so a workgroup that is behind never holds up its group's theta).
+  if (wave == 6 + NGW && is_leader) {
+    for (int l = 0; l < L; ++l) {
+      const uint32_t epoch = P.epoch_base + (uint32_t)l + 1u;
+      const unsigned long long* st = P.stats + (size_t)l * kStatSlots * 2;
+      unsigned long long m0[SPL], m1[SPL];
+      SpinGuard guard;
+      for (;;) {
+#pragma unroll
+        for (int k = 0; k < SPL; ++k) {
+          const int t = lane + kWave * k;
+          const unsigned long long* sp = st + (size_t)(t < GS ? t : 0) * 2;
+          m0[k] = ld_u64(sp);
+          m1[k] = ld_u64(sp + 1);
+        }
+        bool ok = true;
+#pragma unroll
+        for (int k = 0; k < SPL; ++k) ok = ok && hi32(m0[k]) == epoch && hi32(m1[k]) == epoch;
+        if (__all(ok)) break;
+        if (guard.expired(ab, 2)) return;
+        if (prof) pw[3] += 1;
+      }
+      // merge (Chan et al.): mean = sum n_s mean_s / n, M2 = sum M2_s + n_s (mean_s - mean)^2
+      float s1 = 0.f;
+#pragma unroll
+      for (int k = 0; k < SPL; ++k) {
+        const int t = lane + kWave * k;
+        const int ns = t < GS ? max(0, min(P.RS, P.d_ff - t * P.RS)) : 0;
+        s1 += (float)ns * lo_f32(m0[k]);
+      }
+      const float mean = wave_sum_dpp(s1) / (float)P.d_ff;
+      float m2 = 0.f;
+#pragma unroll
+      for (int k = 0; k < SPL; ++k) {
+        const int t = lane + kWave * k;
+        const int ns = t < GS ? max(0, min(P.RS, P.d_ff - t * P.RS)) : 0;
+        const float d = lo_f32(m0[k]) - mean;
+        m2 += (t < GS ? lo_f32(m1[k]) : 0.f) + (float)ns * d * d;
+      }
+      m2 = wave_sum_dpp(m2);
+      const float theta = mean + sqrtf(m2 / (float)(P.d_ff - 1)) * P.z;
+      if (lane == 0) {
+        st_u64(P.thetaw + ((size_t)l * kLeaders + lead) * kCell, pack(theta, epoch));
+        if (lead == 0 && P.theta) P.theta[l] = theta;
+      }
+      mark(l);
+    }
+    prof_flush();
+    return;
+  }
+
   // ------------------------------------------------------------------------------ collector
   // In a leader workgroup: republishes min(layers written) over the group's writers.
   if (wave == 5 + NGW && is_leader) {
@@ -836,15 +877,15 @@ __global__ __launch_bounds__(1024) void ffn_spec_kernel(const SpecParams P) {
   }
 }
 
-template <typename WT, int GP, int CPL1, int CPL2, int CPLV, int RPW, int RIF, int NS, int NGW, int RB, int CW4>
+template <typename WT, bool QB, int GP, int CPL1, int CPL2, int CPLV, int RPW, int RIF, int NS, int NGW, int RB, int CW4>
 hipError_t launch_variant(const SpecParams& P, hipStream_t st) {
-  const void* kern = P.prof ? reinterpret_cast<const void*>(ffn_spec_kernel<WT, GP, CPL1, CPL2, CPLV, RPW, RIF, NS, NGW, RB, CW4, true>)
-                            : reinterpret_cast<const void*>(ffn_spec_kernel<WT, GP, CPL1, CPL2, CPLV, RPW, RIF, NS, NGW, RB, CW4, false>);
+  const void* kern = P.prof ? reinterpret_cast<const void*>(ffn_spec_kernel<WT, QB, GP, CPL1, CPL2, CPLV, RPW, RIF, NS, NGW, RB, CW4, true>)
+                            : reinterpret_cast<const void*>(ffn_spec_kernel<WT, QB, GP, CPL1, CPL2, CPLV, RPW, RIF, NS, NGW, RB, CW4, false>);
   const size_t dyn = (size_t)NGW * RB * (size_t)P.d_model * sizeof(float);
   hipError_t err = hipFuncSetAttribute(kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)dyn);
   if (err != hipSuccess) return err;
   void* args[] = {const_cast<SpecParams*>(&P)};
-  constexpr int waves = (NS + 1 > NGW + 6) ? NS + 1 : NGW + 6;
+  constexpr int waves = (NS + 1 > NGW + 7) ? NS + 1 : NGW + 7;
   // A plain launch: every workgroup needs a compute unit of its own (the LDS request makes
   // sure of that) and all of them must be resident together, which holds when the device has
   // kG compute units and no other kernel is running on it.  If it does not hold, the
@@ -896,8 +937,8 @@ struct Variant {
 constexpr Variant kVariants[] = {
     {1, 16, 2, 3, 5, 6, 3, 12, 8, 2, 8},    // Gemma-2 2B class
     {1, 16, 2, 3, 5, 8, 4, 14, 8, 2, 8},    // the same with the wider d_ff of the paper's 2B model
-    {1, 8, 3, 4, 7, 5, 3, 15, 10, 1, 16},   // Gemma-2 9B class
-    {0, 8, 4, 5, 9, 4, 2, 12, 10, 1, 12},   // fp32 weights
+    {1, 8, 3, 4, 7, 5, 3, 15, 9, 1, 16},    // Gemma-2 9B class
+    {0, 8, 4, 5, 9, 4, 2, 12, 9, 1, 12},    // fp32 weights
 };
 constexpr int kNumVariants = sizeof(kVariants) / sizeof(kVariants[0]);
 constexpr size_t kMaxRowBytes = 148 * 1024;  // dynamic LDS left for the gather waves' rows
@@ -938,10 +979,12 @@ int spec_variant(const FfnProblem& p) {
 template <int I>
 hipError_t launch_index(const SpecParams& P, hipStream_t st) {
   constexpr Variant v = kVariants[I];
-  if constexpr (v.bf16)
-    return launch_variant<bf16_t, v.gp, v.cpl1, v.cpl2, v.cplv, v.rpw, v.rif, v.ns, v.ngw, v.rb, v.cw4>(P, st);
-  else
-    return launch_variant<float, v.gp, v.cpl1, v.cpl2, v.cplv, v.rpw, v.rif, v.ns, v.ngw, v.rb, v.cw4>(P, st);
+  if constexpr (v.bf16) {
+    if (P.q_bf16) return launch_variant<bf16_t, true, v.gp, v.cpl1, v.cpl2, v.cplv, v.rpw, v.rif, v.ns, v.ngw, v.rb, v.cw4>(P, st);
+    return launch_variant<bf16_t, false, v.gp, v.cpl1, v.cpl2, v.cplv, v.rpw, v.rif, v.ns, v.ngw, v.rb, v.cw4>(P, st);
+  } else {
+    return launch_variant<float, false, v.gp, v.cpl1, v.cpl2, v.cplv, v.rpw, v.rif, v.ns, v.ngw, v.rb, v.cw4>(P, st);
+  }
 }
 
 }  // namespace
@@ -1003,7 +1046,8 @@ hipError_t launch_ffn_fused(const FfnProblem& p0, const void* const* k1n, const 
     P.thetaw = reinterpret_cast<unsigned long long*>(s + lay.thetaw);
     P.gdone2 = reinterpret_cast<unsigned long long*>(s + lay.gdone2);
     P.part = reinterpret_cast<float*>(s + lay.part);
-    P.prof = g_fused_profile ? reinterpret_cast<long long*>(s + lay.prof) : nullptr;
+    P.prof = g_fused_profile == 1 ? reinterpret_cast<long long*>(s + lay.prof) : nullptr;
+    P.xmode = g_fused_profile >= 2 ? g_fused_profile : 0;
     P.n_layers = L;
     P.d_model = p0.d_model;
     P.d_ff = p0.d_ff;
