@@ -187,7 +187,7 @@ def spark_debug_force_general(on: bool):
 
 
 def spark_debug_profile(on: bool):
-    load_library().spark_debug_profile(int(on))
+    load_library().spark_debug_profile(1 if on else 0)
 
 
 def spark_debug_read_profile(workspace: torch.Tensor, d_model: int, d_ff: int, batch: int):

@@ -251,7 +251,7 @@ spark_status spark_ffn_check(const void* workspace, int32_t d_model, int32_t d_f
 
 void spark_debug_force_general(int on) { g_force_general = on != 0; }
 
-void spark_debug_profile(int on) { spark::fused_set_profile(on); }
+void spark_debug_profile(int on) { spark::fused_set_profile(on != 0); }
 
 spark_status spark_debug_read_profile(const void* workspace, int32_t d_model, int32_t d_ff, int32_t batch,
                                       int64_t* out, int64_t n_words, void* hip_stream) {

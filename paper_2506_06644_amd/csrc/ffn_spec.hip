@@ -47,6 +47,7 @@ constexpr int kMaxGather = 128;    // most gather workgroups any variant uses
 constexpr int kLeaders = 8;        // gather workgroups that fan synchronisation words in and out
 constexpr int kCell = 64;          // 64-bit words between two leaders' words (separate 512-byte cells)
 constexpr int kRing = 4;           // LDS ring depth (layers)
+constexpr int kTeams = 2;          // layers a gather workgroup keeps in flight
 constexpr int kStatSlots = 256;    // statistics slots reserved per layer
 // 64-bit mask words of a gather workgroup's neurons (GP = gather workgroups per group of 32)
 constexpr int mask_words(int gp) { return gp >= 12 ? 2 : 4; }
@@ -74,7 +75,6 @@ struct SpecParams {
   int32_t* status;
   long long* prof;
   int n_layers, d_model, d_ff, r, q_bf16, gelu;
-  int xmode;  // TEMP experiment switch
   float z;
   int RS;   // neurons per stream workgroup
   int NPG;  // neurons per gather workgroup
@@ -231,7 +231,7 @@ struct GatherShared {
   unsigned long long mask_hist[kFusedMaxLayers][MW];
   int theta_ready;       // layers whose theta / mask / a are posted (in layer order)
   int red_seen;          // layers a reduce wave has seen written by every gather workgroup
-  int g_consumed[kRing]; // gather-wave reads of a ring slot (layer l consumed at NGW * (l / kRing + 1))
+  int g_consumed[kRing]; // gather-wave reads of a ring slot (layer l consumed at TW * (l / kRing + 1), TW = waves of a team)
   int row_full[32];      // per (gather wave, row slot): 2 * (layer posted + 1) + (the row holds data)
   int row_free[16];      // per gather wave: layers the writer has drained
   int q2_ready;          // the shared copy of q[r:] is in LDS
@@ -255,6 +255,10 @@ __global__ __launch_bounds__(1024) void ffn_spec_kernel(const SpecParams P) {
   constexpr int WPL = (GG + kWave - 1) / kWave;    // writers per lane of a reduce wave
   constexpr int MW = mask_words(GP);
   constexpr int FPL = CPLV * VEC / 4;              // float4 columns per lane of an LDS row
+  // The gather waves work in kTeams teams: team t handles the layers l = t (mod kTeams), so a
+  // workgroup has kTeams layers' row gathers in flight (the gathers are bound by latency).
+  constexpr int TW = NGW / kTeams;                 // waves per team
+  static_assert(NGW % kTeams == 0 && kRing % kTeams == 0, "teams");
   static_assert(NS * RPW <= 128, "a stream workgroup owns at most 128 neurons");
   static_assert(NS + 1 <= 16 && NGW + 7 <= 16, "at most 16 waves per workgroup");
   static_assert(GG % kLeaders == 0 && GG / kLeaders <= kWave, "leader groups");
@@ -371,7 +375,6 @@ __global__ __launch_bounds__(1024) void ffn_spec_kernel(const SpecParams P) {
         const bool more = l + 1 < L;
         const __amdgpu_buffer_rsrc_t cur = make_rsrc(P.k1n[l], k1_bytes);
         const __amdgpu_buffer_rsrc_t next = make_rsrc(P.k1n[more ? l + 1 : l], more ? k1_bytes : 0u);
-        const uint32_t epoch = P.epoch_base + (uint32_t)l + 1u;
         float mys = 0.f;  // lane i keeps the score of the wave's i-th row
 #pragma unroll
         for (int i = 0; i < RPW; ++i) {
@@ -444,7 +447,6 @@ __global__ __launch_bounds__(1024) void ffn_spec_kernel(const SpecParams P) {
   }
 
   // ================================================================ GATHER workgroup
-  if (P.xmode == 2) return;  // TEMP: stream only
   const int g = grp * GP + (gi - (kGroup - GP));  // index among gather workgroups
   const int NPG = P.NPG;
   const int NPGg = max(0, min(NPG, P.d_ff - g * NPG));  // neurons owned
@@ -461,7 +463,7 @@ __global__ __launch_bounds__(1024) void ffn_spec_kernel(const SpecParams P) {
   // ------------------------------------------------------------------------------ control
   if (wave < 2) {
     for (int l = wave; l < L; l += 2) {
-      if (l >= kRing && !wait_ge(&sh.g.g_consumed[l % kRing], NGW * (l / kRing), ab, W(1))) return;
+      if (l >= kRing && !wait_ge(&sh.g.g_consumed[l % kRing], TW * (l / kRing), ab, W(1))) return;
       const uint32_t epoch = P.epoch_base + (uint32_t)l + 1u;
       const unsigned long long* sc = P.scores + (size_t)l * P.d_ff + (NPGg > 0 ? (size_t)g * NPG : 0);
       unsigned long long sv[MW];
@@ -527,9 +529,11 @@ __global__ __launch_bounds__(1024) void ffn_spec_kernel(const SpecParams P) {
       f32x4 acc[FPL];
 #pragma unroll
       for (int k = 0; k < FPL; ++k) acc[k] = f32x4{0.f, 0.f, 0.f, 0.f};
-      for (int i = 0; i < NGW; ++i) {
-        const int slot = i * RB + l % RB;
-        if (!wait_ge(&sh.g.row_full[slot], 2 * (l + 1), ab, W(1))) return;
+      const int o = l / kTeams;  // ordinal of the layer within its team
+      for (int ti = 0; ti < TW; ++ti) {
+        const int i = l % kTeams + kTeams * ti;
+        const int slot = i * RB + o % RB;
+        if (!wait_ge(&sh.g.row_full[slot], 2 * (o + 1), ab, W(1))) return;
         if (lds_read(&sh.g.row_full[slot]) & 1) {
           const float* row = rows + (size_t)slot * P.d_model;
 #pragma unroll
@@ -539,7 +543,7 @@ __global__ __launch_bounds__(1024) void ffn_spec_kernel(const SpecParams P) {
           }
         }
         lds_fence();
-        if (lane == 0) lds_signal_set(&sh.g.row_free[i], l + 1);
+        if (lane == 0) lds_signal_set(&sh.g.row_free[i], o + 1);
       }
       const long long tc = prof ? wall_clock64() : 0;
       const uint32_t row_off = (uint32_t)(l * GG + g) * DP * 4u;
@@ -703,16 +707,18 @@ __global__ __launch_bounds__(1024) void ffn_spec_kernel(const SpecParams P) {
     const uint32_t k2_bytes = (uint32_t)P.d_ff * (uint32_t)r2 * (uint32_t)sizeof(WT);
     const uint32_t v_bytes = (uint32_t)P.d_ff * (uint32_t)P.d_model * (uint32_t)sizeof(WT);
 
-    for (int l = 0; l < L; ++l) {
+    const int team = gw % kTeams, gt = gw / kTeams;  // team, and index within the team
+    for (int l = team; l < L; l += kTeams) {
       if (!wait_ge(&sh.g.theta_ready, l + 1, ab, W(1))) return;
-      const int slot = gw * RB + l % RB;
+      const int o = l / kTeams;  // ordinal of the layer within the team
+      const int slot = gw * RB + o % RB;
       float* myrow = rows + (size_t)slot * P.d_model;
-      // This wave's neurons of the layer: every NGW-th active one, starting at a position
+      // This wave's neurons of the layer: every TW-th active one, starting at a position
       // that rotates with the layer.  They are handled two at a time (both row pairs are
-      // requested before either is used), so that a layer with up to 2 * NGW active neurons
+      // requested before either is used), so that a layer with up to 2 * TW active neurons
       // costs the workgroup one memory round trip.
-      int first = gw - (l * 3) % NGW;  // position of the wave's first neuron among the active ones
-      if (first < 0) first += NGW;
+      int first = gt - (o * 3) % TW;  // position of the wave's first neuron among the active ones
+      if (first < 0) first += TW;
       unsigned long long mk[MW];
 #pragma unroll
       for (int k = 0; k < MW; ++k) mk[k] = uniform_u64(sh.g.mask_ring[l % kRing][k]);
@@ -725,7 +731,7 @@ __global__ __launch_bounds__(1024) void ffn_spec_kernel(const SpecParams P) {
             const int nl = __builtin_ctzll(mk[k]);
             mk[k] &= mk[k] - 1;
             if (skip == 0) {
-              skip = NGW - 1;
+              skip = TW - 1;
               return kWave * k + nl;
             }
             --skip;
@@ -769,7 +775,7 @@ __global__ __launch_bounds__(1024) void ffn_spec_kernel(const SpecParams P) {
         if (prof) pw[3] += wall_clock64() - tq0;
         // the wave's LDS row of this layer: the first neuron overwrites it (once the writer
         // has drained the layer that used the row before), later ones add to it
-        if (mine == 0 && l >= RB && !wait_ge(&sh.g.row_free[gw], l - RB + 1, ab, W(2))) return;
+        if (mine == 0 && o >= RB && !wait_ge(&sh.g.row_free[gw], o - RB + 1, ab, W(2))) return;
 #pragma unroll
         for (int c = 0; c < CPLV; ++c) {
           const int ch = lane + kWave * c;
@@ -791,8 +797,8 @@ __global__ __launch_bounds__(1024) void ffn_spec_kernel(const SpecParams P) {
       lds_fence();
       if (lane == 0) lds_signal_add(&sh.g.g_consumed[l % kRing]);
       // the slot's previous posting must have been read before it is overwritten
-      if (mine == 0 && l >= RB && !wait_ge(&sh.g.row_free[gw], l - RB + 1, ab, W(2))) return;
-      if (lane == 0) lds_signal_set(&sh.g.row_full[slot], 2 * (l + 1) + (mine ? 1 : 0));
+      if (mine == 0 && o >= RB && !wait_ge(&sh.g.row_free[gw], o - RB + 1, ab, W(2))) return;
+      if (lane == 0) lds_signal_set(&sh.g.row_full[slot], 2 * (o + 1) + (mine ? 1 : 0));
       mark(l);
     }
     prof_flush();
@@ -937,8 +943,8 @@ struct Variant {
 constexpr Variant kVariants[] = {
     {1, 16, 2, 3, 5, 6, 3, 12, 8, 2, 8},    // Gemma-2 2B class
     {1, 16, 2, 3, 5, 8, 4, 14, 8, 2, 8},    // the same with the wider d_ff of the paper's 2B model
-    {1, 8, 3, 4, 7, 5, 3, 15, 9, 1, 16},    // Gemma-2 9B class
-    {0, 8, 4, 5, 9, 4, 2, 12, 9, 1, 12},    // fp32 weights
+    {1, 8, 3, 4, 7, 5, 3, 15, 8, 1, 16},    // Gemma-2 9B class
+    {0, 8, 4, 5, 9, 4, 2, 12, 8, 1, 12},    // fp32 weights
 };
 constexpr int kNumVariants = sizeof(kVariants) / sizeof(kVariants[0]);
 constexpr size_t kMaxRowBytes = 148 * 1024;  // dynamic LDS left for the gather waves' rows
@@ -1046,8 +1052,7 @@ hipError_t launch_ffn_fused(const FfnProblem& p0, const void* const* k1n, const 
     P.thetaw = reinterpret_cast<unsigned long long*>(s + lay.thetaw);
     P.gdone2 = reinterpret_cast<unsigned long long*>(s + lay.gdone2);
     P.part = reinterpret_cast<float*>(s + lay.part);
-    P.prof = g_fused_profile == 1 ? reinterpret_cast<long long*>(s + lay.prof) : nullptr;
-    P.xmode = g_fused_profile >= 2 ? g_fused_profile : 0;
+    P.prof = g_fused_profile ? reinterpret_cast<long long*>(s + lay.prof) : nullptr;
     P.n_layers = L;
     P.d_model = p0.d_model;
     P.d_ff = p0.d_ff;
