@@ -25,6 +25,10 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0
+# HBM bytes per launch of the persistent kernel from two rocprofv3 --pmc runs (FETCH_SIZE, then
+# WRITE_SIZE, each scaled by what the counter reads for a plain 1 GiB device copy: x2.000 and
+# x1.000); workload key = (shape, layers, batch).  Other workloads report null.
+MEASURED_TRAFFIC_BYTES = {("gemma2-2b", 26, 1): 662.9e6 + 33.3e6}
 
 
 def algorithmic_bytes(shape, counts, wbytes):
@@ -84,6 +88,46 @@ def cpu_baseline(shape, weights_cpu, q_cpu, budget_s=12.0):
             "sample": f"{n} evaluations of layer 0 of the same stack (batch 1), {dt:.1f} s"}
 
 
+def stat_topk_bench(torch, binding, synth, dev, with_cpu):
+    """Row-wise statistical top-k on the 8192 x 9216 activation matrix (k = 737), bf16 and fp32:
+    one read and one write of the tensor are the algorithmic bytes."""
+    rows, n, k = 8192, 9216, 737
+    out = {"workload": f"rows={rows} n={n} k={k}, rows N(mu_i, sigma_i^2) with 1% Student-t3 outliers"}
+    for name, dt, w in (("bf16", torch.bfloat16, 2), ("f32", torch.float32, 4)):
+        x = synth.topk_rows(rows, n, seed=4242, dtype=dt, device=dev)
+        y = torch.empty_like(x)
+        theta = torch.empty(rows, device=dev)
+        count = torch.empty(rows, dtype=torch.int32, device=dev)
+
+        def step():
+            binding.spark_stat_topk(x, k, y=y, theta=theta, count=count)
+
+        gpu_s, _ = time_region(step, 50, 5, torch)
+        avg_s, _ = sampled_launch_time(step, 20, torch)
+        nbytes = 2.0 * rows * n * w + 8.0 * rows
+        out[name] = {"rows_per_s": rows * 50 / gpu_s, "us_per_call": gpu_s / 50 * 1e6,
+                     "roofline": {"bound": "hbm", "achieved": nbytes / avg_s / 1e9, "peak": HBM_PEAK_GBS,
+                                  "unit": "GB/s", "frac": nbytes / avg_s / 1e9 / HBM_PEAK_GBS, "traffic": None,
+                                  "kernel": "stat_topk_cached_kernel", "bytes_per_launch": nbytes,
+                                  "launch_us": avg_s * 1e6},
+                     "count_mean": float(count.float().mean()), "count_min": int(count.min()),
+                     "count_max": int(count.max())}
+        if with_cpu and name == "f32":
+            import oracle
+            sample = 512
+            xs = synth.to_oracle(x[:sample])
+            t0 = time.perf_counter()
+            reps = 0
+            while time.perf_counter() - t0 < 4.0:
+                oracle.stat_topk_rows(xs, k)
+                reps += 1
+            dt_s = time.perf_counter() - t0
+            out["cpu_baseline"] = {"value": sample * reps / dt_s, "unit": "rows/s", "cores": oracle.max_threads(),
+                                   "kind": "oracle", "sample": f"{reps} passes over the first {sample} rows (fp32), {dt_s:.1f} s"}
+        del x, y
+    return out
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -94,6 +138,10 @@ def main():
     ap.add_argument("--batch", type=int, default=1)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-dense", action="store_true")
+    ap.add_argument("--no-stat-topk", action="store_true")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run three plain 1 GiB device copies (the known-size reference for the "
+                         "FETCH_SIZE / WRITE_SIZE counters)")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on one GPU only (no collectives, no sharding); use --gpus 1")
@@ -140,7 +188,8 @@ def main():
     bytes_step = float(sum(algorithmic_bytes(shape, [int(m) for m in fetch_rows], 2)))
     achieved = bytes_step / launch_avg_s / 1e9
     roofline = {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                "frac": achieved / HBM_PEAK_GBS, "traffic": None,
+                "frac": achieved / HBM_PEAK_GBS,
+                "traffic": MEASURED_TRAFFIC_BYTES.get((args.shape, L, B)),
                 "kernel": ("ffn_spec_kernel: one persistent launch per spark_ffn_decode_layers call (%d layers)" % L)
                 if B == 1 else "whole spark_ffn_decode_layers call (several kernels per layer)",
                 "bytes_per_launch": bytes_step, "launch_us": launch_avg_s * 1e6,
@@ -182,6 +231,18 @@ def main():
                         "speedup_sparse_over_dense": (layers_per_s) / (L * dsteps / d_s)}
         err = (yd - y).norm() / y.norm()
         out["dense"]["rel_l2_vs_sparse"] = float(err)
+
+    if args.calibrate_copy:
+        src = torch.full((1 << 30,), 7, dtype=torch.uint8, device=dev)
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        out["calibration_copy_bytes"] = 1 << 30
+        del src, dst
+
+    if not args.no_stat_topk:
+        out["stat_topk"] = stat_topk_bench(torch, binding, synth, dev, not args.no_cpu_baseline)
 
     if not args.no_cpu_baseline:
         wcpu = tuple(synth.to_oracle(t) for t in weights[0])
