@@ -58,7 +58,8 @@ __global__ __launch_bounds__(THREADS) void stat_topk_cached_kernel(
     const int vi = i * THREADS + tid;
     nv[i] = vi < nfull ? VEC : (vi == nfull ? tail : 0);
     if (vi < nfull) {
-      v[i] = load_vec16<T>(xr + (int64_t)vi * VEC);
+      // the tensor is streamed once: keep it from displacing anything in the caches
+      v[i].raw = __builtin_nontemporal_load(reinterpret_cast<const decltype(v[i].raw)*>(xr + (int64_t)vi * VEC));
     } else {
       v[i].raw = (decltype(v[i].raw))(0);
       if (vi == nfull) {
@@ -115,7 +116,7 @@ __global__ __launch_bounds__(THREADS) void stat_topk_cached_kernel(
 #pragma unroll
       for (int e = 0; e < VEC; ++e) o.set(e, ((act[i] >> e) & 1u) ? v[i].get(e) - theta : fillv);
       if (nv[i] == VEC) {
-        store_vec16<T>(yr + (int64_t)vi * VEC, o);
+        __builtin_nontemporal_store(o.raw, reinterpret_cast<decltype(o.raw)*>(yr + (int64_t)vi * VEC));
       } else {
 #pragma unroll
         for (int e = 0; e < VEC; ++e)
