@@ -943,7 +943,7 @@ struct Variant {
 constexpr Variant kVariants[] = {
     {1, 16, 2, 3, 5, 6, 3, 12, 8, 2, 8},    // Gemma-2 2B class
     {1, 16, 2, 3, 5, 8, 4, 14, 8, 2, 8},    // the same with the wider d_ff of the paper's 2B model
-    {1, 8, 3, 4, 7, 5, 3, 15, 8, 1, 16},    // Gemma-2 9B class
+    {1, 16, 3, 4, 7, 8, 3, 14, 8, 1, 8},    // Gemma-2 9B class
     {0, 8, 4, 5, 9, 4, 2, 12, 8, 1, 12},    // fp32 weights
 };
 constexpr int kNumVariants = sizeof(kVariants) / sizeof(kVariants[0]);
