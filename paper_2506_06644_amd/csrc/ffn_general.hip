@@ -62,35 +62,40 @@ __global__ __launch_bounds__(1024) void union_kernel(const int32_t* __restrict__
                                                      int32_t* __restrict__ ucount,
                                                      int32_t* __restrict__ user_idx,
                                                      int32_t* __restrict__ user_count) {
+  // One workgroup; thread t owns the consecutive entries [t * per, (t + 1) * per): counts,
+  // one workgroup-wide exclusive scan of the counts, then ordered writes.
   constexpr int NW = 1024 / kWave;
   __shared__ int tab[NW];
-  __shared__ int running;
   const int tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid / kWave;
-  if (tid == 0) running = 0;
+  const int per = (d_ff + 1023) / 1024;
+  const int lo = min(d_ff, tid * per), hi = min(d_ff, lo + per);
+  int cnt = 0;
+  for (int i = lo; i < hi; ++i) cnt += flags[i] != 0;
+  int incl = cnt;
+#pragma unroll
+  for (int o = 1; o < kWave; o <<= 1) {
+    const int t = __shfl_up(incl, o, kWave);
+    if (lane >= o) incl += t;
+  }
+  if (lane == kWave - 1) tab[wave] = incl;
   __syncthreads();
-  for (int base = 0; base < d_ff; base += 1024) {
-    const int i = base + tid;
-    const bool a = i < d_ff && flags[i] != 0;
-    const uint64_t b = __ballot(a);
-    if (lane == 0) tab[wave] = __popcll(b);
-    __syncthreads();
-    int pos = running + lanes_below(b);
-    for (int w = 0; w < wave; ++w) pos += tab[w];
-    if (a) {
+  int base = 0, total = 0;
+  for (int w = 0; w < NW; ++w) {
+    const int t = tab[w];
+    if (w < wave) base += t;
+    total += t;
+  }
+  int pos = base + incl - cnt;
+  for (int i = lo; i < hi; ++i) {
+    if (flags[i] != 0) {
       uidx[pos] = i;
       if (user_idx) user_idx[pos] = i;
+      ++pos;
     }
-    __syncthreads();
-    if (tid == 0) {
-      int t = running;
-      for (int w = 0; w < NW; ++w) t += tab[w];
-      running = t;
-    }
-    __syncthreads();
   }
   if (tid == 0) {
-    ucount[0] = running;
-    if (user_count) user_count[0] = running;
+    ucount[0] = total;
+    if (user_count) user_count[0] = total;
   }
 }
 
@@ -230,6 +235,235 @@ __global__ __launch_bounds__(kBlock) void reduce_kernel(const float* __restrict_
   y[i] = s;
 }
 
+// ------------------------------------------------------------------- batched path on MFMA
+// For batches of 2..64 tokens with bf16 weights and bf16 tokens the two row-times-token
+// products are small GEMMs (Appendix B: the prefill / chunk case):
+//   rows x tokens:   G[j][b] = W[j][:] . q_b[off : off + K]   for 16 rows j and all tokens
+// v_mfma_f32_16x16x32_bf16 takes, per lane, 8 consecutive k of one row (A) and 8 consecutive
+// k of one token (B): both are plain 16-byte loads of the neuron-major / token-major arrays.
+// bf16 x bf16 products are exact in fp32 and the accumulation is fp32, as in the batch-1 path.
+typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+
+// One workgroup (8 waves) = one tile of 16 rows; the waves take every 8th step of 32 k (so that
+// for r around 1024 a wave issues all its loads at once) and their partial tiles are summed
+// through LDS in wave order.  MODE 0: rows are neurons
+// 16 * tile + i and the result goes to S[b][j].  MODE 1: rows are union entries
+// uidx[16 * tile + i] and the result becomes uact[m][b] = GELU(A[b][j]) * g (0 if A[b][j] <= 0).
+constexpr int kRowsWaves = 8;
+template <int NB, int MODE>
+__global__ __launch_bounds__(kRowsWaves * kWave) void rows_mfma_kernel(const bf16_t* __restrict__ w, int n_rows, int K,
+                                                        const bf16_t* __restrict__ q, int64_t ldq, int qoff,
+                                                        int B, int d_ff, const int32_t* __restrict__ uidx,
+                                                        const int32_t* __restrict__ ucount,
+                                                        const float* __restrict__ A, float* __restrict__ out,
+                                                        int gelu_kind, int dense, int32_t* __restrict__ flags,
+                                                        int32_t* __restrict__ status) {
+  __shared__ float red[kRowsWaves - 1][NB * 4][kWave];
+  const int tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid / kWave;
+  const int tile = blockIdx.x;
+  if (MODE == 0) {
+    for (int i = blockIdx.x * blockDim.x + tid; i < d_ff; i += gridDim.x * blockDim.x) flags[i] = 0;
+    if (blockIdx.x == 0 && tid == 0) status[0] = 0;  // this path cannot abort
+  }
+  const int m_total = MODE == 0 ? n_rows : ucount[0];
+  if (tile * 16 >= m_total) return;
+  const int ri = lane & 15, kg = lane >> 4;  // row (or token) within the tile, group of 8 k
+  const int m = tile * 16 + ri;
+  const int mc = m < m_total ? m : m_total - 1;
+  const int j = MODE == 0 ? mc : uidx[mc];
+  const bf16_t* wrow = w + (int64_t)j * K;
+  const bf16_t* qrow[NB];
+#pragma unroll
+  for (int nb = 0; nb < NB; ++nb) {
+    const int b = nb * 16 + ri;
+    qrow[nb] = q + (int64_t)(b < B ? b : B - 1) * ldq + qoff;
+  }
+  const int nchunk = K / 8;               // 16-byte chunks per row
+  const int nsteps = (nchunk + 3) / 4;    // steps of 32 k
+  f32x4 acc[NB];
+#pragma unroll
+  for (int nb = 0; nb < NB; ++nb) acc[nb] = f32x4{0.f, 0.f, 0.f, 0.f};
+  for (int s0 = wave; s0 < nsteps; s0 += 4 * kRowsWaves) {
+    u32x4 a[4], bq[4][NB];
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      const int ch = (s0 + kRowsWaves * u) * 4 + kg;
+      const bool ok = s0 + kRowsWaves * u < nsteps && ch < nchunk;
+      const int chc = ok ? ch : 0;
+      a[u] = *reinterpret_cast<const u32x4*>(wrow + (int64_t)chc * 8);
+      if (!ok) a[u] = u32x4{0u, 0u, 0u, 0u};
+#pragma unroll
+      for (int nb = 0; nb < NB; ++nb) bq[u][nb] = *reinterpret_cast<const u32x4*>(qrow[nb] + (int64_t)chc * 8);
+    }
+#pragma unroll
+    for (int u = 0; u < 4; ++u)
+#pragma unroll
+      for (int nb = 0; nb < NB; ++nb)
+        acc[nb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, a[u]),
+                                                          __builtin_bit_cast(bf16x8_t, bq[u][nb]), acc[nb], 0, 0, 0);
+  }
+  // sum the waves' tiles in wave order
+  if (wave > 0) {
+#pragma unroll
+    for (int nb = 0; nb < NB; ++nb)
+#pragma unroll
+      for (int e = 0; e < 4; ++e) red[wave - 1][nb * 4 + e][lane] = acc[nb][e];
+  }
+  __syncthreads();
+  if (wave != 0) return;
+#pragma unroll
+  for (int nb = 0; nb < NB; ++nb)
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+#pragma unroll
+      for (int wv = 0; wv < kRowsWaves - 1; ++wv) acc[nb][e] += red[wv][nb * 4 + e][lane];
+    }
+  // lane holds D[row 4 * kg + e][token ri] of every token block
+#pragma unroll
+  for (int nb = 0; nb < NB; ++nb) {
+    const int b = nb * 16 + ri;
+    if (b >= B) continue;
+    if (MODE == 0 && (d_ff & 3) == 0 && tile * 16 + 4 * kg + 3 < m_total) {
+      *reinterpret_cast<f32x4*>(out + (int64_t)b * d_ff + tile * 16 + 4 * kg) = acc[nb];
+      continue;
+    }
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      const int mm = tile * 16 + 4 * kg + e;
+      if (mm >= m_total) continue;
+      if (MODE == 0) {
+        out[(int64_t)b * d_ff + mm] = acc[nb][e];
+      } else {
+        const int jj = uidx[mm];
+        const float av = A[(int64_t)b * d_ff + jj];
+        out[(int64_t)mm * B + b] = av > 0.f ? gelu(av, gelu_kind) * acc[nb][e] : 0.f;
+      }
+    }
+  }
+}
+
+// y partials: part[ks][b][c] = sum over the union rows m of slice ks of uact[m][b] * Vn[U[m]][c].
+// The contraction runs over rows while Vn is contiguous along columns, so the bf16 MFMA
+// (which wants 8 consecutive k per lane) would need a transpose; v_mfma_f32_32x32x2_f32 takes a
+// single k per lane instead: lanes 0..31 hold one row and lanes 32..63 the next, each lane
+// two columns (one 4-byte load, 128 bytes per row and wave), widened to fp32.  A = uact
+// (32 tokens x 2 rows), D = 32 tokens x 32 columns, two column phases, NH token halves.
+// The loop is software-pipelined by hand: row indices are fetched two steps ahead and the
+// rows themselves one step ahead of the MFMAs that consume them.
+template <int NH>
+__global__ __launch_bounds__(256) void v_mfma_kernel(const bf16_t* __restrict__ vn, int d_model, int B,
+                                                     const float* __restrict__ uact,
+                                                     const int32_t* __restrict__ uidx,
+                                                     const int32_t* __restrict__ ucount,
+                                                     float* __restrict__ part) {
+  extern __shared__ float vred[];  // [NH * 32][kWave]
+  constexpr int UNR = 8;
+  const int tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid / kWave;
+  const int half = lane >> 5, cl = lane & 31;
+  const int c0 = blockIdx.x * 64 + cl * 2;
+  const bool col_ok = c0 < d_model;
+  const int cc = col_ok ? c0 : 0;
+  const int m_total = ucount[0];
+  const int ksplit = gridDim.y;
+  const int per = ((m_total + ksplit - 1) / ksplit + 1) / 2 * 2;  // even: rows are taken in pairs
+  const int m_lo = blockIdx.y * per;
+  const int m_hi = min(m_total, m_lo + per);
+  const int m_safe = m_total > 0 ? min(m_lo, m_total - 1) : 0;  // a valid row for clamped reads
+
+  f32x16 acc[NH][2];
+#pragma unroll
+  for (int h = 0; h < NH; ++h)
+#pragma unroll
+    for (int e = 0; e < 2; ++e)
+#pragma unroll
+      for (int x = 0; x < 16; ++x) acc[h][e][x] = 0.f;
+
+  // row of (step t, slot u) for this lane; rows past the slice are clamped and weighted by 0
+  auto row_of = [&](int t, int u) { return m_lo + 2 * wave + half + 8 * (t * UNR + u); };
+  auto load_j = [&](int t, int (&j)[UNR]) {
+#pragma unroll
+    for (int u = 0; u < UNR; ++u) {
+      const int m = row_of(t, u);
+      j[u] = uidx[m < m_hi ? m : m_safe];
+    }
+  };
+  auto load_rows = [&](int t, const int (&j)[UNR], uint32_t (&vv)[UNR], float (&av)[UNR][NH]) {
+#pragma unroll
+    for (int u = 0; u < UNR; ++u) {
+      const int m = row_of(t, u);
+      const bool ok = m < m_hi;
+      vv[u] = *reinterpret_cast<const uint32_t*>(vn + (int64_t)j[u] * d_model + cc);
+#pragma unroll
+      for (int h = 0; h < NH; ++h) {
+        const int b = 32 * h + cl;
+        const float a = uact[(int64_t)(ok ? m : m_safe) * B + (b < B ? b : 0)];
+        av[u][h] = (ok && b < B) ? a : 0.f;
+      }
+    }
+  };
+  const int rows_w = max(0, m_hi - (m_lo + 2 * wave));      // rows from this wave's first pair on
+  const int steps = (rows_w + 8 * UNR - 1) / (8 * UNR);
+  if (m_total > 0 && steps > 0) {
+    int j0[UNR], j1[UNR];
+    uint32_t v0[UNR], v1[UNR];
+    float a0[UNR][NH], a1[UNR][NH];
+    load_j(0, j0);
+    load_j(1, j1);
+    load_rows(0, j0, v0, a0);
+    for (int t = 0; t < steps; ++t) {
+      int j2[UNR];
+      load_j(t + 2, j2);
+      load_rows(t + 1, j1, v1, a1);
+#pragma unroll
+      for (int u = 0; u < UNR; ++u) {
+        const float w[2] = {bf16_lo(v0[u]), bf16_hi(v0[u])};
+#pragma unroll
+        for (int h = 0; h < NH; ++h)
+#pragma unroll
+          for (int e = 0; e < 2; ++e) acc[h][e] = __builtin_amdgcn_mfma_f32_32x32x2f32(a0[u][h], w[e], acc[h][e], 0, 0, 0);
+      }
+#pragma unroll
+      for (int u = 0; u < UNR; ++u) {
+        v0[u] = v1[u];
+        j1[u] = j2[u];
+#pragma unroll
+        for (int h = 0; h < NH; ++h) a0[u][h] = a1[u][h];
+      }
+    }
+  }
+  // sum the four waves' tiles through LDS in wave order, then wave 0 stores
+  for (int wv = 3; wv >= 1; --wv) {
+    __syncthreads();
+    if (wave == wv) {
+#pragma unroll
+      for (int h = 0; h < NH; ++h)
+#pragma unroll
+        for (int e = 0; e < 2; ++e)
+#pragma unroll
+          for (int x = 0; x < 16; ++x) {
+            float* slot = &vred[((h * 2 + e) * 16 + x) * kWave + lane];
+            *slot = (wv == 3) ? acc[h][e][x] : *slot + acc[h][e][x];
+          }
+    }
+  }
+  __syncthreads();
+  if (wave != 0 || !col_ok) return;
+  float* dst = part + (int64_t)blockIdx.y * B * d_model;
+#pragma unroll
+  for (int h = 0; h < NH; ++h)
+#pragma unroll
+    for (int x = 0; x < 16; ++x) {
+      // D[i][n]: n = lane % 32, i = 8 * (x / 4) + 4 * (lane / 32) + x % 4
+      const int b = 32 * h + 8 * (x / 4) + 4 * half + (x % 4);
+      if (b >= B) continue;
+      float2 o;
+      o.x = acc[h][0][x] + vred[((h * 2 + 0) * 16 + x) * kWave + lane];
+      o.y = acc[h][1][x] + vred[((h * 2 + 1) * 16 + x) * kWave + lane];
+      *reinterpret_cast<float2*>(dst + (int64_t)b * d_model + c0) = o;
+    }
+}
+
 template <typename WT>
 hipError_t launch_general_t(const FfnProblem& p, const FfnWorkspace& ws, int dense, hipStream_t st) {
   const WT* k1n = static_cast<const WT*>(p.k1n);
@@ -237,6 +471,43 @@ hipError_t launch_general_t(const FfnProblem& p, const FfnWorkspace& ws, int den
   const WT* vn = static_cast<const WT*>(p.vn);
   const int B = p.batch;
   const int r2 = p.d_model - p.r;
+
+  if constexpr (sizeof(WT) == 2) {
+    if (B >= 2 && p.q_bf16) {
+      const bf16_t* qb = static_cast<const bf16_t*>(p.q);
+      const int tiles = (p.d_ff + 15) / 16;
+      const int nb = (B + 15) / 16;
+#define SPARK_LAUNCH_ROWS(NB, MODE, W, K, QOFF, OUT)                                                     \
+  hipLaunchKernelGGL((rows_mfma_kernel<NB, MODE>), dim3(tiles), dim3(kRowsWaves * kWave), 0, st, W, p.d_ff, K, qb, p.ldq, \
+                     QOFF, B, p.d_ff, ws.uidx, ws.ucount, ws.A, OUT, p.gelu, dense, ws.flags,             \
+                     static_cast<int32_t*>(ws.fused))
+      if (nb == 1) SPARK_LAUNCH_ROWS(1, 0, k1n, p.r, 0, ws.S);
+      else if (nb == 2) SPARK_LAUNCH_ROWS(2, 0, k1n, p.r, 0, ws.S);
+      else SPARK_LAUNCH_ROWS(4, 0, k1n, p.r, 0, ws.S);
+      hipError_t e = launch_stat_topk(ws.S, 0, B, p.d_ff, p.d_ff, p.z, 0, ws.A, p.d_ff, p.theta, p.active_count,
+                                      p.active_idx, p.d_ff, ws.flags, st);
+      if (e != hipSuccess) return e;
+      hipLaunchKernelGGL(union_kernel, dim3(1), dim3(1024), 0, st, ws.flags, p.d_ff, ws.uidx, ws.ucount,
+                         p.union_idx, p.union_count);
+      if (dense) hipLaunchKernelGGL(iota_kernel, dim3(16), dim3(256), 0, st, p.d_ff, ws.uidx, ws.ucount);
+      if (nb == 1) SPARK_LAUNCH_ROWS(1, 1, k2n, r2, p.r, ws.uact);
+      else if (nb == 2) SPARK_LAUNCH_ROWS(2, 1, k2n, r2, p.r, ws.uact);
+      else SPARK_LAUNCH_ROWS(4, 1, k2n, r2, p.r, ws.uact);
+#undef SPARK_LAUNCH_ROWS
+      const int ksv = ws.ksplit < 16 ? ws.ksplit : 16;
+      const dim3 vgrid((p.d_model + 63) / 64, ksv);
+      if (B <= 32)
+        hipLaunchKernelGGL((v_mfma_kernel<1>), vgrid, dim3(256), 32 * kWave * 4, st, vn, p.d_model, B, ws.uact,
+                           ws.uidx, ws.ucount, ws.part);
+      else
+        hipLaunchKernelGGL((v_mfma_kernel<2>), vgrid, dim3(256), 2 * 32 * kWave * 4, st, vn, p.d_model, B,
+                           ws.uact, ws.uidx, ws.ucount, ws.part);
+      const int64_t n = (int64_t)B * p.d_model;
+      hipLaunchKernelGGL(reduce_kernel, dim3((unsigned)((n + kBlock - 1) / kBlock)), dim3(kBlock), 0, st, ws.part,
+                         ksv, n, p.y);
+      return hipGetLastError();
+    }
+  }
 
   {
     const int grid = min((p.d_ff + kWavesPerBlock - 1) / kWavesPerBlock, 4096);
