@@ -230,8 +230,17 @@ __global__ __launch_bounds__(kBlock) void reduce_kernel(const float* __restrict_
                                                         int64_t n, float* __restrict__ y) {
   const int64_t i = (int64_t)blockIdx.x * kBlock + threadIdx.x;
   if (i >= n) return;
+  // slices are added in ascending order; the loads of eight slices are issued together
   float s = 0.f;
-  for (int ks = 0; ks < ksplit; ++ks) s += part[(int64_t)ks * n + i];
+  int ks = 0;
+  for (; ks + 8 <= ksplit; ks += 8) {
+    float v[8];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) v[u] = part[(int64_t)(ks + u) * n + i];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) s += v[u];
+  }
+  for (; ks < ksplit; ++ks) s += part[(int64_t)ks * n + i];
   y[i] = s;
 }
 
@@ -464,6 +473,108 @@ __global__ __launch_bounds__(256) void v_mfma_kernel(const bf16_t* __restrict__ 
     }
 }
 
+// ------------------------------------------------------------------- dense comparison path
+// Batch 1, every neuron's K2n and Vn row is read (Eq.3 instead of Eq.4): the same-GPU
+// comparison point of the sparse path.  Three launches: all scores and all K2 products in one
+// sweep over K1n and K2n, the statistical top-k of the scores, a column-blocked sweep over Vn.
+template <typename WT>
+__global__ __launch_bounds__(256) void dense_rows_kernel(const WT* __restrict__ k1n, const WT* __restrict__ k2n,
+                                                         int d_ff, int r, int r2, const void* __restrict__ q,
+                                                         int q_bf16, float* __restrict__ S, float* __restrict__ G,
+                                                         int32_t* __restrict__ flags, int32_t* __restrict__ status) {
+  constexpr int VEC = Vec16<WT>::N;
+  extern __shared__ float qs[];  // q as fp32, d_model entries
+  const int tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid / kWave;
+  for (int i = blockIdx.x * 256 + tid; i < d_ff; i += gridDim.x * 256) flags[i] = 0;
+  if (blockIdx.x == 0 && tid == 0) status[0] = 0;
+  for (int i = tid; i < r + r2; i += 256) qs[i] = load_q(q, q_bf16, i);
+  __syncthreads();
+  const int nvec1 = r / VEC, nvec2 = r2 / VEC;
+  const int gw = blockIdx.x * 4 + wave, nw = gridDim.x * 4;
+  for (int j = gw * 2; j < d_ff; j += nw * 2) {
+    const int jb = j + 1 < d_ff ? j + 1 : j;
+    const WT *a1 = k1n + (int64_t)j * r, *b1 = k1n + (int64_t)jb * r;
+    const WT *a2 = k2n + (int64_t)j * r2, *b2 = k2n + (int64_t)jb * r2;
+    float sa = 0.f, sb = 0.f, ga = 0.f, gb = 0.f;
+    for (int c = lane; c < nvec1; c += kWave) {
+      const Vec16<WT> wa = load_vec16<WT>(a1 + (int64_t)c * VEC), wb = load_vec16<WT>(b1 + (int64_t)c * VEC);
+#pragma unroll
+      for (int e = 0; e < VEC; ++e) {
+        const float qv = qs[c * VEC + e];
+        sa += wa.get(e) * qv;
+        sb += wb.get(e) * qv;
+      }
+    }
+    for (int c = lane; c < nvec2; c += kWave) {
+      const Vec16<WT> wa = load_vec16<WT>(a2 + (int64_t)c * VEC), wb = load_vec16<WT>(b2 + (int64_t)c * VEC);
+#pragma unroll
+      for (int e = 0; e < VEC; ++e) {
+        const float qv = qs[r + c * VEC + e];
+        ga += wa.get(e) * qv;
+        gb += wb.get(e) * qv;
+      }
+    }
+    sa = wave_sum(sa);
+    sb = wave_sum(sb);
+    ga = wave_sum(ga);
+    gb = wave_sum(gb);
+    if (lane == 0) {
+      S[j] = sa;
+      G[j] = ga;
+      if (j + 1 < d_ff) {
+        S[j + 1] = sb;
+        G[j + 1] = gb;
+      }
+    }
+  }
+}
+
+// part[ks][c] = sum over the rows j of slice ks of u_j * Vn[j][c], u_j = GELU(a_j) * g_j (0 where
+// a_j <= 0).  Thread = (16-byte column chunk cc of 16, row group rr of 32); the 32 row groups
+// are summed through LDS in a fixed order.
+template <typename WT>
+__global__ __launch_bounds__(512) void dense_v_kernel(const WT* __restrict__ vn, int d_ff, int d_model,
+                                                      const float* __restrict__ A, const float* __restrict__ G,
+                                                      int gelu_kind, float* __restrict__ part) {
+  constexpr int VEC = Vec16<WT>::N;
+  constexpr int RG = 32, UNR = 4;
+  __shared__ float red[RG][16 * VEC + 1];
+  const int tid = threadIdx.x, cc = tid & 15, rr = tid >> 4;
+  const int col0 = (blockIdx.x * 16 + cc) * VEC;
+  const bool col_ok = col0 < d_model;
+  const int per = (d_ff + gridDim.y - 1) / gridDim.y;
+  const int j_lo = blockIdx.y * per, j_hi = min(d_ff, j_lo + per);
+  float acc[VEC];
+#pragma unroll
+  for (int e = 0; e < VEC; ++e) acc[e] = 0.f;
+  for (int j0 = j_lo + rr; j0 < j_hi; j0 += RG * UNR) {
+    Vec16<WT> w[UNR];
+    float u[UNR];
+#pragma unroll
+    for (int t = 0; t < UNR; ++t) {
+      const int j = j0 + RG * t;
+      const bool ok = j < j_hi;
+      const int jc = ok ? j : j_lo;
+      w[t] = load_vec16<WT>(vn + (int64_t)jc * d_model + (col_ok ? col0 : 0));
+      const float a = A[jc];
+      u[t] = (ok && a > 0.f) ? gelu(a, gelu_kind) * G[jc] : 0.f;
+    }
+#pragma unroll
+    for (int t = 0; t < UNR; ++t)
+#pragma unroll
+      for (int e = 0; e < VEC; ++e) acc[e] += u[t] * w[t].get(e);
+  }
+#pragma unroll
+  for (int e = 0; e < VEC; ++e) red[rr][cc * VEC + e] = acc[e];
+  __syncthreads();
+  if (tid < 16 * VEC) {
+    float s = 0.f;
+    for (int g = 0; g < RG; ++g) s += red[g][tid];
+    const int c = blockIdx.x * 16 * VEC + tid;
+    if (c < d_model) part[(int64_t)blockIdx.y * d_model + c] = s;
+  }
+}
+
 template <typename WT>
 hipError_t launch_general_t(const FfnProblem& p, const FfnWorkspace& ws, int dense, hipStream_t st) {
   const WT* k1n = static_cast<const WT*>(p.k1n);
@@ -471,6 +582,21 @@ hipError_t launch_general_t(const FfnProblem& p, const FfnWorkspace& ws, int den
   const WT* vn = static_cast<const WT*>(p.vn);
   const int B = p.batch;
   const int r2 = p.d_model - p.r;
+
+  if (dense && B == 1) {
+    hipLaunchKernelGGL((dense_rows_kernel<WT>), dim3(2048), dim3(256), (size_t)p.d_model * 4, st, k1n, k2n, p.d_ff,
+                       p.r, r2, p.q, p.q_bf16, ws.S, ws.uact, ws.flags, static_cast<int32_t*>(ws.fused));
+    hipError_t e = launch_stat_topk(ws.S, 0, 1, p.d_ff, p.d_ff, p.z, 0, ws.A, p.d_ff, p.theta, p.active_count,
+                                    p.active_idx, p.d_ff, nullptr, st);
+    if (e != hipSuccess) return e;
+    constexpr int VEC = Vec16<WT>::N;
+    const dim3 grid((p.d_model + 16 * VEC - 1) / (16 * VEC), ws.ksplit);
+    hipLaunchKernelGGL((dense_v_kernel<WT>), grid, dim3(512), 0, st, vn, p.d_ff, p.d_model, ws.A, ws.uact, p.gelu,
+                       ws.part);
+    hipLaunchKernelGGL(reduce_kernel, dim3((unsigned)((p.d_model + kBlock - 1) / kBlock)), dim3(kBlock), 0, st,
+                       ws.part, ws.ksplit, (int64_t)p.d_model, p.y);
+    return hipGetLastError();
+  }
 
   if constexpr (sizeof(WT) == 2) {
     if (B >= 2 && p.q_bf16) {
