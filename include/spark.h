@@ -175,9 +175,13 @@ spark_status spark_ffn_dense_decode(const spark_ffn_layer* layer, const void* q,
 spark_status spark_ffn_check(const void* workspace, int32_t d_model, int32_t d_ff, int32_t batch,
                              void* hip_stream);
 
-/* Host.  Testing aid: a non-zero value routes batch-1 calls through the general multi-kernel
- * path instead of the persistent launch (process-wide). */
+/* Host.  Testing aid (process-wide): 0 = automatic choice of the batch-1 path (phase by
+ * phase over the layers of a call), 1 = general multi-kernel path, 2 = persistent launch. */
 void spark_debug_force_general(int on);
+
+/* Host.  Testing / tuning aid (process-wide): rows per workgroup of the predictor sweep and
+ * neurons per workgroup of the gather of the batch-1 path; 0 = automatic. */
+void spark_debug_tuning(int rows_per_predict_block, int neurons_per_gather_block);
 
 /* Host.  Testing aid: with profiling on, every wavefront of the persistent launch records
  * how long it lived and how long it spent in each of its waits (100 MHz ticks);

@@ -72,11 +72,12 @@ spark::FfnProblem make_problem(const spark_ffn_layer* L, const void* q, int qdty
   return p;
 }
 
-int g_force_general = 0;
+int g_force_general = 0;  // 0: automatic, 1: general multi-kernel path, 2: persistent launch
 
-// Runs layers[0..n) for one token through the persistent launch.
+// Runs layers[0..n) for one token through the phase-by-phase path (persistent = false) or
+// the persistent launch.
 hipError_t run_fused(const spark_ffn_layer* layers, int32_t n_layers, const spark::FfnProblem& p0,
-                     const spark::FfnWorkspace& ws, hipStream_t st) {
+                     const spark::FfnWorkspace& ws, bool persistent, hipStream_t st) {
   const void* k1n[256];
   const void* k2n[256];
   const void* vn[256];
@@ -95,7 +96,8 @@ hipError_t run_fused(const spark_ffn_layer* layers, int32_t n_layers, const spar
     if (p.active_idx) p.active_idx += (int64_t)base * p0.d_ff;
     if (p.union_count) p.union_count += base;
     if (p.union_idx) p.union_idx += (int64_t)base * p0.d_ff;
-    e = spark::launch_ffn_fused(p, k1n, k2n, vn, n, ws.fused, st);
+    e = persistent ? spark::launch_ffn_fused(p, k1n, k2n, vn, n, ws.fused, st)
+                   : spark::launch_ffn_phased(p, k1n, k2n, vn, n, ws.fused, st);
   }
   return e;
 }
@@ -181,8 +183,10 @@ spark_status spark_ffn_decode(const spark_ffn_layer* layer, const void* q, spark
                                            union_count, union_idx);
   const spark::FfnWorkspace ws = spark::carve_workspace(workspace, layer->d_model, layer->d_ff, batch);
   hipError_t e;
-  if (!g_force_general && spark::fused_supported(p, 1))
-    e = run_fused(layer, 1, p, ws, static_cast<hipStream_t>(hip_stream));
+  if (g_force_general == 0 && spark::phased_supported(p))
+    e = run_fused(layer, 1, p, ws, false, static_cast<hipStream_t>(hip_stream));
+  else if (g_force_general == 2 && spark::fused_supported(p, 1))
+    e = run_fused(layer, 1, p, ws, true, static_cast<hipStream_t>(hip_stream));
   else
     e = spark::launch_ffn_general(p, ws, 0, static_cast<hipStream_t>(hip_stream));
   return e == hipSuccess ? SPARK_OK : SPARK_ERR_DEVICE;
@@ -208,8 +212,12 @@ spark_status spark_ffn_decode_layers(const spark_ffn_layer* layers, int32_t n_la
   {
     const spark::FfnProblem p0 = make_problem(&layers[0], q, qdtype, batch, ldq, y, theta, active_count,
                                               active_idx, union_count, union_idx);
-    if (!g_force_general && spark::fused_supported(p0, n_layers)) {
-      const hipError_t e = run_fused(layers, n_layers, p0, ws, static_cast<hipStream_t>(hip_stream));
+    if (g_force_general == 0 && spark::phased_supported(p0)) {
+      const hipError_t e = run_fused(layers, n_layers, p0, ws, false, static_cast<hipStream_t>(hip_stream));
+      return e == hipSuccess ? SPARK_OK : SPARK_ERR_DEVICE;
+    }
+    if (g_force_general == 2 && spark::fused_supported(p0, n_layers)) {
+      const hipError_t e = run_fused(layers, n_layers, p0, ws, true, static_cast<hipStream_t>(hip_stream));
       return e == hipSuccess ? SPARK_OK : SPARK_ERR_DEVICE;
     }
   }
@@ -249,7 +257,11 @@ spark_status spark_ffn_check(const void* workspace, int32_t d_model, int32_t d_f
   return word == 0 ? SPARK_OK : SPARK_ERR_DEVICE;
 }
 
-void spark_debug_force_general(int on) { g_force_general = on != 0; }
+void spark_debug_force_general(int on) { g_force_general = (on == 1 || on == 2) ? on : 0; }
+
+void spark_debug_tuning(int rows_per_predict_block, int neurons_per_gather_block) {
+  spark::phased_set_tuning(rows_per_predict_block, neurons_per_gather_block);
+}
 
 void spark_debug_profile(int on) { spark::fused_set_profile(on != 0); }
 

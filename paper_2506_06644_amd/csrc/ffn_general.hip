@@ -6,6 +6,8 @@
 //   k2       u[m][b]   = GELU(A[b][U[m]]) * (K2n[U[m]] . q_b[r:])      (reads only union rows)
 //   v        y[b][c]   = sum_m u[m][b] * Vn[U[m]][c]                    (reads only union rows)
 // Per-token masks skip arithmetic; the union decides which rows are fetched (Appendix B).
+#include <algorithm>
+
 #include "spark_device.h"
 #include "spark_internal.h"
 
@@ -702,7 +704,7 @@ size_t ffn_workspace_bytes(int d_model, int d_ff, int batch) {
   t += 256;                                            // ucount
   t += align_up(F * B * 4, 256);                       // uact
   t += align_up((size_t)pick_ksplit(d_model) * B * D * 4, 256);  // part
-  t += align_up(fused_scratch_bytes(d_model, d_ff), 256);
+  t += align_up(std::max(fused_scratch_bytes(d_model, d_ff), phased_scratch_bytes(d_model, d_ff)), 256);
   return t;
 }
 
@@ -719,7 +721,7 @@ FfnWorkspace carve_workspace(void* base, int d_model, int d_ff, int batch) {
   ws.ksplit = pick_ksplit(d_model);
   ws.part = reinterpret_cast<float*>(p);     p += align_up((size_t)ws.ksplit * B * D * 4, 256);
   ws.fused = p;
-  ws.fused_bytes = fused_scratch_bytes(d_model, d_ff);
+  ws.fused_bytes = std::max(fused_scratch_bytes(d_model, d_ff), phased_scratch_bytes(d_model, d_ff));
   return ws;
 }
 

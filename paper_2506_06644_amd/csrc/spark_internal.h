@@ -62,4 +62,14 @@ bool fused_supported(const FfnProblem& p, int n_layers);
 hipError_t launch_ffn_fused(const FfnProblem& p0, const void* const* k1n, const void* const* k2n,
                             const void* const* vn, int n_layers, void* scratch, hipStream_t st);
 
+// Phase-by-phase batch-1 path: predictor sweep, gather, reduce as ordinary launches over up
+// to kPhasedMaxLayers layers at a time (longer stacks are chained).  `scratch` holds
+// phased_scratch_bytes(d_model, d_ff) bytes, 256-byte aligned, and needs no initialisation.
+constexpr int kPhasedMaxLayers = 64;
+size_t phased_scratch_bytes(int d_model, int d_ff);
+bool phased_supported(const FfnProblem& p);
+void phased_set_tuning(int rows_per_predict_block, int neurons_per_gather_block);  // 0 = automatic
+hipError_t launch_ffn_phased(const FfnProblem& p0, const void* const* k1n, const void* const* k2n,
+                             const void* const* vn, int n_layers, void* scratch, hipStream_t st);
+
 }  // namespace spark

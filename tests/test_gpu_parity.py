@@ -153,8 +153,9 @@ def test_tanh_gelu_variant():
     _ffn_case(synth.TINY, torch.float32, torch.float32, 1, gelu=binding.GELU_TANH)
 
 
-# batch 1 has two implementations (one persistent launch / separate kernels): both are held to the oracle
-@pytest.mark.parametrize("force_general", [False, True])
+# batch 1 has three implementations (phase by phase over the layers of a call, separate kernels
+# per layer, one persistent launch): all are held to the oracle
+@pytest.mark.parametrize("force_general", [0, 1, 2])
 @pytest.mark.parametrize("shape,wdtype,qdtype", [
     (synth.TINY, torch.float32, torch.float32), (synth.TINY, torch.bfloat16, torch.bfloat16),
     (synth.TINY, torch.bfloat16, torch.float32), (synth.RAGGED, torch.bfloat16, torch.bfloat16),
@@ -163,25 +164,40 @@ def test_batch1_both_paths(shape, wdtype, qdtype, force_general):
     _ffn_case(shape, wdtype, qdtype, 1, n_layers=3, via_layers=True, force_general=force_general, seed=31)
 
 
+@pytest.mark.parametrize("path", [0, 2])
 @pytest.mark.parametrize("n_layers", [1, 2, 9, 70])
-def test_persistent_launch_layer_counts(n_layers):
-    """Stacks shorter and longer than the kernel's internal rings, and longer than one launch holds."""
-    _ffn_case(synth.TINY, torch.bfloat16, torch.bfloat16, 1, n_layers=n_layers, via_layers=True, seed=500)
+def test_layer_counts(n_layers, path):
+    """Stacks shorter and longer than the persistent kernel's rings, and longer than one launch holds."""
+    _ffn_case(synth.TINY, torch.bfloat16, torch.bfloat16, 1, n_layers=n_layers, via_layers=True, seed=500,
+              force_general=path)
 
 
-def test_persistent_launch_is_reproducible():
+@pytest.mark.parametrize("path", [0, 2])
+def test_batch1_is_reproducible(path):
     sh = synth.GEMMA2_2B
     weights = synth.ffn_stack(sh, 4, base_seed=1000, dtype=torch.bfloat16)
     q = synth.tokens(sh, 1, 2001, torch.bfloat16)
-    a = run_gpu_ffn(sh, weights, q, via_layers=True)
+    a = run_gpu_ffn(sh, weights, q, via_layers=True, force_general=path)
     for _ in range(3):
-        b = run_gpu_ffn(sh, weights, q, via_layers=True)
+        b = run_gpu_ffn(sh, weights, q, via_layers=True, force_general=path)
         assert np.array_equal(a["y"], b["y"]) and np.array_equal(a["idx"], b["idx"])
 
 
-def test_paper_layer_shape_and_9b_shape():
-    _ffn_case(synth.PAPER_2B, torch.bfloat16, torch.bfloat16, 1, n_layers=2, via_layers=True, seed=9)
-    _ffn_case(synth.GEMMA2_9B, torch.bfloat16, torch.bfloat16, 1, n_layers=2, via_layers=True, seed=10)
+@pytest.mark.parametrize("rpb,npb", [(16, 64), (48, 192), (256, 1024), (64, 128)])
+def test_block_sizes_of_the_phased_path(rpb, npb):
+    """Every split of the neurons into predictor / gather blocks gives the oracle's layer (ragged tails included)."""
+    binding.spark_debug_tuning(rpb, npb)
+    try:
+        _ffn_case(synth.RAGGED, torch.bfloat16, torch.bfloat16, 1, n_layers=3, via_layers=True, seed=77)
+        _ffn_case(synth.TINY, torch.float32, torch.float32, 1, n_layers=2, via_layers=True, seed=78)
+    finally:
+        binding.spark_debug_tuning(0, 0)
+
+
+@pytest.mark.parametrize("path", [0, 2])
+def test_paper_layer_shape_and_9b_shape(path):
+    _ffn_case(synth.PAPER_2B, torch.bfloat16, torch.bfloat16, 1, n_layers=2, via_layers=True, seed=9, force_general=path)
+    _ffn_case(synth.GEMMA2_9B, torch.bfloat16, torch.bfloat16, 1, n_layers=2, via_layers=True, seed=10, force_general=path)
     _ffn_case(synth.GEMMA2_9B, torch.bfloat16, torch.bfloat16, 8, n_layers=1, seed=11)
 
 
