@@ -181,7 +181,7 @@ void spark_debug_force_general(int on);
 
 /* Host.  Testing / tuning aid (process-wide): rows per workgroup of the predictor sweep and
  * neurons per workgroup of the gather of the batch-1 path; 0 = automatic. */
-void spark_debug_tuning(int rows_per_predict_block, int neurons_per_gather_block);
+void spark_debug_tuning(int rows_per_predict_block, int neurons_per_gather_block, int alt);
 
 /* Host.  Testing aid: with profiling on, every wavefront of the persistent launch records
  * how long it lived and how long it spent in each of its waits (100 MHz ticks);

@@ -83,7 +83,7 @@ def load_library():
     lib.spark_debug_force_general.restype = None
     lib.spark_debug_force_general.argtypes = [c_int]
     lib.spark_debug_tuning.restype = None
-    lib.spark_debug_tuning.argtypes = [c_int, c_int]
+    lib.spark_debug_tuning.argtypes = [c_int, c_int, c_int]
     _lib = lib
     return lib
 
@@ -189,8 +189,8 @@ def spark_debug_force_general(on):
     load_library().spark_debug_force_general(int(on))
 
 
-def spark_debug_tuning(rows_per_predict_block: int = 0, neurons_per_gather_block: int = 0):
-    load_library().spark_debug_tuning(int(rows_per_predict_block), int(neurons_per_gather_block))
+def spark_debug_tuning(rows_per_predict_block: int = 0, neurons_per_gather_block: int = 0, alt: int = 0):
+    load_library().spark_debug_tuning(int(rows_per_predict_block), int(neurons_per_gather_block), int(alt))
 
 
 def spark_debug_profile(on: bool):

@@ -211,14 +211,31 @@ __global__ __launch_bounds__(256) void predict_layers_kernel(const PhasedParams 
 }
 
 // ---------------------------------------------------------------------------------- gather
+// 16-byte load of chunk `ch` of a weight row through a buffer descriptor that spans exactly
+// that row (or nothing): chunks past the end of the row, and every chunk of a row that does
+// not exist, come back as zeros without touching memory, so the loads need no branches and
+// their number in flight is a compile-time constant.
+__device__ __forceinline__ __amdgpu_buffer_rsrc_t row_rsrc(const void* row, uint32_t bytes) {
+  return __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(row), 0, (int)bytes, 0x00020000);
+}
+template <typename WT>
+__device__ __forceinline__ Vec16<WT> row_load(__amdgpu_buffer_rsrc_t r, int ch) {
+  Vec16<WT> v;
+  const u32x4 u = __builtin_amdgcn_raw_buffer_load_b128(r, ch * 16, 0, 0);
+  v.raw = __builtin_bit_cast(decltype(v.raw), u);
+  return v;
+}
+
 // Workgroup (NW waves) = NPB consecutive neurons of one layer.  The active neurons of the
-// block are dealt to the waves round-robin in ascending order; a wave takes NIF of them at a
-// time (all their row loads are issued before the first is used) and accumulates into
-// registers; the waves' rows are then summed through LDS as a binary tree in a fixed order.
-template <typename WT, int CPL2, int CPLV, int NW, int NIF>
-__global__ __launch_bounds__(NW * kWave) void gather_layers_kernel(const PhasedParams P) {
+// block are dealt to the waves round-robin in ascending order.  A wave always has the rows of
+// its next neuron in flight while it works on the current one (two register buffers) and
+// accumulates into registers; the waves' rows are then summed through LDS as a binary tree
+// in a fixed order.
+template <typename WT, int CPL2, int CPLV, int NW, int OCC>
+__global__ __launch_bounds__(NW * kWave, OCC) void gather_layers_kernel(const PhasedParams P) {
   constexpr int VEC = Vec16<WT>::N;
   constexpr int MAXW = 16;  // mask words: NPB <= 1024
+  constexpr int SPW = (MAXW + NW - 1) / NW;
   static_assert((NW & (NW - 1)) == 0 && NW >= 2, "tree reduction");
   __shared__ unsigned long long maskw[MAXW];
   __shared__ float s_blk[MAXW * kWave];
@@ -226,7 +243,8 @@ __global__ __launch_bounds__(NW * kWave) void gather_layers_kernel(const PhasedP
   float* q2s = dyn;
   float* rows = dyn + CPL2 * kWave * VEC;
 
-  const int tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid / kWave;
+  const int tid = threadIdx.x, lane = tid & (kWave - 1);
+  const int wave = __builtin_amdgcn_readfirstlane(tid / kWave);
   const int l = blockIdx.y, blk = blockIdx.x;
   const int r2 = P.d_model - P.r;
   const int nvec2 = r2 / VEC, nvecv = P.d_model / VEC;
@@ -234,9 +252,9 @@ __global__ __launch_bounds__(NW * kWave) void gather_layers_kernel(const PhasedP
   const int nwords = P.NPB / kWave;
 
   // scores of the block (requested before the statistics are needed)
-  float sv[(MAXW + NW - 1) / NW];
+  float sv[SPW];
 #pragma unroll
-  for (int k = 0; k < (MAXW + NW - 1) / NW; ++k) {
+  for (int k = 0; k < SPW; ++k) {
     const int wd = wave + NW * k;  // mask word handled by this wave
     const int n = wd * kWave + lane;
     sv[k] = (wd < nwords && n < nn) ? P.scores[(size_t)l * P.d_ff + n0 + n] : 0.f;
@@ -249,7 +267,7 @@ __global__ __launch_bounds__(NW * kWave) void gather_layers_kernel(const PhasedP
   }
   const float theta = layer_theta(P, l, lane);
 #pragma unroll
-  for (int k = 0; k < (MAXW + NW - 1) / NW; ++k) {
+  for (int k = 0; k < SPW; ++k) {
     const int wd = wave + NW * k;
     if (wd < nwords) {
       const int n = wd * kWave + lane;
@@ -287,53 +305,42 @@ __global__ __launch_bounds__(NW * kWave) void gather_layers_kernel(const PhasedP
       cur = uniform_u64(maskw[wd]);
     }
   };
+  auto request = [&](int n, Vec16<WT>(&kr)[CPL2], Vec16<WT>(&vr)[CPLV]) {
+    const size_t j = (size_t)(n0 + (n >= 0 ? n : 0));
+    const __amdgpu_buffer_rsrc_t kb = row_rsrc(k2 + j * r2, n >= 0 ? (uint32_t)r2 * (uint32_t)sizeof(WT) : 0u);
+    const __amdgpu_buffer_rsrc_t vb = row_rsrc(vn + j * P.d_model, n >= 0 ? (uint32_t)P.d_model * (uint32_t)sizeof(WT) : 0u);
+#pragma unroll
+    for (int c = 0; c < CPL2; ++c) kr[c] = row_load<WT>(kb, lane + kWave * c);
+#pragma unroll
+    for (int c = 0; c < CPLV; ++c) vr[c] = row_load<WT>(vb, lane + kWave * c);
+  };
+  auto consume = [&](int n, const Vec16<WT>(&kr)[CPL2], const Vec16<WT>(&vr)[CPLV]) {
+    float gd = 0.f;
+#pragma unroll
+    for (int c = 0; c < CPL2; ++c) {
+      const float* qp = &q2s[(lane + kWave * c) * VEC];  // zero past the end of q[r:]
+#pragma unroll
+      for (int e = 0; e < VEC; ++e) gd += kr[c].get(e) * qp[e];
+    }
+    gd = wave_total(gd);
+    const float u = gelu(s_blk[n], P.gelu) * gd;
+#pragma unroll
+    for (int c = 0; c < CPLV; ++c)
+#pragma unroll
+      for (int e = 0; e < VEC; ++e) acc[c][e] += u * vr[c].get(e);
+  };
 
-  for (;;) {
-    int nl[NIF];
-    nl[0] = next_neuron();
-    if (nl[0] < 0) break;
-#pragma unroll
-    for (int i = 1; i < NIF; ++i) nl[i] = nl[i - 1] >= 0 ? next_neuron() : -1;
-    Vec16<WT> kr[NIF][CPL2], vr[NIF][CPLV];
-#pragma unroll
-    for (int i = 0; i < NIF; ++i) {
-      if (nl[i] >= 0) {  // uniform
-        const WT* krow = k2 + (size_t)(n0 + nl[i]) * r2;
-#pragma unroll
-        for (int c = 0; c < CPL2; ++c) {
-          const int ch = lane + kWave * c;
-          kr[i][c] = load_stream<WT>(krow + (size_t)(ch < nvec2 ? ch : 0) * VEC);
-        }
-      }
-    }
-#pragma unroll
-    for (int i = 0; i < NIF; ++i) {
-      if (nl[i] >= 0) {
-        const WT* vrow = vn + (size_t)(n0 + nl[i]) * P.d_model;
-#pragma unroll
-        for (int c = 0; c < CPLV; ++c) {
-          const int ch = lane + kWave * c;
-          vr[i][c] = load_stream<WT>(vrow + (size_t)(ch < nvecv ? ch : 0) * VEC);
-        }
-      }
-    }
-#pragma unroll
-    for (int i = 0; i < NIF; ++i) {
-      if (nl[i] >= 0) {
-        float gd = 0.f;
-#pragma unroll
-        for (int c = 0; c < CPL2; ++c) {
-          const float* qp = &q2s[(lane + kWave * c) * VEC];  // zero past the end of q[r:]
-#pragma unroll
-          for (int e = 0; e < VEC; ++e) gd += kr[i][c].get(e) * qp[e];
-        }
-        gd = wave_total(gd);
-        const float u = gelu(s_blk[nl[i]], P.gelu) * gd;
-#pragma unroll
-        for (int c = 0; c < CPLV; ++c)
-#pragma unroll
-          for (int e = 0; e < VEC; ++e) acc[c][e] += u * vr[i][c].get(e);
-      }
+  {
+    Vec16<WT> ka[CPL2], va[CPLV], kb[CPL2], vb[CPLV];
+    int na = next_neuron();
+    request(na, ka, va);
+    while (na >= 0) {
+      const int nb = next_neuron();
+      request(nb, kb, vb);
+      consume(na, ka, va);
+      na = nb >= 0 ? next_neuron() : -1;
+      request(na, ka, va);
+      if (nb >= 0) consume(nb, kb, vb);
     }
   }
 
@@ -460,13 +467,13 @@ PhasedLayout phased_layout(int d_model, int d_ff) {
 
 // Compiled gather variants: chunks per lane of a K2n row and of a Vn row.
 struct GatherVariant {
-  int bf16, cpl2, cplv, nif;
+  int bf16, cpl2, cplv, nw, occ;  // waves per workgroup, waves per SIMD the registers are held to
 };
 constexpr GatherVariant kGather[] = {
-    {1, 1, 1, 2}, {1, 3, 5, 2}, {1, 4, 7, 2}, {0, 1, 1, 2}, {0, 2, 2, 2}, {0, 5, 9, 1},
+    {1, 1, 1, 8, 4}, {1, 3, 5, 4, 3}, {1, 4, 7, 4, 2}, {0, 1, 1, 8, 4}, {0, 2, 2, 8, 4}, {0, 5, 9, 4, 2},
+    {1, 3, 5, 8, 4},  // alternative for the 2B class (tuning switch)
 };
 constexpr int kNumGather = sizeof(kGather) / sizeof(kGather[0]);
-constexpr int kGatherWaves = 8;
 
 int gather_variant(const FfnProblem& p) {
   const int vec = p.w_bf16 ? 8 : 4;
@@ -476,7 +483,7 @@ int gather_variant(const FfnProblem& p) {
   return -1;
 }
 
-int g_phased_rpb = 0, g_phased_npb = 0;  // tuning overrides (0 = automatic)
+int g_phased_rpb = 0, g_phased_npb = 0, g_phased_alt = 0;  // tuning overrides (0 = automatic)
 
 template <typename WT, bool QB>
 hipError_t launch_predict(const PhasedParams& P, int cpl1, dim3 grid, hipStream_t st) {
@@ -490,29 +497,30 @@ hipError_t launch_predict(const PhasedParams& P, int cpl1, dim3 grid, hipStream_
   return hipGetLastError();
 }
 
-template <typename WT, int CPL2, int CPLV, int NIF>
+template <typename WT, int CPL2, int CPLV, int NW, int OCC>
 hipError_t launch_gather(const PhasedParams& P, dim3 grid, hipStream_t st) {
   constexpr int VEC = Vec16<WT>::N;
-  const size_t dyn = ((size_t)CPL2 * kWave * VEC + (size_t)(kGatherWaves / 2) * P.d_model) * sizeof(float);
-  const void* kern = reinterpret_cast<const void*>(gather_layers_kernel<WT, CPL2, CPLV, kGatherWaves, NIF>);
+  const size_t dyn = ((size_t)CPL2 * kWave * VEC + (size_t)(NW / 2) * P.d_model) * sizeof(float);
+  const void* kern = reinterpret_cast<const void*>(gather_layers_kernel<WT, CPL2, CPLV, NW, OCC>);
   hipError_t e = hipFuncSetAttribute(kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)dyn);
   if (e != hipSuccess) return e;
-  hipLaunchKernelGGL((gather_layers_kernel<WT, CPL2, CPLV, kGatherWaves, NIF>), grid, dim3(kGatherWaves * kWave), dyn, st, P);
+  hipLaunchKernelGGL((gather_layers_kernel<WT, CPL2, CPLV, NW, OCC>), grid, dim3(NW * kWave), dyn, st, P);
   return hipGetLastError();
 }
 
 template <int I>
 hipError_t launch_gather_index(const PhasedParams& P, dim3 grid, hipStream_t st) {
   constexpr GatherVariant v = kGather[I];
-  if constexpr (v.bf16) return launch_gather<bf16_t, v.cpl2, v.cplv, v.nif>(P, grid, st);
-  else return launch_gather<float, v.cpl2, v.cplv, v.nif>(P, grid, st);
+  if constexpr (v.bf16) return launch_gather<bf16_t, v.cpl2, v.cplv, v.nw, v.occ>(P, grid, st);
+  else return launch_gather<float, v.cpl2, v.cplv, v.nw, v.occ>(P, grid, st);
 }
 
 }  // namespace
 
-void phased_set_tuning(int rpb, int npb) {
+void phased_set_tuning(int rpb, int npb, int alt) {
   g_phased_rpb = rpb;
   g_phased_npb = npb;
+  g_phased_alt = alt;
 }
 
 size_t phased_scratch_bytes(int d_model, int d_ff) { return phased_layout(d_model, d_ff).total; }
@@ -520,15 +528,16 @@ size_t phased_scratch_bytes(int d_model, int d_ff) { return phased_layout(d_mode
 bool phased_supported(const FfnProblem& p) {
   const int vec = p.w_bf16 ? 8 : 4;
   const int c1 = (p.r / vec + kWave - 1) / kWave;
-  const size_t lds = ((size_t)8 * kWave * 8 + (size_t)(kGatherWaves / 2) * p.d_model) * sizeof(float);
+  const size_t lds = ((size_t)8 * kWave * 8 + (size_t)4 * p.d_model) * sizeof(float);
   return p.batch == 1 && c1 <= 4 && gather_variant(p) >= 0 && lds <= 150 * 1024;
 }
 
 hipError_t launch_ffn_phased(const FfnProblem& p0, const void* const* k1n, const void* const* k2n,
                              const void* const* vn, int n_layers, void* scratch, hipStream_t st) {
   const PhasedLayout lay = phased_layout(p0.d_model, p0.d_ff);
-  const int gv = gather_variant(p0);
+  int gv = gather_variant(p0);
   if (gv < 0) return hipErrorInvalidValue;
+  if (gv == 1 && g_phased_alt == 1) gv = 6;
   const int vec = p0.w_bf16 ? 8 : 4;
   const int cpl1 = (p0.r / vec + kWave - 1) / kWave;
   char* s = static_cast<char*>(scratch);
@@ -593,6 +602,7 @@ hipError_t launch_ffn_phased(const FfnProblem& p0, const void* const* k1n, const
       case 3: err = launch_gather_index<3>(P, gc, st); break;
       case 4: err = launch_gather_index<4>(P, gc, st); break;
       case 5: err = launch_gather_index<5>(P, gc, st); break;
+      case 6: err = launch_gather_index<6>(P, gc, st); break;
       default: err = hipErrorInvalidValue; break;
     }
     if (err != hipSuccess) return err;
