@@ -25,10 +25,14 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0
-# HBM bytes per launch of the persistent kernel from two rocprofv3 --pmc runs (FETCH_SIZE, then
-# WRITE_SIZE, each scaled by what the counter reads for a plain 1 GiB device copy: x2.000 and
-# x1.000); workload key = (shape, layers, batch).  Other workloads report null.
-MEASURED_TRAFFIC_BYTES = {("gemma2-2b", 26, 1): 662.9e6 + 33.3e6}
+# HBM bytes per launch of each kernel from two rocprofv3 --pmc runs (FETCH_SIZE, then WRITE_SIZE,
+# each scaled by what the counter reads for a plain 1 GiB device copy); workload key =
+# (shape, layers, batch).  Other workloads report null.
+MEASURED_TRAFFIC_BYTES = {("gemma2-2b", 26, 1): {
+    "predict_layers_kernel": 490.8e6 + 1.08e6,   # FETCH 239652.7 KiB x 2, WRITE 1053.9 KiB x 1
+    "gather_layers_kernel": 137.26e6 + 8.63e6,   # FETCH 67023.3 KiB x 2, WRITE 8424.2 KiB x 1
+    "reduce_layers_kernel": 8.65e6 + 0.24e6,     # FETCH 4223.5 KiB x 2, WRITE 234.0 KiB x 1
+}}
 
 
 def algorithmic_bytes(shape, counts, wbytes):
@@ -52,6 +56,21 @@ def time_region(fn, steps, warmup, torch):
     torch.cuda.synchronize()
     wall = time.perf_counter() - t0
     return e0.elapsed_time(e1) * 1e-3, wall
+
+
+def back_to_back_time(fn, n, torch):
+    """Average duration of `n` back-to-back calls of `fn` between one event pair on the stream
+    the library launches on (torch's current stream): for a call that is a single kernel launch
+    this is the kernel's duration (consecutive launches on one stream do not overlap)."""
+    a = torch.cuda.Event(enable_timing=True)
+    b = torch.cuda.Event(enable_timing=True)
+    torch.cuda.synchronize()
+    a.record()
+    for _ in range(n):
+        fn()
+    b.record()
+    torch.cuda.synchronize()
+    return a.elapsed_time(b) * 1e-3 / n
 
 
 def sampled_launch_time(fn, samples, torch):
@@ -183,17 +202,49 @@ def main():
     ms_per_step = gpu_s * 1e3 / args.steps
     layers_per_s = L * args.steps / gpu_s
 
-    launch_avg_s, launch_med_s = sampled_launch_time(step, 50, torch)
     fetch_rows = union if B > 1 else counts[:, 0]
-    bytes_step = float(sum(algorithmic_bytes(shape, [int(m) for m in fetch_rows], 2)))
-    achieved = bytes_step / launch_avg_s / 1e9
-    roofline = {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                "frac": achieved / HBM_PEAK_GBS,
-                "traffic": MEASURED_TRAFFIC_BYTES.get((args.shape, L, B)),
-                "kernel": ("ffn_spec_kernel: one persistent launch per spark_ffn_decode_layers call (%d layers)" % L)
-                if B == 1 else "whole spark_ffn_decode_layers call (several kernels per layer)",
-                "bytes_per_launch": bytes_step, "launch_us": launch_avg_s * 1e6,
-                "launch_us_median": launch_med_s * 1e6}
+    per_layer = algorithmic_bytes(shape, [int(m) for m in fetch_rows], 2)
+    bytes_step = float(sum(per_layer))
+    call_avg_s, call_med_s = sampled_launch_time(step, 50, torch)
+    if B == 1:
+        # Each kernel of the call timed alone (the other launches switched off; their outputs of
+        # the full call above are still in the workspace): 200 back-to-back launches between
+        # two events, five times; the median of the five averages is reported as well.
+        k1_bytes = 2.0 * shape.d_ff * shape.r * L
+        kernels = {}
+        for name, mask, nbytes in (("predict_layers_kernel", 1, k1_bytes),
+                                   ("gather_layers_kernel", 2, bytes_step - k1_bytes),
+                                   ("reduce_layers_kernel", 4, None)):
+            binding.spark_debug_phases(mask)
+            for _ in range(5):
+                step()
+            runs = sorted(back_to_back_time(step, 200, torch) for _ in range(5))
+            avg_s, med_s = sum(runs) / len(runs), runs[len(runs) // 2]
+            kernels[name] = {"launch_us": avg_s * 1e6, "launch_us_median": med_s * 1e6}
+            if nbytes:
+                kernels[name].update(bytes_per_launch=nbytes, achieved=nbytes / avg_s / 1e9,
+                                     frac=nbytes / avg_s / 1e9 / HBM_PEAK_GBS)
+        binding.spark_debug_phases(0)
+        dom = kernels["predict_layers_kernel"]
+        traffic = MEASURED_TRAFFIC_BYTES.get((args.shape, L, B))
+        roofline = {"bound": "hbm", "achieved": dom["achieved"], "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                    "frac": dom["frac"], "traffic": traffic["predict_layers_kernel"] if traffic else None,
+                    "kernel": "predict_layers_kernel (the predictor sweep over all K1n of the call: the dominant "
+                              "kernel, %d layers per launch)" % L,
+                    "bytes_per_launch": dom["bytes_per_launch"], "launch_us": dom["launch_us"],
+                    "launch_us_median": dom["launch_us_median"],
+                    "other_kernels": {k: dict(v, traffic=(traffic or {}).get(k)) for k, v in kernels.items()
+                                      if k != "predict_layers_kernel"},
+                    "whole_call": {"bytes": bytes_step, "call_us": call_avg_s * 1e6,
+                                   "call_us_median": call_med_s * 1e6, "achieved": bytes_step / call_avg_s / 1e9,
+                                   "frac": bytes_step / call_avg_s / 1e9 / HBM_PEAK_GBS}}
+    else:
+        achieved = bytes_step / call_avg_s / 1e9
+        roofline = {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                    "frac": achieved / HBM_PEAK_GBS, "traffic": None,
+                    "kernel": "whole spark_ffn_decode_layers call (several kernels per layer)",
+                    "bytes_per_launch": bytes_step, "launch_us": call_avg_s * 1e6,
+                    "launch_us_median": call_med_s * 1e6}
 
     out = {
         "metric": "Spark-FFN decode layers/s + achieved HBM GB/s vs peak (Gemma-2-2B shape, b=1)",

@@ -179,6 +179,12 @@ spark_status spark_ffn_check(const void* workspace, int32_t d_model, int32_t d_f
  * phase over the layers of a call), 1 = general multi-kernel path, 2 = persistent launch. */
 void spark_debug_force_general(int on);
 
+/* Host.  Measurement aid (process-wide): which launches of the batch-1 path a call makes: bit 0
+ * the predictor sweep, bit 1 the gather, bit 2 the reduction (and the index lists); 0 = all.
+ * A call that skips a launch leaves that launch's outputs as an earlier full call on the same
+ * workspace wrote them, so each kernel can be timed alone on valid inputs. */
+void spark_debug_phases(int mask);
+
 /* Host.  Testing / tuning aid (process-wide): rows per workgroup of the predictor sweep and
  * neurons per workgroup of the gather of the batch-1 path; 0 = automatic. */
 void spark_debug_tuning(int rows_per_predict_block, int neurons_per_gather_block, int alt);

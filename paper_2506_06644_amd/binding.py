@@ -24,7 +24,7 @@ MAX_BATCH = 64
 EXPORTS = (
     "spark_status_string", "spark_version", "spark_normal_quantile", "spark_stat_topk",
     "spark_ffn_workspace_bytes", "spark_ffn_decode", "spark_ffn_decode_layers",
-    "spark_ffn_dense_decode", "spark_ffn_check", "spark_debug_force_general", "spark_debug_tuning",
+    "spark_ffn_dense_decode", "spark_ffn_check", "spark_debug_force_general", "spark_debug_tuning", "spark_debug_phases",
     "spark_debug_profile", "spark_debug_read_profile",
 )
 
@@ -82,6 +82,8 @@ def load_library():
     lib.spark_debug_read_profile.argtypes = [vp, i32, i32, i32, vp, i64, vp]
     lib.spark_debug_force_general.restype = None
     lib.spark_debug_force_general.argtypes = [c_int]
+    lib.spark_debug_phases.restype = None
+    lib.spark_debug_phases.argtypes = [c_int]
     lib.spark_debug_tuning.restype = None
     lib.spark_debug_tuning.argtypes = [c_int, c_int, c_int]
     _lib = lib
@@ -187,6 +189,10 @@ def spark_ffn_check(workspace: torch.Tensor, d_model: int, d_ff: int, batch: int
 def spark_debug_force_general(on):
     """False / 0: automatic path, True / 1: general multi-kernel path, 2: persistent launch."""
     load_library().spark_debug_force_general(int(on))
+
+
+def spark_debug_phases(mask: int = 0):
+    load_library().spark_debug_phases(int(mask))
 
 
 def spark_debug_tuning(rows_per_predict_block: int = 0, neurons_per_gather_block: int = 0, alt: int = 0):

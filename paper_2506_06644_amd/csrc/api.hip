@@ -259,6 +259,8 @@ spark_status spark_ffn_check(const void* workspace, int32_t d_model, int32_t d_f
 
 void spark_debug_force_general(int on) { g_force_general = (on == 1 || on == 2) ? on : 0; }
 
+void spark_debug_phases(int mask) { spark::phased_set_phases(mask); }
+
 void spark_debug_tuning(int rows_per_predict_block, int neurons_per_gather_block, int alt) {
   spark::phased_set_tuning(rows_per_predict_block, neurons_per_gather_block, alt);
 }

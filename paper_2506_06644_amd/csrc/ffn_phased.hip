@@ -108,9 +108,10 @@ __device__ __forceinline__ float layer_theta(const PhasedParams& P, int l, int l
 }
 
 // --------------------------------------------------------------------------------- predict
-// Workgroup (4 waves) = RPB consecutive neurons of one layer; a wave owns RPB / 4 consecutive
-// rows and reads them four at a time (4 * CPL1 16-byte loads in flight per lane; occupancy
-// does the rest of the latency hiding).
+// Workgroup (4 waves) = RPB consecutive neurons of one layer, swept 16 rows at a time: each
+// wave reads four consecutive rows of the 16 (4 * CPL1 16-byte loads in flight per lane;
+// occupancy does the rest of the latency hiding), so the workgroup as a whole walks through
+// one contiguous stretch of memory.
 template <typename WT, bool QB, int CPL1>
 __global__ __launch_bounds__(256) void predict_layers_kernel(const PhasedParams P) {
   constexpr int VEC = Vec16<WT>::N;
@@ -146,7 +147,7 @@ __global__ __launch_bounds__(256) void predict_layers_kernel(const PhasedParams 
     Vec16<WT> reg[R][CPL1];
 #pragma unroll
     for (int e = 0; e < R; ++e) {
-      const int lr = wave * rpw + i + e;
+      const int lr = i * 4 + wave * R + e;
       // rows past the end of the layer re-read the block's first row; the value is dropped
       const WT* row = base + (size_t)(row0 + (lr < nrows ? lr : 0)) * P.r;
 #pragma unroll
@@ -175,7 +176,7 @@ __global__ __launch_bounds__(256) void predict_layers_kernel(const PhasedParams 
           for (int v = 0; v < VEC; ++v) acc += reg[e][c].get(v) * q1[c][v];
       }
       acc = wave_total(acc);
-      const int lr = wave * rpw + i + e;
+      const int lr = i * 4 + wave * R + e;
       if (lane == 0 && lr < nrows) s_sh[lr] = acc;
     }
   }
@@ -484,6 +485,7 @@ int gather_variant(const FfnProblem& p) {
 }
 
 int g_phased_rpb = 0, g_phased_npb = 0, g_phased_alt = 0;  // tuning overrides (0 = automatic)
+int g_phased_mask = 7;  // measurement aid: which of predict (1), gather (2), reduce / select (4) are launched
 
 template <typename WT, bool QB>
 hipError_t launch_predict(const PhasedParams& P, int cpl1, dim3 grid, hipStream_t st) {
@@ -516,6 +518,8 @@ hipError_t launch_gather_index(const PhasedParams& P, dim3 grid, hipStream_t st)
 }
 
 }  // namespace
+
+void phased_set_phases(int mask) { g_phased_mask = (mask & 7) ? (mask & 7) : 7; }
 
 void phased_set_tuning(int rpb, int npb, int alt) {
   g_phased_rpb = rpb;
@@ -591,11 +595,12 @@ hipError_t launch_ffn_phased(const FfnProblem& p0, const void* const* k1n, const
     P.NBC = (p0.d_ff + npb - 1) / npb;
 
     const dim3 ga(P.NBA, L);
-    if (p0.w_bf16) err = p0.q_bf16 ? launch_predict<bf16_t, true>(P, cpl1, ga, st) : launch_predict<bf16_t, false>(P, cpl1, ga, st);
+    if (!(g_phased_mask & 1)) err = hipSuccess;
+    else if (p0.w_bf16) err = p0.q_bf16 ? launch_predict<bf16_t, true>(P, cpl1, ga, st) : launch_predict<bf16_t, false>(P, cpl1, ga, st);
     else err = launch_predict<float, false>(P, cpl1, ga, st);
     if (err != hipSuccess) return err;
     const dim3 gc(P.NBC, L);
-    switch (gv) {
+    if (g_phased_mask & 2) switch (gv) {
       case 0: err = launch_gather_index<0>(P, gc, st); break;
       case 1: err = launch_gather_index<1>(P, gc, st); break;
       case 2: err = launch_gather_index<2>(P, gc, st); break;
@@ -606,6 +611,7 @@ hipError_t launch_ffn_phased(const FfnProblem& p0, const void* const* k1n, const
       default: err = hipErrorInvalidValue; break;
     }
     if (err != hipSuccess) return err;
+    if (!(g_phased_mask & 4)) continue;
     hipLaunchKernelGGL(reduce_layers_kernel, dim3((p0.d_model + 255) / 256, L), dim3(256), 0, st, P);
     if (P.count || P.idx || P.ucount || P.uidx)
       hipLaunchKernelGGL(select_layers_kernel, dim3(L), dim3(1024), 0, st, P);
