@@ -90,14 +90,15 @@ hipError_t run_fused(const spark_ffn_layer* layers, int32_t n_layers, const spar
       vn[l] = layers[base + l].vn;
     }
     spark::FfnProblem p = p0;
-    p.y = p0.y + (int64_t)base * p0.d_model;
-    if (p.theta) p.theta += base;
-    if (p.active_count) p.active_count += base;
-    if (p.active_idx) p.active_idx += (int64_t)base * p0.d_ff;
+    p.y = p0.y + (int64_t)base * p0.batch * p0.d_model;
+    if (p.theta) p.theta += (int64_t)base * p0.batch;
+    if (p.active_count) p.active_count += (int64_t)base * p0.batch;
+    if (p.active_idx) p.active_idx += (int64_t)base * p0.batch * p0.d_ff;
     if (p.union_count) p.union_count += base;
     if (p.union_idx) p.union_idx += (int64_t)base * p0.d_ff;
-    e = persistent ? spark::launch_ffn_fused(p, k1n, k2n, vn, n, ws.fused, st)
-                   : spark::launch_ffn_phased(p, k1n, k2n, vn, n, ws.fused, st);
+    if (p.batch >= 2) e = spark::launch_ffn_phased_batch(p, k1n, k2n, vn, n, ws.fused, st);
+    else e = persistent ? spark::launch_ffn_fused(p, k1n, k2n, vn, n, ws.fused, st)
+                        : spark::launch_ffn_phased(p, k1n, k2n, vn, n, ws.fused, st);
   }
   return e;
 }
@@ -183,7 +184,7 @@ spark_status spark_ffn_decode(const spark_ffn_layer* layer, const void* q, spark
                                            union_count, union_idx);
   const spark::FfnWorkspace ws = spark::carve_workspace(workspace, layer->d_model, layer->d_ff, batch);
   hipError_t e;
-  if (g_force_general == 0 && spark::phased_supported(p))
+  if (g_force_general == 0 && (spark::phased_supported(p) || spark::phased_batch_supported(p)))
     e = run_fused(layer, 1, p, ws, false, static_cast<hipStream_t>(hip_stream));
   else if (g_force_general == 2 && spark::fused_supported(p, 1))
     e = run_fused(layer, 1, p, ws, true, static_cast<hipStream_t>(hip_stream));
@@ -212,7 +213,7 @@ spark_status spark_ffn_decode_layers(const spark_ffn_layer* layers, int32_t n_la
   {
     const spark::FfnProblem p0 = make_problem(&layers[0], q, qdtype, batch, ldq, y, theta, active_count,
                                               active_idx, union_count, union_idx);
-    if (g_force_general == 0 && spark::phased_supported(p0)) {
+    if (g_force_general == 0 && (spark::phased_supported(p0) || spark::phased_batch_supported(p0))) {
       const hipError_t e = run_fused(layers, n_layers, p0, ws, false, static_cast<hipStream_t>(hip_stream));
       return e == hipSuccess ? SPARK_OK : SPARK_ERR_DEVICE;
     }

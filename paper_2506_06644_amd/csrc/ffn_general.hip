@@ -694,6 +694,12 @@ int pick_ksplit(int d_model) {
 
 }  // namespace
 
+// The region the single-launch, phased and batched phased paths share (one of them runs per call).
+static size_t fused_region_bytes(int d_model, int d_ff, int batch) {
+  if (batch >= 2) return phased_batch_scratch_bytes(d_model, d_ff, batch);
+  return std::max(fused_scratch_bytes(d_model, d_ff), phased_scratch_bytes(d_model, d_ff));
+}
+
 size_t ffn_workspace_bytes(int d_model, int d_ff, int batch) {
   const size_t B = (size_t)batch, F = (size_t)d_ff, D = (size_t)d_model;
   size_t t = 0;
@@ -704,7 +710,7 @@ size_t ffn_workspace_bytes(int d_model, int d_ff, int batch) {
   t += 256;                                            // ucount
   t += align_up(F * B * 4, 256);                       // uact
   t += align_up((size_t)pick_ksplit(d_model) * B * D * 4, 256);  // part
-  t += align_up(std::max(fused_scratch_bytes(d_model, d_ff), phased_scratch_bytes(d_model, d_ff)), 256);
+  t += align_up(fused_region_bytes(d_model, d_ff, batch), 256);
   return t;
 }
 
@@ -721,7 +727,7 @@ FfnWorkspace carve_workspace(void* base, int d_model, int d_ff, int batch) {
   ws.ksplit = pick_ksplit(d_model);
   ws.part = reinterpret_cast<float*>(p);     p += align_up((size_t)ws.ksplit * B * D * 4, 256);
   ws.fused = p;
-  ws.fused_bytes = std::max(fused_scratch_bytes(d_model, d_ff), phased_scratch_bytes(d_model, d_ff));
+  ws.fused_bytes = fused_region_bytes(d_model, d_ff, batch);
   return ws;
 }
 

@@ -583,8 +583,10 @@ hipError_t launch_ffn_phased(const FfnProblem& p0, const void* const* k1n, const
     rpb = max(16, min(kMaxRPB, rpb / 16 * 16));
     int npb = g_phased_npb;
     if (npb <= 0) {
-      npb = 256;
-      while (npb > 64 && (long long)L * ((p0.d_ff + npb - 1) / npb) < 768) npb /= 2;
+      // long per-wave runs of rows pipeline best: the largest block that still leaves about
+      // two workgroups for every compute unit
+      npb = 1024;
+      while (npb > 64 && (long long)L * ((p0.d_ff + npb - 1) / npb) < 600) npb -= 64;
     }
     npb = max(64, min(1024, npb / 64 * 64));
     while ((p0.d_ff + npb - 1) / npb > kMaxNBC) npb += 64;

@@ -1,0 +1,580 @@
+// Spark-FFN decode (Eq.2 of arXiv 2506.06644) for a batch of 2..64 tokens and a stack of
+// independent layers, phase by phase over the whole stack, on the matrix cores of gfx950
+// (bf16 weights and bf16 tokens; Appendix B's batching: every token has its own threshold and
+// mask, the union of the masks decides which weight rows are fetched).
+//
+//   predict   S[l][b][j] = K1n_l[j] . q_b[:r]: tiles of 16 neurons x all tokens,
+//             v_mfma_f32_16x16x32_bf16 with the k range split over the 8 waves of a workgroup;
+//             the token fragments stay in registers while the workgroup walks its tiles.
+//   select    one workgroup per (layer, token): mean and std of the row (two passes over
+//             registers), theta (Eq.11), the token's index list, and the token's mask OR-ed
+//             into the layer's union mask.
+//   k2        tiles of 16 union rows: G[m][b] = K2n[U[m]] . q_b[r:] (same MFMA scheme, rows
+//             found by rank in the union mask), u[m][b] = GELU(s_bj - theta_b) * G (0 where
+//             token b does not activate the row), stored token-major as three bf16 planes
+//             (u = p0 + p1 + p2 carries all 24 significant bits of the fp32 value, so the
+//             bf16 MFMA of the next phase loses nothing).
+//   v         y[b][c] += sum_m u[m][b] * Vn[U[m]][c]: the contraction runs over rows while Vn
+//             is contiguous along columns, so each wave stages its 32 rows x 64 columns
+//             through LDS and reads them back transposed (8 consecutive rows of one column
+//             per lane), then v_mfma_f32_16x16x32_bf16 with tokens as M and columns as N.
+//             Row slices give partial outputs.
+//   reduce    y = sum of the partial outputs in slice order.
+//
+// bf16 x bf16 products are exact in fp32 and all accumulation is fp32.  Nothing waits on
+// another workgroup inside a launch, and every sum has a fixed order.
+#include "spark_device.h"
+#include "spark_internal.h"
+
+namespace spark {
+
+namespace {
+
+typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
+
+constexpr int kRowWaves = 8;     // waves of a predict / k2 workgroup (k split)
+constexpr int kVPitch = 160;     // bytes between row positions of a staged V tile (conflict-free transposed reads)
+constexpr int kVSlabWaves = 4;   // waves of a v workgroup, 64 columns each
+constexpr int kPlanes = 3;       // bf16 planes of u: 3 x 8 significant bits carry an fp32 value
+constexpr int kMaxWords = 256;   // 64-bit union mask words per layer: d_ff <= 16384
+
+struct BatchParams {
+  const void* k1n[kBatchMaxLayers];
+  const void* k2n[kBatchMaxLayers];
+  const void* vn[kBatchMaxLayers];
+  const bf16_t* q;     // [B][ldq]
+  int64_t ldq;
+  float* y;            // [L][B][d_model]
+  float* theta;        // [L][B]        optional
+  int32_t* count;      // [L][B]        optional
+  int32_t* idx;        // [L][B][d_ff]  optional
+  int32_t* ucount;     // [L]           optional
+  int32_t* uidx;       // [L][d_ff]     optional
+  float* S;                    // [L][B][d_ff]  predictor scores
+  float* thetas;               // [L][B]
+  unsigned long long* umask;   // [L][kMaxWords]  union of the tokens' masks
+  int32_t* urow;               // [L][d_ff]       union rank -> neuron
+  int32_t* utotal;             // [L]             union size
+  uint16_t* up;                // [kPlanes][L][B][ldu]  bf16 planes of u (u = sum of the planes), by union rank
+  size_t plane;                // elements between planes
+  float* part;                 // [L][KS][B][d_model]
+  int32_t* status;
+  int n_layers, B, d_model, d_ff, r, gelu, ldu;
+  float z;
+  int TPW1;  // predict tiles per workgroup (even)
+  int TPW2;  // k2 tiles per workgroup (even, <= 32)
+  int KS;    // row slices of the v phase
+};
+
+__device__ __forceinline__ u32x4 ld16(const void* p) { return *reinterpret_cast<const u32x4*>(p); }
+__device__ __forceinline__ u32x4 ld16_stream(const void* p) {
+  return __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(p));
+}
+__device__ __forceinline__ f32x4 mfma_bf16(u32x4 a, u32x4 b, f32x4 c) {
+  return __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, a), __builtin_bit_cast(bf16x8_t, b), c, 0, 0, 0);
+}
+// k step (of 32) that wave `w` takes as its s-th: steps are dealt in pairs so that a wave
+// reads whole 128-byte lines of a row
+__device__ __forceinline__ int k_step(int s, int w) { return (s >> 1) * 16 + 2 * w + (s & 1); }
+
+// ---------------------------------------------------------------------------- rows x tokens
+// Shared by predict (MODE 0: rows are the neurons 16 * tile + i) and k2 (MODE 1: rows are the
+// union ranks, looked up in `rowidx`).  Returns through `emit(tile, item, value)` the reduced
+// D[row 4 * kg + e][token nb * 16 + ri] with item = nb * 4 + e, for the items this wave sums.
+template <int NB, int SPW, typename RowOf, typename Emit>
+__device__ __forceinline__ void rows_times_tokens(const bf16_t* __restrict__ w, int K, const bf16_t* __restrict__ q,
+                                                  int64_t ldq, int qoff, int B, int tile0, int ntiles,
+                                                  float (*red)[kRowWaves][NB * 4][kWave], RowOf row_of, Emit emit) {
+  const int lane = threadIdx.x & (kWave - 1);
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
+  const int ri = lane & 15, kg = lane >> 4;
+  const int nsteps = K / 32;
+  u32x4 qf[SPW][NB];
+#pragma unroll
+  for (int s = 0; s < SPW; ++s) {
+    const int ks = k_step(s, wave);
+#pragma unroll
+    for (int nb = 0; nb < NB; ++nb) {
+      const int b = nb * 16 + ri;
+      const bool ok = ks < nsteps && b < B;
+      qf[s][nb] = ld16(q + (int64_t)(b < B ? b : 0) * ldq + qoff + ((ks < nsteps ? ks : 0) * 4 + kg) * 8);
+      if (!ok) qf[s][nb] = u32x4{0u, 0u, 0u, 0u};
+    }
+  }
+  auto load_tile = [&](int t, u32x4(&a)[SPW]) {
+    const bf16_t* row = w + (int64_t)row_of(t, ri) * K;
+#pragma unroll
+    for (int s = 0; s < SPW; ++s) {
+      const int ks = k_step(s, wave);
+      a[s] = ld16_stream(row + ((ks < nsteps ? ks : 0) * 4 + kg) * 8);  // steps past K meet a zero token fragment
+    }
+  };
+  auto process = [&](int t, const u32x4(&a)[SPW], int buf) {
+    f32x4 acc[NB];
+#pragma unroll
+    for (int nb = 0; nb < NB; ++nb) acc[nb] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int s = 0; s < SPW; ++s)
+#pragma unroll
+      for (int nb = 0; nb < NB; ++nb) acc[nb] = mfma_bf16(a[s], qf[s][nb], acc[nb]);
+#pragma unroll
+    for (int nb = 0; nb < NB; ++nb)
+#pragma unroll
+      for (int e = 0; e < 4; ++e) red[buf][wave][nb * 4 + e][lane] = acc[nb][e];
+    // one barrier per tile: the buffers alternate, and a wave that writes buffer `buf` again
+    // two tiles later has passed the barrier of the tile in between, which every wave reaches
+    // only after it has finished reading `buf`
+    __syncthreads();
+    for (int item = wave; item < NB * 4; item += kRowWaves) {
+      float v = 0.f;
+#pragma unroll
+      for (int wv = 0; wv < kRowWaves; ++wv) v += red[buf][wv][item][lane];
+      emit(t, item, v);
+    }
+  };
+  u32x4 a0[SPW], a1[SPW];
+  load_tile(tile0, a0);
+  for (int i = 0; i < ntiles; i += 2) {  // ntiles is even; tiles past the end repeat the last valid rows
+    load_tile(tile0 + i + 1, a1);
+    process(tile0 + i, a0, 0);
+    load_tile(tile0 + i + 2, a0);
+    process(tile0 + i + 1, a1, 1);
+  }
+}
+
+// --------------------------------------------------------------------------------- predict
+template <int NB, int SPW>
+__global__ __launch_bounds__(kRowWaves * kWave) void predict_batch_kernel(const BatchParams P) {
+  extern __shared__ __align__(16) float red_raw[];
+  float(*red)[kRowWaves][NB * 4][kWave] = reinterpret_cast<float(*)[kRowWaves][NB * 4][kWave]>(red_raw);
+  const int lane = threadIdx.x & (kWave - 1);
+  const int ri = lane & 15, kg = lane >> 4;
+  const int l = blockIdx.y;
+  const int tiles_total = (P.d_ff + 15) / 16;
+  const int tile0 = blockIdx.x * P.TPW1;
+  if (blockIdx.x == 0) {
+    for (int i = threadIdx.x; i < kMaxWords; i += kRowWaves * kWave) P.umask[(size_t)l * kMaxWords + i] = 0ull;
+    if (l == 0 && threadIdx.x == 0) *P.status = 0;  // this path cannot abort
+  }
+  if (tile0 >= tiles_total) return;
+  float* S = P.S + (size_t)l * P.B * P.d_ff;
+  rows_times_tokens<NB, SPW>(
+      static_cast<const bf16_t*>(P.k1n[l]), P.r, P.q, P.ldq, 0, P.B, tile0, P.TPW1, red,
+      [&](int t, int i) { return min(t * 16 + i, P.d_ff - 1); },
+      [&](int t, int item, float v) {
+        const int b = (item >> 2) * 16 + ri, j = t * 16 + 4 * kg + (item & 3);
+        if (b < P.B && j < P.d_ff && t < tiles_total) S[(size_t)b * P.d_ff + j] = v;
+      });
+}
+
+// ---------------------------------------------------------------------------------- select
+// One workgroup per (token, layer); the row of scores sits in registers (<= 16 per thread).
+__global__ __launch_bounds__(1024) void select_batch_kernel(const BatchParams P) {
+  __shared__ float red[16];
+  __shared__ int wcount[16];
+  const int tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid / kWave;
+  const int b = blockIdx.x, l = blockIdx.y;
+  const float* row = P.S + ((size_t)l * P.B + b) * P.d_ff;
+  float v[16];
+  float sum = 0.f;
+#pragma unroll
+  for (int k = 0; k < 16; ++k) {
+    const int j = tid + 1024 * k;
+    v[k] = j < P.d_ff ? row[j] : 0.f;
+    sum += v[k];
+  }
+  const float mean = block_sum<1024>(sum, red) / (float)P.d_ff;
+  float sq = 0.f;
+#pragma unroll
+  for (int k = 0; k < 16; ++k) {
+    const float d = tid + 1024 * k < P.d_ff ? v[k] - mean : 0.f;
+    sq += d * d;
+  }
+  const float m2 = block_sum<1024>(sq, red);
+  const float theta = mean + sqrtf(m2 / (float)(P.d_ff - 1)) * P.z;
+  if (tid == 0) {
+    P.thetas[(size_t)l * P.B + b] = theta;
+    if (P.theta) P.theta[(size_t)l * P.B + b] = theta;
+  }
+  int running = 0;
+  const bool want_idx = P.idx || P.count;
+#pragma unroll
+  for (int k = 0; k < 16; ++k) {
+    if (1024 * k >= P.d_ff) break;  // uniform
+    const int j = tid + 1024 * k;
+    const bool on = j < P.d_ff && v[k] > theta;
+    const unsigned long long m = __ballot(on);
+    if (lane == 0 && m) atomicOr(&P.umask[(size_t)l * kMaxWords + (j >> 6)], m);
+    if (want_idx) {
+      __syncthreads();
+      if (lane == 0) wcount[wave] = __popcll(m);
+      __syncthreads();
+      int before = 0, total = 0;
+#pragma unroll
+      for (int w = 0; w < 16; ++w) {
+        before += w < wave ? wcount[w] : 0;
+        total += wcount[w];
+      }
+      if (on && P.idx) P.idx[((size_t)l * P.B + b) * P.d_ff + running + before + lanes_below(m)] = j;
+      running += total;
+    }
+  }
+  if (tid == 0 && P.count) P.count[(size_t)l * P.B + b] = running;
+}
+
+// -------------------------------------------------------------------------------------- k2
+template <int NB, int SPW>
+__global__ __launch_bounds__(kRowWaves * kWave) void k2_batch_kernel(const BatchParams P) {
+  extern __shared__ __align__(16) float red_raw[];
+  float(*red)[kRowWaves][NB * 4][kWave] = reinterpret_cast<float(*)[kRowWaves][NB * 4][kWave]>(red_raw);
+  __shared__ int wprefix[kMaxWords + 1];
+  __shared__ int rowidx[32 * 16 + 16];
+  const int tid = threadIdx.x, lane = tid & (kWave - 1);
+  const int wave = __builtin_amdgcn_readfirstlane(tid / kWave);
+  const int ri = lane & 15, kg = lane >> 4;
+  const int l = blockIdx.y;
+  const int nwords = (P.d_ff + 63) / 64;
+  const unsigned long long* um = P.umask + (size_t)l * kMaxWords;
+  if (wave == 0) {
+    int running = 0;
+    for (int base = 0; base < nwords; base += kWave) {
+      const int c = base + lane < nwords ? __popcll(um[base + lane]) : 0;
+      int inc = c;
+#pragma unroll
+      for (int o = 1; o < kWave; o <<= 1) {
+        const int t = __shfl_up(inc, o, kWave);
+        if (lane >= o) inc += t;
+      }
+      if (base + lane < nwords) wprefix[base + lane + 1] = running + inc;
+      running += __shfl(inc, kWave - 1, kWave);
+    }
+    if (lane == 0) wprefix[0] = 0;
+  }
+  __syncthreads();
+  const int m_total = wprefix[nwords];
+  const int tiles_total = (m_total + 15) / 16;
+  const int tile0 = blockIdx.x * P.TPW2;
+  if (blockIdx.x == 0 && tid == 0) {
+    P.utotal[l] = m_total;
+    if (P.ucount) P.ucount[l] = m_total;
+  }
+  if (tile0 >= tiles_total) return;
+  // neuron of every union rank this workgroup handles (ranks past the end repeat the last one)
+  for (int i = tid; i < P.TPW2 * 16 + 16; i += kRowWaves * kWave) {
+    const int rho = tile0 * 16 + i;
+    const int rc = min(rho, m_total - 1);
+    int lo = 0, hi = nwords - 1;  // last word with wprefix[word] <= rc
+    while (lo < hi) {
+      const int mid = (lo + hi + 1) >> 1;
+      if (wprefix[mid] <= rc) lo = mid;
+      else hi = mid - 1;
+    }
+    unsigned long long bits = um[lo];
+    for (int k = rc - wprefix[lo]; k > 0; --k) bits &= bits - 1;
+    const int j = lo * 64 + __builtin_ctzll(bits);
+    rowidx[i] = j;
+    if (rho < m_total && i < P.TPW2 * 16) {
+      P.urow[(size_t)l * P.d_ff + rho] = j;
+      if (P.uidx) P.uidx[(size_t)l * P.d_ff + rho] = j;
+    }
+  }
+  __syncthreads();
+  const int rank_end = (m_total + 31) / 32 * 32;  // the v phase reads ranks below this
+  const float* S = P.S + (size_t)l * P.B * P.d_ff;
+  float th[NB];
+#pragma unroll
+  for (int nb = 0; nb < NB; ++nb) th[nb] = P.thetas[(size_t)l * P.B + min(nb * 16 + ri, P.B - 1)];
+  uint16_t* up = P.up + (size_t)l * P.B * P.ldu;
+  rows_times_tokens<NB, SPW>(
+      static_cast<const bf16_t*>(P.k2n[l]), P.d_model - P.r, P.q, P.ldq, P.r, P.B, tile0, P.TPW2, red,
+      [&](int t, int i) { return rowidx[min((t - tile0) * 16 + i, P.TPW2 * 16 + 15)]; },
+      [&](int t, int item, float g) {
+        const int nb = item >> 2, b = nb * 16 + ri;
+        const int li = (t - tile0) * 16 + 4 * kg + (item & 3), rho = tile0 * 16 + li;
+        if (b >= P.B || rho >= rank_end) return;
+        float u = 0.f;
+        if (rho < m_total) {
+          const float a = S[(size_t)b * P.d_ff + rowidx[li]] - th[nb];
+          u = a > 0.f ? gelu(a, P.gelu) * g : 0.f;
+        }
+        float rest = u;
+#pragma unroll
+        for (int pl = 0; pl < kPlanes; ++pl) {
+          const uint16_t h = float_to_bf16_rne(rest);
+          up[pl * P.plane + (size_t)b * P.ldu + rho] = h;
+          rest -= bf16_bits_to_float(h);
+        }
+      });
+  // ranks between the last tile of the union and the end of the v phase's last 32-row group
+  // read as zero
+  if (tile0 + P.TPW2 >= tiles_total) {
+    const int from = (tile0 + P.TPW2) * 16, to = rank_end;
+    for (int i = tid; i < (to - from) * P.B; i += kRowWaves * kWave) {
+      const int b = i / (to - from), rho = from + i % (to - from);
+#pragma unroll
+      for (int pl = 0; pl < kPlanes; ++pl) up[pl * P.plane + (size_t)b * P.ldu + rho] = 0;
+    }
+  }
+}
+
+// --------------------------------------------------------------------------------------- v
+// Workgroup = 4 waves x 64 columns, one slice of the union's 32-row groups.  Per group a wave
+// loads 32 rows x 128 bytes (lane = row 8 t + lane / 8, 16-byte chunk lane % 8, t < 4), parks
+// them in its own LDS tile with row 8 t + j at position 4 j + t (pitch 160 bytes: the four
+// lane groups of a transposed read then hit disjoint banks), and reads back, per 16-column
+// tile, the 8 rows 8 kg + e of column ri as the B operand.  A operand: 8 consecutive ranks of
+// token ri from each bf16 plane of u.
+template <int NB>
+__global__ __launch_bounds__(kVSlabWaves * kWave) void v_batch_kernel(const BatchParams P) {
+  __shared__ __align__(16) unsigned char stage[kVSlabWaves][32 * kVPitch];
+  const int tid = threadIdx.x, lane = tid & (kWave - 1);
+  const int wave = __builtin_amdgcn_readfirstlane(tid / kWave);
+  const int ri = lane & 15, kg = lane >> 4;
+  const int l = blockIdx.z, ks = blockIdx.y;
+  const int col0 = (blockIdx.x * kVSlabWaves + wave) * 64;
+  if (col0 >= P.d_model) return;  // the staging tiles are private to a wave: no barriers below
+  const int m_total = P.utotal[l];
+  const int groups_total = (m_total + 31) / 32;
+  const int per = (groups_total + P.KS - 1) / P.KS;
+  const int g0 = ks * per, g1 = min(g0 + per, groups_total);
+  const bf16_t* vn = static_cast<const bf16_t*>(P.vn[l]);
+  const int32_t* urow = P.urow + (size_t)l * P.d_ff;
+  const uint16_t* up = P.up + (size_t)l * P.B * P.ldu;
+  unsigned char* mine = stage[wave];
+
+  f32x4 acc[4][NB];
+#pragma unroll
+  for (int ct = 0; ct < 4; ++ct)
+#pragma unroll
+    for (int nb = 0; nb < NB; ++nb) acc[ct][nb] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+  const int lr = lane >> 3, lc = lane & 7;
+  auto load_idx = [&](int g, int(&j)[4]) {
+#pragma unroll
+    for (int t = 0; t < 4; ++t) j[t] = urow[max(0, min(g * 32 + 8 * t + lr, m_total - 1))];
+  };
+  auto load_rows = [&](const int(&j)[4], u32x4(&v)[4]) {
+#pragma unroll
+    for (int t = 0; t < 4; ++t) v[t] = ld16_stream(vn + (int64_t)j[t] * P.d_model + col0 + lc * 8);
+  };
+  auto load_u = [&](int g, u32x4(&a)[NB][kPlanes]) {
+#pragma unroll
+    for (int nb = 0; nb < NB; ++nb) {
+      const int b = nb * 16 + ri;
+      const size_t off = (size_t)min(b, P.B - 1) * P.ldu + (size_t)g * 32 + 8 * kg;
+#pragma unroll
+      for (int pl = 0; pl < kPlanes; ++pl) {
+        a[nb][pl] = ld16(up + pl * P.plane + off);
+        if (b >= P.B) a[nb][pl] = u32x4{0u, 0u, 0u, 0u};
+      }
+    }
+  };
+  if (g0 < g1) {
+    int j0[4], j1[4];
+    u32x4 v0[4], v1[4], u0[NB][kPlanes], u1[NB][kPlanes];
+    load_idx(g0, j0);
+    load_idx(min(g0 + 1, g1 - 1), j1);
+    load_rows(j0, v0);
+    load_u(g0, u0);
+    for (int g = g0; g < g1; ++g) {
+      // row indices two groups ahead, rows and activations one group ahead
+      load_rows(j1, v1);
+      load_u(min(g + 1, g1 - 1), u1);
+      load_idx(min(g + 2, g1 - 1), j1);
+#pragma unroll
+      for (int t = 0; t < 4; ++t)
+        *reinterpret_cast<u32x4*>(mine + (4 * lr + t) * kVPitch + lc * 16) = v0[t];
+      asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+      __builtin_amdgcn_wave_barrier();
+#pragma unroll
+      for (int ct = 0; ct < 4; ++ct) {
+        u32x4 bv;
+#pragma unroll
+        for (int e = 0; e < 8; e += 2) {
+          const uint32_t x0 = *reinterpret_cast<const uint16_t*>(mine + (4 * e + kg) * kVPitch + (ct * 16 + ri) * 2);
+          const uint32_t x1 = *reinterpret_cast<const uint16_t*>(mine + (4 * (e + 1) + kg) * kVPitch + (ct * 16 + ri) * 2);
+          bv[e >> 1] = x0 | (x1 << 16);
+        }
+#pragma unroll
+        for (int nb = 0; nb < NB; ++nb) {
+#pragma unroll
+          for (int pl = kPlanes - 1; pl >= 0; --pl) acc[ct][nb] = mfma_bf16(u0[nb][pl], bv, acc[ct][nb]);
+        }
+      }
+      asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+      __builtin_amdgcn_wave_barrier();
+#pragma unroll
+      for (int t = 0; t < 4; ++t) v0[t] = v1[t];
+#pragma unroll
+      for (int nb = 0; nb < NB; ++nb) {
+#pragma unroll
+        for (int pl = 0; pl < kPlanes; ++pl) u0[nb][pl] = u1[nb][pl];
+      }
+    }
+  }
+  // D[token 4 kg + e][column ri] of every (column tile, token block)
+  float* dst = P.part + ((size_t)l * P.KS + ks) * P.B * P.d_model;
+#pragma unroll
+  for (int ct = 0; ct < 4; ++ct)
+#pragma unroll
+    for (int nb = 0; nb < NB; ++nb)
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        const int b = nb * 16 + 4 * kg + e;
+        if (b < P.B) dst[(size_t)b * P.d_model + col0 + ct * 16 + ri] = acc[ct][nb][e];
+      }
+}
+
+// ---------------------------------------------------------------------------------- reduce
+__global__ __launch_bounds__(256) void reduce_batch_kernel(const BatchParams P) {
+  const int l = blockIdx.y;
+  const size_t n = (size_t)P.B * P.d_model;
+  const size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
+  if (i >= n) return;
+  const float* p = P.part + (size_t)l * P.KS * n + i;
+  float acc = 0.f;
+  for (int ks = 0; ks < P.KS; ++ks) acc += p[(size_t)ks * n];
+  P.y[(size_t)l * n + i] = acc;
+}
+
+size_t align256(size_t v) { return (v + 255) / 256 * 256; }
+
+int v_slabs(int d_model) { return (d_model + 64 * kVSlabWaves - 1) / (64 * kVSlabWaves); }
+int part_rows(int d_model) { return kBatchMaxLayers + (768 + v_slabs(d_model) - 1) / v_slabs(d_model); }
+
+struct BatchLayout {
+  size_t S, thetas, umask, urow, utotal, up, plane, part, total;
+  int ldu;
+};
+
+BatchLayout batch_layout(int d_model, int d_ff, int B) {
+  BatchLayout s;
+  const size_t L = kBatchMaxLayers;
+  s.ldu = (d_ff + 64 + 7) / 8 * 8;
+  size_t o = 256;  // the first word is the status word spark_ffn_check reads
+  s.S = o;      o += align256(L * B * (size_t)d_ff * 4);
+  s.thetas = o; o += align256(L * B * 4);
+  s.umask = o;  o += align256(L * kMaxWords * 8);
+  s.urow = o;   o += align256(L * (size_t)d_ff * 4);
+  s.utotal = o; o += align256(L * 4);
+  s.plane = align256(L * B * (size_t)s.ldu * 2) / 2;
+  s.up = o;     o += kPlanes * s.plane * 2;
+  s.part = o;   o += align256((size_t)part_rows(d_model) * B * (size_t)d_model * 4);
+  s.total = o;
+  return s;
+}
+
+int spw_for(int K) { return 2 * ((K / 32 + 15) / 16); }
+
+template <int NB, int SPW>
+void launch_rows(const BatchParams& P, int mode, dim3 grid, hipStream_t st) {
+  const size_t dyn = (size_t)2 * kRowWaves * NB * 4 * kWave * sizeof(float);
+  const void* kern = mode == 0 ? reinterpret_cast<const void*>(predict_batch_kernel<NB, SPW>)
+                               : reinterpret_cast<const void*>(k2_batch_kernel<NB, SPW>);
+  if (hipFuncSetAttribute(kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)dyn) != hipSuccess) return;
+  if (mode == 0) hipLaunchKernelGGL((predict_batch_kernel<NB, SPW>), grid, dim3(kRowWaves * kWave), dyn, st, P);
+  else hipLaunchKernelGGL((k2_batch_kernel<NB, SPW>), grid, dim3(kRowWaves * kWave), dyn, st, P);
+}
+template <int NB>
+hipError_t launch_rows_spw(const BatchParams& P, int mode, int spw, dim3 grid, hipStream_t st) {
+  switch (spw) {
+    case 2: launch_rows<NB, 2>(P, mode, grid, st); break;
+    case 4: launch_rows<NB, 4>(P, mode, grid, st); break;
+    case 6: launch_rows<NB, 6>(P, mode, grid, st); break;
+    case 8: launch_rows<NB, 8>(P, mode, grid, st); break;
+    default: return hipErrorInvalidValue;
+  }
+  return hipGetLastError();
+}
+hipError_t launch_rows_nb(const BatchParams& P, int mode, int nb, int spw, dim3 grid, hipStream_t st) {
+  switch (nb) {
+    case 1: return launch_rows_spw<1>(P, mode, spw, grid, st);
+    case 2: return launch_rows_spw<2>(P, mode, spw, grid, st);
+    case 3: return launch_rows_spw<3>(P, mode, spw, grid, st);
+    case 4: return launch_rows_spw<4>(P, mode, spw, grid, st);
+    default: return hipErrorInvalidValue;
+  }
+}
+
+}  // namespace
+
+size_t phased_batch_scratch_bytes(int d_model, int d_ff, int batch) { return batch_layout(d_model, d_ff, batch).total; }
+
+bool phased_batch_supported(const FfnProblem& p) {
+  const int r2 = p.d_model - p.r;
+  return p.batch >= 2 && p.batch <= 64 && p.w_bf16 && p.q_bf16 && p.r % 32 == 0 && r2 % 32 == 0 &&
+         p.d_model % 64 == 0 && p.d_ff <= 64 * kMaxWords && p.d_ff >= 16 && spw_for(p.r) <= 8 && spw_for(r2) <= 8;
+}
+
+hipError_t launch_ffn_phased_batch(const FfnProblem& p0, const void* const* k1n, const void* const* k2n,
+                                   const void* const* vn, int n_layers, void* scratch, hipStream_t st) {
+  const BatchLayout lay = batch_layout(p0.d_model, p0.d_ff, p0.batch);
+  char* s = static_cast<char*>(scratch);
+  const int B = p0.batch, nb = (B + 15) / 16;
+  hipError_t err = hipSuccess;
+  for (int base = 0; base < n_layers && err == hipSuccess; base += kBatchMaxLayers) {
+    const int L = min(kBatchMaxLayers, n_layers - base);
+    BatchParams P;
+    for (int l = 0; l < kBatchMaxLayers; ++l) {
+      P.k1n[l] = l < L ? k1n[base + l] : nullptr;
+      P.k2n[l] = l < L ? k2n[base + l] : nullptr;
+      P.vn[l] = l < L ? vn[base + l] : nullptr;
+    }
+    P.q = static_cast<const bf16_t*>(p0.q);
+    P.ldq = p0.ldq;
+    P.y = p0.y + (size_t)base * B * p0.d_model;
+    P.theta = p0.theta ? p0.theta + (size_t)base * B : nullptr;
+    P.count = p0.active_count ? p0.active_count + (size_t)base * B : nullptr;
+    P.idx = p0.active_idx ? p0.active_idx + (size_t)base * B * p0.d_ff : nullptr;
+    P.ucount = p0.union_count ? p0.union_count + base : nullptr;
+    P.uidx = p0.union_idx ? p0.union_idx + (size_t)base * p0.d_ff : nullptr;
+    P.S = reinterpret_cast<float*>(s + lay.S);
+    P.thetas = reinterpret_cast<float*>(s + lay.thetas);
+    P.umask = reinterpret_cast<unsigned long long*>(s + lay.umask);
+    P.urow = reinterpret_cast<int32_t*>(s + lay.urow);
+    P.utotal = reinterpret_cast<int32_t*>(s + lay.utotal);
+    P.up = reinterpret_cast<uint16_t*>(s + lay.up);
+    P.plane = lay.plane;
+    P.part = reinterpret_cast<float*>(s + lay.part);
+    P.status = reinterpret_cast<int32_t*>(s);
+    P.n_layers = L;
+    P.B = B;
+    P.d_model = p0.d_model;
+    P.d_ff = p0.d_ff;
+    P.r = p0.r;
+    P.gelu = p0.gelu;
+    P.ldu = lay.ldu;
+    P.z = p0.z;
+    const int tiles = (p0.d_ff + 15) / 16;
+    int tpw1 = 16;
+    while (tpw1 > 2 && (long long)L * ((tiles + tpw1 - 1) / tpw1) < 768) tpw1 /= 2;
+    int tpw2 = 8;
+    while (tpw2 > 2 && (long long)L * ((tiles + tpw2 - 1) / tpw2) < 1024) tpw2 /= 2;
+    P.TPW1 = tpw1;
+    P.TPW2 = tpw2;
+    const int slabs = v_slabs(p0.d_model);
+    int ksl = (768 + slabs * L - 1) / (slabs * L);
+    ksl = max(1, min(16, ksl));
+    while (L * ksl > part_rows(p0.d_model)) --ksl;
+    P.KS = ksl;
+
+    err = launch_rows_nb(P, 0, nb, spw_for(p0.r), dim3((tiles + tpw1 - 1) / tpw1, L), st);
+    if (err != hipSuccess) return err;
+    hipLaunchKernelGGL(select_batch_kernel, dim3(B, L), dim3(1024), 0, st, P);
+    err = launch_rows_nb(P, 1, nb, spw_for(p0.d_model - p0.r), dim3((tiles + tpw2 - 1) / tpw2, L), st);
+    if (err != hipSuccess) return err;
+    const dim3 gv(slabs, ksl, L);
+    switch (nb) {
+      case 1: hipLaunchKernelGGL((v_batch_kernel<1>), gv, dim3(kVSlabWaves * kWave), 0, st, P); break;
+      case 2: hipLaunchKernelGGL((v_batch_kernel<2>), gv, dim3(kVSlabWaves * kWave), 0, st, P); break;
+      case 3: hipLaunchKernelGGL((v_batch_kernel<3>), gv, dim3(kVSlabWaves * kWave), 0, st, P); break;
+      default: hipLaunchKernelGGL((v_batch_kernel<4>), gv, dim3(kVSlabWaves * kWave), 0, st, P); break;
+    }
+    const size_t n = (size_t)B * p0.d_model;
+    hipLaunchKernelGGL(reduce_batch_kernel, dim3((unsigned)((n + 255) / 256), L), dim3(256), 0, st, P);
+    err = hipGetLastError();
+  }
+  return err;
+}
+
+}  // namespace spark

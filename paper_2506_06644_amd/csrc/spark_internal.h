@@ -73,4 +73,12 @@ void phased_set_tuning(int rows_per_predict_block, int neurons_per_gather_block,
 hipError_t launch_ffn_phased(const FfnProblem& p0, const void* const* k1n, const void* const* k2n,
                              const void* const* vn, int n_layers, void* scratch, hipStream_t st);
 
+// Phase-by-phase path for batches of 2..64 tokens on the matrix cores (bf16 weights and
+// tokens), up to kBatchMaxLayers layers per set of launches.
+constexpr int kBatchMaxLayers = 32;
+size_t phased_batch_scratch_bytes(int d_model, int d_ff, int batch);
+bool phased_batch_supported(const FfnProblem& p);
+hipError_t launch_ffn_phased_batch(const FfnProblem& p0, const void* const* k1n, const void* const* k2n,
+                                   const void* const* vn, int n_layers, void* scratch, hipStream_t st);
+
 }  // namespace spark
