@@ -15,7 +15,7 @@ HIPCC_FLAGS = [
     "-O3", "-std=c++17", "--offload-arch=gfx950", "-fPIC", "-shared",
     # packed fp32 VALU forms are kept off for every device function of this library
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
-    "-Wall", "-Wno-unused-function",
+    "-Wall", "-Wno-unused-function", *os.environ.get("SPARK_EXTRA_FLAGS", "").split(),
 ]
 
 

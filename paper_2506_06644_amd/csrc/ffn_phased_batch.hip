@@ -34,7 +34,6 @@ typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
 
 constexpr int kRowWaves = 8;     // waves of a predict / k2 workgroup (k split)
 constexpr int kVPitch = 160;     // bytes between row positions of a staged V tile (conflict-free transposed reads)
-constexpr int kVSlabWaves = 4;   // waves of a v workgroup, 64 columns each
 constexpr int kPlanes = 3;       // bf16 planes of u: 3 x 8 significant bits carry an fp32 value
 constexpr int kMaxWords = 256;   // 64-bit union mask words per layer: d_ff <= 16384
 
@@ -73,18 +72,38 @@ __device__ __forceinline__ u32x4 ld16_stream(const void* p) {
 __device__ __forceinline__ f32x4 mfma_bf16(u32x4 a, u32x4 b, f32x4 c) {
   return __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, a), __builtin_bit_cast(bf16x8_t, b), c, 0, 0, 0);
 }
+// Workgroup barrier that orders LDS traffic only.  __syncthreads() also fences global memory,
+// i.e. waits for every outstanding global load of the wave, which would drain the very
+// prefetch that is meant to stay in flight across the barrier.
+__device__ __forceinline__ void lds_barrier() {
+  asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+  __builtin_amdgcn_s_barrier();
+  asm volatile("" ::: "memory");
+}
 // k step (of 32) that wave `w` takes as its s-th: steps are dealt in pairs so that a wave
 // reads whole 128-byte lines of a row
-__device__ __forceinline__ int k_step(int s, int w) { return (s >> 1) * 16 + 2 * w + (s & 1); }
+template <int SPW> __device__ __forceinline__ int k_step_t(int s, int w) { return (s >> 1) * 16 + 2 * w + (s & 1); }
 
 // ---------------------------------------------------------------------------- rows x tokens
 // Shared by predict (MODE 0: rows are the neurons 16 * tile + i) and k2 (MODE 1: rows are the
-// union ranks, looked up in `rowidx`).  Returns through `emit(tile, item, value)` the reduced
-// D[row 4 * kg + e][token nb * 16 + ri] with item = nb * 4 + e, for the items this wave sums.
-template <int NB, int SPW, typename RowOf, typename Emit>
-__device__ __forceinline__ void rows_times_tokens(const bf16_t* __restrict__ w, int K, const bf16_t* __restrict__ q,
-                                                  int64_t ldq, int qoff, int B, int tile0, int ntiles,
-                                                  float (*red)[kRowWaves][NB * 4][kWave], RowOf row_of, Emit emit) {
+// union ranks, looked up in `rowidx`).  Returns through `emit(tile, item, value, side)` the
+// reduced D[row 4 * kg + e][token nb * 16 + ri] with item = nb * 4 + e, for the items this
+// wave sums; `side` is what `pre(tile, item)` fetched for that item together with the tile's
+// rows (so that no load issued after the prefetch of the next tile has to be waited for:
+// loads return in order).
+//
+// DEPTH tiles are kept in flight per wave.  A tile past `tile_end` is requested through a
+// buffer descriptor without records: the loads are issued all the same (their number in
+// flight stays a compile-time constant, so the waits can be exact) but touch no memory.
+template <int NB>
+constexpr int tile_depth() { return NB <= 2 ? 4 : 2; }
+template <int NB, int SPW, typename RowOf, typename Pre, typename Emit>
+__device__ __forceinline__ void rows_times_tokens(const bf16_t* __restrict__ w, uint32_t w_bytes, int K,
+                                                  const bf16_t* __restrict__ q, int64_t ldq, int qoff, int B,
+                                                  int tile0, int ntiles, int tile_end,
+                                                  float (*red)[kRowWaves][NB * 4][kWave], RowOf row_of, Pre pre, Emit emit) {
+  constexpr int IPW = (NB * 4 + kRowWaves - 1) / kRowWaves;  // items a wave sums per tile
+  constexpr int DEPTH = tile_depth<NB>();
   const int lane = threadIdx.x & (kWave - 1);
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
   const int ri = lane & 15, kg = lane >> 4;
@@ -92,7 +111,7 @@ __device__ __forceinline__ void rows_times_tokens(const bf16_t* __restrict__ w, 
   u32x4 qf[SPW][NB];
 #pragma unroll
   for (int s = 0; s < SPW; ++s) {
-    const int ks = k_step(s, wave);
+    const int ks = k_step_t<SPW>(s, wave);
 #pragma unroll
     for (int nb = 0; nb < NB; ++nb) {
       const int b = nb * 16 + ri;
@@ -101,15 +120,19 @@ __device__ __forceinline__ void rows_times_tokens(const bf16_t* __restrict__ w, 
       if (!ok) qf[s][nb] = u32x4{0u, 0u, 0u, 0u};
     }
   }
-  auto load_tile = [&](int t, u32x4(&a)[SPW]) {
-    const bf16_t* row = w + (int64_t)row_of(t, ri) * K;
+  auto load_tile = [&](int t, u32x4(&a)[SPW], float(&side)[IPW]) {
+    const __amdgpu_buffer_rsrc_t rs =
+        __builtin_amdgcn_make_buffer_rsrc(const_cast<bf16_t*>(w), 0, t < tile_end ? (int)w_bytes : 0, 0x00020000);
+#pragma unroll
+    for (int i = 0; i < IPW; ++i) side[i] = wave + kRowWaves * i < NB * 4 ? pre(t, wave + kRowWaves * i) : 0.f;
+    const uint32_t row_off = (uint32_t)row_of(t, ri) * (uint32_t)K * 2u;
 #pragma unroll
     for (int s = 0; s < SPW; ++s) {
-      const int ks = k_step(s, wave);
-      a[s] = ld16_stream(row + ((ks < nsteps ? ks : 0) * 4 + kg) * 8);  // steps past K meet a zero token fragment
+      const int ks = k_step_t<SPW>(s, wave);  // steps past K meet a zero token fragment
+      a[s] = __builtin_amdgcn_raw_buffer_load_b128(rs, (int)(row_off + (uint32_t)((ks < nsteps ? ks : 0) * 4 + kg) * 16u), 0, 0);
     }
   };
-  auto process = [&](int t, const u32x4(&a)[SPW], int buf) {
+  auto process = [&](int t, const u32x4(&a)[SPW], const float(&side)[IPW], int buf) {
     f32x4 acc[NB];
 #pragma unroll
     for (int nb = 0; nb < NB; ++nb) acc[nb] = f32x4{0.f, 0.f, 0.f, 0.f};
@@ -124,21 +147,28 @@ __device__ __forceinline__ void rows_times_tokens(const bf16_t* __restrict__ w, 
     // one barrier per tile: the buffers alternate, and a wave that writes buffer `buf` again
     // two tiles later has passed the barrier of the tile in between, which every wave reaches
     // only after it has finished reading `buf`
-    __syncthreads();
-    for (int item = wave; item < NB * 4; item += kRowWaves) {
-      float v = 0.f;
+    lds_barrier();
 #pragma unroll
-      for (int wv = 0; wv < kRowWaves; ++wv) v += red[buf][wv][item][lane];
-      emit(t, item, v);
+    for (int i = 0; i < IPW; ++i) {
+      const int item = wave + kRowWaves * i;
+      if (item < NB * 4) {
+        float v = 0.f;
+#pragma unroll
+        for (int wv = 0; wv < kRowWaves; ++wv) v += red[buf][wv][item][lane];
+        emit(t, item, v, side[i]);
+      }
     }
   };
-  u32x4 a0[SPW], a1[SPW];
-  load_tile(tile0, a0);
-  for (int i = 0; i < ntiles; i += 2) {  // ntiles is even; tiles past the end repeat the last valid rows
-    load_tile(tile0 + i + 1, a1);
-    process(tile0 + i, a0, 0);
-    load_tile(tile0 + i + 2, a0);
-    process(tile0 + i + 1, a1, 1);
+  u32x4 a[DEPTH][SPW];
+  float sd[DEPTH][IPW];
+#pragma unroll
+  for (int d = 0; d < DEPTH; ++d) load_tile(tile0 + d, a[d], sd[d]);
+  for (int i = 0; i < ntiles; i += DEPTH) {  // ntiles is a multiple of DEPTH (an even number)
+#pragma unroll
+    for (int d = 0; d < DEPTH; ++d) {
+      process(tile0 + i + d, a[d], sd[d], d & 1);
+      load_tile(tile0 + i + d + DEPTH, a[d], sd[d]);
+    }
   }
 }
 
@@ -159,9 +189,10 @@ __global__ __launch_bounds__(kRowWaves * kWave) void predict_batch_kernel(const 
   if (tile0 >= tiles_total) return;
   float* S = P.S + (size_t)l * P.B * P.d_ff;
   rows_times_tokens<NB, SPW>(
-      static_cast<const bf16_t*>(P.k1n[l]), P.r, P.q, P.ldq, 0, P.B, tile0, P.TPW1, red,
-      [&](int t, int i) { return min(t * 16 + i, P.d_ff - 1); },
-      [&](int t, int item, float v) {
+      static_cast<const bf16_t*>(P.k1n[l]), (uint32_t)P.d_ff * (uint32_t)P.r * 2u, P.r, P.q, P.ldq, 0, P.B, tile0, P.TPW1,
+      min(tile0 + P.TPW1, tiles_total), red,
+      [&](int t, int i) { return min(t * 16 + i, P.d_ff - 1); }, [](int, int) { return 0.f; },
+      [&](int t, int item, float v, float) {
         const int b = (item >> 2) * 16 + ri, j = t * 16 + 4 * kg + (item & 3);
         if (b < P.B && j < P.d_ff && t < tiles_total) S[(size_t)b * P.d_ff + j] = v;
       });
@@ -286,15 +317,20 @@ __global__ __launch_bounds__(kRowWaves * kWave) void k2_batch_kernel(const Batch
   for (int nb = 0; nb < NB; ++nb) th[nb] = P.thetas[(size_t)l * P.B + min(nb * 16 + ri, P.B - 1)];
   uint16_t* up = P.up + (size_t)l * P.B * P.ldu;
   rows_times_tokens<NB, SPW>(
-      static_cast<const bf16_t*>(P.k2n[l]), P.d_model - P.r, P.q, P.ldq, P.r, P.B, tile0, P.TPW2, red,
+      static_cast<const bf16_t*>(P.k2n[l]), (uint32_t)P.d_ff * (uint32_t)(P.d_model - P.r) * 2u, P.d_model - P.r, P.q, P.ldq,
+      P.r, P.B, tile0, P.TPW2, min(tile0 + P.TPW2, tiles_total), red,
       [&](int t, int i) { return rowidx[min((t - tile0) * 16 + i, P.TPW2 * 16 + 15)]; },
-      [&](int t, int item, float g) {
+      [&](int t, int item) {  // the score the item's (row, token) pair will need
+        const int b = min((item >> 2) * 16 + ri, P.B - 1);
+        return S[(size_t)b * P.d_ff + rowidx[min((t - tile0) * 16 + 4 * kg + (item & 3), P.TPW2 * 16 + 15)]];
+      },
+      [&](int t, int item, float g, float score) {
         const int nb = item >> 2, b = nb * 16 + ri;
         const int li = (t - tile0) * 16 + 4 * kg + (item & 3), rho = tile0 * 16 + li;
         if (b >= P.B || rho >= rank_end) return;
         float u = 0.f;
         if (rho < m_total) {
-          const float a = S[(size_t)b * P.d_ff + rowidx[li]] - th[nb];
+          const float a = score - th[nb];
           u = a > 0.f ? gelu(a, P.gelu) * g : 0.f;
         }
         float rest = u;
@@ -318,21 +354,32 @@ __global__ __launch_bounds__(kRowWaves * kWave) void k2_batch_kernel(const Batch
 }
 
 // --------------------------------------------------------------------------------------- v
-// Workgroup = 4 waves x 64 columns, one slice of the union's 32-row groups.  Per group a wave
-// loads 32 rows x 128 bytes (lane = row 8 t + lane / 8, 16-byte chunk lane % 8, t < 4), parks
-// them in its own LDS tile with row 8 t + j at position 4 j + t (pitch 160 bytes: the four
-// lane groups of a transposed read then hit disjoint banks), and reads back, per 16-column
-// tile, the 8 rows 8 kg + e of column ri as the B operand.  A operand: 8 consecutive ranks of
-// token ri from each bf16 plane of u.
+// Workgroup = NWV waves (4..8) x 64 columns, one slice of the union's 32-row groups.  Per
+// group a wave loads 32 rows x 128 bytes (lane = row 8 t + lane / 8, 16-byte chunk lane % 8,
+// t < 4), parks them in its own LDS tile with row 8 t + j at position 4 j + t (pitch 160 bytes:
+// the four lane groups of a transposed read then hit disjoint banks), and reads back, per
+// 16-column tile, the 8 rows 8 kg + e of column ri as the B operand.  The A operands (8
+// consecutive ranks of token ri from each bf16 plane of u) are the same for every wave: the
+// workgroup fetches them once per group into LDS, already in lane order.  One barrier per
+// group; the next group's rows and activations are in flight during the MFMAs.
+constexpr int kVMinWaves = 4, kVMaxWaves = 8;
 template <int NB>
-__global__ __launch_bounds__(kVSlabWaves * kWave) void v_batch_kernel(const BatchParams P) {
-  __shared__ __align__(16) unsigned char stage[kVSlabWaves][32 * kVPitch];
-  const int tid = threadIdx.x, lane = tid & (kWave - 1);
+__global__ __launch_bounds__(kVMaxWaves * kWave, (NB >= 3 ? 3 : 4)) void v_batch_kernel(const BatchParams P) {
+  constexpr int UCH = kPlanes * NB * kWave;                            // 16-byte chunks of u per group
+  constexpr int UPT = (UCH + kVMinWaves * kWave - 1) / (kVMinWaves * kWave);  // most chunks per thread
+  extern __shared__ __align__(16) unsigned char lds[];
+  const int tid = threadIdx.x, lane = tid & (kWave - 1), nthreads = blockDim.x;
   const int wave = __builtin_amdgcn_readfirstlane(tid / kWave);
+  const int nwv = nthreads / kWave;
+  unsigned char* mine = lds + (size_t)wave * 32 * kVPitch;
+  u32x4* ush = reinterpret_cast<u32x4*>(lds + (size_t)nwv * 32 * kVPitch);  // [2][UCH]
   const int ri = lane & 15, kg = lane >> 4;
   const int l = blockIdx.z, ks = blockIdx.y;
-  const int col0 = (blockIdx.x * kVSlabWaves + wave) * 64;
-  if (col0 >= P.d_model) return;  // the staging tiles are private to a wave: no barriers below
+  const int col_own = (blockIdx.x * nwv + wave) * 64;
+  // a wave past the last column still helps with u and the barriers; its row loads go to the
+  // last strip (unconditional loads keep the number in flight a compile-time constant)
+  const bool active = col_own < P.d_model;
+  const int col0 = active ? col_own : P.d_model - 64;
   const int m_total = P.utotal[l];
   const int groups_total = (m_total + 31) / 32;
   const int per = (groups_total + P.KS - 1) / P.KS;
@@ -340,7 +387,6 @@ __global__ __launch_bounds__(kVSlabWaves * kWave) void v_batch_kernel(const Batc
   const bf16_t* vn = static_cast<const bf16_t*>(P.vn[l]);
   const int32_t* urow = P.urow + (size_t)l * P.d_ff;
   const uint16_t* up = P.up + (size_t)l * P.B * P.ldu;
-  unsigned char* mine = stage[wave];
 
   f32x4 acc[4][NB];
 #pragma unroll
@@ -349,69 +395,82 @@ __global__ __launch_bounds__(kVSlabWaves * kWave) void v_batch_kernel(const Batc
     for (int nb = 0; nb < NB; ++nb) acc[ct][nb] = f32x4{0.f, 0.f, 0.f, 0.f};
 
   const int lr = lane >> 3, lc = lane & 7;
-  auto load_idx = [&](int g, int(&j)[4]) {
+  // neuron of rank 32 g + lane % 32 (ranks past the end repeat the last neuron; their u is 0)
+  auto load_idx = [&](int g) { return urow[max(0, min(g * 32 + (lane & 31), m_total - 1))]; };
+  auto load_rows = [&](int jn, u32x4(&v)[4]) {
 #pragma unroll
-    for (int t = 0; t < 4; ++t) j[t] = urow[max(0, min(g * 32 + 8 * t + lr, m_total - 1))];
+    for (int t = 0; t < 4; ++t) {
+      const int j = __shfl(jn, 8 * t + lr, kWave);
+      v[t] = ld16_stream(vn + (int64_t)j * P.d_model + col0 + lc * 8);
+    }
   };
-  auto load_rows = [&](const int(&j)[4], u32x4(&v)[4]) {
+  auto load_u = [&](int g, u32x4(&a)[UPT]) {
 #pragma unroll
-    for (int t = 0; t < 4; ++t) v[t] = ld16_stream(vn + (int64_t)j[t] * P.d_model + col0 + lc * 8);
-  };
-  auto load_u = [&](int g, u32x4(&a)[NB][kPlanes]) {
-#pragma unroll
-    for (int nb = 0; nb < NB; ++nb) {
-      const int b = nb * 16 + ri;
-      const size_t off = (size_t)min(b, P.B - 1) * P.ldu + (size_t)g * 32 + 8 * kg;
-#pragma unroll
-      for (int pl = 0; pl < kPlanes; ++pl) {
-        a[nb][pl] = ld16(up + pl * P.plane + off);
-        if (b >= P.B) a[nb][pl] = u32x4{0u, 0u, 0u, 0u};
+    for (int i = 0; i < UPT; ++i) {
+      const int c = tid + i * nthreads;
+      if (c < UCH) {
+        const int cl = c & (kWave - 1), nb = (c >> 6) % NB, pl = (c >> 6) / NB;
+        const int b = nb * 16 + (cl & 15);
+        // tokens past the batch re-read the last token; they are zeroed when the chunk is parked
+        // in LDS (a select here would have to wait for the load, and with it for every load
+        // issued before it)
+        a[i] = ld16(up + pl * P.plane + (size_t)min(b, P.B - 1) * P.ldu + (size_t)g * 32 + 8 * (cl >> 4));
       }
     }
   };
+  bool u_pad[UPT];
+#pragma unroll
+  for (int i = 0; i < UPT; ++i) {
+    const int c = tid + i * nthreads;
+    u_pad[i] = ((c >> 6) % NB) * 16 + (c & 15) >= P.B;
+  }
   if (g0 < g1) {
-    int j0[4], j1[4];
-    u32x4 v0[4], v1[4], u0[NB][kPlanes], u1[NB][kPlanes];
-    load_idx(g0, j0);
-    load_idx(min(g0 + 1, g1 - 1), j1);
-    load_rows(j0, v0);
-    load_u(g0, u0);
+    u32x4 v0[4], ur[UPT];
+    int jn = load_idx(g0);
+    load_rows(jn, v0);
+    load_u(g0, ur);
+    jn = load_idx(min(g0 + 1, g1 - 1));
     for (int g = g0; g < g1; ++g) {
-      // row indices two groups ahead, rows and activations one group ahead
-      load_rows(j1, v1);
-      load_u(min(g + 1, g1 - 1), u1);
-      load_idx(min(g + 2, g1 - 1), j1);
+      u32x4* ub = ush + ((g - g0) & 1) * UCH;
+      if (active) {
 #pragma unroll
-      for (int t = 0; t < 4; ++t)
-        *reinterpret_cast<u32x4*>(mine + (4 * lr + t) * kVPitch + lc * 16) = v0[t];
-      asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
-      __builtin_amdgcn_wave_barrier();
-#pragma unroll
-      for (int ct = 0; ct < 4; ++ct) {
-        u32x4 bv;
-#pragma unroll
-        for (int e = 0; e < 8; e += 2) {
-          const uint32_t x0 = *reinterpret_cast<const uint16_t*>(mine + (4 * e + kg) * kVPitch + (ct * 16 + ri) * 2);
-          const uint32_t x1 = *reinterpret_cast<const uint16_t*>(mine + (4 * (e + 1) + kg) * kVPitch + (ct * 16 + ri) * 2);
-          bv[e >> 1] = x0 | (x1 << 16);
-        }
-#pragma unroll
-        for (int nb = 0; nb < NB; ++nb) {
-#pragma unroll
-          for (int pl = kPlanes - 1; pl >= 0; --pl) acc[ct][nb] = mfma_bf16(u0[nb][pl], bv, acc[ct][nb]);
-        }
+        for (int t = 0; t < 4; ++t) *reinterpret_cast<u32x4*>(mine + (4 * lr + t) * kVPitch + lc * 16) = v0[t];
       }
-      asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
-      __builtin_amdgcn_wave_barrier();
 #pragma unroll
-      for (int t = 0; t < 4; ++t) v0[t] = v1[t];
+      for (int i = 0; i < UPT; ++i)
+        if (tid + i * nthreads < UCH) ub[tid + i * nthreads] = u_pad[i] ? u32x4{0u, 0u, 0u, 0u} : ur[i];
+      // the row indices two groups ahead are requested first (loads return in order: waiting
+      // for them in the next round must not mean waiting for that round's rows), then the rows
+      // and activations of the next group (the last group is simply fetched again)
+      const int jn2 = load_idx(min(g + 2, g1 - 1));
+      load_rows(jn, v0);
+      load_u(min(g + 1, g1 - 1), ur);
+      jn = jn2;
+      lds_barrier();
+      if (active) {
+        u32x4 af[NB][kPlanes];
 #pragma unroll
-      for (int nb = 0; nb < NB; ++nb) {
+        for (int nb = 0; nb < NB; ++nb)
 #pragma unroll
-        for (int pl = 0; pl < kPlanes; ++pl) u0[nb][pl] = u1[nb][pl];
+          for (int pl = 0; pl < kPlanes; ++pl) af[nb][pl] = ub[(pl * NB + nb) * kWave + lane];
+#pragma unroll
+        for (int ct = 0; ct < 4; ++ct) {
+          u32x4 bv;
+#pragma unroll
+          for (int e = 0; e < 8; e += 2) {
+            const uint32_t x0 = *reinterpret_cast<const uint16_t*>(mine + (4 * e + kg) * kVPitch + (ct * 16 + ri) * 2);
+            const uint32_t x1 = *reinterpret_cast<const uint16_t*>(mine + (4 * (e + 1) + kg) * kVPitch + (ct * 16 + ri) * 2);
+            bv[e >> 1] = x0 | (x1 << 16);
+          }
+#pragma unroll
+          for (int nb = 0; nb < NB; ++nb)
+#pragma unroll
+            for (int pl = kPlanes - 1; pl >= 0; --pl) acc[ct][nb] = mfma_bf16(af[nb][pl], bv, acc[ct][nb]);
+        }
       }
     }
   }
+  if (!active) return;
   // D[token 4 kg + e][column ri] of every (column tile, token block)
   float* dst = P.part + ((size_t)l * P.KS + ks) * P.B * P.d_model;
 #pragma unroll
@@ -439,7 +498,14 @@ __global__ __launch_bounds__(256) void reduce_batch_kernel(const BatchParams P) 
 
 size_t align256(size_t v) { return (v + 255) / 256 * 256; }
 
-int v_slabs(int d_model) { return (d_model + 64 * kVSlabWaves - 1) / (64 * kVSlabWaves); }
+// Waves of a v workgroup: the largest count in 4..8 that divides the 64-column strips evenly.
+int v_waves(int d_model) {
+  const int n64 = (d_model + 63) / 64;
+  for (int w = kVMaxWaves; w >= kVMinWaves; --w)
+    if (n64 % w == 0) return w;
+  return n64 < kVMinWaves ? kVMinWaves : kVMaxWaves;
+}
+int v_slabs(int d_model) { return ((d_model + 63) / 64 + v_waves(d_model) - 1) / v_waves(d_model); }
 int part_rows(int d_model) { return kBatchMaxLayers + (768 + v_slabs(d_model) - 1) / v_slabs(d_model); }
 
 struct BatchLayout {
@@ -503,7 +569,8 @@ size_t phased_batch_scratch_bytes(int d_model, int d_ff, int batch) { return bat
 bool phased_batch_supported(const FfnProblem& p) {
   const int r2 = p.d_model - p.r;
   return p.batch >= 2 && p.batch <= 64 && p.w_bf16 && p.q_bf16 && p.r % 32 == 0 && r2 % 32 == 0 &&
-         p.d_model % 64 == 0 && p.d_ff <= 64 * kMaxWords && p.d_ff >= 16 && spw_for(p.r) <= 8 && spw_for(r2) <= 8;
+         p.d_model % 64 == 0 && p.d_ff <= 64 * kMaxWords && p.d_ff >= 16 && spw_for(p.r) <= 8 && spw_for(r2) <= 8 &&
+         (size_t)p.d_ff * (size_t)p.d_model * 2 < ((size_t)1 << 31);  // 32-bit buffer offsets
 }
 
 hipError_t launch_ffn_phased_batch(const FfnProblem& p0, const void* const* k1n, const void* const* k2n,
@@ -546,10 +613,10 @@ hipError_t launch_ffn_phased_batch(const FfnProblem& p0, const void* const* k1n,
     P.ldu = lay.ldu;
     P.z = p0.z;
     const int tiles = (p0.d_ff + 15) / 16;
-    int tpw1 = 16;
-    while (tpw1 > 2 && (long long)L * ((tiles + tpw1 - 1) / tpw1) < 768) tpw1 /= 2;
+    int tpw1 = 16;  // multiples of 4 (the deepest tile pipeline)
+    while (tpw1 > 4 && (long long)L * ((tiles + tpw1 - 1) / tpw1) < 768) tpw1 /= 2;
     int tpw2 = 8;
-    while (tpw2 > 2 && (long long)L * ((tiles + tpw2 - 1) / tpw2) < 1024) tpw2 /= 2;
+    while (tpw2 > 4 && (long long)L * ((tiles + tpw2 - 1) / tpw2) < 1024) tpw2 /= 2;
     P.TPW1 = tpw1;
     P.TPW2 = tpw2;
     const int slabs = v_slabs(p0.d_model);
@@ -564,11 +631,19 @@ hipError_t launch_ffn_phased_batch(const FfnProblem& p0, const void* const* k1n,
     err = launch_rows_nb(P, 1, nb, spw_for(p0.d_model - p0.r), dim3((tiles + tpw2 - 1) / tpw2, L), st);
     if (err != hipSuccess) return err;
     const dim3 gv(slabs, ksl, L);
+    const int nwv = v_waves(p0.d_model);
+    const size_t vdyn = (size_t)nwv * 32 * kVPitch + (size_t)2 * kPlanes * nb * kWave * 16;
+    const void* vk = nb == 1 ? reinterpret_cast<const void*>(v_batch_kernel<1>)
+                     : nb == 2 ? reinterpret_cast<const void*>(v_batch_kernel<2>)
+                     : nb == 3 ? reinterpret_cast<const void*>(v_batch_kernel<3>)
+                               : reinterpret_cast<const void*>(v_batch_kernel<4>);
+    err = hipFuncSetAttribute(vk, hipFuncAttributeMaxDynamicSharedMemorySize, (int)vdyn);
+    if (err != hipSuccess) return err;
     switch (nb) {
-      case 1: hipLaunchKernelGGL((v_batch_kernel<1>), gv, dim3(kVSlabWaves * kWave), 0, st, P); break;
-      case 2: hipLaunchKernelGGL((v_batch_kernel<2>), gv, dim3(kVSlabWaves * kWave), 0, st, P); break;
-      case 3: hipLaunchKernelGGL((v_batch_kernel<3>), gv, dim3(kVSlabWaves * kWave), 0, st, P); break;
-      default: hipLaunchKernelGGL((v_batch_kernel<4>), gv, dim3(kVSlabWaves * kWave), 0, st, P); break;
+      case 1: hipLaunchKernelGGL((v_batch_kernel<1>), gv, dim3(nwv * kWave), vdyn, st, P); break;
+      case 2: hipLaunchKernelGGL((v_batch_kernel<2>), gv, dim3(nwv * kWave), vdyn, st, P); break;
+      case 3: hipLaunchKernelGGL((v_batch_kernel<3>), gv, dim3(nwv * kWave), vdyn, st, P); break;
+      default: hipLaunchKernelGGL((v_batch_kernel<4>), gv, dim3(nwv * kWave), vdyn, st, P); break;
     }
     const size_t n = (size_t)B * p0.d_model;
     hipLaunchKernelGGL(reduce_batch_kernel, dim3((unsigned)((n + 255) / 256), L), dim3(256), 0, st, P);
