@@ -147,6 +147,46 @@ def stat_topk_bench(torch, binding, synth, dev, with_cpu):
     return out
 
 
+def time_config(torch, binding, shape, layers, q, dev, steps=20):
+    """One stack / batch: us per layer and fraction of 8 TB/s on the algorithmic bytes (all of K1n,
+    plus the K2n and Vn rows of the union of the tokens' active sets)."""
+    L, B = len(layers), q.shape[0]
+    ws = binding.make_workspace(shape.d_model, shape.d_ff, B, dev)
+    y = torch.empty(L, B, shape.d_model, device=dev)
+    ucnt = torch.zeros(L, dtype=torch.int32, device=dev)
+    binding.spark_ffn_decode_layers(layers, q, y, ws, union_count=ucnt)
+    binding.spark_ffn_check(ws, shape.d_model, shape.d_ff, B)
+    union = ucnt.cpu().numpy()
+    nbytes = float(sum(algorithmic_bytes(shape, [int(m) for m in union], 2)))
+    gpu_s, _ = time_region(lambda: binding.spark_ffn_decode_layers(layers, q, y, ws), steps, 3, torch)
+    per_call = gpu_s / steps
+    del ws, y
+    return {"shape": shape.name, "layers": L, "batch": B, "us_per_layer": per_call / L * 1e6,
+            "layers_per_s": L / per_call, "tokens_per_s": B / per_call, "union_size_mean": float(union.mean()),
+            "algorithmic_bytes_per_layer": nbytes / L, "achieved_gbs": nbytes / per_call / 1e9,
+            "hbm_frac": nbytes / per_call / 1e9 / HBM_PEAK_GBS}
+
+
+def other_configs(torch, binding, synth, dev, main_shape, L, weights, layers):
+    """The batched decode configurations on the same stack, and the Gemma-2-9B-shaped stack at
+    batch 1 and 8 (42 layers, 12.95 GB of weights)."""
+    res = []
+    shape = synth.SHAPES[main_shape]
+    for B in (4, 16, 64):
+        q = synth.tokens(shape, B, 2000 + B, dtype=torch.bfloat16, device=dev)
+        res.append(time_config(torch, binding, shape, layers, q, dev))
+    if main_shape == "gemma2-2b":
+        shape9 = synth.SHAPES["gemma2-9b"]
+        w9 = synth.ffn_stack(shape9, 42, base_seed=1000, dtype=torch.bfloat16, device=dev)
+        l9 = [binding.make_layer(w[0], w[1], w[2], shape9.k) for w in w9]
+        for B in (1, 8):
+            q = synth.tokens(shape9, B, 2000 + B, dtype=torch.bfloat16, device=dev)
+            res.append(time_config(torch, binding, shape9, l9, q, dev))
+        del w9, l9
+        torch.cuda.empty_cache()
+    return res
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -158,6 +198,8 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-dense", action="store_true")
     ap.add_argument("--no-stat-topk", action="store_true")
+    ap.add_argument("--no-extra", action="store_true",
+                    help="skip the single-layer-call timing and the batched / 9B-shaped configurations")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run three plain 1 GiB device copies (the known-size reference for the "
                          "FETCH_SIZE / WRITE_SIZE counters)")
@@ -270,8 +312,7 @@ def main():
         yd = torch.empty(L, B, shape.d_model, device=dev)
 
         def dense_step():
-            for l in range(L):
-                binding.spark_ffn_dense_decode(layers[l], q, yd[l], ws)
+            binding.spark_ffn_dense_decode_layers(layers, q, yd, ws)
 
         dsteps = max(10, args.steps // 10)
         d_s, _ = time_region(dense_step, dsteps, 3, torch)
@@ -291,6 +332,20 @@ def main():
         torch.cuda.synchronize()
         out["calibration_copy_bytes"] = 1 << 30
         del src, dst
+
+    if B == 1 and not args.no_extra:
+        # the same stack called one layer at a time (what a decoder whose layers feed each other
+        # would do): every call is a predictor sweep, a gather and a reduction of one layer
+        def chain_step():
+            for l in range(L):
+                binding.spark_ffn_decode(layers[l], q, y[l], ws)
+
+        c_s, _ = time_region(chain_step, max(5, args.steps // 20), 2, torch)
+        out["single_layer_calls"] = {"us_per_layer": c_s / max(5, args.steps // 20) / L * 1e6,
+                                     "hbm_frac": bytes_step / L / (c_s / max(5, args.steps // 20) / L) / 1e9 / HBM_PEAK_GBS}
+
+    if not args.no_extra:
+        out["other_configs"] = other_configs(torch, binding, synth, dev, args.shape, L, weights, layers)
 
     if not args.no_stat_topk:
         out["stat_topk"] = stat_topk_bench(torch, binding, synth, dev, not args.no_cpu_baseline)

@@ -164,6 +164,14 @@ spark_status spark_ffn_dense_decode(const spark_ffn_layer* layer, const void* q,
                                     spark_dtype qdtype, int32_t batch, int64_t ldq, float* y,
                                     void* workspace, size_t workspace_bytes, void* hip_stream);
 
+/* The same for n_layers independent layers on the same q (y [n_layers][batch][d_model]); for
+ * batch 1 the layers are evaluated phase by phase over the whole stack like
+ * spark_ffn_decode_layers, with every K2 / V row fetched. */
+spark_status spark_ffn_dense_decode_layers(const spark_ffn_layer* layers, int32_t n_layers,
+                                           const void* q, spark_dtype qdtype, int32_t batch,
+                                           int64_t ldq, float* y, void* workspace,
+                                           size_t workspace_bytes, void* hip_stream);
+
 /*
  * Host, synchronising.  The batch-1 entry points run as one persistent launch whose
  * wavefronts wait on each other; every such wait is bounded, and a launch that had to give

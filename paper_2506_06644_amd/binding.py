@@ -24,7 +24,7 @@ MAX_BATCH = 64
 EXPORTS = (
     "spark_status_string", "spark_version", "spark_normal_quantile", "spark_stat_topk",
     "spark_ffn_workspace_bytes", "spark_ffn_decode", "spark_ffn_decode_layers",
-    "spark_ffn_dense_decode", "spark_ffn_check", "spark_debug_force_general", "spark_debug_tuning", "spark_debug_phases",
+    "spark_ffn_dense_decode", "spark_ffn_dense_decode_layers", "spark_ffn_check", "spark_debug_force_general", "spark_debug_tuning", "spark_debug_phases",
     "spark_debug_profile", "spark_debug_read_profile",
 )
 
@@ -74,6 +74,8 @@ def load_library():
                                             vp, vp, vp, vp, sz, vp]
     lib.spark_ffn_dense_decode.restype = c_int
     lib.spark_ffn_dense_decode.argtypes = [ctypes.POINTER(_Layer), vp, c_int, i32, i64, vp, vp, sz, vp]
+    lib.spark_ffn_dense_decode_layers.restype = c_int
+    lib.spark_ffn_dense_decode_layers.argtypes = [ctypes.POINTER(_Layer), i32, vp, c_int, i32, i64, vp, vp, sz, vp]
     lib.spark_ffn_check.restype = c_int
     lib.spark_ffn_check.argtypes = [vp, i32, i32, i32, vp]
     lib.spark_debug_profile.restype = None
@@ -178,6 +180,14 @@ def spark_ffn_dense_decode(layer: _Layer, q: torch.Tensor, y: torch.Tensor, work
         ctypes.byref(layer), _p(q), _dt(q), q.shape[0], q.stride(0), _p(y), _p(workspace),
         workspace.numel(), _stream())
     _check(rc, "spark_ffn_dense_decode")
+
+
+def spark_ffn_dense_decode_layers(layers: Sequence[_Layer], q: torch.Tensor, y: torch.Tensor, workspace: torch.Tensor):
+    """``len(layers)`` independent layers, every K2 / V row read; ``y[L, batch, d_model]``."""
+    arr = (_Layer * len(layers))(*layers)
+    rc = load_library().spark_ffn_dense_decode_layers(
+        arr, len(layers), _p(q), _dt(q), q.shape[0], q.stride(0), _p(y), _p(workspace), workspace.numel(), _stream())
+    _check(rc, "spark_ffn_dense_decode_layers")
 
 
 def spark_ffn_check(workspace: torch.Tensor, d_model: int, d_ff: int, batch: int):

@@ -77,7 +77,7 @@ int g_force_general = 0;  // 0: automatic, 1: general multi-kernel path, 2: pers
 // Runs layers[0..n) for one token through the phase-by-phase path (persistent = false) or
 // the persistent launch.
 hipError_t run_fused(const spark_ffn_layer* layers, int32_t n_layers, const spark::FfnProblem& p0,
-                     const spark::FfnWorkspace& ws, bool persistent, hipStream_t st) {
+                     const spark::FfnWorkspace& ws, bool persistent, hipStream_t st, int dense = 0) {
   const void* k1n[256];
   const void* k2n[256];
   const void* vn[256];
@@ -98,7 +98,7 @@ hipError_t run_fused(const spark_ffn_layer* layers, int32_t n_layers, const spar
     if (p.union_idx) p.union_idx += (int64_t)base * p0.d_ff;
     if (p.batch >= 2) e = spark::launch_ffn_phased_batch(p, k1n, k2n, vn, n, ws.fused, st);
     else e = persistent ? spark::launch_ffn_fused(p, k1n, k2n, vn, n, ws.fused, st)
-                        : spark::launch_ffn_phased(p, k1n, k2n, vn, n, ws.fused, st);
+                        : spark::launch_ffn_phased(p, k1n, k2n, vn, n, dense, ws.fused, st);
   }
   return e;
 }
@@ -244,6 +244,35 @@ spark_status spark_ffn_dense_decode(const spark_ffn_layer* layer, const void* q,
   const spark::FfnWorkspace ws = spark::carve_workspace(workspace, layer->d_model, layer->d_ff, batch);
   const hipError_t e = spark::launch_ffn_general(p, ws, 1, static_cast<hipStream_t>(hip_stream));
   return e == hipSuccess ? SPARK_OK : SPARK_ERR_DEVICE;
+}
+
+spark_status spark_ffn_dense_decode_layers(const spark_ffn_layer* layers, int32_t n_layers, const void* q,
+                                           spark_dtype qdtype, int32_t batch, int64_t ldq, float* y,
+                                           void* workspace, size_t workspace_bytes, void* hip_stream) {
+  if (!layers) return SPARK_ERR_NULL;
+  if (n_layers < 1) return SPARK_ERR_SHAPE;
+  for (int32_t l = 0; l < n_layers; ++l) {
+    const spark_status s = validate_decode(&layers[l], q, qdtype, batch, ldq, y, workspace, workspace_bytes);
+    if (s != SPARK_OK) return s;
+    if (layers[l].d_model != layers[0].d_model || layers[l].d_ff != layers[0].d_ff ||
+        layers[l].r != layers[0].r || layers[l].k != layers[0].k || layers[l].wdtype != layers[0].wdtype ||
+        layers[l].gelu != layers[0].gelu)
+      return SPARK_ERR_SHAPE;
+  }
+  const int64_t d_model = layers[0].d_model;
+  const spark::FfnWorkspace ws = spark::carve_workspace(workspace, layers[0].d_model, layers[0].d_ff, batch);
+  const spark::FfnProblem p0 =
+      make_problem(&layers[0], q, qdtype, batch, ldq, y, nullptr, nullptr, nullptr, nullptr, nullptr);
+  if (g_force_general == 0 && spark::phased_supported(p0)) {
+    const hipError_t e = run_fused(layers, n_layers, p0, ws, false, static_cast<hipStream_t>(hip_stream), 1);
+    return e == hipSuccess ? SPARK_OK : SPARK_ERR_DEVICE;
+  }
+  for (int32_t l = 0; l < n_layers; ++l) {
+    const spark::FfnProblem p = make_problem(&layers[l], q, qdtype, batch, ldq, y + (int64_t)l * batch * d_model,
+                                             nullptr, nullptr, nullptr, nullptr, nullptr);
+    if (spark::launch_ffn_general(p, ws, 1, static_cast<hipStream_t>(hip_stream)) != hipSuccess) return SPARK_ERR_DEVICE;
+  }
+  return SPARK_OK;
 }
 
 spark_status spark_ffn_check(const void* workspace, int32_t d_model, int32_t d_ff, int32_t batch,

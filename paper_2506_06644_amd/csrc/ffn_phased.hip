@@ -44,6 +44,7 @@ struct PhasedParams {
   float* part;         // [L][NBC][d_model]
   int32_t* status;     // cleared: this path cannot abort
   int n_layers, d_model, d_ff, r, q_bf16, gelu;
+  int dense;  // every neuron's K2n and Vn row is read (inactive ones contribute an exact zero)
   float z;
   int RPB;  // predictor rows per workgroup (multiple of 16, <= kMaxRPB)
   int NBA;  // predictor workgroups per layer, ceil(d_ff / RPB)
@@ -272,7 +273,7 @@ __global__ __launch_bounds__(NW * kWave, OCC) void gather_layers_kernel(const Ph
     const int wd = wave + NW * k;
     if (wd < nwords) {
       const int n = wd * kWave + lane;
-      const unsigned long long m = __ballot(n < nn && sv[k] > theta);
+      const unsigned long long m = __ballot(n < nn && (P.dense || sv[k] > theta));
       s_blk[n] = sv[k] - theta;
       if (lane == 0) maskw[wd] = m;
     }
@@ -324,7 +325,8 @@ __global__ __launch_bounds__(NW * kWave, OCC) void gather_layers_kernel(const Ph
       for (int e = 0; e < VEC; ++e) gd += kr[c].get(e) * qp[e];
     }
     gd = wave_total(gd);
-    const float u = gelu(s_blk[n], P.gelu) * gd;
+    const float a = s_blk[n];  // s_j - theta
+    const float u = a > 0.f ? gelu(a, P.gelu) * gd : 0.f;
 #pragma unroll
     for (int c = 0; c < CPLV; ++c)
 #pragma unroll
@@ -537,7 +539,7 @@ bool phased_supported(const FfnProblem& p) {
 }
 
 hipError_t launch_ffn_phased(const FfnProblem& p0, const void* const* k1n, const void* const* k2n,
-                             const void* const* vn, int n_layers, void* scratch, hipStream_t st) {
+                             const void* const* vn, int n_layers, int dense, void* scratch, hipStream_t st) {
   const PhasedLayout lay = phased_layout(p0.d_model, p0.d_ff);
   int gv = gather_variant(p0);
   if (gv < 0) return hipErrorInvalidValue;
@@ -571,6 +573,7 @@ hipError_t launch_ffn_phased(const FfnProblem& p0, const void* const* k1n, const
     P.r = p0.r;
     P.q_bf16 = p0.q_bf16;
     P.gelu = p0.gelu;
+    P.dense = dense;
     P.z = p0.z;
     // Block sizes: enough workgroups to fill 256 compute units several times over, as few
     // partial rows as that allows.

@@ -71,7 +71,7 @@ bool phased_supported(const FfnProblem& p);
 void phased_set_phases(int mask);  // measurement aid: bit 0 predict, bit 1 gather, bit 2 reduce / select; 0 = all
 void phased_set_tuning(int rows_per_predict_block, int neurons_per_gather_block, int alt);  // 0 = automatic
 hipError_t launch_ffn_phased(const FfnProblem& p0, const void* const* k1n, const void* const* k2n,
-                             const void* const* vn, int n_layers, void* scratch, hipStream_t st);
+                             const void* const* vn, int n_layers, int dense, void* scratch, hipStream_t st);
 
 // Phase-by-phase path for batches of 2..64 tokens on the matrix cores (bf16 weights and
 // tokens), up to kBatchMaxLayers layers per set of launches.

@@ -52,7 +52,9 @@ def run_gpu_ffn(shape, weights, q, gelu=binding.GELU_ERF, dense=False, via_layer
     ucnt = torch.zeros(L, dtype=torch.int32, device=dev)
     uidx = torch.full((L, shape.d_ff), -1, dtype=torch.int32, device=dev)
     binding.spark_debug_force_general(force_general)
-    if dense:
+    if dense and via_layers:
+        binding.spark_ffn_dense_decode_layers(layers, qd, y, ws)
+    elif dense:
         for l in range(L):
             binding.spark_ffn_dense_decode(layers[l], qd, y[l], ws)
     elif via_layers:

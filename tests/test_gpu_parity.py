@@ -233,6 +233,15 @@ def test_dense_evaluation_gives_the_same_layer():
     assert rel_l2(dense["y"], sparse["y"]) < 1e-6
 
 
+def test_dense_layers_entry_point():
+    """Dense evaluation of a stack, phase by phase (batch 1) and layer by layer (batch 3)."""
+    for sh, batch, n_layers in ((synth.TINY, 1, 5), (synth.RAGGED, 1, 3), (synth.TINY, 3, 2), (synth.GEMMA2_2B, 1, 2)):
+        weights = synth.ffn_stack(sh, n_layers, base_seed=91, dtype=torch.bfloat16)
+        q = synth.tokens(sh, batch, 92, torch.bfloat16)
+        dense = run_gpu_ffn(sh, weights, q, dense=True, via_layers=True)
+        check_ffn_against_oracle(sh, weights, q, dense, TOL_BF16_TIGHT, dense=True, what="dense layers")
+
+
 def test_batch_members_do_not_influence_each_other():
     sh = synth.TINY
     weights = synth.ffn_stack(sh, 1, base_seed=5, dtype=torch.bfloat16)
