@@ -325,7 +325,7 @@ __global__ __launch_bounds__(NW * kWave, OCC) void gather_layers_kernel(const Ph
       for (int e = 0; e < VEC; ++e) gd += kr[c].get(e) * qp[e];
     }
     gd = wave_total(gd);
-    const float a = s_blk[n];  // s_j - theta
+    const float a = n >= 0 ? s_blk[n] : 0.f;  // s_j - theta
     const float u = a > 0.f ? gelu(a, P.gelu) * gd : 0.f;
 #pragma unroll
     for (int c = 0; c < CPLV; ++c)
@@ -334,16 +334,25 @@ __global__ __launch_bounds__(NW * kWave, OCC) void gather_layers_kernel(const Ph
   };
 
   {
+    // this wave's share of the block's active neurons: every NW-th one, starting at `wave`
+    int total = 0;
+    for (int w = 0; w < nwords; ++w) total += __popcll(uniform_u64(maskw[w]));
+    const int mine = total > wave ? (total - wave + NW - 1) / NW : 0;
     Vec16<WT> ka[CPL2], va[CPLV], kb[CPL2], vb[CPLV];
     int na = next_neuron();
     request(na, ka, va);
-    while (na >= 0) {
-      const int nb = next_neuron();
-      request(nb, kb, vb);
+    int nb = next_neuron();
+    request(nb, kb, vb);
+    // The body is branch-free: a buffer whose neuron does not exist was requested through a
+    // descriptor without records, holds zeros and adds zeros (only in the last round), so the
+    // number of loads in flight is a compile-time constant and every wait is exact.
+    for (int i = 0; i < mine; i += 2) {
       consume(na, ka, va);
-      na = nb >= 0 ? next_neuron() : -1;
+      na = next_neuron();
       request(na, ka, va);
-      if (nb >= 0) consume(nb, kb, vb);
+      consume(nb, kb, vb);
+      nb = next_neuron();
+      request(nb, kb, vb);
     }
   }
 

@@ -201,10 +201,32 @@ def test_paper_layer_shape_and_9b_shape(path):
     _ffn_case(synth.GEMMA2_9B, torch.bfloat16, torch.bfloat16, 8, n_layers=1, seed=11)
 
 
-@pytest.mark.parametrize("batch", [1, 4])
+@pytest.mark.parametrize("batch", [1, 4, 16, 64])
 def test_gemma2_2b_layer(batch):
     out = _ffn_case(synth.GEMMA2_2B, torch.bfloat16, torch.bfloat16, batch, seed=1000)
     assert np.all(np.abs(out["count"] - 737) < 6 * 26)
+
+
+def test_gemma2_2b_stack_as_benchmarked():
+    """The benchmark's launch configuration (26 layers per call, batch 1 and 16): every layer's index
+    set and theta against the oracle, y of the first, a middle and the last layer."""
+    sh = synth.GEMMA2_2B
+    weights = synth.ffn_stack(sh, 26, base_seed=1000, dtype=torch.bfloat16)
+    for batch in (1, 16):
+        q = synth.tokens(sh, batch, 2000 + batch, torch.bfloat16)
+        out = run_gpu_ffn(sh, weights, q, via_layers=True)
+        pick = [0, 13, 25]
+        sub = {k: (v[pick] if v.shape[0] == 26 else v) for k, v in out.items()}
+        check_ffn_against_oracle(sh, [weights[i] for i in pick], q, sub, TOL_BF16_TIGHT, what=f"stack B={batch}")
+        qs = synth.to_oracle(q)
+        for l in range(26):
+            k1n = synth.to_oracle(weights[l][0])
+            for b in range(0, batch, 5):
+                s = k1n.astype(np.float64) @ qs[b][:sh.r].astype(np.float64)
+                ref = oracle.stat_topk_rows(s[None, :], sh.k)
+                assert abs(out["theta"][l, b] - ref.theta[0]) <= 1e-5 * ref.std[0] + 1e-6 * abs(ref.theta[0])
+                m = int(out["count"][l, b])
+                assert_active_set(out["idx"][l, b, :m], s, ref.theta[0], ref.std[0], f"layer {l} token {b}")
 
 
 def test_gemma2_2b_fp32_weights():
