@@ -32,7 +32,7 @@ namespace {
 
 typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
 
-constexpr int kRowWaves = 8;     // waves of a predict / k2 workgroup (k split)
+constexpr int kRowWavesAll = 12;  // waves of a predict / k2 workgroup: NLW loaders (k split) + the rest emit
 constexpr int kVPitch = 160;     // bytes between row positions of a staged V tile (conflict-free transposed reads)
 constexpr int kPlanes = 3;       // bf16 planes of u: 3 x 8 significant bits carry an fp32 value
 constexpr int kMaxWords = 256;   // 64-bit union mask words per layer: d_ff <= 16384
@@ -49,16 +49,19 @@ struct BatchParams {
   int32_t* idx;        // [L][B][d_ff]  optional
   int32_t* ucount;     // [L]           optional
   int32_t* uidx;       // [L][d_ff]     optional
-  float* S;                    // [L][B][d_ff]  predictor scores
+  float* S;                    // [L][B][d_ff]  predictor scores, token-major (read by select)
+  float* ST;                   // [L][d_ff][BP] the same, neuron-major (read by k2: one 64-byte piece per row and token block)
   float* thetas;               // [L][B]
   unsigned long long* umask;   // [L][kMaxWords]  union of the tokens' masks
   int32_t* urow;               // [L][d_ff]       union rank -> neuron
   int32_t* utotal;             // [L]             union size
-  uint16_t* up;                // [kPlanes][L][B][ldu]  bf16 planes of u (u = sum of the planes), by union rank
+  uint16_t* up;                // [kPlanes][L][ldu / 8][B][8]  bf16 planes of u (u = sum of the planes): union ranks in
+                               // blocks of 8, so that the 8 consecutive ranks of one token the v phase feeds to a lane
+                               // are 16 contiguous bytes and a group's tokens are contiguous too
   size_t plane;                // elements between planes
   float* part;                 // [L][KS][B][d_model]
   int32_t* status;
-  int n_layers, B, d_model, d_ff, r, gelu, ldu;
+  int n_layers, B, BP, d_model, d_ff, r, gelu, ldu;  // BP = B rounded up to 16
   float z;
   int TPW1;  // predict tiles per workgroup (even)
   int TPW2;  // k2 tiles per workgroup (even, <= 32)
@@ -82,36 +85,66 @@ __device__ __forceinline__ void lds_barrier() {
 }
 // k step (of 32) that wave `w` takes as its s-th: steps are dealt in pairs so that a wave
 // reads whole 128-byte lines of a row
-template <int SPW> __device__ __forceinline__ int k_step_t(int s, int w) { return (s >> 1) * 16 + 2 * w + (s & 1); }
+template <int SPW, int NLW> __device__ __forceinline__ int k_step_t(int s, int w) { return (s >> 1) * 2 * NLW + 2 * w + (s & 1); }
 
 // ---------------------------------------------------------------------------- rows x tokens
-// Shared by predict (MODE 0: rows are the neurons 16 * tile + i) and k2 (MODE 1: rows are the
-// union ranks, looked up in `rowidx`).  Returns through `emit(tile, item, value, side)` the
-// reduced D[row 4 * kg + e][token nb * 16 + ri] with item = nb * 4 + e, for the items this
-// wave sums; `side` is what `pre(tile, item)` fetched for that item together with the tile's
-// rows (so that no load issued after the prefetch of the next tile has to be waited for:
-// loads return in order).
+// Shared by predict (rows are the neurons 16 * tile + i) and k2 (rows are union ranks, looked up
+// in `rowidx`).  A workgroup has NLW LOADER waves (8 or 10, whichever
+// covers the k steps with fewer registers) and 12 - NLW EMIT waves.
 //
-// DEPTH tiles are kept in flight per wave.  A tile past `tile_end` is requested through a
-// buffer descriptor without records: the loads are issued all the same (their number in
-// flight stays a compile-time constant, so the waits can be exact) but touch no memory.
+// Loader wave w owns the k steps k_step(s, w): it holds the token fragments of those steps in
+// registers, keeps DEPTH tiles of its row slices in flight, multiplies, and leaves its partial
+// tile in LDS.  Its loop contains no store and no branch: on this target stores share the
+// loads' counter and a wave with both kinds pending can only wait for all of them, so a
+// store in this loop would drain the prefetch at every tile.  A tile past `tile_end` is
+// requested through a buffer descriptor without records: the loads are issued all the same
+// (their number in flight stays a compile-time constant, the waits are exact) but touch no
+// memory.  With HAS_SIDE a loader also fetches, together with a tile, one value per (item,
+// lane) that the emit step will need (`pre(tile, item)`), and passes it on through LDS.
+//
+// Emit wave e sums the loaders' partials of the items e, e + kEmitWaves, ... in loader order
+// and hands D[row 4 * kg + i][token nb * 16 + ri] (item = nb * 4 + i) to `emit(tile, item,
+// value, side)`, which stores.  One LDS-only barrier per tile; the partial buffers alternate,
+// and a loader that writes a buffer again two tiles later has passed the barrier of the tile
+// in between, which the emit waves reach only after they have finished reading it.
+constexpr int kRowThreads = kRowWavesAll * kWave;
+template <int NB, int SPW>
+constexpr int tile_depth() { return (NB <= 2 && SPW <= 4) ? 4 : 2; }  // DEPTH * SPW * 4 registers hold the tiles in flight
 template <int NB>
-constexpr int tile_depth() { return NB <= 2 ? 4 : 2; }
-template <int NB, int SPW, typename RowOf, typename Pre, typename Emit>
+constexpr size_t rows_lds_bytes() { return (size_t)2 * (10 + 1) * NB * 4 * kWave * sizeof(float); }
+template <int NB, int SPW, int NLW, bool HAS_SIDE, typename RowOf, typename Pre, typename Emit>
 __device__ __forceinline__ void rows_times_tokens(const bf16_t* __restrict__ w, uint32_t w_bytes, int K,
                                                   const bf16_t* __restrict__ q, int64_t ldq, int qoff, int B,
                                                   int tile0, int ntiles, int tile_end,
-                                                  float (*red)[kRowWaves][NB * 4][kWave], RowOf row_of, Pre pre, Emit emit) {
-  constexpr int IPW = (NB * 4 + kRowWaves - 1) / kRowWaves;  // items a wave sums per tile
-  constexpr int DEPTH = tile_depth<NB>();
+                                                  float* red_raw, RowOf row_of, Pre pre, Emit emit) {
+  constexpr int kRowWaves = NLW, kEmitWaves = kRowWavesAll - NLW;
+  constexpr int IPW = (NB * 4 + kRowWaves - 1) / kRowWaves;  // side values a loader fetches per tile
+  float(*red)[kRowWaves + 1][NB * 4][kWave] = reinterpret_cast<float(*)[kRowWaves + 1][NB * 4][kWave]>(red_raw);
+  constexpr int DEPTH = tile_depth<NB, SPW>();
   const int lane = threadIdx.x & (kWave - 1);
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
-  const int ri = lane & 15, kg = lane >> 4;
+  const int kg = lane >> 4, ri = lane & 15;
+  if (wave >= kRowWaves) {
+    // ------------------------------------------------------------------ emit wave
+    const int ew = wave - kRowWaves;
+    for (int i = 0; i < ntiles; ++i) {
+      const int buf = i & 1;
+      lds_barrier();
+      for (int item = ew; item < NB * 4; item += kEmitWaves) {
+        float v = 0.f;
+#pragma unroll
+        for (int wv = 0; wv < kRowWaves; ++wv) v += red[buf][wv][item][lane];
+        emit(tile0 + i, item, v, HAS_SIDE ? red[buf][kRowWaves][item][lane] : 0.f);
+      }
+    }
+    return;
+  }
+  // -------------------------------------------------------------------- loader wave
   const int nsteps = K / 32;
   u32x4 qf[SPW][NB];
 #pragma unroll
   for (int s = 0; s < SPW; ++s) {
-    const int ks = k_step_t<SPW>(s, wave);
+    const int ks = k_step_t<SPW, NLW>(s, wave);
 #pragma unroll
     for (int nb = 0; nb < NB; ++nb) {
       const int b = nb * 16 + ri;
@@ -123,16 +156,18 @@ __device__ __forceinline__ void rows_times_tokens(const bf16_t* __restrict__ w, 
   auto load_tile = [&](int t, u32x4(&a)[SPW], float(&side)[IPW]) {
     const __amdgpu_buffer_rsrc_t rs =
         __builtin_amdgcn_make_buffer_rsrc(const_cast<bf16_t*>(w), 0, t < tile_end ? (int)w_bytes : 0, 0x00020000);
+    if constexpr (HAS_SIDE) {
 #pragma unroll
-    for (int i = 0; i < IPW; ++i) side[i] = wave + kRowWaves * i < NB * 4 ? pre(t, wave + kRowWaves * i) : 0.f;
+      for (int i = 0; i < IPW; ++i) side[i] = pre(t, min(wave + kRowWaves * i, NB * 4 - 1));
+    }
     const uint32_t row_off = (uint32_t)row_of(t, ri) * (uint32_t)K * 2u;
 #pragma unroll
     for (int s = 0; s < SPW; ++s) {
-      const int ks = k_step_t<SPW>(s, wave);  // steps past K meet a zero token fragment
+      const int ks = k_step_t<SPW, NLW>(s, wave);  // steps past K meet a zero token fragment
       a[s] = __builtin_amdgcn_raw_buffer_load_b128(rs, (int)(row_off + (uint32_t)((ks < nsteps ? ks : 0) * 4 + kg) * 16u), 0, 0);
     }
   };
-  auto process = [&](int t, const u32x4(&a)[SPW], const float(&side)[IPW], int buf) {
+  auto process = [&](const u32x4(&a)[SPW], const float(&side)[IPW], int buf) {
     f32x4 acc[NB];
 #pragma unroll
     for (int nb = 0; nb < NB; ++nb) acc[nb] = f32x4{0.f, 0.f, 0.f, 0.f};
@@ -144,20 +179,11 @@ __device__ __forceinline__ void rows_times_tokens(const bf16_t* __restrict__ w, 
     for (int nb = 0; nb < NB; ++nb)
 #pragma unroll
       for (int e = 0; e < 4; ++e) red[buf][wave][nb * 4 + e][lane] = acc[nb][e];
-    // one barrier per tile: the buffers alternate, and a wave that writes buffer `buf` again
-    // two tiles later has passed the barrier of the tile in between, which every wave reaches
-    // only after it has finished reading `buf`
-    lds_barrier();
+    if constexpr (HAS_SIDE) {
 #pragma unroll
-    for (int i = 0; i < IPW; ++i) {
-      const int item = wave + kRowWaves * i;
-      if (item < NB * 4) {
-        float v = 0.f;
-#pragma unroll
-        for (int wv = 0; wv < kRowWaves; ++wv) v += red[buf][wv][item][lane];
-        emit(t, item, v, side[i]);
-      }
+      for (int i = 0; i < IPW; ++i) red[buf][kRowWaves][min(wave + kRowWaves * i, NB * 4 - 1)][lane] = side[i];
     }
+    lds_barrier();
   };
   u32x4 a[DEPTH][SPW];
   float sd[DEPTH][IPW];
@@ -166,35 +192,38 @@ __device__ __forceinline__ void rows_times_tokens(const bf16_t* __restrict__ w, 
   for (int i = 0; i < ntiles; i += DEPTH) {  // ntiles is a multiple of DEPTH (an even number)
 #pragma unroll
     for (int d = 0; d < DEPTH; ++d) {
-      process(tile0 + i + d, a[d], sd[d], d & 1);
+      process(a[d], sd[d], d & 1);
       load_tile(tile0 + i + d + DEPTH, a[d], sd[d]);
     }
   }
 }
 
 // --------------------------------------------------------------------------------- predict
-template <int NB, int SPW>
-__global__ __launch_bounds__(kRowWaves * kWave) void predict_batch_kernel(const BatchParams P) {
+template <int NB, int SPW, int NLW>
+__global__ __launch_bounds__(kRowThreads) void predict_batch_kernel(const BatchParams P) {
   extern __shared__ __align__(16) float red_raw[];
-  float(*red)[kRowWaves][NB * 4][kWave] = reinterpret_cast<float(*)[kRowWaves][NB * 4][kWave]>(red_raw);
   const int lane = threadIdx.x & (kWave - 1);
   const int ri = lane & 15, kg = lane >> 4;
   const int l = blockIdx.y;
   const int tiles_total = (P.d_ff + 15) / 16;
   const int tile0 = blockIdx.x * P.TPW1;
   if (blockIdx.x == 0) {
-    for (int i = threadIdx.x; i < kMaxWords; i += kRowWaves * kWave) P.umask[(size_t)l * kMaxWords + i] = 0ull;
+    for (int i = threadIdx.x; i < kMaxWords; i += kRowThreads) P.umask[(size_t)l * kMaxWords + i] = 0ull;
     if (l == 0 && threadIdx.x == 0) *P.status = 0;  // this path cannot abort
   }
   if (tile0 >= tiles_total) return;
   float* S = P.S + (size_t)l * P.B * P.d_ff;
-  rows_times_tokens<NB, SPW>(
+  float* ST = P.ST + (size_t)l * P.d_ff * P.BP;
+  rows_times_tokens<NB, SPW, NLW, false>(
       static_cast<const bf16_t*>(P.k1n[l]), (uint32_t)P.d_ff * (uint32_t)P.r * 2u, P.r, P.q, P.ldq, 0, P.B, tile0, P.TPW1,
-      min(tile0 + P.TPW1, tiles_total), red,
+      min(tile0 + P.TPW1, tiles_total), red_raw,
       [&](int t, int i) { return min(t * 16 + i, P.d_ff - 1); }, [](int, int) { return 0.f; },
       [&](int t, int item, float v, float) {
         const int b = (item >> 2) * 16 + ri, j = t * 16 + 4 * kg + (item & 3);
-        if (b < P.B && j < P.d_ff && t < tiles_total) S[(size_t)b * P.d_ff + j] = v;
+        if (j < P.d_ff && t < tiles_total) {
+          if (b < P.B) S[(size_t)b * P.d_ff + j] = v;
+          if (b < P.BP) ST[(size_t)j * P.BP + b] = v;  // tokens past the batch have v = 0: whole lines are written
+        }
       });
 }
 
@@ -254,10 +283,9 @@ __global__ __launch_bounds__(1024) void select_batch_kernel(const BatchParams P)
 }
 
 // -------------------------------------------------------------------------------------- k2
-template <int NB, int SPW>
-__global__ __launch_bounds__(kRowWaves * kWave) void k2_batch_kernel(const BatchParams P) {
+template <int NB, int SPW, int NLW>
+__global__ __launch_bounds__(kRowThreads) void k2_batch_kernel(const BatchParams P) {
   extern __shared__ __align__(16) float red_raw[];
-  float(*red)[kRowWaves][NB * 4][kWave] = reinterpret_cast<float(*)[kRowWaves][NB * 4][kWave]>(red_raw);
   __shared__ int wprefix[kMaxWords + 1];
   __shared__ int rowidx[32 * 16 + 16];
   const int tid = threadIdx.x, lane = tid & (kWave - 1);
@@ -291,7 +319,7 @@ __global__ __launch_bounds__(kRowWaves * kWave) void k2_batch_kernel(const Batch
   }
   if (tile0 >= tiles_total) return;
   // neuron of every union rank this workgroup handles (ranks past the end repeat the last one)
-  for (int i = tid; i < P.TPW2 * 16 + 16; i += kRowWaves * kWave) {
+  for (int i = tid; i < P.TPW2 * 16 + 16; i += kRowThreads) {
     const int rho = tile0 * 16 + i;
     const int rc = min(rho, m_total - 1);
     int lo = 0, hi = nwords - 1;  // last word with wprefix[word] <= rc
@@ -311,22 +339,22 @@ __global__ __launch_bounds__(kRowWaves * kWave) void k2_batch_kernel(const Batch
   }
   __syncthreads();
   const int rank_end = (m_total + 31) / 32 * 32;  // the v phase reads ranks below this
-  const float* S = P.S + (size_t)l * P.B * P.d_ff;
+  const float* ST = P.ST + (size_t)l * P.d_ff * P.BP;
   float th[NB];
 #pragma unroll
   for (int nb = 0; nb < NB; ++nb) th[nb] = P.thetas[(size_t)l * P.B + min(nb * 16 + ri, P.B - 1)];
   uint16_t* up = P.up + (size_t)l * P.B * P.ldu;
-  rows_times_tokens<NB, SPW>(
+  rows_times_tokens<NB, SPW, NLW, true>(
       static_cast<const bf16_t*>(P.k2n[l]), (uint32_t)P.d_ff * (uint32_t)(P.d_model - P.r) * 2u, P.d_model - P.r, P.q, P.ldq,
-      P.r, P.B, tile0, P.TPW2, min(tile0 + P.TPW2, tiles_total), red,
+      P.r, P.B, tile0, P.TPW2, min(tile0 + P.TPW2, tiles_total), red_raw,
       [&](int t, int i) { return rowidx[min((t - tile0) * 16 + i, P.TPW2 * 16 + 15)]; },
       [&](int t, int item) {  // the score the item's (row, token) pair will need
         const int b = min((item >> 2) * 16 + ri, P.B - 1);
-        return S[(size_t)b * P.d_ff + rowidx[min((t - tile0) * 16 + 4 * kg + (item & 3), P.TPW2 * 16 + 15)]];
+        return ST[(size_t)rowidx[min((t - tile0) * 16 + 4 * kg + (item & 3), P.TPW2 * 16 + 15)] * P.BP + b];
       },
       [&](int t, int item, float g, float score) {
         const int nb = item >> 2, b = nb * 16 + ri;
-        const int li = (t - tile0) * 16 + 4 * kg + (item & 3), rho = tile0 * 16 + li;
+        const int rho = t * 16 + 4 * kg + (item & 3);
         if (b >= P.B || rho >= rank_end) return;
         float u = 0.f;
         if (rho < m_total) {
@@ -337,7 +365,7 @@ __global__ __launch_bounds__(kRowWaves * kWave) void k2_batch_kernel(const Batch
 #pragma unroll
         for (int pl = 0; pl < kPlanes; ++pl) {
           const uint16_t h = float_to_bf16_rne(rest);
-          up[pl * P.plane + (size_t)b * P.ldu + rho] = h;
+          up[pl * P.plane + ((size_t)(rho >> 3) * P.B + b) * 8 + (rho & 7)] = h;
           rest -= bf16_bits_to_float(h);
         }
       });
@@ -345,10 +373,10 @@ __global__ __launch_bounds__(kRowWaves * kWave) void k2_batch_kernel(const Batch
   // read as zero
   if (tile0 + P.TPW2 >= tiles_total) {
     const int from = (tile0 + P.TPW2) * 16, to = rank_end;
-    for (int i = tid; i < (to - from) * P.B; i += kRowWaves * kWave) {
+    for (int i = tid; i < (to - from) * P.B; i += kRowThreads) {
       const int b = i / (to - from), rho = from + i % (to - from);
 #pragma unroll
-      for (int pl = 0; pl < kPlanes; ++pl) up[pl * P.plane + (size_t)b * P.ldu + rho] = 0;
+      for (int pl = 0; pl < kPlanes; ++pl) up[pl * P.plane + ((size_t)(rho >> 3) * P.B + b) * 8 + (rho & 7)] = 0;
     }
   }
 }
@@ -366,7 +394,8 @@ constexpr int kVMinWaves = 4, kVMaxWaves = 8;
 template <int NB>
 __global__ __launch_bounds__(kVMaxWaves * kWave, (NB >= 3 ? 3 : 4)) void v_batch_kernel(const BatchParams P) {
   constexpr int UCH = kPlanes * NB * kWave;                            // 16-byte chunks of u per group
-  constexpr int UPT = (UCH + kVMinWaves * kWave - 1) / (kVMinWaves * kWave);  // most chunks per thread
+  constexpr int MINW = NB >= 3 ? 6 : kVMinWaves;                        // fewest waves the launch uses
+  constexpr int UPT = (UCH + MINW * kWave - 1) / (MINW * kWave);        // most chunks per thread
   extern __shared__ __align__(16) unsigned char lds[];
   const int tid = threadIdx.x, lane = tid & (kWave - 1), nthreads = blockDim.x;
   const int wave = __builtin_amdgcn_readfirstlane(tid / kWave);
@@ -414,7 +443,7 @@ __global__ __launch_bounds__(kVMaxWaves * kWave, (NB >= 3 ? 3 : 4)) void v_batch
         // tokens past the batch re-read the last token; they are zeroed when the chunk is parked
         // in LDS (a select here would have to wait for the load, and with it for every load
         // issued before it)
-        a[i] = ld16(up + pl * P.plane + (size_t)min(b, P.B - 1) * P.ldu + (size_t)g * 32 + 8 * (cl >> 4));
+        a[i] = ld16(up + pl * P.plane + ((size_t)(g * 4 + (cl >> 4)) * P.B + min(b, P.B - 1)) * 8);
       }
     }
   };
@@ -499,17 +528,18 @@ __global__ __launch_bounds__(256) void reduce_batch_kernel(const BatchParams P) 
 size_t align256(size_t v) { return (v + 255) / 256 * 256; }
 
 // Waves of a v workgroup: the largest count in 4..8 that divides the 64-column strips evenly.
-int v_waves(int d_model) {
-  const int n64 = (d_model + 63) / 64;
-  for (int w = kVMaxWaves; w >= kVMinWaves; --w)
+// (at least 6 for more than 32 tokens, so that a thread fetches at most two chunks of u per group)
+int v_waves(int d_model, int nb) {
+  const int n64 = (d_model + 63) / 64, lo = nb >= 3 ? 6 : kVMinWaves;
+  for (int w = kVMaxWaves; w >= lo; --w)
     if (n64 % w == 0) return w;
-  return n64 < kVMinWaves ? kVMinWaves : kVMaxWaves;
+  return n64 < lo ? lo : kVMaxWaves;
 }
-int v_slabs(int d_model) { return ((d_model + 63) / 64 + v_waves(d_model) - 1) / v_waves(d_model); }
-int part_rows(int d_model) { return kBatchMaxLayers + (768 + v_slabs(d_model) - 1) / v_slabs(d_model); }
+int v_slabs(int d_model, int nb) { return ((d_model + 63) / 64 + v_waves(d_model, nb) - 1) / v_waves(d_model, nb); }
+int part_rows(int d_model) { return kBatchMaxLayers + (768 + v_slabs(d_model, 4) - 1) / v_slabs(d_model, 4); }
 
 struct BatchLayout {
-  size_t S, thetas, umask, urow, utotal, up, plane, part, total;
+  size_t S, ST, thetas, umask, urow, utotal, up, plane, part, total;
   int ldu;
 };
 
@@ -519,6 +549,7 @@ BatchLayout batch_layout(int d_model, int d_ff, int B) {
   s.ldu = (d_ff + 64 + 7) / 8 * 8;
   size_t o = 256;  // the first word is the status word spark_ffn_check reads
   s.S = o;      o += align256(L * B * (size_t)d_ff * 4);
+  s.ST = o;     o += align256(L * (size_t)((B + 15) / 16 * 16) * (size_t)d_ff * 4);
   s.thetas = o; o += align256(L * B * 4);
   s.umask = o;  o += align256(L * kMaxWords * 8);
   s.urow = o;   o += align256(L * (size_t)d_ff * 4);
@@ -530,46 +561,67 @@ BatchLayout batch_layout(int d_model, int d_ff, int B) {
   return s;
 }
 
-int spw_for(int K) { return 2 * ((K / 32 + 15) / 16); }
-
-template <int NB, int SPW>
-void launch_rows(const BatchParams& P, int mode, dim3 grid, hipStream_t st) {
-  const size_t dyn = (size_t)2 * kRowWaves * NB * 4 * kWave * sizeof(float);
-  const void* kern = mode == 0 ? reinterpret_cast<const void*>(predict_batch_kernel<NB, SPW>)
-                               : reinterpret_cast<const void*>(k2_batch_kernel<NB, SPW>);
-  if (hipFuncSetAttribute(kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)dyn) != hipSuccess) return;
-  if (mode == 0) hipLaunchKernelGGL((predict_batch_kernel<NB, SPW>), grid, dim3(kRowWaves * kWave), dyn, st, P);
-  else hipLaunchKernelGGL((k2_batch_kernel<NB, SPW>), grid, dim3(kRowWaves * kWave), dyn, st, P);
+// Loader waves and k steps per loader for a row of K elements: the smallest (NLW, SPW) whose
+// NLW * SPW steps of 32 cover K.  Returns false when none of the compiled ones does.
+bool split_for(int K, int* nlw, int* spw) {
+  static const int cand[][2] = {{8, 4}, {10, 4}, {8, 6}, {10, 6}, {8, 8}};
+  for (const auto& c : cand)
+    if (c[0] * c[1] * 32 >= K) {
+      *nlw = c[0];
+      *spw = c[1];
+      return true;
+    }
+  return false;
 }
-template <int NB>
-hipError_t launch_rows_spw(const BatchParams& P, int mode, int spw, dim3 grid, hipStream_t st) {
-  switch (spw) {
-    case 2: launch_rows<NB, 2>(P, mode, grid, st); break;
-    case 4: launch_rows<NB, 4>(P, mode, grid, st); break;
-    case 6: launch_rows<NB, 6>(P, mode, grid, st); break;
-    case 8: launch_rows<NB, 8>(P, mode, grid, st); break;
-    default: return hipErrorInvalidValue;
-  }
+
+template <int NB, int SPW, int NLW>
+hipError_t launch_rows(const BatchParams& P, int mode, dim3 grid, hipStream_t st) {
+  const size_t dyn = rows_lds_bytes<NB>();
+  const void* kern = mode == 0 ? reinterpret_cast<const void*>(predict_batch_kernel<NB, SPW, NLW>)
+                               : reinterpret_cast<const void*>(k2_batch_kernel<NB, SPW, NLW>);
+  const hipError_t e = hipFuncSetAttribute(kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)dyn);
+  if (e != hipSuccess) return e;
+  if (mode == 0) hipLaunchKernelGGL((predict_batch_kernel<NB, SPW, NLW>), grid, dim3(kRowThreads), dyn, st, P);
+  else hipLaunchKernelGGL((k2_batch_kernel<NB, SPW, NLW>), grid, dim3(kRowThreads), dyn, st, P);
   return hipGetLastError();
 }
-hipError_t launch_rows_nb(const BatchParams& P, int mode, int nb, int spw, dim3 grid, hipStream_t st) {
+template <int NB>
+hipError_t launch_rows_split(const BatchParams& P, int mode, int nlw, int spw, dim3 grid, hipStream_t st) {
+  if (nlw == 8 && spw == 4) return launch_rows<NB, 4, 8>(P, mode, grid, st);
+  if (nlw == 10 && spw == 4) return launch_rows<NB, 4, 10>(P, mode, grid, st);
+  if (nlw == 8 && spw == 6) return launch_rows<NB, 6, 8>(P, mode, grid, st);
+  if (nlw == 10 && spw == 6) return launch_rows<NB, 6, 10>(P, mode, grid, st);
+  if (nlw == 8 && spw == 8) return launch_rows<NB, 8, 8>(P, mode, grid, st);
+  return hipErrorInvalidValue;
+}
+hipError_t launch_rows_nb(const BatchParams& P, int mode, int nb, int K, dim3 grid, hipStream_t st) {
+  int nlw = 0, spw = 0;
+  if (!split_for(K, &nlw, &spw)) return hipErrorInvalidValue;
   switch (nb) {
-    case 1: return launch_rows_spw<1>(P, mode, spw, grid, st);
-    case 2: return launch_rows_spw<2>(P, mode, spw, grid, st);
-    case 3: return launch_rows_spw<3>(P, mode, spw, grid, st);
-    case 4: return launch_rows_spw<4>(P, mode, spw, grid, st);
+    case 1: return launch_rows_split<1>(P, mode, nlw, spw, grid, st);
+    case 2: return launch_rows_split<2>(P, mode, nlw, spw, grid, st);
+    case 3: return launch_rows_split<3>(P, mode, nlw, spw, grid, st);
+    case 4: return launch_rows_split<4>(P, mode, nlw, spw, grid, st);
     default: return hipErrorInvalidValue;
   }
 }
 
+int g_batch_tpw1 = 0, g_batch_tpw2 = 0;  // tuning overrides (multiples of 4; 0 = automatic)
+
 }  // namespace
+
+void phased_batch_set_tuning(int tpw1, int tpw2) {
+  g_batch_tpw1 = tpw1 > 0 ? (tpw1 + 3) / 4 * 4 : 0;
+  g_batch_tpw2 = tpw2 > 0 ? min(32, (tpw2 + 3) / 4 * 4) : 0;
+}
 
 size_t phased_batch_scratch_bytes(int d_model, int d_ff, int batch) { return batch_layout(d_model, d_ff, batch).total; }
 
 bool phased_batch_supported(const FfnProblem& p) {
   const int r2 = p.d_model - p.r;
+  int a = 0, b = 0;
   return p.batch >= 2 && p.batch <= 64 && p.w_bf16 && p.q_bf16 && p.r % 32 == 0 && r2 % 32 == 0 &&
-         p.d_model % 64 == 0 && p.d_ff <= 64 * kMaxWords && p.d_ff >= 16 && spw_for(p.r) <= 8 && spw_for(r2) <= 8 &&
+         p.d_model % 64 == 0 && p.d_ff <= 64 * kMaxWords && p.d_ff >= 16 && split_for(p.r, &a, &b) && split_for(r2, &a, &b) &&
          (size_t)p.d_ff * (size_t)p.d_model * 2 < ((size_t)1 << 31);  // 32-bit buffer offsets
 }
 
@@ -596,6 +648,8 @@ hipError_t launch_ffn_phased_batch(const FfnProblem& p0, const void* const* k1n,
     P.ucount = p0.union_count ? p0.union_count + base : nullptr;
     P.uidx = p0.union_idx ? p0.union_idx + (size_t)base * p0.d_ff : nullptr;
     P.S = reinterpret_cast<float*>(s + lay.S);
+    P.ST = reinterpret_cast<float*>(s + lay.ST);
+    P.BP = (B + 15) / 16 * 16;
     P.thetas = reinterpret_cast<float*>(s + lay.thetas);
     P.umask = reinterpret_cast<unsigned long long*>(s + lay.umask);
     P.urow = reinterpret_cast<int32_t*>(s + lay.urow);
@@ -617,21 +671,23 @@ hipError_t launch_ffn_phased_batch(const FfnProblem& p0, const void* const* k1n,
     while (tpw1 > 4 && (long long)L * ((tiles + tpw1 - 1) / tpw1) < 768) tpw1 /= 2;
     int tpw2 = 8;
     while (tpw2 > 4 && (long long)L * ((tiles + tpw2 - 1) / tpw2) < 1024) tpw2 /= 2;
+    if (g_batch_tpw1 > 0) tpw1 = g_batch_tpw1;
+    if (g_batch_tpw2 > 0) tpw2 = g_batch_tpw2;
     P.TPW1 = tpw1;
     P.TPW2 = tpw2;
-    const int slabs = v_slabs(p0.d_model);
+    const int slabs = v_slabs(p0.d_model, nb);
     int ksl = (768 + slabs * L - 1) / (slabs * L);
     ksl = max(1, min(16, ksl));
     while (L * ksl > part_rows(p0.d_model)) --ksl;
     P.KS = ksl;
 
-    err = launch_rows_nb(P, 0, nb, spw_for(p0.r), dim3((tiles + tpw1 - 1) / tpw1, L), st);
+    err = launch_rows_nb(P, 0, nb, p0.r, dim3((tiles + tpw1 - 1) / tpw1, L), st);
     if (err != hipSuccess) return err;
     hipLaunchKernelGGL(select_batch_kernel, dim3(B, L), dim3(1024), 0, st, P);
-    err = launch_rows_nb(P, 1, nb, spw_for(p0.d_model - p0.r), dim3((tiles + tpw2 - 1) / tpw2, L), st);
+    err = launch_rows_nb(P, 1, nb, p0.d_model - p0.r, dim3((tiles + tpw2 - 1) / tpw2, L), st);
     if (err != hipSuccess) return err;
     const dim3 gv(slabs, ksl, L);
-    const int nwv = v_waves(p0.d_model);
+    const int nwv = v_waves(p0.d_model, nb);
     const size_t vdyn = (size_t)nwv * 32 * kVPitch + (size_t)2 * kPlanes * nb * kWave * 16;
     const void* vk = nb == 1 ? reinterpret_cast<const void*>(v_batch_kernel<1>)
                      : nb == 2 ? reinterpret_cast<const void*>(v_batch_kernel<2>)
