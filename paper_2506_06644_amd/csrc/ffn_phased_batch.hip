@@ -7,8 +7,8 @@
 //             v_mfma_f32_16x16x32_bf16 with the k range split over the 8 waves of a workgroup;
 //             the token fragments stay in registers while the workgroup walks its tiles.
 //   select    one workgroup per (layer, token): mean and std of the row (two passes over
-//             registers), theta (Eq.11), the token's index list, and the token's mask OR-ed
-//             into the layer's union mask.
+//             registers), theta (Eq.11), the token's index list and the token's mask; a small
+//             launch then ORs the tokens' masks of a layer into its union mask.
 //   k2        tiles of 16 union rows: G[m][b] = K2n[U[m]] . q_b[r:] (same MFMA scheme, rows
 //             found by rank in the union mask), u[m][b] = GELU(s_bj - theta_b) * G (0 where
 //             token b does not activate the row), stored token-major as three bf16 planes
@@ -52,6 +52,7 @@ struct BatchParams {
   float* S;                    // [L][B][d_ff]  predictor scores, token-major (read by select)
   float* ST;                   // [L][d_ff][BP] the same, neuron-major (read by k2: one 64-byte piece per row and token block)
   float* thetas;               // [L][B]
+  unsigned long long* tmask;   // [L][B][kMaxWords]  mask of every token
   unsigned long long* umask;   // [L][kMaxWords]  union of the tokens' masks
   int32_t* urow;               // [L][d_ff]       union rank -> neuron
   int32_t* utotal;             // [L]             union size
@@ -207,10 +208,7 @@ __global__ __launch_bounds__(kRowThreads) void predict_batch_kernel(const BatchP
   const int l = blockIdx.y;
   const int tiles_total = (P.d_ff + 15) / 16;
   const int tile0 = blockIdx.x * P.TPW1;
-  if (blockIdx.x == 0) {
-    for (int i = threadIdx.x; i < kMaxWords; i += kRowThreads) P.umask[(size_t)l * kMaxWords + i] = 0ull;
-    if (l == 0 && threadIdx.x == 0) *P.status = 0;  // this path cannot abort
-  }
+  if (blockIdx.x == 0 && l == 0 && threadIdx.x == 0) *P.status = 0;  // this path cannot abort
   if (tile0 >= tiles_total) return;
   float* S = P.S + (size_t)l * P.B * P.d_ff;
   float* ST = P.ST + (size_t)l * P.d_ff * P.BP;
@@ -228,29 +226,34 @@ __global__ __launch_bounds__(kRowThreads) void predict_batch_kernel(const BatchP
 }
 
 // ---------------------------------------------------------------------------------- select
-// One workgroup per (token, layer); the row of scores sits in registers (<= 16 per thread).
-__global__ __launch_bounds__(1024) void select_batch_kernel(const BatchParams P) {
-  __shared__ float red[16];
-  __shared__ int wcount[16];
+// One workgroup (4 waves) per (token, layer); the row of scores sits in registers (VPT per
+// thread; small workgroups so that many rows are in flight per compute unit).
+constexpr int kSelThreads = 256;
+template <int VPT>
+__global__ __launch_bounds__(kSelThreads) void select_batch_kernel(const BatchParams P) {
+  constexpr int NWS = kSelThreads / kWave;
+  __shared__ float red[NWS];
+  __shared__ int wcount[NWS];
   const int tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid / kWave;
   const int b = blockIdx.x, l = blockIdx.y;
   const float* row = P.S + ((size_t)l * P.B + b) * P.d_ff;
-  float v[16];
+  float v[VPT];
   float sum = 0.f;
 #pragma unroll
-  for (int k = 0; k < 16; ++k) {
-    const int j = tid + 1024 * k;
+  for (int k = 0; k < VPT; ++k) {
+    const int j = tid + kSelThreads * k;
     v[k] = j < P.d_ff ? row[j] : 0.f;
-    sum += v[k];
   }
-  const float mean = block_sum<1024>(sum, red) / (float)P.d_ff;
+#pragma unroll
+  for (int k = 0; k < VPT; ++k) sum += v[k];
+  const float mean = block_sum<kSelThreads>(sum, red) / (float)P.d_ff;
   float sq = 0.f;
 #pragma unroll
-  for (int k = 0; k < 16; ++k) {
-    const float d = tid + 1024 * k < P.d_ff ? v[k] - mean : 0.f;
+  for (int k = 0; k < VPT; ++k) {
+    const float d = tid + kSelThreads * k < P.d_ff ? v[k] - mean : 0.f;
     sq += d * d;
   }
-  const float m2 = block_sum<1024>(sq, red);
+  const float m2 = block_sum<kSelThreads>(sq, red);
   const float theta = mean + sqrtf(m2 / (float)(P.d_ff - 1)) * P.z;
   if (tid == 0) {
     P.thetas[(size_t)l * P.B + b] = theta;
@@ -259,19 +262,19 @@ __global__ __launch_bounds__(1024) void select_batch_kernel(const BatchParams P)
   int running = 0;
   const bool want_idx = P.idx || P.count;
 #pragma unroll
-  for (int k = 0; k < 16; ++k) {
-    if (1024 * k >= P.d_ff) break;  // uniform
-    const int j = tid + 1024 * k;
+  for (int k = 0; k < VPT; ++k) {
+    if (kSelThreads * k >= P.d_ff) break;  // uniform
+    const int j = tid + kSelThreads * k;
     const bool on = j < P.d_ff && v[k] > theta;
     const unsigned long long m = __ballot(on);
-    if (lane == 0 && m) atomicOr(&P.umask[(size_t)l * kMaxWords + (j >> 6)], m);
+    if (lane == 0) P.tmask[((size_t)l * P.B + b) * kMaxWords + (j >> 6)] = m;
     if (want_idx) {
       __syncthreads();
       if (lane == 0) wcount[wave] = __popcll(m);
       __syncthreads();
       int before = 0, total = 0;
 #pragma unroll
-      for (int w = 0; w < 16; ++w) {
+      for (int w = 0; w < NWS; ++w) {
         before += w < wave ? wcount[w] : 0;
         total += wcount[w];
       }
@@ -280,6 +283,23 @@ __global__ __launch_bounds__(1024) void select_batch_kernel(const BatchParams P)
     }
   }
   if (tid == 0 && P.count) P.count[(size_t)l * P.B + b] = running;
+}
+
+// One workgroup per layer: the union of the tokens' masks, word by word (plain stores and
+// loads: no atomics, and nothing to clear beforehand).
+__global__ __launch_bounds__(4 * kMaxWords) void union_batch_kernel(const BatchParams P) {
+  __shared__ unsigned long long part[4][kMaxWords];
+  const int l = blockIdx.x, w = threadIdx.x % kMaxWords, q = threadIdx.x / kMaxWords;  // q: every 4th token
+  const bool live = w < (P.d_ff + 63) / 64;
+  const unsigned long long* tm = P.tmask + (size_t)l * P.B * kMaxWords + w;
+  unsigned long long m = 0ull;
+  if (live) {
+#pragma unroll 4
+    for (int b = q; b < P.B; b += 4) m |= tm[(size_t)b * kMaxWords];
+  }
+  part[q][w] = m;
+  __syncthreads();
+  if (q == 0 && live) P.umask[(size_t)l * kMaxWords + w] = part[0][w] | part[1][w] | part[2][w] | part[3][w];
 }
 
 // -------------------------------------------------------------------------------------- k2
@@ -539,7 +559,7 @@ int v_slabs(int d_model, int nb) { return ((d_model + 63) / 64 + v_waves(d_model
 int part_rows(int d_model) { return kBatchMaxLayers + (768 + v_slabs(d_model, 4) - 1) / v_slabs(d_model, 4); }
 
 struct BatchLayout {
-  size_t S, ST, thetas, umask, urow, utotal, up, plane, part, total;
+  size_t S, ST, thetas, tmask, umask, urow, utotal, up, plane, part, total;
   int ldu;
 };
 
@@ -551,6 +571,7 @@ BatchLayout batch_layout(int d_model, int d_ff, int B) {
   s.S = o;      o += align256(L * B * (size_t)d_ff * 4);
   s.ST = o;     o += align256(L * (size_t)((B + 15) / 16 * 16) * (size_t)d_ff * 4);
   s.thetas = o; o += align256(L * B * 4);
+  s.tmask = o;  o += align256(L * B * kMaxWords * 8);
   s.umask = o;  o += align256(L * kMaxWords * 8);
   s.urow = o;   o += align256(L * (size_t)d_ff * 4);
   s.utotal = o; o += align256(L * 4);
@@ -651,6 +672,7 @@ hipError_t launch_ffn_phased_batch(const FfnProblem& p0, const void* const* k1n,
     P.ST = reinterpret_cast<float*>(s + lay.ST);
     P.BP = (B + 15) / 16 * 16;
     P.thetas = reinterpret_cast<float*>(s + lay.thetas);
+    P.tmask = reinterpret_cast<unsigned long long*>(s + lay.tmask);
     P.umask = reinterpret_cast<unsigned long long*>(s + lay.umask);
     P.urow = reinterpret_cast<int32_t*>(s + lay.urow);
     P.utotal = reinterpret_cast<int32_t*>(s + lay.utotal);
@@ -683,7 +705,9 @@ hipError_t launch_ffn_phased_batch(const FfnProblem& p0, const void* const* k1n,
 
     err = launch_rows_nb(P, 0, nb, p0.r, dim3((tiles + tpw1 - 1) / tpw1, L), st);
     if (err != hipSuccess) return err;
-    hipLaunchKernelGGL(select_batch_kernel, dim3(B, L), dim3(1024), 0, st, P);
+    if (p0.d_ff <= 36 * kSelThreads) hipLaunchKernelGGL((select_batch_kernel<36>), dim3(B, L), dim3(kSelThreads), 0, st, P);
+    else hipLaunchKernelGGL((select_batch_kernel<64>), dim3(B, L), dim3(kSelThreads), 0, st, P);
+    hipLaunchKernelGGL(union_batch_kernel, dim3(L), dim3(4 * kMaxWords), 0, st, P);
     err = launch_rows_nb(P, 1, nb, p0.d_model - p0.r, dim3((tiles + tpw2 - 1) / tpw2, L), st);
     if (err != hipSuccess) return err;
     const dim3 gv(slabs, ksl, L);
