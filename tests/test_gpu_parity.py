@@ -273,3 +273,33 @@ def test_batch_members_do_not_influence_each_other():
         solo = run_gpu_ffn(sh, weights, q[b:b + 1])
         assert np.array_equal(solo["idx"][0, 0], full["idx"][0, b])
         assert rel_l2(solo["y"][0, 0], full["y"][0, b]) < 1e-6
+
+
+@pytest.mark.parametrize("batch", [1, 4, 64])
+@pytest.mark.parametrize("path", [0, 1])
+def test_degenerate_layers(batch, path):
+    """Constant scores (zero predictor weights): std = 0, theta = mean, nothing is strictly greater, so the
+    active sets and the union are empty and y = 0.  And k = d_ff - 1: theta drops so far that almost every
+    neuron is active (the gather degenerates to the dense layer)."""
+    sh = synth.TINY
+    weights = synth.ffn_stack(sh, 2, base_seed=321, dtype=torch.bfloat16)
+    q = synth.tokens(sh, batch, 322, torch.bfloat16)
+    zeroed = [(torch.zeros_like(w[0]), w[1], w[2]) for w in weights]
+    out = run_gpu_ffn(sh, zeroed, q, via_layers=True, force_general=path)
+    assert np.all(out["y"] == 0.0) and np.all(out["count"] == 0) and np.all(out["ucount"] == 0)
+    assert np.all(out["theta"] == 0.0) and np.all(out["idx"] == -1)
+    import dataclasses
+    wide = dataclasses.replace(sh, k=sh.d_ff - 1)
+    out = run_gpu_ffn(wide, weights, q, via_layers=True, force_general=path)
+    check_ffn_against_oracle(wide, weights, q, out, TOL_BF16_TIGHT, what=f"k=d_ff-1 B={batch}")
+    assert np.all(out["count"] > 0.99 * sh.d_ff)
+
+
+def test_batch_sizes_around_the_token_blocks():
+    """Batches that do not fill the 16-token blocks of the matrix-core path, and the largest batch."""
+    sh = synth.TINY
+    weights = synth.ffn_stack(sh, 2, base_seed=55, dtype=torch.bfloat16)
+    for batch in (2, 15, 17, 33, 48, 63, 64):
+        q = synth.tokens(sh, batch, 56 + batch, torch.bfloat16)
+        out = run_gpu_ffn(sh, weights, q, via_layers=True)
+        check_ffn_against_oracle(sh, weights, q, out, TOL_BF16_TIGHT, what=f"B={batch}")
