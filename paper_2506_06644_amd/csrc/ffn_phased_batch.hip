@@ -110,7 +110,7 @@ template <int SPW, int NLW> __device__ __forceinline__ int k_step_t(int s, int w
 // in between, which the emit waves reach only after they have finished reading it.
 constexpr int kRowThreads = kRowWavesAll * kWave;
 template <int NB, int SPW>
-constexpr int tile_depth() { return (NB <= 2 && SPW <= 4) ? 4 : 2; }  // DEPTH * SPW * 4 registers hold the tiles in flight
+constexpr int tile_depth() { return 2; }  // tiles in flight per loader wave (deeper did not pay: see the notes on measurements)  // DEPTH * SPW * 4 registers hold the tiles in flight
 template <int NB>
 constexpr size_t rows_lds_bytes() { return (size_t)2 * (10 + 1) * NB * 4 * kWave * sizeof(float); }
 template <int NB, int SPW, int NLW, bool HAS_SIDE, typename RowOf, typename Pre, typename Emit>
@@ -691,8 +691,8 @@ hipError_t launch_ffn_phased_batch(const FfnProblem& p0, const void* const* k1n,
     const int tiles = (p0.d_ff + 15) / 16;
     int tpw1 = 16;  // multiples of 4 (the deepest tile pipeline)
     while (tpw1 > 4 && (long long)L * ((tiles + tpw1 - 1) / tpw1) < 768) tpw1 /= 2;
-    int tpw2 = 8;
-    while (tpw2 > 4 && (long long)L * ((tiles + tpw2 - 1) / tpw2) < 1024) tpw2 /= 2;
+    int tpw2 = 16;  // long ranges amortise the rank lookup of a k2 workgroup
+    while (tpw2 > 4 && (long long)L * ((tiles + tpw2 - 1) / tpw2) < 512) tpw2 /= 2;
     if (g_batch_tpw1 > 0) tpw1 = g_batch_tpw1;
     if (g_batch_tpw2 > 0) tpw2 = g_batch_tpw2;
     P.TPW1 = tpw1;
