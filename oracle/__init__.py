@@ -63,6 +63,11 @@ def _load():
     lib.spark_ref_spark_ffn.restype = c_int
     lib.spark_ref_spark_ffn.argtypes = [vp, vp, vp, vp, c_i64, c_i64, c_i64, c_i64, c_int, c_int,
                                         vp, vp, vp, vp, vp, vp, vp, vp, c_int]
+    lib.spark_ref_softplus.restype = c_d
+    lib.spark_ref_softplus.argtypes = [c_d]
+    lib.spark_ref_spark_attention.restype = c_int
+    lib.spark_ref_spark_attention.argtypes = [vp, vp, vp, vp, c_i64, c_i64, c_i64, c_i64, c_int,
+                                              vp, vp, vp, vp, vp, vp, vp]
     _lib = lib
     return lib
 
@@ -222,6 +227,51 @@ def spark_ffn_batch(k1n, k2n, vn, q, k: int, gelu_kind: int = GELU_ERF,
     outs = [spark_ffn(k1n, k2n, vn, q[b], k, gelu_kind, skip_inactive, threads)
             for b in range(q.shape[0])]
     return outs, union_of([o.idx for o in outs])
+
+
+@dataclass
+class SparkAttention:
+    y: np.ndarray        # [d_attn] float64
+    s: np.ndarray        # [n_ctx] predictor scores
+    p: np.ndarray        # [n_ctx] softmax over the kept keys (0 elsewhere)
+    g: np.ndarray        # [n_ctx] softplus(K2^T q[r:])
+    mean: float
+    std: float
+    z: float
+    theta: float         # -inf when n_ctx <= k (every key kept)
+    idx: np.ndarray      # ascending kept keys
+    count: int
+
+
+def softplus(x: float) -> float:
+    return float(_load().spark_ref_softplus(float(x)))
+
+
+def spark_attention(k1c, k2c, vc, q, k: int, skip_inactive: bool = False) -> SparkAttention:
+    """One head of Spark attention for one query (Eq.7); caches token-major float32 arrays
+    k1c[n_ctx, r], k2c[n_ctx, d_attn - r], vc[n_ctx, d_attn]."""
+    k1c = np.ascontiguousarray(k1c, dtype=np.float32)
+    k2c = np.ascontiguousarray(k2c, dtype=np.float32)
+    vc = np.ascontiguousarray(vc, dtype=np.float32)
+    q = np.ascontiguousarray(q, dtype=np.float32)
+    n_ctx, r = k1c.shape
+    d_attn = vc.shape[1]
+    if k2c.shape != (n_ctx, d_attn - r) or vc.shape[0] != n_ctx or q.shape != (d_attn,):
+        raise ValueError("spark_attention: inconsistent shapes")
+    y = np.empty(d_attn, np.float64)
+    s = np.empty(n_ctx, np.float64)
+    p = np.empty(n_ctx, np.float64)
+    g = np.empty(n_ctx, np.float64)
+    stats = np.empty(4, np.float64)
+    idx = np.empty(n_ctx, np.int32)
+    cnt = np.zeros(1, np.int64)
+    rc = _load().spark_ref_spark_attention(_ptr(k1c), _ptr(k2c), _ptr(vc), _ptr(q), n_ctx, d_attn, r,
+                                           int(k), int(bool(skip_inactive)), _ptr(y), _ptr(s), _ptr(p),
+                                           _ptr(g), _ptr(stats), _ptr(idx), _ptr(cnt))
+    _check(rc, "spark_attention")
+    m = int(cnt[0])
+    return SparkAttention(y, s, p, g, float(stats[0]), float(stats[1]), float(stats[2]),
+                          float(stats[3]), idx[:m].copy(), m)
 
 
 def union_of(index_sets) -> np.ndarray:

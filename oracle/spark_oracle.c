@@ -1,5 +1,6 @@
 /*
- * CPU oracle for the Spark-FFN sparse decode path (Spark Transformer, arXiv 2506.06644).
+ * CPU oracle for the Spark-FFN sparse decode path and the Spark-attention decode path
+ * (Spark Transformer, arXiv 2506.06644).
  *
  * TEST INFRASTRUCTURE ONLY.  This file is the plain, slow, double-precision statement of
  * what the path computes, written from the paper's definitions.  It shares no code, header,
@@ -15,8 +16,12 @@
  * routines; count ~ k on Gaussian rows; nesting with the sort-based top-m set by brute
  * force; zero/shift structure; affine and permutation equivariance; variational optimality;
  * GEMV / gathered-sum steps vs. float64 matmul; sparse == dense; the FLOP identities of
- * Eq.3/Eq.4.  The numeric values of y for the Gemma-shaped layers have no printed example
- * in the paper: they are pinned only through the composition of these steps.
+ * Eq.3/Eq.4.  Spark attention (Eq.7): the gated softmax lookup with library softmax /
+ * logaddexp when every key is kept; the sort-based top-m set and the softmax restricted to it;
+ * closed forms (zero gate keys and identical values give ln 2 times the value; identity values
+ * expose p_i g_i; constant scores give 0); shift and permutation invariance; kept count ~ k.
+ * The numeric values of y for the Gemma-shaped layers and caches have no printed example in
+ * the paper: they are pinned only through the composition of these steps.
  */
 #include <math.h>
 #include <stdint.h>
@@ -317,5 +322,102 @@ int spark_ref_spark_ffn(const float* k1n, const float* k2n, const float* vn, con
     macs[2] = mac3;
   }
   free(s); free(a); free(u); free(idx);
+  return REF_OK;
+}
+
+/* Entrywise softplus, log(1 + exp(x)), evaluated without overflow. */
+double spark_ref_softplus(double x) { return x > 0.0 ? x + log1p(exp(-x)) : log1p(exp(x)); }
+
+/*
+ * One head of Spark attention for one query (Eq.7, with Top_k^(-inf) as described after
+ * Eq.11).  Caches are token-major ("row format"): k1c[n_ctx][r] holds the first r entries of
+ * every key, k2c[n_ctx][d_attn - r] the rest, vc[n_ctx][d_attn] the values.
+ *
+ *   s_i = sum_{t<r} k1c[i][t] * q[t]                              predictor scores
+ *   a   = StatTop_k^(-inf)(s):  a_i = s_i - theta if s_i > theta, else -inf
+ *   p   = softmax(a)            (entries at -inf get weight 0)
+ *   g_i = softplus( sum_{t<d_attn-r} k2c[i][t] * q[r+t] )
+ *   y_c = sum_i p_i * g_i * vc[i][c]
+ *
+ * Readings where the paper is silent: when n_ctx <= k every key is kept (the FLOP count uses
+ * min{k, n_ctx}), i.e. theta = -inf and a = s; when no score exceeds theta (all scores
+ * equal) the softmax has nothing to normalise and y = 0.  No 1/sqrt(d) factor is applied:
+ * Eq.5 and Eq.7 carry none (a caller folds it into q).
+ * Outputs (any may be NULL): y[d_attn], s[n_ctx], p[n_ctx], g[n_ctx] (0 where p_i = 0 and
+ * skip_inactive is set), stats[4] = {mean, std, Q, theta}, idx[count], count.
+ */
+int spark_ref_spark_attention(const float* k1c, const float* k2c, const float* vc, const float* q,
+                              int64_t n_ctx, int64_t d_attn, int64_t r, int64_t k,
+                              int skip_inactive, double* y, double* s_out, double* p_out,
+                              double* g_out, double* stats, int32_t* idx_out, int64_t* count_out) {
+  if (!k1c || !k2c || !vc || !q) return REF_ERR_NULL;
+  if (n_ctx < 1 || d_attn < 2 || r < 1 || r > d_attn - 1) return REF_ERR_SHAPE;
+  if (k < 1) return REF_ERR_K;
+  const int64_t r2 = d_attn - r;
+  double* s = (double*)malloc((size_t)n_ctx * sizeof(double));
+  double* a = (double*)malloc((size_t)n_ctx * sizeof(double));
+  double* p = (double*)malloc((size_t)n_ctx * sizeof(double));
+  double* g = (double*)malloc((size_t)n_ctx * sizeof(double));
+  int32_t* idx = (int32_t*)malloc((size_t)n_ctx * sizeof(int32_t));
+  if (!s || !a || !p || !g || !idx) {
+    free(s); free(a); free(p); free(g); free(idx);
+    return REF_ERR_SHAPE;
+  }
+  for (int64_t i = 0; i < n_ctx; ++i) {
+    double acc = 0.0;
+    for (int64_t t = 0; t < r; ++t) acc += (double)k1c[i * r + t] * (double)q[t];
+    s[i] = acc;
+  }
+  double st[4] = {0.0, 0.0, 0.0, -INFINITY};
+  int64_t m = 0;
+  if (n_ctx <= k) {
+    for (int64_t i = 0; i < n_ctx; ++i) {
+      a[i] = s[i];
+      idx[i] = (int32_t)i;
+    }
+    m = n_ctx;
+  } else {
+    const int rc = spark_ref_stat_topk(s, n_ctx, k, REF_FILL_NEG_INF, a, st, idx, &m);
+    if (rc != REF_OK) {
+      free(s); free(a); free(p); free(g); free(idx);
+      return rc;
+    }
+  }
+  /* softmax over the kept entries, shifted by their maximum */
+  double amax = -INFINITY;
+  for (int64_t i = 0; i < n_ctx; ++i)
+    if (a[i] > amax) amax = a[i];
+  double den = 0.0;
+  for (int64_t i = 0; i < n_ctx; ++i) {
+    p[i] = a[i] == -INFINITY ? 0.0 : exp(a[i] - amax);
+    den += p[i];
+  }
+  for (int64_t i = 0; i < n_ctx; ++i) p[i] = den > 0.0 ? p[i] / den : 0.0;
+  for (int64_t i = 0; i < n_ctx; ++i) {
+    if (skip_inactive && p[i] == 0.0) {
+      g[i] = 0.0;
+      continue;
+    }
+    double acc = 0.0;
+    for (int64_t t = 0; t < r2; ++t) acc += (double)k2c[i * r2 + t] * (double)q[r + t];
+    g[i] = spark_ref_softplus(acc);
+  }
+  if (y) {
+    for (int64_t c = 0; c < d_attn; ++c) {
+      double acc = 0.0;
+      for (int64_t i = 0; i < n_ctx; ++i) {
+        if (skip_inactive && p[i] == 0.0) continue;
+        acc += p[i] * g[i] * (double)vc[i * d_attn + c];
+      }
+      y[c] = acc;
+    }
+  }
+  if (s_out) memcpy(s_out, s, (size_t)n_ctx * sizeof(double));
+  if (p_out) memcpy(p_out, p, (size_t)n_ctx * sizeof(double));
+  if (g_out) memcpy(g_out, g, (size_t)n_ctx * sizeof(double));
+  if (idx_out) memcpy(idx_out, idx, (size_t)m * sizeof(int32_t));
+  if (stats) memcpy(stats, st, sizeof(st));
+  if (count_out) *count_out = m;
+  free(s); free(a); free(p); free(g); free(idx);
   return REF_OK;
 }

@@ -423,3 +423,99 @@ def test_rows_entry_equals_vector_entry(oracle):
         assert np.all(out.idx[r, one.count:] == -1)
     one_thread = oracle.stat_topk_rows(x, 40, threads=1)
     assert np.array_equal(one_thread.y, out.y)
+
+
+# --------------------------------------------------------------------------- Spark attention (Eq.7)
+def _attn_case(seed, n_ctx, d_attn, r, scale=0.125):
+    rng = np.random.default_rng(seed)
+    k1c = (rng.standard_normal((n_ctx, r)) * scale).astype(np.float32)
+    k2c = (rng.standard_normal((n_ctx, d_attn - r)) * scale).astype(np.float32)
+    vc = rng.standard_normal((n_ctx, d_attn)).astype(np.float32)
+    q = rng.standard_normal(d_attn).astype(np.float32)
+    return k1c, k2c, vc, q
+
+
+def test_softplus_values(oracle):
+    assert oracle.softplus(0.0) == pytest.approx(math.log(2.0), rel=1e-15)
+    for x in (-745.0, -40.0, -3.0, -1e-9, 1e-9, 0.5, 3.0, 40.0, 700.0, 1e6):
+        assert oracle.softplus(x) == pytest.approx(float(np.logaddexp(0.0, x)), rel=1e-14, abs=1e-300)
+    assert oracle.softplus(800.0) == 800.0 and oracle.softplus(-800.0) == 0.0
+
+
+def test_attention_with_every_key_kept_is_the_gated_softmax_lookup(oracle):
+    """n_ctx <= k: Top_k keeps everything, and Eq.7 is V (softmax(K1^T q1) * softplus(K2^T q2)), here
+    with library softmax / logaddexp / matmul in float64."""
+    for n_ctx, k in ((40, 40), (17, 256), (1, 5)):
+        k1c, k2c, vc, q = _attn_case(n_ctx, n_ctx, 32, 16)
+        o = oracle.spark_attention(k1c, k2c, vc, q, k)
+        s = k1c.astype(np.float64) @ q[:16].astype(np.float64)
+        p = scipy.special.softmax(s)
+        g = np.logaddexp(0.0, k2c.astype(np.float64) @ q[16:].astype(np.float64))
+        assert o.count == n_ctx and o.theta == -math.inf
+        np.testing.assert_allclose(o.p, p, rtol=1e-12, atol=0)
+        np.testing.assert_allclose(o.y, vc.astype(np.float64).T @ (p * g), rtol=1e-11, atol=1e-14)
+
+
+def test_attention_keeps_the_exact_top_m_and_renormalises_over_it(oracle):
+    """n_ctx > k: the kept keys are the sort-based top-m (m = count), weights are the softmax over those
+    keys only, everything else has weight exactly 0."""
+    for seed, n_ctx, k in ((1, 300, 30), (2, 1000, 256), (3, 64, 1), (4, 64, 63)):
+        k1c, k2c, vc, q = _attn_case(seed, n_ctx, 48, 24)
+        o = oracle.spark_attention(k1c, k2c, vc, q, k)
+        s = k1c.astype(np.float64) @ q[:24].astype(np.float64)
+        theta = s.mean() + s.std(ddof=1) * float(scipy.special.ndtri(1.0 - k / n_ctx))
+        assert o.theta == pytest.approx(theta, rel=1e-11)
+        top = np.sort(np.argsort(-s, kind="stable")[:o.count])
+        assert np.array_equal(o.idx, top)
+        p = np.zeros(n_ctx)
+        p[top] = scipy.special.softmax(s[top])
+        np.testing.assert_allclose(o.p, p, rtol=1e-12, atol=0)
+        assert np.all(o.p[np.setdiff1d(np.arange(n_ctx), top)] == 0.0)
+        g = np.logaddexp(0.0, k2c.astype(np.float64) @ q[24:].astype(np.float64))
+        np.testing.assert_allclose(o.y, vc.astype(np.float64).T @ (p * g), rtol=1e-11, atol=1e-14)
+        sk = oracle.spark_attention(k1c, k2c, vc, q, k, skip_inactive=True)
+        assert np.array_equal(sk.y, o.y)          # the skipped terms are exact zeros
+
+
+def test_attention_closed_forms(oracle):
+    k1c, k2c, vc, q = _attn_case(7, 500, 32, 16)
+    # (1) zero gate keys: softplus(0) = ln 2; identical values: the convex combination is that value
+    v = np.linspace(-1.0, 2.0, 32).astype(np.float32)
+    o = oracle.spark_attention(k1c, np.zeros_like(k2c), np.tile(v, (500, 1)), q, 40)
+    np.testing.assert_allclose(o.y, math.log(2.0) * v.astype(np.float64), rtol=1e-13)
+    # (2) values = identity: y_i = p_i g_i on the kept keys, exactly 0 elsewhere, and sum y_i / g_i = 1
+    k1c, k2c, _, q = _attn_case(8, 32, 32, 16)
+    o = oracle.spark_attention(k1c, k2c, np.eye(32, dtype=np.float32), q, 6)
+    assert 1 <= o.count < 32
+    np.testing.assert_allclose(o.y, o.p * o.g, rtol=1e-14)
+    off = np.setdiff1d(np.arange(32), o.idx)
+    assert np.all(o.y[off] == 0.0)
+    assert float(np.sum(o.y[o.idx] / o.g[o.idx])) == pytest.approx(1.0, rel=1e-13)
+    # (3) constant scores: nothing exceeds theta = mean, the lookup returns 0
+    k1c, k2c, vc, q = _attn_case(9, 100, 32, 16)
+    o = oracle.spark_attention(np.zeros_like(k1c), k2c, vc, q, 10)
+    assert o.count == 0 and np.all(o.y == 0.0) and o.theta == 0.0
+
+
+def test_attention_invariances(oracle):
+    k1c, k2c, vc, q = _attn_case(11, 400, 32, 16)
+    base = oracle.spark_attention(k1c, k2c, vc, q, 50)
+    # adding a constant to every score (an extra key feature 1, query entry c) shifts theta and nothing else
+    c = 3.25
+    k1x = np.concatenate([k1c, np.ones((400, 1), np.float32)], axis=1)
+    qx = np.concatenate([q[:16], [np.float32(c)], q[16:]])
+    sh = oracle.spark_attention(k1x, k2c, np.concatenate([vc, vc[:, :1]], axis=1), qx, 50)
+    assert sh.theta == pytest.approx(base.theta + c, rel=1e-12)
+    assert np.array_equal(sh.idx, base.idx)
+    np.testing.assert_allclose(sh.y[:32], base.y, rtol=1e-10, atol=1e-13)
+    # permuting the keys (rows of all three caches) permutes the kept set and leaves y alone
+    perm = np.random.default_rng(12).permutation(400)
+    pm = oracle.spark_attention(k1c[perm], k2c[perm], vc[perm], q, 50)
+    assert np.array_equal(np.sort(perm[pm.idx]), base.idx)
+    np.testing.assert_allclose(pm.y, base.y, rtol=1e-11, atol=1e-14)
+    # kept count ~ k on Gaussian scores (Theorem 1), at the paper's attention setting
+    counts = []
+    for seed in range(20):
+        a, b, v, qq = _attn_case(100 + seed, 8192, 32, 16)
+        counts.append(oracle.spark_attention(a, b, v, qq, 256).count)
+    assert abs(np.mean(counts) - 256) < 12 and min(counts) > 180 and max(counts) < 340
