@@ -172,6 +172,51 @@ spark_status spark_ffn_dense_decode_layers(const spark_ffn_layer* layers, int32_
                                            int64_t ldq, float* y, void* workspace,
                                            size_t workspace_bytes, void* hip_stream);
 
+/* ------------------------------------------------------------------------------------------
+ * Spark-attention decode (Section 2.2, Eq.7): for every query head,
+ *   y = V ( softmax( Top_k^(-inf)( K1^T q[:r] ) ) * softplus( K2^T q[r:] ) ),
+ * Top_k^(-inf) being the statistical top-k of Eq.9-11 that sets the entries at or below the
+ * threshold to -inf (text after Eq.11).  One cache serves `group` query heads.
+ * Host struct holding device pointers; the caches are token-major:
+ */
+typedef struct {
+  int32_t n_ctx;      /* cached keys, 1 .. 16384                                   */
+  int32_t d_attn;     /* head width                                                */
+  int32_t r;          /* predictor width, 1 <= r <= d_attn-1                       */
+  int32_t k;          /* keys to keep, >= 1; n_ctx <= k keeps every key            */
+  int32_t cdtype;     /* spark_dtype of the three caches                           */
+  int32_t group;      /* query heads sharing this cache, 1 .. 4                    */
+  const void* k1c;    /* [n_ctx][r]           first r entries of every key         */
+  const void* k2c;    /* [n_ctx][d_attn - r]  the rest of every key                */
+  const void* vc;     /* [n_ctx][d_attn]      values                               */
+} spark_attn_head;
+
+/* Host. Bytes of device workspace spark_attn_decode needs (0 on invalid arguments). */
+size_t spark_attn_workspace_bytes(int32_t n_heads, int32_t group, int32_t n_ctx);
+
+/*
+ * One decode step of n_heads caches (host array `heads`; all must agree in n_ctx, d_attn, r,
+ * k, cdtype, group), one query per query head.
+ *
+ *   q           [n_heads][group][d_attn] of `qdtype`, contiguous                    in
+ *   y           [n_heads][group][d_attn] fp32, overwritten                          out
+ *   theta       [n_heads][group] fp32 (-inf when n_ctx <= k)                        out, optional
+ *   kept_count  [n_heads][group] int32, #{i : s_i > theta}                          out, optional
+ *   kept_idx    [n_heads][group][n_ctx] int32, ascending kept keys; entries past    out, optional
+ *               the count are left untouched
+ *   workspace   >= spark_attn_workspace_bytes(n_heads, group, n_ctx), 256-byte aligned
+ *
+ * Arithmetic: caches and q widened exactly to fp32, products and sums fp32; the softmax is
+ * evaluated as exp(s - max s) over the kept keys divided by its sum.  No 1/sqrt(d) factor is
+ * applied (Eq.7 carries none: fold it into q).  If no score exceeds theta (all scores equal)
+ * y = 0.  Supported shapes: r, d_attn - r and d_attn each a power-of-two number of 16-byte
+ * chunks (4..64 for r, 4..32 for d_attn - r, 8..64 for d_attn); others -> SHAPE.
+ */
+spark_status spark_attn_decode(const spark_attn_head* heads, int32_t n_heads, const void* q,
+                               spark_dtype qdtype, float* y, float* theta, int32_t* kept_count,
+                               int32_t* kept_idx, void* workspace, size_t workspace_bytes,
+                               void* hip_stream);
+
 /*
  * Host, synchronising.  The batch-1 entry points run as one persistent launch whose
  * wavefronts wait on each other; every such wait is bounded, and a launch that had to give

@@ -24,7 +24,8 @@ MAX_BATCH = 64
 EXPORTS = (
     "spark_status_string", "spark_version", "spark_normal_quantile", "spark_stat_topk",
     "spark_ffn_workspace_bytes", "spark_ffn_decode", "spark_ffn_decode_layers",
-    "spark_ffn_dense_decode", "spark_ffn_dense_decode_layers", "spark_ffn_check", "spark_debug_force_general", "spark_debug_tuning", "spark_debug_phases",
+    "spark_ffn_dense_decode", "spark_ffn_dense_decode_layers", "spark_ffn_check",
+    "spark_attn_workspace_bytes", "spark_attn_decode", "spark_debug_force_general", "spark_debug_tuning", "spark_debug_phases",
     "spark_debug_profile", "spark_debug_read_profile",
 )
 
@@ -40,6 +41,14 @@ class _Layer(ctypes.Structure):
         ("d_model", ctypes.c_int32), ("d_ff", ctypes.c_int32), ("r", ctypes.c_int32),
         ("k", ctypes.c_int32), ("wdtype", ctypes.c_int32), ("gelu", ctypes.c_int32),
         ("k1n", ctypes.c_void_p), ("k2n", ctypes.c_void_p), ("vn", ctypes.c_void_p),
+    ]
+
+
+class _AttnHead(ctypes.Structure):
+    _fields_ = [
+        ("n_ctx", ctypes.c_int32), ("d_attn", ctypes.c_int32), ("r", ctypes.c_int32),
+        ("k", ctypes.c_int32), ("cdtype", ctypes.c_int32), ("group", ctypes.c_int32),
+        ("k1c", ctypes.c_void_p), ("k2c", ctypes.c_void_p), ("vc", ctypes.c_void_p),
     ]
 
 
@@ -74,6 +83,10 @@ def load_library():
                                             vp, vp, vp, vp, sz, vp]
     lib.spark_ffn_dense_decode.restype = c_int
     lib.spark_ffn_dense_decode.argtypes = [ctypes.POINTER(_Layer), vp, c_int, i32, i64, vp, vp, sz, vp]
+    lib.spark_attn_workspace_bytes.restype = sz
+    lib.spark_attn_workspace_bytes.argtypes = [i32, i32, i32]
+    lib.spark_attn_decode.restype = c_int
+    lib.spark_attn_decode.argtypes = [ctypes.POINTER(_AttnHead), i32, vp, c_int, vp, vp, vp, vp, vp, sz, vp]
     lib.spark_ffn_dense_decode_layers.restype = c_int
     lib.spark_ffn_dense_decode_layers.argtypes = [ctypes.POINTER(_Layer), i32, vp, c_int, i32, i64, vp, vp, sz, vp]
     lib.spark_ffn_check.restype = c_int
@@ -188,6 +201,34 @@ def spark_ffn_dense_decode_layers(layers: Sequence[_Layer], q: torch.Tensor, y: 
     rc = load_library().spark_ffn_dense_decode_layers(
         arr, len(layers), _p(q), _dt(q), q.shape[0], q.stride(0), _p(y), _p(workspace), workspace.numel(), _stream())
     _check(rc, "spark_ffn_dense_decode_layers")
+
+
+def make_attn_head(k1c: torch.Tensor, k2c: torch.Tensor, vc: torch.Tensor, k: int, group: int = 1) -> _AttnHead:
+    """One key / value cache (token-major): k1c[n_ctx, r], k2c[n_ctx, d_attn - r], vc[n_ctx, d_attn]."""
+    n_ctx, r = k1c.shape
+    d_attn = vc.shape[1]
+    if k2c.shape != (n_ctx, d_attn - r) or vc.shape[0] != n_ctx:
+        raise ValueError("inconsistent cache shapes")
+    if not (k1c.is_contiguous() and k2c.is_contiguous() and vc.is_contiguous()):
+        raise ValueError("caches must be contiguous token-major arrays")
+    if not (k1c.dtype == k2c.dtype == vc.dtype):
+        raise ValueError("the three caches must share a dtype")
+    return _AttnHead(n_ctx, d_attn, r, int(k), _dt(k1c), int(group), k1c.data_ptr(), k2c.data_ptr(), vc.data_ptr())
+
+
+def attn_workspace_bytes(n_heads: int, group: int, n_ctx: int) -> int:
+    return int(load_library().spark_attn_workspace_bytes(int(n_heads), int(group), int(n_ctx)))
+
+
+def spark_attn_decode(heads: Sequence[_AttnHead], q: torch.Tensor, y: torch.Tensor, workspace: torch.Tensor,
+                      theta=None, kept_count=None, kept_idx=None):
+    """One decode step of Spark attention: q[n_heads, group, d_attn] -> y[n_heads, group, d_attn] (fp32)."""
+    if not q.is_contiguous():
+        raise ValueError("q must be contiguous")
+    arr = (_AttnHead * len(heads))(*heads)
+    rc = load_library().spark_attn_decode(arr, len(heads), _p(q), _dt(q), _p(y), _p(theta), _p(kept_count),
+                                          _p(kept_idx), _p(workspace), workspace.numel(), _stream())
+    _check(rc, "spark_attn_decode")
 
 
 def spark_ffn_check(workspace: torch.Tensor, d_model: int, d_ff: int, batch: int):

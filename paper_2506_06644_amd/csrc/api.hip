@@ -275,6 +275,70 @@ spark_status spark_ffn_dense_decode_layers(const spark_ffn_layer* layers, int32_
   return SPARK_OK;
 }
 
+size_t spark_attn_workspace_bytes(int32_t n_heads, int32_t group, int32_t n_ctx) {
+  if (n_heads < 1 || group < 1 || group > 4 || n_ctx < 1 || n_ctx > spark::kAttnMaxCtx) return 0;
+  return spark::attn_workspace_bytes(n_heads, group, n_ctx);
+}
+
+spark_status spark_attn_decode(const spark_attn_head* heads, int32_t n_heads, const void* q, spark_dtype qdtype,
+                               float* y, float* theta, int32_t* kept_count, int32_t* kept_idx, void* workspace,
+                               size_t workspace_bytes, void* hip_stream) {
+  if (!heads || !q || !y) return SPARK_ERR_NULL;
+  if (n_heads < 1) return SPARK_ERR_SHAPE;
+  if (!dtype_ok(qdtype)) return SPARK_ERR_DTYPE;
+  const spark_attn_head& h0 = heads[0];
+  for (int32_t i = 0; i < n_heads; ++i) {
+    const spark_attn_head& h = heads[i];
+    if (!h.k1c || !h.k2c || !h.vc) return SPARK_ERR_NULL;
+    if (!dtype_ok(h.cdtype)) return SPARK_ERR_DTYPE;
+    if (h.n_ctx != h0.n_ctx || h.d_attn != h0.d_attn || h.r != h0.r || h.k != h0.k || h.cdtype != h0.cdtype ||
+        h.group != h0.group)
+      return SPARK_ERR_SHAPE;
+    if (!aligned16(h.k1c) || !aligned16(h.k2c) || !aligned16(h.vc)) return SPARK_ERR_ALIGN;
+  }
+  if (h0.n_ctx < 1 || h0.d_attn < 2 || h0.r < 1 || h0.r > h0.d_attn - 1) return SPARK_ERR_SHAPE;
+  if (h0.k < 1) return SPARK_ERR_K;
+  spark::AttnProblem p;
+  p.n_ctx = h0.n_ctx;
+  p.d_attn = h0.d_attn;
+  p.r = h0.r;
+  p.k = h0.k;
+  p.group = h0.group;
+  p.c_bf16 = h0.cdtype == SPARK_BF16;
+  p.q_bf16 = qdtype == SPARK_BF16;
+  p.z = h0.n_ctx > h0.k ? (float)spark_normal_quantile(1.0 - (double)h0.k / (double)h0.n_ctx) : 0.f;
+  p.q = q;
+  p.y = y;
+  p.theta = theta;
+  p.count = kept_count;
+  p.idx = kept_idx;
+  if (!spark::attn_supported(p)) return SPARK_ERR_SHAPE;
+  if (!aligned16(q) || (h0.r * dtype_size(qdtype)) % 16 || (h0.d_attn * dtype_size(qdtype)) % 16) return SPARK_ERR_ALIGN;
+  if (!workspace || (reinterpret_cast<uintptr_t>(workspace) & 255u)) return SPARK_ERR_WORKSPACE;
+  if (workspace_bytes < spark_attn_workspace_bytes(n_heads, h0.group, h0.n_ctx)) return SPARK_ERR_WORKSPACE;
+  const void* k1c[spark::kAttnMaxHeads];
+  const void* k2c[spark::kAttnMaxHeads];
+  const void* vc[spark::kAttnMaxHeads];
+  hipStream_t st = static_cast<hipStream_t>(hip_stream);
+  for (int32_t base = 0; base < n_heads; base += spark::kAttnMaxHeads) {
+    const int32_t n = n_heads - base < spark::kAttnMaxHeads ? n_heads - base : spark::kAttnMaxHeads;
+    for (int32_t i = 0; i < n; ++i) {
+      k1c[i] = heads[base + i].k1c;
+      k2c[i] = heads[base + i].k2c;
+      vc[i] = heads[base + i].vc;
+    }
+    spark::AttnProblem pc = p;
+    const size_t hg0 = (size_t)base * p.group;
+    pc.q = static_cast<const char*>(q) + hg0 * p.d_attn * dtype_size(qdtype);
+    pc.y = y + hg0 * p.d_attn;
+    pc.theta = theta ? theta + hg0 : nullptr;
+    pc.count = kept_count ? kept_count + hg0 : nullptr;
+    pc.idx = kept_idx ? kept_idx + hg0 * p.n_ctx : nullptr;
+    if (spark::launch_attn_decode(pc, k1c, k2c, vc, n, workspace, st) != hipSuccess) return SPARK_ERR_DEVICE;
+  }
+  return SPARK_OK;
+}
+
 spark_status spark_ffn_check(const void* workspace, int32_t d_model, int32_t d_ff, int32_t batch,
                              void* hip_stream) {
   if (!workspace) return SPARK_ERR_WORKSPACE;

@@ -1,0 +1,363 @@
+// Spark-attention decode (Eq.7 of arXiv 2506.06644) for one query per head over token-major
+// key / value caches (gfx950):
+//
+//   y = V ( softmax( Top_k^(-inf)( K1^T q[:r] ) ) * softplus( K2^T q[r:] ) )
+//
+// with Top_k^(-inf) the statistical top-k that sets the entries at or below
+// theta = mean + std * Q(1 - k / n_ctx) to -inf (text after Eq.11).  The caches keep the
+// first r entries of every key (k1c[n_ctx][r]), the rest of the key (k2c[n_ctx][d_attn - r])
+// and the value (vc[n_ctx][d_attn]) in separate token-major arrays, so that the predictor
+// sweep reads one dense array and everything a kept key needs is one contiguous burst per
+// array (Appendix B's "row format").  Two launches for all heads of a call:
+//
+//   predict   s[h][g][i] = k1c_h[i] . q_hg[:r] for every cached key: a fully coalesced sweep
+//             (a wave instruction covers 64 / LPR consecutive keys, LPR lanes per key); the
+//             `group` query heads that share a cache are served by one pass over it.
+//   gather    one workgroup per (query head): mean / std of the scores (two passes over
+//             registers), theta, the kept keys in ascending order, then for those only the
+//             k2c and vc rows: w = exp(s - max s) * softplus(k2c[i] . q[r:]),
+//             y = sum w vc[i] / sum exp(s - max s), summed in a fixed order.
+//
+// When n_ctx <= k every key is kept (theta = -inf); when no score exceeds theta, y = 0.
+#include "spark_device.h"
+#include "spark_internal.h"
+
+namespace spark {
+
+namespace {
+
+constexpr int kKeysPerBlock = 256;   // predict: 4 waves x 64 keys
+constexpr int kGatherWavesA = 16;    // gather: waves per workgroup
+constexpr int kMaxVPT = kAttnMaxCtx / (kGatherWavesA * kWave);  // scores per thread of the gather
+
+struct AttnParams {
+  const void* k1c[kAttnMaxHeads];
+  const void* k2c[kAttnMaxHeads];
+  const void* vc[kAttnMaxHeads];
+  const void* q;      // [heads][G][d_attn]
+  float* y;           // [heads][G][d_attn]
+  float* theta;       // [heads][G]         optional
+  int32_t* count;     // [heads][G]         optional
+  int32_t* idx;       // [heads][G][n_ctx]  optional
+  float* scores;      // [heads][G][n_ctx]
+  int n_ctx, d_attn, r, G, q_bf16, keep_all;
+  float z;
+};
+
+__device__ __forceinline__ float softplus_f(float x) { return x > 0.f ? x + log1pf(expf(-x)) : log1pf(expf(x)); }
+
+// Sum over groups of LPR consecutive lanes (LPR a power of two); every lane ends with its
+// group's total.  The order of additions is fixed.
+template <int LPR>
+__device__ __forceinline__ float group_sum(float v) {
+#pragma unroll
+  for (int o = 1; o < LPR; o <<= 1) v += __shfl_xor(v, o, kWave);
+  return v;
+}
+
+// --------------------------------------------------------------------------------- predict
+template <typename WT, int LPR, int G>
+__global__ __launch_bounds__(256) void attn_predict_kernel(const AttnParams P) {
+  constexpr int VEC = Vec16<WT>::N;
+  constexpr int RPI = kWave / LPR;   // keys per wave instruction
+  constexpr int NI = kWave / RPI;    // instructions per wave (64 keys)
+  constexpr int U = NI < 8 ? NI : 8;  // loads in flight per lane
+  __shared__ float s_sh[G][kKeysPerBlock];
+  const int tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid / kWave;
+  const int h = blockIdx.y, key0 = blockIdx.x * kKeysPerBlock;
+  const int sub = lane / LPR, ch = lane % LPR;
+  float qv[G][VEC];
+#pragma unroll
+  for (int g = 0; g < G; ++g) load_q_vec<VEC>(P.q, P.q_bf16, ((int64_t)h * G + g) * P.d_attn + (int64_t)ch * VEC, qv[g]);
+  const WT* base = static_cast<const WT*>(P.k1c[h]);
+  for (int i0 = 0; i0 < NI; i0 += U) {
+    Vec16<WT> reg[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const int key = key0 + wave * kWave + (i0 + u) * RPI + sub;
+      reg[u].raw = __builtin_nontemporal_load(reinterpret_cast<const decltype(reg[u].raw)*>(
+          base + (size_t)min(key, P.n_ctx - 1) * P.r + (size_t)ch * VEC));
+    }
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+#pragma unroll
+      for (int g = 0; g < G; ++g) {
+        float acc = 0.f;
+#pragma unroll
+        for (int e = 0; e < VEC; ++e) acc += reg[u].get(e) * qv[g][e];
+        acc = group_sum<LPR>(acc);
+        if (ch == 0) s_sh[g][wave * kWave + (i0 + u) * RPI + sub] = acc;
+      }
+    }
+  }
+  __syncthreads();
+#pragma unroll
+  for (int g = 0; g < G; ++g)
+    if (key0 + tid < P.n_ctx) P.scores[((size_t)h * G + g) * P.n_ctx + key0 + tid] = s_sh[g][tid];
+}
+
+// ---------------------------------------------------------------------------------- gather
+template <int T>
+__device__ __forceinline__ float block_max(float v, float* red) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, kWave));
+  const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
+  __syncthreads();
+  if (lane == 0) red[wave] = v;
+  __syncthreads();
+  float t = red[0];
+#pragma unroll
+  for (int w = 1; w < T / kWave; ++w) t = fmaxf(t, red[w]);
+  return t;
+}
+
+// LPR2 / LPRV: lanes per k2c row / vc row (16-byte chunks); a wave step handles 64 / LPRV keys.
+template <typename WT, int LPR2, int LPRV>
+__global__ __launch_bounds__(kGatherWavesA * kWave) void attn_gather_kernel(const AttnParams P) {
+  constexpr int VEC = Vec16<WT>::N;
+  constexpr int T = kGatherWavesA * kWave;
+  constexpr int KPS = kWave / LPRV;  // keys per wave step
+  static_assert(LPR2 <= LPRV, "the gate half of a key is not longer than the value");
+  __shared__ float red[kGatherWavesA];
+  __shared__ int wcount[kGatherWavesA];
+  __shared__ float den_sh[kGatherWavesA];
+  extern __shared__ __align__(16) unsigned char dyn[];
+  float* s_sh = reinterpret_cast<float*>(dyn);                                  // [n_ctx] scores, later [16][d_attn] partial rows
+  uint16_t* list = reinterpret_cast<uint16_t*>(dyn + (size_t)max(P.n_ctx, kGatherWavesA * P.d_attn) * 4);  // [n_ctx] kept keys, ascending
+  const int tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid / kWave;
+  const int g = blockIdx.x, h = blockIdx.y, G = P.G, n = P.n_ctx;
+  const size_t hg = (size_t)h * G + g;
+  const float* sc = P.scores + hg * n;
+
+  float v[kMaxVPT];
+  float sum = 0.f, vmax = -INFINITY;
+#pragma unroll
+  for (int k = 0; k < kMaxVPT; ++k) {
+    const int j = tid + T * k;
+    v[k] = j < n ? sc[j] : 0.f;
+    sum += v[k];
+    if (j < n) {
+      vmax = fmaxf(vmax, v[k]);
+      s_sh[j] = v[k];
+    }
+  }
+  float theta = -INFINITY;
+  if (!P.keep_all) {
+    const float mean = block_sum<T>(sum, red) / (float)n;
+    float sq = 0.f;
+#pragma unroll
+    for (int k = 0; k < kMaxVPT; ++k) {
+      const float d = tid + T * k < n ? v[k] - mean : 0.f;
+      sq += d * d;
+    }
+    const float m2 = block_sum<T>(sq, red);
+    theta = mean + sqrtf(m2 / (float)(n - 1)) * P.z;
+  }
+  const float smax = block_max<T>(vmax, red);
+  // ordered compaction of the kept keys
+  int running = 0;
+#pragma unroll
+  for (int k = 0; k < kMaxVPT; ++k) {
+    if (T * k >= n) break;  // uniform
+    const int j = tid + T * k;
+    const bool on = j < n && v[k] > theta;
+    const unsigned long long m = __ballot(on);
+    __syncthreads();
+    if (lane == 0) wcount[wave] = __popcll(m);
+    __syncthreads();
+    int before = 0, total = 0;
+#pragma unroll
+    for (int w = 0; w < kGatherWavesA; ++w) {
+      before += w < wave ? wcount[w] : 0;
+      total += wcount[w];
+    }
+    if (on) {
+      const int pos = running + before + lanes_below(m);
+      list[pos] = (uint16_t)j;
+      if (P.idx) P.idx[hg * n + pos] = j;
+    }
+    running += total;
+  }
+  const int count = running;
+  if (tid == 0) {
+    if (P.theta) P.theta[hg] = theta;
+    if (P.count) P.count[hg] = count;
+  }
+  __syncthreads();
+
+  // the kept keys, KPS per wave step, dealt to the waves round-robin in ascending order
+  const int sub = lane / LPRV, ch = lane % LPRV;
+  const int r2 = P.d_attn - P.r;
+  const WT* k2 = static_cast<const WT*>(P.k2c[h]);
+  const WT* vv = static_cast<const WT*>(P.vc[h]);
+  float q2[VEC];
+  load_q_vec<VEC>(P.q, P.q_bf16, (int64_t)hg * P.d_attn + P.r + (int64_t)(ch < LPR2 ? ch : 0) * VEC, q2);
+  if (ch >= LPR2) {
+#pragma unroll
+    for (int e = 0; e < VEC; ++e) q2[e] = 0.f;
+  }
+  float acc[VEC];
+#pragma unroll
+  for (int e = 0; e < VEC; ++e) acc[e] = 0.f;
+  float den = 0.f;
+  const int stride = kGatherWavesA * KPS;
+  auto fetch = [&](int t, Vec16<WT>& kr, Vec16<WT>& vr, float& s) {
+    const int key = list[min(t, max(count - 1, 0))];
+    kr = load_vec16<WT>(k2 + (size_t)key * r2 + (size_t)(ch < LPR2 ? ch : 0) * VEC);
+    vr = load_vec16<WT>(vv + (size_t)key * P.d_attn + (size_t)ch * VEC);
+    s = s_sh[key];
+  };
+  auto use = [&](int t, const Vec16<WT>& kr, const Vec16<WT>& vr, float s) {
+    float gd = 0.f;
+#pragma unroll
+    for (int e = 0; e < VEC; ++e) gd += kr.get(e) * q2[e];
+    gd = group_sum<LPRV>(gd);
+    const float e0 = t < count ? expf(s - smax) : 0.f;
+    const float w = e0 * softplus_f(gd);
+    den += e0;
+#pragma unroll
+    for (int e = 0; e < VEC; ++e) acc[e] += w * vr.get(e);
+  };
+  if (count > 0) {
+    Vec16<WT> ka, va, kb, vb;
+    float sa, sb;
+    int t = wave * KPS + sub;
+    fetch(t, ka, va, sa);
+    for (; t - sub < count; t += 2 * stride) {  // uniform bound: the wave's first key of the step
+      fetch(t + stride, kb, vb, sb);
+      use(t, ka, va, sa);
+      fetch(t + 2 * stride, ka, va, sa);
+      use(t + stride, kb, vb, sb);
+    }
+  }
+  // the KPS lane groups of a wave, then the waves in order
+#pragma unroll
+  for (int o = LPRV; o < kWave; o <<= 1) {
+#pragma unroll
+    for (int e = 0; e < VEC; ++e) acc[e] += __shfl_xor(acc[e], o, kWave);
+    den += __shfl_xor(den, o, kWave);
+  }
+  __syncthreads();  // s_sh is reused for the waves' rows
+  if (sub == 0) {
+#pragma unroll
+    for (int e = 0; e < VEC; ++e) s_sh[(size_t)wave * P.d_attn + ch * VEC + e] = acc[e];
+  }
+  if (lane == 0) den_sh[wave] = den;
+  __syncthreads();
+  for (int c = tid; c < P.d_attn; c += T) {
+    float num = 0.f, dn = 0.f;
+#pragma unroll
+    for (int w = 0; w < kGatherWavesA; ++w) {
+      num += s_sh[(size_t)w * P.d_attn + c];
+      dn += den_sh[w];
+    }
+    P.y[hg * P.d_attn + c] = count > 0 ? num / dn : 0.f;
+  }
+}
+
+bool pow2(int v) { return v > 0 && (v & (v - 1)) == 0; }
+
+template <typename WT, int LPR>
+hipError_t launch_predict_g(const AttnParams& P, dim3 grid, hipStream_t st) {
+  switch (P.G) {
+    case 1: hipLaunchKernelGGL((attn_predict_kernel<WT, LPR, 1>), grid, dim3(256), 0, st, P); break;
+    case 2: hipLaunchKernelGGL((attn_predict_kernel<WT, LPR, 2>), grid, dim3(256), 0, st, P); break;
+    case 3: hipLaunchKernelGGL((attn_predict_kernel<WT, LPR, 3>), grid, dim3(256), 0, st, P); break;
+    case 4: hipLaunchKernelGGL((attn_predict_kernel<WT, LPR, 4>), grid, dim3(256), 0, st, P); break;
+    default: return hipErrorInvalidValue;
+  }
+  return hipGetLastError();
+}
+template <typename WT>
+hipError_t launch_predict_t(const AttnParams& P, int lpr, dim3 grid, hipStream_t st) {
+  switch (lpr) {
+    case 4: return launch_predict_g<WT, 4>(P, grid, st);
+    case 8: return launch_predict_g<WT, 8>(P, grid, st);
+    case 16: return launch_predict_g<WT, 16>(P, grid, st);
+    case 32: return launch_predict_g<WT, 32>(P, grid, st);
+    case 64: return launch_predict_g<WT, 64>(P, grid, st);
+    default: return hipErrorInvalidValue;
+  }
+}
+
+template <typename WT, int LPR2, int LPRV>
+hipError_t launch_gather_k(const AttnParams& P, dim3 grid, size_t dyn, hipStream_t st) {
+  const void* kern = reinterpret_cast<const void*>(attn_gather_kernel<WT, LPR2, LPRV>);
+  const hipError_t e = hipFuncSetAttribute(kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)dyn);
+  if (e != hipSuccess) return e;
+  hipLaunchKernelGGL((attn_gather_kernel<WT, LPR2, LPRV>), grid, dim3(kGatherWavesA * kWave), dyn, st, P);
+  return hipGetLastError();
+}
+template <typename WT, int LPRV>
+hipError_t launch_gather_v(const AttnParams& P, int lpr2, dim3 grid, size_t dyn, hipStream_t st) {
+  if constexpr (LPRV >= 4) if (lpr2 == 4) return launch_gather_k<WT, 4, LPRV>(P, grid, dyn, st);
+  if constexpr (LPRV >= 8) if (lpr2 == 8) return launch_gather_k<WT, 8, LPRV>(P, grid, dyn, st);
+  if constexpr (LPRV >= 16) if (lpr2 == 16) return launch_gather_k<WT, 16, LPRV>(P, grid, dyn, st);
+  if constexpr (LPRV >= 32) if (lpr2 == 32) return launch_gather_k<WT, 32, LPRV>(P, grid, dyn, st);
+  return hipErrorInvalidValue;
+}
+template <typename WT>
+hipError_t launch_gather_t(const AttnParams& P, int lpr2, int lprv, dim3 grid, size_t dyn, hipStream_t st) {
+  switch (lprv) {
+    case 8: return launch_gather_v<WT, 8>(P, lpr2, grid, dyn, st);
+    case 16: return launch_gather_v<WT, 16>(P, lpr2, grid, dyn, st);
+    case 32: return launch_gather_v<WT, 32>(P, lpr2, grid, dyn, st);
+    case 64: return launch_gather_v<WT, 64>(P, lpr2, grid, dyn, st);
+    default: return hipErrorInvalidValue;
+  }
+}
+
+}  // namespace
+
+bool attn_supported(const AttnProblem& p) {
+  const int vec = p.c_bf16 ? 8 : 4;
+  if (p.r % vec || (p.d_attn - p.r) % vec || p.d_attn % vec) return false;
+  const int l1 = p.r / vec, l2 = (p.d_attn - p.r) / vec, lv = p.d_attn / vec;
+  return pow2(l1) && l1 >= 4 && l1 <= 64 && pow2(l2) && l2 >= 4 && pow2(lv) && lv >= 8 && lv <= 64 && l2 <= 32 &&
+         p.n_ctx >= 1 && p.n_ctx <= kAttnMaxCtx && p.group >= 1 && p.group <= 4;
+}
+
+size_t attn_workspace_bytes(int n_heads, int group, int n_ctx) {
+  const size_t per = ((size_t)group * n_ctx * 4 + 255) / 256 * 256;
+  return per * (size_t)(n_heads < kAttnMaxHeads ? n_heads : kAttnMaxHeads);
+}
+
+hipError_t launch_attn_decode(const AttnProblem& p, const void* const* k1c, const void* const* k2c,
+                              const void* const* vc, int n_heads, void* workspace, hipStream_t st) {
+  const int vec = p.c_bf16 ? 8 : 4;
+  const int l1 = p.r / vec, l2 = (p.d_attn - p.r) / vec, lv = p.d_attn / vec;
+  hipError_t err = hipSuccess;
+  for (int base = 0; base < n_heads && err == hipSuccess; base += kAttnMaxHeads) {
+    const int H = n_heads - base < kAttnMaxHeads ? n_heads - base : kAttnMaxHeads;
+    AttnParams P;
+    for (int i = 0; i < kAttnMaxHeads; ++i) {
+      P.k1c[i] = i < H ? k1c[base + i] : nullptr;
+      P.k2c[i] = i < H ? k2c[base + i] : nullptr;
+      P.vc[i] = i < H ? vc[base + i] : nullptr;
+    }
+    const size_t hg0 = (size_t)base * p.group;
+    P.q = static_cast<const char*>(p.q) + hg0 * p.d_attn * (p.q_bf16 ? 2 : 4);
+    P.y = p.y + hg0 * p.d_attn;
+    P.theta = p.theta ? p.theta + hg0 : nullptr;
+    P.count = p.count ? p.count + hg0 : nullptr;
+    P.idx = p.idx ? p.idx + hg0 * p.n_ctx : nullptr;
+    P.scores = static_cast<float*>(workspace);
+    P.n_ctx = p.n_ctx;
+    P.d_attn = p.d_attn;
+    P.r = p.r;
+    P.G = p.group;
+    P.q_bf16 = p.q_bf16;
+    P.keep_all = p.n_ctx <= p.k;
+    P.z = p.z;
+    const dim3 gp((p.n_ctx + kKeysPerBlock - 1) / kKeysPerBlock, H);
+    err = p.c_bf16 ? launch_predict_t<bf16_t>(P, l1, gp, st) : launch_predict_t<float>(P, l1, gp, st);
+    if (err != hipSuccess) return err;
+    const size_t rows = (size_t)(p.n_ctx > kGatherWavesA * p.d_attn ? p.n_ctx : kGatherWavesA * p.d_attn);
+    const size_t dyn = rows * 4 + (size_t)p.n_ctx * 2 + 16;
+    const dim3 gg(p.group, H);
+    err = p.c_bf16 ? launch_gather_t<bf16_t>(P, l2, lv, gg, dyn, st) : launch_gather_t<float>(P, l2, lv, gg, dyn, st);
+  }
+  return err;
+}
+
+}  // namespace spark

@@ -82,4 +82,23 @@ void phased_batch_set_tuning(int predict_tiles_per_workgroup, int k2_tiles_per_w
 hipError_t launch_ffn_phased_batch(const FfnProblem& p0, const void* const* k1n, const void* const* k2n,
                                    const void* const* vn, int n_layers, void* scratch, hipStream_t st);
 
+// Spark-attention decode: one query per head over token-major caches, all heads of a call
+// in two launches (up to kAttnMaxHeads caches per pair of launches; longer lists are chained).
+constexpr int kAttnMaxHeads = 64;
+constexpr int kAttnMaxCtx = 16384;
+struct AttnProblem {
+  int n_ctx, d_attn, r, k, group;
+  int c_bf16, q_bf16;
+  float z;          // Q(1 - k / n_ctx) (unused when n_ctx <= k)
+  const void* q;    // [n_heads][group][d_attn]
+  float* y;         // [n_heads][group][d_attn]
+  float* theta;     // [n_heads][group]         optional
+  int32_t* count;   // [n_heads][group]         optional
+  int32_t* idx;     // [n_heads][group][n_ctx]  optional
+};
+bool attn_supported(const AttnProblem& p);
+size_t attn_workspace_bytes(int n_heads, int group, int n_ctx);
+hipError_t launch_attn_decode(const AttnProblem& p, const void* const* k1c, const void* const* k2c,
+                              const void* const* vc, int n_heads, void* workspace, hipStream_t st);
+
 }  // namespace spark

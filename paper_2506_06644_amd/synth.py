@@ -79,6 +79,26 @@ def tokens(shape: FFNShape, batch: int, seed: int, dtype=torch.bfloat16, device=
     return q.to(dtype).contiguous()
 
 
+def attn_caches(n_ctx: int, d_attn: int, r: int, seed: int, dtype=torch.bfloat16, device="cpu"):
+    """Token-major caches of one key / value head: k1c[n_ctx, r], k2c[n_ctx, d_attn - r] with
+    keys ~ N(0, 1 / d_attn), vc[n_ctx, d_attn] ~ N(0, 1), each rounded once to ``dtype``."""
+    g = _gen(seed, device)
+    scale = float(d_attn) ** -0.5
+
+    def draw(cols, sc):
+        w = torch.randn(n_ctx, cols, generator=g, device=device, dtype=torch.float32)
+        return (w * sc).to(dtype).contiguous()
+
+    return draw(r, scale), draw(d_attn - r, scale), draw(d_attn, 1.0)
+
+
+def attn_queries(n_heads: int, group: int, d_attn: int, seed: int, dtype=torch.bfloat16, device="cpu"):
+    """q[n_heads, group, d_attn] ~ N(0, 1), rounded once to ``dtype``."""
+    g = _gen(seed, device)
+    q = torch.randn(n_heads, group, d_attn, generator=g, device=device, dtype=torch.float32)
+    return q.to(dtype).contiguous()
+
+
 def topk_rows(rows: int, n: int, seed: int = 4242, dtype=torch.float32, device="cpu",
               outlier_prob: float = 0.01, chunk: int = 1024):
     """Activation matrix for the standalone row-wise statistical top-k."""

@@ -1,0 +1,105 @@
+"""GPU parity of the Spark-attention decode path (Eq.7) against the CPU oracle, through the C ABI."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2506_06644_amd import binding, synth
+
+from parity_util import TOL_BF16, TOL_BF16_TIGHT, TOL_F32, assert_active_set, rel_l2
+
+pytestmark = pytest.mark.gpu
+DEV = torch.device("cuda:0") if torch.cuda.is_available() else None
+
+
+def run_gpu_attention(caches, q, k, group):
+    """caches: list of (k1c, k2c, vc) CPU tensors, one per cache; q: CPU [n_heads, group, d_attn]."""
+    H = len(caches)
+    n_ctx, d_attn = caches[0][2].shape
+    cd = [[t.to(DEV) for t in c] for c in caches]
+    heads = [binding.make_attn_head(c[0], c[1], c[2], k, group) for c in cd]
+    ws = torch.empty(binding.attn_workspace_bytes(H, group, n_ctx), dtype=torch.uint8, device=DEV)
+    y = torch.full((H, group, d_attn), float("nan"), device=DEV)
+    theta = torch.zeros(H, group, device=DEV)
+    cnt = torch.zeros(H, group, dtype=torch.int32, device=DEV)
+    idx = torch.full((H, group, n_ctx), -1, dtype=torch.int32, device=DEV)
+    binding.spark_attn_decode(heads, q.to(DEV), y, ws, theta, cnt, idx)
+    torch.cuda.synchronize()
+    return dict(y=y.cpu().numpy(), theta=theta.cpu().numpy(), count=cnt.cpu().numpy(), idx=idx.cpu().numpy())
+
+
+def check_attention(caches, q, k, out, tol, what="", heads=None):
+    """Kept sets identical except inside the |s - theta| < 1e-3 std band; y within `tol` wherever the
+    sets agree (a key that flips at the threshold carries a softmax weight that is not small)."""
+    compared = 0
+    for h in (range(len(caches)) if heads is None else heads):
+        k1c, k2c, vc = (synth.to_oracle(t) for t in caches[h])
+        for g in range(q.shape[1]):
+            o = oracle.spark_attention(k1c, k2c, vc, synth.to_oracle(q[h, g]), k, skip_inactive=True)
+            tag = f"{what} head {h} query {g}"
+            m = int(out["count"][h, g])
+            gi = out["idx"][h, g, :m]
+            assert np.all(np.diff(gi) > 0), f"{tag}: indices not ascending"
+            assert np.all(out["idx"][h, g, m:] == -1), f"{tag}: wrote past count"
+            if np.isinf(o.theta):
+                assert np.isinf(out["theta"][h, g]) and out["theta"][h, g] < 0 and m == len(o.s)
+            else:
+                assert abs(out["theta"][h, g] - o.theta) <= 1e-5 * o.std + 1e-6 * abs(o.theta), tag
+                assert_active_set(gi, o.s, o.theta, o.std, tag)
+            if np.array_equal(gi, o.idx):
+                err = rel_l2(out["y"][h, g], o.y)
+                assert err <= tol, f"{tag}: y rel L2 {err:.3e} > {tol}"
+                compared += 1
+    return compared
+
+
+@pytest.mark.parametrize("dtype", [torch.bfloat16, torch.float32])
+@pytest.mark.parametrize("n_ctx,k,group", [(1, 8, 1), (5, 8, 2), (100, 100, 1), (300, 30, 3), (1000, 64, 4),
+                                           (4099, 256, 2)])
+def test_small_heads(dtype, n_ctx, k, group):
+    d_attn, r, H = 64, 32, 3
+    caches = [synth.attn_caches(n_ctx, d_attn, r, 700 + h, dtype) for h in range(H)]
+    q = synth.attn_queries(H, group, d_attn, 800 + n_ctx, dtype)
+    out = run_gpu_attention(caches, q, k, group)
+    n = check_attention(caches, q, k, out, TOL_F32 if dtype == torch.float32 else TOL_BF16_TIGHT, f"n_ctx={n_ctx}")
+    assert n >= H * group - 1
+
+
+@pytest.mark.parametrize("n_ctx", [4096, 8192])
+def test_paper_attention_shape(n_ctx):
+    """d_attn 256, r 128, at most 256 attended keys, two query heads per cache (the Gemma-2 2B setting)."""
+    H, group, d_attn, r, k = 8, 2, 256, 128, 256
+    caches = [synth.attn_caches(n_ctx, d_attn, r, 900 + h, torch.bfloat16) for h in range(H)]
+    q = synth.attn_queries(H, group, d_attn, 901, torch.bfloat16)
+    out = run_gpu_attention(caches, q, k, group)
+    n = check_attention(caches, q, k, out, TOL_BF16_TIGHT, f"paper n_ctx={n_ctx}")
+    assert n >= H * group - 2
+    assert np.all(np.abs(out["count"] - 256) < 6 * 16)
+
+
+def test_more_caches_than_one_launch_holds_and_mixed_query_dtype():
+    H, group, d_attn, r, k, n_ctx = 70, 1, 64, 32, 20, 400
+    caches = [synth.attn_caches(n_ctx, d_attn, r, 1000 + h, torch.bfloat16) for h in range(H)]
+    q = synth.attn_queries(H, group, d_attn, 1001, torch.float32)
+    out = run_gpu_attention(caches, q, k, group)
+    n = check_attention(caches, q, k, out, TOL_BF16_TIGHT, "70 caches", heads=[0, 1, 63, 64, 69])
+    assert n >= 4
+
+
+def test_constant_scores_give_zero():
+    n_ctx, d_attn, r = 500, 64, 32
+    k1c, k2c, vc = synth.attn_caches(n_ctx, d_attn, r, 5, torch.bfloat16)
+    q = synth.attn_queries(1, 2, d_attn, 6, torch.bfloat16)
+    out = run_gpu_attention([(torch.zeros_like(k1c), k2c, vc)], q, 50, 2)
+    assert np.all(out["y"] == 0.0) and np.all(out["count"] == 0) and np.all(out["theta"] == 0.0)
+
+
+def test_rejects_unsupported_shapes():
+    k1c, k2c, vc = (t.to(DEV) for t in synth.attn_caches(64, 48, 24, 1, torch.bfloat16))   # 3 chunks per key half
+    head = binding.make_attn_head(k1c, k2c, vc, 8)
+    ws = torch.empty(1 << 20, dtype=torch.uint8, device=DEV)
+    q = synth.attn_queries(1, 1, 48, 2, torch.bfloat16).to(DEV)
+    y = torch.empty(1, 1, 48, device=DEV)
+    with pytest.raises(binding.SparkError) as e:
+        binding.spark_attn_decode([head], q, y, ws)
+    assert e.value.code == 2
