@@ -187,6 +187,48 @@ def other_configs(torch, binding, synth, dev, main_shape, L, weights, layers):
     return res
 
 
+def attention_bench(torch, binding, synth, dev, with_cpu):
+    """One decode step of Spark attention at the paper's Gemma-2-2B setting: 26 layers x 4 key / value
+    heads (104 caches of 8192 keys, token-major, bf16), 2 query heads per cache, d_attn 256, r 128, at
+    most 256 attended keys.  Algorithmic bytes: all of the k1c caches, plus the k2c and vc rows of the
+    kept keys of every query head."""
+    H, group, n_ctx, d_attn, r, k = 104, 2, 8192, 256, 128, 256
+    caches = [synth.attn_caches(n_ctx, d_attn, r, 3000 + h, torch.bfloat16, dev) for h in range(H)]
+    q = synth.attn_queries(H, group, d_attn, 3999, torch.bfloat16, dev)
+    heads = [binding.make_attn_head(c[0], c[1], c[2], k, group) for c in caches]
+    ws = torch.empty(binding.attn_workspace_bytes(H, group, n_ctx), dtype=torch.uint8, device=dev)
+    y = torch.empty(H, group, d_attn, device=dev)
+    cnt = torch.zeros(H, group, dtype=torch.int32, device=dev)
+    binding.spark_attn_decode(heads, q, y, ws, kept_count=cnt)
+    torch.cuda.synchronize()
+    kept = cnt.cpu().numpy().astype(float)
+
+    def step():
+        binding.spark_attn_decode(heads, q, y, ws)
+
+    gpu_s, _ = time_region(step, 100, 10, torch)
+    per = gpu_s / 100
+    nbytes = 2.0 * (H * n_ctx * r + kept.sum() * ((d_attn - r) + d_attn))
+    dense_bytes = 2.0 * H * n_ctx * 2 * d_attn
+    out = {"workload": f"{H} caches x {n_ctx} keys, {group} query heads per cache, d_attn={d_attn} r={r} k={k}, bf16",
+           "us_per_step": per * 1e6, "query_heads_per_s": H * group / per, "kept_mean": float(kept.mean()),
+           "kept_min": int(kept.min()), "kept_max": int(kept.max()), "algorithmic_bytes": nbytes,
+           "achieved_gbs": nbytes / per / 1e9, "hbm_frac": nbytes / per / 1e9 / HBM_PEAK_GBS,
+           "dense_attention_bytes": dense_bytes}
+    if with_cpu:
+        import oracle
+        k1c, k2c, vc = (synth.to_oracle(t) for t in caches[0])
+        q0 = synth.to_oracle(q[0, 0])
+        t0, n = time.perf_counter(), 0
+        while time.perf_counter() - t0 < 4.0:
+            oracle.spark_attention(k1c, k2c, vc, q0, k, skip_inactive=True)
+            n += 1
+        dt = time.perf_counter() - t0
+        out["cpu_baseline"] = {"value": n / dt, "unit": "query heads/s", "cores": 1, "kind": "oracle",
+                               "sample": f"{n} evaluations of query head 0 of the same step, {dt:.1f} s"}
+    return out
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -198,6 +240,7 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-dense", action="store_true")
     ap.add_argument("--no-stat-topk", action="store_true")
+    ap.add_argument("--no-attention", action="store_true")
     ap.add_argument("--no-extra", action="store_true",
                     help="skip the single-layer-call timing and the batched / 9B-shaped configurations")
     ap.add_argument("--calibrate-copy", action="store_true",
@@ -349,6 +392,9 @@ def main():
 
     if not args.no_stat_topk:
         out["stat_topk"] = stat_topk_bench(torch, binding, synth, dev, not args.no_cpu_baseline)
+
+    if not args.no_attention:
+        out["attention"] = attention_bench(torch, binding, synth, dev, not args.no_cpu_baseline)
 
     if not args.no_cpu_baseline:
         wcpu = tuple(synth.to_oracle(t) for t in weights[0])

@@ -28,6 +28,7 @@ namespace {
 
 constexpr int kKeysPerBlock = 256;   // predict: 4 waves x 64 keys
 constexpr int kGatherWavesA = 16;    // gather: waves per workgroup
+constexpr int kChunk = 4096;         // kept keys handled per pass of the gather
 constexpr int kMaxVPT = kAttnMaxCtx / (kGatherWavesA * kWave);  // scores per thread of the gather
 
 struct AttnParams {
@@ -119,8 +120,9 @@ __global__ __launch_bounds__(kGatherWavesA * kWave) void attn_gather_kernel(cons
   constexpr int KPS = kWave / LPRV;  // keys per wave step
   static_assert(LPR2 <= LPRV, "the gate half of a key is not longer than the value");
   __shared__ float red[kGatherWavesA];
-  __shared__ int wcount[kGatherWavesA];
-  __shared__ float den_sh[kGatherWavesA];
+  __shared__ int wcnt[kMaxVPT * kGatherWavesA];
+  __shared__ int woff[kMaxVPT * kGatherWavesA + 1];
+  __shared__ float w_sh[kChunk];  // gate products, then weights, by list position within the chunk
   extern __shared__ __align__(16) unsigned char dyn[];
   float* s_sh = reinterpret_cast<float*>(dyn);                                  // [n_ctx] scores, later [16][d_attn] partial rows
   uint16_t* list = reinterpret_cast<uint16_t*>(dyn + (size_t)max(P.n_ctx, kGatherWavesA * P.d_attn) * 4);  // [n_ctx] kept keys, ascending
@@ -154,30 +156,42 @@ __global__ __launch_bounds__(kGatherWavesA * kWave) void attn_gather_kernel(cons
     theta = mean + sqrtf(m2 / (float)(n - 1)) * P.z;
   }
   const float smax = block_max<T>(vmax, red);
-  // ordered compaction of the kept keys
-  int running = 0;
+  // ordered compaction of the kept keys: key j = tid + T * k, so the order is k, then wave, then
+  // lane; one scan over the (k, wave) counts gives every wave its offsets
+  unsigned long long bal[kMaxVPT];
 #pragma unroll
   for (int k = 0; k < kMaxVPT; ++k) {
-    if (T * k >= n) break;  // uniform
     const int j = tid + T * k;
-    const bool on = j < n && v[k] > theta;
-    const unsigned long long m = __ballot(on);
-    __syncthreads();
-    if (lane == 0) wcount[wave] = __popcll(m);
-    __syncthreads();
-    int before = 0, total = 0;
+    bal[k] = __ballot(j < n && v[k] > theta);
+    if (lane == 0) wcnt[k * kGatherWavesA + wave] = __popcll(bal[k]);
+  }
+  __syncthreads();
+  if (wave == 0) {
+    int run = 0;
+    for (int base = 0; base < kMaxVPT * kGatherWavesA; base += kWave) {
+      const int c = wcnt[base + lane];
+      int inc = c;
 #pragma unroll
-    for (int w = 0; w < kGatherWavesA; ++w) {
-      before += w < wave ? wcount[w] : 0;
-      total += wcount[w];
+      for (int o = 1; o < kWave; o <<= 1) {
+        const int t = __shfl_up(inc, o, kWave);
+        if (lane >= o) inc += t;
+      }
+      woff[base + lane] = run + inc - c;
+      run += __shfl(inc, kWave - 1, kWave);
     }
-    if (on) {
-      const int pos = running + before + lanes_below(m);
+    if (lane == 0) woff[kMaxVPT * kGatherWavesA] = run;
+  }
+  __syncthreads();
+#pragma unroll
+  for (int k = 0; k < kMaxVPT; ++k) {
+    const int j = tid + T * k;
+    if ((bal[k] >> lane) & 1ull) {
+      const int pos = woff[k * kGatherWavesA + wave] + lanes_below(bal[k]);
       list[pos] = (uint16_t)j;
       if (P.idx) P.idx[hg * n + pos] = j;
     }
-    running += total;
   }
+  const int running = woff[kMaxVPT * kGatherWavesA];
   const int count = running;
   if (tid == 0) {
     if (P.theta) P.theta[hg] = theta;
@@ -185,73 +199,100 @@ __global__ __launch_bounds__(kGatherWavesA * kWave) void attn_gather_kernel(cons
   }
   __syncthreads();
 
-  // the kept keys, KPS per wave step, dealt to the waves round-robin in ascending order
-  const int sub = lane / LPRV, ch = lane % LPRV;
+  // The kept keys in three steps per chunk of kChunk list positions, so that the exponential
+  // and the softplus are evaluated once per key by one thread each (inside the row loops a wave
+  // would evaluate them for only 64 / LPRV keys per instruction, and they would dominate):
+  //   gate     gd[pos] = k2c[key] . q[r:], 64 / LPR2 keys per wave step
+  //   weights  w[pos] = exp(s - max s) * softplus(gd[pos]); the denominator sums exp(s - max s)
+  //   values   acc += w[pos] * vc[key], 64 / LPRV keys per wave step
+  constexpr int KPG = kWave / LPR2;
   const int r2 = P.d_attn - P.r;
   const WT* k2 = static_cast<const WT*>(P.k2c[h]);
   const WT* vv = static_cast<const WT*>(P.vc[h]);
+  const int gsub = lane / LPR2, gch = lane % LPR2;
+  const int sub = lane / LPRV, ch = lane % LPRV;
   float q2[VEC];
-  load_q_vec<VEC>(P.q, P.q_bf16, (int64_t)hg * P.d_attn + P.r + (int64_t)(ch < LPR2 ? ch : 0) * VEC, q2);
-  if (ch >= LPR2) {
-#pragma unroll
-    for (int e = 0; e < VEC; ++e) q2[e] = 0.f;
-  }
+  load_q_vec<VEC>(P.q, P.q_bf16, (int64_t)hg * P.d_attn + P.r + (int64_t)gch * VEC, q2);
   float acc[VEC];
 #pragma unroll
   for (int e = 0; e < VEC; ++e) acc[e] = 0.f;
-  float den = 0.f;
-  const int stride = kGatherWavesA * KPS;
-  auto fetch = [&](int t, Vec16<WT>& kr, Vec16<WT>& vr, float& s) {
-    const int key = list[min(t, max(count - 1, 0))];
-    kr = load_vec16<WT>(k2 + (size_t)key * r2 + (size_t)(ch < LPR2 ? ch : 0) * VEC);
-    vr = load_vec16<WT>(vv + (size_t)key * P.d_attn + (size_t)ch * VEC);
-    s = s_sh[key];
-  };
-  auto use = [&](int t, const Vec16<WT>& kr, const Vec16<WT>& vr, float s) {
-    float gd = 0.f;
+  float den_mine = 0.f;
+  for (int c0 = 0; c0 < count; c0 += kChunk) {
+    const int cn = min(kChunk, count - c0);  // positions of this chunk
+    {
+      constexpr int D = 4;
+      const int gstride = kGatherWavesA * KPG;
+      auto gfetch = [&](int p, Vec16<WT>& kr) {
+        const int key = list[c0 + min(p, cn - 1)];
+        kr = load_vec16<WT>(k2 + (size_t)key * r2 + (size_t)gch * VEC);
+      };
+      auto guse = [&](int p, const Vec16<WT>& kr) {
+        float gd = 0.f;
 #pragma unroll
-    for (int e = 0; e < VEC; ++e) gd += kr.get(e) * q2[e];
-    gd = group_sum<LPRV>(gd);
-    const float e0 = t < count ? expf(s - smax) : 0.f;
-    const float w = e0 * softplus_f(gd);
-    den += e0;
+        for (int e = 0; e < VEC; ++e) gd += kr.get(e) * q2[e];
+        gd = group_sum<LPR2>(gd);
+        if (gch == 0 && p < cn) w_sh[p] = gd;
+      };
+      Vec16<WT> kr[D];
+      const int p0 = wave * KPG + gsub;
 #pragma unroll
-    for (int e = 0; e < VEC; ++e) acc[e] += w * vr.get(e);
-  };
-  if (count > 0) {
-    Vec16<WT> ka, va, kb, vb;
-    float sa, sb;
-    int t = wave * KPS + sub;
-    fetch(t, ka, va, sa);
-    for (; t - sub < count; t += 2 * stride) {  // uniform bound: the wave's first key of the step
-      fetch(t + stride, kb, vb, sb);
-      use(t, ka, va, sa);
-      fetch(t + 2 * stride, ka, va, sa);
-      use(t + stride, kb, vb, sb);
+      for (int d = 0; d < D; ++d) gfetch(p0 + d * gstride, kr[d]);
+      for (int p = p0; p - gsub < cn; p += D * gstride) {  // uniform bound
+#pragma unroll
+        for (int d = 0; d < D; ++d) {
+          guse(p + d * gstride, kr[d]);
+          gfetch(p + (d + D) * gstride, kr[d]);
+        }
+      }
     }
+    // the first value rows of the chunk are requested before the weights are formed
+    constexpr int DV = 4;
+    const int vstride = kGatherWavesA * KPS;
+    auto vfetch = [&](int p, Vec16<WT>& vr) {
+      const int key = list[c0 + min(p, cn - 1)];
+      vr = load_vec16<WT>(vv + (size_t)key * P.d_attn + (size_t)ch * VEC);
+    };
+    Vec16<WT> vr[DV];
+    const int v0 = wave * KPS + sub;
+#pragma unroll
+    for (int d = 0; d < DV; ++d) vfetch(v0 + d * vstride, vr[d]);
+    __syncthreads();
+    for (int p = tid; p < cn; p += T) {
+      const float e0 = expf(s_sh[list[c0 + p]] - smax);
+      den_mine += e0;
+      w_sh[p] = e0 * softplus_f(w_sh[p]);
+    }
+    __syncthreads();
+    for (int p = v0; p - sub < cn; p += DV * vstride) {  // uniform bound
+#pragma unroll
+      for (int d = 0; d < DV; ++d) {
+        const int pp = p + d * vstride;
+        const float w = pp < cn ? w_sh[pp] : 0.f;
+#pragma unroll
+        for (int e = 0; e < VEC; ++e) acc[e] += w * vr[d].get(e);
+        vfetch(pp + DV * vstride, vr[d]);
+      }
+    }
+    __syncthreads();  // w_sh is rewritten by the next chunk
   }
+  const float den_total = block_sum<T>(den_mine, red);
   // the KPS lane groups of a wave, then the waves in order
 #pragma unroll
   for (int o = LPRV; o < kWave; o <<= 1) {
 #pragma unroll
     for (int e = 0; e < VEC; ++e) acc[e] += __shfl_xor(acc[e], o, kWave);
-    den += __shfl_xor(den, o, kWave);
   }
   __syncthreads();  // s_sh is reused for the waves' rows
   if (sub == 0) {
 #pragma unroll
     for (int e = 0; e < VEC; ++e) s_sh[(size_t)wave * P.d_attn + ch * VEC + e] = acc[e];
   }
-  if (lane == 0) den_sh[wave] = den;
   __syncthreads();
   for (int c = tid; c < P.d_attn; c += T) {
-    float num = 0.f, dn = 0.f;
+    float num = 0.f;
 #pragma unroll
-    for (int w = 0; w < kGatherWavesA; ++w) {
-      num += s_sh[(size_t)w * P.d_attn + c];
-      dn += den_sh[w];
-    }
-    P.y[hg * P.d_attn + c] = count > 0 ? num / dn : 0.f;
+    for (int w = 0; w < kGatherWavesA; ++w) num += s_sh[(size_t)w * P.d_attn + c];
+    P.y[hg * P.d_attn + c] = count > 0 ? num / den_total : 0.f;
   }
 }
 

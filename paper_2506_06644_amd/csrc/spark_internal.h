@@ -84,7 +84,7 @@ hipError_t launch_ffn_phased_batch(const FfnProblem& p0, const void* const* k1n,
 
 // Spark-attention decode: one query per head over token-major caches, all heads of a call
 // in two launches (up to kAttnMaxHeads caches per pair of launches; longer lists are chained).
-constexpr int kAttnMaxHeads = 64;
+constexpr int kAttnMaxHeads = 128;
 constexpr int kAttnMaxCtx = 16384;
 struct AttnProblem {
   int n_ctx, d_attn, r, k, group;
