@@ -26,7 +26,8 @@ namespace spark {
 
 namespace {
 
-constexpr int kKeysPerBlock = 256;   // predict: 4 waves x 64 keys
+constexpr int kKeysPerWave = 64;
+constexpr int kKeysPerBlock = 4 * kKeysPerWave;   // predict: 4 waves
 constexpr int kGatherWavesA = 16;    // gather: waves per workgroup
 constexpr int kChunk = 4096;         // kept keys handled per pass of the gather
 constexpr int kMaxVPT = kAttnMaxCtx / (kGatherWavesA * kWave);  // scores per thread of the gather
@@ -49,33 +50,56 @@ __device__ __forceinline__ float softplus_f(float x) { return x > 0.f ? x + log1
 
 // Sum over groups of LPR consecutive lanes (LPR a power of two); every lane ends with its
 // group's total.  The order of additions is fixed.
+template <int CTRL>
+__device__ __forceinline__ float dpp_add(float x) {
+  const int t = __builtin_amdgcn_update_dpp(0, __float_as_int(x), CTRL, 0xf, 0xf, false);
+  return x + __int_as_float(t);
+}
 template <int LPR>
 __device__ __forceinline__ float group_sum(float v) {
+  // inside a row of 16 lanes: quad swaps and the two row mirrors (DPP, no LDS crossbar)
+  if (LPR >= 2) v = dpp_add<0xB1>(v);   // quad_perm [1,0,3,2]
+  if (LPR >= 4) v = dpp_add<0x4E>(v);   // quad_perm [2,3,0,1]
+  if (LPR >= 8) v = dpp_add<0x141>(v);  // row_half_mirror
+  if (LPR >= 16) v = dpp_add<0x140>(v); // row_mirror
 #pragma unroll
-  for (int o = 1; o < LPR; o <<= 1) v += __shfl_xor(v, o, kWave);
+  for (int o = 16; o < LPR; o <<= 1) v += __shfl_xor(v, o, kWave);
   return v;
 }
 
 // --------------------------------------------------------------------------------- predict
-template <typename WT, int LPR, int G>
+typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ float dot2_bf16(uint32_t a, uint32_t b, float c) {
+  return __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2_t, a), __builtin_bit_cast(bf16x2_t, b), c, false);
+}
+__device__ __forceinline__ uint32_t raw_dword(const Vec16<bf16_t>& v, int d) { return v.raw[d]; }
+__device__ __forceinline__ uint32_t raw_dword(const Vec16<float>& v, int d) { return __float_as_uint(v.raw[d]); }
+
+// QB: bf16 caches and bf16 queries (the packed pairs go straight into the two-element dot
+// product; bf16 products are exact in fp32).
+template <typename WT, int LPR, int G, bool QB>
 __global__ __launch_bounds__(256) void attn_predict_kernel(const AttnParams P) {
   constexpr int VEC = Vec16<WT>::N;
   constexpr int RPI = kWave / LPR;   // keys per wave instruction
-  constexpr int NI = kWave / RPI;    // instructions per wave (64 keys)
+  constexpr int NI = kKeysPerWave / RPI;    // instructions per wave
   constexpr int U = NI < 8 ? NI : 8;  // loads in flight per lane
   __shared__ float s_sh[G][kKeysPerBlock];
   const int tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid / kWave;
   const int h = blockIdx.y, key0 = blockIdx.x * kKeysPerBlock;
   const int sub = lane / LPR, ch = lane % LPR;
-  float qv[G][VEC];
+  float qv[QB ? 1 : G][VEC];
+  u32x4 qp[QB ? G : 1];
 #pragma unroll
-  for (int g = 0; g < G; ++g) load_q_vec<VEC>(P.q, P.q_bf16, ((int64_t)h * G + g) * P.d_attn + (int64_t)ch * VEC, qv[g]);
+  for (int g = 0; g < G; ++g) {
+    if constexpr (QB) qp[g] = *reinterpret_cast<const u32x4*>(static_cast<const uint16_t*>(P.q) + ((int64_t)h * G + g) * P.d_attn + (int64_t)ch * VEC);
+    else load_q_vec<VEC>(P.q, P.q_bf16, ((int64_t)h * G + g) * P.d_attn + (int64_t)ch * VEC, qv[g]);
+  }
   const WT* base = static_cast<const WT*>(P.k1c[h]);
   for (int i0 = 0; i0 < NI; i0 += U) {
     Vec16<WT> reg[U];
 #pragma unroll
     for (int u = 0; u < U; ++u) {
-      const int key = key0 + wave * kWave + (i0 + u) * RPI + sub;
+      const int key = key0 + wave * kKeysPerWave + (i0 + u) * RPI + sub;
       reg[u].raw = __builtin_nontemporal_load(reinterpret_cast<const decltype(reg[u].raw)*>(
           base + (size_t)min(key, P.n_ctx - 1) * P.r + (size_t)ch * VEC));
     }
@@ -84,17 +108,23 @@ __global__ __launch_bounds__(256) void attn_predict_kernel(const AttnParams P) {
 #pragma unroll
       for (int g = 0; g < G; ++g) {
         float acc = 0.f;
+        if constexpr (QB) {
 #pragma unroll
-        for (int e = 0; e < VEC; ++e) acc += reg[u].get(e) * qv[g][e];
+          for (int d = 0; d < 4; ++d) acc = dot2_bf16(raw_dword(reg[u], d), qp[g][d], acc);
+        } else {
+#pragma unroll
+          for (int e = 0; e < VEC; ++e) acc += reg[u].get(e) * qv[g][e];
+        }
         acc = group_sum<LPR>(acc);
-        if (ch == 0) s_sh[g][wave * kWave + (i0 + u) * RPI + sub] = acc;
+        if (ch == 0) s_sh[g][wave * kKeysPerWave + (i0 + u) * RPI + sub] = acc;
       }
     }
   }
   __syncthreads();
 #pragma unroll
   for (int g = 0; g < G; ++g)
-    if (key0 + tid < P.n_ctx) P.scores[((size_t)h * G + g) * P.n_ctx + key0 + tid] = s_sh[g][tid];
+    for (int t = tid; t < kKeysPerBlock; t += 256)
+      if (key0 + t < P.n_ctx) P.scores[((size_t)h * G + g) * P.n_ctx + key0 + t] = s_sh[g][t];
 }
 
 // ---------------------------------------------------------------------------------- gather
@@ -298,25 +328,25 @@ __global__ __launch_bounds__(kGatherWavesA * kWave) void attn_gather_kernel(cons
 
 bool pow2(int v) { return v > 0 && (v & (v - 1)) == 0; }
 
-template <typename WT, int LPR>
+template <typename WT, int LPR, bool QB>
 hipError_t launch_predict_g(const AttnParams& P, dim3 grid, hipStream_t st) {
   switch (P.G) {
-    case 1: hipLaunchKernelGGL((attn_predict_kernel<WT, LPR, 1>), grid, dim3(256), 0, st, P); break;
-    case 2: hipLaunchKernelGGL((attn_predict_kernel<WT, LPR, 2>), grid, dim3(256), 0, st, P); break;
-    case 3: hipLaunchKernelGGL((attn_predict_kernel<WT, LPR, 3>), grid, dim3(256), 0, st, P); break;
-    case 4: hipLaunchKernelGGL((attn_predict_kernel<WT, LPR, 4>), grid, dim3(256), 0, st, P); break;
+    case 1: hipLaunchKernelGGL((attn_predict_kernel<WT, LPR, 1, QB>), grid, dim3(256), 0, st, P); break;
+    case 2: hipLaunchKernelGGL((attn_predict_kernel<WT, LPR, 2, QB>), grid, dim3(256), 0, st, P); break;
+    case 3: hipLaunchKernelGGL((attn_predict_kernel<WT, LPR, 3, QB>), grid, dim3(256), 0, st, P); break;
+    case 4: hipLaunchKernelGGL((attn_predict_kernel<WT, LPR, 4, QB>), grid, dim3(256), 0, st, P); break;
     default: return hipErrorInvalidValue;
   }
   return hipGetLastError();
 }
-template <typename WT>
+template <typename WT, bool QB>
 hipError_t launch_predict_t(const AttnParams& P, int lpr, dim3 grid, hipStream_t st) {
   switch (lpr) {
-    case 4: return launch_predict_g<WT, 4>(P, grid, st);
-    case 8: return launch_predict_g<WT, 8>(P, grid, st);
-    case 16: return launch_predict_g<WT, 16>(P, grid, st);
-    case 32: return launch_predict_g<WT, 32>(P, grid, st);
-    case 64: return launch_predict_g<WT, 64>(P, grid, st);
+    case 4: return launch_predict_g<WT, 4, QB>(P, grid, st);
+    case 8: return launch_predict_g<WT, 8, QB>(P, grid, st);
+    case 16: return launch_predict_g<WT, 16, QB>(P, grid, st);
+    case 32: return launch_predict_g<WT, 32, QB>(P, grid, st);
+    case 64: return launch_predict_g<WT, 64, QB>(P, grid, st);
     default: return hipErrorInvalidValue;
   }
 }
@@ -391,7 +421,8 @@ hipError_t launch_attn_decode(const AttnProblem& p, const void* const* k1c, cons
     P.keep_all = p.n_ctx <= p.k;
     P.z = p.z;
     const dim3 gp((p.n_ctx + kKeysPerBlock - 1) / kKeysPerBlock, H);
-    err = p.c_bf16 ? launch_predict_t<bf16_t>(P, l1, gp, st) : launch_predict_t<float>(P, l1, gp, st);
+    if (p.c_bf16) err = p.q_bf16 ? launch_predict_t<bf16_t, true>(P, l1, gp, st) : launch_predict_t<bf16_t, false>(P, l1, gp, st);
+    else err = launch_predict_t<float, false>(P, l1, gp, st);
     if (err != hipSuccess) return err;
     const size_t rows = (size_t)(p.n_ctx > kGatherWavesA * p.d_attn ? p.n_ctx : kGatherWavesA * p.d_attn);
     const size_t dyn = rows * 4 + (size_t)p.n_ctx * 2 + 16;
