@@ -303,3 +303,14 @@ def test_batch_sizes_around_the_token_blocks():
         q = synth.tokens(sh, batch, 56 + batch, torch.bfloat16)
         out = run_gpu_ffn(sh, weights, q, via_layers=True)
         check_ffn_against_oracle(sh, weights, q, out, TOL_BF16_TIGHT, what=f"B={batch}")
+
+
+@pytest.mark.parametrize("batch", [2, 16, 40])
+def test_matrix_core_path_with_a_ragged_number_of_neurons(batch):
+    """d_ff that is neither a multiple of the 16-row tiles nor of the 64-bit mask words, on the batched
+    matrix-core path (rows of 32-element multiples, so that path is the one that runs)."""
+    sh = synth.FFNShape("ragged-dff", 256, 1000, 128, 77)
+    weights = synth.ffn_stack(sh, 3, base_seed=611, dtype=torch.bfloat16)
+    q = synth.tokens(sh, batch, 612 + batch, torch.bfloat16)
+    out = run_gpu_ffn(sh, weights, q, via_layers=True)
+    check_ffn_against_oracle(sh, weights, q, out, TOL_BF16_TIGHT, what=f"ragged d_ff B={batch}")
