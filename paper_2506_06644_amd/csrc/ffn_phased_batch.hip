@@ -100,27 +100,29 @@ template <int SPW, int NLW> __device__ __forceinline__ int k_step_t(int s, int w
 // store in this loop would drain the prefetch at every tile.  A tile past `tile_end` is
 // requested through a buffer descriptor without records: the loads are issued all the same
 // (their number in flight stays a compile-time constant, the waits are exact) but touch no
-// memory.  With HAS_SIDE a loader also fetches, together with a tile, one value per (item,
-// lane) that the emit step will need (`pre(tile, item)`), and passes it on through LDS.
+// memory.
 //
 // Emit wave e sums the loaders' partials of the items e, e + kEmitWaves, ... in loader order
 // and hands D[row 4 * kg + i][token nb * 16 + ri] (item = nb * 4 + i) to `emit(tile, item,
-// value, side)`, which stores.  One LDS-only barrier per tile; the partial buffers alternate,
+// value, side)`, which stores.  With HAS_SIDE, `side` is a value per (item, lane) that the emit
+// wave fetched two tiles ahead with `pre(tile, item)` (fetched by the loaders instead, these
+// small scattered loads sit in front of the weight rows in the in-order return queue and cost
+// a third of the kernel).  One LDS-only barrier per tile; the partial buffers alternate,
 // and a loader that writes a buffer again two tiles later has passed the barrier of the tile
 // in between, which the emit waves reach only after they have finished reading it.
 constexpr int kRowThreads = kRowWavesAll * kWave;
 template <int NB, int SPW>
 constexpr int tile_depth() { return 2; }  // tiles in flight per loader wave (deeper did not pay: see the notes on measurements)  // DEPTH * SPW * 4 registers hold the tiles in flight
 template <int NB>
-constexpr size_t rows_lds_bytes() { return (size_t)2 * (10 + 1) * NB * 4 * kWave * sizeof(float); }
+constexpr size_t rows_lds_bytes() { return (size_t)2 * 10 * NB * 4 * kWave * sizeof(float); }
 template <int NB, int SPW, int NLW, bool HAS_SIDE, typename RowOf, typename Pre, typename Emit>
 __device__ __forceinline__ void rows_times_tokens(const bf16_t* __restrict__ w, uint32_t w_bytes, int K,
                                                   const bf16_t* __restrict__ q, int64_t ldq, int qoff, int B,
                                                   int tile0, int ntiles, int tile_end,
                                                   float* red_raw, RowOf row_of, Pre pre, Emit emit) {
   constexpr int kRowWaves = NLW, kEmitWaves = kRowWavesAll - NLW;
-  constexpr int IPW = (NB * 4 + kRowWaves - 1) / kRowWaves;  // side values a loader fetches per tile
-  float(*red)[kRowWaves + 1][NB * 4][kWave] = reinterpret_cast<float(*)[kRowWaves + 1][NB * 4][kWave]>(red_raw);
+  constexpr int IPE = (NB * 4 + kEmitWaves - 1) / kEmitWaves;  // items an emit wave handles per tile
+  float(*red)[kRowWaves][NB * 4][kWave] = reinterpret_cast<float(*)[kRowWaves][NB * 4][kWave]>(red_raw);
   constexpr int DEPTH = tile_depth<NB, SPW>();
   const int lane = threadIdx.x & (kWave - 1);
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
@@ -128,15 +130,34 @@ __device__ __forceinline__ void rows_times_tokens(const bf16_t* __restrict__ w, 
   if (wave >= kRowWaves) {
     // ------------------------------------------------------------------ emit wave
     const int ew = wave - kRowWaves;
-    for (int i = 0; i < ntiles; ++i) {
+    float side[2][IPE];
+    auto prefetch = [&](int t, float(&sv)[IPE]) {
+      if constexpr (HAS_SIDE) {
+#pragma unroll
+        for (int k = 0; k < IPE; ++k) sv[k] = pre(t, min(ew + kEmitWaves * k, NB * 4 - 1));
+      }
+    };
+    auto emit_tile = [&](int i, const float(&sv)[IPE]) {
       const int buf = i & 1;
       lds_barrier();
-      for (int item = ew; item < NB * 4; item += kEmitWaves) {
-        float v = 0.f;
 #pragma unroll
-        for (int wv = 0; wv < kRowWaves; ++wv) v += red[buf][wv][item][lane];
-        emit(tile0 + i, item, v, HAS_SIDE ? red[buf][kRowWaves][item][lane] : 0.f);
+      for (int k = 0; k < IPE; ++k) {
+        const int item = ew + kEmitWaves * k;
+        if (item < NB * 4) {
+          float v = 0.f;
+#pragma unroll
+          for (int wv = 0; wv < kRowWaves; ++wv) v += red[buf][wv][item][lane];
+          emit(tile0 + i, item, v, HAS_SIDE ? sv[k] : 0.f);
+        }
       }
+    };
+    prefetch(tile0, side[0]);
+    prefetch(tile0 + 1, side[1]);
+    for (int i = 0; i < ntiles; i += 2) {  // ntiles is even
+      emit_tile(i, side[0]);
+      prefetch(tile0 + i + 2, side[0]);
+      emit_tile(i + 1, side[1]);
+      prefetch(tile0 + i + 3, side[1]);
     }
     return;
   }
@@ -154,13 +175,9 @@ __device__ __forceinline__ void rows_times_tokens(const bf16_t* __restrict__ w, 
       if (!ok) qf[s][nb] = u32x4{0u, 0u, 0u, 0u};
     }
   }
-  auto load_tile = [&](int t, u32x4(&a)[SPW], float(&side)[IPW]) {
+  auto load_tile = [&](int t, u32x4(&a)[SPW]) {
     const __amdgpu_buffer_rsrc_t rs =
         __builtin_amdgcn_make_buffer_rsrc(const_cast<bf16_t*>(w), 0, t < tile_end ? (int)w_bytes : 0, 0x00020000);
-    if constexpr (HAS_SIDE) {
-#pragma unroll
-      for (int i = 0; i < IPW; ++i) side[i] = pre(t, min(wave + kRowWaves * i, NB * 4 - 1));
-    }
     const uint32_t row_off = (uint32_t)row_of(t, ri) * (uint32_t)K * 2u;
 #pragma unroll
     for (int s = 0; s < SPW; ++s) {
@@ -168,7 +185,7 @@ __device__ __forceinline__ void rows_times_tokens(const bf16_t* __restrict__ w, 
       a[s] = __builtin_amdgcn_raw_buffer_load_b128(rs, (int)(row_off + (uint32_t)((ks < nsteps ? ks : 0) * 4 + kg) * 16u), 0, 0);
     }
   };
-  auto process = [&](const u32x4(&a)[SPW], const float(&side)[IPW], int buf) {
+  auto process = [&](const u32x4(&a)[SPW], int buf) {
     f32x4 acc[NB];
 #pragma unroll
     for (int nb = 0; nb < NB; ++nb) acc[nb] = f32x4{0.f, 0.f, 0.f, 0.f};
@@ -180,21 +197,16 @@ __device__ __forceinline__ void rows_times_tokens(const bf16_t* __restrict__ w, 
     for (int nb = 0; nb < NB; ++nb)
 #pragma unroll
       for (int e = 0; e < 4; ++e) red[buf][wave][nb * 4 + e][lane] = acc[nb][e];
-    if constexpr (HAS_SIDE) {
-#pragma unroll
-      for (int i = 0; i < IPW; ++i) red[buf][kRowWaves][min(wave + kRowWaves * i, NB * 4 - 1)][lane] = side[i];
-    }
     lds_barrier();
   };
   u32x4 a[DEPTH][SPW];
-  float sd[DEPTH][IPW];
 #pragma unroll
-  for (int d = 0; d < DEPTH; ++d) load_tile(tile0 + d, a[d], sd[d]);
+  for (int d = 0; d < DEPTH; ++d) load_tile(tile0 + d, a[d]);
   for (int i = 0; i < ntiles; i += DEPTH) {  // ntiles is a multiple of DEPTH (an even number)
 #pragma unroll
     for (int d = 0; d < DEPTH; ++d) {
-      process(a[d], sd[d], d & 1);
-      load_tile(tile0 + i + d + DEPTH, a[d], sd[d]);
+      process(a[d], d & 1);
+      load_tile(tile0 + i + d + DEPTH, a[d]);
     }
   }
 }
