@@ -102,10 +102,11 @@ template <int SPW, int NLW> __device__ __forceinline__ int k_step_t(int s, int w
 // (their number in flight stays a compile-time constant, the waits are exact) but touch no
 // memory.
 //
-// Emit wave e sums the loaders' partials of the items e, e + kEmitWaves, ... in loader order
-// and hands D[row 4 * kg + i][token nb * 16 + ri] (item = nb * 4 + i) to `emit(tile, item,
-// value, side)`, which stores.  With HAS_SIDE, `side` is a value per (item, lane) that the emit
-// wave fetched two tiles ahead with `pre(tile, item)` (fetched by the loaders instead, these
+// Emit wave e sums the loaders' partials of the token blocks e, e + kEmitWaves, ... in loader
+// order and hands the four values D[row 4 * kg + i][token nb * 16 + ri], i < 4, that a lane
+// holds of a block to `emit(tile, nb, values, side)`, which stores them (four consecutive rows
+// of one token per lane: 16- or 8-byte stores).  With HAS_SIDE, `side` holds a value per (row,
+// lane) that the emit wave fetched two tiles ahead with `pre(tile, nb, i)` (fetched by the loaders instead, these
 // small scattered loads sit in front of the weight rows in the in-order return queue and cost
 // a third of the kernel).  One LDS-only barrier per tile; the partial buffers alternate,
 // and a loader that writes a buffer again two tiles later has passed the barrier of the tile
@@ -121,7 +122,7 @@ __device__ __forceinline__ void rows_times_tokens(const bf16_t* __restrict__ w, 
                                                   int tile0, int ntiles, int tile_end,
                                                   float* red_raw, RowOf row_of, Pre pre, Emit emit) {
   constexpr int kRowWaves = NLW, kEmitWaves = kRowWavesAll - NLW;
-  constexpr int IPE = (NB * 4 + kEmitWaves - 1) / kEmitWaves;  // items an emit wave handles per tile
+  constexpr int NBE = (NB + kEmitWaves - 1) / kEmitWaves;  // token blocks an emit wave handles per tile
   float(*red)[kRowWaves][NB * 4][kWave] = reinterpret_cast<float(*)[kRowWaves][NB * 4][kWave]>(red_raw);
   constexpr int DEPTH = tile_depth<NB, SPW>();
   const int lane = threadIdx.x & (kWave - 1);
@@ -130,24 +131,28 @@ __device__ __forceinline__ void rows_times_tokens(const bf16_t* __restrict__ w, 
   if (wave >= kRowWaves) {
     // ------------------------------------------------------------------ emit wave
     const int ew = wave - kRowWaves;
-    float side[2][IPE];
-    auto prefetch = [&](int t, float(&sv)[IPE]) {
+    float side[2][NBE][4];
+    auto prefetch = [&](int t, float(&sv)[NBE][4]) {
       if constexpr (HAS_SIDE) {
 #pragma unroll
-        for (int k = 0; k < IPE; ++k) sv[k] = pre(t, min(ew + kEmitWaves * k, NB * 4 - 1));
+        for (int k = 0; k < NBE; ++k)
+#pragma unroll
+          for (int e = 0; e < 4; ++e) sv[k][e] = pre(t, min(ew + kEmitWaves * k, NB - 1), e);
       }
     };
-    auto emit_tile = [&](int i, const float(&sv)[IPE]) {
+    auto emit_tile = [&](int i, const float(&sv)[NBE][4]) {
       const int buf = i & 1;
       lds_barrier();
 #pragma unroll
-      for (int k = 0; k < IPE; ++k) {
-        const int item = ew + kEmitWaves * k;
-        if (item < NB * 4) {
-          float v = 0.f;
+      for (int k = 0; k < NBE; ++k) {
+        const int nb = ew + kEmitWaves * k;
+        if (nb < NB) {
+          f32x4 v{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-          for (int wv = 0; wv < kRowWaves; ++wv) v += red[buf][wv][item][lane];
-          emit(tile0 + i, item, v, HAS_SIDE ? sv[k] : 0.f);
+          for (int e = 0; e < 4; ++e)
+#pragma unroll
+            for (int wv = 0; wv < kRowWaves; ++wv) v[e] += red[buf][wv][nb * 4 + e][lane];
+          emit(tile0 + i, nb, v, f32x4{sv[k][0], sv[k][1], sv[k][2], sv[k][3]});
         }
       }
     };
@@ -227,12 +232,23 @@ __global__ __launch_bounds__(kRowThreads) void predict_batch_kernel(const BatchP
   rows_times_tokens<NB, SPW, NLW, false>(
       static_cast<const bf16_t*>(P.k1n[l]), (uint32_t)P.d_ff * (uint32_t)P.r * 2u, P.r, P.q, P.ldq, 0, P.B, tile0, P.TPW1,
       min(tile0 + P.TPW1, tiles_total), red_raw,
-      [&](int t, int i) { return min(t * 16 + i, P.d_ff - 1); }, [](int, int) { return 0.f; },
-      [&](int t, int item, float v, float) {
-        const int b = (item >> 2) * 16 + ri, j = t * 16 + 4 * kg + (item & 3);
-        if (j < P.d_ff && t < tiles_total) {
-          if (b < P.B) S[(size_t)b * P.d_ff + j] = v;
-          if (b < P.BP) ST[(size_t)j * P.BP + b] = v;  // tokens past the batch have v = 0: whole lines are written
+      [&](int t, int i) { return min(t * 16 + i, P.d_ff - 1); }, [](int, int, int) { return 0.f; },
+      [&](int t, int nb, f32x4 v, f32x4) {
+        const int b = nb * 16 + ri, j = t * 16 + 4 * kg;
+        if (t >= tiles_total) return;
+        if (b < P.B) {
+          if ((P.d_ff & 3) == 0) {  // the four neurons of a lane are inside the layer together, or none is
+            if (j < P.d_ff) *reinterpret_cast<f32x4*>(S + (size_t)b * P.d_ff + j) = v;
+          } else {
+#pragma unroll
+            for (int e = 0; e < 4; ++e)
+              if (j + e < P.d_ff) S[(size_t)b * P.d_ff + j + e] = v[e];
+          }
+        }
+        if (b < P.BP) {  // tokens past the batch have v = 0: whole lines are written
+#pragma unroll
+          for (int e = 0; e < 4; ++e)
+            if (j + e < P.d_ff) ST[(size_t)(j + e) * P.BP + b] = v[e];
         }
       });
 }
@@ -380,25 +396,30 @@ __global__ __launch_bounds__(kRowThreads) void k2_batch_kernel(const BatchParams
       static_cast<const bf16_t*>(P.k2n[l]), (uint32_t)P.d_ff * (uint32_t)(P.d_model - P.r) * 2u, P.d_model - P.r, P.q, P.ldq,
       P.r, P.B, tile0, P.TPW2, min(tile0 + P.TPW2, tiles_total), red_raw,
       [&](int t, int i) { return rowidx[min((t - tile0) * 16 + i, P.TPW2 * 16 + 15)]; },
-      [&](int t, int item) {  // the score the item's (row, token) pair will need
-        const int b = min((item >> 2) * 16 + ri, P.B - 1);
-        return ST[(size_t)rowidx[min((t - tile0) * 16 + 4 * kg + (item & 3), P.TPW2 * 16 + 15)] * P.BP + b];
+      [&](int t, int nb, int e) {  // the score the (row, token) pair will need
+        const int b = min(nb * 16 + ri, P.B - 1);
+        return ST[(size_t)rowidx[min((t - tile0) * 16 + 4 * kg + e, P.TPW2 * 16 + 15)] * P.BP + b];
       },
-      [&](int t, int item, float g, float score) {
-        const int nb = item >> 2, b = nb * 16 + ri;
-        const int rho = t * 16 + 4 * kg + (item & 3);
+      [&](int t, int nb, f32x4 g, f32x4 score) {
+        const int b = nb * 16 + ri;
+        const int rho = t * 16 + 4 * kg;  // first of the lane's four ranks (inside one block of 8)
         if (b >= P.B || rho >= rank_end) return;
-        float u = 0.f;
-        if (rho < m_total) {
-          const float a = score - th[nb];
-          u = a > 0.f ? gelu(a, P.gelu) * g : 0.f;
+        float rest[4];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          const float a = score[e] - th[nb];
+          rest[e] = (rho + e < m_total && a > 0.f) ? gelu(a, P.gelu) * g[e] : 0.f;
         }
-        float rest = u;
 #pragma unroll
         for (int pl = 0; pl < kPlanes; ++pl) {
-          const uint16_t h = float_to_bf16_rne(rest);
-          up[pl * P.plane + ((size_t)(rho >> 3) * P.B + b) * 8 + (rho & 7)] = h;
-          rest -= bf16_bits_to_float(h);
+          uint32_t h[4];
+#pragma unroll
+          for (int e = 0; e < 4; ++e) {
+            h[e] = float_to_bf16_rne(rest[e]);
+            rest[e] -= bf16_bits_to_float(h[e]);
+          }
+          *reinterpret_cast<u32x2*>(up + pl * P.plane + ((size_t)(rho >> 3) * P.B + b) * 8 + (rho & 7)) =
+              u32x2{h[0] | (h[1] << 16), h[2] | (h[3] << 16)};
         }
       });
   // ranks between the last tile of the union and the end of the v phase's last 32-row group
