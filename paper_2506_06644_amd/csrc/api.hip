@@ -357,7 +357,7 @@ void spark_debug_phases(int mask) { spark::phased_set_phases(mask); }
 
 void spark_debug_tuning(int rows_per_predict_block, int neurons_per_gather_block, int alt) {
   spark::phased_set_tuning(rows_per_predict_block, neurons_per_gather_block, alt);
-  spark::phased_batch_set_tuning(rows_per_predict_block / 16, neurons_per_gather_block / 16);
+  spark::phased_batch_set_tuning(rows_per_predict_block / 16, neurons_per_gather_block / 16, alt);
 }
 
 void spark_debug_profile(int on) { spark::fused_set_profile(on != 0); }

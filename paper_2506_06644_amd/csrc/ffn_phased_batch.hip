@@ -660,11 +660,12 @@ hipError_t launch_rows_nb(const BatchParams& P, int mode, int nb, int K, dim3 gr
   }
 }
 
-int g_batch_tpw1 = 0, g_batch_tpw2 = 0;  // tuning overrides (multiples of 4; 0 = automatic)
+int g_batch_tpw1 = 0, g_batch_tpw2 = 0, g_batch_ks = 0;  // tuning overrides (0 = automatic)
 
 }  // namespace
 
-void phased_batch_set_tuning(int tpw1, int tpw2) {
+void phased_batch_set_tuning(int tpw1, int tpw2, int ks) {
+  g_batch_ks = ks;
   g_batch_tpw1 = tpw1 > 0 ? (tpw1 + 3) / 4 * 4 : 0;
   g_batch_tpw2 = tpw2 > 0 ? min(32, (tpw2 + 3) / 4 * 4) : 0;
 }
@@ -685,8 +686,10 @@ hipError_t launch_ffn_phased_batch(const FfnProblem& p0, const void* const* k1n,
   char* s = static_cast<char*>(scratch);
   const int B = p0.batch, nb = (B + 15) / 16;
   hipError_t err = hipSuccess;
-  for (int base = 0; base < n_layers && err == hipSuccess; base += kBatchMaxLayers) {
-    const int L = min(kBatchMaxLayers, n_layers - base);
+  // equal chunks of at most kBatchMaxLayers layers
+  const int chunks = (n_layers + kBatchMaxLayers - 1) / kBatchMaxLayers, per = (n_layers + chunks - 1) / max(1, chunks);
+  for (int base = 0; base < n_layers && err == hipSuccess; base += per) {
+    const int L = min(per, n_layers - base);
     BatchParams P;
     for (int l = 0; l < kBatchMaxLayers; ++l) {
       P.k1n[l] = l < L ? k1n[base + l] : nullptr;
@@ -731,7 +734,18 @@ hipError_t launch_ffn_phased_batch(const FfnProblem& p0, const void* const* k1n,
     P.TPW1 = tpw1;
     P.TPW2 = tpw2;
     const int slabs = v_slabs(p0.d_model, nb);
-    int ksl = (768 + slabs * L - 1) / (slabs * L);
+    // Row slices: a workgroup's time is its share of the rows plus a fixed part (start-up and
+    // its partial sums, about 2 % of a whole column slab), and the launch takes as many rounds
+    // as its workgroups need of the chip's resident slots; take the cheapest count.
+    const int v_slots = 256 * max(1, 4 * (nb >= 3 ? 3 : 4) / v_waves(p0.d_model, nb));
+    int ksl = 1;
+    double cost_best = 1e30;
+    for (int c = 1; c <= 16 && L * c <= part_rows(p0.d_model); ++c) {
+      const long long n = (long long)slabs * L * c;
+      const double cost = (double)((n + v_slots - 1) / v_slots) * (1.0 / c + 0.02);
+      if (cost < cost_best) { cost_best = cost; ksl = c; }
+    }
+    if (g_batch_ks > 0) ksl = g_batch_ks;
     ksl = max(1, min(16, ksl));
     while (L * ksl > part_rows(p0.d_model)) --ksl;
     P.KS = ksl;

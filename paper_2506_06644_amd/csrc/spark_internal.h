@@ -78,7 +78,7 @@ hipError_t launch_ffn_phased(const FfnProblem& p0, const void* const* k1n, const
 constexpr int kBatchMaxLayers = 32;
 size_t phased_batch_scratch_bytes(int d_model, int d_ff, int batch);
 bool phased_batch_supported(const FfnProblem& p);
-void phased_batch_set_tuning(int predict_tiles_per_workgroup, int k2_tiles_per_workgroup);  // 0 = automatic
+void phased_batch_set_tuning(int predict_tiles_per_workgroup, int k2_tiles_per_workgroup, int v_row_slices);  // 0 = automatic
 hipError_t launch_ffn_phased_batch(const FfnProblem& p0, const void* const* k1n, const void* const* k2n,
                                    const void* const* vn, int n_layers, void* scratch, hipStream_t st);
 
