@@ -144,9 +144,9 @@ spark_status spark_ffn_decode(const spark_ffn_layer* layer, const void* q, spark
  * Output arrays carry a leading n_layers dimension:
  *   y [n_layers][batch][d_model], theta [n_layers][batch], active_count [n_layers][batch],
  *   active_idx [n_layers][batch][d_ff], union_count [n_layers], union_idx [n_layers][d_ff].
- * For batch == 1 and supported shapes this is one persistent launch that keeps the next
- * layer's predictor rows in flight while the current layer's gather runs; results are the
- * same as n_layers calls of spark_ffn_decode.
+ * The layers are independent (they share q), so every step of the path - predictor sweep,
+ * thresholds and compaction, gathered products, final sums - is one launch over all layers;
+ * results are the same as n_layers calls of spark_ffn_decode.
  */
 spark_status spark_ffn_decode_layers(const spark_ffn_layer* layers, int32_t n_layers,
                                      const void* q, spark_dtype qdtype, int32_t batch,
@@ -154,6 +154,37 @@ spark_status spark_ffn_decode_layers(const spark_ffn_layer* layers, int32_t n_la
                                      int32_t* active_idx, int32_t* union_count,
                                      int32_t* union_idx, void* workspace,
                                      size_t workspace_bytes, void* hip_stream);
+
+/* Host. Bytes of device workspace spark_ffn_prefill needs for this layer shape and chunk size
+ * (0 on invalid arguments). */
+size_t spark_ffn_prefill_workspace_bytes(int32_t d_model, int32_t d_ff, int32_t chunk);
+
+/*
+ * Prefill: n_tokens tokens of a prompt through one layer, in chunks of `chunk` consecutive
+ * tokens (Section 4.3 and Appendix B: the prompt is processed in chunks, 64 tokens in the
+ * paper's set-up; within a chunk every token keeps its own threshold and mask, and the
+ * union of the chunk's masks decides which weight rows are fetched).  Token t belongs to
+ * chunk t / chunk; the last chunk may be shorter.  Every y[t] equals what spark_ffn_decode
+ * gives for that token alone.
+ *
+ *   q             [n_tokens][d_model] of `qdtype`, row pitch ldq elements          in
+ *   y             [n_tokens][d_model] fp32, overwritten                            out
+ *   theta         [n_tokens] fp32                                                  out, optional
+ *   active_count  [n_tokens] int32                                                 out, optional
+ *   active_idx    [n_tokens][d_ff] int32, ascending active neurons of each token   out, optional
+ *   union_count   [ceil(n_tokens / chunk)] int32, union size of each chunk         out, optional
+ *   union_idx     [ceil(n_tokens / chunk)][d_ff] int32, ascending union per chunk  out, optional
+ *   workspace     >= spark_ffn_prefill_workspace_bytes(d_model, d_ff, chunk), 256-byte aligned
+ *
+ * 1 <= chunk <= SPARK_MAX_BATCH; n_tokens = 0 is a no-op.  The full chunks are independent
+ * and are evaluated step by step over all chunks at once (bf16 weights and tokens; other
+ * types chunk by chunk).  Arithmetic and errors as for spark_ffn_decode.
+ */
+spark_status spark_ffn_prefill(const spark_ffn_layer* layer, const void* q, spark_dtype qdtype,
+                               int64_t n_tokens, int32_t chunk, int64_t ldq, float* y,
+                               float* theta, int32_t* active_count, int32_t* active_idx,
+                               int32_t* union_count, int32_t* union_idx, void* workspace,
+                               size_t workspace_bytes, void* hip_stream);
 
 /*
  * Dense evaluation of the same layer (every neuron's K2 and V row is read; the result

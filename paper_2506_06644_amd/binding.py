@@ -25,6 +25,7 @@ EXPORTS = (
     "spark_status_string", "spark_version", "spark_normal_quantile", "spark_stat_topk",
     "spark_ffn_workspace_bytes", "spark_ffn_decode", "spark_ffn_decode_layers",
     "spark_ffn_dense_decode", "spark_ffn_dense_decode_layers", "spark_ffn_check",
+    "spark_ffn_prefill_workspace_bytes", "spark_ffn_prefill",
     "spark_attn_workspace_bytes", "spark_attn_decode", "spark_debug_force_general", "spark_debug_tuning", "spark_debug_phases",
     "spark_debug_profile", "spark_debug_read_profile",
 )
@@ -81,6 +82,11 @@ def load_library():
     lib.spark_ffn_decode_layers.restype = c_int
     lib.spark_ffn_decode_layers.argtypes = [ctypes.POINTER(_Layer), i32, vp, c_int, i32, i64, vp, vp, vp,
                                             vp, vp, vp, vp, sz, vp]
+    lib.spark_ffn_prefill_workspace_bytes.restype = sz
+    lib.spark_ffn_prefill_workspace_bytes.argtypes = [i32, i32, i32]
+    lib.spark_ffn_prefill.restype = c_int
+    lib.spark_ffn_prefill.argtypes = [ctypes.POINTER(_Layer), vp, c_int, i64, i32, i64, vp, vp, vp, vp, vp, vp,
+                                      vp, sz, vp]
     lib.spark_ffn_dense_decode.restype = c_int
     lib.spark_ffn_dense_decode.argtypes = [ctypes.POINTER(_Layer), vp, c_int, i32, i64, vp, vp, sz, vp]
     lib.spark_attn_workspace_bytes.restype = sz
@@ -185,6 +191,26 @@ def spark_ffn_decode_layers(layers: Sequence[_Layer], q: torch.Tensor, y: torch.
         arr, len(layers), _p(q), _dt(q), q.shape[0], q.stride(0), _p(y), _p(theta), _p(active_count),
         _p(active_idx), _p(union_count), _p(union_idx), _p(workspace), workspace.numel(), _stream())
     _check(rc, "spark_ffn_decode_layers")
+
+
+def ffn_prefill_workspace_bytes(d_model: int, d_ff: int, chunk: int) -> int:
+    return int(load_library().spark_ffn_prefill_workspace_bytes(int(d_model), int(d_ff), int(chunk)))
+
+
+def make_prefill_workspace(d_model: int, d_ff: int, chunk: int, device) -> torch.Tensor:
+    return torch.empty(ffn_prefill_workspace_bytes(d_model, d_ff, chunk), dtype=torch.uint8, device=device)
+
+
+def spark_ffn_prefill(layer: _Layer, q: torch.Tensor, chunk: int, y: torch.Tensor, workspace: torch.Tensor,
+                      theta=None, active_count=None, active_idx=None, union_count=None, union_idx=None,
+                      n_tokens=None):
+    """``q[n_tokens, d_model]`` through one layer in chunks of ``chunk`` tokens; ``y[n_tokens, d_model]``
+    (``n_tokens`` defaults to all rows of ``q``)."""
+    rc = load_library().spark_ffn_prefill(
+        ctypes.byref(layer), _p(q), _dt(q), q.shape[0] if n_tokens is None else int(n_tokens), int(chunk), q.stride(0), _p(y), _p(theta),
+        _p(active_count), _p(active_idx), _p(union_count), _p(union_idx), _p(workspace), workspace.numel(),
+        _stream())
+    _check(rc, "spark_ffn_prefill")
 
 
 def spark_ffn_dense_decode(layer: _Layer, q: torch.Tensor, y: torch.Tensor, workspace: torch.Tensor):

@@ -234,6 +234,69 @@ spark_status spark_ffn_decode_layers(const spark_ffn_layer* layers, int32_t n_la
   return SPARK_OK;
 }
 
+size_t spark_ffn_prefill_workspace_bytes(int32_t d_model, int32_t d_ff, int32_t chunk) {
+  size_t need = 0;  // a shorter last chunk may take another path with another scratch layout
+  for (int32_t b = 1; b <= chunk; ++b) {
+    const size_t w = spark_ffn_workspace_bytes(d_model, d_ff, b);
+    if (w == 0) return 0;
+    need = w > need ? w : need;
+  }
+  return need;
+}
+
+spark_status spark_ffn_prefill(const spark_ffn_layer* layer, const void* q, spark_dtype qdtype, int64_t n_tokens,
+                               int32_t chunk, int64_t ldq, float* y, float* theta, int32_t* active_count,
+                               int32_t* active_idx, int32_t* union_count, int32_t* union_idx, void* workspace,
+                               size_t workspace_bytes, void* hip_stream) {
+  if (n_tokens < 0 || n_tokens > 2147483647LL) return SPARK_ERR_SHAPE;
+  const spark_status s = validate_decode(layer, q, qdtype, chunk, ldq, y, workspace, workspace_bytes);
+  if (s != SPARK_OK) return s;
+  if (workspace_bytes < spark_ffn_prefill_workspace_bytes(layer->d_model, layer->d_ff, chunk)) return SPARK_ERR_WORKSPACE;
+  hipStream_t st = static_cast<hipStream_t>(hip_stream);
+  const int64_t d_model = layer->d_model, d_ff = layer->d_ff, n_full = n_tokens / chunk;
+  const int32_t tail = (int32_t)(n_tokens % chunk);
+  const size_t qs = dtype_size(qdtype);
+  // outputs and tokens of the chunk that starts at token t0 (c = its chunk number)
+  auto problem_at = [&](int64_t t0, int64_t c, int32_t batch) {
+    return make_problem(layer, static_cast<const char*>(q) + (size_t)t0 * (size_t)ldq * qs, qdtype, batch, ldq,
+                        y + t0 * d_model, theta ? theta + t0 : nullptr, active_count ? active_count + t0 : nullptr,
+                        active_idx ? active_idx + t0 * d_ff : nullptr, union_count ? union_count + c : nullptr,
+                        union_idx ? union_idx + c * d_ff : nullptr);
+  };
+  auto one_chunk = [&](int64_t t0, int64_t c, int32_t batch) {
+    const spark::FfnProblem p = problem_at(t0, c, batch);
+    const spark::FfnWorkspace ws = spark::carve_workspace(workspace, layer->d_model, layer->d_ff, batch);
+    if (g_force_general == 0 && (spark::phased_supported(p) || spark::phased_batch_supported(p)))
+      return run_fused(layer, 1, p, ws, false, st);
+    return spark::launch_ffn_general(p, ws, 0, st);
+  };
+  int64_t c = 0;
+  if (n_full > 0 && g_force_general == 0 && spark::phased_batch_supported(problem_at(0, 0, chunk))) {
+    // the full chunks are independent of each other: they go through the batched path as the
+    // "layers" of one launch, every slot with the same weights and its own block of tokens
+    const spark::FfnWorkspace ws = spark::carve_workspace(workspace, layer->d_model, layer->d_ff, chunk);
+    const void* w1[256];
+    const void* w2[256];
+    const void* w3[256];
+    for (int i = 0; i < 256; ++i) {
+      w1[i] = layer->k1n;
+      w2[i] = layer->k2n;
+      w3[i] = layer->vn;
+    }
+    for (; c < n_full; c += 256) {
+      spark::FfnProblem p = problem_at(c * chunk, c, chunk);
+      p.q_slot_stride = (int64_t)chunk * ldq;
+      const int n = (int)(n_full - c < 256 ? n_full - c : 256);
+      if (spark::launch_ffn_phased_batch(p, w1, w2, w3, n, ws.fused, st) != hipSuccess) return SPARK_ERR_DEVICE;
+    }
+    c = n_full;
+  }
+  for (; c < n_full; ++c)
+    if (one_chunk(c * chunk, c, chunk) != hipSuccess) return SPARK_ERR_DEVICE;
+  if (tail > 0 && one_chunk(n_full * chunk, n_full, tail) != hipSuccess) return SPARK_ERR_DEVICE;
+  return SPARK_OK;
+}
+
 spark_status spark_ffn_dense_decode(const spark_ffn_layer* layer, const void* q, spark_dtype qdtype,
                                     int32_t batch, int64_t ldq, float* y, void* workspace,
                                     size_t workspace_bytes, void* hip_stream) {

@@ -41,8 +41,9 @@ struct BatchParams {
   const void* k1n[kBatchMaxLayers];
   const void* k2n[kBatchMaxLayers];
   const void* vn[kBatchMaxLayers];
-  const bf16_t* q;     // [B][ldq]
+  const bf16_t* q;     // [B][ldq]; layer slot l reads the block at q + l * qslot
   int64_t ldq;
+  int64_t qslot;
   float* y;            // [L][B][d_model]
   float* theta;        // [L][B]        optional
   int32_t* count;      // [L][B]        optional
@@ -230,7 +231,7 @@ __global__ __launch_bounds__(kRowThreads) void predict_batch_kernel(const BatchP
   float* S = P.S + (size_t)l * P.B * P.d_ff;
   float* ST = P.ST + (size_t)l * P.d_ff * P.BP;
   rows_times_tokens<NB, SPW, NLW, false>(
-      static_cast<const bf16_t*>(P.k1n[l]), (uint32_t)P.d_ff * (uint32_t)P.r * 2u, P.r, P.q, P.ldq, 0, P.B, tile0, P.TPW1,
+      static_cast<const bf16_t*>(P.k1n[l]), (uint32_t)P.d_ff * (uint32_t)P.r * 2u, P.r, P.q + (size_t)l * P.qslot, P.ldq, 0, P.B, tile0, P.TPW1,
       min(tile0 + P.TPW1, tiles_total), red_raw,
       [&](int t, int i) { return min(t * 16 + i, P.d_ff - 1); }, [](int, int, int) { return 0.f; },
       [&](int t, int nb, f32x4 v, f32x4) {
@@ -393,7 +394,7 @@ __global__ __launch_bounds__(kRowThreads) void k2_batch_kernel(const BatchParams
   for (int nb = 0; nb < NB; ++nb) th[nb] = P.thetas[(size_t)l * P.B + min(nb * 16 + ri, P.B - 1)];
   uint16_t* up = P.up + (size_t)l * P.B * P.ldu;
   rows_times_tokens<NB, SPW, NLW, true>(
-      static_cast<const bf16_t*>(P.k2n[l]), (uint32_t)P.d_ff * (uint32_t)(P.d_model - P.r) * 2u, P.d_model - P.r, P.q, P.ldq,
+      static_cast<const bf16_t*>(P.k2n[l]), (uint32_t)P.d_ff * (uint32_t)(P.d_model - P.r) * 2u, P.d_model - P.r, P.q + (size_t)l * P.qslot, P.ldq,
       P.r, P.B, tile0, P.TPW2, min(tile0 + P.TPW2, tiles_total), red_raw,
       [&](int t, int i) { return rowidx[min((t - tile0) * 16 + i, P.TPW2 * 16 + 15)]; },
       [&](int t, int nb, int e) {  // the score the (row, token) pair will need
@@ -696,7 +697,8 @@ hipError_t launch_ffn_phased_batch(const FfnProblem& p0, const void* const* k1n,
       P.k2n[l] = l < L ? k2n[base + l] : nullptr;
       P.vn[l] = l < L ? vn[base + l] : nullptr;
     }
-    P.q = static_cast<const bf16_t*>(p0.q);
+    P.q = static_cast<const bf16_t*>(p0.q) + (size_t)base * p0.q_slot_stride;
+    P.qslot = p0.q_slot_stride;
     P.ldq = p0.ldq;
     P.y = p0.y + (size_t)base * B * p0.d_model;
     P.theta = p0.theta ? p0.theta + (size_t)base * B : nullptr;

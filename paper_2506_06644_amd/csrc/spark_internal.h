@@ -19,6 +19,8 @@ struct FfnProblem {
   const void *k1n, *k2n, *vn;
   const void* q;
   int64_t ldq;
+  int64_t q_slot_stride = 0;  // batched multi-layer launches: elements between the token blocks of
+                              // consecutive layer slots (0: every slot reads the same tokens)
   int batch;
   float z;  // Q(1 - k/d_ff)
   // outputs (optional ones may be null)
