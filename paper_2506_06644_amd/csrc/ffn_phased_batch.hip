@@ -6,6 +6,9 @@
 //   predict   S[l][b][j] = K1n_l[j] . q_b[:r]: tiles of 16 neurons x all tokens,
 //             v_mfma_f32_16x16x32_bf16 with the k range split over the 8 waves of a workgroup;
 //             the token fragments stay in registers while the workgroup walks its tiles.
+//             With at most 16 tokens (one token block) the token fragments of every k step fit
+//             in LDS instead, and a wave streams whole tiles by itself (no k split, no partial
+//             sums, no barriers); the same holds for k2.
 //   select    one workgroup per (layer, token): mean and std of the row (two passes over
 //             registers), theta (Eq.11), the token's index list and the token's mask; a small
 //             launch then ORs the tokens' masks of a layer into its union mask.
@@ -332,15 +335,14 @@ __global__ __launch_bounds__(4 * kMaxWords) void union_batch_kernel(const BatchP
 }
 
 // -------------------------------------------------------------------------------------- k2
-template <int NB, int SPW, int NLW>
-__global__ __launch_bounds__(kRowThreads) void k2_batch_kernel(const BatchParams P) {
-  extern __shared__ __align__(16) float red_raw[];
-  __shared__ int wprefix[kMaxWords + 1];
-  __shared__ int rowidx[32 * 16 + 16];
+// Shared opening of the k2 kernels: prefix sums of the union mask's words, the union size, and
+// the neuron of every union rank the workgroup handles (ranks past the end repeat the last
+// one), in LDS and, for the real ranks, in urow / uidx.  Returns the union size; workgroups
+// with no tile to do get -1.
+template <int THREADS>
+__device__ __forceinline__ int k2_ranks_to_rows(const BatchParams& P, int l, int tile0, int* wprefix, int* rowidx) {
   const int tid = threadIdx.x, lane = tid & (kWave - 1);
   const int wave = __builtin_amdgcn_readfirstlane(tid / kWave);
-  const int ri = lane & 15, kg = lane >> 4;
-  const int l = blockIdx.y;
   const int nwords = (P.d_ff + 63) / 64;
   const unsigned long long* um = P.umask + (size_t)l * kMaxWords;
   if (wave == 0) {
@@ -361,14 +363,12 @@ __global__ __launch_bounds__(kRowThreads) void k2_batch_kernel(const BatchParams
   __syncthreads();
   const int m_total = wprefix[nwords];
   const int tiles_total = (m_total + 15) / 16;
-  const int tile0 = blockIdx.x * P.TPW2;
   if (blockIdx.x == 0 && tid == 0) {
     P.utotal[l] = m_total;
     if (P.ucount) P.ucount[l] = m_total;
   }
-  if (tile0 >= tiles_total) return;
-  // neuron of every union rank this workgroup handles (ranks past the end repeat the last one)
-  for (int i = tid; i < P.TPW2 * 16 + 16; i += kRowThreads) {
+  if (tile0 >= tiles_total) return -1;
+  for (int i = tid; i < P.TPW2 * 16 + 16; i += THREADS) {
     const int rho = tile0 * 16 + i;
     const int rc = min(rho, m_total - 1);
     int lo = 0, hi = nwords - 1;  // last word with wprefix[word] <= rc
@@ -387,6 +387,55 @@ __global__ __launch_bounds__(kRowThreads) void k2_batch_kernel(const BatchParams
     }
   }
   __syncthreads();
+  return m_total;
+}
+
+// The activations of four consecutive union ranks of one token, u = GELU(s - theta) * g where
+// the token activates the row and 0 elsewhere, as three bf16 planes.
+__device__ __forceinline__ void k2_store_u(const BatchParams& P, uint16_t* up, int rho, int b, int m_total, float th,
+                                           f32x4 g, f32x4 score) {
+  float rest[4];
+#pragma unroll
+  for (int e = 0; e < 4; ++e) {
+    const float a = score[e] - th;
+    rest[e] = (rho + e < m_total && a > 0.f) ? gelu(a, P.gelu) * g[e] : 0.f;
+  }
+#pragma unroll
+  for (int pl = 0; pl < kPlanes; ++pl) {
+    uint32_t h[4];
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      h[e] = float_to_bf16_rne(rest[e]);
+      rest[e] -= bf16_bits_to_float(h[e]);
+    }
+    *reinterpret_cast<u32x2*>(up + pl * P.plane + ((size_t)(rho >> 3) * P.B + b) * 8 + (rho & 7)) =
+        u32x2{h[0] | (h[1] << 16), h[2] | (h[3] << 16)};
+  }
+}
+
+// Ranks between the last tile of the union and the end of the v phase's last 32-row group read
+// as zero (called by the workgroup that holds the union's last tile).
+template <int THREADS>
+__device__ __forceinline__ void k2_zero_tail(const BatchParams& P, uint16_t* up, int from, int to) {
+  for (int i = threadIdx.x; i < (to - from) * P.B; i += THREADS) {
+    const int b = i / (to - from), rho = from + i % (to - from);
+#pragma unroll
+    for (int pl = 0; pl < kPlanes; ++pl) up[pl * P.plane + ((size_t)(rho >> 3) * P.B + b) * 8 + (rho & 7)] = 0;
+  }
+}
+
+template <int NB, int SPW, int NLW>
+__global__ __launch_bounds__(kRowThreads) void k2_batch_kernel(const BatchParams P) {
+  extern __shared__ __align__(16) float red_raw[];
+  __shared__ int wprefix[kMaxWords + 1];
+  __shared__ int rowidx[32 * 16 + 16];
+  const int tid = threadIdx.x, lane = tid & (kWave - 1);
+  const int ri = lane & 15, kg = lane >> 4;
+  const int l = blockIdx.y;
+  const int tile0 = blockIdx.x * P.TPW2;
+  const int m_total = k2_ranks_to_rows<kRowThreads>(P, l, tile0, wprefix, rowidx);
+  if (m_total < 0) return;
+  const int tiles_total = (m_total + 15) / 16;
   const int rank_end = (m_total + 31) / 32 * 32;  // the v phase reads ranks below this
   const float* ST = P.ST + (size_t)l * P.d_ff * P.BP;
   float th[NB];
@@ -405,34 +454,154 @@ __global__ __launch_bounds__(kRowThreads) void k2_batch_kernel(const BatchParams
         const int b = nb * 16 + ri;
         const int rho = t * 16 + 4 * kg;  // first of the lane's four ranks (inside one block of 8)
         if (b >= P.B || rho >= rank_end) return;
-        float rest[4];
-#pragma unroll
-        for (int e = 0; e < 4; ++e) {
-          const float a = score[e] - th[nb];
-          rest[e] = (rho + e < m_total && a > 0.f) ? gelu(a, P.gelu) * g[e] : 0.f;
-        }
-#pragma unroll
-        for (int pl = 0; pl < kPlanes; ++pl) {
-          uint32_t h[4];
-#pragma unroll
-          for (int e = 0; e < 4; ++e) {
-            h[e] = float_to_bf16_rne(rest[e]);
-            rest[e] -= bf16_bits_to_float(h[e]);
-          }
-          *reinterpret_cast<u32x2*>(up + pl * P.plane + ((size_t)(rho >> 3) * P.B + b) * 8 + (rho & 7)) =
-              u32x2{h[0] | (h[1] << 16), h[2] | (h[3] << 16)};
-        }
+        k2_store_u(P, up, rho, b, m_total, th[nb], g, score);
       });
-  // ranks between the last tile of the union and the end of the v phase's last 32-row group
-  // read as zero
-  if (tile0 + P.TPW2 >= tiles_total) {
-    const int from = (tile0 + P.TPW2) * 16, to = rank_end;
-    for (int i = tid; i < (to - from) * P.B; i += kRowThreads) {
-      const int b = i / (to - from), rho = from + i % (to - from);
+  if (tile0 + P.TPW2 >= tiles_total) k2_zero_tail<kRowThreads>(P, up, (tile0 + P.TPW2) * 16, rank_end);
+}
+
+// ------------------------------------------------------------- rows x tokens, streamed (<= 16 tokens)
+// With one token block the token fragments of every k step fit in LDS (32 bytes per k), and a
+// wave can take whole tiles by itself: no k split, no partial sums, no barrier after the
+// opening.  Workgroup = 4 waves, 4 NT consecutive tiles; wave w takes tiles w, w + 4, ...  A
+// tile's k steps come in NG groups of GS steps; two groups are in flight per wave while a third
+// is multiplied, across tile boundaries, in straight-line code (NG, NT are compile-time), so
+// every wait is exact.  The accumulators of a wave's NT tiles stay in registers and everything
+// is stored after the last multiply: a store between the loads would make the wave wait for
+// all of its loads at the next use (stores and loads share one counter on this target).
+constexpr int kStreamWaves = 4, kStreamThreads = kStreamWaves * kWave;
+template <int GS, int NG, int NT, typename RowOf>
+__device__ __forceinline__ void rows_stream(const bf16_t* __restrict__ w, uint32_t w_bytes, int K,
+                                            const bf16_t* __restrict__ q, int64_t ldq, int qoff, int B, int tile0,
+                                            int tile_end, u32x4* qsh, RowOf row_of, f32x4 (&acc)[NT]) {
+  static_assert(NG % 2 == 0, "the two group buffers alternate with the group's parity");
+  const int tid = threadIdx.x, lane = tid & (kWave - 1);
+  const int wave = __builtin_amdgcn_readfirstlane(tid / kWave);
+  const int kg = lane >> 4, ri = lane & 15;
+  // token fragments in the lane order of each k step: chunk (4 step + kg) of token ri sits at
+  // 64 step + lane (tokens past the batch are zero)
+  auto stage_tokens = [&]() {
+    for (int c = tid; c < (K / 8) * 16; c += kStreamThreads) {
+      const int b = c & 15, ch = c >> 4;
+      u32x4 v{0u, 0u, 0u, 0u};
+      if (b < B) v = ld16(q + (int64_t)b * ldq + qoff + ch * 8);
+      qsh[c] = v;
+    }
+    __syncthreads();
+  };
+  auto load_group = [&](int i, int g, u32x4(&a)[GS]) {
+    const int t = tile0 + i * kStreamWaves + wave;  // tiles past tile_end: a descriptor without records
+    const __amdgpu_buffer_rsrc_t rs =
+        __builtin_amdgcn_make_buffer_rsrc(const_cast<bf16_t*>(w), 0, t < tile_end ? (int)w_bytes : 0, 0x00020000);
+    const uint32_t off = (uint32_t)row_of(t, ri) * (uint32_t)K * 2u + (uint32_t)(g * GS * 4 + kg) * 16u;
 #pragma unroll
-      for (int pl = 0; pl < kPlanes; ++pl) up[pl * P.plane + ((size_t)(rho >> 3) * P.B + b) * 8 + (rho & 7)] = 0;
+    for (int s = 0; s < GS; ++s) a[s] = __builtin_amdgcn_raw_buffer_load_b128(rs, (int)(off + (uint32_t)s * 64u), 0, 0);
+  };
+  auto multiply = [&](const u32x4(&a)[GS], int g, f32x4& c) {
+#pragma unroll
+    for (int s = 0; s < GS; ++s) c = mfma_bf16(a[s], qsh[(g * GS + s) * kWave + lane], c);
+  };
+  // Long workgroups stage the tokens first (loads return in order: behind the first row
+  // requests the staging, and the barrier after it, would wait for those rows); short ones,
+  // which run in several rounds, gain more from having their rows on the way meanwhile.
+  u32x4 a0[GS], a1[GS];
+  if constexpr (NT > 1) stage_tokens();
+  load_group(0, 0, a0);
+  load_group(0, 1, a1);
+  __builtin_amdgcn_sched_barrier(0);
+  if constexpr (NT == 1) stage_tokens();
+#pragma unroll
+  for (int i = 0; i < NT; ++i) {
+    acc[i] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int g = 0; g < NG; g += 2) {
+      // (the scheduler is kept from moving the requests: their order is the pipeline)
+      multiply(a0, g, acc[i]);
+      __builtin_amdgcn_sched_barrier(0);
+      if (g + 2 < NG) load_group(i, g + 2, a0);
+      else if (i + 1 < NT) load_group(i + 1, 0, a0);
+      __builtin_amdgcn_sched_barrier(0);
+      multiply(a1, g + 1, acc[i]);
+      __builtin_amdgcn_sched_barrier(0);
+      if (g + 2 < NG) load_group(i, g + 3, a1);
+      else if (i + 1 < NT) load_group(i + 1, 1, a1);
+      __builtin_amdgcn_sched_barrier(0);
     }
   }
+}
+
+template <int GS, int NG, int NT>
+__global__ __launch_bounds__(kStreamThreads, 4) void predict_stream_kernel(const BatchParams P) {
+  extern __shared__ __align__(16) u32x4 qsh[];
+  const int lane = threadIdx.x & (kWave - 1);
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
+  const int ri = lane & 15, kg = lane >> 4;
+  const int l = blockIdx.y;
+  const int tiles_total = (P.d_ff + 15) / 16;
+  const int tile0 = blockIdx.x * (kStreamWaves * NT);
+  if (blockIdx.x == 0 && l == 0 && threadIdx.x == 0) *P.status = 0;  // this path cannot abort
+  if (tile0 >= tiles_total) return;
+  f32x4 acc[NT];
+  rows_stream<GS, NG, NT>(static_cast<const bf16_t*>(P.k1n[l]), (uint32_t)P.d_ff * (uint32_t)P.r * 2u, P.r,
+                          P.q + (size_t)l * P.qslot, P.ldq, 0, P.B, tile0, min(tile0 + kStreamWaves * NT, tiles_total), qsh,
+                          [&](int t, int i) { return min(t * 16 + i, P.d_ff - 1); }, acc);
+  float* S = P.S + (size_t)l * P.B * P.d_ff;
+  float* ST = P.ST + (size_t)l * P.d_ff * P.BP;
+  const int b = ri;
+#pragma unroll
+  for (int i = 0; i < NT; ++i) {
+    const int t = tile0 + i * kStreamWaves + wave, j = t * 16 + 4 * kg;
+    if (t >= tiles_total) continue;
+    if (b < P.B) {
+      if ((P.d_ff & 3) == 0) {  // the four neurons of a lane are inside the layer together, or none is
+        if (j < P.d_ff) *reinterpret_cast<f32x4*>(S + (size_t)b * P.d_ff + j) = acc[i];
+      } else {
+#pragma unroll
+        for (int e = 0; e < 4; ++e)
+          if (j + e < P.d_ff) S[(size_t)b * P.d_ff + j + e] = acc[i][e];
+      }
+    }
+#pragma unroll
+    for (int e = 0; e < 4; ++e)  // tokens past the batch have 0: whole lines are written (BP = 16 here)
+      if (j + e < P.d_ff) ST[(size_t)(j + e) * P.BP + b] = acc[i][e];
+  }
+}
+
+template <int GS, int NG, int NT>
+__global__ __launch_bounds__(kStreamThreads, 4) void k2_stream_kernel(const BatchParams P) {
+  extern __shared__ __align__(16) u32x4 qsh[];
+  __shared__ int wprefix[kMaxWords + 1];
+  __shared__ int rowidx[kStreamWaves * NT * 16 + 16];
+  const int lane = threadIdx.x & (kWave - 1);
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
+  const int ri = lane & 15, kg = lane >> 4;
+  const int l = blockIdx.y;
+  const int tile0 = blockIdx.x * P.TPW2;  // the launch sets TPW2 = 4 NT
+  const int m_total = k2_ranks_to_rows<kStreamThreads>(P, l, tile0, wprefix, rowidx);
+  if (m_total < 0) return;
+  const int tiles_total = (m_total + 15) / 16;
+  const int rank_end = (m_total + 31) / 32 * 32;  // the v phase reads ranks below this
+  const float* ST = P.ST + (size_t)l * P.d_ff * P.BP;
+  const int b = ri;
+  // the scores the lane's (row, token) pairs will need: requested ahead of the weight rows
+  f32x4 score[NT];
+#pragma unroll
+  for (int i = 0; i < NT; ++i)
+#pragma unroll
+    for (int e = 0; e < 4; ++e)
+      score[i][e] = ST[(size_t)rowidx[(i * kStreamWaves + wave) * 16 + 4 * kg + e] * P.BP + min(b, P.B - 1)];
+  const float th = P.thetas[(size_t)l * P.B + min(b, P.B - 1)];
+  f32x4 acc[NT];
+  rows_stream<GS, NG, NT>(static_cast<const bf16_t*>(P.k2n[l]), (uint32_t)P.d_ff * (uint32_t)(P.d_model - P.r) * 2u,
+                          P.d_model - P.r, P.q + (size_t)l * P.qslot, P.ldq, P.r, P.B, tile0,
+                          min(tile0 + kStreamWaves * NT, tiles_total), qsh,
+                          [&](int t, int i) { return rowidx[(t - tile0) * 16 + i]; }, acc);
+  uint16_t* up = P.up + (size_t)l * P.B * P.ldu;
+#pragma unroll
+  for (int i = 0; i < NT; ++i) {
+    const int rho = (tile0 + i * kStreamWaves + wave) * 16 + 4 * kg;  // first of the lane's four ranks
+    if (b < P.B && rho < rank_end) k2_store_u(P, up, rho, b, m_total, th, acc[i], score[i]);
+  }
+  if (tile0 + kStreamWaves * NT >= tiles_total) k2_zero_tail<kStreamThreads>(P, up, (tile0 + kStreamWaves * NT) * 16, rank_end);
 }
 
 // --------------------------------------------------------------------------------------- v
@@ -661,12 +830,50 @@ hipError_t launch_rows_nb(const BatchParams& P, int mode, int nb, int K, dim3 gr
   }
 }
 
+// Streamed kernels (at most 16 tokens): k steps per group and groups per row for a row of K
+// elements, from the compiled combinations.
+bool stream_split(int K, int* gs, int* ng) {
+  static const int cand[][2] = {{8, 2}, {8, 4}, {8, 6}, {8, 8}, {10, 4}};
+  for (const auto& c : cand)
+    if (c[0] * c[1] * 32 == K) {
+      *gs = c[0];
+      *ng = c[1];
+      return true;
+    }
+  return false;
+}
+template <int GS, int NG, int NT>
+hipError_t launch_stream(const BatchParams& P, int mode, int tiles, hipStream_t st) {
+  const size_t dyn = (size_t)GS * NG * 32 * 32;  // 32 bytes of token fragments per k
+  const void* kern = mode == 0 ? reinterpret_cast<const void*>(predict_stream_kernel<GS, NG, NT>)
+                               : reinterpret_cast<const void*>(k2_stream_kernel<GS, NG, NT>);
+  const hipError_t e = hipFuncSetAttribute(kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)dyn);
+  if (e != hipSuccess) return e;
+  const dim3 grid((tiles + kStreamWaves * NT - 1) / (kStreamWaves * NT), P.n_layers);
+  if (mode == 0) hipLaunchKernelGGL((predict_stream_kernel<GS, NG, NT>), grid, dim3(kStreamThreads), dyn, st, P);
+  else hipLaunchKernelGGL((k2_stream_kernel<GS, NG, NT>), grid, dim3(kStreamThreads), dyn, st, P);
+  return hipGetLastError();
+}
+template <int NT>
+hipError_t launch_stream_split(const BatchParams& P, int mode, int gs, int ng, int tiles, hipStream_t st) {
+  if (gs == 8 && ng == 2) return launch_stream<8, 2, NT>(P, mode, tiles, st);
+  if (gs == 8 && ng == 4) return launch_stream<8, 4, NT>(P, mode, tiles, st);
+  if (gs == 8 && ng == 6) return launch_stream<8, 6, NT>(P, mode, tiles, st);
+  if (gs == 8 && ng == 8) return launch_stream<8, 8, NT>(P, mode, tiles, st);
+  if (gs == 10 && ng == 4) return launch_stream<10, 4, NT>(P, mode, tiles, st);
+  return hipErrorInvalidValue;
+}
+
 int g_batch_tpw1 = 0, g_batch_tpw2 = 0, g_batch_ks = 0;  // tuning overrides (0 = automatic)
+int g_batch_stream = 1;                                  // 0: never take the streamed kernels, 2: wherever compiled
 
 }  // namespace
 
 void phased_batch_set_tuning(int tpw1, int tpw2, int ks) {
-  g_batch_ks = ks;
+  // 100 + ks: the k-split kernels for every batch size; 200 + ks: the streamed kernels wherever
+  // they are compiled, however small the launch
+  g_batch_stream = ks >= 200 ? 2 : ks >= 100 ? 0 : 1;
+  g_batch_ks = ks % 100;
   g_batch_tpw1 = tpw1 > 0 ? (tpw1 + 3) / 4 * 4 : 0;
   g_batch_tpw2 = tpw2 > 0 ? min(32, (tpw2 + 3) / 4 * 4) : 0;
 }
@@ -752,12 +959,29 @@ hipError_t launch_ffn_phased_batch(const FfnProblem& p0, const void* const* k1n,
     while (L * ksl > part_rows(p0.d_model)) --ksl;
     P.KS = ksl;
 
-    err = launch_rows_nb(P, 0, nb, p0.r, dim3((tiles + tpw1 - 1) / tpw1, L), st);
+    // one token block: the streamed kernels where a row's length is among the compiled ones;
+    // 16 tiles per workgroup when that still fills the chip, else 4
+    int gs = 0, ng = 0;
+    const bool few_wgs = (long long)L * ((tiles + 15) / 16) < 600;
+    // (k2 walks the union only: with few tokens it is small, and short workgroups spread it better)
+    const bool s1_short = g_batch_tpw1 > 0 ? g_batch_tpw1 < 16 : few_wgs, s2_short = g_batch_tpw2 > 0 ? g_batch_tpw2 < 16 : (few_wgs || B <= 4);
+    // (a launch too small to give every compute unit a streamed workgroup keeps the k-split kernels,
+    // whose workgroups have three times the waves)
+    const bool stream_ok = nb == 1 && (g_batch_stream == 2 || (g_batch_stream == 1 && (long long)L * ((tiles + 3) / 4) >= 256));
+    if (stream_ok && stream_split(p0.r, &gs, &ng))
+      err = s1_short ? launch_stream_split<1>(P, 0, gs, ng, tiles, st) : launch_stream_split<4>(P, 0, gs, ng, tiles, st);
+    else
+      err = launch_rows_nb(P, 0, nb, p0.r, dim3((tiles + tpw1 - 1) / tpw1, L), st);
     if (err != hipSuccess) return err;
     if (p0.d_ff <= 36 * kSelThreads) hipLaunchKernelGGL((select_batch_kernel<36>), dim3(B, L), dim3(kSelThreads), 0, st, P);
     else hipLaunchKernelGGL((select_batch_kernel<64>), dim3(B, L), dim3(kSelThreads), 0, st, P);
     hipLaunchKernelGGL(union_batch_kernel, dim3(L), dim3(4 * kMaxWords), 0, st, P);
-    err = launch_rows_nb(P, 1, nb, p0.d_model - p0.r, dim3((tiles + tpw2 - 1) / tpw2, L), st);
+    if (stream_ok && stream_split(p0.d_model - p0.r, &gs, &ng)) {
+      P.TPW2 = kStreamWaves * (s2_short ? 1 : 4);
+      err = s2_short ? launch_stream_split<1>(P, 1, gs, ng, tiles, st) : launch_stream_split<4>(P, 1, gs, ng, tiles, st);
+    } else {
+      err = launch_rows_nb(P, 1, nb, p0.d_model - p0.r, dim3((tiles + tpw2 - 1) / tpw2, L), st);
+    }
     if (err != hipSuccess) return err;
     const dim3 gv(slabs, ksl, L);
     const int nwv = v_waves(p0.d_model, nb);

@@ -314,3 +314,22 @@ def test_matrix_core_path_with_a_ragged_number_of_neurons(batch):
     q = synth.tokens(sh, batch, 612 + batch, torch.bfloat16)
     out = run_gpu_ffn(sh, weights, q, via_layers=True)
     check_ffn_against_oracle(sh, weights, q, out, TOL_BF16_TIGHT, what=f"ragged d_ff B={batch}")
+
+
+@pytest.mark.parametrize("d_model,d_ff,r,k", [(1024, 1000, 512, 77), (2304, 600, 1024, 48), (3584, 40, 1536, 5),
+                                              (1024, 2085, 512, 160)])
+@pytest.mark.parametrize("batch", [2, 7, 16])
+def test_streamed_kernels_of_one_token_block(d_model, d_ff, r, k, batch):
+    """At most 16 tokens: a wave takes whole 16-row tiles over the full row length.  Every compiled
+    row length (512, 1024, 1280, 1536, 2048), ragged numbers of neurons and of union tiles, one and
+    several layers; the switch makes small launches take these kernels too."""
+    sh = synth.FFNShape("stream", d_model, d_ff, r, k)
+    for n_layers in (1, 3):
+        weights = synth.ffn_stack(sh, n_layers, base_seed=700 + n_layers, dtype=torch.bfloat16)
+        q = synth.tokens(sh, batch, 710 + batch, torch.bfloat16)
+        binding.spark_debug_tuning(0, 0, 200)
+        try:
+            out = run_gpu_ffn(sh, weights, q, via_layers=True)
+        finally:
+            binding.spark_debug_tuning(0, 0, 0)
+        check_ffn_against_oracle(sh, weights, q, out, TOL_BF16_TIGHT, what=f"streamed B={batch} L={n_layers}")
