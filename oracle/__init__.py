@@ -56,6 +56,12 @@ def _load():
     lib.spark_ref_stat_topk_rows.restype = c_int
     lib.spark_ref_stat_topk_rows.argtypes = [vp, c_i64, c_i64, c_i64, c_i64, c_int, vp, c_i64,
                                              vp, vp, vp, vp, c_i64, c_int]
+    lib.spark_ref_huber.restype = c_d
+    lib.spark_ref_huber.argtypes = [c_d, c_d]
+    lib.spark_ref_huber_stat_topk_rows.restype = c_int
+    lib.spark_ref_huber_stat_topk_rows.argtypes = [vp, c_i64, c_i64, c_i64, c_d, vp, vp, c_int]
+    lib.spark_ref_huber_stat_topk_vjp_rows.restype = c_int
+    lib.spark_ref_huber_stat_topk_vjp_rows.argtypes = [vp, vp, c_i64, c_i64, c_i64, c_d, vp, c_int]
     lib.spark_ref_exact_topk.restype = c_int
     lib.spark_ref_exact_topk.argtypes = [vp, c_i64, c_i64, vp]
     lib.spark_ref_exact_topk_rows.restype = c_int
@@ -154,6 +160,40 @@ def stat_topk_rows(x, k: int, fill: int = FILL_ZERO, want_y: bool = True, want_i
                                           int(threads))
     _check(rc, "stat_topk_rows")
     return StatTopKRows(y, theta, std, count, idx)
+
+
+def huber(x: float, delta: float) -> float:
+    """Huber loss (Section 3.2, Eq.13) for one number."""
+    return float(_load().spark_ref_huber(float(x), float(delta)))
+
+
+def huber_stat_topk(x, k: int, delta: float, threads: int = 0):
+    """Huber(StatTop_k(x); delta) / delta (Section 3.2, Eq.14, Theorem 2) of a vector or of every row of a
+    matrix; delta = 0 gives StatTop_k itself.  Returns (y, theta) as float64 arrays."""
+    x = np.ascontiguousarray(x, dtype=np.float64)
+    x2 = x.reshape(1, -1) if x.ndim == 1 else x
+    rows, d = x2.shape
+    y = np.empty((rows, d), np.float64)
+    theta = np.empty(rows, np.float64)
+    rc = _load().spark_ref_huber_stat_topk_rows(_ptr(x2), rows, d, int(k), float(delta), _ptr(y), _ptr(theta),
+                                                int(threads))
+    _check(rc, "huber_stat_topk")
+    return (y[0], theta) if x.ndim == 1 else (y, theta)
+
+
+def huber_stat_topk_vjp(x, gy, k: int, delta: float, threads: int = 0) -> np.ndarray:
+    """gx = gy . d(Huber(StatTop_k(x); delta) / delta)/dx, per vector or per row, float64."""
+    x = np.ascontiguousarray(x, dtype=np.float64)
+    gy = np.ascontiguousarray(gy, dtype=np.float64)
+    if gy.shape != x.shape:
+        raise ValueError("gy must have the shape of x")
+    x2 = x.reshape(1, -1) if x.ndim == 1 else x
+    rows, d = x2.shape
+    gx = np.empty((rows, d), np.float64)
+    rc = _load().spark_ref_huber_stat_topk_vjp_rows(_ptr(x2), _ptr(gy.reshape(rows, d)), rows, d, int(k),
+                                                    float(delta), _ptr(gx), int(threads))
+    _check(rc, "huber_stat_topk_vjp")
+    return gx[0] if x.ndim == 1 else gx
 
 
 def exact_topk(x, k: int) -> np.ndarray:

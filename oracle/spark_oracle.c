@@ -158,6 +158,109 @@ int spark_ref_stat_topk_rows(const double* x, int64_t rows, int64_t d, int64_t l
 }
 
 /*
+ * Huber loss (Section 3.2, Eq.13), entrywise: x^2 / 2 for |x| < delta, delta (|x| - delta / 2)
+ * otherwise.
+ */
+double spark_ref_huber(double x, double delta) {
+  const double ax = fabs(x);
+  return ax < delta ? 0.5 * x * x : delta * (ax - 0.5 * delta);
+}
+
+/*
+ * Huber statistical top-k of one vector (Section 3.2, Eq.14): y = Huber(StatTop_k(x); delta)
+ * / delta, the continuously differentiable variant of Theorem 2.  delta = 0 is the limit
+ * the paper uses in practice, y = StatTop_k(x) (StatTop_k(x) >= 0, so Huber / delta -> |.|
+ * returns it unchanged).  stats as in spark_ref_stat_topk.
+ */
+int spark_ref_huber_stat_topk(const double* x, int64_t d, int64_t k, double delta, double* y,
+                              double* stats) {
+  if (!x || !y) return REF_ERR_NULL;
+  if (!(delta >= 0.0)) return REF_ERR_SHAPE;
+  const int rc = spark_ref_stat_topk(x, d, k, REF_FILL_ZERO, y, stats, NULL, NULL);
+  if (rc != REF_OK) return rc;
+  if (delta > 0.0)
+    for (int64_t i = 0; i < d; ++i) y[i] = spark_ref_huber(y[i], delta) / delta;
+  return REF_OK;
+}
+
+/*
+ * Vector-Jacobian product of the Huber statistical top-k: gx_j = sum_i gy_i * dy_i / dx_j.
+ * The operator is the composition used in the proof of Theorem 2 (Appendix A.2):
+ *   theta(x) = mean + std * z,         z = Q(1 - k/d) a constant,
+ *   y_i      = h(x_i, theta),          h = Huber(max(x - theta, 0); delta) / delta,
+ * whose partial derivatives the proof lists (divided by delta here):
+ *   dh/dx = -dh/dtheta = 1               for x > theta + delta,
+ *                        (x - theta)/delta  for theta <= x <= theta + delta,
+ *                        0               for x < theta
+ * (for delta = 0: 1 for x > theta, 0 otherwise: soft thresholding, differentiable except where
+ * an entry meets theta).  theta is a linear combination of the sample mean and the sample
+ * standard deviation (Eq.9, Eq.11):
+ *   d mean / dx_j = 1/d,   d std / dx_j = (x_j - mean) / ((d - 1) std).
+ * Chain rule: gx_j = gy_j * dh/dx(x_j) - (sum_i gy_i * dh/dx(x_i)) * dtheta/dx_j.
+ * A constant vector has std = 0: no entry exceeds theta, every dh/dx is 0 and gx = 0 (the
+ * derivative of std does not exist there and is not needed).
+ */
+int spark_ref_huber_stat_topk_vjp(const double* x, const double* gy, int64_t d, int64_t k,
+                                  double delta, double* gx) {
+  if (!x || !gy || !gx) return REF_ERR_NULL;
+  if (!(delta >= 0.0)) return REF_ERR_SHAPE;
+  double st[4];
+  const int rc = spark_ref_stat_topk(x, d, k, REF_FILL_ZERO, NULL, st, NULL, NULL);
+  if (rc != REF_OK) return rc;
+  const double mean = st[0], std = st[1], z = st[2], theta = st[3];
+  double total = 0.0;
+  for (int64_t i = 0; i < d; ++i) {
+    const double a = x[i] - theta;
+    double slope = 0.0;
+    if (a > 0.0) slope = (delta > 0.0 && a < delta) ? a / delta : 1.0;
+    gx[i] = gy[i] * slope;
+    total += gy[i] * slope;
+  }
+  if (total != 0.0)
+    for (int64_t j = 0; j < d; ++j) {
+      const double dstd = std > 0.0 ? (x[j] - mean) / ((double)(d - 1) * std) : 0.0;
+      gx[j] -= total * (1.0 / (double)d + z * dstd);
+    }
+  return REF_OK;
+}
+
+/* Row-wise forms over x[rows][d] (contiguous rows of length d). */
+int spark_ref_huber_stat_topk_rows(const double* x, int64_t rows, int64_t d, int64_t k, double delta,
+                                   double* y, double* theta, int threads) {
+  if (!x || !y) return REF_ERR_NULL;
+  if (rows < 0 || d < 2) return REF_ERR_SHAPE;
+  if (k < 1 || k > d - 1) return REF_ERR_K;
+  if (!(delta >= 0.0)) return REF_ERR_SHAPE;
+#ifdef _OPENMP
+  if (threads <= 0) threads = omp_get_max_threads();
+#endif
+  (void)threads;
+#pragma omp parallel for num_threads(threads) schedule(static)
+  for (int64_t row = 0; row < rows; ++row) {
+    double st[4];
+    spark_ref_huber_stat_topk(x + row * d, d, k, delta, y + row * d, st);
+    if (theta) theta[row] = st[3];
+  }
+  return REF_OK;
+}
+
+int spark_ref_huber_stat_topk_vjp_rows(const double* x, const double* gy, int64_t rows, int64_t d,
+                                       int64_t k, double delta, double* gx, int threads) {
+  if (!x || !gy || !gx) return REF_ERR_NULL;
+  if (rows < 0 || d < 2) return REF_ERR_SHAPE;
+  if (k < 1 || k > d - 1) return REF_ERR_K;
+  if (!(delta >= 0.0)) return REF_ERR_SHAPE;
+#ifdef _OPENMP
+  if (threads <= 0) threads = omp_get_max_threads();
+#endif
+  (void)threads;
+#pragma omp parallel for num_threads(threads) schedule(static)
+  for (int64_t row = 0; row < rows; ++row)
+    spark_ref_huber_stat_topk_vjp(x + row * d, gy + row * d, d, k, delta, gx + row * d);
+  return REF_OK;
+}
+
+/*
  * Exact top-k by sorting: indices of the k largest entries (ties: lower index first),
  * returned ascending by index.  Used to measure how far the statistical set is from the
  * sort-based one, and as the brute-force side of the nesting pin.

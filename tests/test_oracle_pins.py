@@ -519,3 +519,144 @@ def test_attention_invariances(oracle):
         a, b, v, qq = _attn_case(100 + seed, 8192, 32, 16)
         counts.append(oracle.spark_attention(a, b, v, qq, 256).count)
     assert abs(np.mean(counts) - 256) < 12 and min(counts) > 180 and max(counts) < 340
+
+
+# --------------------------------------------------------------------------- Huber statistical top-k (Eq.13, Eq.14) and its gradient
+def test_huber_is_the_library_huber(oracle):
+    for delta in (0.05, 0.7, 3.0):
+        for x in np.linspace(-5, 5, 41):
+            assert oracle.huber(x, delta) == pytest.approx(float(scipy.special.huber(delta, x)), rel=1e-14, abs=1e-300)
+
+
+def test_huber_stat_topk_piecewise_form_and_limits(oracle):
+    """The three cases listed in the proof of Theorem 2 (divided by delta), with the constant of the
+    first case taken from the Huber definition (delta^2 / 2: the value that makes the cases meet at
+    theta + delta); delta = 0 is StatTop_k itself; 0 <= StatTop_k(x) - y <= delta / 2."""
+    rng = np.random.default_rng(21)
+    x = rng.standard_normal(500)
+    base = oracle.stat_topk(x, 60)
+    y0, th0 = oracle.huber_stat_topk(x, 60, 0.0)
+    assert np.array_equal(y0, base.y) and th0[0] == base.theta
+    for delta in (1e-3, 0.2, 0.9, 50.0):
+        y, th = oracle.huber_stat_topk(x, 60, delta)
+        assert th[0] == base.theta
+        a = x - base.theta
+        want = np.where(a > delta, (delta * x - delta * base.theta - 0.5 * delta * delta) / delta,
+                        np.where(a >= 0, 0.5 * a * a / delta, 0.0))
+        assert np.allclose(y, want, rtol=1e-13, atol=1e-15)
+        assert np.all(base.y - y >= -1e-15) and np.all(base.y - y <= delta / 2 + 1e-15)
+        assert np.array_equal(y > 0, base.y > 0)
+    # the two branches meet at theta + delta, value and slope
+    d = 0.37
+    assert oracle.huber(d, d) / d == pytest.approx(d / 2, rel=1e-15)
+    eps = 1e-7
+    assert (oracle.huber(d + eps, d) - oracle.huber(d - eps, d)) / (2 * eps) / d == pytest.approx(1.0, abs=1e-6)
+
+
+def _fd_jacobian(f, x, h=1e-6):
+    J = np.empty((x.size, x.size))
+    for j in range(x.size):
+        e = np.zeros_like(x)
+        e[j] = h
+        J[:, j] = (f(x + e) - f(x - e)) / (2 * h)
+    return J
+
+
+@pytest.mark.parametrize("delta", [0.0, 0.05, 0.4, 5.0])
+def test_vjp_against_finite_differences_of_the_forward(oracle, delta):
+    """The whole Jacobian of the forward operator by central differences (the forward shares no code
+    with the gradient's formula), including the path through theta."""
+    rng = np.random.default_rng(5)
+    d, k = 14, 4
+    for trial in range(6):
+        x = rng.standard_normal(d) * (0.5 + trial)
+        if delta == 0.0:      # stay away from the kinks of plain soft thresholding
+            th = oracle.stat_topk(x, k).theta
+            if np.min(np.abs(x - th)) < 1e-3:
+                continue
+        J = _fd_jacobian(lambda v: oracle.huber_stat_topk(v, k, delta)[0], x)
+        for _ in range(3):
+            gy = rng.standard_normal(d)
+            got = oracle.huber_stat_topk_vjp(x, gy, k, delta)
+            assert np.allclose(got, gy @ J, rtol=2e-6, atol=2e-7)
+
+
+@pytest.mark.parametrize("delta", [0.0, 0.3])
+def test_vjp_against_automatic_differentiation(oracle, delta):
+    """The same operator written with library tensor ops (mean, unbiased std, clamp, where) and
+    differentiated by autograd in float64."""
+    g = torch.Generator().manual_seed(77)
+    rows, d, k = 5, 300, 31
+    x = torch.randn(rows, d, generator=g, dtype=torch.float64, requires_grad=True)
+    gy = torch.randn(rows, d, generator=g, dtype=torch.float64)
+    z = float(scipy.stats.norm.ppf(1 - k / d))
+    theta = x.mean(dim=1, keepdim=True) + x.std(dim=1, unbiased=True, keepdim=True) * z
+    a = torch.clamp(x - theta, min=0)
+    y = a if delta == 0 else torch.where(a < delta, 0.5 * a * a, delta * (a - 0.5 * delta)) / delta
+    y.backward(gy)
+    got = oracle.huber_stat_topk_vjp(x.detach().numpy(), gy.numpy(), k, delta)
+    assert np.allclose(got, x.grad.numpy(), rtol=1e-10, atol=1e-12)
+    yo, _ = oracle.huber_stat_topk(x.detach().numpy(), k, delta)
+    assert np.allclose(yo, y.detach().numpy(), rtol=1e-12, atol=1e-14)
+
+
+def test_vjp_invariants(oracle):
+    """y does not change when a constant is added to x, so every row of gx sums to zero; plain
+    StatTop_k is positively homogeneous of degree one, so gx . x = gy . y (Euler); a constant row
+    keeps nothing and gets a zero gradient."""
+    rng = np.random.default_rng(31)
+    x = rng.standard_normal((7, 200)) * 3 + 1
+    gy = rng.standard_normal((7, 200))
+    for delta in (0.0, 0.25):
+        gx = oracle.huber_stat_topk_vjp(x, gy, 20, delta)
+        assert np.allclose(gx.sum(axis=1), 0, atol=1e-12)
+    gx = oracle.huber_stat_topk_vjp(x, gy, 20, 0.0)
+    y, _ = oracle.huber_stat_topk(x, 20, 0.0)
+    assert np.allclose((gx * x).sum(axis=1), (gy * y).sum(axis=1), rtol=1e-11)
+    const = np.full(50, 2.5)
+    assert np.array_equal(oracle.huber_stat_topk_vjp(const, np.ones(50), 5, 0.1), np.zeros(50))
+    assert np.array_equal(oracle.huber_stat_topk(const, 5, 0.1)[0], np.zeros(50))
+
+
+def test_gradient_is_continuous_with_huber_and_jumps_without(oracle):
+    """Theorem 2: move one entry across the threshold; with delta > 0 the gradient changes by an
+    amount proportional to the step, with delta = 0 it jumps."""
+    rng = np.random.default_rng(41)
+    x = rng.standard_normal(120)
+    gy = np.ones(120)
+    k = 12
+    i = int(np.argmin(np.abs(x - oracle.stat_topk(x, k).theta)))
+
+    def active(t):
+        v = x.copy()
+        v[i] += t
+        return v[i] > oracle.stat_topk(v, k).theta
+
+    lo, hi = -1.0, 1.0
+    assert not active(lo) and active(hi)
+    for _ in range(60):
+        mid = 0.5 * (lo + hi)
+        lo, hi = (lo, mid) if active(mid) else (mid, hi)
+    for delta, smooth in ((0.2, True), (0.0, False)):
+        step = []
+        for gap in (1e-3, 1e-5):
+            a, b = x.copy(), x.copy()
+            a[i] += lo - gap
+            b[i] += hi + gap
+            step.append(np.max(np.abs(oracle.huber_stat_topk_vjp(a, gy, k, delta) -
+                                      oracle.huber_stat_topk_vjp(b, gy, k, delta))))
+        if smooth:
+            assert step[0] < 0.05 and step[1] < step[0] / 50
+        else:
+            assert step[1] > 0.5
+
+
+def test_huber_argument_errors(oracle):
+    x = np.arange(10.0)
+    for bad in (-0.1, float("nan")):
+        with pytest.raises(Exception):
+            oracle.huber_stat_topk(x, 3, bad)
+        with pytest.raises(Exception):
+            oracle.huber_stat_topk_vjp(x, x, 3, bad)
+    with pytest.raises(Exception):
+        oracle.huber_stat_topk_vjp(x, x, 10, 0.1)
