@@ -131,6 +131,21 @@ def stat_topk_bench(torch, binding, synth, dev, with_cpu):
                                   "launch_us": avg_s * 1e6},
                      "count_mean": float(count.float().mean()), "count_min": int(count.min()),
                      "count_max": int(count.max())}
+        # backward pass of the Huber-smoothed operator (gradient through theta): x and gy read
+        # once, gx written once
+        gy = synth.grad_rows(rows, n, seed=4243, dtype=dt, device=dev)
+
+        def back():
+            binding.spark_stat_topk_huber_backward(x, gy, k, 0.25, y)
+
+        bavg_s, _ = sampled_launch_time(back, 20, torch)
+        bbytes = 3.0 * rows * n * w
+        out[name]["backward"] = {"us_per_call": bavg_s * 1e6, "rows_per_s": rows / bavg_s, "delta": 0.25,
+                                 "roofline": {"bound": "hbm", "achieved": bbytes / bavg_s / 1e9, "peak": HBM_PEAK_GBS,
+                                              "unit": "GB/s", "frac": bbytes / bavg_s / 1e9 / HBM_PEAK_GBS,
+                                              "traffic": None, "kernel": "stat_topk_vjp_cached_kernel",
+                                              "bytes_per_launch": bbytes, "launch_us": bavg_s * 1e6}}
+        del gy
         if with_cpu and name == "f32":
             import oracle
             sample = 512

@@ -95,6 +95,43 @@ spark_status spark_stat_topk(const void* x, spark_dtype dt, int64_t rows, int64_
                              int64_t k, spark_fill fill, void* y, int64_t ldy, float* theta,
                              int32_t* count, int32_t* idx, int64_t idx_cap, void* hip_stream);
 
+/*
+ * The continuously differentiable variant of Section 3.2 (Eq.13, Eq.14, Theorem 2):
+ *   y = Huber(StatTop_k(x); delta) / delta,  Huber(a; delta) = a^2 / 2 for |a| < delta,
+ *                                            delta (|a| - delta / 2) otherwise,
+ * row by row; delta = 0 is the limit the paper uses in practice, y = StatTop_k(x).
+ *
+ *   x, y   [rows][n] of `dt`, row pitches ldx, ldy elements (>= n); y may alias x exactly
+ *   delta  >= 0, finite
+ *   theta  [rows] fp32                                                            out, optional
+ *
+ * fp32 arithmetic, rounded to nearest-even on store for bf16.  Needs no workspace.
+ * Errors as spark_stat_topk; delta negative, NaN or infinite -> SHAPE.
+ */
+spark_status spark_stat_topk_huber(const void* x, spark_dtype dt, int64_t rows, int64_t n,
+                                   int64_t ldx, int64_t k, float delta, void* y, int64_t ldy,
+                                   float* theta, void* hip_stream);
+
+/*
+ * Backward pass of spark_stat_topk_huber (and, with delta = 0, of spark_stat_topk with zero
+ * fill): gx[row] = gy[row] . dy/dx.  The gradient flows through the threshold as well
+ * (theta is a linear combination of the row's mean and standard deviation, both functions of
+ * x: Appendix A.2):
+ *   w_i  = gy_i * h'(x_i - theta) where x_i > theta, else 0,  h'(a) = a / delta below delta, else 1
+ *   gx_j = w_j - (sum_i w_i) * (1/n + Q(1 - k/n) (x_j - mean) / ((n - 1) std)).
+ * With delta = 0 the operator is not differentiable where an entry equals theta; the
+ * one-sided value 0 is used there.  A constant row (std = 0) keeps nothing and gets gx = 0.
+ *
+ *   x, gy, gx  [rows][n] of `dt`, row pitches ldx, ldgy, ldgx; gx may alias gy or x exactly
+ *
+ * Each of x and gy is read once and gx written once (rows up to 24576 fp32 / 32768 bf16
+ * elements; longer rows are re-read).  fp32 arithmetic.  Needs no workspace.  Errors as above.
+ */
+spark_status spark_stat_topk_huber_backward(const void* x, const void* gy, spark_dtype dt,
+                                            int64_t rows, int64_t n, int64_t ldx, int64_t ldgy,
+                                            int64_t k, float delta, void* gx, int64_t ldgx,
+                                            void* hip_stream);
+
 /* ------------------------------------------------------------------------------------------
  * One Spark-FFN layer (Eq.2).  Host struct holding device pointers.
  */

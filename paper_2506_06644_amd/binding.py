@@ -23,6 +23,7 @@ MAX_BATCH = 64
 
 EXPORTS = (
     "spark_status_string", "spark_version", "spark_normal_quantile", "spark_stat_topk",
+    "spark_stat_topk_huber", "spark_stat_topk_huber_backward",
     "spark_ffn_workspace_bytes", "spark_ffn_decode", "spark_ffn_decode_layers",
     "spark_ffn_dense_decode", "spark_ffn_dense_decode_layers", "spark_ffn_check",
     "spark_ffn_prefill_workspace_bytes", "spark_ffn_prefill",
@@ -74,6 +75,10 @@ def load_library():
     lib.spark_normal_quantile.argtypes = [ctypes.c_double]
     lib.spark_stat_topk.restype = c_int
     lib.spark_stat_topk.argtypes = [vp, c_int, i64, i64, i64, i64, c_int, vp, i64, vp, vp, vp, i64, vp]
+    lib.spark_stat_topk_huber.restype = c_int
+    lib.spark_stat_topk_huber.argtypes = [vp, c_int, i64, i64, i64, i64, ctypes.c_float, vp, i64, vp, vp]
+    lib.spark_stat_topk_huber_backward.restype = c_int
+    lib.spark_stat_topk_huber_backward.argtypes = [vp, vp, c_int, i64, i64, i64, i64, i64, ctypes.c_float, vp, i64, vp]
     lib.spark_ffn_workspace_bytes.restype = sz
     lib.spark_ffn_workspace_bytes.argtypes = [i32, i32, i32]
     lib.spark_ffn_decode.restype = c_int
@@ -154,6 +159,25 @@ def spark_stat_topk(x: torch.Tensor, k: int, fill: int = FILL_ZERO, y: Optional[
         _p(x), _dt(x), rows, n, x.stride(0), int(k), int(fill), _p(y),
         0 if y is None else y.stride(0), _p(theta), _p(count), _p(idx), idx_cap, _stream())
     _check(rc, "spark_stat_topk")
+
+
+def spark_stat_topk_huber(x: torch.Tensor, k: int, delta: float, y: torch.Tensor,
+                          theta: Optional[torch.Tensor] = None):
+    """``y = Huber(StatTop_k(x); delta) / delta`` row by row (``delta = 0``: StatTop_k itself)."""
+    rows, n = x.shape
+    rc = load_library().spark_stat_topk_huber(_p(x), _dt(x), rows, n, x.stride(0), int(k), float(delta), _p(y),
+                                              y.stride(0), _p(theta), _stream())
+    _check(rc, "spark_stat_topk_huber")
+
+
+def spark_stat_topk_huber_backward(x: torch.Tensor, gy: torch.Tensor, k: int, delta: float, gx: torch.Tensor):
+    """``gx = gy . dy/dx`` of :func:`spark_stat_topk_huber`, row by row (same dtype for all three)."""
+    rows, n = x.shape
+    if gy.dtype != x.dtype or gx.dtype != x.dtype or gy.shape != x.shape or gx.shape != x.shape:
+        raise ValueError("x, gy and gx must share shape and dtype")
+    rc = load_library().spark_stat_topk_huber_backward(_p(x), _p(gy), _dt(x), rows, n, x.stride(0), gy.stride(0),
+                                                       int(k), float(delta), _p(gx), gx.stride(0), _stream())
+    _check(rc, "spark_stat_topk_huber_backward")
 
 
 def make_layer(k1n: torch.Tensor, k2n: torch.Tensor, vn: torch.Tensor, k: int, gelu: int = GELU_ERF) -> _Layer:

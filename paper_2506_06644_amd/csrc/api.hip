@@ -163,9 +163,42 @@ spark_status spark_stat_topk(const void* x, spark_dtype dt, int64_t rows, int64_
   if (!aligned16(x) || (ldx * es) % 16) return SPARK_ERR_ALIGN;
   if (y && (!aligned16(y) || (ldy * es) % 16)) return SPARK_ERR_ALIGN;
   const float z = (float)spark_normal_quantile(1.0 - (double)k / (double)n);
-  const hipError_t e = spark::launch_stat_topk(x, dt == SPARK_BF16, rows, n, ldx, z, fill == SPARK_FILL_NEG_INF,
+  const hipError_t e = spark::launch_stat_topk(x, dt == SPARK_BF16, rows, n, ldx, z, fill == SPARK_FILL_NEG_INF, 0.f,
                                                y, ldy, theta, count, idx, idx_cap, nullptr,
                                                static_cast<hipStream_t>(hip_stream));
+  return e == hipSuccess ? SPARK_OK : SPARK_ERR_DEVICE;
+}
+
+spark_status spark_stat_topk_huber(const void* x, spark_dtype dt, int64_t rows, int64_t n, int64_t ldx, int64_t k,
+                                   float delta, void* y, int64_t ldy, float* theta, void* hip_stream) {
+  if (!x || !y) return SPARK_ERR_NULL;
+  if (!dtype_ok(dt)) return SPARK_ERR_DTYPE;
+  if (rows < 0 || rows > 2147483647LL || n < 2 || n > 2147483647LL || ldx < n || ldy < n) return SPARK_ERR_SHAPE;
+  if (!(delta >= 0.f) || std::isinf(delta)) return SPARK_ERR_SHAPE;
+  if (k < 1 || k > n - 1) return SPARK_ERR_K;
+  const size_t es = dtype_size(dt);
+  if (!aligned16(x) || (ldx * es) % 16 || !aligned16(y) || (ldy * es) % 16) return SPARK_ERR_ALIGN;
+  const float z = (float)spark_normal_quantile(1.0 - (double)k / (double)n);
+  const hipError_t e = spark::launch_stat_topk(x, dt == SPARK_BF16, rows, n, ldx, z, 0, delta, y, ldy, theta, nullptr,
+                                               nullptr, 0, nullptr, static_cast<hipStream_t>(hip_stream));
+  return e == hipSuccess ? SPARK_OK : SPARK_ERR_DEVICE;
+}
+
+spark_status spark_stat_topk_huber_backward(const void* x, const void* gy, spark_dtype dt, int64_t rows, int64_t n,
+                                            int64_t ldx, int64_t ldgy, int64_t k, float delta, void* gx,
+                                            int64_t ldgx, void* hip_stream) {
+  if (!x || !gy || !gx) return SPARK_ERR_NULL;
+  if (!dtype_ok(dt)) return SPARK_ERR_DTYPE;
+  if (rows < 0 || rows > 2147483647LL || n < 2 || n > 2147483647LL || ldx < n || ldgy < n || ldgx < n)
+    return SPARK_ERR_SHAPE;
+  if (!(delta >= 0.f) || std::isinf(delta)) return SPARK_ERR_SHAPE;
+  if (k < 1 || k > n - 1) return SPARK_ERR_K;
+  const size_t es = dtype_size(dt);
+  if (!aligned16(x) || (ldx * es) % 16 || !aligned16(gy) || (ldgy * es) % 16 || !aligned16(gx) || (ldgx * es) % 16)
+    return SPARK_ERR_ALIGN;
+  const float z = (float)spark_normal_quantile(1.0 - (double)k / (double)n);
+  const hipError_t e = spark::launch_stat_topk_vjp(x, gy, dt == SPARK_BF16, rows, n, ldx, ldgy, z, delta, gx, ldgx,
+                                                   static_cast<hipStream_t>(hip_stream));
   return e == hipSuccess ? SPARK_OK : SPARK_ERR_DEVICE;
 }
 

@@ -588,7 +588,7 @@ hipError_t launch_general_t(const FfnProblem& p, const FfnWorkspace& ws, int den
   if (dense && B == 1) {
     hipLaunchKernelGGL((dense_rows_kernel<WT>), dim3(2048), dim3(256), (size_t)p.d_model * 4, st, k1n, k2n, p.d_ff,
                        p.r, r2, p.q, p.q_bf16, ws.S, ws.uact, ws.flags, static_cast<int32_t*>(ws.fused));
-    hipError_t e = launch_stat_topk(ws.S, 0, 1, p.d_ff, p.d_ff, p.z, 0, ws.A, p.d_ff, p.theta, p.active_count,
+    hipError_t e = launch_stat_topk(ws.S, 0, 1, p.d_ff, p.d_ff, p.z, 0, 0.f, ws.A, p.d_ff, p.theta, p.active_count,
                                     p.active_idx, p.d_ff, nullptr, st);
     if (e != hipSuccess) return e;
     constexpr int VEC = Vec16<WT>::N;
@@ -612,7 +612,7 @@ hipError_t launch_general_t(const FfnProblem& p, const FfnWorkspace& ws, int den
       if (nb == 1) SPARK_LAUNCH_ROWS(1, 0, k1n, p.r, 0, ws.S);
       else if (nb == 2) SPARK_LAUNCH_ROWS(2, 0, k1n, p.r, 0, ws.S);
       else SPARK_LAUNCH_ROWS(4, 0, k1n, p.r, 0, ws.S);
-      hipError_t e = launch_stat_topk(ws.S, 0, B, p.d_ff, p.d_ff, p.z, 0, ws.A, p.d_ff, p.theta, p.active_count,
+      hipError_t e = launch_stat_topk(ws.S, 0, B, p.d_ff, p.d_ff, p.z, 0, 0.f, ws.A, p.d_ff, p.theta, p.active_count,
                                       p.active_idx, p.d_ff, ws.flags, st);
       if (e != hipSuccess) return e;
       hipLaunchKernelGGL(union_kernel, dim3(1), dim3(1024), 0, st, ws.flags, p.d_ff, ws.uidx, ws.ucount,
@@ -646,7 +646,7 @@ hipError_t launch_general_t(const FfnProblem& p, const FfnWorkspace& ws, int den
       hipLaunchKernelGGL((predict_kernel<WT, 4>), dim3(grid), dim3(kBlock), 0, st, k1n, p.d_ff, p.r, p.q,
                          p.q_bf16, p.ldq, B, ws.S, ws.flags, static_cast<int32_t*>(ws.fused));
   }
-  hipError_t e = launch_stat_topk(ws.S, 0, B, p.d_ff, p.d_ff, p.z, 0, ws.A, p.d_ff, p.theta, p.active_count,
+  hipError_t e = launch_stat_topk(ws.S, 0, B, p.d_ff, p.d_ff, p.z, 0, 0.f, ws.A, p.d_ff, p.theta, p.active_count,
                                   p.active_idx, p.d_ff, ws.flags, st);
   if (e != hipSuccess) return e;
   hipLaunchKernelGGL(union_kernel, dim3(1), dim3(1024), 0, st, ws.flags, p.d_ff, ws.uidx, ws.ucount,

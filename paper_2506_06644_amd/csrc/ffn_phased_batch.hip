@@ -402,14 +402,12 @@ __device__ __forceinline__ void k2_store_u(const BatchParams& P, uint16_t* up, i
   }
 #pragma unroll
   for (int pl = 0; pl < kPlanes; ++pl) {
-    uint32_t h[4];
-#pragma unroll
-    for (int e = 0; e < 4; ++e) {
-      h[e] = float_to_bf16_rne(rest[e]);
-      rest[e] -= bf16_bits_to_float(h[e]);
-    }
-    *reinterpret_cast<u32x2*>(up + pl * P.plane + ((size_t)(rho >> 3) * P.B + b) * 8 + (rho & 7)) =
-        u32x2{h[0] | (h[1] << 16), h[2] | (h[3] << 16)};
+    const uint32_t w01 = pack_bf16x2_rne(rest[0], rest[1]), w23 = pack_bf16x2_rne(rest[2], rest[3]);
+    rest[0] -= bf16_lo(w01);
+    rest[1] -= bf16_hi(w01);
+    rest[2] -= bf16_lo(w23);
+    rest[3] -= bf16_hi(w23);
+    *reinterpret_cast<u32x2*>(up + pl * P.plane + ((size_t)(rho >> 3) * P.B + b) * 8 + (rho & 7)) = u32x2{w01, w23};
   }
 }
 

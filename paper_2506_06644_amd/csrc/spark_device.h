@@ -20,12 +20,16 @@ __device__ __forceinline__ float bf16_bits_to_float(uint32_t b) { return __uint_
 __device__ __forceinline__ float bf16_lo(uint32_t w) { return __uint_as_float(w << 16); }
 __device__ __forceinline__ float bf16_hi(uint32_t w) { return __uint_as_float(w & 0xffff0000u); }
 
-// fp32 -> bf16, round to nearest even; NaN stays NaN, +-inf stays +-inf.
+// fp32 -> bf16, round to nearest even; NaN stays NaN, +-inf stays +-inf (the target's own
+// conversion instruction, two values at a time).
 __device__ __forceinline__ uint16_t float_to_bf16_rne(float f) {
-  uint32_t u = __float_as_uint(f);
-  if ((u & 0x7fffffffu) > 0x7f800000u) return (uint16_t)((u >> 16) | 0x0040u);
-  u += 0x7fffu + ((u >> 16) & 1u);
-  return (uint16_t)(u >> 16);
+  return __builtin_bit_cast(uint16_t, static_cast<__bf16>(f));
+}
+// (lo, hi) -> one 32-bit word holding the two bf16 values
+__device__ __forceinline__ uint32_t pack_bf16x2_rne(float lo, float hi) {
+  typedef __bf16 bf16x2_v __attribute__((ext_vector_type(2)));
+  typedef float f32x2_v __attribute__((ext_vector_type(2)));
+  return __builtin_bit_cast(uint32_t, __builtin_convertvector(f32x2_v{lo, hi}, bf16x2_v));
 }
 
 // One 16-byte vector of storage type T seen as VEC floats.
@@ -38,6 +42,11 @@ struct Vec16<float> {
   f32x4 raw;
   __device__ __forceinline__ float get(int i) const { return raw[i]; }
   __device__ __forceinline__ void set(int i, float v) { raw[i] = v; }
+  // elements 2 i and 2 i + 1 at once
+  __device__ __forceinline__ void set2(int i, float v0, float v1) {
+    raw[2 * i] = v0;
+    raw[2 * i + 1] = v1;
+  }
   __device__ __forceinline__ static float load1(const float* p) { return *p; }
   __device__ __forceinline__ static void store1(float* p, float v) { *p = v; }
 };
@@ -56,6 +65,7 @@ struct Vec16<bf16_t> {
     w = (i & 1) ? ((w & 0x0000ffffu) | (h << 16)) : ((w & 0xffff0000u) | h);
     raw[i >> 1] = w;
   }
+  __device__ __forceinline__ void set2(int i, float v0, float v1) { raw[i] = pack_bf16x2_rne(v0, v1); }
   __device__ __forceinline__ static float load1(const bf16_t* p) { return bf16_bits_to_float(p->bits); }
   __device__ __forceinline__ static void store1(bf16_t* p, float v) { p->bits = float_to_bf16_rne(v); }
 };

@@ -9,9 +9,13 @@ namespace spark {
 
 // Row-wise statistical top-k.  dt: 0 = fp32, 1 = bf16.  `flags`, when given, receives a 1 at
 // every active column (used to form the union of the active sets of a batch).
+// delta > 0: the kept entries are mapped through Huber(.; delta) / delta (0: plain soft threshold)
 hipError_t launch_stat_topk(const void* x, int dt, int64_t rows, int64_t n, int64_t ldx, float z,
-                            int fill, void* y, int64_t ldy, float* theta, int32_t* count,
+                            int fill, float delta, void* y, int64_t ldy, float* theta, int32_t* count,
                             int32_t* idx, int64_t idx_cap, int32_t* flags, hipStream_t st);
+// gx = gy . d(Huber(StatTop_k(x); delta) / delta)/dx, row by row
+hipError_t launch_stat_topk_vjp(const void* x, const void* gy, int dt, int64_t rows, int64_t n, int64_t ldx,
+                                int64_t ldgy, float z, float delta, void* gx, int64_t ldgx, hipStream_t st);
 
 struct FfnProblem {
   int d_model, d_ff, r, k;

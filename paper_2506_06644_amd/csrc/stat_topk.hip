@@ -35,9 +35,19 @@ __device__ __forceinline__ void wave0_exclusive_scan(int* tab, int n) {
   }
 }
 
+// Huber(a; delta) / delta for a > 0 (Section 3.2, Eq.13 / Eq.14): a^2 / (2 delta) below delta,
+// a - delta / 2 from there on; delta = 0 leaves a as it is (plain soft thresholding).  The
+// kernels pass 1 / delta, formed once per thread (a division per element costs as much as the
+// rest of the pass); it is not used when delta = 0, where no a > 0 is below delta.
+__device__ __forceinline__ float huber_over_delta(float a, float delta, float inv_delta) {
+  return a < delta ? 0.5f * a * a * inv_delta : a - 0.5f * delta;
+}
+// Its derivative in a (Appendix A.2): a / delta below delta, 1 from there on.
+__device__ __forceinline__ float huber_slope(float a, float delta, float inv_delta) { return a < delta ? a * inv_delta : 1.f; }
+
 template <typename T, int THREADS, int ITEMS>
 __global__ __launch_bounds__(THREADS) void stat_topk_cached_kernel(
-    const T* x, int64_t ldx, int n, float z, int fill_neg_inf, T* y, int64_t ldy,
+    const T* x, int64_t ldx, int n, float z, int fill_neg_inf, float delta, T* y, int64_t ldy,
     float* __restrict__ theta_out, int32_t* __restrict__ count_out, int32_t* __restrict__ idx_out,
     int64_t idx_cap, int32_t* __restrict__ flags) {
   constexpr int VEC = Vec16<T>::N;
@@ -88,6 +98,7 @@ __global__ __launch_bounds__(THREADS) void stat_topk_cached_kernel(
   const float m2 = block_sum<THREADS>(ss, red);
   const float sd = sqrtf(m2 / (float)(n - 1));
   const float theta = mean + sd * z;
+  const float inv_delta = delta > 0.f ? 1.f / delta : 0.f;
   if (tid == 0 && theta_out) theta_out[row] = theta;
 
   const float fillv = fill_neg_inf ? -__builtin_inff() : 0.f;
@@ -114,7 +125,9 @@ __global__ __launch_bounds__(THREADS) void stat_topk_cached_kernel(
       if (nv[i] == 0) continue;
       Vec16<T> o;
 #pragma unroll
-      for (int e = 0; e < VEC; ++e) o.set(e, ((act[i] >> e) & 1u) ? v[i].get(e) - theta : fillv);
+      for (int e = 0; e < VEC; e += 2)
+        o.set2(e / 2, ((act[i] >> e) & 1u) ? huber_over_delta(v[i].get(e) - theta, delta, inv_delta) : fillv,
+               ((act[i] >> (e + 1)) & 1u) ? huber_over_delta(v[i].get(e + 1) - theta, delta, inv_delta) : fillv);
       if (nv[i] == VEC) {
         __builtin_nontemporal_store(o.raw, reinterpret_cast<decltype(o.raw)*>(yr + (int64_t)vi * VEC));
       } else {
@@ -175,7 +188,7 @@ __global__ __launch_bounds__(THREADS) void stat_topk_cached_kernel(
 // Fallback for rows that do not fit the register file: three reads of the row.
 template <typename T, int THREADS>
 __global__ __launch_bounds__(THREADS) void stat_topk_stream_kernel(
-    const T* x, int64_t ldx, int n, float z, int fill_neg_inf, T* y, int64_t ldy,
+    const T* x, int64_t ldx, int n, float z, int fill_neg_inf, float delta, T* y, int64_t ldy,
     float* __restrict__ theta_out, int32_t* __restrict__ count_out, int32_t* __restrict__ idx_out,
     int64_t idx_cap, int32_t* __restrict__ flags) {
   constexpr int NW = THREADS / kWave;
@@ -197,6 +210,7 @@ __global__ __launch_bounds__(THREADS) void stat_topk_stream_kernel(
   }
   const float m2 = block_sum<THREADS>(ss, red);
   const float theta = mean + sqrtf(m2 / (float)(n - 1)) * z;
+  const float inv_delta = delta > 0.f ? 1.f / delta : 0.f;
   if (tid == 0 && theta_out) theta_out[row] = theta;
   const float fillv = fill_neg_inf ? -__builtin_inff() : 0.f;
   if (tid == 0) running = 0;
@@ -210,7 +224,7 @@ __global__ __launch_bounds__(THREADS) void stat_topk_stream_kernel(
     if (i < n) {
       xv = Vec16<T>::load1(xr + i);
       a = xv > theta;
-      if (y) Vec16<T>::store1(y + row * ldy + i, a ? xv - theta : fillv);
+      if (y) Vec16<T>::store1(y + row * ldy + i, a ? huber_over_delta(xv - theta, delta, inv_delta) : fillv);
       if (a && flags) flags[i] = 1;
     }
     cnt += a;
@@ -238,7 +252,7 @@ __global__ __launch_bounds__(THREADS) void stat_topk_stream_kernel(
 }
 
 template <typename T>
-hipError_t launch_stat_topk_t(const T* x, int64_t rows, int64_t n, int64_t ldx, float z, int fill,
+hipError_t launch_stat_topk_t(const T* x, int64_t rows, int64_t n, int64_t ldx, float z, int fill, float delta,
                               T* y, int64_t ldy, float* theta, int32_t* count, int32_t* idx,
                               int64_t idx_cap, int32_t* flags, hipStream_t st) {
   if (rows == 0) return hipSuccess;
@@ -247,7 +261,7 @@ hipError_t launch_stat_topk_t(const T* x, int64_t rows, int64_t n, int64_t ldx, 
   const dim3 grid((unsigned)rows);
 #define SPARK_LAUNCH_CACHED(THREADS, ITEMS)                                                        \
   hipLaunchKernelGGL((stat_topk_cached_kernel<T, THREADS, ITEMS>), grid, dim3(THREADS), 0, st, x, \
-                     ldx, (int)n, z, fill, y, ldy, theta, count, idx, idx_cap, flags)
+                     ldx, (int)n, z, fill, delta, y, ldy, theta, count, idx, idx_cap, flags)
   if (nvec <= 256 * 1) SPARK_LAUNCH_CACHED(256, 1);
   else if (nvec <= 256 * 2) SPARK_LAUNCH_CACHED(256, 2);
   else if (nvec <= 256 * 5) SPARK_LAUNCH_CACHED(256, 5);
@@ -259,21 +273,201 @@ hipError_t launch_stat_topk_t(const T* x, int64_t rows, int64_t n, int64_t ldx, 
     if constexpr (sizeof(T) == 4) SPARK_LAUNCH_CACHED(1024, 16);
   } else
     hipLaunchKernelGGL((stat_topk_stream_kernel<T, 1024>), grid, dim3(1024), 0, st, x, ldx, (int)n,
-                       z, fill, y, ldy, theta, count, idx, idx_cap, flags);
+                       z, fill, delta, y, ldy, theta, count, idx, idx_cap, flags);
 #undef SPARK_LAUNCH_CACHED
+  return hipGetLastError();
+}
+
+
+// Between the passes over a row held in registers: the packed vectors are declared changed, so
+// the compiler unpacks bf16 pairs again in the next pass (one shift or mask per element)
+// instead of keeping every widened value alive across the passes, which triples the registers
+// of a thread and halves the rows in flight per compute unit.
+template <typename V, int N>
+__device__ __forceinline__ void forget_unpacked(V (&v)[N]) {
+#pragma unroll
+  for (int i = 0; i < N; ++i) asm volatile("" : "+v"(v[i].raw));
+}
+
+// ------------------------------------------------------------------------------- backward
+// gx = gy . d(Huber(StatTop_k(x); delta) / delta)/dx for one row per workgroup (chain rule
+// through theta = mean + z std, Appendix A.2):
+//   w_i  = gy_i * slope(x_i - theta) where x_i > theta, else 0;   G = sum_i w_i
+//   gx_j = w_j - G * (1/n + z (x_j - mean) / ((n - 1) std))
+// x and gy are each read once (both rows sit in registers), gx is written once.  A constant
+// row (std = 0) has no active entry: G = 0 and gx = 0.
+template <typename T, int THREADS, int ITEMS>
+__global__ __launch_bounds__(THREADS) void stat_topk_vjp_cached_kernel(const T* x, int64_t ldx, const T* gy, int64_t ldgy,
+                                                                      int n, float z, float delta, T* gx, int64_t ldgx) {
+  constexpr int VEC = Vec16<T>::N;
+  constexpr int NW = THREADS / kWave;
+  __shared__ float red[NW];
+  const int tid = threadIdx.x;
+  const int64_t row = blockIdx.x;
+  const T* xr = x + row * ldx;
+  const T* gr = gy + row * ldgy;
+  const int nfull = n / VEC, tail = n - nfull * VEC;
+
+  Vec16<T> v[ITEMS], g[ITEMS];
+  int nv[ITEMS];
+#pragma unroll
+  for (int i = 0; i < ITEMS; ++i) {
+    const int vi = i * THREADS + tid;
+    nv[i] = vi < nfull ? VEC : (vi == nfull ? tail : 0);
+    v[i].raw = (decltype(v[i].raw))(0);
+    g[i].raw = (decltype(g[i].raw))(0);
+    if (vi < nfull) {
+      v[i].raw = __builtin_nontemporal_load(reinterpret_cast<const decltype(v[i].raw)*>(xr + (int64_t)vi * VEC));
+      g[i].raw = __builtin_nontemporal_load(reinterpret_cast<const decltype(g[i].raw)*>(gr + (int64_t)vi * VEC));
+    } else if (vi == nfull) {
+#pragma unroll
+      for (int e = 0; e < VEC; ++e)
+        if (e < tail) {
+          v[i].set(e, Vec16<T>::load1(xr + (int64_t)vi * VEC + e));
+          g[i].set(e, Vec16<T>::load1(gr + (int64_t)vi * VEC + e));
+        }
+    }
+  }
+  float s = 0.f;
+#pragma unroll
+  for (int i = 0; i < ITEMS; ++i)
+#pragma unroll
+    for (int e = 0; e < VEC; ++e) s += (e < nv[i]) ? v[i].get(e) : 0.f;
+  const float mean = block_sum<THREADS>(s, red) / (float)n;
+  forget_unpacked(v);
+  float ss = 0.f;
+#pragma unroll
+  for (int i = 0; i < ITEMS; ++i)
+#pragma unroll
+    for (int e = 0; e < VEC; ++e) {
+      const float c = v[i].get(e) - mean;
+      ss += (e < nv[i]) ? c * c : 0.f;
+    }
+  const float m2 = block_sum<THREADS>(ss, red);
+  const float sd = sqrtf(m2 / (float)(n - 1));
+  const float theta = mean + sd * z;
+  const float inv_delta = delta > 0.f ? 1.f / delta : 0.f;
+  forget_unpacked(v);
+  float wsum = 0.f;
+#pragma unroll
+  for (int i = 0; i < ITEMS; ++i)
+#pragma unroll
+    for (int e = 0; e < VEC; ++e) {
+      const float a = v[i].get(e) - theta;
+      wsum += (e < nv[i] && a > 0.f) ? g[i].get(e) * huber_slope(a, delta, inv_delta) : 0.f;
+    }
+  const float G = block_sum<THREADS>(wsum, red);
+  forget_unpacked(v);
+  forget_unpacked(g);
+  const float c0 = G / (float)n, c1 = sd > 0.f ? G * z / ((float)(n - 1) * sd) : 0.f;
+  T* or_ = gx + row * ldgx;
+#pragma unroll
+  for (int i = 0; i < ITEMS; ++i) {
+    const int vi = i * THREADS + tid;
+    if (nv[i] == 0) continue;
+    Vec16<T> o;
+#pragma unroll
+    for (int e = 0; e < VEC; e += 2) {
+      float r[2];
+#pragma unroll
+      for (int h = 0; h < 2; ++h) {
+        const float xv = v[i].get(e + h), a = xv - theta;
+        const float w = a > 0.f ? g[i].get(e + h) * huber_slope(a, delta, inv_delta) : 0.f;
+        r[h] = w - (c0 + c1 * (xv - mean));
+      }
+      o.set2(e / 2, r[0], r[1]);
+    }
+    if (nv[i] == VEC) {
+      __builtin_nontemporal_store(o.raw, reinterpret_cast<decltype(o.raw)*>(or_ + (int64_t)vi * VEC));
+    } else {
+#pragma unroll
+      for (int e = 0; e < VEC; ++e)
+        if (e < nv[i]) Vec16<T>::store1(or_ + (int64_t)vi * VEC + e, o.get(e));
+    }
+  }
+}
+
+// Rows too long for the register file: x is read three times, gy twice.
+template <typename T, int THREADS>
+__global__ __launch_bounds__(THREADS) void stat_topk_vjp_stream_kernel(const T* x, int64_t ldx, const T* gy, int64_t ldgy,
+                                                                      int n, float z, float delta, T* gx, int64_t ldgx) {
+  constexpr int NW = THREADS / kWave;
+  __shared__ float red[NW];
+  const int tid = threadIdx.x;
+  const int64_t row = blockIdx.x;
+  const T* xr = x + row * ldx;
+  const T* gr = gy + row * ldgy;
+  float s = 0.f;
+  for (int i = tid; i < n; i += THREADS) s += Vec16<T>::load1(xr + i);
+  const float mean = block_sum<THREADS>(s, red) / (float)n;
+  float ss = 0.f;
+  for (int i = tid; i < n; i += THREADS) {
+    const float c = Vec16<T>::load1(xr + i) - mean;
+    ss += c * c;
+  }
+  const float m2 = block_sum<THREADS>(ss, red);
+  const float sd = sqrtf(m2 / (float)(n - 1));
+  const float theta = mean + sd * z;
+  const float inv_delta = delta > 0.f ? 1.f / delta : 0.f;
+  float wsum = 0.f;
+  for (int i = tid; i < n; i += THREADS) {
+    const float a = Vec16<T>::load1(xr + i) - theta;
+    if (a > 0.f) wsum += Vec16<T>::load1(gr + i) * huber_slope(a, delta, inv_delta);
+  }
+  const float G = block_sum<THREADS>(wsum, red);
+  const float c0 = G / (float)n, c1 = sd > 0.f ? G * z / ((float)(n - 1) * sd) : 0.f;
+  for (int i = tid; i < n; i += THREADS) {
+    const float xv = Vec16<T>::load1(xr + i), a = xv - theta;
+    const float w = a > 0.f ? Vec16<T>::load1(gr + i) * huber_slope(a, delta, inv_delta) : 0.f;
+    Vec16<T>::store1(gx + row * ldgx + i, w - (c0 + c1 * (xv - mean)));
+  }
+}
+
+template <typename T>
+hipError_t launch_stat_topk_vjp_t(const T* x, const T* gy, int64_t rows, int64_t n, int64_t ldx, int64_t ldgy, float z,
+                                  float delta, T* gx, int64_t ldgx, hipStream_t st) {
+  if (rows == 0) return hipSuccess;
+  constexpr int VEC = Vec16<T>::N;
+  const int64_t nvec = (n + VEC - 1) / VEC;
+  const dim3 grid((unsigned)rows);
+#define SPARK_LAUNCH_VJP(THREADS, ITEMS)                                                                   \
+  hipLaunchKernelGGL((stat_topk_vjp_cached_kernel<T, THREADS, ITEMS>), grid, dim3(THREADS), 0, st, x, ldx, \
+                     gy, ldgy, (int)n, z, delta, gx, ldgx)
+  // two rows of registers per thread: more threads per row than the forward kernel uses
+  if (nvec <= 256 * 1) SPARK_LAUNCH_VJP(256, 1);
+  else if (nvec <= 256 * 2) SPARK_LAUNCH_VJP(256, 2);
+  else if (nvec <= 256 * 4) SPARK_LAUNCH_VJP(256, 4);
+  else if (nvec <= 512 * 3) SPARK_LAUNCH_VJP(512, 3);
+  else if (nvec <= 512 * 5) SPARK_LAUNCH_VJP(512, 5);
+  else if (nvec <= 1024 * 4) SPARK_LAUNCH_VJP(1024, 4);
+  else if (sizeof(T) == 4 && nvec <= 1024 * 6) {
+    if constexpr (sizeof(T) == 4) SPARK_LAUNCH_VJP(1024, 6);
+  } else
+    hipLaunchKernelGGL((stat_topk_vjp_stream_kernel<T, 1024>), grid, dim3(1024), 0, st, x, ldx, gy, ldgy, (int)n, z,
+                       delta, gx, ldgx);
+#undef SPARK_LAUNCH_VJP
   return hipGetLastError();
 }
 
 }  // namespace
 
 hipError_t launch_stat_topk(const void* x, int dt, int64_t rows, int64_t n, int64_t ldx, float z,
-                            int fill, void* y, int64_t ldy, float* theta, int32_t* count,
+                            int fill, float delta, void* y, int64_t ldy, float* theta, int32_t* count,
                             int32_t* idx, int64_t idx_cap, int32_t* flags, hipStream_t st) {
   if (dt == 0)
-    return launch_stat_topk_t<float>(static_cast<const float*>(x), rows, n, ldx, z, fill,
+    return launch_stat_topk_t<float>(static_cast<const float*>(x), rows, n, ldx, z, fill, delta,
                                      static_cast<float*>(y), ldy, theta, count, idx, idx_cap, flags, st);
-  return launch_stat_topk_t<bf16_t>(static_cast<const bf16_t*>(x), rows, n, ldx, z, fill,
+  return launch_stat_topk_t<bf16_t>(static_cast<const bf16_t*>(x), rows, n, ldx, z, fill, delta,
                                     static_cast<bf16_t*>(y), ldy, theta, count, idx, idx_cap, flags, st);
+}
+
+hipError_t launch_stat_topk_vjp(const void* x, const void* gy, int dt, int64_t rows, int64_t n, int64_t ldx,
+                                int64_t ldgy, float z, float delta, void* gx, int64_t ldgx, hipStream_t st) {
+  if (dt == 0)
+    return launch_stat_topk_vjp_t<float>(static_cast<const float*>(x), static_cast<const float*>(gy), rows, n, ldx,
+                                         ldgy, z, delta, static_cast<float*>(gx), ldgx, st);
+  return launch_stat_topk_vjp_t<bf16_t>(static_cast<const bf16_t*>(x), static_cast<const bf16_t*>(gy), rows, n, ldx,
+                                        ldgy, z, delta, static_cast<bf16_t*>(gx), ldgx, st);
 }
 
 }  // namespace spark

@@ -120,6 +120,12 @@ def topk_rows(rows: int, n: int, seed: int = 4242, dtype=torch.float32, device="
     return out
 
 
+def grad_rows(rows: int, n: int, seed: int = 5151, dtype=torch.float32, device="cpu"):
+    """Upstream gradient for the backward pass of the row-wise top-k: i.i.d. N(0, 1), rounded once."""
+    g = _gen(seed, device)
+    return torch.randn(rows, n, generator=g, device=device, dtype=torch.float32).to(dtype).contiguous()
+
+
 def to_oracle(t: torch.Tensor):
     """Exact float32 view of a stored tensor for the CPU oracle (bf16 -> fp32 is exact)."""
     return t.detach().to("cpu").to(torch.float32).numpy()
