@@ -66,6 +66,10 @@ def _load():
     lib.spark_ref_exact_topk.argtypes = [vp, c_i64, c_i64, vp]
     lib.spark_ref_exact_topk_rows.restype = c_int
     lib.spark_ref_exact_topk_rows.argtypes = [vp, c_i64, c_i64, c_i64, c_i64, vp, c_int]
+    lib.spark_ref_fp8_e4m3_value.restype = c_d
+    lib.spark_ref_fp8_e4m3_value.argtypes = [ctypes.c_uint]
+    lib.spark_ref_fp8_dequantize_rows.restype = c_int
+    lib.spark_ref_fp8_dequantize_rows.argtypes = [vp, vp, c_i64, c_i64, vp]
     lib.spark_ref_spark_ffn.restype = c_int
     lib.spark_ref_spark_ffn.argtypes = [vp, vp, vp, vp, c_i64, c_i64, c_i64, c_i64, c_int, c_int,
                                         vp, vp, vp, vp, vp, vp, vp, vp, c_int]
@@ -212,6 +216,23 @@ def exact_topk_rows(x, k: int, threads: int = 0) -> np.ndarray:
     rc = _load().spark_ref_exact_topk_rows(_ptr(x), rows, d, d, int(k), _ptr(idx), int(threads))
     _check(rc, "exact_topk_rows")
     return idx
+
+
+def fp8_e4m3_value(code: int) -> float:
+    """Value of one OCP E4M3 code (0..255)."""
+    return float(_load().spark_ref_fp8_e4m3_value(int(code)))
+
+
+def fp8_dequantize_rows(codes, scales) -> np.ndarray:
+    """float32 weights ``scales[row] * value(codes[row, c])`` of a matrix of E4M3 codes (uint8)."""
+    codes = np.ascontiguousarray(codes, dtype=np.uint8)
+    scales = np.ascontiguousarray(scales, dtype=np.float32)
+    rows, cols = codes.shape
+    if scales.shape != (rows,):
+        raise ValueError("one scale per row")
+    out = np.empty((rows, cols), np.float32)
+    _check(_load().spark_ref_fp8_dequantize_rows(_ptr(codes), _ptr(scales), rows, cols, _ptr(out)), "fp8_dequantize_rows")
+    return out
 
 
 @dataclass

@@ -317,6 +317,34 @@ int spark_ref_exact_topk_rows(const double* x, int64_t rows, int64_t d, int64_t 
 }
 
 /*
+ * Value of an 8-bit floating-point code in the OCP "E4M3" format (1 sign, 4 exponent bits with
+ * bias 7, 3 mantissa bits; no infinities; exponent 15 with mantissa 7 is NaN; exponent 0 holds
+ * the subnormals m / 8 * 2^-6; largest finite value 448).  This is the storage format of the
+ * low-precision weight rows (the quantisation synergy of Appendix D.4): a stored row is its
+ * codes and one fp32 scale, weight = scale * value(code).
+ */
+double spark_ref_fp8_e4m3_value(unsigned code) {
+  const unsigned sign = (code >> 7) & 1u, e = (code >> 3) & 15u, m = code & 7u;
+  double v;
+  if (e == 15u && m == 7u) return NAN;
+  if (e == 0u) v = ldexp((double)m / 8.0, -6);
+  else v = ldexp(1.0 + (double)m / 8.0, (int)e - 7);
+  return sign ? -v : v;
+}
+
+/* weight[row][c] = scale[row] * value(code[row][c]) for rows x cols codes, as float (exact when
+ * the scale has at most 20 significant bits; the synthetic inputs keep to 8). */
+int spark_ref_fp8_dequantize_rows(const uint8_t* codes, const float* scales, int64_t rows, int64_t cols,
+                                  float* out) {
+  if (!codes || !scales || !out) return REF_ERR_NULL;
+  if (rows < 0 || cols < 0) return REF_ERR_SHAPE;
+  for (int64_t r = 0; r < rows; ++r)
+    for (int64_t c = 0; c < cols; ++c)
+      out[r * cols + c] = (float)((double)scales[r] * spark_ref_fp8_e4m3_value(codes[r * cols + c]));
+  return REF_OK;
+}
+
+/*
  * One Spark-FFN layer for one token (Eq.2), weights neuron-major (row j = column j of the
  * paper's K1 / K2 / V):
  *   s_j = sum_{i<r} K1n[j][i] * q[i]                          predictor, all j

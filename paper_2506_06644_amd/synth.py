@@ -126,6 +126,21 @@ def grad_rows(rows: int, n: int, seed: int = 5151, dtype=torch.float32, device="
     return torch.randn(rows, n, generator=g, device=device, dtype=torch.float32).to(dtype).contiguous()
 
 
+def quantize_rows_fp8(w: torch.Tensor):
+    """Per-row symmetric quantisation of a weight matrix to OCP E4M3 codes: ``scale = max|row| / 448``
+    rounded to 8 significant bits (bf16), ``code = round_to_nearest_even(w / scale)``.  Returns
+    (codes uint8 [rows, cols], scales float32 [rows]); an input generator, used on the CPU."""
+    w = w.detach().to("cpu", torch.float32)
+    amax = w.abs().amax(dim=1)
+    scale = torch.where(amax > 0, amax / 448.0, torch.ones_like(amax))
+    scale = scale.to(torch.bfloat16).to(torch.float32)
+    # a scale rounded down would push the row's largest entry past 448: step it up one bf16 ulp
+    low = scale * 448.0 < amax
+    scale = torch.where(low, (scale.to(torch.bfloat16).view(torch.int16) + 1).view(torch.bfloat16).to(torch.float32), scale)
+    codes = (w / scale[:, None]).clamp(-448.0, 448.0).to(torch.float8_e4m3fn).view(torch.uint8)
+    return codes.contiguous(), scale.contiguous()
+
+
 def to_oracle(t: torch.Tensor):
     """Exact float32 view of a stored tensor for the CPU oracle (bf16 -> fp32 is exact)."""
     return t.detach().to("cpu").to(torch.float32).numpy()

@@ -660,3 +660,33 @@ def test_huber_argument_errors(oracle):
             oracle.huber_stat_topk_vjp(x, x, 3, bad)
     with pytest.raises(Exception):
         oracle.huber_stat_topk_vjp(x, x, 10, 0.1)
+
+
+# --------------------------------------------------------------------------- 8-bit weight codes (OCP E4M3)
+def test_fp8_code_values_against_the_library_type_and_the_format_definition(oracle):
+    """All 256 codes against torch's float8_e4m3fn, plus the points the format fixes: bias 7, three
+    mantissa bits, subnormals down to 2^-9, largest finite value 448, no infinities, two NaN codes."""
+    lib = torch.arange(256, dtype=torch.uint8).view(torch.float8_e4m3fn).to(torch.float32).numpy()
+    for code in range(256):
+        v = oracle.fp8_e4m3_value(code)
+        if code in (0x7F, 0xFF):
+            assert math.isnan(v) and math.isnan(lib[code])
+        else:
+            assert v == float(lib[code]), code
+    assert oracle.fp8_e4m3_value(0x00) == 0.0 and oracle.fp8_e4m3_value(0x38) == 1.0
+    assert oracle.fp8_e4m3_value(0x01) == 2.0 ** -9 and oracle.fp8_e4m3_value(0x08) == 2.0 ** -6
+    assert oracle.fp8_e4m3_value(0x7E) == 448.0 and oracle.fp8_e4m3_value(0xFE) == -448.0
+    assert oracle.fp8_e4m3_value(0x3C) == 1.5 and oracle.fp8_e4m3_value(0xB8) == -1.0
+
+
+def test_fp8_rows_dequantise_exactly(oracle):
+    """The synthetic quantiser keeps scales to 8 significant bits, so scale * value(code) is exact in
+    float32: the oracle's weights are the stored weights, and re-quantising them returns the codes."""
+    w = synth.ffn_layer(synth.TINY, 3, torch.float32)[0]
+    codes, scales = synth.quantize_rows_fp8(w)
+    deq = oracle.fp8_dequantize_rows(codes.numpy(), scales.numpy())
+    exact = scales.numpy().astype(np.float64)[:, None] * np.vectorize(oracle.fp8_e4m3_value)(codes.numpy())
+    assert np.array_equal(deq.astype(np.float64), exact)
+    assert np.max(np.abs(deq - w.numpy()) / np.abs(w.numpy()).max(axis=1, keepdims=True)) <= 2.0 ** -4 * 1.01
+    again = (torch.from_numpy(deq) / scales[:, None]).to(torch.float8_e4m3fn).view(torch.uint8)
+    assert torch.equal(again, codes)
