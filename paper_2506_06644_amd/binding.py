@@ -16,7 +16,7 @@ import torch
 _PKG = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_PKG, "libspark_hip.so")
 
-F32, BF16 = 0, 1
+F32, BF16, FP8_E4M3 = 0, 1, 2
 FILL_ZERO, FILL_NEG_INF = 0, 1
 GELU_ERF, GELU_TANH = 0, 1
 MAX_BATCH = 64
@@ -215,6 +215,27 @@ def spark_ffn_decode_layers(layers: Sequence[_Layer], q: torch.Tensor, y: torch.
         arr, len(layers), _p(q), _dt(q), q.shape[0], q.stride(0), _p(y), _p(theta), _p(active_count),
         _p(active_idx), _p(union_count), _p(union_idx), _p(workspace), workspace.numel(), _stream())
     _check(rc, "spark_ffn_decode_layers")
+
+
+def pack_fp8_rows(codes: torch.Tensor, scales: torch.Tensor) -> torch.Tensor:
+    """One 8-bit weight array as the library reads it: the E4M3 codes ``[rows, cols]`` (uint8) followed
+    by one fp32 scale per row, in one allocation (returned as a flat uint8 tensor)."""
+    if codes.dtype != torch.uint8 or scales.dtype != torch.float32 or scales.shape != (codes.shape[0],):
+        raise ValueError("codes must be uint8 [rows, cols] and scales float32 [rows]")
+    if codes.shape[1] % 16:
+        raise ValueError("rows of 8-bit weights must be multiples of 16 elements")
+    return torch.cat([codes.contiguous().reshape(-1), scales.contiguous().view(torch.uint8).reshape(-1)])
+
+
+def make_layer_fp8(k1n: torch.Tensor, k2n: torch.Tensor, vn: torch.Tensor, d_model: int, d_ff: int, r: int, k: int,
+                   gelu: int = GELU_ERF) -> _Layer:
+    """Layer over three arrays packed by :func:`pack_fp8_rows` (the caller keeps them alive)."""
+    need = (d_ff * (r + 4), d_ff * (d_model - r + 4), d_ff * (d_model + 4))
+    for t, n in zip((k1n, k2n, vn), need):
+        if t.dtype != torch.uint8 or t.numel() != n or not t.is_contiguous():
+            raise ValueError("packed 8-bit weight array of the wrong size")
+    return _Layer(int(d_model), int(d_ff), int(r), int(k), FP8_E4M3, int(gelu), k1n.data_ptr(), k2n.data_ptr(),
+                  vn.data_ptr())
 
 
 def ffn_prefill_workspace_bytes(d_model: int, d_ff: int, chunk: int) -> int:

@@ -9,15 +9,16 @@
 namespace {
 
 bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
-size_t dtype_size(int dt) { return dt == SPARK_BF16 ? 2 : 4; }
-bool dtype_ok(int dt) { return dt == SPARK_F32 || dt == SPARK_BF16; }
+size_t dtype_size(int dt) { return dt == SPARK_FP8_E4M3 ? 1 : dt == SPARK_BF16 ? 2 : 4; }
+bool dtype_ok(int dt) { return dt == SPARK_F32 || dt == SPARK_BF16; }            // tokens, activations
+bool weight_dtype_ok(int dt) { return dtype_ok(dt) || dt == SPARK_FP8_E4M3; }  // weight arrays
 
 double normal_cdf(double z) { return 0.5 * std::erfc(-z * 0.70710678118654752440); }
 
 spark_status validate_layer(const spark_ffn_layer* L) {
   if (!L) return SPARK_ERR_NULL;
   if (!L->k1n || !L->k2n || !L->vn) return SPARK_ERR_NULL;
-  if (!dtype_ok(L->wdtype)) return SPARK_ERR_DTYPE;
+  if (!weight_dtype_ok(L->wdtype)) return SPARK_ERR_DTYPE;
   if (L->gelu != SPARK_GELU_ERF && L->gelu != SPARK_GELU_TANH) return SPARK_ERR_DTYPE;
   if (L->d_ff < 2 || L->d_model < 2) return SPARK_ERR_SHAPE;
   if (L->r < 1 || L->r > L->d_model - 1) return SPARK_ERR_SHAPE;
@@ -27,6 +28,10 @@ spark_status validate_layer(const spark_ffn_layer* L) {
   if (!aligned16(L->k1n) || !aligned16(L->k2n) || !aligned16(L->vn)) return SPARK_ERR_ALIGN;
   return SPARK_OK;
 }
+
+spark::FfnProblem make_problem(const spark_ffn_layer* L, const void* q, int qdtype, int32_t batch, int64_t ldq,
+                               float* y, float* theta, int32_t* active_count, int32_t* active_idx,
+                               int32_t* union_count, int32_t* union_idx);
 
 spark_status validate_decode(const spark_ffn_layer* L, const void* q, int qdtype, int32_t batch, int64_t ldq,
                              const float* y, const void* workspace, size_t workspace_bytes) {
@@ -42,6 +47,11 @@ spark_status validate_decode(const spark_ffn_layer* L, const void* q, int qdtype
   if (!workspace) return SPARK_ERR_WORKSPACE;
   if (reinterpret_cast<uintptr_t>(workspace) & 255u) return SPARK_ERR_WORKSPACE;
   if (workspace_bytes < spark_ffn_workspace_bytes(L->d_model, L->d_ff, batch)) return SPARK_ERR_WORKSPACE;
+  if (L->wdtype == SPARK_FP8_E4M3) {
+    // 8-bit weights exist for the one-token path only
+    const spark::FfnProblem p = make_problem(L, q, qdtype, batch, ldq, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr);
+    if (batch != 1 || !spark::phased_supported(p)) return SPARK_ERR_DTYPE;
+  }
   return SPARK_OK;
 }
 
@@ -54,6 +64,7 @@ spark::FfnProblem make_problem(const spark_ffn_layer* L, const void* q, int qdty
   p.r = L->r;
   p.k = L->k;
   p.w_bf16 = L->wdtype == SPARK_BF16;
+  p.w_fp8 = L->wdtype == SPARK_FP8_E4M3;
   p.q_bf16 = qdtype == SPARK_BF16;
   p.gelu = L->gelu;
   p.k1n = L->k1n;
@@ -217,7 +228,7 @@ spark_status spark_ffn_decode(const spark_ffn_layer* layer, const void* q, spark
                                            union_count, union_idx);
   const spark::FfnWorkspace ws = spark::carve_workspace(workspace, layer->d_model, layer->d_ff, batch);
   hipError_t e;
-  if (g_force_general == 0 && (spark::phased_supported(p) || spark::phased_batch_supported(p)))
+  if ((g_force_general == 0 || p.w_fp8) && (spark::phased_supported(p) || spark::phased_batch_supported(p)))
     e = run_fused(layer, 1, p, ws, false, static_cast<hipStream_t>(hip_stream));
   else if (g_force_general == 2 && spark::fused_supported(p, 1))
     e = run_fused(layer, 1, p, ws, true, static_cast<hipStream_t>(hip_stream));
@@ -246,7 +257,7 @@ spark_status spark_ffn_decode_layers(const spark_ffn_layer* layers, int32_t n_la
   {
     const spark::FfnProblem p0 = make_problem(&layers[0], q, qdtype, batch, ldq, y, theta, active_count,
                                               active_idx, union_count, union_idx);
-    if (g_force_general == 0 && (spark::phased_supported(p0) || spark::phased_batch_supported(p0))) {
+    if ((g_force_general == 0 || p0.w_fp8) && (spark::phased_supported(p0) || spark::phased_batch_supported(p0))) {
       const hipError_t e = run_fused(layers, n_layers, p0, ws, false, static_cast<hipStream_t>(hip_stream));
       return e == hipSuccess ? SPARK_OK : SPARK_ERR_DEVICE;
     }
@@ -299,7 +310,7 @@ spark_status spark_ffn_prefill(const spark_ffn_layer* layer, const void* q, spar
   auto one_chunk = [&](int64_t t0, int64_t c, int32_t batch) {
     const spark::FfnProblem p = problem_at(t0, c, batch);
     const spark::FfnWorkspace ws = spark::carve_workspace(workspace, layer->d_model, layer->d_ff, batch);
-    if (g_force_general == 0 && (spark::phased_supported(p) || spark::phased_batch_supported(p)))
+    if ((g_force_general == 0 || p.w_fp8) && (spark::phased_supported(p) || spark::phased_batch_supported(p)))
       return run_fused(layer, 1, p, ws, false, st);
     return spark::launch_ffn_general(p, ws, 0, st);
   };
@@ -335,6 +346,7 @@ spark_status spark_ffn_dense_decode(const spark_ffn_layer* layer, const void* q,
                                     size_t workspace_bytes, void* hip_stream) {
   const spark_status s = validate_decode(layer, q, qdtype, batch, ldq, y, workspace, workspace_bytes);
   if (s != SPARK_OK) return s;
+  if (layer->wdtype == SPARK_FP8_E4M3) return SPARK_ERR_DTYPE;  // use spark_ffn_dense_decode_layers
   const spark::FfnProblem p =
       make_problem(layer, q, qdtype, batch, ldq, y, nullptr, nullptr, nullptr, nullptr, nullptr);
   const spark::FfnWorkspace ws = spark::carve_workspace(workspace, layer->d_model, layer->d_ff, batch);
@@ -359,7 +371,7 @@ spark_status spark_ffn_dense_decode_layers(const spark_ffn_layer* layers, int32_
   const spark::FfnWorkspace ws = spark::carve_workspace(workspace, layers[0].d_model, layers[0].d_ff, batch);
   const spark::FfnProblem p0 =
       make_problem(&layers[0], q, qdtype, batch, ldq, y, nullptr, nullptr, nullptr, nullptr, nullptr);
-  if (g_force_general == 0 && spark::phased_supported(p0)) {
+  if ((g_force_general == 0 || p0.w_fp8) && spark::phased_supported(p0)) {
     const hipError_t e = run_fused(layers, n_layers, p0, ws, false, static_cast<hipStream_t>(hip_stream), 1);
     return e == hipSuccess ? SPARK_OK : SPARK_ERR_DEVICE;
   }

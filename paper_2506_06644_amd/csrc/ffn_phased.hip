@@ -88,6 +88,14 @@ __device__ __forceinline__ Vec16<WT> load_stream(const WT* p) {
   return v;
 }
 
+// Per-row scale of an 8-bit weight array: the fp32 scales follow the last row of codes.  Other
+// weight types carry no scale.
+template <typename WT>
+__device__ __forceinline__ const float* row_scales(const void* w, int rows, int cols) {
+  if constexpr (sizeof(WT) == 1) return reinterpret_cast<const float*>(static_cast<const char*>(w) + (size_t)rows * (size_t)cols);
+  else return nullptr;
+}
+
 // Rows of one predictor block that are real neurons (the last block of a layer may be short).
 __device__ __forceinline__ int rows_in_block(int blk, int rpb, int d_ff) { return max(0, min(rpb, d_ff - blk * rpb)); }
 
@@ -144,13 +152,17 @@ __global__ __launch_bounds__(256) void predict_layers_kernel(const PhasedParams 
   }
 
   const WT* base = static_cast<const WT*>(P.k1n[l]);
+  const float* scales = row_scales<WT>(P.k1n[l], P.d_ff, P.r);
   for (int i = 0; i < rpw; i += R) {
     Vec16<WT> reg[R][CPL1];
+    float sc[R];
 #pragma unroll
     for (int e = 0; e < R; ++e) {
       const int lr = i * 4 + wave * R + e;
       // rows past the end of the layer re-read the block's first row; the value is dropped
       const WT* row = base + (size_t)(row0 + (lr < nrows ? lr : 0)) * P.r;
+      sc[e] = 1.f;
+      if constexpr (sizeof(WT) == 1) sc[e] = scales[row0 + (lr < nrows ? lr : 0)];
 #pragma unroll
       for (int c = 0; c < CPL1; ++c) {
         const int ch = lane + kWave * c;
@@ -178,7 +190,7 @@ __global__ __launch_bounds__(256) void predict_layers_kernel(const PhasedParams 
       }
       acc = wave_total(acc);
       const int lr = i * 4 + wave * R + e;
-      if (lane == 0 && lr < nrows) s_sh[lr] = acc;
+      if (lane == 0 && lr < nrows) s_sh[lr] = acc * sc[e];
     }
   }
   if (l == 0 && blk == 0 && threadIdx.x == 0) *P.status = 0;
@@ -289,6 +301,9 @@ __global__ __launch_bounds__(NW * kWave, OCC) void gather_layers_kernel(const Ph
 
   const WT* k2 = static_cast<const WT*>(P.k2n[l]);
   const WT* vn = static_cast<const WT*>(P.vn[l]);
+  constexpr bool SCALED = sizeof(WT) == 1;
+  const float* k2_scales = row_scales<WT>(P.k2n[l], P.d_ff, r2);
+  const float* vn_scales = row_scales<WT>(P.vn[l], P.d_ff, P.d_model);
   // pops this wave's next active neuron (index inside the block), -1 when there is none
   int wd = 0, skip = wave;
   unsigned long long cur = nwords > 0 ? uniform_u64(maskw[0]) : 0ull;
@@ -307,7 +322,9 @@ __global__ __launch_bounds__(NW * kWave, OCC) void gather_layers_kernel(const Ph
       cur = uniform_u64(maskw[wd]);
     }
   };
-  auto request = [&](int n, Vec16<WT>(&kr)[CPL2], Vec16<WT>(&vr)[CPLV]) {
+  // (8-bit weights: the row's two scales travel with it, as the product scale_k2 * scale_v, which
+  // is all the sum needs: u_j * Vn[j] = GELU(a) * (scale_k2 g) * (scale_v codes))
+  auto request = [&](int n, Vec16<WT>(&kr)[CPL2], Vec16<WT>(&vr)[CPLV], float& sc) {
     const size_t j = (size_t)(n0 + (n >= 0 ? n : 0));
     const __amdgpu_buffer_rsrc_t kb = row_rsrc(k2 + j * r2, n >= 0 ? (uint32_t)r2 * (uint32_t)sizeof(WT) : 0u);
     const __amdgpu_buffer_rsrc_t vb = row_rsrc(vn + j * P.d_model, n >= 0 ? (uint32_t)P.d_model * (uint32_t)sizeof(WT) : 0u);
@@ -315,8 +332,10 @@ __global__ __launch_bounds__(NW * kWave, OCC) void gather_layers_kernel(const Ph
     for (int c = 0; c < CPL2; ++c) kr[c] = row_load<WT>(kb, lane + kWave * c);
 #pragma unroll
     for (int c = 0; c < CPLV; ++c) vr[c] = row_load<WT>(vb, lane + kWave * c);
+    sc = 1.f;
+    if constexpr (SCALED) sc = k2_scales[j] * vn_scales[j];
   };
-  auto consume = [&](int n, const Vec16<WT>(&kr)[CPL2], const Vec16<WT>(&vr)[CPLV]) {
+  auto consume = [&](int n, const Vec16<WT>(&kr)[CPL2], const Vec16<WT>(&vr)[CPLV], float sc) {
     float gd = 0.f;
 #pragma unroll
     for (int c = 0; c < CPL2; ++c) {
@@ -326,7 +345,7 @@ __global__ __launch_bounds__(NW * kWave, OCC) void gather_layers_kernel(const Ph
     }
     gd = wave_total(gd);
     const float a = n >= 0 ? s_blk[n] : 0.f;  // s_j - theta
-    const float u = a > 0.f ? gelu(a, P.gelu) * gd : 0.f;
+    const float u = a > 0.f ? gelu(a, P.gelu) * (gd * sc) : 0.f;
 #pragma unroll
     for (int c = 0; c < CPLV; ++c)
 #pragma unroll
@@ -339,20 +358,21 @@ __global__ __launch_bounds__(NW * kWave, OCC) void gather_layers_kernel(const Ph
     for (int w = 0; w < nwords; ++w) total += __popcll(uniform_u64(maskw[w]));
     const int mine = total > wave ? (total - wave + NW - 1) / NW : 0;
     Vec16<WT> ka[CPL2], va[CPLV], kb[CPL2], vb[CPLV];
+    float sa, sb;
     int na = next_neuron();
-    request(na, ka, va);
+    request(na, ka, va, sa);
     int nb = next_neuron();
-    request(nb, kb, vb);
+    request(nb, kb, vb, sb);
     // The body is branch-free: a buffer whose neuron does not exist was requested through a
     // descriptor without records, holds zeros and adds zeros (only in the last round), so the
     // number of loads in flight is a compile-time constant and every wait is exact.
     for (int i = 0; i < mine; i += 2) {
-      consume(na, ka, va);
+      consume(na, ka, va, sa);
       na = next_neuron();
-      request(na, ka, va);
-      consume(nb, kb, vb);
+      request(na, ka, va, sa);
+      consume(nb, kb, vb, sb);
       nb = next_neuron();
-      request(nb, kb, vb);
+      request(nb, kb, vb, sb);
     }
   }
 
@@ -479,19 +499,24 @@ PhasedLayout phased_layout(int d_model, int d_ff) {
 
 // Compiled gather variants: chunks per lane of a K2n row and of a Vn row.
 struct GatherVariant {
-  int bf16, cpl2, cplv, nw, occ;  // waves per workgroup, waves per SIMD the registers are held to
+  int kind, cpl2, cplv, nw, occ;  // weight type (0 fp32, 1 bf16, 2 fp8), chunks, waves per workgroup,
+                                  // waves per SIMD the registers are held to
 };
 constexpr GatherVariant kGather[] = {
     {1, 1, 1, 8, 4}, {1, 3, 5, 4, 3}, {1, 4, 7, 4, 2}, {0, 1, 1, 8, 4}, {0, 2, 2, 8, 4}, {0, 5, 9, 4, 2},
     {1, 3, 5, 8, 4},  // alternative for the 2B class (tuning switch)
+    {2, 1, 1, 8, 4}, {2, 2, 3, 4, 3}, {2, 2, 4, 4, 2},
 };
 constexpr int kNumGather = sizeof(kGather) / sizeof(kGather[0]);
 
+int weight_kind(const FfnProblem& p) { return p.w_fp8 ? 2 : p.w_bf16 ? 1 : 0; }
+int weight_vec(const FfnProblem& p) { return p.w_fp8 ? 16 : p.w_bf16 ? 8 : 4; }  // elements per 16 bytes
+
 int gather_variant(const FfnProblem& p) {
-  const int vec = p.w_bf16 ? 8 : 4;
+  const int vec = weight_vec(p);
   const int c2 = ((p.d_model - p.r) / vec + kWave - 1) / kWave, cv = (p.d_model / vec + kWave - 1) / kWave;
   for (int i = 0; i < kNumGather; ++i)
-    if (kGather[i].bf16 == (p.w_bf16 ? 1 : 0) && c2 <= kGather[i].cpl2 && cv <= kGather[i].cplv) return i;
+    if (kGather[i].kind == weight_kind(p) && c2 <= kGather[i].cpl2 && cv <= kGather[i].cplv) return i;
   return -1;
 }
 
@@ -524,7 +549,8 @@ hipError_t launch_gather(const PhasedParams& P, dim3 grid, hipStream_t st) {
 template <int I>
 hipError_t launch_gather_index(const PhasedParams& P, dim3 grid, hipStream_t st) {
   constexpr GatherVariant v = kGather[I];
-  if constexpr (v.bf16) return launch_gather<bf16_t, v.cpl2, v.cplv, v.nw, v.occ>(P, grid, st);
+  if constexpr (v.kind == 2) return launch_gather<fp8_t, v.cpl2, v.cplv, v.nw, v.occ>(P, grid, st);
+  else if constexpr (v.kind == 1) return launch_gather<bf16_t, v.cpl2, v.cplv, v.nw, v.occ>(P, grid, st);
   else return launch_gather<float, v.cpl2, v.cplv, v.nw, v.occ>(P, grid, st);
 }
 
@@ -541,7 +567,7 @@ void phased_set_tuning(int rpb, int npb, int alt) {
 size_t phased_scratch_bytes(int d_model, int d_ff) { return phased_layout(d_model, d_ff).total; }
 
 bool phased_supported(const FfnProblem& p) {
-  const int vec = p.w_bf16 ? 8 : 4;
+  const int vec = weight_vec(p);
   const int c1 = (p.r / vec + kWave - 1) / kWave;
   const size_t lds = ((size_t)8 * kWave * 8 + (size_t)4 * p.d_model) * sizeof(float);
   return p.batch == 1 && c1 <= 4 && gather_variant(p) >= 0 && lds <= 150 * 1024;
@@ -553,7 +579,7 @@ hipError_t launch_ffn_phased(const FfnProblem& p0, const void* const* k1n, const
   int gv = gather_variant(p0);
   if (gv < 0) return hipErrorInvalidValue;
   if (gv == 1 && g_phased_alt == 1) gv = 6;
-  const int vec = p0.w_bf16 ? 8 : 4;
+  const int vec = weight_vec(p0);
   const int cpl1 = (p0.r / vec + kWave - 1) / kWave;
   char* s = static_cast<char*>(scratch);
   hipError_t err = hipSuccess;
@@ -610,6 +636,7 @@ hipError_t launch_ffn_phased(const FfnProblem& p0, const void* const* k1n, const
 
     const dim3 ga(P.NBA, L);
     if (!(g_phased_mask & 1)) err = hipSuccess;
+    else if (p0.w_fp8) err = launch_predict<fp8_t, false>(P, cpl1, ga, st);
     else if (p0.w_bf16) err = p0.q_bf16 ? launch_predict<bf16_t, true>(P, cpl1, ga, st) : launch_predict<bf16_t, false>(P, cpl1, ga, st);
     else err = launch_predict<float, false>(P, cpl1, ga, st);
     if (err != hipSuccess) return err;
@@ -622,6 +649,9 @@ hipError_t launch_ffn_phased(const FfnProblem& p0, const void* const* k1n, const
       case 4: err = launch_gather_index<4>(P, gc, st); break;
       case 5: err = launch_gather_index<5>(P, gc, st); break;
       case 6: err = launch_gather_index<6>(P, gc, st); break;
+      case 7: err = launch_gather_index<7>(P, gc, st); break;
+      case 8: err = launch_gather_index<8>(P, gc, st); break;
+      case 9: err = launch_gather_index<9>(P, gc, st); break;
       default: err = hipErrorInvalidValue; break;
     }
     if (err != hipSuccess) return err;

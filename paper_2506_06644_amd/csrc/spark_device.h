@@ -70,6 +70,25 @@ struct Vec16<bf16_t> {
   __device__ __forceinline__ static void store1(bf16_t* p, float v) { p->bits = float_to_bf16_rne(v); }
 };
 
+// One weight code in the OCP E4M3 format (1 sign, 4 exponent bits with bias 7, 3 mantissa bits;
+// largest finite value 448).  Rows of codes are followed, after the last row, by one fp32 scale
+// per row: weight = scale * value(code).  Read-only storage type: 16 codes per 16-byte vector,
+// widened by the target's conversion instruction two at a time.
+struct fp8_t {
+  uint8_t bits;
+};
+template <>
+struct Vec16<fp8_t> {
+  static constexpr int N = 16;
+  u32x4 raw;
+  __device__ __forceinline__ float get(int i) const {
+    typedef float f32x2_v __attribute__((ext_vector_type(2)));
+    const f32x2_v two = (i & 2) ? __builtin_amdgcn_cvt_pk_f32_fp8((int)raw[i >> 2], true)
+                                : __builtin_amdgcn_cvt_pk_f32_fp8((int)raw[i >> 2], false);
+    return two[i & 1];
+  }
+};
+
 template <typename T>
 __device__ __forceinline__ Vec16<T> load_vec16(const T* p) {
   Vec16<T> v;
@@ -88,9 +107,14 @@ __device__ __forceinline__ float load_q(const void* q, int q_is_bf16, int64_t i)
                    : static_cast<const float*>(q)[i];
 }
 
-// N consecutive token elements starting at element i (i is a multiple of N, N = 4 or 8).
+// N consecutive token elements starting at element i (i is a multiple of N, N = 4, 8 or 16).
 template <int N>
 __device__ __forceinline__ void load_q_vec(const void* q, int q_is_bf16, int64_t i, float* out) {
+  if constexpr (N == 16) {
+    load_q_vec<8>(q, q_is_bf16, i, out);
+    load_q_vec<8>(q, q_is_bf16, i + 8, out + 8);
+    return;
+  }
   if (q_is_bf16) {
     const uint16_t* p = static_cast<const uint16_t*>(q) + i;
     if (N == 8) {

@@ -129,8 +129,8 @@ def grad_rows(rows: int, n: int, seed: int = 5151, dtype=torch.float32, device="
 def quantize_rows_fp8(w: torch.Tensor):
     """Per-row symmetric quantisation of a weight matrix to OCP E4M3 codes: ``scale = max|row| / 448``
     rounded to 8 significant bits (bf16), ``code = round_to_nearest_even(w / scale)``.  Returns
-    (codes uint8 [rows, cols], scales float32 [rows]); an input generator, used on the CPU."""
-    w = w.detach().to("cpu", torch.float32)
+    (codes uint8 [rows, cols], scales float32 [rows]) on the device of ``w``; an input generator."""
+    w = w.detach().to(torch.float32)
     amax = w.abs().amax(dim=1)
     scale = torch.where(amax > 0, amax / 448.0, torch.ones_like(amax))
     scale = scale.to(torch.bfloat16).to(torch.float32)
