@@ -15,9 +15,9 @@
  * General conventions
  *   - All array arguments are DEVICE pointers (HIP global memory of the current device)
  *     unless the comment says "host".  The library never allocates or frees device memory:
- *     every buffer, including the workspace, is owned by the caller.  The only state kept
- *     between calls is a process-wide launch counter (it stamps the synchronisation words
- *     of the persistent launch, so the workspace needs no initialisation).
+ *     every buffer, including the workspace, is owned by the caller, and the workspace needs
+ *     no initialisation.  The only state kept between calls is the spark_debug_* switches
+ *     and a launch counter of the alternative persistent kernel they can select.
  *   - Calls enqueue work on `hip_stream` (a hipStream_t passed as void*; NULL = the default
  *     stream) and return without synchronising.  Outputs are valid once the stream has
  *     been synchronised by the caller.  Two calls that share a workspace must be ordered
@@ -296,12 +296,14 @@ spark_status spark_attn_decode(const spark_attn_head* heads, int32_t n_heads, co
                                void* hip_stream);
 
 /*
- * Host, synchronising.  The batch-1 entry points run as one persistent launch whose
+ * Host, synchronising.  The default paths launch ordinary kernels that wait for nothing and
+ * cannot give up: for them this call only synchronises and returns SPARK_OK.  The alternative
+ * batch-1 path selected with spark_debug_force_general(2) is one persistent launch whose
  * wavefronts wait on each other; every such wait is bounded, and a launch that had to give
  * up (for instance because another process held part of the GPU) leaves a non-zero status
  * word in the workspace instead of results.  This call waits for `hip_stream`, reads that
- * word and returns SPARK_ERR_DEVICE if the last batch-1 decode on this workspace aborted,
- * SPARK_OK otherwise.  Arguments as for spark_ffn_workspace_bytes.
+ * word and returns SPARK_ERR_DEVICE if the last decode on this workspace aborted, SPARK_OK
+ * otherwise.  Arguments as for spark_ffn_workspace_bytes.
  */
 spark_status spark_ffn_check(const void* workspace, int32_t d_model, int32_t d_ff, int32_t batch,
                              void* hip_stream);
@@ -317,7 +319,11 @@ void spark_debug_force_general(int on);
 void spark_debug_phases(int mask);
 
 /* Host.  Testing / tuning aid (process-wide): rows per workgroup of the predictor sweep and
- * neurons per workgroup of the gather of the batch-1 path; 0 = automatic. */
+ * neurons per workgroup of the gather of the batch-1 path; 0 = automatic.  `alt`: batch 1: 1
+ * selects the 8-wave gather variant; batches: row slices of the V step (0 = automatic), plus
+ * 100 to keep the k-split kernels for every batch size, plus 200 to take the streamed kernels
+ * (at most 16 tokens) however small the launch.  For batches the first two arguments, divided
+ * by 16, set the tiles per workgroup of the predict and k2 steps. */
 void spark_debug_tuning(int rows_per_predict_block, int neurons_per_gather_block, int alt);
 
 /* Host.  Testing aid: with profiling on, every wavefront of the persistent launch records
