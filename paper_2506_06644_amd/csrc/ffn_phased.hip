@@ -615,8 +615,10 @@ hipError_t launch_ffn_phased(const FfnProblem& p0, const void* const* k1n, const
     const long long want_wg = 2048;
     int rpb = g_phased_rpb;
     if (rpb <= 0) {
-      rpb = 64;
-      while (rpb > 16 && (long long)L * ((p0.d_ff + rpb - 1) / rpb) < want_wg) rpb /= 2;
+      // 64 rows where that still gives every compute unit several workgroups; with fewer
+      // layers 48 (measured best for 1..12 layers of the 2B shape: smaller blocks only lengthen
+      // the list of block statistics every gather workgroup merges)
+      rpb = (long long)L * ((p0.d_ff + 63) / 64) >= want_wg ? 64 : 48;
     }
     rpb = max(16, min(kMaxRPB, rpb / 16 * 16));
     int npb = g_phased_npb;
