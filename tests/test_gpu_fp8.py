@@ -115,3 +115,34 @@ def test_prefill_token_by_token_and_unsupported_uses():
     with pytest.raises(binding.SparkError) as e:
         binding.spark_ffn_decode(bad, torch.zeros(1, 328, device=DEV), torch.zeros(1, 328, device=DEV), ws)
     assert e.value.code == 5              # SPARK_ERR_ALIGN
+
+
+def test_stack_as_benchmarked_52_layers():
+    """The benchmark's launch configuration (52 quantised 2B-shaped layers in one call): y of the
+    first, a middle and the last layer, and every layer's index set, against the oracle."""
+    sh, L = synth.GEMMA2_2B, 52
+    packed, host = [], {}
+    for l in range(L):
+        w = synth.ffn_layer(sh, 1000 + l, torch.float32, DEV)
+        arrays = []
+        for i, t in enumerate(w):
+            codes, scales = synth.quantize_rows_fp8(t)
+            arrays.append(binding.pack_fp8_rows(codes, scales))
+            if i == 0 or l in (0, 25, 51):
+                host[(l, i)] = oracle.fp8_dequantize_rows(codes.cpu().numpy(), scales.cpu().numpy())
+        packed.append(arrays)
+        del w
+    q = synth.tokens(sh, 1, 2001, torch.bfloat16)
+    out = _run(sh, packed, q, True)
+    qs = synth.to_oracle(q)[0]
+    pick = [0, 25, 51]
+    sub = {k: (v[pick] if v.shape[0] == L else v) for k, v in out.items()}
+    deq = [tuple(torch.from_numpy(host[(l, i)]) for i in range(3)) for l in pick]
+    check_ffn_against_oracle(sh, deq, q, sub, TOL_BF16_TIGHT, what="fp8 stack")
+    from parity_util import assert_active_set
+    for l in range(L):
+        s = host[(l, 0)].astype(np.float64) @ qs[:sh.r].astype(np.float64)
+        ref = oracle.stat_topk_rows(s[None, :], sh.k)
+        assert abs(out["theta"][l, 0] - ref.theta[0]) <= 1e-5 * ref.std[0] + 1e-6 * abs(ref.theta[0])
+        m = int(out["count"][l, 0])
+        assert_active_set(out["idx"][l, 0, :m], s, ref.theta[0], ref.std[0], f"layer {l}")

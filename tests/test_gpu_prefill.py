@@ -131,3 +131,39 @@ def test_prefill_argument_errors_and_empty_prompt():
     binding.spark_ffn_prefill(layer, q, 4, y, ws, n_tokens=0)   # nothing to do, nothing written
     torch.cuda.synchronize()
     assert torch.all(y == 7.0)
+
+
+def test_prefill_as_benchmarked_4096_tokens():
+    """The benchmark's launch configuration (4096 tokens, chunks of 64: two sets of 32 chunk slots):
+    sampled tokens against the oracle, every chunk's union against its tokens' own index sets."""
+    sh = synth.GEMMA2_2B
+    T, chunk = 4096, 64
+    w = synth.ffn_layer(sh, 1000, torch.bfloat16)
+    dev = torch.device("cuda:0")
+    q = synth.tokens(sh, T, 7000, torch.bfloat16, dev)
+    wd = [t.to(dev) for t in w]
+    layer = binding.make_layer(wd[0], wd[1], wd[2], sh.k)
+    ws = binding.make_prefill_workspace(sh.d_model, sh.d_ff, chunk, dev)
+    y = torch.full((T, sh.d_model), float("nan"), device=dev)
+    cnt = torch.zeros(T, dtype=torch.int32, device=dev)
+    idx = torch.full((T, sh.d_ff), -1, dtype=torch.int32, device=dev)
+    ucnt = torch.zeros(T // chunk, dtype=torch.int32, device=dev)
+    uidx = torch.full((T // chunk, sh.d_ff), -1, dtype=torch.int32, device=dev)
+    binding.spark_ffn_prefill(layer, q, chunk, y, ws, None, cnt, idx, ucnt, uidx)
+    torch.cuda.synchronize()
+    assert torch.isfinite(y).all()
+    import oracle
+    k1n, k2n, vn = (synth.to_oracle(t) for t in w)
+    qs = synth.to_oracle(q)
+    for t in (0, 63, 64, 2047, 2048, 2111, 4032, 4095):
+        o = oracle.spark_ffn(k1n, k2n, vn, qs[t], sh.k, skip_inactive=True)
+        assert rel_l2(y[t].cpu().numpy(), o.y) <= TOL_BF16_TIGHT, t
+        m = int(cnt[t])
+        got = set(idx[t, :m].cpu().tolist())
+        for j in got ^ set(o.idx.tolist()):
+            assert abs(o.s[j] - o.theta) < 1e-3 * o.std
+    cnt_h, ucnt_h = cnt.cpu().numpy(), ucnt.cpu().numpy()
+    for c in (0, 31, 32, 63):
+        rows = idx[c * chunk:(c + 1) * chunk].cpu().numpy()
+        un = np.unique(np.concatenate([rows[i, :cnt_h[c * chunk + i]] for i in range(chunk)]))
+        assert ucnt_h[c] == len(un) and np.array_equal(uidx[c, :len(un)].cpu().numpy(), un)
