@@ -98,3 +98,50 @@ def test_workspace_query():
     assert binding.ffn_workspace_bytes(2304, 9216, 64) > binding.ffn_workspace_bytes(2304, 9216, 1)
     assert binding.ffn_workspace_bytes(2304, 9216, 0) == 0
     assert binding.ffn_workspace_bytes(2304, 9216, 65) == 0
+
+
+def test_huber_entries_reject_bad_arguments_before_launch():
+    lib = binding.load_library()
+    vp = ctypes.c_void_p
+
+    def fwd(x=0x1000, dt=0, rows=4, n=64, ldx=64, k=5, delta=0.25, y=0x2000, ldy=64):
+        return lib.spark_stat_topk_huber(vp(x), dt, rows, n, ldx, k, delta, vp(y), ldy, None, None)
+
+    def bwd(x=0x1000, gy=0x2000, dt=0, rows=4, n=64, ldx=64, ldgy=64, k=5, delta=0.25, gx=0x3000, ldgx=64):
+        return lib.spark_stat_topk_huber_backward(vp(x), vp(gy), dt, rows, n, ldx, ldgy, k, delta, vp(gx), ldgx, None)
+
+    assert fwd(x=0) == 1 and fwd(y=0) == 1
+    assert fwd(n=1) == 2 and fwd(ldy=32) == 2 and fwd(delta=-1.0) == 2 and fwd(delta=float("nan")) == 2
+    assert fwd(k=0) == 3 and fwd(k=64) == 3
+    assert fwd(dt=2) == 4                                     # the 8-bit code type is a weight type only
+    assert fwd(x=0x1004) == 5 and fwd(dt=1, ldx=68, ldy=68) == 5
+    assert fwd(rows=0) == 0
+    assert bwd(gy=0) == 1 and bwd(gx=0) == 1
+    assert bwd(ldgy=60) == 2 and bwd(ldgx=60) == 2 and bwd(delta=float("inf")) == 2
+    assert bwd(k=64) == 3 and bwd(dt=5) == 4 and bwd(gy=0x2008) == 5
+    assert bwd(rows=0) == 0
+
+
+def test_prefill_and_8bit_weights_reject_bad_arguments_before_launch():
+    lib = binding.load_library()
+    vp = ctypes.c_void_p
+
+    def prefill(layer, n_tokens=100, chunk=16, q=0x4000, qd=binding.BF16, ldq=256, y=0x5000, ws=0x10000, ws_bytes=None):
+        if ws_bytes is None:
+            ws_bytes = binding.ffn_prefill_workspace_bytes(layer.d_model, layer.d_ff, max(1, min(chunk, 64)))
+        return lib.spark_ffn_prefill(ctypes.byref(layer), vp(q), qd, n_tokens, chunk, ldq, vp(y), None, None, None,
+                                     None, None, vp(ws), ws_bytes, None)
+
+    assert prefill(_layer(), n_tokens=-1) == 2
+    assert prefill(_layer(), chunk=0) == 2 and prefill(_layer(), chunk=65) == 2
+    assert prefill(_layer(), q=0) == 1
+    assert prefill(_layer(), ws_bytes=4096) == 6
+    assert prefill(_layer(), n_tokens=0) == 0                 # nothing to do
+    assert binding.ffn_prefill_workspace_bytes(256, 1024, 16) >= binding.ffn_workspace_bytes(256, 1024, 16)
+    assert binding.ffn_prefill_workspace_bytes(256, 1024, 16) >= binding.ffn_workspace_bytes(256, 1024, 1)
+    # 8-bit weight codes: one token per call, rows of whole 16-byte chunks
+    f8 = binding.FP8_E4M3
+    assert _decode(_layer(wd=f8), batch=2) == 4
+    assert _decode(_layer(wd=f8, r=136, d_model=328), ldq=328) == 5
+    assert prefill(_layer(wd=f8), chunk=4) == 4
+    assert _decode(_layer(wd=f8), qd=f8) == 4                 # tokens cannot be codes
