@@ -257,6 +257,92 @@ __global__ __launch_bounds__(kRowThreads) void predict_batch_kernel(const BatchP
       });
 }
 
+// ------------------------------------------------------------------- predict, a few tokens
+// Up to 4 tokens: the predictor sweep of the one-token path with T dot products per row
+// instead of one (two-element bf16 dot products on the vector ALUs, DPP sums): every load
+// instruction reads a whole kilobyte of one row, which keeps the compute unit's request queue
+// fuller than MFMA-shaped loads do, and four tokens cost the vector ALUs little.  Workgroup =
+// 4 waves = 64 consecutive neurons, 16 at a time (4 rows per wave in flight).  Writes the
+// scores in both layouts the later steps read (token-major S, neuron-major ST with the
+// padding tokens as zeros).
+typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ float dot2_bf16(uint32_t a, uint32_t b, float c) {
+  return __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2_t, a), __builtin_bit_cast(bf16x2_t, b), c, false);
+}
+template <int CTRL, int ROW_MASK>
+__device__ __forceinline__ float dpp_add(float x) {
+  const int t = __builtin_amdgcn_update_dpp(0, __float_as_int(x), CTRL, ROW_MASK, 0xf, false);
+  return x + __int_as_float(t);
+}
+// Sum over the wavefront (quad swaps, row mirrors, row broadcasts), returned as a uniform value.
+__device__ __forceinline__ float wave_total(float x) {
+  x = dpp_add<0xB1, 0xf>(x);
+  x = dpp_add<0x4E, 0xf>(x);
+  x = dpp_add<0x141, 0xf>(x);
+  x = dpp_add<0x140, 0xf>(x);
+  x = dpp_add<0x142, 0xa>(x);
+  x = dpp_add<0x143, 0xc>(x);
+  return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(x), 63));
+}
+constexpr int kTokRows = 64;  // neurons per workgroup
+template <int T, int CPL1>
+__global__ __launch_bounds__(256) void predict_tokens_kernel(const BatchParams P) {
+  constexpr int R = 4;
+  __shared__ float s_sh[T][kTokRows];
+  const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
+  const int l = blockIdx.y, blk = blockIdx.x;
+  const int nvec1 = P.r / 8;
+  const int row0 = blk * kTokRows, nrows = max(0, min(kTokRows, P.d_ff - row0));
+  if (blockIdx.x == 0 && l == 0 && threadIdx.x == 0) *P.status = 0;  // this path cannot abort
+  const bf16_t* q = P.q + (size_t)l * P.qslot;
+  u32x4 qp[T][CPL1];
+#pragma unroll
+  for (int t = 0; t < T; ++t)
+#pragma unroll
+    for (int c = 0; c < CPL1; ++c) {
+      const int ch = lane + kWave * c;
+      qp[t][c] = ld16(q + (int64_t)min(t, P.B - 1) * P.ldq + (ch < nvec1 ? ch : 0) * 8);
+      if (ch >= nvec1 || t >= P.B) qp[t][c] = u32x4{0u, 0u, 0u, 0u};
+    }
+  const bf16_t* base = static_cast<const bf16_t*>(P.k1n[l]);
+  for (int i = 0; i < kTokRows / 4; i += R) {
+    u32x4 reg[R][CPL1];
+#pragma unroll
+    for (int e = 0; e < R; ++e) {
+      const int lr = i * 4 + wave * R + e;
+      // rows past the end of the layer re-read the block's first row; the value is dropped
+      const bf16_t* row = base + (size_t)(row0 + (lr < nrows ? lr : 0)) * P.r;
+#pragma unroll
+      for (int c = 0; c < CPL1; ++c) reg[e][c] = ld16_stream(row + (size_t)(lane + kWave * c < nvec1 ? lane + kWave * c : 0) * 8);
+    }
+#pragma unroll
+    for (int e = 0; e < R; ++e) {
+      const int lr = i * 4 + wave * R + e;
+#pragma unroll
+      for (int t = 0; t < T; ++t) {
+        float acc = 0.f;
+#pragma unroll
+        for (int c = 0; c < CPL1; ++c)
+#pragma unroll
+          for (int d = 0; d < 4; ++d) acc = dot2_bf16(reg[e][c][d], qp[t][c][d], acc);
+        acc = wave_total(acc);
+        if (lane == 0) s_sh[t][lr] = acc;
+      }
+    }
+  }
+  __syncthreads();
+  float* S = P.S + (size_t)l * P.B * P.d_ff;
+  float* ST = P.ST + (size_t)l * P.d_ff * P.BP;
+  for (int idx = threadIdx.x; idx < P.B * kTokRows; idx += 256) {
+    const int t = idx / kTokRows, rr = idx % kTokRows;
+    if (rr < nrows) S[(size_t)t * P.d_ff + row0 + rr] = s_sh[t][rr];
+  }
+  for (int idx = threadIdx.x; idx < kTokRows * P.BP; idx += 256) {
+    const int rr = idx / P.BP, t = idx % P.BP;
+    if (rr < nrows) ST[(size_t)(row0 + rr) * P.BP + t] = t < T ? s_sh[t][rr] : 0.f;
+  }
+}
+
 // ---------------------------------------------------------------------------------- select
 // One workgroup (4 waves) per (token, layer); the row of scores sits in registers (VPT per
 // thread; small workgroups so that many rows are in flight per compute unit).
@@ -966,7 +1052,14 @@ hipError_t launch_ffn_phased_batch(const FfnProblem& p0, const void* const* k1n,
     // (a launch too small to give every compute unit a streamed workgroup keeps the k-split kernels,
     // whose workgroups have three times the waves)
     const bool stream_ok = nb == 1 && (g_batch_stream == 2 || (g_batch_stream == 1 && (long long)L * ((tiles + 3) / 4) >= 256));
-    if (stream_ok && stream_split(p0.r, &gs, &ng))
+    const int cpl1 = (p0.r / 8 + kWave - 1) / kWave;
+    if (B <= 4 && cpl1 <= 2 && g_batch_stream != 0) {
+      // a few tokens: the vector-ALU sweep (whole-row loads)
+      const dim3 gt((p0.d_ff + kTokRows - 1) / kTokRows, L);
+      if (cpl1 == 1) hipLaunchKernelGGL((predict_tokens_kernel<4, 1>), gt, dim3(256), 0, st, P);
+      else hipLaunchKernelGGL((predict_tokens_kernel<4, 2>), gt, dim3(256), 0, st, P);
+      err = hipGetLastError();
+    } else if (stream_ok && stream_split(p0.r, &gs, &ng))
       err = s1_short ? launch_stream_split<1>(P, 0, gs, ng, tiles, st) : launch_stream_split<4>(P, 0, gs, ng, tiles, st);
     else
       err = launch_rows_nb(P, 0, nb, p0.r, dim3((tiles + tpw1 - 1) / tpw1, L), st);

@@ -333,3 +333,22 @@ def test_streamed_kernels_of_one_token_block(d_model, d_ff, r, k, batch):
         finally:
             binding.spark_debug_tuning(0, 0, 0)
         check_ffn_against_oracle(sh, weights, q, out, TOL_BF16_TIGHT, what=f"streamed B={batch} L={n_layers}")
+
+
+@pytest.mark.parametrize("batch", [2, 3, 4])
+@pytest.mark.parametrize("shape", [synth.GEMMA2_2B, synth.FFNShape("few", 1024, 1000, 520, 77)])
+def test_few_token_predictor(shape, batch):
+    """Two to four tokens take the vector-ALU predictor sweep (whole-row loads, a dot product per
+    token): the 2B shape, and a shape whose predictor rows do not fill the last chunks of a wave and
+    whose neuron count is ragged; against the oracle, and against the matrix-core kernels."""
+    weights = synth.ffn_stack(shape, 2, base_seed=800, dtype=torch.bfloat16)
+    q = synth.tokens(shape, batch, 810 + batch, torch.bfloat16)
+    out = run_gpu_ffn(shape, weights, q, via_layers=True)
+    check_ffn_against_oracle(shape, weights, q, out, TOL_BF16_TIGHT, what=f"few tokens B={batch}")
+    binding.spark_debug_tuning(0, 0, 100)
+    try:
+        other = run_gpu_ffn(shape, weights, q, via_layers=True)
+    finally:
+        binding.spark_debug_tuning(0, 0, 0)
+    assert np.array_equal(out["count"], other["count"]) and np.array_equal(out["idx"], other["idx"])
+    assert rel_l2(out["y"], other["y"]) < 1e-6
