@@ -352,3 +352,38 @@ def test_few_token_predictor(shape, batch):
         binding.spark_debug_tuning(0, 0, 0)
     assert np.array_equal(out["count"], other["count"]) and np.array_equal(out["idx"], other["idx"])
     assert rel_l2(out["y"], other["y"]) < 1e-6
+
+
+@pytest.mark.parametrize("batch", [1, 4, 16])
+def test_calls_can_be_captured_in_a_graph_and_replayed(batch):
+    """The library allocates nothing and clears nothing with memset nodes, so a call can sit in a HIP
+    graph: three replays, with eager calls on other inputs in between, each give the eager result."""
+    sh = synth.TINY
+    dev = torch.device(DEV)
+    weights = synth.ffn_stack(sh, 3, base_seed=900, dtype=torch.bfloat16, device=dev)
+    layers = [binding.make_layer(w[0], w[1], w[2], sh.k) for w in weights]
+    ws = binding.make_workspace(sh.d_model, sh.d_ff, batch, dev)
+    q = synth.tokens(sh, batch, 901, torch.bfloat16, dev)
+    q_static = q.clone()
+    y_graph = torch.zeros(3, batch, sh.d_model, device=dev)
+    y_eager = torch.zeros_like(y_graph)
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        binding.spark_ffn_decode_layers(layers, q_static, y_graph, ws)      # warm-up outside the capture
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        binding.spark_ffn_decode_layers(layers, q_static, y_graph, ws)
+    for rep in range(3):
+        qr = synth.tokens(sh, batch, 910 + rep, torch.bfloat16, dev)
+        q_static.copy_(qr)
+        y_graph.fill_(float("nan"))
+        graph.replay()
+        torch.cuda.synchronize()
+        # eager work on the same workspace between the replays, on other tokens and then on these
+        binding.spark_ffn_decode_layers(layers, q, y_eager, ws)
+        binding.spark_ffn_decode_layers(layers, qr, y_eager, ws)
+        torch.cuda.synchronize()
+        assert torch.equal(y_graph, y_eager), rep
