@@ -121,11 +121,13 @@ __device__ __forceinline__ float layer_theta(const PhasedParams& P, int l, int l
 // wave reads four consecutive rows of the 16 (4 * CPL1 16-byte loads in flight per lane;
 // occupancy does the rest of the latency hiding), so the workgroup as a whole walks through
 // one contiguous stretch of memory.
-template <typename WT, bool QB, int CPL1>
+// R = rows a wave has in flight: 4 when many workgroups share a compute unit, 12 (a block of
+// 48 rows in a single sweep) when a call has so few layers that a workgroup is alone on its
+// compute unit and its own loads are all the latency hiding there is.
+template <typename WT, bool QB, int CPL1, int R = 4>
 __global__ __launch_bounds__(256) void predict_layers_kernel(const PhasedParams P) {
   constexpr int VEC = Vec16<WT>::N;
   constexpr bool DOT2 = QB && VEC == 8;
-  constexpr int R = 4;
   __shared__ float s_sh[kMaxRPB];
   const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
   const int l = blockIdx.y, blk = blockIdx.x;
@@ -525,6 +527,11 @@ int g_phased_mask = 7;  // measurement aid: which of predict (1), gather (2), re
 
 template <typename WT, bool QB>
 hipError_t launch_predict(const PhasedParams& P, int cpl1, dim3 grid, hipStream_t st) {
+  if (P.RPB == 48 && cpl1 <= 2) {  // few layers: one sweep of 12 rows per wave
+    if (cpl1 == 1) hipLaunchKernelGGL((predict_layers_kernel<WT, QB, 1, 12>), grid, dim3(256), 0, st, P);
+    else hipLaunchKernelGGL((predict_layers_kernel<WT, QB, 2, 12>), grid, dim3(256), 0, st, P);
+    return hipGetLastError();
+  }
   switch (cpl1) {
     case 1: hipLaunchKernelGGL((predict_layers_kernel<WT, QB, 1>), grid, dim3(256), 0, st, P); break;
     case 2: hipLaunchKernelGGL((predict_layers_kernel<WT, QB, 2>), grid, dim3(256), 0, st, P); break;
