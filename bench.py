@@ -282,8 +282,8 @@ def prefill_bench(torch, binding, synth, dev, np):
             "note": "the weight fetch rate may exceed the HBM peak: all chunks read the same layer, from cache"}
 
 
-def fp8_bench(torch, binding, synth, dev, np):
-    """Batch-1 decode with 8-bit weight rows (OCP E4M3 codes + one fp32 scale per row; Appendix D.4's
+def fp8_bench(torch, binding, synth, dev, np, kind="fp8"):
+    """Batch-1 decode with 8-bit weight rows (OCP E4M3 or signed 8-bit integer codes + one fp32 scale per row; Appendix D.4's
     quantisation synergy): the Gemma-2-2B-shaped layers of the main benchmark quantised row by row, 52
     of them so that a step still touches more than the 256 MB Infinity Cache (26 would touch 314 MB).
     Algorithmic bytes per layer: d_ff (r + 4) for the predictor, m (2 d_model - r + 8) for the m
@@ -294,14 +294,16 @@ def fp8_bench(torch, binding, synth, dev, np):
         w = synth.ffn_layer(sh, 1000 + l, torch.float32, dev)
         layer_arrays = []
         for t in w:
-            codes, scales = synth.quantize_rows_fp8(t)
+            quantize = synth.quantize_rows_fp8 if kind == "fp8" else synth.quantize_rows_int8
+            codes, scales = quantize(t)
             if l == 0 and t is w[0]:      # the device's conversion agrees with the host's
-                c2, s2 = synth.quantize_rows_fp8(t.cpu())
+                c2, s2 = quantize(t.cpu())
                 assert torch.equal(codes.cpu(), c2) and torch.equal(scales.cpu(), s2)
             layer_arrays.append(binding.pack_fp8_rows(codes, scales))
         packed.append(layer_arrays)
         del w
-    layers = [binding.make_layer_fp8(p[0], p[1], p[2], sh.d_model, sh.d_ff, sh.r, sh.k) for p in packed]
+    code = binding.FP8_E4M3 if kind == "fp8" else binding.INT8
+    layers = [binding.make_layer_fp8(p[0], p[1], p[2], sh.d_model, sh.d_ff, sh.r, sh.k, code_dtype=code) for p in packed]
     q = synth.tokens(sh, 1, 2001, torch.bfloat16, dev)
     ws = binding.make_workspace(sh.d_model, sh.d_ff, 1, dev)
     y = torch.empty(L, 1, sh.d_model, device=dev)
@@ -316,7 +318,8 @@ def fp8_bench(torch, binding, synth, dev, np):
     gpu_s, _ = time_region(step, 200, 20, torch)
     per = gpu_s / 200
     nbytes = float(np.sum(sh.d_ff * (sh.r + 4) + m * (2 * sh.d_model - sh.r + 8)))
-    return {"workload": f"gemma2-2b-shape, {L} layers, batch 1, E4M3 weight codes with per-row fp32 scales",
+    return {"workload": f"gemma2-2b-shape, {L} layers, batch 1, {'E4M3' if kind == 'fp8' else 'signed 8-bit integer'} "
+                        "weight codes with per-row fp32 scales",
             "us_per_layer": per / L * 1e6, "layers_per_s": L / per, "active_count_mean": float(m.mean()),
             "algorithmic_bytes_per_layer": nbytes / L, "achieved_gbs": nbytes / per / 1e9,
             "hbm_frac": nbytes / per / 1e9 / HBM_PEAK_GBS}
@@ -495,6 +498,7 @@ def main():
     if not args.no_extra:
         out["prefill"] = prefill_bench(torch, binding, synth, dev, np)
         out["fp8_weights"] = fp8_bench(torch, binding, synth, dev, np)
+        out["int8_weights"] = fp8_bench(torch, binding, synth, dev, np, kind="int8")
     if not args.no_attention:
         out["attention"] = attention_bench(torch, binding, synth, dev, not args.no_cpu_baseline)
 

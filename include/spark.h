@@ -53,9 +53,10 @@ typedef enum {
   SPARK_ERR_DEVICE = 7     /* the HIP runtime refused a launch or a query                   */
 } spark_status;
 
-/* SPARK_FP8_E4M3 is a weight type only (spark_ffn_layer.wdtype): OCP E4M3 codes (1 sign, 4
- * exponent bits with bias 7, 3 mantissa bits, largest finite value 448), one byte each. */
-typedef enum { SPARK_F32 = 0, SPARK_BF16 = 1, SPARK_FP8_E4M3 = 2 } spark_dtype;
+/* SPARK_FP8_E4M3 and SPARK_INT8 are weight types only (spark_ffn_layer.wdtype), one byte per
+ * code: OCP E4M3 (1 sign, 4 exponent bits with bias 7, 3 mantissa bits, largest finite value
+ * 448), or a signed integer in two's complement. */
+typedef enum { SPARK_F32 = 0, SPARK_BF16 = 1, SPARK_FP8_E4M3 = 2, SPARK_INT8 = 3 } spark_dtype;
 
 /* What StatTop_k writes for entries at or below theta: 0 (Eq.10) or -inf (the Top_k^(-inf)
  * variant used in front of a softmax, Section 3 after Eq.11). */
@@ -137,7 +138,7 @@ spark_status spark_stat_topk_huber_backward(const void* x, const void* gy, spark
 /* ------------------------------------------------------------------------------------------
  * One Spark-FFN layer (Eq.2).  Host struct holding device pointers.
  */
-/* 8-bit weights (wdtype = SPARK_FP8_E4M3; the quantisation synergy of Appendix D.4: the sparse
+/* 8-bit weights (wdtype = SPARK_FP8_E4M3 or SPARK_INT8; the quantisation synergy of Appendix D.4: the sparse
  * path touches half the bytes again).  Each of the three arrays is then one allocation holding
  * the codes [d_ff][cols], one byte each, immediately followed by d_ff fp32 scales, one per
  * row: weight[j][c] = scale[j] * value(code[j][c]).  cols (r, d_model - r, d_model) must be

@@ -70,6 +70,8 @@ def _load():
     lib.spark_ref_fp8_e4m3_value.argtypes = [ctypes.c_uint]
     lib.spark_ref_fp8_dequantize_rows.restype = c_int
     lib.spark_ref_fp8_dequantize_rows.argtypes = [vp, vp, c_i64, c_i64, vp]
+    lib.spark_ref_int8_dequantize_rows.restype = c_int
+    lib.spark_ref_int8_dequantize_rows.argtypes = [vp, vp, c_i64, c_i64, vp]
     lib.spark_ref_spark_ffn.restype = c_int
     lib.spark_ref_spark_ffn.argtypes = [vp, vp, vp, vp, c_i64, c_i64, c_i64, c_i64, c_int, c_int,
                                         vp, vp, vp, vp, vp, vp, vp, vp, c_int]
@@ -232,6 +234,18 @@ def fp8_dequantize_rows(codes, scales) -> np.ndarray:
         raise ValueError("one scale per row")
     out = np.empty((rows, cols), np.float32)
     _check(_load().spark_ref_fp8_dequantize_rows(_ptr(codes), _ptr(scales), rows, cols, _ptr(out)), "fp8_dequantize_rows")
+    return out
+
+
+def int8_dequantize_rows(codes, scales) -> np.ndarray:
+    """float32 weights ``scales[row] * codes[row, c]`` of a matrix of signed 8-bit codes."""
+    codes = np.ascontiguousarray(codes).view(np.int8)
+    scales = np.ascontiguousarray(scales, dtype=np.float32)
+    rows, cols = codes.shape
+    if scales.shape != (rows,):
+        raise ValueError("one scale per row")
+    out = np.empty((rows, cols), np.float32)
+    _check(_load().spark_ref_int8_dequantize_rows(_ptr(codes), _ptr(scales), rows, cols, _ptr(out)), "int8_dequantize_rows")
     return out
 
 

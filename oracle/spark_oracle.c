@@ -344,6 +344,16 @@ int spark_ref_fp8_dequantize_rows(const uint8_t* codes, const float* scales, int
   return REF_OK;
 }
 
+/* The same for signed 8-bit integer codes (two's complement): weight = scale * code. */
+int spark_ref_int8_dequantize_rows(const int8_t* codes, const float* scales, int64_t rows, int64_t cols,
+                                   float* out) {
+  if (!codes || !scales || !out) return REF_ERR_NULL;
+  if (rows < 0 || cols < 0) return REF_ERR_SHAPE;
+  for (int64_t r = 0; r < rows; ++r)
+    for (int64_t c = 0; c < cols; ++c) out[r * cols + c] = (float)((double)scales[r] * (double)codes[r * cols + c]);
+  return REF_OK;
+}
+
 /*
  * One Spark-FFN layer for one token (Eq.2), weights neuron-major (row j = column j of the
  * paper's K1 / K2 / V):

@@ -16,7 +16,7 @@ import torch
 _PKG = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_PKG, "libspark_hip.so")
 
-F32, BF16, FP8_E4M3 = 0, 1, 2
+F32, BF16, FP8_E4M3, INT8 = 0, 1, 2, 3
 FILL_ZERO, FILL_NEG_INF = 0, 1
 GELU_ERF, GELU_TANH = 0, 1
 MAX_BATCH = 64
@@ -218,7 +218,7 @@ def spark_ffn_decode_layers(layers: Sequence[_Layer], q: torch.Tensor, y: torch.
 
 
 def pack_fp8_rows(codes: torch.Tensor, scales: torch.Tensor) -> torch.Tensor:
-    """One 8-bit weight array as the library reads it: the E4M3 codes ``[rows, cols]`` (uint8) followed
+    """One 8-bit weight array as the library reads it: the codes ``[rows, cols]`` (E4M3 or int8 bytes, as uint8) followed
     by one fp32 scale per row, in one allocation (returned as a flat uint8 tensor)."""
     if codes.dtype != torch.uint8 or scales.dtype != torch.float32 or scales.shape != (codes.shape[0],):
         raise ValueError("codes must be uint8 [rows, cols] and scales float32 [rows]")
@@ -228,13 +228,14 @@ def pack_fp8_rows(codes: torch.Tensor, scales: torch.Tensor) -> torch.Tensor:
 
 
 def make_layer_fp8(k1n: torch.Tensor, k2n: torch.Tensor, vn: torch.Tensor, d_model: int, d_ff: int, r: int, k: int,
-                   gelu: int = GELU_ERF) -> _Layer:
-    """Layer over three arrays packed by :func:`pack_fp8_rows` (the caller keeps them alive)."""
+                   gelu: int = GELU_ERF, code_dtype: int = FP8_E4M3) -> _Layer:
+    """Layer over three arrays packed by :func:`pack_fp8_rows` (the caller keeps them alive);
+    ``code_dtype`` says how the bytes read: ``FP8_E4M3`` or ``INT8``."""
     need = (d_ff * (r + 4), d_ff * (d_model - r + 4), d_ff * (d_model + 4))
     for t, n in zip((k1n, k2n, vn), need):
         if t.dtype != torch.uint8 or t.numel() != n or not t.is_contiguous():
             raise ValueError("packed 8-bit weight array of the wrong size")
-    return _Layer(int(d_model), int(d_ff), int(r), int(k), FP8_E4M3, int(gelu), k1n.data_ptr(), k2n.data_ptr(),
+    return _Layer(int(d_model), int(d_ff), int(r), int(k), int(code_dtype), int(gelu), k1n.data_ptr(), k2n.data_ptr(),
                   vn.data_ptr())
 
 

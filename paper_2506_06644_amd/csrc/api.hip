@@ -9,9 +9,10 @@
 namespace {
 
 bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
-size_t dtype_size(int dt) { return dt == SPARK_FP8_E4M3 ? 1 : dt == SPARK_BF16 ? 2 : 4; }
+bool is_code_dtype(int dt) { return dt == SPARK_FP8_E4M3 || dt == SPARK_INT8; }  // 8-bit codes with row scales
+size_t dtype_size(int dt) { return is_code_dtype(dt) ? 1 : dt == SPARK_BF16 ? 2 : 4; }
 bool dtype_ok(int dt) { return dt == SPARK_F32 || dt == SPARK_BF16; }            // tokens, activations
-bool weight_dtype_ok(int dt) { return dtype_ok(dt) || dt == SPARK_FP8_E4M3; }  // weight arrays
+bool weight_dtype_ok(int dt) { return dtype_ok(dt) || is_code_dtype(dt); }  // weight arrays
 
 double normal_cdf(double z) { return 0.5 * std::erfc(-z * 0.70710678118654752440); }
 
@@ -47,7 +48,7 @@ spark_status validate_decode(const spark_ffn_layer* L, const void* q, int qdtype
   if (!workspace) return SPARK_ERR_WORKSPACE;
   if (reinterpret_cast<uintptr_t>(workspace) & 255u) return SPARK_ERR_WORKSPACE;
   if (workspace_bytes < spark_ffn_workspace_bytes(L->d_model, L->d_ff, batch)) return SPARK_ERR_WORKSPACE;
-  if (L->wdtype == SPARK_FP8_E4M3) {
+  if (is_code_dtype(L->wdtype)) {
     // 8-bit weights exist for the one-token path only
     const spark::FfnProblem p = make_problem(L, q, qdtype, batch, ldq, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr);
     if (batch != 1 || !spark::phased_supported(p)) return SPARK_ERR_DTYPE;
@@ -64,7 +65,7 @@ spark::FfnProblem make_problem(const spark_ffn_layer* L, const void* q, int qdty
   p.r = L->r;
   p.k = L->k;
   p.w_bf16 = L->wdtype == SPARK_BF16;
-  p.w_fp8 = L->wdtype == SPARK_FP8_E4M3;
+  p.w_fp8 = L->wdtype == SPARK_FP8_E4M3 ? 1 : L->wdtype == SPARK_INT8 ? 2 : 0;
   p.q_bf16 = qdtype == SPARK_BF16;
   p.gelu = L->gelu;
   p.k1n = L->k1n;
@@ -346,7 +347,7 @@ spark_status spark_ffn_dense_decode(const spark_ffn_layer* layer, const void* q,
                                     size_t workspace_bytes, void* hip_stream) {
   const spark_status s = validate_decode(layer, q, qdtype, batch, ldq, y, workspace, workspace_bytes);
   if (s != SPARK_OK) return s;
-  if (layer->wdtype == SPARK_FP8_E4M3) return SPARK_ERR_DTYPE;  // use spark_ffn_dense_decode_layers
+  if (is_code_dtype(layer->wdtype)) return SPARK_ERR_DTYPE;  // use spark_ffn_dense_decode_layers
   const spark::FfnProblem p =
       make_problem(layer, q, qdtype, batch, ldq, y, nullptr, nullptr, nullptr, nullptr, nullptr);
   const spark::FfnWorkspace ws = spark::carve_workspace(workspace, layer->d_model, layer->d_ff, batch);

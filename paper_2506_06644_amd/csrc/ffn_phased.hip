@@ -501,17 +501,18 @@ PhasedLayout phased_layout(int d_model, int d_ff) {
 
 // Compiled gather variants: chunks per lane of a K2n row and of a Vn row.
 struct GatherVariant {
-  int kind, cpl2, cplv, nw, occ;  // weight type (0 fp32, 1 bf16, 2 fp8), chunks, waves per workgroup,
+  int kind, cpl2, cplv, nw, occ;  // weight type (0 fp32, 1 bf16, 2 fp8, 3 int8), chunks, waves per workgroup,
                                   // waves per SIMD the registers are held to
 };
 constexpr GatherVariant kGather[] = {
     {1, 1, 1, 8, 4}, {1, 3, 5, 4, 3}, {1, 4, 7, 4, 2}, {0, 1, 1, 8, 4}, {0, 2, 2, 8, 4}, {0, 5, 9, 4, 2},
     {1, 3, 5, 8, 4},  // alternative for the 2B class (tuning switch)
     {2, 1, 1, 8, 4}, {2, 2, 3, 4, 3}, {2, 2, 4, 4, 2},
+    {3, 1, 1, 8, 4}, {3, 2, 3, 4, 3}, {3, 2, 4, 4, 2},
 };
 constexpr int kNumGather = sizeof(kGather) / sizeof(kGather[0]);
 
-int weight_kind(const FfnProblem& p) { return p.w_fp8 ? 2 : p.w_bf16 ? 1 : 0; }
+int weight_kind(const FfnProblem& p) { return p.w_fp8 == 2 ? 3 : p.w_fp8 ? 2 : p.w_bf16 ? 1 : 0; }
 int weight_vec(const FfnProblem& p) { return p.w_fp8 ? 16 : p.w_bf16 ? 8 : 4; }  // elements per 16 bytes
 
 int gather_variant(const FfnProblem& p) {
@@ -556,7 +557,8 @@ hipError_t launch_gather(const PhasedParams& P, dim3 grid, hipStream_t st) {
 template <int I>
 hipError_t launch_gather_index(const PhasedParams& P, dim3 grid, hipStream_t st) {
   constexpr GatherVariant v = kGather[I];
-  if constexpr (v.kind == 2) return launch_gather<fp8_t, v.cpl2, v.cplv, v.nw, v.occ>(P, grid, st);
+  if constexpr (v.kind == 3) return launch_gather<i8_t, v.cpl2, v.cplv, v.nw, v.occ>(P, grid, st);
+  else if constexpr (v.kind == 2) return launch_gather<fp8_t, v.cpl2, v.cplv, v.nw, v.occ>(P, grid, st);
   else if constexpr (v.kind == 1) return launch_gather<bf16_t, v.cpl2, v.cplv, v.nw, v.occ>(P, grid, st);
   else return launch_gather<float, v.cpl2, v.cplv, v.nw, v.occ>(P, grid, st);
 }
@@ -645,6 +647,7 @@ hipError_t launch_ffn_phased(const FfnProblem& p0, const void* const* k1n, const
 
     const dim3 ga(P.NBA, L);
     if (!(g_phased_mask & 1)) err = hipSuccess;
+    else if (p0.w_fp8 == 2) err = launch_predict<i8_t, false>(P, cpl1, ga, st);
     else if (p0.w_fp8) err = launch_predict<fp8_t, false>(P, cpl1, ga, st);
     else if (p0.w_bf16) err = p0.q_bf16 ? launch_predict<bf16_t, true>(P, cpl1, ga, st) : launch_predict<bf16_t, false>(P, cpl1, ga, st);
     else err = launch_predict<float, false>(P, cpl1, ga, st);
@@ -661,6 +664,9 @@ hipError_t launch_ffn_phased(const FfnProblem& p0, const void* const* k1n, const
       case 7: err = launch_gather_index<7>(P, gc, st); break;
       case 8: err = launch_gather_index<8>(P, gc, st); break;
       case 9: err = launch_gather_index<9>(P, gc, st); break;
+      case 10: err = launch_gather_index<10>(P, gc, st); break;
+      case 11: err = launch_gather_index<11>(P, gc, st); break;
+      case 12: err = launch_gather_index<12>(P, gc, st); break;
       default: err = hipErrorInvalidValue; break;
     }
     if (err != hipSuccess) return err;

@@ -89,6 +89,20 @@ struct Vec16<fp8_t> {
   }
 };
 
+// One weight code as a signed 8-bit integer (two's complement, -127..127 used), with the same
+// row layout as the E4M3 codes: weight = scale * code.
+struct i8_t {
+  int8_t bits;
+};
+template <>
+struct Vec16<i8_t> {
+  static constexpr int N = 16;
+  u32x4 raw;
+  __device__ __forceinline__ float get(int i) const {
+    return (float)(int)(int8_t)(raw[i >> 2] >> (8 * (i & 3)));
+  }
+};
+
 template <typename T>
 __device__ __forceinline__ Vec16<T> load_vec16(const T* p) {
   Vec16<T> v;

@@ -20,7 +20,8 @@ hipError_t launch_stat_topk_vjp(const void* x, const void* gy, int dt, int64_t r
 struct FfnProblem {
   int d_model, d_ff, r, k;
   int w_bf16, q_bf16, gelu;
-  int w_fp8 = 0;  // weights are OCP E4M3 codes, every array followed by one fp32 scale per row (batch-1 phased path only)
+  int w_fp8 = 0;  // 1: weights are OCP E4M3 codes, 2: signed 8-bit integers; every array followed by one fp32
+                  // scale per row (batch-1 phased path only)
   const void *k1n, *k2n, *vn;
   const void* q;
   int64_t ldq;

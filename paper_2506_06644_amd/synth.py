@@ -141,6 +141,20 @@ def quantize_rows_fp8(w: torch.Tensor):
     return codes.contiguous(), scale.contiguous()
 
 
+def quantize_rows_int8(w: torch.Tensor):
+    """Per-row symmetric quantisation to signed 8-bit codes: ``scale = max|row| / 127`` rounded up to 8
+    significant bits (bf16), ``code = round_to_nearest_even(w / scale)`` in -127..127.  Returns (codes
+    as uint8 bytes [rows, cols], scales float32 [rows]) on the device of ``w``; an input generator."""
+    w = w.detach().to(torch.float32)
+    amax = w.abs().amax(dim=1)
+    scale = torch.where(amax > 0, amax / 127.0, torch.ones_like(amax))
+    scale = scale.to(torch.bfloat16).to(torch.float32)
+    low = scale * 127.0 < amax
+    scale = torch.where(low, (scale.to(torch.bfloat16).view(torch.int16) + 1).view(torch.bfloat16).to(torch.float32), scale)
+    codes = torch.round(w / scale[:, None]).clamp(-127, 127).to(torch.int8).view(torch.uint8)
+    return codes.contiguous(), scale.contiguous()
+
+
 def to_oracle(t: torch.Tensor):
     """Exact float32 view of a stored tensor for the CPU oracle (bf16 -> fp32 is exact)."""
     return t.detach().to("cpu").to(torch.float32).numpy()

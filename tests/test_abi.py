@@ -113,7 +113,7 @@ def test_huber_entries_reject_bad_arguments_before_launch():
     assert fwd(x=0) == 1 and fwd(y=0) == 1
     assert fwd(n=1) == 2 and fwd(ldy=32) == 2 and fwd(delta=-1.0) == 2 and fwd(delta=float("nan")) == 2
     assert fwd(k=0) == 3 and fwd(k=64) == 3
-    assert fwd(dt=2) == 4                                     # the 8-bit code type is a weight type only
+    assert fwd(dt=2) == 4 and fwd(dt=3) == 4                  # the 8-bit code types are weight types only
     assert fwd(x=0x1004) == 5 and fwd(dt=1, ldx=68, ldy=68) == 5
     assert fwd(rows=0) == 0
     assert bwd(gy=0) == 1 and bwd(gx=0) == 1
@@ -145,3 +145,4 @@ def test_prefill_and_8bit_weights_reject_bad_arguments_before_launch():
     assert _decode(_layer(wd=f8, r=136, d_model=328), ldq=328) == 5
     assert prefill(_layer(wd=f8), chunk=4) == 4
     assert _decode(_layer(wd=f8), qd=f8) == 4                 # tokens cannot be codes
+    assert _decode(_layer(wd=binding.INT8), batch=2) == 4 and _decode(_layer(wd=binding.INT8), qd=binding.INT8) == 4

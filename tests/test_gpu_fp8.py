@@ -1,4 +1,4 @@
-"""GPU parity of the Spark-FFN decode path with 8-bit (OCP E4M3) weight rows and per-row scales
+"""GPU parity of the Spark-FFN decode path with 8-bit (OCP E4M3 or signed integer) weight rows and per-row scales
 (the quantisation synergy of Appendix D.4) against the CPU oracle.
 
 The synthetic quantiser keeps scales to 8 significant bits, so the oracle's float weights
@@ -18,24 +18,30 @@ pytestmark = pytest.mark.gpu
 DEV = "cuda:0"
 
 
-def _quantised_stack(shape, n_layers, seed):
+KINDS = {"fp8": (binding.FP8_E4M3, synth.quantize_rows_fp8, oracle.fp8_dequantize_rows),
+         "int8": (binding.INT8, synth.quantize_rows_int8, oracle.int8_dequantize_rows)}
+
+
+def _quantised_stack(shape, n_layers, seed, kind="fp8"):
     """(packed device arrays per layer, dequantised float32 CPU weights per layer)."""
+    _, quantize, dequantize = KINDS[kind]
     packed, deq = [], []
     for l in range(n_layers):
         w = synth.ffn_layer(shape, seed + l, torch.float32)
         pk, dq = [], []
         for t in w:
-            codes, scales = synth.quantize_rows_fp8(t)
+            codes, scales = quantize(t)
             pk.append(binding.pack_fp8_rows(codes, scales).to(DEV))
-            dq.append(torch.from_numpy(oracle.fp8_dequantize_rows(codes.numpy(), scales.numpy())))
+            dq.append(torch.from_numpy(dequantize(codes.numpy(), scales.numpy())))
         packed.append(pk)
         deq.append(tuple(dq))
     return packed, deq
 
 
-def _run(shape, packed, q, via_layers, dense=False, gelu=binding.GELU_ERF):
+def _run(shape, packed, q, via_layers, dense=False, gelu=binding.GELU_ERF, kind="fp8"):
     L = len(packed)
-    layers = [binding.make_layer_fp8(p[0], p[1], p[2], shape.d_model, shape.d_ff, shape.r, shape.k, gelu) for p in packed]
+    layers = [binding.make_layer_fp8(p[0], p[1], p[2], shape.d_model, shape.d_ff, shape.r, shape.k, gelu, KINDS[kind][0])
+              for p in packed]
     qd = q.to(DEV)
     ws = binding.make_workspace(shape.d_model, shape.d_ff, 1, DEV)
     y = torch.full((L, 1, shape.d_model), float("nan"), device=DEV)
@@ -57,35 +63,38 @@ def _run(shape, packed, q, via_layers, dense=False, gelu=binding.GELU_ERF):
                 ucount=ucnt.cpu().numpy(), uidx=uidx.cpu().numpy())
 
 
+@pytest.mark.parametrize("kind", ["fp8", "int8"])
 @pytest.mark.parametrize("qdtype", [torch.bfloat16, torch.float32])
 @pytest.mark.parametrize("via_layers", [False, True])
-def test_tiny_layers(qdtype, via_layers):
+def test_tiny_layers(qdtype, via_layers, kind):
     sh = synth.TINY
-    packed, deq = _quantised_stack(sh, 3, 300)
+    packed, deq = _quantised_stack(sh, 3, 300, kind)
     q = synth.tokens(sh, 1, 301, qdtype)
-    out = _run(sh, packed, q, via_layers)
+    out = _run(sh, packed, q, via_layers, kind=kind)
     worst = check_ffn_against_oracle(sh, deq, q, out, TOL_BF16_TIGHT, what=f"fp8 tiny {qdtype}")
     assert worst < TOL_BF16_TIGHT
 
 
+@pytest.mark.parametrize("kind", ["fp8", "int8"])
 @pytest.mark.parametrize("shape", [synth.GEMMA2_2B, synth.GEMMA2_9B, synth.FFNShape("odd", 1040, 1000, 272, 77)])
-def test_model_shapes_and_a_ragged_one(shape):
+def test_model_shapes_and_a_ragged_one(shape, kind):
     """The 2B and 9B layer shapes (two layers in one call) and a shape whose rows do not fill the last
     16-byte chunks of a wave and whose d_ff is ragged."""
-    packed, deq = _quantised_stack(shape, 2, 310)
+    packed, deq = _quantised_stack(shape, 2, 310, kind)
     q = synth.tokens(shape, 1, 311, torch.bfloat16)
-    out = _run(shape, packed, q, True)
+    out = _run(shape, packed, q, True, kind=kind)
     check_ffn_against_oracle(shape, deq, q, out, TOL_BF16_TIGHT, what=f"fp8 {shape.name}")
     assert np.all(np.abs(out["count"] - shape.k) < 6 * np.sqrt(shape.k) + 6)
 
 
-def test_dense_evaluation_and_tanh_gelu():
+@pytest.mark.parametrize("kind", ["fp8", "int8"])
+def test_dense_evaluation_and_tanh_gelu(kind):
     sh = synth.TINY
-    packed, deq = _quantised_stack(sh, 2, 320)
+    packed, deq = _quantised_stack(sh, 2, 320, kind)
     q = synth.tokens(sh, 1, 321, torch.bfloat16)
-    out = _run(sh, packed, q, True, dense=True)
+    out = _run(sh, packed, q, True, dense=True, kind=kind)
     check_ffn_against_oracle(sh, deq, q, out, TOL_BF16_TIGHT, dense=True, what="fp8 dense")
-    out = _run(sh, packed, q, True, gelu=binding.GELU_TANH)
+    out = _run(sh, packed, q, True, gelu=binding.GELU_TANH, kind=kind)
     check_ffn_against_oracle(sh, deq, q, out, TOL_BF16_TIGHT, gelu=oracle.GELU_TANH, what="fp8 tanh")
 
 

@@ -690,3 +690,17 @@ def test_fp8_rows_dequantise_exactly(oracle):
     assert np.max(np.abs(deq - w.numpy()) / np.abs(w.numpy()).max(axis=1, keepdims=True)) <= 2.0 ** -4 * 1.01
     again = (torch.from_numpy(deq) / scales[:, None]).to(torch.float8_e4m3fn).view(torch.uint8)
     assert torch.equal(again, codes)
+
+
+def test_int8_rows_dequantise_exactly(oracle):
+    """Signed 8-bit codes: scale * code against numpy's int8 view, exact in float32 with 8-bit scales,
+    and the quantiser's round trip."""
+    w = synth.ffn_layer(synth.TINY, 4, torch.float32)[2]
+    codes, scales = synth.quantize_rows_int8(w)
+    deq = oracle.int8_dequantize_rows(codes.numpy(), scales.numpy())
+    exact = scales.numpy().astype(np.float64)[:, None] * codes.numpy().view(np.int8).astype(np.float64)
+    assert np.array_equal(deq.astype(np.float64), exact)
+    assert codes.numpy().view(np.int8).min() >= -127
+    assert np.max(np.abs(deq - w.numpy()) / np.abs(w.numpy()).max(axis=1, keepdims=True)) <= 0.5 / 127 * 1.02
+    again = torch.round(torch.from_numpy(deq) / scales[:, None]).to(torch.int8).view(torch.uint8)
+    assert torch.equal(again, codes)
