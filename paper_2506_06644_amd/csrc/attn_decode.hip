@@ -82,7 +82,7 @@ __global__ __launch_bounds__(256) void attn_predict_kernel(const AttnParams P) {
   constexpr int VEC = Vec16<WT>::N;
   constexpr int RPI = kWave / LPR;   // keys per wave instruction
   constexpr int NI = kKeysPerWave / RPI;    // instructions per wave
-  constexpr int U = NI < 8 ? NI : 8;  // loads in flight per lane
+  constexpr int U = NI < 16 ? NI : 16;  // loads in flight per lane
   __shared__ float s_sh[G][kKeysPerBlock];
   const int tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid / kWave;
   const int h = blockIdx.y, key0 = blockIdx.x * kKeysPerBlock;
