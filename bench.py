@@ -35,6 +35,16 @@ MEASURED_TRAFFIC_BYTES = {("gemma2-2b", 26, 1): {
 }}
 
 
+# The same for the row-wise top-k kernels on rows=8192, n=9216 (forward: read + write, backward:
+# two reads + write); key = (dtype name, "forward" | "backward").
+STAT_TOPK_TRAFFIC_BYTES = {
+    ("f32", "forward"): 302.2e6 + 302.5e6,    # FETCH 147567.2 KiB x 2, WRITE 295426.3 KiB x 1
+    ("bf16", "forward"): 151.2e6 + 151.5e6,   # FETCH 73849.7 KiB x 2, WRITE 147972.0 KiB x 1
+    ("f32", "backward"): 604.1e6 + 302.0e6,   # FETCH 294968.6 KiB x 2, WRITE 294925.4 KiB x 1
+    ("bf16", "backward"): 302.1e6 + 151.0e6,  # FETCH 147520.5 KiB x 2, WRITE 147456.0 KiB x 1
+}
+
+
 def algorithmic_bytes(shape, counts, wbytes):
     """Weights the method must touch for one token in one layer: K1n fully, K2n and Vn at the
     active rows only.  `counts` = measured active count per layer."""
@@ -126,7 +136,8 @@ def stat_topk_bench(torch, binding, synth, dev, with_cpu):
         nbytes = 2.0 * rows * n * w + 8.0 * rows
         out[name] = {"rows_per_s": rows * 50 / gpu_s, "us_per_call": gpu_s / 50 * 1e6,
                      "roofline": {"bound": "hbm", "achieved": nbytes / avg_s / 1e9, "peak": HBM_PEAK_GBS,
-                                  "unit": "GB/s", "frac": nbytes / avg_s / 1e9 / HBM_PEAK_GBS, "traffic": None,
+                                  "unit": "GB/s", "frac": nbytes / avg_s / 1e9 / HBM_PEAK_GBS,
+                                  "traffic": STAT_TOPK_TRAFFIC_BYTES.get((name, "forward")),
                                   "kernel": "stat_topk_cached_kernel", "bytes_per_launch": nbytes,
                                   "launch_us": avg_s * 1e6},
                      "count_mean": float(count.float().mean()), "count_min": int(count.min()),
@@ -143,7 +154,8 @@ def stat_topk_bench(torch, binding, synth, dev, with_cpu):
         out[name]["backward"] = {"us_per_call": bavg_s * 1e6, "rows_per_s": rows / bavg_s, "delta": 0.25,
                                  "roofline": {"bound": "hbm", "achieved": bbytes / bavg_s / 1e9, "peak": HBM_PEAK_GBS,
                                               "unit": "GB/s", "frac": bbytes / bavg_s / 1e9 / HBM_PEAK_GBS,
-                                              "traffic": None, "kernel": "stat_topk_vjp_cached_kernel",
+                                              "traffic": STAT_TOPK_TRAFFIC_BYTES.get((name, "backward")),
+                                              "kernel": "stat_topk_vjp_cached_kernel",
                                               "bytes_per_launch": bbytes, "launch_us": bavg_s * 1e6}}
         del gy
         if with_cpu and name == "f32":
