@@ -361,7 +361,8 @@ def main():
     import numpy as np
     import torch
 
-    from paper_2506_06644_amd import binding, synth
+    import synth
+    from paper_2506_06644_amd import binding
 
     if not torch.cuda.is_available():
         sys.exit("bench.py needs a GPU")

@@ -80,6 +80,8 @@ def _load():
     lib.spark_ref_spark_attention.restype = c_int
     lib.spark_ref_spark_attention.argtypes = [vp, vp, vp, vp, c_i64, c_i64, c_i64, c_i64, c_int,
                                               vp, vp, vp, vp, vp, vp, vp]
+    lib.spark_ref_spark_attention_on_set.restype = c_int
+    lib.spark_ref_spark_attention_on_set.argtypes = [vp, vp, vp, vp, c_i64, c_i64, c_i64, vp, c_i64, vp]
     _lib = lib
     return lib
 
@@ -347,6 +349,24 @@ def spark_attention(k1c, k2c, vc, q, k: int, skip_inactive: bool = False) -> Spa
     m = int(cnt[0])
     return SparkAttention(y, s, p, g, float(stats[0]), float(stats[1]), float(stats[2]),
                           float(stats[3]), idx[:m].copy(), m)
+
+
+def spark_attention_on_set(k1c, k2c, vc, q, kept) -> np.ndarray:
+    """Eq.7 evaluated on a given kept set (softmax over exactly those keys): y[d_attn] float64."""
+    k1c = np.ascontiguousarray(k1c, dtype=np.float32)
+    k2c = np.ascontiguousarray(k2c, dtype=np.float32)
+    vc = np.ascontiguousarray(vc, dtype=np.float32)
+    q = np.ascontiguousarray(q, dtype=np.float32)
+    kept = np.ascontiguousarray(kept, dtype=np.int32)
+    n_ctx, r = k1c.shape
+    d_attn = vc.shape[1]
+    if k2c.shape != (n_ctx, d_attn - r) or vc.shape[0] != n_ctx or q.shape != (d_attn,):
+        raise ValueError("spark_attention_on_set: inconsistent shapes")
+    y = np.empty(d_attn, np.float64)
+    rc = _load().spark_ref_spark_attention_on_set(_ptr(k1c), _ptr(k2c), _ptr(vc), _ptr(q), n_ctx, d_attn, r,
+                                                  _ptr(kept), kept.shape[0], _ptr(y))
+    _check(rc, "spark_attention_on_set")
+    return y
 
 
 def union_of(index_sets) -> np.ndarray:

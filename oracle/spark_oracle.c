@@ -308,10 +308,10 @@ int spark_ref_exact_topk_rows(const double* x, int64_t rows, int64_t d, int64_t 
 #endif
   (void)threads;
   int rc = REF_OK;
-#pragma omp parallel for num_threads(threads) schedule(static)
+#pragma omp parallel for num_threads(threads) schedule(static) reduction(max : rc)
   for (int64_t row = 0; row < rows; ++row) {
     int e = spark_ref_exact_topk(x + row * ldx, d, k, idx + row * k);
-    if (e != REF_OK) rc = e;
+    if (e > rc) rc = e;
   }
   return rc;
 }
@@ -560,5 +560,61 @@ int spark_ref_spark_attention(const float* k1c, const float* k2c, const float* v
   if (stats) memcpy(stats, st, sizeof(st));
   if (count_out) *count_out = m;
   free(s); free(a); free(p); free(g); free(idx);
+  return REF_OK;
+}
+
+/*
+ * Eq.7 with the kept set handed in instead of derived: the softmax runs over exactly the keys
+ * kept[0..m) (every other key has weight 0, as after Top_k^(-inf)), gated by softplus and
+ * applied to the values,
+ *   y_c = sum_{i in kept} softmax_kept(s)_i * softplus(k2c[i] . q[r:]) * vc[i][c],
+ *   s_i = k1c[i] . q[:r].
+ * The softmax is invariant to the shift by theta, so the scores themselves are used.  It says
+ * what Eq.7 yields for a kept set that differs from the oracle's own by keys sitting at the
+ * threshold.  m = 0 gives y = 0.
+ */
+int spark_ref_spark_attention_on_set(const float* k1c, const float* k2c, const float* vc, const float* q,
+                                     int64_t n_ctx, int64_t d_attn, int64_t r, const int32_t* kept,
+                                     int64_t m, double* y) {
+  if (!k1c || !k2c || !vc || !q || !y || (m > 0 && !kept)) return REF_ERR_NULL;
+  if (n_ctx < 1 || d_attn < 2 || r < 1 || r > d_attn - 1 || m < 0 || m > n_ctx) return REF_ERR_SHAPE;
+  const int64_t r2 = d_attn - r;
+  for (int64_t c = 0; c < d_attn; ++c) y[c] = 0.0;
+  if (m == 0) return REF_OK;
+  double* s = (double*)malloc((size_t)m * sizeof(double));
+  double* w = (double*)malloc((size_t)m * sizeof(double));
+  if (!s || !w) {
+    free(s); free(w);
+    return REF_ERR_SHAPE;
+  }
+  double smax = -INFINITY;
+  for (int64_t t = 0; t < m; ++t) {
+    const int64_t i = kept[t];
+    if (i < 0 || i >= n_ctx) {
+      free(s); free(w);
+      return REF_ERR_SHAPE;
+    }
+    double acc = 0.0;
+    for (int64_t e = 0; e < r; ++e) acc += (double)k1c[i * r + e] * (double)q[e];
+    s[t] = acc;
+    if (acc > smax) smax = acc;
+  }
+  double den = 0.0;
+  for (int64_t t = 0; t < m; ++t) {
+    w[t] = exp(s[t] - smax);
+    den += w[t];
+  }
+  for (int64_t t = 0; t < m; ++t) {
+    const int64_t i = kept[t];
+    double acc = 0.0;
+    for (int64_t e = 0; e < r2; ++e) acc += (double)k2c[i * r2 + e] * (double)q[r + e];
+    w[t] = w[t] / den * spark_ref_softplus(acc);
+  }
+  for (int64_t c = 0; c < d_attn; ++c) {
+    double acc = 0.0;
+    for (int64_t t = 0; t < m; ++t) acc += w[t] * (double)vc[(int64_t)kept[t] * d_attn + c];
+    y[c] = acc;
+  }
+  free(s); free(w);
   return REF_OK;
 }

@@ -9,7 +9,8 @@ import numpy as np
 import torch
 
 import oracle
-from paper_2506_06644_amd import binding, synth
+import synth
+from paper_2506_06644_amd import binding
 
 BAND = 1e-3
 TOL_F32 = 1e-5

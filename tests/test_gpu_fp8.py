@@ -11,7 +11,8 @@ import pytest
 import torch
 
 import oracle
-from paper_2506_06644_amd import binding, synth
+import synth
+from paper_2506_06644_amd import binding
 from parity_util import TOL_BF16_TIGHT, check_ffn_against_oracle
 
 pytestmark = pytest.mark.gpu

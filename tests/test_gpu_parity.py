@@ -4,7 +4,8 @@ import pytest
 import torch
 
 import oracle
-from paper_2506_06644_amd import binding, synth
+import synth
+from paper_2506_06644_amd import binding
 
 from parity_util import (TOL_BF16, TOL_BF16_TIGHT, TOL_F32, assert_active_set, check_ffn_against_oracle,
                          rel_l2, run_gpu_ffn)

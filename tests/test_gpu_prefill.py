@@ -4,7 +4,8 @@ import numpy as np
 import pytest
 import torch
 
-from paper_2506_06644_amd import binding, synth
+import synth
+from paper_2506_06644_amd import binding
 from parity_util import TOL_BF16_TIGHT, TOL_F32, check_ffn_against_oracle, rel_l2
 
 pytestmark = pytest.mark.gpu

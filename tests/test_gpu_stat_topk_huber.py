@@ -15,7 +15,8 @@ import pytest
 import torch
 
 import oracle
-from paper_2506_06644_amd import binding, synth
+import synth
+from paper_2506_06644_amd import binding
 from parity_util import rel_l2
 
 pytestmark = pytest.mark.gpu

@@ -14,7 +14,7 @@ import scipy.special
 import scipy.stats
 import torch
 
-from paper_2506_06644_amd import synth
+import synth
 
 GOLDEN = os.path.join(os.path.dirname(__file__), "golden")
 
@@ -495,6 +495,30 @@ def test_attention_closed_forms(oracle):
     k1c, k2c, vc, q = _attn_case(9, 100, 32, 16)
     o = oracle.spark_attention(np.zeros_like(k1c), k2c, vc, q, 10)
     assert o.count == 0 and np.all(o.y == 0.0) and o.theta == 0.0
+
+
+def test_attention_on_a_given_kept_set(oracle):
+    """Eq.7 with the kept set handed in: on the oracle's own set it is the oracle's y; on any other set it
+    is the library softmax over exactly those keys, gated and applied to the values; an empty set gives 0."""
+    for seed, n_ctx, k in ((21, 300, 30), (22, 1000, 256), (23, 17, 40)):
+        k1c, k2c, vc, q = _attn_case(seed, n_ctx, 48, 24)
+        o = oracle.spark_attention(k1c, k2c, vc, q, k)
+        np.testing.assert_allclose(oracle.spark_attention_on_set(k1c, k2c, vc, q, o.idx), o.y, rtol=1e-11, atol=1e-14)
+        rng = np.random.default_rng(seed)
+        for m in (1, 2, min(n_ctx, 50)):
+            kept = np.sort(rng.choice(n_ctx, size=m, replace=False)).astype(np.int32)
+            s = k1c[kept].astype(np.float64) @ q[:24].astype(np.float64)
+            g = np.logaddexp(0.0, k2c[kept].astype(np.float64) @ q[24:].astype(np.float64))
+            want = vc[kept].astype(np.float64).T @ (scipy.special.softmax(s) * g)
+            np.testing.assert_allclose(oracle.spark_attention_on_set(k1c, k2c, vc, q, kept), want, rtol=1e-11, atol=1e-14)
+        # dropping the weakest kept key changes y by about that key's softmax mass, and is not the same y
+        if o.count > 2:
+            weakest = o.idx[np.argmin(o.s[o.idx])]
+            y2 = oracle.spark_attention_on_set(k1c, k2c, vc, q, o.idx[o.idx != weakest])
+            assert not np.array_equal(y2, o.y)
+        assert np.all(oracle.spark_attention_on_set(k1c, k2c, vc, q, np.zeros(0, np.int32)) == 0.0)
+    with pytest.raises(ValueError):
+        oracle.spark_attention_on_set(k1c, k2c, vc, q, np.array([n_ctx], np.int32))
 
 
 def test_attention_invariances(oracle):
