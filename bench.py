@@ -3,21 +3,34 @@
 
 A "step" is one pass of the whole hot path (predictor, statistical top-k, compaction,
 gathered K2 / V products) over every layer of a stack of Gemma-2-2B-shaped layers that is
-resident in HBM (26 layers x 127.4 MB, so the weights cannot stay in the 256 MB Infinity
-Cache), for one batch-1 token vector.  Inputs are synthetic (weights N(0, 1/d_model) in bf16,
-token N(0, 1) in bf16) and are on the device before the timed region starts.
+resident in HBM (26 layers x 84.9 MB = 2.2 GB of weights, 627 MB of them touched per step, so
+the weights cannot stay in the 256 MB Infinity Cache), for one batch-1 token vector.  Inputs are
+synthetic (weights N(0, 1/d_model) in bf16, token N(0, 1) in bf16) and are on the device before
+the timed region starts.
 
 Prints ONE JSON line.  `value` is layers per second; the `roofline` object prices the
-kernel that does the work against MI355X's 8 TB/s HBM peak using the algorithmic bytes
-(all of K1n plus the active rows of K2n and Vn, with the measured active count of every
-layer); `cpu_baseline` is the CPU oracle timed on the host cores on a bounded sample.
+dominant kernel (the predictor sweep) against MI355X's 8 TB/s HBM peak on its algorithmic
+bytes, with the whole call and the other kernels beside it; `cpu_baseline` is the CPU oracle
+timed on the host cores on a bounded sample.
+
+HBM traffic (`roofline.traffic`) is measured in the same run: before this process touches the
+GPU it starts `rocprofv3 --pmc FETCH_SIZE` and `rocprofv3 --pmc WRITE_SIZE` over
+`python3 bench.py --traffic-probe` (the same workload, a few calls) and scales each counter by
+what it reads for the library's plain copy kernel of known size.  If the profiler is missing or a
+run fails, `traffic` is null and `traffic_note` says why.
 """
 from __future__ import annotations
 
 import argparse
+import csv
+import glob
 import json
 import os
+import shutil
+import signal
+import subprocess
 import sys
+import tempfile
 import time
 
 ROOT = os.path.dirname(os.path.abspath(__file__))
@@ -25,24 +38,123 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0
-# HBM bytes per launch of each kernel from two rocprofv3 --pmc runs (FETCH_SIZE, then WRITE_SIZE,
-# each scaled by what the counter reads for a plain 1 GiB device copy); workload key =
-# (shape, layers, batch).  Other workloads report null.
-MEASURED_TRAFFIC_BYTES = {("gemma2-2b", 26, 1): {
-    "predict_layers_kernel": 490.8e6 + 1.08e6,   # FETCH 239652.7 KiB x 2, WRITE 1053.9 KiB x 1
-    "gather_layers_kernel": 137.26e6 + 8.63e6,   # FETCH 67023.3 KiB x 2, WRITE 8424.2 KiB x 1
-    "reduce_layers_kernel": 8.65e6 + 0.24e6,     # FETCH 4223.5 KiB x 2, WRITE 234.0 KiB x 1
-}}
+CAL_COPY_BYTES = 256 << 20   # size of the calibration copy in the traffic probe
 
 
-# The same for the row-wise top-k kernels on rows=8192, n=9216 (forward: read + write, backward:
-# two reads + write); key = (dtype name, "forward" | "backward").
-STAT_TOPK_TRAFFIC_BYTES = {
-    ("f32", "forward"): 302.2e6 + 302.5e6,    # FETCH 147567.2 KiB x 2, WRITE 295426.3 KiB x 1
-    ("bf16", "forward"): 151.2e6 + 151.5e6,   # FETCH 73849.7 KiB x 2, WRITE 147972.0 KiB x 1
-    ("f32", "backward"): 604.1e6 + 302.0e6,   # FETCH 294968.6 KiB x 2, WRITE 294925.4 KiB x 1
-    ("bf16", "backward"): 302.1e6 + 151.0e6,  # FETCH 147520.5 KiB x 2, WRITE 147456.0 KiB x 1
-}
+# ------------------------------------------------------------------------------- HBM traffic
+def traffic_probe(args):
+    """Child of `measure_traffic` (runs under rocprofv3 --pmc): a few calls of the main workload, of
+    the row-wise top-k kernels and of the plain copy kernel.  Prints nothing that is parsed."""
+    import torch
+
+    import synth
+    from paper_2506_06644_amd import binding
+
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+    src = torch.full((CAL_COPY_BYTES,), 7, dtype=torch.uint8, device=dev)
+    dst = torch.empty_like(src)
+    for _ in range(3):
+        binding.spark_copy_bytes(dst, src)
+    torch.cuda.synchronize()
+    del src, dst
+    shape = synth.SHAPES[args.shape]
+    L, B = args.layers, args.batch
+    weights = synth.ffn_stack(shape, L, base_seed=1000, dtype=torch.bfloat16, device=dev)
+    q = synth.tokens(shape, B, 2000 + B, dtype=torch.bfloat16, device=dev)
+    layers = [binding.make_layer(w[0], w[1], w[2], shape.k) for w in weights]
+    ws = binding.make_workspace(shape.d_model, shape.d_ff, B, dev)
+    y = torch.empty(L, B, shape.d_model, device=dev)
+    for _ in range(4):
+        binding.spark_ffn_decode_layers(layers, q, y, ws)
+    torch.cuda.synchronize()
+    del weights, layers, ws, y
+    if not args.no_stat_topk:
+        rows, n, k = 8192, 9216, 737
+        for dt in (torch.bfloat16, torch.float32):
+            x = synth.topk_rows(rows, n, seed=4242, dtype=dt, device=dev)
+            out = torch.empty_like(x)
+            gy = synth.grad_rows(rows, n, seed=4243, dtype=dt, device=dev)
+            theta = torch.empty(rows, device=dev)
+            count = torch.empty(rows, dtype=torch.int32, device=dev)
+            for _ in range(2):
+                binding.spark_stat_topk(x, k, y=out, theta=theta, count=count)
+                binding.spark_stat_topk_huber_backward(x, gy, k, 0.25, out)
+            torch.cuda.synchronize()
+            del x, out, gy
+    print("traffic probe done", flush=True)
+
+
+def _counter_rows(out_dir, counter):
+    """[(kernel name, value)] of one rocprofv3 --pmc run written as csv."""
+    rows = []
+    for path in glob.glob(os.path.join(out_dir, "**", "*counter_collection.csv"), recursive=True):
+        with open(path, newline="") as f:
+            for rec in csv.DictReader(f):
+                if rec.get("Counter_Name") == counter:
+                    rows.append((rec.get("Kernel_Name", ""), float(rec.get("Counter_Value", "nan"))))
+    return rows
+
+
+def measure_traffic(args):
+    """HBM bytes per dispatch of every kernel of the workload: FETCH_SIZE and WRITE_SIZE (KiB per
+    dispatch, one counter per profiler run) of `bench.py --traffic-probe`, each scaled by the factor
+    that makes the counter of the plain copy kernel equal to the bytes it is known to move.
+    Returns ({kernel name: {"fetch_bytes", "write_bytes", "dispatches"}}, note)."""
+    rocprof = shutil.which("rocprofv3") or "/opt/rocm/bin/rocprofv3"
+    if not os.path.exists(rocprof):
+        return None, "rocprofv3 not found"
+    per_counter, notes = {}, []
+    for counter in ("FETCH_SIZE", "WRITE_SIZE"):
+        out_dir = tempfile.mkdtemp(prefix="spark_traffic_", dir="/tmp")
+        cmd = [rocprof, "--pmc", counter, "-d", out_dir, "-o", "t", "-f", "csv", "--", sys.executable,
+               os.path.join(ROOT, "bench.py"), "--traffic-probe", "--shape", args.shape, "--layers", str(args.layers),
+               "--batch", str(args.batch)] + (["--no-stat-topk"] if args.no_stat_topk else [])
+        env = dict(os.environ, TMPDIR="/tmp")
+        try:
+            proc = subprocess.Popen(cmd, cwd="/tmp", env=env, stdout=subprocess.PIPE, stderr=subprocess.STDOUT,
+                                    start_new_session=True, text=True)
+            try:
+                log, _ = proc.communicate(timeout=args.traffic_timeout)
+            except subprocess.TimeoutExpired:
+                os.killpg(proc.pid, signal.SIGKILL)
+                proc.communicate()
+                return None, f"rocprofv3 --pmc {counter} did not finish within {args.traffic_timeout} s"
+            if proc.returncode != 0 or "traffic probe done" not in log:
+                return None, f"rocprofv3 --pmc {counter} failed (exit {proc.returncode}): {log[-300:]!r}"
+            rows = _counter_rows(out_dir, counter)
+        except OSError as e:
+            return None, f"could not run rocprofv3: {e}"
+        finally:
+            shutil.rmtree(out_dir, ignore_errors=True)
+        if not rows:
+            return None, f"rocprofv3 --pmc {counter} wrote no counter rows"
+        per_kernel = {}
+        for name, val in rows:
+            per_kernel.setdefault(name, []).append(val)
+        cal = [v for name, vals in per_kernel.items() if "copy_bytes_kernel" in name for v in vals]
+        if not cal or not sum(cal) > 0:
+            return None, f"the calibration copy does not appear in the {counter} run"
+        scale = CAL_COPY_BYTES / (sum(cal) / len(cal))      # bytes per counter unit
+        notes.append(f"{counter} x {scale / 1024:.3f} KiB")
+        per_counter[counter] = {name: (sum(v) / len(v) * scale, len(v)) for name, v in per_kernel.items()}
+    out = {}
+    for name, (fb, n) in per_counter["FETCH_SIZE"].items():
+        wb = per_counter["WRITE_SIZE"].get(name, (0.0, 0))[0]
+        out[name] = {"fetch_bytes": fb, "write_bytes": wb, "dispatches": n}
+    return out, ("two rocprofv3 --pmc runs of `bench.py --traffic-probe` in this run; counter units from the "
+                 f"{CAL_COPY_BYTES >> 20} MiB copy kernel: " + ", ".join(notes))
+
+
+def traffic_of(traffic, *needles):
+    """fetch + write bytes per dispatch of the one kernel whose name contains every needle (None if
+    traffic was not measured or the kernel did not run in the probe)."""
+    if not traffic:
+        return None
+    hits = [v for name, v in traffic.items() if all(n in name for n in needles)]
+    if len(hits) != 1:
+        return None
+    return hits[0]["fetch_bytes"] + hits[0]["write_bytes"]
 
 
 def algorithmic_bytes(shape, counts, wbytes):
@@ -117,12 +229,14 @@ def cpu_baseline(shape, weights_cpu, q_cpu, budget_s=12.0):
             "sample": f"{n} evaluations of layer 0 of the same stack (batch 1), {dt:.1f} s"}
 
 
-def stat_topk_bench(torch, binding, synth, dev, with_cpu):
+def stat_topk_bench(torch, binding, synth, dev, with_cpu, traffic, np):
     """Row-wise statistical top-k on the 8192 x 9216 activation matrix (k = 737), bf16 and fp32:
-    one read and one write of the tensor are the algorithmic bytes."""
+    one read and one write of the tensor are the algorithmic bytes.  With the oracle at hand, the
+    active sets of a row sample are compared with exact sort-based top-k on the same rows (Section 3's
+    cost argument: 2d flops for the statistics against a sort), and both are timed on the host."""
     rows, n, k = 8192, 9216, 737
     out = {"workload": f"rows={rows} n={n} k={k}, rows N(mu_i, sigma_i^2) with 1% Student-t3 outliers"}
-    for name, dt, w in (("bf16", torch.bfloat16, 2), ("f32", torch.float32, 4)):
+    for name, dt, w, tname in (("bf16", torch.bfloat16, 2, "spark::bf16_t"), ("f32", torch.float32, 4, "float")):
         x = synth.topk_rows(rows, n, seed=4242, dtype=dt, device=dev)
         y = torch.empty_like(x)
         theta = torch.empty(rows, device=dev)
@@ -134,14 +248,15 @@ def stat_topk_bench(torch, binding, synth, dev, with_cpu):
         gpu_s, _ = time_region(step, 50, 5, torch)
         avg_s, _ = sampled_launch_time(step, 20, torch)
         nbytes = 2.0 * rows * n * w + 8.0 * rows
+        cnt = count.cpu().numpy()
         out[name] = {"rows_per_s": rows * 50 / gpu_s, "us_per_call": gpu_s / 50 * 1e6,
                      "roofline": {"bound": "hbm", "achieved": nbytes / avg_s / 1e9, "peak": HBM_PEAK_GBS,
                                   "unit": "GB/s", "frac": nbytes / avg_s / 1e9 / HBM_PEAK_GBS,
-                                  "traffic": STAT_TOPK_TRAFFIC_BYTES.get((name, "forward")),
+                                  "traffic": traffic_of(traffic, "stat_topk_cached_kernel<" + tname),
                                   "kernel": "stat_topk_cached_kernel", "bytes_per_launch": nbytes,
                                   "launch_us": avg_s * 1e6},
-                     "count_mean": float(count.float().mean()), "count_min": int(count.min()),
-                     "count_max": int(count.max())}
+                     "count_mean": float(cnt.mean()), "count_std": float(cnt.std()), "count_min": int(cnt.min()),
+                     "count_max": int(cnt.max())}
         # backward pass of the Huber-smoothed operator (gradient through theta): x and gy read
         # once, gx written once
         gy = synth.grad_rows(rows, n, seed=4243, dtype=dt, device=dev)
@@ -154,22 +269,60 @@ def stat_topk_bench(torch, binding, synth, dev, with_cpu):
         out[name]["backward"] = {"us_per_call": bavg_s * 1e6, "rows_per_s": rows / bavg_s, "delta": 0.25,
                                  "roofline": {"bound": "hbm", "achieved": bbytes / bavg_s / 1e9, "peak": HBM_PEAK_GBS,
                                               "unit": "GB/s", "frac": bbytes / bavg_s / 1e9 / HBM_PEAK_GBS,
-                                              "traffic": STAT_TOPK_TRAFFIC_BYTES.get((name, "backward")),
+                                              "traffic": traffic_of(traffic, "stat_topk_vjp_cached_kernel<" + tname),
                                               "kernel": "stat_topk_vjp_cached_kernel",
                                               "bytes_per_launch": bbytes, "launch_us": bavg_s * 1e6}}
         del gy
+        if with_cpu:
+            import oracle
+            # the GPU's active sets of the first `sample` rows against exact sort-based top-k of the
+            # same rows (oracle): precision |I n T_k| / |I|, recall |I n T_k| / k, and nesting (a
+            # threshold set is the exact top-|I| set, so it contains T_k or is contained in it)
+            sample, cap = 1024, 2048
+            idx = torch.full((sample, cap), -1, dtype=torch.int32, device=dev)
+            binding.spark_stat_topk(x[:sample], k, count=count[:sample], idx=idx)
+            torch.cuda.synchronize()
+            xs = synth.to_oracle(x[:sample]).astype(np.float64)
+            gi, gc = idx.cpu().numpy(), count[:sample].cpu().numpy().astype(np.int64)
+            t0 = time.perf_counter()
+            tk = oracle.exact_topk_rows(xs, k)
+            t_exact = time.perf_counter() - t0
+            t0 = time.perf_counter()
+            ref = oracle.stat_topk_rows(xs, k, want_y=True, want_idx=True)
+            t_stat = time.perf_counter() - t0
+            in_tk = np.zeros((sample, n), bool)
+            in_tk[np.arange(sample)[:, None], tk] = True
+            valid = np.arange(cap)[None, :] < gc[:, None]
+            hit = np.zeros((sample, cap), bool)
+            hit[valid] = in_tk[np.broadcast_to(np.arange(sample)[:, None], gi.shape)[valid], gi[valid]]
+            inter = hit.sum(1)
+            out[name]["vs_exact_topk"] = {
+                "rows": sample, "precision_mean": float((inter / np.maximum(gc, 1)).mean()),
+                "recall_mean": float((inter / k).mean()), "recall_min": float((inter / k).min()),
+                "nested_rows": int((inter == np.minimum(gc, k)).sum()),
+                "count_equals_oracle_rows": int((gc == ref.count).sum()),
+                "oracle_exact_topk_rows_per_s": sample / t_exact, "oracle_stat_topk_rows_per_s": sample / t_stat,
+                "cores": oracle.max_threads()}
+            del idx
         if with_cpu and name == "f32":
             import oracle
             sample = 512
             xs = synth.to_oracle(x[:sample])
             t0 = time.perf_counter()
             reps = 0
-            while time.perf_counter() - t0 < 4.0:
+            while time.perf_counter() - t0 < 3.0:
                 oracle.stat_topk_rows(xs, k)
                 reps += 1
             dt_s = time.perf_counter() - t0
+            t0, ereps = time.perf_counter(), 0
+            while time.perf_counter() - t0 < 3.0:
+                oracle.exact_topk_rows(xs, k)
+                ereps += 1
+            et_s = time.perf_counter() - t0
             out["cpu_baseline"] = {"value": sample * reps / dt_s, "unit": "rows/s", "cores": oracle.max_threads(),
-                                   "kind": "oracle", "sample": f"{reps} passes over the first {sample} rows (fp32), {dt_s:.1f} s"}
+                                   "kind": "oracle", "sample": f"{reps} passes over the first {sample} rows (fp32), {dt_s:.1f} s",
+                                   "exact_sort_topk_rows_per_s": sample * ereps / et_s,
+                                   "exact_sort_topk_sample": f"{ereps} passes of the sort-based exact top-k over the same rows, {et_s:.1f} s"}
         del x, y
     return out
 
@@ -182,7 +335,7 @@ def time_config(torch, binding, shape, layers, q, dev, steps=20):
     y = torch.empty(L, B, shape.d_model, device=dev)
     ucnt = torch.zeros(L, dtype=torch.int32, device=dev)
     binding.spark_ffn_decode_layers(layers, q, y, ws, union_count=ucnt)
-    binding.spark_ffn_check(ws, shape.d_model, shape.d_ff, B)
+    torch.cuda.synchronize()
     union = ucnt.cpu().numpy()
     nbytes = float(sum(algorithmic_bytes(shape, [int(m) for m in union], 2)))
     gpu_s, _ = time_region(lambda: binding.spark_ffn_decode_layers(layers, q, y, ws), steps, 3, torch)
@@ -195,8 +348,8 @@ def time_config(torch, binding, shape, layers, q, dev, steps=20):
 
 
 def other_configs(torch, binding, synth, dev, main_shape, L, weights, layers):
-    """The batched decode configurations on the same stack, and the Gemma-2-9B-shaped stack at
-    batch 1 and 8 (42 layers, 12.95 GB of weights)."""
+    """The batched decode configurations on the same stack, the Gemma-2-9B-shaped stack at batch 1
+    and 8 (42 layers, 8.6 GB of weights), and 26 layers of the paper's own layer shape at batch 1."""
     res = []
     shape = synth.SHAPES[main_shape]
     for B in (4, 16, 64):
@@ -210,6 +363,13 @@ def other_configs(torch, binding, synth, dev, main_shape, L, weights, layers):
             q = synth.tokens(shape9, B, 2000 + B, dtype=torch.bfloat16, device=dev)
             res.append(time_config(torch, binding, shape9, l9, q, dev))
         del w9, l9
+        torch.cuda.empty_cache()
+        # the layer the paper itself trains (Section 4.1: d_ff 13824, k 1106, r 1024), 26 of them
+        shp = synth.SHAPES["spark-paper-2b"]
+        wp = synth.ffn_stack(shp, 26, base_seed=1000, dtype=torch.bfloat16, device=dev)
+        lp = [binding.make_layer(w[0], w[1], w[2], shp.k) for w in wp]
+        res.append(time_config(torch, binding, shp, lp, synth.tokens(shp, 1, 2001, dtype=torch.bfloat16, device=dev), dev))
+        del wp, lp
         torch.cuda.empty_cache()
     return res
 
@@ -321,7 +481,7 @@ def fp8_bench(torch, binding, synth, dev, np, kind="fp8"):
     y = torch.empty(L, 1, sh.d_model, device=dev)
     cnt = torch.zeros(L, 1, dtype=torch.int32, device=dev)
     binding.spark_ffn_decode_layers(layers, q, y, ws, active_count=cnt)
-    binding.spark_ffn_check(ws, sh.d_model, sh.d_ff, 1)
+    torch.cuda.synchronize()
     m = cnt.cpu().numpy().astype(np.float64)[:, 0]
 
     def step():
@@ -337,6 +497,23 @@ def fp8_bench(torch, binding, synth, dev, np, kind="fp8"):
             "hbm_frac": nbytes / per / 1e9 / HBM_PEAK_GBS}
 
 
+def master_weight_error(torch, binding, synth, dev, shape, q, y0, cnt0, idx0):
+    """Reported, not gated: layer 0 of the stack as the kernels evaluate it (bf16-rounded weights) against
+    the oracle on the unrounded fp32 master weights of the same seed (what rounding the weights costs)."""
+    import numpy as np
+
+    import oracle
+
+    master = synth.ffn_layer(shape, 1000, torch.float32, dev)      # the stack's layer 0 before rounding
+    o = oracle.spark_ffn(*(synth.to_oracle(t) for t in master), synth.to_oracle(q)[0], shape.k, skip_inactive=True)
+    yg = y0.cpu().numpy().astype(np.float64)
+    gset = set(int(i) for i in idx0[:int(cnt0)].cpu().numpy())
+    oset = set(int(i) for i in o.idx)
+    return {"rel_l2_y_vs_oracle_on_fp32_master_weights": float(np.linalg.norm(yg - o.y) / np.linalg.norm(o.y)),
+            "active_set_symmetric_difference": len(gset ^ oset), "active_count_oracle_master": int(o.count),
+            "layer": 0}
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -350,13 +527,25 @@ def main():
     ap.add_argument("--no-stat-topk", action="store_true")
     ap.add_argument("--no-attention", action="store_true")
     ap.add_argument("--no-extra", action="store_true",
-                    help="skip the single-layer-call timing and the batched / 9B-shaped configurations")
-    ap.add_argument("--calibrate-copy", action="store_true",
-                    help="also run three plain 1 GiB device copies (the known-size reference for the "
-                         "FETCH_SIZE / WRITE_SIZE counters)")
+                    help="skip the single-layer-call timing and the batched / 9B-shaped / paper-shaped configurations")
+    ap.add_argument("--no-traffic", action="store_true",
+                    help="do not start the two rocprofv3 --pmc child runs that measure HBM traffic")
+    ap.add_argument("--traffic-timeout", type=int, default=240, help="seconds allowed per counter run")
+    ap.add_argument("--traffic-probe", action="store_true", help=argparse.SUPPRESS)
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on one GPU only (no collectives, no sharding); use --gpus 1")
+    if args.traffic_probe:
+        return traffic_probe(args)
+
+    # HBM traffic first: the counter runs are child processes, started before this process
+    # initialises the GPU
+    if args.no_traffic:
+        traffic, traffic_note = None, "not measured (--no-traffic)"
+    elif args.batch != 1:
+        traffic, traffic_note = None, "measured for the batch-1 workload only"
+    else:
+        traffic, traffic_note = measure_traffic(args)
 
     import numpy as np
     import torch
@@ -378,14 +567,15 @@ def main():
     y = torch.empty(L, B, shape.d_model, device=dev)
     cnt = torch.zeros(L, B, dtype=torch.int32, device=dev)
     ucnt = torch.zeros(L, dtype=torch.int32, device=dev)
+    idx0 = torch.full((1, B, shape.d_ff), -1, dtype=torch.int32, device=dev)
 
     def step():
         # the product call of a decoder: y only (the index lists and counts are optional outputs)
         binding.spark_ffn_decode_layers(layers, q, y, ws)
 
-    # one untimed call that also returns the active counts, for the byte accounting
+    # untimed calls that also return the active counts (for the byte accounting) and layer 0's set
     binding.spark_ffn_decode_layers(layers, q, y, ws, active_count=cnt, union_count=ucnt)
-    binding.spark_ffn_check(ws, shape.d_model, shape.d_ff, B)
+    binding.spark_ffn_decode_layers(layers[:1], q, y[:1], ws, active_idx=idx0)
     step()
     torch.cuda.synchronize()
     counts = cnt.cpu().numpy()
@@ -401,47 +591,59 @@ def main():
     bytes_step = float(sum(per_layer))
     call_avg_s, call_med_s = sampled_launch_time(step, 50, torch)
     if B == 1:
-        # Each kernel of the call timed alone (the other launches switched off; their outputs of
-        # the full call above are still in the workspace): 200 back-to-back launches between
-        # two events, five times; the median of the five averages is reported as well.
+        # Each kernel of the call launched alone (the other launches switched off for that call; their
+        # outputs of the full call above are still in the workspace).  `launch_us` is the average over
+        # single launches, each between its own pair of events on the launch stream; the average of
+        # 200 back-to-back launches between one pair of events is given beside it (consecutive
+        # launches overlap their ramp and tail, so it is a little shorter).
         k1_bytes = 2.0 * shape.d_ff * shape.r * L
         kernels = {}
         for name, mask, nbytes in (("predict_layers_kernel", 1, k1_bytes),
                                    ("gather_layers_kernel", 2, bytes_step - k1_bytes),
                                    ("gather+reduce", 6, None)):
-            binding.spark_debug_phases(mask)
+            tune = binding.Tuning(phases=mask)
+
+            def one():
+                binding.spark_ffn_decode_layers_tuned(layers, q, y, ws, tune)
+
             for _ in range(5):
-                step()
-            runs = sorted(back_to_back_time(step, 200, torch) for _ in range(5))
-            avg_s, med_s = sum(runs) / len(runs), runs[len(runs) // 2]
-            kernels[name] = {"launch_us": avg_s * 1e6, "launch_us_median": med_s * 1e6}
+                one()
+            avg_s, med_s = sampled_launch_time(one, 100, torch)
+            b2b = sorted(back_to_back_time(one, 200, torch) for _ in range(3))[1]
+            kernels[name] = {"launch_us": avg_s * 1e6, "launch_us_median": med_s * 1e6,
+                             "launch_us_back_to_back": b2b * 1e6}
             if nbytes:
                 kernels[name].update(bytes_per_launch=nbytes, achieved=nbytes / avg_s / 1e9,
                                      frac=nbytes / avg_s / 1e9 / HBM_PEAK_GBS)
-        binding.spark_debug_phases(0)
         # the reduce kernel alone is shorter than the host's launch interval: back-to-back launches
         # of it would time the host, so it is timed behind the gather and the gather subtracted
         both = kernels.pop("gather+reduce")
         kernels["reduce_layers_kernel"] = {
-            k: both[k] - kernels["gather_layers_kernel"][k] for k in ("launch_us", "launch_us_median")}
+            k: both[k] - kernels["gather_layers_kernel"][k] for k in ("launch_us", "launch_us_median", "launch_us_back_to_back")}
         kernels["reduce_layers_kernel"]["timed_as"] = "gather + reduce launches minus gather alone"
+        step()
+        torch.cuda.synchronize()
         dom = kernels["predict_layers_kernel"]
-        traffic = MEASURED_TRAFFIC_BYTES.get((args.shape, L, B))
         roofline = {"bound": "hbm", "achieved": dom["achieved"], "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                    "frac": dom["frac"], "traffic": traffic["predict_layers_kernel"] if traffic else None,
+                    "frac": dom["frac"], "traffic": traffic_of(traffic, "predict_layers_kernel"),
+                    "traffic_note": traffic_note,
                     "kernel": "predict_layers_kernel (the predictor sweep over all K1n of the call: the dominant "
                               "kernel, %d layers per launch)" % L,
                     "bytes_per_launch": dom["bytes_per_launch"], "launch_us": dom["launch_us"],
                     "launch_us_median": dom["launch_us_median"],
-                    "other_kernels": {k: dict(v, traffic=(traffic or {}).get(k)) for k, v in kernels.items()
+                    "launch_us_back_to_back": dom["launch_us_back_to_back"],
+                    "other_kernels": {k: dict(v, traffic=traffic_of(traffic, k)) for k, v in kernels.items()
                                       if k != "predict_layers_kernel"},
                     "whole_call": {"bytes": bytes_step, "call_us": call_avg_s * 1e6,
                                    "call_us_median": call_med_s * 1e6, "achieved": bytes_step / call_avg_s / 1e9,
-                                   "frac": bytes_step / call_avg_s / 1e9 / HBM_PEAK_GBS}}
+                                   "frac": bytes_step / call_avg_s / 1e9 / HBM_PEAK_GBS,
+                                   "traffic": (None if traffic is None else sum(
+                                       traffic_of(traffic, k) or 0.0 for k in
+                                       ("predict_layers_kernel", "gather_layers_kernel", "reduce_layers_kernel")))}}
     else:
         achieved = bytes_step / call_avg_s / 1e9
         roofline = {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                    "frac": achieved / HBM_PEAK_GBS, "traffic": None,
+                    "frac": achieved / HBM_PEAK_GBS, "traffic": None, "traffic_note": traffic_note,
                     "kernel": "whole spark_ffn_decode_layers call (several kernels per layer)",
                     "bytes_per_launch": bytes_step, "launch_us": call_avg_s * 1e6,
                     "launch_us_median": call_med_s * 1e6}
@@ -476,20 +678,13 @@ def main():
         d_s, _ = time_region(dense_step, dsteps, 3, torch)
         dense_bytes = 2.0 * shape.d_ff * 2 * shape.d_model
         out["dense"] = {"layers_per_s": L * dsteps / d_s, "us_per_layer": d_s / dsteps / L * 1e6,
+                        "bytes_per_layer": dense_bytes,
                         "achieved_gbs": dense_bytes * L * dsteps / d_s / 1e9,
                         "hbm_frac": dense_bytes * L * dsteps / d_s / 1e9 / HBM_PEAK_GBS,
                         "speedup_sparse_over_dense": (layers_per_s) / (L * dsteps / d_s)}
         err = (yd - y).norm() / y.norm()
         out["dense"]["rel_l2_vs_sparse"] = float(err)
-
-    if args.calibrate_copy:
-        src = torch.full((1 << 30,), 7, dtype=torch.uint8, device=dev)
-        dst = torch.empty_like(src)
-        for _ in range(3):
-            dst.copy_(src)
-        torch.cuda.synchronize()
-        out["calibration_copy_bytes"] = 1 << 30
-        del src, dst
+        del yd
 
     if B == 1 and not args.no_extra:
         # the same stack called one layer at a time (what a decoder whose layers feed each other
@@ -498,15 +693,21 @@ def main():
             for l in range(L):
                 binding.spark_ffn_decode(layers[l], q, y[l], ws)
 
-        c_s, _ = time_region(chain_step, max(5, args.steps // 20), 2, torch)
-        out["single_layer_calls"] = {"us_per_layer": c_s / max(5, args.steps // 20) / L * 1e6,
-                                     "hbm_frac": bytes_step / L / (c_s / max(5, args.steps // 20) / L) / 1e9 / HBM_PEAK_GBS}
+        csteps = max(5, args.steps // 20)
+        c_s, _ = time_region(chain_step, csteps, 2, torch)
+        out["single_layer_calls"] = {"us_per_layer": c_s / csteps / L * 1e6,
+                                     "hbm_frac": bytes_step / L / (c_s / csteps / L) / 1e9 / HBM_PEAK_GBS}
+        step()
+        torch.cuda.synchronize()
+
+    if B == 1 and not args.no_cpu_baseline and args.shape in ("gemma2-2b", "gemma2-9b", "spark-paper-2b", "tiny"):
+        out["master_weights"] = master_weight_error(torch, binding, synth, dev, shape, q, y[0, 0], cnt[0, 0], idx0[0, 0])
 
     if not args.no_extra:
         out["other_configs"] = other_configs(torch, binding, synth, dev, args.shape, L, weights, layers)
 
     if not args.no_stat_topk:
-        out["stat_topk"] = stat_topk_bench(torch, binding, synth, dev, not args.no_cpu_baseline)
+        out["stat_topk"] = stat_topk_bench(torch, binding, synth, dev, not args.no_cpu_baseline, traffic, np)
 
     if not args.no_extra:
         out["prefill"] = prefill_bench(torch, binding, synth, dev, np)

@@ -16,8 +16,9 @@
  *   - All array arguments are DEVICE pointers (HIP global memory of the current device)
  *     unless the comment says "host".  The library never allocates or frees device memory:
  *     every buffer, including the workspace, is owned by the caller, and the workspace needs
- *     no initialisation.  The only state kept between calls is the spark_debug_* switches
- *     and a launch counter of the alternative persistent kernel they can select.
+ *     no initialisation.  No state is kept between calls: nothing a call does depends on an
+ *     earlier call, and calls from several threads (on their own streams and workspaces) do
+ *     not interact.
  *   - Calls enqueue work on `hip_stream` (a hipStream_t passed as void*; NULL = the default
  *     stream) and return without synchronising.  Outputs are valid once the stream has
  *     been synchronised by the caller.  Two calls that share a workspace must be ordered
@@ -94,6 +95,10 @@ double spark_normal_quantile(double p);
  * Needs no workspace.  Errors: NULL x; rows < 0, n < 2, n > 2^31-1 or a pitch < n -> SHAPE;
  * k out of range -> K; dt -> DTYPE; alignment -> ALIGN.
  */
+/* Host. Bytes of device workspace spark_stat_topk needs: always 0 (a row stays on chip between
+ * its statistics and its thresholding). */
+size_t spark_stat_topk_workspace_bytes(int64_t rows, int64_t n);
+
 spark_status spark_stat_topk(const void* x, spark_dtype dt, int64_t rows, int64_t n, int64_t ldx,
                              int64_t k, spark_fill fill, void* y, int64_t ldy, float* theta,
                              int32_t* count, int32_t* idx, int64_t idx_cap, void* hip_stream);
@@ -296,43 +301,44 @@ spark_status spark_attn_decode(const spark_attn_head* heads, int32_t n_heads, co
                                int32_t* kept_idx, void* workspace, size_t workspace_bytes,
                                void* hip_stream);
 
-/*
- * Host, synchronising.  The default paths launch ordinary kernels that wait for nothing and
- * cannot give up: for them this call only synchronises and returns SPARK_OK.  The alternative
- * batch-1 path selected with spark_debug_force_general(2) is one persistent launch whose
- * wavefronts wait on each other; every such wait is bounded, and a launch that had to give
- * up (for instance because another process held part of the GPU) leaves a non-zero status
- * word in the workspace instead of results.  This call waits for `hip_stream`, reads that
- * word and returns SPARK_ERR_DEVICE if the last decode on this workspace aborted, SPARK_OK
- * otherwise.  Arguments as for spark_ffn_workspace_bytes.
+/* ------------------------------------------------------------------------------------------
+ * Testing and measurement aids.
  */
-spark_status spark_ffn_check(const void* workspace, int32_t d_model, int32_t d_ff, int32_t batch,
-                             void* hip_stream);
 
-/* Host.  Testing aid (process-wide): 0 = automatic choice of the batch-1 path (phase by
- * phase over the layers of a call), 1 = general multi-kernel path, 2 = persistent launch. */
-void spark_debug_force_general(int on);
+/* Host struct.  Choices a caller may pin for one spark_ffn_decode_layers_tuned call instead of
+ * leaving them to the library; every field 0 = automatic.  Results do not depend on them beyond
+ * the order of fp32 additions. */
+typedef struct {
+  int32_t path;                     /* 1 = the general multi-kernel path even where a phase-by-phase
+                                       path exists (8-bit weights have no general path: ignored)    */
+  int32_t phases;                   /* one-token path: which launches the call makes: bit 0 the
+                                       predictor sweep, bit 1 the gather, bit 2 the reduction (and the
+                                       index lists).  A call that skips a launch finds that launch's
+                                       outputs as an earlier full call on the same workspace left
+                                       them, so each kernel can be timed alone on valid inputs       */
+  int32_t rows_per_predict_block;   /* one token: rows per workgroup of the predictor sweep; batches:
+                                       16 x the tiles per workgroup of the predict step              */
+  int32_t neurons_per_gather_block; /* one token: neurons per workgroup of the gather; batches: 16 x
+                                       the tiles per workgroup of the k2 step                        */
+  int32_t variant;                  /* one token: 1 = the 8-wave gather variant; batches: row slices
+                                       of the V step, plus 100 to keep the k-split kernels for every
+                                       batch size, plus 200 to take the streamed kernels (at most 16
+                                       tokens) however small the launch                              */
+} spark_ffn_tuning;
 
-/* Host.  Measurement aid (process-wide): which launches of the batch-1 path a call makes: bit 0
- * the predictor sweep, bit 1 the gather, bit 2 the reduction (and the index lists); 0 = all.
- * A call that skips a launch leaves that launch's outputs as an earlier full call on the same
- * workspace wrote them, so each kernel can be timed alone on valid inputs. */
-void spark_debug_phases(int mask);
+/* spark_ffn_decode_layers with pinned choices (`tuning` is a host pointer, NULL = automatic). */
+spark_status spark_ffn_decode_layers_tuned(const spark_ffn_layer* layers, int32_t n_layers,
+                                           const void* q, spark_dtype qdtype, int32_t batch,
+                                           int64_t ldq, float* y, float* theta, int32_t* active_count,
+                                           int32_t* active_idx, int32_t* union_count,
+                                           int32_t* union_idx, void* workspace,
+                                           size_t workspace_bytes, const spark_ffn_tuning* tuning,
+                                           void* hip_stream);
 
-/* Host.  Testing / tuning aid (process-wide): rows per workgroup of the predictor sweep and
- * neurons per workgroup of the gather of the batch-1 path; 0 = automatic.  `alt`: batch 1: 1
- * selects the 8-wave gather variant; batches: row slices of the V step (0 = automatic), plus
- * 100 to keep the k-split kernels for every batch size, plus 200 to take the streamed kernels
- * (at most 16 tokens) however small the launch.  For batches the first two arguments, divided
- * by 16, set the tiles per workgroup of the predict and k2 steps. */
-void spark_debug_tuning(int rows_per_predict_block, int neurons_per_gather_block, int alt);
-
-/* Host.  Testing aid: with profiling on, every wavefront of the persistent launch records
- * how long it lived and how long it spent in each of its waits (100 MHz ticks);
- * spark_debug_read_profile synchronises and copies out [256 workgroups][16 waves][8] words. */
-void spark_debug_profile(int on);
-spark_status spark_debug_read_profile(const void* workspace, int32_t d_model, int32_t d_ff, int32_t batch,
-                                      int64_t* out, int64_t n_words, void* hip_stream);
+/* A plain device-to-device copy kernel (dst, src 16-byte aligned, nbytes a multiple of 16; the
+ * ranges must not overlap): it reads exactly nbytes and writes exactly nbytes, which makes it the
+ * known-size reference the HBM byte counters are scaled by when kernel traffic is measured. */
+spark_status spark_copy_bytes(void* dst, const void* src, size_t nbytes, void* hip_stream);
 
 #ifdef __cplusplus
 }

@@ -9,8 +9,6 @@ from .binding import (  # noqa: F401
     ffn_workspace_bytes,
     load_library,
     normal_quantile,
-    spark_debug_force_general,
-    spark_ffn_check,
     spark_ffn_decode,
     spark_ffn_decode_layers,
     spark_ffn_dense_decode,

@@ -25,10 +25,10 @@ EXPORTS = (
     "spark_status_string", "spark_version", "spark_normal_quantile", "spark_stat_topk",
     "spark_stat_topk_huber", "spark_stat_topk_huber_backward",
     "spark_ffn_workspace_bytes", "spark_ffn_decode", "spark_ffn_decode_layers",
-    "spark_ffn_dense_decode", "spark_ffn_dense_decode_layers", "spark_ffn_check",
+    "spark_ffn_dense_decode", "spark_ffn_dense_decode_layers",
     "spark_ffn_prefill_workspace_bytes", "spark_ffn_prefill",
-    "spark_attn_workspace_bytes", "spark_attn_decode", "spark_debug_force_general", "spark_debug_tuning", "spark_debug_phases",
-    "spark_debug_profile", "spark_debug_read_profile",
+    "spark_attn_workspace_bytes", "spark_attn_decode", "spark_stat_topk_workspace_bytes",
+    "spark_ffn_decode_layers_tuned", "spark_copy_bytes",
 )
 
 
@@ -51,6 +51,14 @@ class _AttnHead(ctypes.Structure):
         ("n_ctx", ctypes.c_int32), ("d_attn", ctypes.c_int32), ("r", ctypes.c_int32),
         ("k", ctypes.c_int32), ("cdtype", ctypes.c_int32), ("group", ctypes.c_int32),
         ("k1c", ctypes.c_void_p), ("k2c", ctypes.c_void_p), ("vc", ctypes.c_void_p),
+    ]
+
+
+class Tuning(ctypes.Structure):
+    """``spark_ffn_tuning``: choices pinned for one ``spark_ffn_decode_layers_tuned`` call (0 = automatic)."""
+    _fields_ = [
+        ("path", ctypes.c_int32), ("phases", ctypes.c_int32), ("rows_per_predict_block", ctypes.c_int32),
+        ("neurons_per_gather_block", ctypes.c_int32), ("variant", ctypes.c_int32),
     ]
 
 
@@ -100,18 +108,13 @@ def load_library():
     lib.spark_attn_decode.argtypes = [ctypes.POINTER(_AttnHead), i32, vp, c_int, vp, vp, vp, vp, vp, sz, vp]
     lib.spark_ffn_dense_decode_layers.restype = c_int
     lib.spark_ffn_dense_decode_layers.argtypes = [ctypes.POINTER(_Layer), i32, vp, c_int, i32, i64, vp, vp, sz, vp]
-    lib.spark_ffn_check.restype = c_int
-    lib.spark_ffn_check.argtypes = [vp, i32, i32, i32, vp]
-    lib.spark_debug_profile.restype = None
-    lib.spark_debug_profile.argtypes = [c_int]
-    lib.spark_debug_read_profile.restype = c_int
-    lib.spark_debug_read_profile.argtypes = [vp, i32, i32, i32, vp, i64, vp]
-    lib.spark_debug_force_general.restype = None
-    lib.spark_debug_force_general.argtypes = [c_int]
-    lib.spark_debug_phases.restype = None
-    lib.spark_debug_phases.argtypes = [c_int]
-    lib.spark_debug_tuning.restype = None
-    lib.spark_debug_tuning.argtypes = [c_int, c_int, c_int]
+    lib.spark_stat_topk_workspace_bytes.restype = sz
+    lib.spark_stat_topk_workspace_bytes.argtypes = [i64, i64]
+    lib.spark_ffn_decode_layers_tuned.restype = c_int
+    lib.spark_ffn_decode_layers_tuned.argtypes = [ctypes.POINTER(_Layer), i32, vp, c_int, i32, i64, vp, vp, vp,
+                                                  vp, vp, vp, vp, sz, ctypes.POINTER(Tuning), vp]
+    lib.spark_copy_bytes.restype = c_int
+    lib.spark_copy_bytes.argtypes = [vp, vp, sz, vp]
     _lib = lib
     return lib
 
@@ -217,6 +220,30 @@ def spark_ffn_decode_layers(layers: Sequence[_Layer], q: torch.Tensor, y: torch.
     _check(rc, "spark_ffn_decode_layers")
 
 
+def spark_ffn_decode_layers_tuned(layers: Sequence[_Layer], q: torch.Tensor, y: torch.Tensor,
+                                  workspace: torch.Tensor, tuning: Optional[Tuning], theta=None, active_count=None,
+                                  active_idx=None, union_count=None, union_idx=None):
+    """:func:`spark_ffn_decode_layers` with the choices of ``tuning`` pinned (``None`` = automatic)."""
+    arr = (_Layer * len(layers))(*layers)
+    rc = load_library().spark_ffn_decode_layers_tuned(
+        arr, len(layers), _p(q), _dt(q), q.shape[0], q.stride(0), _p(y), _p(theta), _p(active_count),
+        _p(active_idx), _p(union_count), _p(union_idx), _p(workspace), workspace.numel(),
+        None if tuning is None else ctypes.byref(tuning), _stream())
+    _check(rc, "spark_ffn_decode_layers_tuned")
+
+
+def stat_topk_workspace_bytes(rows: int, n: int) -> int:
+    return int(load_library().spark_stat_topk_workspace_bytes(int(rows), int(n)))
+
+
+def spark_copy_bytes(dst: torch.Tensor, src: torch.Tensor):
+    """Plain device copy of ``src`` into ``dst`` (same byte size) by the library's reference copy kernel."""
+    n = src.numel() * src.element_size()
+    if dst.numel() * dst.element_size() != n:
+        raise ValueError("dst and src must have the same size in bytes")
+    _check(load_library().spark_copy_bytes(_p(dst), _p(src), n, _stream()), "spark_copy_bytes")
+
+
 def pack_fp8_rows(codes: torch.Tensor, scales: torch.Tensor) -> torch.Tensor:
     """One 8-bit weight array as the library reads it: the codes ``[rows, cols]`` (E4M3 or int8 bytes, as uint8) followed
     by one fp32 scale per row, in one allocation (returned as a flat uint8 tensor)."""
@@ -301,37 +328,3 @@ def spark_attn_decode(heads: Sequence[_AttnHead], q: torch.Tensor, y: torch.Tens
     rc = load_library().spark_attn_decode(arr, len(heads), _p(q), _dt(q), _p(y), _p(theta), _p(kept_count),
                                           _p(kept_idx), _p(workspace), workspace.numel(), _stream())
     _check(rc, "spark_attn_decode")
-
-
-def spark_ffn_check(workspace: torch.Tensor, d_model: int, d_ff: int, batch: int):
-    """Waits for the current stream and raises if the last batch-1 decode on ``workspace`` aborted."""
-    rc = load_library().spark_ffn_check(_p(workspace), int(d_model), int(d_ff), int(batch), _stream())
-    _check(rc, "spark_ffn_check")
-
-
-def spark_debug_force_general(on):
-    """False / 0: automatic path, True / 1: general multi-kernel path, 2: persistent launch."""
-    load_library().spark_debug_force_general(int(on))
-
-
-def spark_debug_phases(mask: int = 0):
-    load_library().spark_debug_phases(int(mask))
-
-
-def spark_debug_tuning(rows_per_predict_block: int = 0, neurons_per_gather_block: int = 0, alt: int = 0):
-    load_library().spark_debug_tuning(int(rows_per_predict_block), int(neurons_per_gather_block), int(alt))
-
-
-def spark_debug_profile(on: bool):
-    load_library().spark_debug_profile(1 if on else 0)
-
-
-def spark_debug_read_profile(workspace: torch.Tensor, d_model: int, d_ff: int, batch: int):
-    """[256, 16, 8] int64 tick counters of the last profiled persistent launch."""
-    import numpy as np
-
-    out = np.zeros((256, 16, 8), np.int64)
-    rc = load_library().spark_debug_read_profile(_p(workspace), int(d_model), int(d_ff), int(batch),
-                                                 out.ctypes.data_as(ctypes.c_void_p), out.size, _stream())
-    _check(rc, "spark_debug_read_profile")
-    return out

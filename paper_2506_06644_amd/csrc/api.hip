@@ -34,8 +34,9 @@ spark::FfnProblem make_problem(const spark_ffn_layer* L, const void* q, int qdty
                                float* y, float* theta, int32_t* active_count, int32_t* active_idx,
                                int32_t* union_count, int32_t* union_idx);
 
-spark_status validate_decode(const spark_ffn_layer* L, const void* q, int qdtype, int32_t batch, int64_t ldq,
-                             const float* y, const void* workspace, size_t workspace_bytes) {
+// Everything about a decode call but its workspace.
+spark_status validate_decode_args(const spark_ffn_layer* L, const void* q, int qdtype, int32_t batch, int64_t ldq,
+                                  const float* y) {
   spark_status s = validate_layer(L);
   if (s != SPARK_OK) return s;
   if (!q || !y) return SPARK_ERR_NULL;
@@ -45,6 +46,13 @@ spark_status validate_decode(const spark_ffn_layer* L, const void* q, int qdtype
   const size_t qs = dtype_size(qdtype);
   // the split point r and every token row must fall on a 16-byte boundary of q as well
   if (!aligned16(q) || (ldq * qs) % 16 || (L->r * qs) % 16 || (L->d_model * qs) % 16) return SPARK_ERR_ALIGN;
+  return SPARK_OK;
+}
+
+spark_status validate_decode(const spark_ffn_layer* L, const void* q, int qdtype, int32_t batch, int64_t ldq,
+                             const float* y, const void* workspace, size_t workspace_bytes) {
+  const spark_status s = validate_decode_args(L, q, qdtype, batch, ldq, y);
+  if (s != SPARK_OK) return s;
   if (!workspace) return SPARK_ERR_WORKSPACE;
   if (reinterpret_cast<uintptr_t>(workspace) & 255u) return SPARK_ERR_WORKSPACE;
   if (workspace_bytes < spark_ffn_workspace_bytes(L->d_model, L->d_ff, batch)) return SPARK_ERR_WORKSPACE;
@@ -84,12 +92,27 @@ spark::FfnProblem make_problem(const spark_ffn_layer* L, const void* q, int qdty
   return p;
 }
 
-int g_force_general = 0;  // 0: automatic, 1: general multi-kernel path, 2: persistent launch
+spark::FfnTuning make_tuning(const spark_ffn_tuning* t) {
+  spark::FfnTuning u;
+  if (t) {
+    u.path = t->path == 1 ? 1 : 0;
+    u.phases = t->phases;
+    u.rows_per_predict_block = t->rows_per_predict_block;
+    u.neurons_per_gather_block = t->neurons_per_gather_block;
+    u.variant = t->variant;
+  }
+  return u;
+}
 
-// Runs layers[0..n) for one token through the phase-by-phase path (persistent = false) or
-// the persistent launch.
-hipError_t run_fused(const spark_ffn_layer* layers, int32_t n_layers, const spark::FfnProblem& p0,
-                     const spark::FfnWorkspace& ws, bool persistent, hipStream_t st, int dense = 0) {
+// May this problem take a phase-by-phase path under this tuning?  (8-bit weights have no other.)
+bool takes_phased(const spark::FfnProblem& p, const spark::FfnTuning& tune) {
+  return (tune.path == 0 || p.w_fp8) && (spark::phased_supported(p) || spark::phased_batch_supported(p));
+}
+
+// Runs layers[0..n) phase by phase: the one-token path or the batched path on the matrix cores.
+// `scratch` is laid out for `layer_cap` layers per set of launches (one-token path).
+hipError_t run_phased(const spark_ffn_layer* layers, int32_t n_layers, const spark::FfnProblem& p0,
+                      const spark::FfnTuning& tune, void* scratch, int layer_cap, hipStream_t st, int dense = 0) {
   const void* k1n[256];
   const void* k2n[256];
   const void* vn[256];
@@ -108,11 +131,43 @@ hipError_t run_fused(const spark_ffn_layer* layers, int32_t n_layers, const spar
     if (p.active_idx) p.active_idx += (int64_t)base * p0.batch * p0.d_ff;
     if (p.union_count) p.union_count += base;
     if (p.union_idx) p.union_idx += (int64_t)base * p0.d_ff;
-    if (p.batch >= 2) e = spark::launch_ffn_phased_batch(p, k1n, k2n, vn, n, ws.fused, st);
-    else e = persistent ? spark::launch_ffn_fused(p, k1n, k2n, vn, n, ws.fused, st)
-                        : spark::launch_ffn_phased(p, k1n, k2n, vn, n, dense, ws.fused, st);
+    if (p.batch >= 2) e = spark::launch_ffn_phased_batch(p, k1n, k2n, vn, n, tune, scratch, st);
+    else e = spark::launch_ffn_phased(p, k1n, k2n, vn, n, dense, tune, scratch, layer_cap, st);
   }
   return e;
+}
+
+spark_status decode_layers(const spark_ffn_layer* layers, int32_t n_layers, const void* q, spark_dtype qdtype,
+                           int32_t batch, int64_t ldq, float* y, float* theta, int32_t* active_count,
+                           int32_t* active_idx, int32_t* union_count, int32_t* union_idx, void* workspace,
+                           size_t workspace_bytes, const spark::FfnTuning& tune, hipStream_t st) {
+  if (!layers) return SPARK_ERR_NULL;
+  if (n_layers < 1) return SPARK_ERR_SHAPE;
+  for (int32_t l = 0; l < n_layers; ++l) {
+    const spark_status s = validate_decode(&layers[l], q, qdtype, batch, ldq, y, workspace, workspace_bytes);
+    if (s != SPARK_OK) return s;
+    if (layers[l].d_model != layers[0].d_model || layers[l].d_ff != layers[0].d_ff ||
+        layers[l].r != layers[0].r || layers[l].k != layers[0].k || layers[l].wdtype != layers[0].wdtype ||
+        layers[l].gelu != layers[0].gelu)
+      return SPARK_ERR_SHAPE;
+  }
+  const int64_t d_model = layers[0].d_model, d_ff = layers[0].d_ff;
+  const spark::FfnWorkspace ws = spark::carve_workspace(workspace, layers[0].d_model, layers[0].d_ff, batch);
+  const spark::FfnProblem p0 = make_problem(&layers[0], q, qdtype, batch, ldq, y, theta, active_count, active_idx,
+                                            union_count, union_idx);
+  if (takes_phased(p0, tune)) {
+    const hipError_t e = run_phased(layers, n_layers, p0, tune, ws.phased, spark::kPhasedMaxLayers, st);
+    return e == hipSuccess ? SPARK_OK : SPARK_ERR_DEVICE;
+  }
+  for (int32_t l = 0; l < n_layers; ++l) {
+    const spark::FfnProblem p = make_problem(
+        &layers[l], q, qdtype, batch, ldq, y + (int64_t)l * batch * d_model,
+        theta ? theta + (int64_t)l * batch : nullptr, active_count ? active_count + (int64_t)l * batch : nullptr,
+        active_idx ? active_idx + (int64_t)l * batch * d_ff : nullptr, union_count ? union_count + l : nullptr,
+        union_idx ? union_idx + (int64_t)l * d_ff : nullptr);
+    if (spark::launch_ffn_general(p, ws, 0, st) != hipSuccess) return SPARK_ERR_DEVICE;
+  }
+  return SPARK_OK;
 }
 
 }  // namespace
@@ -223,19 +278,8 @@ spark_status spark_ffn_decode(const spark_ffn_layer* layer, const void* q, spark
                               int64_t ldq, float* y, float* theta, int32_t* active_count,
                               int32_t* active_idx, int32_t* union_count, int32_t* union_idx,
                               void* workspace, size_t workspace_bytes, void* hip_stream) {
-  const spark_status s = validate_decode(layer, q, qdtype, batch, ldq, y, workspace, workspace_bytes);
-  if (s != SPARK_OK) return s;
-  const spark::FfnProblem p = make_problem(layer, q, qdtype, batch, ldq, y, theta, active_count, active_idx,
-                                           union_count, union_idx);
-  const spark::FfnWorkspace ws = spark::carve_workspace(workspace, layer->d_model, layer->d_ff, batch);
-  hipError_t e;
-  if ((g_force_general == 0 || p.w_fp8) && (spark::phased_supported(p) || spark::phased_batch_supported(p)))
-    e = run_fused(layer, 1, p, ws, false, static_cast<hipStream_t>(hip_stream));
-  else if (g_force_general == 2 && spark::fused_supported(p, 1))
-    e = run_fused(layer, 1, p, ws, true, static_cast<hipStream_t>(hip_stream));
-  else
-    e = spark::launch_ffn_general(p, ws, 0, static_cast<hipStream_t>(hip_stream));
-  return e == hipSuccess ? SPARK_OK : SPARK_ERR_DEVICE;
+  return decode_layers(layer, layer ? 1 : 0, q, qdtype, batch, ldq, y, theta, active_count, active_idx, union_count,
+                       union_idx, workspace, workspace_bytes, spark::FfnTuning(), static_cast<hipStream_t>(hip_stream));
 }
 
 spark_status spark_ffn_decode_layers(const spark_ffn_layer* layers, int32_t n_layers, const void* q,
@@ -243,40 +287,17 @@ spark_status spark_ffn_decode_layers(const spark_ffn_layer* layers, int32_t n_la
                                      int32_t* active_count, int32_t* active_idx, int32_t* union_count,
                                      int32_t* union_idx, void* workspace, size_t workspace_bytes,
                                      void* hip_stream) {
-  if (!layers) return SPARK_ERR_NULL;
-  if (n_layers < 1) return SPARK_ERR_SHAPE;
-  for (int32_t l = 0; l < n_layers; ++l) {
-    const spark_status s = validate_decode(&layers[l], q, qdtype, batch, ldq, y, workspace, workspace_bytes);
-    if (s != SPARK_OK) return s;
-    if (layers[l].d_model != layers[0].d_model || layers[l].d_ff != layers[0].d_ff ||
-        layers[l].r != layers[0].r || layers[l].k != layers[0].k || layers[l].wdtype != layers[0].wdtype ||
-        layers[l].gelu != layers[0].gelu)
-      return SPARK_ERR_SHAPE;
-  }
-  const int64_t d_model = layers[0].d_model, d_ff = layers[0].d_ff;
-  const spark::FfnWorkspace ws = spark::carve_workspace(workspace, layers[0].d_model, layers[0].d_ff, batch);
-  {
-    const spark::FfnProblem p0 = make_problem(&layers[0], q, qdtype, batch, ldq, y, theta, active_count,
-                                              active_idx, union_count, union_idx);
-    if ((g_force_general == 0 || p0.w_fp8) && (spark::phased_supported(p0) || spark::phased_batch_supported(p0))) {
-      const hipError_t e = run_fused(layers, n_layers, p0, ws, false, static_cast<hipStream_t>(hip_stream));
-      return e == hipSuccess ? SPARK_OK : SPARK_ERR_DEVICE;
-    }
-    if (g_force_general == 2 && spark::fused_supported(p0, n_layers)) {
-      const hipError_t e = run_fused(layers, n_layers, p0, ws, true, static_cast<hipStream_t>(hip_stream));
-      return e == hipSuccess ? SPARK_OK : SPARK_ERR_DEVICE;
-    }
-  }
-  for (int32_t l = 0; l < n_layers; ++l) {
-    const spark::FfnProblem p = make_problem(
-        &layers[l], q, qdtype, batch, ldq, y + (int64_t)l * batch * d_model,
-        theta ? theta + (int64_t)l * batch : nullptr, active_count ? active_count + (int64_t)l * batch : nullptr,
-        active_idx ? active_idx + (int64_t)l * batch * d_ff : nullptr, union_count ? union_count + l : nullptr,
-        union_idx ? union_idx + (int64_t)l * d_ff : nullptr);
-    const hipError_t e = spark::launch_ffn_general(p, ws, 0, static_cast<hipStream_t>(hip_stream));
-    if (e != hipSuccess) return SPARK_ERR_DEVICE;
-  }
-  return SPARK_OK;
+  return decode_layers(layers, n_layers, q, qdtype, batch, ldq, y, theta, active_count, active_idx, union_count,
+                       union_idx, workspace, workspace_bytes, spark::FfnTuning(), static_cast<hipStream_t>(hip_stream));
+}
+
+spark_status spark_ffn_decode_layers_tuned(const spark_ffn_layer* layers, int32_t n_layers, const void* q,
+                                           spark_dtype qdtype, int32_t batch, int64_t ldq, float* y, float* theta,
+                                           int32_t* active_count, int32_t* active_idx, int32_t* union_count,
+                                           int32_t* union_idx, void* workspace, size_t workspace_bytes,
+                                           const spark_ffn_tuning* tuning, void* hip_stream) {
+  return decode_layers(layers, n_layers, q, qdtype, batch, ldq, y, theta, active_count, active_idx, union_count,
+                       union_idx, workspace, workspace_bytes, make_tuning(tuning), static_cast<hipStream_t>(hip_stream));
 }
 
 size_t spark_ffn_prefill_workspace_bytes(int32_t d_model, int32_t d_ff, int32_t chunk) {
@@ -298,6 +319,7 @@ spark_status spark_ffn_prefill(const spark_ffn_layer* layer, const void* q, spar
   if (s != SPARK_OK) return s;
   if (workspace_bytes < spark_ffn_prefill_workspace_bytes(layer->d_model, layer->d_ff, chunk)) return SPARK_ERR_WORKSPACE;
   hipStream_t st = static_cast<hipStream_t>(hip_stream);
+  const spark::FfnTuning tune;
   const int64_t d_model = layer->d_model, d_ff = layer->d_ff, n_full = n_tokens / chunk;
   const int32_t tail = (int32_t)(n_tokens % chunk);
   const size_t qs = dtype_size(qdtype);
@@ -311,12 +333,11 @@ spark_status spark_ffn_prefill(const spark_ffn_layer* layer, const void* q, spar
   auto one_chunk = [&](int64_t t0, int64_t c, int32_t batch) {
     const spark::FfnProblem p = problem_at(t0, c, batch);
     const spark::FfnWorkspace ws = spark::carve_workspace(workspace, layer->d_model, layer->d_ff, batch);
-    if ((g_force_general == 0 || p.w_fp8) && (spark::phased_supported(p) || spark::phased_batch_supported(p)))
-      return run_fused(layer, 1, p, ws, false, st);
+    if (takes_phased(p, tune)) return run_phased(layer, 1, p, tune, ws.phased, spark::kPhasedMaxLayers, st);
     return spark::launch_ffn_general(p, ws, 0, st);
   };
   int64_t c = 0;
-  if (n_full > 0 && g_force_general == 0 && spark::phased_batch_supported(problem_at(0, 0, chunk))) {
+  if (n_full > 0 && spark::phased_batch_supported(problem_at(0, 0, chunk))) {
     // the full chunks are independent of each other: they go through the batched path as the
     // "layers" of one launch, every slot with the same weights and its own block of tokens
     const spark::FfnWorkspace ws = spark::carve_workspace(workspace, layer->d_model, layer->d_ff, chunk);
@@ -332,7 +353,7 @@ spark_status spark_ffn_prefill(const spark_ffn_layer* layer, const void* q, spar
       spark::FfnProblem p = problem_at(c * chunk, c, chunk);
       p.q_slot_stride = (int64_t)chunk * ldq;
       const int n = (int)(n_full - c < 256 ? n_full - c : 256);
-      if (spark::launch_ffn_phased_batch(p, w1, w2, w3, n, ws.fused, st) != hipSuccess) return SPARK_ERR_DEVICE;
+      if (spark::launch_ffn_phased_batch(p, w1, w2, w3, n, tune, ws.phased, st) != hipSuccess) return SPARK_ERR_DEVICE;
     }
     c = n_full;
   }
@@ -372,8 +393,9 @@ spark_status spark_ffn_dense_decode_layers(const spark_ffn_layer* layers, int32_
   const spark::FfnWorkspace ws = spark::carve_workspace(workspace, layers[0].d_model, layers[0].d_ff, batch);
   const spark::FfnProblem p0 =
       make_problem(&layers[0], q, qdtype, batch, ldq, y, nullptr, nullptr, nullptr, nullptr, nullptr);
-  if ((g_force_general == 0 || p0.w_fp8) && spark::phased_supported(p0)) {
-    const hipError_t e = run_fused(layers, n_layers, p0, ws, false, static_cast<hipStream_t>(hip_stream), 1);
+  if (spark::phased_supported(p0)) {
+    const hipError_t e = run_phased(layers, n_layers, p0, spark::FfnTuning(), ws.phased, spark::kPhasedMaxLayers,
+                                    static_cast<hipStream_t>(hip_stream), 1);
     return e == hipSuccess ? SPARK_OK : SPARK_ERR_DEVICE;
   }
   for (int32_t l = 0; l < n_layers; ++l) {
@@ -448,40 +470,18 @@ spark_status spark_attn_decode(const spark_attn_head* heads, int32_t n_heads, co
   return SPARK_OK;
 }
 
-spark_status spark_ffn_check(const void* workspace, int32_t d_model, int32_t d_ff, int32_t batch,
-                             void* hip_stream) {
-  if (!workspace) return SPARK_ERR_WORKSPACE;
-  if (spark_ffn_workspace_bytes(d_model, d_ff, batch) == 0) return SPARK_ERR_SHAPE;
-  const spark::FfnWorkspace ws = spark::carve_workspace(const_cast<void*>(workspace), d_model, d_ff, batch);
-  int32_t word = 0;
-  hipStream_t st = static_cast<hipStream_t>(hip_stream);
-  if (hipMemcpyAsync(&word, ws.fused, sizeof(word), hipMemcpyDeviceToHost, st) != hipSuccess) return SPARK_ERR_DEVICE;
-  if (hipStreamSynchronize(st) != hipSuccess) return SPARK_ERR_DEVICE;
-  return word == 0 ? SPARK_OK : SPARK_ERR_DEVICE;
+size_t spark_stat_topk_workspace_bytes(int64_t rows, int64_t n) {
+  (void)rows;
+  (void)n;
+  return 0;  // the row-wise kernels keep a row on chip: no scratch memory
 }
 
-void spark_debug_force_general(int on) { g_force_general = (on == 1 || on == 2) ? on : 0; }
-
-void spark_debug_phases(int mask) { spark::phased_set_phases(mask); }
-
-void spark_debug_tuning(int rows_per_predict_block, int neurons_per_gather_block, int alt) {
-  spark::phased_set_tuning(rows_per_predict_block, neurons_per_gather_block, alt);
-  spark::phased_batch_set_tuning(rows_per_predict_block / 16, neurons_per_gather_block / 16, alt);
-}
-
-void spark_debug_profile(int on) { spark::fused_set_profile(on != 0); }
-
-spark_status spark_debug_read_profile(const void* workspace, int32_t d_model, int32_t d_ff, int32_t batch,
-                                      int64_t* out, int64_t n_words, void* hip_stream) {
-  if (!workspace || !out) return SPARK_ERR_NULL;
-  if (spark_ffn_workspace_bytes(d_model, d_ff, batch) == 0) return SPARK_ERR_SHAPE;
-  const spark::FfnWorkspace ws = spark::carve_workspace(const_cast<void*>(workspace), d_model, d_ff, batch);
-  size_t bytes = (size_t)n_words * 8;
-  if (bytes > spark::fused_profile_bytes()) bytes = spark::fused_profile_bytes();
-  hipStream_t st = static_cast<hipStream_t>(hip_stream);
-  const char* src = static_cast<const char*>(ws.fused) + spark::fused_profile_offset(d_model, d_ff);
-  if (hipMemcpyAsync(out, src, bytes, hipMemcpyDeviceToHost, st) != hipSuccess) return SPARK_ERR_DEVICE;
-  return hipStreamSynchronize(st) == hipSuccess ? SPARK_OK : SPARK_ERR_DEVICE;
+spark_status spark_copy_bytes(void* dst, const void* src, size_t nbytes, void* hip_stream) {
+  if (nbytes == 0) return SPARK_OK;
+  if (!dst || !src) return SPARK_ERR_NULL;
+  if (!aligned16(dst) || !aligned16(src) || nbytes % 16) return SPARK_ERR_ALIGN;
+  const hipError_t e = spark::launch_copy_bytes(dst, src, nbytes, static_cast<hipStream_t>(hip_stream));
+  return e == hipSuccess ? SPARK_OK : SPARK_ERR_DEVICE;
 }
 
 }  // extern "C"

@@ -354,8 +354,11 @@ hipError_t launch_predict_t(const AttnParams& P, int lpr, dim3 grid, hipStream_t
 template <typename WT, int LPR2, int LPRV>
 hipError_t launch_gather_k(const AttnParams& P, dim3 grid, size_t dyn, hipStream_t st) {
   const void* kern = reinterpret_cast<const void*>(attn_gather_kernel<WT, LPR2, LPRV>);
-  const hipError_t e = hipFuncSetAttribute(kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)dyn);
+  // the attribute is set to the most any call may ask for (scores of kAttnMaxCtx keys + their list),
+  // the same value every time, so calls from several threads cannot undercut each other
+  const hipError_t e = hipFuncSetAttribute(kern, hipFuncAttributeMaxDynamicSharedMemorySize, kAttnMaxCtx * 6 + 16);
   if (e != hipSuccess) return e;
+  if (dyn > (size_t)kAttnMaxCtx * 6 + 16) return hipErrorInvalidValue;
   hipLaunchKernelGGL((attn_gather_kernel<WT, LPR2, LPRV>), grid, dim3(kGatherWavesA * kWave), dyn, st, P);
   return hipGetLastError();
 }

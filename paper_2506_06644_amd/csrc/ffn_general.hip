@@ -23,12 +23,10 @@ template <typename WT, int TB>
 __global__ __launch_bounds__(kBlock) void predict_kernel(const WT* __restrict__ k1n, int d_ff, int r,
                                                          const void* __restrict__ q, int q_bf16,
                                                          int64_t ldq, int B, float* __restrict__ S,
-                                                         int32_t* __restrict__ flags,
-                                                         int32_t* __restrict__ status) {
+                                                         int32_t* __restrict__ flags) {
   constexpr int VEC = Vec16<WT>::N;
   const int tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid / kWave;
   for (int i = blockIdx.x * kBlock + tid; i < d_ff; i += gridDim.x * kBlock) flags[i] = 0;
-  if (blockIdx.x == 0 && tid == 0) status[0] = 0;  // this path cannot abort
   const int nvec = r / VEC;
   const int gw = blockIdx.x * kWavesPerBlock + wave, nw = gridDim.x * kWavesPerBlock;
   for (int j = gw; j < d_ff; j += nw) {
@@ -268,14 +266,12 @@ __global__ __launch_bounds__(kRowsWaves * kWave) void rows_mfma_kernel(const bf1
                                                         int B, int d_ff, const int32_t* __restrict__ uidx,
                                                         const int32_t* __restrict__ ucount,
                                                         const float* __restrict__ A, float* __restrict__ out,
-                                                        int gelu_kind, int dense, int32_t* __restrict__ flags,
-                                                        int32_t* __restrict__ status) {
+                                                        int gelu_kind, int dense, int32_t* __restrict__ flags) {
   __shared__ float red[kRowsWaves - 1][NB * 4][kWave];
   const int tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid / kWave;
   const int tile = blockIdx.x;
   if (MODE == 0) {
     for (int i = blockIdx.x * blockDim.x + tid; i < d_ff; i += gridDim.x * blockDim.x) flags[i] = 0;
-    if (blockIdx.x == 0 && tid == 0) status[0] = 0;  // this path cannot abort
   }
   const int m_total = MODE == 0 ? n_rows : ucount[0];
   if (tile * 16 >= m_total) return;
@@ -483,12 +479,11 @@ template <typename WT>
 __global__ __launch_bounds__(256) void dense_rows_kernel(const WT* __restrict__ k1n, const WT* __restrict__ k2n,
                                                          int d_ff, int r, int r2, const void* __restrict__ q,
                                                          int q_bf16, float* __restrict__ S, float* __restrict__ G,
-                                                         int32_t* __restrict__ flags, int32_t* __restrict__ status) {
+                                                         int32_t* __restrict__ flags) {
   constexpr int VEC = Vec16<WT>::N;
   extern __shared__ float qs[];  // q as fp32, d_model entries
   const int tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid / kWave;
   for (int i = blockIdx.x * 256 + tid; i < d_ff; i += gridDim.x * 256) flags[i] = 0;
-  if (blockIdx.x == 0 && tid == 0) status[0] = 0;
   for (int i = tid; i < r + r2; i += 256) qs[i] = load_q(q, q_bf16, i);
   __syncthreads();
   const int nvec1 = r / VEC, nvec2 = r2 / VEC;
@@ -587,7 +582,7 @@ hipError_t launch_general_t(const FfnProblem& p, const FfnWorkspace& ws, int den
 
   if (dense && B == 1) {
     hipLaunchKernelGGL((dense_rows_kernel<WT>), dim3(2048), dim3(256), (size_t)p.d_model * 4, st, k1n, k2n, p.d_ff,
-                       p.r, r2, p.q, p.q_bf16, ws.S, ws.uact, ws.flags, static_cast<int32_t*>(ws.fused));
+                       p.r, r2, p.q, p.q_bf16, ws.S, ws.uact, ws.flags);
     hipError_t e = launch_stat_topk(ws.S, 0, 1, p.d_ff, p.d_ff, p.z, 0, 0.f, ws.A, p.d_ff, p.theta, p.active_count,
                                     p.active_idx, p.d_ff, nullptr, st);
     if (e != hipSuccess) return e;
@@ -607,8 +602,7 @@ hipError_t launch_general_t(const FfnProblem& p, const FfnWorkspace& ws, int den
       const int nb = (B + 15) / 16;
 #define SPARK_LAUNCH_ROWS(NB, MODE, W, K, QOFF, OUT)                                                     \
   hipLaunchKernelGGL((rows_mfma_kernel<NB, MODE>), dim3(tiles), dim3(kRowsWaves * kWave), 0, st, W, p.d_ff, K, qb, p.ldq, \
-                     QOFF, B, p.d_ff, ws.uidx, ws.ucount, ws.A, OUT, p.gelu, dense, ws.flags,             \
-                     static_cast<int32_t*>(ws.fused))
+                     QOFF, B, p.d_ff, ws.uidx, ws.ucount, ws.A, OUT, p.gelu, dense, ws.flags)
       if (nb == 1) SPARK_LAUNCH_ROWS(1, 0, k1n, p.r, 0, ws.S);
       else if (nb == 2) SPARK_LAUNCH_ROWS(2, 0, k1n, p.r, 0, ws.S);
       else SPARK_LAUNCH_ROWS(4, 0, k1n, p.r, 0, ws.S);
@@ -641,10 +635,10 @@ hipError_t launch_general_t(const FfnProblem& p, const FfnWorkspace& ws, int den
     const int grid = min((p.d_ff + kWavesPerBlock - 1) / kWavesPerBlock, 4096);
     if (B == 1)
       hipLaunchKernelGGL((predict_kernel<WT, 1>), dim3(grid), dim3(kBlock), 0, st, k1n, p.d_ff, p.r, p.q,
-                         p.q_bf16, p.ldq, B, ws.S, ws.flags, static_cast<int32_t*>(ws.fused));
+                         p.q_bf16, p.ldq, B, ws.S, ws.flags);
     else
       hipLaunchKernelGGL((predict_kernel<WT, 4>), dim3(grid), dim3(kBlock), 0, st, k1n, p.d_ff, p.r, p.q,
-                         p.q_bf16, p.ldq, B, ws.S, ws.flags, static_cast<int32_t*>(ws.fused));
+                         p.q_bf16, p.ldq, B, ws.S, ws.flags);
   }
   hipError_t e = launch_stat_topk(ws.S, 0, B, p.d_ff, p.d_ff, p.z, 0, 0.f, ws.A, p.d_ff, p.theta, p.active_count,
                                   p.active_idx, p.d_ff, ws.flags, st);
@@ -694,10 +688,10 @@ int pick_ksplit(int d_model) {
 
 }  // namespace
 
-// The region the single-launch, phased and batched phased paths share (one of them runs per call).
-static size_t fused_region_bytes(int d_model, int d_ff, int batch) {
+// The region the phase-by-phase paths use (one of them runs per call).
+static size_t phased_region_bytes(int d_model, int d_ff, int batch) {
   if (batch >= 2) return phased_batch_scratch_bytes(d_model, d_ff, batch);
-  return std::max(fused_scratch_bytes(d_model, d_ff), phased_scratch_bytes(d_model, d_ff));
+  return phased_scratch_bytes(d_model, d_ff, kPhasedMaxLayers);
 }
 
 size_t ffn_workspace_bytes(int d_model, int d_ff, int batch) {
@@ -710,7 +704,7 @@ size_t ffn_workspace_bytes(int d_model, int d_ff, int batch) {
   t += 256;                                            // ucount
   t += align_up(F * B * 4, 256);                       // uact
   t += align_up((size_t)pick_ksplit(d_model) * B * D * 4, 256);  // part
-  t += align_up(fused_region_bytes(d_model, d_ff, batch), 256);
+  t += align_up(phased_region_bytes(d_model, d_ff, batch), 256);
   return t;
 }
 
@@ -726,8 +720,8 @@ FfnWorkspace carve_workspace(void* base, int d_model, int d_ff, int batch) {
   ws.uact = reinterpret_cast<float*>(p);     p += align_up(F * B * 4, 256);
   ws.ksplit = pick_ksplit(d_model);
   ws.part = reinterpret_cast<float*>(p);     p += align_up((size_t)ws.ksplit * B * D * 4, 256);
-  ws.fused = p;
-  ws.fused_bytes = fused_region_bytes(d_model, d_ff, batch);
+  ws.phased = p;
+  ws.phased_bytes = phased_region_bytes(d_model, d_ff, batch);
   return ws;
 }
 

@@ -42,7 +42,6 @@ struct PhasedParams {
   float* scores;       // [L][d_ff]
   float* stats;        // [L][NBA][2]  (mean, M2) of each predictor block
   float* part;         // [L][NBC][d_model]
-  int32_t* status;     // cleared: this path cannot abort
   int n_layers, d_model, d_ff, r, q_bf16, gelu;
   int dense;  // every neuron's K2n and Vn row is read (inactive ones contribute an exact zero)
   float z;
@@ -195,7 +194,6 @@ __global__ __launch_bounds__(256) void predict_layers_kernel(const PhasedParams 
       if (lane == 0 && lr < nrows) s_sh[lr] = acc * sc[e];
     }
   }
-  if (l == 0 && blk == 0 && threadIdx.x == 0) *P.status = 0;
   __syncthreads();
   for (int t = threadIdx.x; t < nrows; t += 256) P.scores[(size_t)l * P.d_ff + row0 + t] = s_sh[t];
   if (wave == 0) {
@@ -489,12 +487,12 @@ struct PhasedLayout {
 };
 constexpr int kMaxNBC = 64;  // most gather blocks per layer
 
-PhasedLayout phased_layout(int d_model, int d_ff) {
+PhasedLayout phased_layout(int d_model, int d_ff, int layer_cap) {
   PhasedLayout s;
-  size_t o = 256;  // the first word of the scratch is the status word spark_ffn_check reads
-  s.scores = o; o += align256((size_t)kPhasedMaxLayers * (size_t)d_ff * 4);
-  s.stats = o;  o += align256((size_t)kPhasedMaxLayers * (size_t)((d_ff + 15) / 16) * 8);
-  s.part = o;   o += align256((size_t)kPhasedMaxLayers * kMaxNBC * (size_t)d_model * 4);
+  size_t o = 0;
+  s.scores = o; o += align256((size_t)layer_cap * (size_t)d_ff * 4);
+  s.stats = o;  o += align256((size_t)layer_cap * (size_t)((d_ff + 15) / 16) * 8);
+  s.part = o;   o += align256((size_t)layer_cap * kMaxNBC * (size_t)d_model * 4);
   s.total = o;
   return s;
 }
@@ -523,9 +521,6 @@ int gather_variant(const FfnProblem& p) {
   return -1;
 }
 
-int g_phased_rpb = 0, g_phased_npb = 0, g_phased_alt = 0;  // tuning overrides (0 = automatic)
-int g_phased_mask = 7;  // measurement aid: which of predict (1), gather (2), reduce / select (4) are launched
-
 template <typename WT, bool QB>
 hipError_t launch_predict(const PhasedParams& P, int cpl1, dim3 grid, hipStream_t st) {
   if (P.RPB == 48 && cpl1 <= 2) {  // few layers: one sweep of 12 rows per wave
@@ -546,10 +541,8 @@ hipError_t launch_predict(const PhasedParams& P, int cpl1, dim3 grid, hipStream_
 template <typename WT, int CPL2, int CPLV, int NW, int OCC>
 hipError_t launch_gather(const PhasedParams& P, dim3 grid, hipStream_t st) {
   constexpr int VEC = Vec16<WT>::N;
+  // (at most 40 KB for the compiled variants: below the 64 KB a launch may ask for without an attribute)
   const size_t dyn = ((size_t)CPL2 * kWave * VEC + (size_t)(NW / 2) * P.d_model) * sizeof(float);
-  const void* kern = reinterpret_cast<const void*>(gather_layers_kernel<WT, CPL2, CPLV, NW, OCC>);
-  hipError_t e = hipFuncSetAttribute(kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)dyn);
-  if (e != hipSuccess) return e;
   hipLaunchKernelGGL((gather_layers_kernel<WT, CPL2, CPLV, NW, OCC>), grid, dim3(NW * kWave), dyn, st, P);
   return hipGetLastError();
 }
@@ -565,15 +558,7 @@ hipError_t launch_gather_index(const PhasedParams& P, dim3 grid, hipStream_t st)
 
 }  // namespace
 
-void phased_set_phases(int mask) { g_phased_mask = (mask & 7) ? (mask & 7) : 7; }
-
-void phased_set_tuning(int rpb, int npb, int alt) {
-  g_phased_rpb = rpb;
-  g_phased_npb = npb;
-  g_phased_alt = alt;
-}
-
-size_t phased_scratch_bytes(int d_model, int d_ff) { return phased_layout(d_model, d_ff).total; }
+size_t phased_scratch_bytes(int d_model, int d_ff, int layer_cap) { return phased_layout(d_model, d_ff, layer_cap).total; }
 
 bool phased_supported(const FfnProblem& p) {
   const int vec = weight_vec(p);
@@ -583,17 +568,20 @@ bool phased_supported(const FfnProblem& p) {
 }
 
 hipError_t launch_ffn_phased(const FfnProblem& p0, const void* const* k1n, const void* const* k2n,
-                             const void* const* vn, int n_layers, int dense, void* scratch, hipStream_t st) {
-  const PhasedLayout lay = phased_layout(p0.d_model, p0.d_ff);
+                             const void* const* vn, int n_layers, int dense, const FfnTuning& tune, void* scratch,
+                             int layer_cap, hipStream_t st) {
+  layer_cap = max(1, min(layer_cap, kPhasedMaxLayers));
+  const PhasedLayout lay = phased_layout(p0.d_model, p0.d_ff, layer_cap);
+  const int phases = (tune.phases & 7) ? (tune.phases & 7) : 7;
   int gv = gather_variant(p0);
   if (gv < 0) return hipErrorInvalidValue;
-  if (gv == 1 && g_phased_alt == 1) gv = 6;
+  if (gv == 1 && tune.variant == 1) gv = 6;
   const int vec = weight_vec(p0);
   const int cpl1 = (p0.r / vec + kWave - 1) / kWave;
   char* s = static_cast<char*>(scratch);
   hipError_t err = hipSuccess;
-  for (int base = 0; base < n_layers && err == hipSuccess; base += kPhasedMaxLayers) {
-    const int L = min(kPhasedMaxLayers, n_layers - base);
+  for (int base = 0; base < n_layers && err == hipSuccess; base += layer_cap) {
+    const int L = min(layer_cap, n_layers - base);
     PhasedParams P;
     for (int l = 0; l < kPhasedMaxLayers; ++l) {
       P.k1n[l] = l < L ? k1n[base + l] : nullptr;
@@ -610,7 +598,6 @@ hipError_t launch_ffn_phased(const FfnProblem& p0, const void* const* k1n, const
     P.scores = reinterpret_cast<float*>(s + lay.scores);
     P.stats = reinterpret_cast<float*>(s + lay.stats);
     P.part = reinterpret_cast<float*>(s + lay.part);
-    P.status = reinterpret_cast<int32_t*>(s);
     P.n_layers = L;
     P.d_model = p0.d_model;
     P.d_ff = p0.d_ff;
@@ -622,7 +609,7 @@ hipError_t launch_ffn_phased(const FfnProblem& p0, const void* const* k1n, const
     // Block sizes: enough workgroups to fill 256 compute units several times over, as few
     // partial rows as that allows.
     const long long want_wg = 2048;
-    int rpb = g_phased_rpb;
+    int rpb = tune.rows_per_predict_block;
     if (rpb <= 0) {
       // 64 rows where that still gives every compute unit several workgroups; with fewer
       // layers 48 (measured best for 1..12 layers of the 2B shape: smaller blocks only lengthen
@@ -630,7 +617,7 @@ hipError_t launch_ffn_phased(const FfnProblem& p0, const void* const* k1n, const
       rpb = (long long)L * ((p0.d_ff + 63) / 64) >= want_wg ? 64 : 48;
     }
     rpb = max(16, min(kMaxRPB, rpb / 16 * 16));
-    int npb = g_phased_npb;
+    int npb = tune.neurons_per_gather_block;
     if (npb <= 0) {
       // long per-wave runs of rows pipeline best: the largest block that still leaves about
       // two workgroups for every compute unit
@@ -646,14 +633,14 @@ hipError_t launch_ffn_phased(const FfnProblem& p0, const void* const* k1n, const
     P.NBC = (p0.d_ff + npb - 1) / npb;
 
     const dim3 ga(P.NBA, L);
-    if (!(g_phased_mask & 1)) err = hipSuccess;
+    if (!(phases & 1)) err = hipSuccess;
     else if (p0.w_fp8 == 2) err = launch_predict<i8_t, false>(P, cpl1, ga, st);
     else if (p0.w_fp8) err = launch_predict<fp8_t, false>(P, cpl1, ga, st);
     else if (p0.w_bf16) err = p0.q_bf16 ? launch_predict<bf16_t, true>(P, cpl1, ga, st) : launch_predict<bf16_t, false>(P, cpl1, ga, st);
     else err = launch_predict<float, false>(P, cpl1, ga, st);
     if (err != hipSuccess) return err;
     const dim3 gc(P.NBC, L);
-    if (g_phased_mask & 2) switch (gv) {
+    if (phases & 2) switch (gv) {
       case 0: err = launch_gather_index<0>(P, gc, st); break;
       case 1: err = launch_gather_index<1>(P, gc, st); break;
       case 2: err = launch_gather_index<2>(P, gc, st); break;
@@ -670,7 +657,7 @@ hipError_t launch_ffn_phased(const FfnProblem& p0, const void* const* k1n, const
       default: err = hipErrorInvalidValue; break;
     }
     if (err != hipSuccess) return err;
-    if (!(g_phased_mask & 4)) continue;
+    if (!(phases & 4)) continue;
     hipLaunchKernelGGL(reduce_layers_kernel, dim3((p0.d_model + 255) / 256, L), dim3(256), 0, st, P);
     if (P.count || P.idx || P.ucount || P.uidx)
       hipLaunchKernelGGL(select_layers_kernel, dim3(L), dim3(1024), 0, st, P);

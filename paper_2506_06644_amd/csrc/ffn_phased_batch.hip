@@ -65,7 +65,6 @@ struct BatchParams {
                                // are 16 contiguous bytes and a group's tokens are contiguous too
   size_t plane;                // elements between planes
   float* part;                 // [L][KS][B][d_model]
-  int32_t* status;
   int n_layers, B, BP, d_model, d_ff, r, gelu, ldu;  // BP = B rounded up to 16
   float z;
   int TPW1;  // predict tiles per workgroup (even)
@@ -229,7 +228,6 @@ __global__ __launch_bounds__(kRowThreads) void predict_batch_kernel(const BatchP
   const int l = blockIdx.y;
   const int tiles_total = (P.d_ff + 15) / 16;
   const int tile0 = blockIdx.x * P.TPW1;
-  if (blockIdx.x == 0 && l == 0 && threadIdx.x == 0) *P.status = 0;  // this path cannot abort
   if (tile0 >= tiles_total) return;
   float* S = P.S + (size_t)l * P.B * P.d_ff;
   float* ST = P.ST + (size_t)l * P.d_ff * P.BP;
@@ -293,7 +291,6 @@ __global__ __launch_bounds__(256) void predict_tokens_kernel(const BatchParams P
   const int l = blockIdx.y, blk = blockIdx.x;
   const int nvec1 = P.r / 8;
   const int row0 = blk * kTokRows, nrows = max(0, min(kTokRows, P.d_ff - row0));
-  if (blockIdx.x == 0 && l == 0 && threadIdx.x == 0) *P.status = 0;  // this path cannot abort
   const bf16_t* q = P.q + (size_t)l * P.qslot;
   u32x4 qp[T][CPL1];
 #pragma unroll
@@ -622,7 +619,6 @@ __global__ __launch_bounds__(kStreamThreads, 4) void predict_stream_kernel(const
   const int l = blockIdx.y;
   const int tiles_total = (P.d_ff + 15) / 16;
   const int tile0 = blockIdx.x * (kStreamWaves * NT);
-  if (blockIdx.x == 0 && l == 0 && threadIdx.x == 0) *P.status = 0;  // this path cannot abort
   if (tile0 >= tiles_total) return;
   f32x4 acc[NT];
   rows_stream<GS, NG, NT>(static_cast<const bf16_t*>(P.k1n[l]), (uint32_t)P.d_ff * (uint32_t)P.r * 2u, P.r,
@@ -854,7 +850,7 @@ BatchLayout batch_layout(int d_model, int d_ff, int B) {
   BatchLayout s;
   const size_t L = kBatchMaxLayers;
   s.ldu = (d_ff + 64 + 7) / 8 * 8;
-  size_t o = 256;  // the first word is the status word spark_ffn_check reads
+  size_t o = 0;
   s.S = o;      o += align256(L * B * (size_t)d_ff * 4);
   s.ST = o;     o += align256(L * (size_t)((B + 15) / 16 * 16) * (size_t)d_ff * 4);
   s.thetas = o; o += align256(L * B * 4);
@@ -948,19 +944,7 @@ hipError_t launch_stream_split(const BatchParams& P, int mode, int gs, int ng, i
   return hipErrorInvalidValue;
 }
 
-int g_batch_tpw1 = 0, g_batch_tpw2 = 0, g_batch_ks = 0;  // tuning overrides (0 = automatic)
-int g_batch_stream = 1;                                  // 0: never take the streamed kernels, 2: wherever compiled
-
 }  // namespace
-
-void phased_batch_set_tuning(int tpw1, int tpw2, int ks) {
-  // 100 + ks: the k-split kernels for every batch size; 200 + ks: the streamed kernels wherever
-  // they are compiled, however small the launch
-  g_batch_stream = ks >= 200 ? 2 : ks >= 100 ? 0 : 1;
-  g_batch_ks = ks % 100;
-  g_batch_tpw1 = tpw1 > 0 ? (tpw1 + 3) / 4 * 4 : 0;
-  g_batch_tpw2 = tpw2 > 0 ? min(32, (tpw2 + 3) / 4 * 4) : 0;
-}
 
 size_t phased_batch_scratch_bytes(int d_model, int d_ff, int batch) { return batch_layout(d_model, d_ff, batch).total; }
 
@@ -973,8 +957,17 @@ bool phased_batch_supported(const FfnProblem& p) {
 }
 
 hipError_t launch_ffn_phased_batch(const FfnProblem& p0, const void* const* k1n, const void* const* k2n,
-                                   const void* const* vn, int n_layers, void* scratch, hipStream_t st) {
+                                   const void* const* vn, int n_layers, const FfnTuning& tune, void* scratch,
+                                   hipStream_t st) {
   const BatchLayout lay = batch_layout(p0.d_model, p0.d_ff, p0.batch);
+  // pinned choices (0 = automatic): tiles per workgroup of the predict and k2 steps (the block sizes
+  // divided by 16), row slices of the V step; variant 100 + ks: the k-split kernels for every batch
+  // size, 200 + ks: the streamed kernels wherever they are compiled, however small the launch
+  const int t1 = tune.rows_per_predict_block / 16, t2 = tune.neurons_per_gather_block / 16;
+  const int g_batch_stream = tune.variant >= 200 ? 2 : tune.variant >= 100 ? 0 : 1;
+  const int g_batch_ks = tune.variant % 100;
+  const int g_batch_tpw1 = t1 > 0 ? (t1 + 3) / 4 * 4 : 0;
+  const int g_batch_tpw2 = t2 > 0 ? min(32, (t2 + 3) / 4 * 4) : 0;
   char* s = static_cast<char*>(scratch);
   const int B = p0.batch, nb = (B + 15) / 16;
   hipError_t err = hipSuccess;
@@ -1008,7 +1001,6 @@ hipError_t launch_ffn_phased_batch(const FfnProblem& p0, const void* const* k1n,
     P.up = reinterpret_cast<uint16_t*>(s + lay.up);
     P.plane = lay.plane;
     P.part = reinterpret_cast<float*>(s + lay.part);
-    P.status = reinterpret_cast<int32_t*>(s);
     P.n_layers = L;
     P.B = B;
     P.d_model = p0.d_model;
@@ -1081,7 +1073,9 @@ hipError_t launch_ffn_phased_batch(const FfnProblem& p0, const void* const* k1n,
                      : nb == 2 ? reinterpret_cast<const void*>(v_batch_kernel<2>)
                      : nb == 3 ? reinterpret_cast<const void*>(v_batch_kernel<3>)
                                : reinterpret_cast<const void*>(v_batch_kernel<4>);
-    err = hipFuncSetAttribute(vk, hipFuncAttributeMaxDynamicSharedMemorySize, (int)vdyn);
+    // (the attribute is set to the most this variant can ask for, the same value on every call)
+    err = hipFuncSetAttribute(vk, hipFuncAttributeMaxDynamicSharedMemorySize,
+                              (int)((size_t)kVMaxWaves * 32 * kVPitch + (size_t)2 * kPlanes * nb * kWave * 16));
     if (err != hipSuccess) return err;
     switch (nb) {
       case 1: hipLaunchKernelGGL((v_batch_kernel<1>), gv, dim3(nwv * kWave), vdyn, st, P); break;

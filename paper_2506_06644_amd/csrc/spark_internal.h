@@ -48,8 +48,8 @@ struct FfnWorkspace {
   float* uact;       // [d_ff][batch] GELU(a) * g per union row
   float* part;       // [ksplit][batch][d_model] split partial sums of y
   int ksplit;
-  void* fused;       // scratch of the persistent batch-1 kernel
-  size_t fused_bytes;
+  void* phased;      // scratch of the phase-by-phase paths
+  size_t phased_bytes;
 };
 
 size_t ffn_workspace_bytes(int d_model, int d_ff, int batch);
@@ -58,37 +58,40 @@ FfnWorkspace carve_workspace(void* base, int d_model, int d_ff, int batch);
 // General path: separate kernels, any batch <= 64.  dense != 0 reads every K2 / V row.
 hipError_t launch_ffn_general(const FfnProblem& p, const FfnWorkspace& ws, int dense, hipStream_t st);
 
-// Persistent batch-1 path: one launch for up to kFusedMaxLayers layers (longer stacks are
-// chained).  `scratch` is ws.fused (fused_scratch_bytes(d_model, d_ff) bytes, 256-byte aligned); its
-// first int32 is a status word the launch clears and sets non-zero if it had to abort.
-constexpr int kFusedMaxLayers = 64;
-size_t fused_scratch_bytes(int d_model, int d_ff);
-void fused_set_profile(int on);               // testing aid: per-wave wait-time counters
-size_t fused_profile_offset(int d_model, int d_ff);     // byte offset of the counters inside the scratch
-size_t fused_profile_bytes();
-bool fused_supported(const FfnProblem& p, int n_layers);
-hipError_t launch_ffn_fused(const FfnProblem& p0, const void* const* k1n, const void* const* k2n,
-                            const void* const* vn, int n_layers, void* scratch, hipStream_t st);
+// Per-call choices a caller may pin instead of leaving them to the library (all 0 = automatic);
+// mirrors spark_ffn_tuning of the C ABI.
+struct FfnTuning {
+  int path = 0;     // 1: the general multi-kernel path even where a phase-by-phase path exists
+  int phases = 0;   // batch-1 path: bit 0 predictor sweep, bit 1 gather, bit 2 reduction / index lists; 0 = all
+  int rows_per_predict_block = 0;
+  int neurons_per_gather_block = 0;
+  int variant = 0;  // batch 1: 1 = the 8-wave gather; batches: row slices of the V step, +100 k-split kernels
+                    // for every batch size, +200 streamed kernels however small the launch
+};
 
 // Phase-by-phase batch-1 path: predictor sweep, gather, reduce as ordinary launches over up
-// to kPhasedMaxLayers layers at a time (longer stacks are chained).  `scratch` holds
-// phased_scratch_bytes(d_model, d_ff) bytes, 256-byte aligned, and needs no initialisation.
+// to `layer_cap` (<= kPhasedMaxLayers) layers at a time (longer stacks are chained).  `scratch`
+// holds phased_scratch_bytes(d_model, d_ff, layer_cap) bytes, 256-byte aligned, and needs no
+// initialisation.
 constexpr int kPhasedMaxLayers = 64;
-size_t phased_scratch_bytes(int d_model, int d_ff);
+size_t phased_scratch_bytes(int d_model, int d_ff, int layer_cap);
 bool phased_supported(const FfnProblem& p);
-void phased_set_phases(int mask);  // measurement aid: bit 0 predict, bit 1 gather, bit 2 reduce / select; 0 = all
-void phased_set_tuning(int rows_per_predict_block, int neurons_per_gather_block, int alt);  // 0 = automatic
 hipError_t launch_ffn_phased(const FfnProblem& p0, const void* const* k1n, const void* const* k2n,
-                             const void* const* vn, int n_layers, int dense, void* scratch, hipStream_t st);
+                             const void* const* vn, int n_layers, int dense, const FfnTuning& tune, void* scratch,
+                             int layer_cap, hipStream_t st);
 
 // Phase-by-phase path for batches of 2..64 tokens on the matrix cores (bf16 weights and
 // tokens), up to kBatchMaxLayers layers per set of launches.
 constexpr int kBatchMaxLayers = 32;
 size_t phased_batch_scratch_bytes(int d_model, int d_ff, int batch);
 bool phased_batch_supported(const FfnProblem& p);
-void phased_batch_set_tuning(int predict_tiles_per_workgroup, int k2_tiles_per_workgroup, int v_row_slices);  // 0 = automatic
 hipError_t launch_ffn_phased_batch(const FfnProblem& p0, const void* const* k1n, const void* const* k2n,
-                                   const void* const* vn, int n_layers, void* scratch, hipStream_t st);
+                                   const void* const* vn, int n_layers, const FfnTuning& tune, void* scratch,
+                                   hipStream_t st);
+
+// A plain device-to-device copy kernel of known size (the reference the HBM byte counters are
+// scaled by when traffic is measured).
+hipError_t launch_copy_bytes(void* dst, const void* src, size_t nbytes, hipStream_t st);
 
 // Spark-attention decode: one query per head over token-major caches, all heads of a call
 // in two launches (up to kAttnMaxHeads caches per pair of launches; longer lists are chained).

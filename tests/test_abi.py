@@ -146,3 +146,25 @@ def test_prefill_and_8bit_weights_reject_bad_arguments_before_launch():
     assert prefill(_layer(wd=f8), chunk=4) == 4
     assert _decode(_layer(wd=f8), qd=f8) == 4                 # tokens cannot be codes
     assert _decode(_layer(wd=binding.INT8), batch=2) == 4 and _decode(_layer(wd=binding.INT8), qd=binding.INT8) == 4
+
+
+def test_stat_topk_needs_no_workspace_and_copy_validates():
+    assert binding.stat_topk_workspace_bytes(8192, 9216) == 0
+    lib = binding.load_library()
+    vp = ctypes.c_void_p
+    assert lib.spark_copy_bytes(vp(0x1000), vp(0x2000), 0, None) == 0       # nothing to do
+    assert lib.spark_copy_bytes(None, vp(0x2000), 64, None) == 1
+    assert lib.spark_copy_bytes(vp(0x1008), vp(0x2000), 64, None) == 5
+    assert lib.spark_copy_bytes(vp(0x1000), vp(0x2000), 40, None) == 5
+
+
+def test_tuned_entry_point_validates_like_the_plain_one():
+    lib = binding.load_library()
+    vp = ctypes.c_void_p
+    layer = _layer()
+    ws_bytes = binding.ffn_workspace_bytes(256, 1024, 1)
+    tune = binding.Tuning(path=1)
+    args = lambda n, ws: (ctypes.byref(layer), n, vp(0x4000), binding.BF16, 1, 256, vp(0x5000), None, None, None,
+                          None, None, vp(0x10000), ws, ctypes.byref(tune), None)
+    assert lib.spark_ffn_decode_layers_tuned(*args(0, ws_bytes)) == 2
+    assert lib.spark_ffn_decode_layers_tuned(*args(1, ws_bytes - 1)) == 6

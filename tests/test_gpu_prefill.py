@@ -11,7 +11,7 @@ from parity_util import TOL_BF16_TIGHT, TOL_F32, check_ffn_against_oracle, rel_l
 pytestmark = pytest.mark.gpu
 
 
-def _run_prefill(shape, w, q, chunk, gelu=binding.GELU_ERF, force_general=0):
+def _run_prefill(shape, w, q, chunk, gelu=binding.GELU_ERF):
     dev = torch.device("cuda:0")
     T = q.shape[0]
     nch = (T + chunk - 1) // chunk
@@ -25,11 +25,7 @@ def _run_prefill(shape, w, q, chunk, gelu=binding.GELU_ERF, force_general=0):
     idx = torch.full((T, shape.d_ff), -1, dtype=torch.int32, device=dev)
     ucnt = torch.zeros(max(nch, 1), dtype=torch.int32, device=dev)
     uidx = torch.full((max(nch, 1), shape.d_ff), -1, dtype=torch.int32, device=dev)
-    binding.spark_debug_force_general(force_general)
-    try:
-        binding.spark_ffn_prefill(layer, qd, chunk, y, ws, theta, cnt, idx, ucnt, uidx)
-    finally:
-        binding.spark_debug_force_general(0)
+    binding.spark_ffn_prefill(layer, qd, chunk, y, ws, theta, cnt, idx, ucnt, uidx)
     torch.cuda.synchronize()
     return dict(y=y.cpu().numpy(), theta=theta.cpu().numpy(), count=cnt.cpu().numpy(), idx=idx.cpu().numpy(),
                 ucount=ucnt.cpu().numpy(), uidx=uidx.cpu().numpy())
@@ -73,15 +69,19 @@ def test_prefill_other_types_and_shapes_go_chunk_by_chunk():
     _check_chunks(sh, w, q, 8, out, TOL_BF16_TIGHT, what="ragged")
 
 
-def test_prefill_equals_the_general_path():
+def test_prefill_equals_chunk_by_chunk_calls_of_the_general_path():
+    from parity_util import run_gpu_ffn
     sh = synth.TINY
     w = synth.ffn_layer(sh, 80, torch.bfloat16)
     q = synth.tokens(sh, 37, 9200, torch.bfloat16)
     a = _run_prefill(sh, w, q, 16)
-    b = _run_prefill(sh, w, q, 16, force_general=1)
-    assert rel_l2(a["y"], b["y"]) < 1e-6
-    assert np.array_equal(a["ucount"], b["ucount"]) and np.array_equal(a["uidx"], b["uidx"])
-    assert np.array_equal(a["count"], b["count"]) and np.array_equal(a["idx"], b["idx"])
+    for c, t0 in enumerate(range(0, 37, 16)):
+        t1 = min(37, t0 + 16)
+        b = run_gpu_ffn(sh, [w], q[t0:t1], force_general=True)
+        assert rel_l2(a["y"][t0:t1], b["y"][0]) < 1e-6
+        mu = int(b["ucount"][0])
+        assert a["ucount"][c] == mu and np.array_equal(a["uidx"][c, :mu], b["uidx"][0, :mu])
+        assert np.array_equal(a["count"][t0:t1], b["count"][0]) and np.array_equal(a["idx"][t0:t1], b["idx"][0])
 
 
 def test_prefill_token_results_do_not_depend_on_the_chunking():
