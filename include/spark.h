@@ -192,6 +192,31 @@ spark_status spark_ffn_decode(const spark_ffn_layer* layer, const void* q, spark
                               void* hip_stream);
 
 /*
+ * spark_ffn_decode for callers that can neither allocate device memory nor pass a workspace: code
+ * under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments
+ * (minus the workspace), same kernels and same results as spark_ffn_decode for one token; the
+ * scratch memory is an array of SPARK_STATIC_SCRATCH_BYTES built into the library's code object
+ * (every GPU the library runs on holds its copy until the process ends).  The call allocates and
+ * frees nothing; the first call on a device looks up the array's address on that device (make it
+ * outside a stream capture).
+ *
+ * Limits: batch = 1 and a shape the one-token kernels take (rows of at most 256 16-byte chunks
+ * for K1n, 448 for Vn with bf16 weights; others -> SPARK_ERR_SHAPE), and a scratch need of
+ * 4 d_ff + 8 ceil(d_ff / 16) + 256 d_model bytes (each term rounded up to 256) within
+ * SPARK_STATIC_SCRATCH_BYTES (-> SPARK_ERR_WORKSPACE beyond; the 2B and 9B layer shapes need 0.6
+ * and 1.0 MB).  Other errors as spark_ffn_decode.
+ *
+ * All calls on one GPU share that GPU's array: calls that may overlap in time (different streams,
+ * different threads) race on it and must be ordered by the caller.  Nothing in the array has to
+ * start at zero, and a call leaves nothing behind that a later call depends on.
+ */
+#define SPARK_STATIC_SCRATCH_BYTES (2u << 20)
+spark_status spark_ffn_decode_static(const spark_ffn_layer* layer, const void* q, spark_dtype qdtype,
+                                     int32_t batch, int64_t ldq, float* y, float* theta,
+                                     int32_t* active_count, int32_t* active_idx, int32_t* union_count,
+                                     int32_t* union_idx, void* hip_stream);
+
+/*
  * n_layers independent layers of one shape, evaluated in order l = 0 .. n_layers-1 on the
  * same q (host array `layers`; every layer must agree in d_model, d_ff, r, k, wdtype, gelu).
  * Output arrays carry a leading n_layers dimension:

@@ -28,7 +28,7 @@ EXPORTS = (
     "spark_ffn_dense_decode", "spark_ffn_dense_decode_layers",
     "spark_ffn_prefill_workspace_bytes", "spark_ffn_prefill",
     "spark_attn_workspace_bytes", "spark_attn_decode", "spark_stat_topk_workspace_bytes",
-    "spark_ffn_decode_layers_tuned", "spark_copy_bytes",
+    "spark_ffn_decode_layers_tuned", "spark_copy_bytes", "spark_ffn_decode_static",
 )
 
 
@@ -113,6 +113,8 @@ def load_library():
     lib.spark_ffn_decode_layers_tuned.restype = c_int
     lib.spark_ffn_decode_layers_tuned.argtypes = [ctypes.POINTER(_Layer), i32, vp, c_int, i32, i64, vp, vp, vp,
                                                   vp, vp, vp, vp, sz, ctypes.POINTER(Tuning), vp]
+    lib.spark_ffn_decode_static.restype = c_int
+    lib.spark_ffn_decode_static.argtypes = [ctypes.POINTER(_Layer), vp, c_int, i32, i64, vp, vp, vp, vp, vp, vp, vp]
     lib.spark_copy_bytes.restype = c_int
     lib.spark_copy_bytes.argtypes = [vp, vp, sz, vp]
     _lib = lib
@@ -207,6 +209,16 @@ def spark_ffn_decode(layer: _Layer, q: torch.Tensor, y: torch.Tensor, workspace:
         ctypes.byref(layer), _p(q), _dt(q), q.shape[0], q.stride(0), _p(y), _p(theta), _p(active_count),
         _p(active_idx), _p(union_count), _p(union_idx), _p(workspace), workspace.numel(), _stream())
     _check(rc, "spark_ffn_decode")
+
+
+def spark_ffn_decode_static(layer: _Layer, q: torch.Tensor, y: torch.Tensor, theta=None, active_count=None,
+                            active_idx=None, union_count=None, union_idx=None):
+    """:func:`spark_ffn_decode` for one token on the library's built-in scratch array (no workspace, no
+    allocation)."""
+    rc = load_library().spark_ffn_decode_static(
+        ctypes.byref(layer), _p(q), _dt(q), q.shape[0], q.stride(0), _p(y), _p(theta), _p(active_count),
+        _p(active_idx), _p(union_count), _p(union_idx), _stream())
+    _check(rc, "spark_ffn_decode_static")
 
 
 def spark_ffn_decode_layers(layers: Sequence[_Layer], q: torch.Tensor, y: torch.Tensor,

@@ -1,12 +1,37 @@
 // C ABI of the Spark-FFN library: host-side validation and dispatch.  See include/spark.h.
 #include "../../include/spark.h"
 
+#include <atomic>
 #include <cmath>
 #include <limits>
 
 #include "spark_internal.h"
 
+// Scratch memory of spark_ffn_decode_static: one copy per GPU, held until the process ends.
+static __device__ __align__(256) unsigned char scratch[SPARK_STATIC_SCRATCH_BYTES];
+
 namespace {
+
+// Device address of `scratch` on the current device, looked up once per device (every GPU holds
+// its own copy of the array at its own address; in host code the array's name is not an address).
+constexpr int kMaxDevices = 64;
+std::atomic<void*> g_scratch_ptr[kMaxDevices];
+
+hipError_t static_scratch_address(void** out) {
+  int dev = -1;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return e;
+  if (dev < 0 || dev >= kMaxDevices) return hipErrorInvalidDevice;
+  void* ptr = g_scratch_ptr[dev].load(std::memory_order_acquire);
+  if (!ptr) {
+    e = hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch));
+    if (e != hipSuccess) return e;
+    if (!ptr) return hipErrorInvalidSymbol;
+    g_scratch_ptr[dev].store(ptr, std::memory_order_release);  // two threads racing here store the same address
+  }
+  *out = ptr;
+  return hipSuccess;
+}
 
 bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 bool is_code_dtype(int dt) { return dt == SPARK_FP8_E4M3 || dt == SPARK_INT8; }  // 8-bit codes with row scales
@@ -280,6 +305,26 @@ spark_status spark_ffn_decode(const spark_ffn_layer* layer, const void* q, spark
                               void* workspace, size_t workspace_bytes, void* hip_stream) {
   return decode_layers(layer, layer ? 1 : 0, q, qdtype, batch, ldq, y, theta, active_count, active_idx, union_count,
                        union_idx, workspace, workspace_bytes, spark::FfnTuning(), static_cast<hipStream_t>(hip_stream));
+}
+
+spark_status spark_ffn_decode_static(const spark_ffn_layer* layer, const void* q, spark_dtype qdtype, int32_t batch,
+                                     int64_t ldq, float* y, float* theta, int32_t* active_count,
+                                     int32_t* active_idx, int32_t* union_count, int32_t* union_idx,
+                                     void* hip_stream) {
+  const spark_status s = validate_decode_args(layer, q, qdtype, batch, ldq, y);
+  if (s != SPARK_OK) return s;
+  if (batch != 1) return SPARK_ERR_SHAPE;
+  const spark::FfnProblem p = make_problem(layer, q, qdtype, batch, ldq, y, theta, active_count, active_idx,
+                                           union_count, union_idx);
+  if (!spark::phased_supported(p)) return SPARK_ERR_SHAPE;
+  if (spark::phased_scratch_bytes(layer->d_model, layer->d_ff, 1) > (size_t)SPARK_STATIC_SCRATCH_BYTES)
+    return SPARK_ERR_WORKSPACE;
+  void* ptr = nullptr;
+  if (static_scratch_address(&ptr) != hipSuccess) return SPARK_ERR_DEVICE;
+  // the same launches as spark_ffn_decode, on the built-in array laid out for one layer; every word
+  // the kernels read from it they have written earlier in this call, so nothing needs clearing
+  const hipError_t e = run_phased(layer, 1, p, spark::FfnTuning(), ptr, 1, static_cast<hipStream_t>(hip_stream));
+  return e == hipSuccess ? SPARK_OK : SPARK_ERR_DEVICE;
 }
 
 spark_status spark_ffn_decode_layers(const spark_ffn_layer* layers, int32_t n_layers, const void* q,

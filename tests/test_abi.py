@@ -168,3 +168,16 @@ def test_tuned_entry_point_validates_like_the_plain_one():
                           None, None, vp(0x10000), ws, ctypes.byref(tune), None)
     assert lib.spark_ffn_decode_layers_tuned(*args(0, ws_bytes)) == 2
     assert lib.spark_ffn_decode_layers_tuned(*args(1, ws_bytes - 1)) == 6
+
+
+def test_static_scratch_entry_point_rejects_on_the_host():
+    """Validation happens before the built-in array is looked up, so these need no GPU."""
+    lib = binding.load_library()
+    vp = ctypes.c_void_p
+    call = lambda layer, batch=1, y=0x5000: lib.spark_ffn_decode_static(
+        ctypes.byref(layer), vp(0x4000), binding.BF16, batch, 256, vp(y) if y else None, None, None, None, None, None, None)
+    assert call(_layer(), y=0) == 1
+    assert call(_layer(), batch=2) == 2                       # one token only
+    assert call(_layer(k=0)) == 3
+    assert call(_layer(d_ff=600000)) == 6                     # scratch need beyond the built-in array
+    assert call(_layer(d_model=328, r=136, wd=binding.F32)) in (2, 5)
