@@ -417,41 +417,50 @@ def attention_bench(torch, binding, synth, dev, with_cpu):
 
 
 def prefill_bench(torch, binding, synth, dev, np):
-    """A 4096-token prompt through one Gemma-2-2B-shaped Spark-FFN layer in chunks of 64 tokens (the
-    paper's prefill set-up: Section 4.3, Appendix C.3), tokens independent N(0,1) rows, so a chunk's
-    union covers nearly every neuron.  The 64 chunks reuse one layer's 85 MB of weights, which stay in
-    the Infinity Cache: the rate is reported as tokens/s and as matrix-core throughput, on the flops the
-    individual masks ask for (2*d_ff*r + 2*m_t*(2*d_model - r) per token) and on the flops the tiles
-    execute (every union row for every token, the V product on three bf16 planes of the activations)."""
-    sh, T, chunk = synth.GEMMA2_2B, 4096, 64
+    """A 4096-token prompt through one Gemma-2-2B-shaped Spark-FFN layer in chunks of 8, 16, 32 and 64
+    tokens (the paper's prefill set-up uses 64: Section 4.3; Appendix C.3 places the point where the
+    batched path turns from memory-bound to FLOP-bound near 64).  Tokens are independent N(0,1) rows, so
+    a chunk's union grows from 49 % of the neurons at 8 tokens to nearly all of them at 64.  All chunks
+    read the same layer's 85 MB of weights, which stay in the Infinity Cache: the rate is reported as
+    tokens/s and as matrix-core throughput, on the flops the individual masks ask for (2*d_ff*r +
+    2*m_t*(2*d_model - r) per token) and on the flops the tiles execute (every union row for every token
+    of the chunk, the V product on three bf16 planes of the activations)."""
+    sh, T = synth.GEMMA2_2B, 4096
     w = synth.ffn_layer(sh, 1000, torch.bfloat16, dev)
     q = synth.tokens(sh, T, 7000, torch.bfloat16, dev)
     layer = binding.make_layer(w[0], w[1], w[2], sh.k)
-    ws = binding.make_prefill_workspace(sh.d_model, sh.d_ff, chunk, dev)
     y = torch.empty(T, sh.d_model, device=dev)
     cnt = torch.zeros(T, dtype=torch.int32, device=dev)
-    ucnt = torch.zeros(T // chunk, dtype=torch.int32, device=dev)
-    binding.spark_ffn_prefill(layer, q, chunk, y, ws, active_count=cnt, union_count=ucnt)
-    torch.cuda.synchronize()
-    m = cnt.cpu().numpy().astype(np.float64)
-    u = ucnt.cpu().numpy().astype(np.float64)
-
-    def step():
-        binding.spark_ffn_prefill(layer, q, chunk, y, ws)
-
-    gpu_s, _ = time_region(step, 20, 3, torch)
-    per = gpu_s / 20
     r2 = sh.d_model - sh.r
-    flops_masks = float(np.sum(2.0 * sh.d_ff * sh.r + 2.0 * m * (r2 + sh.d_model)))
-    flops_tiles = float(np.sum(chunk * (2.0 * sh.d_ff * sh.r + 2.0 * u * (r2 + 3 * sh.d_model))))
-    weight_bytes = float(np.sum(2.0 * (sh.d_ff * sh.r + u * (r2 + sh.d_model))))
-    return {"workload": f"{T} tokens, chunks of {chunk}, one gemma2-2b-shaped layer, bf16",
-            "us_per_call": per * 1e6, "us_per_chunk": per * 1e6 / (T // chunk), "tokens_per_s": T / per,
-            "active_count_mean": float(m.mean()), "union_size_mean": float(u.mean()),
-            "tflops_on_individual_masks": flops_masks / per / 1e12, "tflops_executed_by_tiles": flops_tiles / per / 1e12,
-            "mfma_frac_executed": flops_tiles / per / 1e12 / 2500.0,
-            "weight_bytes_fetched_per_call": weight_bytes, "weight_fetch_gbs": weight_bytes / per / 1e9,
-            "note": "the weight fetch rate may exceed the HBM peak: all chunks read the same layer, from cache"}
+    out = {"workload": f"{T} tokens through one gemma2-2b-shaped layer, bf16, by chunk size", "by_chunk": []}
+    for chunk in (8, 16, 32, 64):
+        ws = binding.make_prefill_workspace(sh.d_model, sh.d_ff, chunk, dev)
+        ucnt = torch.zeros(T // chunk, dtype=torch.int32, device=dev)
+        binding.spark_ffn_prefill(layer, q, chunk, y, ws, active_count=cnt, union_count=ucnt)
+        torch.cuda.synchronize()
+        m = cnt.cpu().numpy().astype(np.float64)
+        u = ucnt.cpu().numpy().astype(np.float64)
+
+        def step():
+            binding.spark_ffn_prefill(layer, q, chunk, y, ws)
+
+        gpu_s, _ = time_region(step, 10, 2, torch)
+        per = gpu_s / 10
+        flops_masks = float(np.sum(2.0 * sh.d_ff * sh.r + 2.0 * m * (r2 + sh.d_model)))
+        flops_tiles = float(np.sum(chunk * (2.0 * sh.d_ff * sh.r + 2.0 * u * (r2 + 3 * sh.d_model))))
+        weight_bytes = float(np.sum(2.0 * (sh.d_ff * sh.r + u * (r2 + sh.d_model))))
+        out["by_chunk"].append({
+            "chunk": chunk, "us_per_call": per * 1e6, "us_per_chunk": per * 1e6 / (T // chunk), "tokens_per_s": T / per,
+            "union_size_mean": float(u.mean()), "tflops_on_individual_masks": flops_masks / per / 1e12,
+            "tflops_executed_by_tiles": flops_tiles / per / 1e12, "mfma_frac_executed": flops_tiles / per / 1e12 / 2500.0,
+            "weight_bytes_fetched_per_call": weight_bytes, "weight_fetch_gbs": weight_bytes / per / 1e9})
+        del ws
+    last = out["by_chunk"][-1]
+    out.update({k: last[k] for k in ("us_per_chunk", "tokens_per_s", "mfma_frac_executed")})
+    out["active_count_mean"] = float(m.mean())
+    out["note"] = ("weights come from cache (all chunks read one layer), so the weight fetch rate may exceed the HBM "
+                   "peak; the top-level figures are those of chunk 64")
+    return out
 
 
 def fp8_bench(torch, binding, synth, dev, np, kind="fp8"):

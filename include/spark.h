@@ -147,10 +147,12 @@ spark_status spark_stat_topk_huber_backward(const void* x, const void* gy, spark
  * path touches half the bytes again).  Each of the three arrays is then one allocation holding
  * the codes [d_ff][cols], one byte each, immediately followed by d_ff fp32 scales, one per
  * row: weight[j][c] = scale[j] * value(code[j][c]).  cols (r, d_model - r, d_model) must be
- * multiples of 16.  Supported for one token per call (batch = 1) through spark_ffn_decode,
- * spark_ffn_decode_layers, spark_ffn_dense_decode_layers and spark_ffn_prefill with chunk 1;
- * other uses return SPARK_ERR_DTYPE.  Arithmetic: codes widened exactly to fp32, fp32
- * products and sums, the row's scale applied to the finished dot product. */
+ * multiples of 16.  One token per call (spark_ffn_decode, spark_ffn_decode_layers,
+ * spark_ffn_dense_decode_layers, spark_ffn_prefill with chunk 1) takes the bandwidth-bound
+ * phase-by-phase kernels; batches and longer chunks are evaluated by the general kernels (a
+ * launch sequence per layer, not tuned); the dense comparison calls take one token only
+ * (SPARK_ERR_DTYPE otherwise).  Arithmetic: codes widened exactly to fp32, fp32 products and
+ * sums, the row's scale applied to the finished dot product. */
 typedef struct {
   int32_t d_model;    /* input / output width                                   */
   int32_t d_ff;       /* number of neurons, >= 2                                */

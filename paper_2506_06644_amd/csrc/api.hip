@@ -81,10 +81,10 @@ spark_status validate_decode(const spark_ffn_layer* L, const void* q, int qdtype
   if (!workspace) return SPARK_ERR_WORKSPACE;
   if (reinterpret_cast<uintptr_t>(workspace) & 255u) return SPARK_ERR_WORKSPACE;
   if (workspace_bytes < spark_ffn_workspace_bytes(L->d_model, L->d_ff, batch)) return SPARK_ERR_WORKSPACE;
-  if (is_code_dtype(L->wdtype)) {
-    // 8-bit weights exist for the one-token path only
+  if (is_code_dtype(L->wdtype) && batch == 1) {
+    // one token with 8-bit weights: the phase-by-phase kernels only (batches take the general kernels)
     const spark::FfnProblem p = make_problem(L, q, qdtype, batch, ldq, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr);
-    if (batch != 1 || !spark::phased_supported(p)) return SPARK_ERR_DTYPE;
+    if (!spark::phased_supported(p)) return SPARK_ERR_DTYPE;
   }
   return SPARK_OK;
 }
@@ -117,6 +117,9 @@ spark::FfnProblem make_problem(const spark_ffn_layer* L, const void* q, int qdty
   return p;
 }
 
+// partial output rows the phase-by-phase region of a caller's workspace holds (64 per layer of a set of launches)
+constexpr int kWorkspacePartRows = spark::kPhasedMaxLayers * 64;
+
 spark::FfnTuning make_tuning(const spark_ffn_tuning* t) {
   spark::FfnTuning u;
   if (t) {
@@ -137,7 +140,8 @@ bool takes_phased(const spark::FfnProblem& p, const spark::FfnTuning& tune) {
 // Runs layers[0..n) phase by phase: the one-token path or the batched path on the matrix cores.
 // `scratch` is laid out for `layer_cap` layers per set of launches (one-token path).
 hipError_t run_phased(const spark_ffn_layer* layers, int32_t n_layers, const spark::FfnProblem& p0,
-                      const spark::FfnTuning& tune, void* scratch, int layer_cap, hipStream_t st, int dense = 0) {
+                      const spark::FfnTuning& tune, void* scratch, int layer_cap, int part_rows, hipStream_t st,
+                      int dense = 0) {
   const void* k1n[256];
   const void* k2n[256];
   const void* vn[256];
@@ -157,7 +161,7 @@ hipError_t run_phased(const spark_ffn_layer* layers, int32_t n_layers, const spa
     if (p.union_count) p.union_count += base;
     if (p.union_idx) p.union_idx += (int64_t)base * p0.d_ff;
     if (p.batch >= 2) e = spark::launch_ffn_phased_batch(p, k1n, k2n, vn, n, tune, scratch, st);
-    else e = spark::launch_ffn_phased(p, k1n, k2n, vn, n, dense, tune, scratch, layer_cap, st);
+    else e = spark::launch_ffn_phased(p, k1n, k2n, vn, n, dense, tune, scratch, layer_cap, part_rows, st);
   }
   return e;
 }
@@ -181,7 +185,7 @@ spark_status decode_layers(const spark_ffn_layer* layers, int32_t n_layers, cons
   const spark::FfnProblem p0 = make_problem(&layers[0], q, qdtype, batch, ldq, y, theta, active_count, active_idx,
                                             union_count, union_idx);
   if (takes_phased(p0, tune)) {
-    const hipError_t e = run_phased(layers, n_layers, p0, tune, ws.phased, spark::kPhasedMaxLayers, st);
+    const hipError_t e = run_phased(layers, n_layers, p0, tune, ws.phased, spark::kPhasedMaxLayers, kWorkspacePartRows, st);
     return e == hipSuccess ? SPARK_OK : SPARK_ERR_DEVICE;
   }
   for (int32_t l = 0; l < n_layers; ++l) {
@@ -319,11 +323,12 @@ spark_status spark_ffn_decode_static(const spark_ffn_layer* layer, const void* q
   if (!spark::phased_supported(p)) return SPARK_ERR_SHAPE;
   if (spark::phased_scratch_bytes(layer->d_model, layer->d_ff, 1) > (size_t)SPARK_STATIC_SCRATCH_BYTES)
     return SPARK_ERR_WORKSPACE;
+  const int part_rows = spark::phased_part_rows(SPARK_STATIC_SCRATCH_BYTES, layer->d_model, layer->d_ff, 1);
   void* ptr = nullptr;
   if (static_scratch_address(&ptr) != hipSuccess) return SPARK_ERR_DEVICE;
   // the same launches as spark_ffn_decode, on the built-in array laid out for one layer; every word
   // the kernels read from it they have written earlier in this call, so nothing needs clearing
-  const hipError_t e = run_phased(layer, 1, p, spark::FfnTuning(), ptr, 1, static_cast<hipStream_t>(hip_stream));
+  const hipError_t e = run_phased(layer, 1, p, spark::FfnTuning(), ptr, 1, part_rows, static_cast<hipStream_t>(hip_stream));
   return e == hipSuccess ? SPARK_OK : SPARK_ERR_DEVICE;
 }
 
@@ -378,7 +383,7 @@ spark_status spark_ffn_prefill(const spark_ffn_layer* layer, const void* q, spar
   auto one_chunk = [&](int64_t t0, int64_t c, int32_t batch) {
     const spark::FfnProblem p = problem_at(t0, c, batch);
     const spark::FfnWorkspace ws = spark::carve_workspace(workspace, layer->d_model, layer->d_ff, batch);
-    if (takes_phased(p, tune)) return run_phased(layer, 1, p, tune, ws.phased, spark::kPhasedMaxLayers, st);
+    if (takes_phased(p, tune)) return run_phased(layer, 1, p, tune, ws.phased, spark::kPhasedMaxLayers, kWorkspacePartRows, st);
     return spark::launch_ffn_general(p, ws, 0, st);
   };
   int64_t c = 0;
@@ -434,13 +439,14 @@ spark_status spark_ffn_dense_decode_layers(const spark_ffn_layer* layers, int32_
         layers[l].gelu != layers[0].gelu)
       return SPARK_ERR_SHAPE;
   }
+  if (is_code_dtype(layers[0].wdtype) && batch != 1) return SPARK_ERR_DTYPE;  // dense comparison of 8-bit weights: one token
   const int64_t d_model = layers[0].d_model;
   const spark::FfnWorkspace ws = spark::carve_workspace(workspace, layers[0].d_model, layers[0].d_ff, batch);
   const spark::FfnProblem p0 =
       make_problem(&layers[0], q, qdtype, batch, ldq, y, nullptr, nullptr, nullptr, nullptr, nullptr);
   if (spark::phased_supported(p0)) {
     const hipError_t e = run_phased(layers, n_layers, p0, spark::FfnTuning(), ws.phased, spark::kPhasedMaxLayers,
-                                    static_cast<hipStream_t>(hip_stream), 1);
+                                    kWorkspacePartRows, static_cast<hipStream_t>(hip_stream), 1);
     return e == hipSuccess ? SPARK_OK : SPARK_ERR_DEVICE;
   }
   for (int32_t l = 0; l < n_layers; ++l) {

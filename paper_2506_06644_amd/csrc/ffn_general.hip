@@ -18,6 +18,31 @@ namespace {
 constexpr int kBlock = 256;
 constexpr int kWavesPerBlock = kBlock / kWave;
 
+// 8-bit weight arrays carry one fp32 scale per row behind the last row of codes; other types none.
+template <typename WT>
+__device__ __forceinline__ float row_scale(const WT* w, int rows, int cols, int j) {
+  if constexpr (sizeof(WT) == 1) return reinterpret_cast<const float*>(reinterpret_cast<const char*>(w) + (size_t)rows * (size_t)cols)[j];
+  else return 1.f;
+}
+// two consecutive weights of a row (column c0 even) as floats
+template <typename WT>
+__device__ __forceinline__ void load_pair(const WT* p, float& w0, float& w1) {
+  if constexpr (sizeof(WT) == 4) {
+    const float2 w = *reinterpret_cast<const float2*>(p);
+    w0 = w.x;
+    w1 = w.y;
+  } else if constexpr (sizeof(WT) == 2) {
+    const uint32_t w = *reinterpret_cast<const uint32_t*>(p);
+    w0 = bf16_lo(w);
+    w1 = bf16_hi(w);
+  } else {
+    Vec16<WT> v;
+    v.raw = u32x4{(uint32_t)*reinterpret_cast<const uint16_t*>(p), 0u, 0u, 0u};
+    w0 = v.get(0);
+    w1 = v.get(1);
+  }
+}
+
 // ---------------------------------------------------------------------------------- predict
 template <typename WT, int TB>
 __global__ __launch_bounds__(kBlock) void predict_kernel(const WT* __restrict__ k1n, int d_ff, int r,
@@ -50,7 +75,7 @@ __global__ __launch_bounds__(kBlock) void predict_kernel(const WT* __restrict__ 
 #pragma unroll
       for (int t = 0; t < TB; ++t) {
         const float tot = wave_sum(acc[t]);
-        if (lane == 0 && b0 + t < B) S[(int64_t)(b0 + t) * d_ff + j] = tot;
+        if (lane == 0 && b0 + t < B) S[(int64_t)(b0 + t) * d_ff + j] = tot * row_scale<WT>(k1n, d_ff, r, j);
       }
     }
   }
@@ -145,7 +170,7 @@ __global__ __launch_bounds__(kBlock) void k2_kernel(const WT* __restrict__ k2n, 
       }
 #pragma unroll
       for (int t = 0; t < TB; ++t) {
-        const float g = any ? wave_sum(acc[t]) : 0.f;
+        const float g = any ? wave_sum(acc[t]) * row_scale<WT>(k2n, d_ff, r2, j) : 0.f;
         if (lane == 0 && b0 + t < B)
           uact[(int64_t)m * B + b0 + t] = a[t] > 0.f ? gelu(a[t], gelu_kind) * g : 0.f;
       }
@@ -157,7 +182,7 @@ __global__ __launch_bounds__(kBlock) void k2_kernel(const WT* __restrict__ k2n, 
 // Workgroup = 64 output columns x one slice of the union rows.  Thread t: column pair
 // t % 32, row slot t / 32 (8 rows in flight per workgroup).
 template <typename WT, int BT>
-__global__ __launch_bounds__(kBlock) void v_kernel(const WT* __restrict__ vn, int d_model, int B,
+__global__ __launch_bounds__(kBlock) void v_kernel(const WT* __restrict__ vn, int d_ff, int d_model, int B,
                                                    const float* __restrict__ uact,
                                                    const int32_t* __restrict__ uidx,
                                                    const int32_t* __restrict__ ucount,
@@ -183,20 +208,13 @@ __global__ __launch_bounds__(kBlock) void v_kernel(const WT* __restrict__ vn, in
       const int j = uidx[m];
       const WT* p = vn + (int64_t)j * d_model + c0;
       float w0, w1;
-      if (sizeof(WT) == 2) {
-        const uint32_t w = *reinterpret_cast<const uint32_t*>(p);
-        w0 = bf16_lo(w);
-        w1 = bf16_hi(w);
-      } else {
-        const float2 w = *reinterpret_cast<const float2*>(p);
-        w0 = w.x;
-        w1 = w.y;
-      }
+      load_pair<WT>(p, w0, w1);
+      const float sv = row_scale<WT>(vn, d_ff, d_model, j);
       const float* up = uact + (int64_t)m * B;
 #pragma unroll
       for (int b = 0; b < BT; ++b) {
         if (b < B) {
-          const float u = up[b];
+          const float u = up[b] * sv;
           acc[b][0] += u * w0;
           acc[b][1] += u * w1;
         }
@@ -580,6 +598,9 @@ hipError_t launch_general_t(const FfnProblem& p, const FfnWorkspace& ws, int den
   const int B = p.batch;
   const int r2 = p.d_model - p.r;
 
+  if constexpr (sizeof(WT) == 1) {
+    if (dense) return hipErrorInvalidValue;  // (8-bit weights: the dense comparison exists on the one-token path only)
+  }
   if (dense && B == 1) {
     hipLaunchKernelGGL((dense_rows_kernel<WT>), dim3(2048), dim3(256), (size_t)p.d_model * 4, st, k1n, k2n, p.d_ff,
                        p.r, r2, p.q, p.q_bf16, ws.S, ws.uact, ws.flags);
@@ -659,7 +680,7 @@ hipError_t launch_general_t(const FfnProblem& p, const FfnWorkspace& ws, int den
     const dim3 grid((p.d_model + 63) / 64, ws.ksplit);
     float* out = ws.ksplit == 1 ? p.y : ws.part;
 #define SPARK_LAUNCH_V(BT)                                                                          \
-  hipLaunchKernelGGL((v_kernel<WT, BT>), grid, dim3(kBlock), 0, st, vn, p.d_model, B, ws.uact, ws.uidx, \
+  hipLaunchKernelGGL((v_kernel<WT, BT>), grid, dim3(kBlock), 0, st, vn, p.d_ff, p.d_model, B, ws.uact, ws.uidx, \
                      ws.ucount, out)
     if (B == 1) SPARK_LAUNCH_V(1);
     else if (B <= 4) SPARK_LAUNCH_V(4);
@@ -726,6 +747,8 @@ FfnWorkspace carve_workspace(void* base, int d_model, int d_ff, int batch) {
 }
 
 hipError_t launch_ffn_general(const FfnProblem& p, const FfnWorkspace& ws, int dense, hipStream_t st) {
+  if (p.w_fp8 == 2) return launch_general_t<i8_t>(p, ws, dense, st);
+  if (p.w_fp8) return launch_general_t<fp8_t>(p, ws, dense, st);
   return p.w_bf16 ? launch_general_t<bf16_t>(p, ws, dense, st) : launch_general_t<float>(p, ws, dense, st);
 }
 

@@ -27,6 +27,8 @@ namespace spark {
 namespace {
 
 constexpr int kMaxRPB = 256;  // most predictor rows per workgroup
+constexpr int kMaxNBC = 64;   // gather blocks per layer the scratch is sized for at the full layer count
+constexpr int kMostNBC = 128;  // most gather blocks per layer (short stacks use the spare partial rows)
 
 struct PhasedParams {
   const void* k1n[kPhasedMaxLayers];
@@ -427,22 +429,27 @@ __global__ __launch_bounds__(NW * kWave, OCC) void gather_layers_kernel(const Ph
 }
 
 // ---------------------------------------------------------------------------------- reduce
-// y[l][c] = sum over the layer's gather blocks of part[l][blk][c], in block order.
+// y[l][c] = sum over the layer's gather blocks of part[l][blk][c].  Workgroup = 64 columns x 4
+// slices of the blocks: a thread sums its slice in block order (16 loads in flight at a time), and
+// the four slice sums of a column are added in slice order.
 __global__ __launch_bounds__(256) void reduce_layers_kernel(const PhasedParams P) {
-  const int l = blockIdx.y, c = blockIdx.x * 256 + threadIdx.x;
-  if (c >= P.d_model) return;
-  const float* p = P.part + (size_t)l * P.NBC * P.d_model + c;
+  constexpr int PER = 16;
+  __shared__ float red[4][kWave];
+  const int l = blockIdx.y, cg = threadIdx.x & (kWave - 1), sl = threadIdx.x / kWave;
+  const int c = blockIdx.x * kWave + cg;
+  const int per = (P.NBC + 3) / 4, b1 = min(P.NBC, (sl + 1) * per);
+  const float* p = P.part + (size_t)l * P.NBC * P.d_model + (c < P.d_model ? c : 0);
   float acc = 0.f;
-  int b = 0;
-  for (; b + 8 <= P.NBC; b += 8) {
-    float t[8];
+  for (int b0 = sl * per; b0 < b1; b0 += PER) {
+    float t[PER];
 #pragma unroll
-    for (int i = 0; i < 8; ++i) t[i] = p[(size_t)(b + i) * P.d_model];
+    for (int i = 0; i < PER; ++i) t[i] = b0 + i < b1 ? p[(size_t)(b0 + i) * P.d_model] : 0.f;
 #pragma unroll
-    for (int i = 0; i < 8; ++i) acc += t[i];
+    for (int i = 0; i < PER; ++i) acc += t[i];
   }
-  for (; b < P.NBC; ++b) acc += p[(size_t)b * P.d_model];
-  P.y[(size_t)l * P.d_model + c] = acc;
+  red[sl][cg] = acc;
+  __syncthreads();
+  if (sl == 0 && c < P.d_model) P.y[(size_t)l * P.d_model + c] = ((red[0][cg] + red[1][cg]) + red[2][cg]) + red[3][cg];
 }
 
 // ---------------------------------------------------------------------------------- select
@@ -485,14 +492,15 @@ size_t align256(size_t v) { return (v + 255) / 256 * 256; }
 struct PhasedLayout {
   size_t scores, stats, part, total;
 };
-constexpr int kMaxNBC = 64;  // most gather blocks per layer
 
-PhasedLayout phased_layout(int d_model, int d_ff, int layer_cap) {
+// Scratch of a set of launches over up to `layer_cap` layers, with room for `part_rows` partial
+// output rows in all.
+PhasedLayout phased_layout(int d_model, int d_ff, int layer_cap, int part_rows) {
   PhasedLayout s;
   size_t o = 0;
   s.scores = o; o += align256((size_t)layer_cap * (size_t)d_ff * 4);
   s.stats = o;  o += align256((size_t)layer_cap * (size_t)((d_ff + 15) / 16) * 8);
-  s.part = o;   o += align256((size_t)layer_cap * kMaxNBC * (size_t)d_model * 4);
+  s.part = o;   o += align256((size_t)part_rows * (size_t)d_model * 4);
   s.total = o;
   return s;
 }
@@ -558,7 +566,16 @@ hipError_t launch_gather_index(const PhasedParams& P, dim3 grid, hipStream_t st)
 
 }  // namespace
 
-size_t phased_scratch_bytes(int d_model, int d_ff, int layer_cap) { return phased_layout(d_model, d_ff, layer_cap).total; }
+size_t phased_scratch_bytes(int d_model, int d_ff, int layer_cap) {
+  return phased_layout(d_model, d_ff, layer_cap, layer_cap * kMaxNBC).total;
+}
+
+int phased_part_rows(size_t scratch_bytes, int d_model, int d_ff, int layer_cap) {
+  const size_t fixed = phased_layout(d_model, d_ff, layer_cap, 0).total;
+  if (scratch_bytes <= fixed) return 0;
+  const size_t rows = (scratch_bytes - fixed) / ((size_t)d_model * 4);
+  return (int)(rows < (size_t)layer_cap * kMostNBC ? rows : (size_t)layer_cap * kMostNBC);
+}
 
 bool phased_supported(const FfnProblem& p) {
   const int vec = weight_vec(p);
@@ -569,9 +586,10 @@ bool phased_supported(const FfnProblem& p) {
 
 hipError_t launch_ffn_phased(const FfnProblem& p0, const void* const* k1n, const void* const* k2n,
                              const void* const* vn, int n_layers, int dense, const FfnTuning& tune, void* scratch,
-                             int layer_cap, hipStream_t st) {
+                             int layer_cap, int part_rows, hipStream_t st) {
   layer_cap = max(1, min(layer_cap, kPhasedMaxLayers));
-  const PhasedLayout lay = phased_layout(p0.d_model, p0.d_ff, layer_cap);
+  if (part_rows < layer_cap) return hipErrorInvalidValue;
+  const PhasedLayout lay = phased_layout(p0.d_model, p0.d_ff, layer_cap, part_rows);
   const int phases = (tune.phases & 7) ? (tune.phases & 7) : 7;
   int gv = gather_variant(p0);
   if (gv < 0) return hipErrorInvalidValue;
@@ -625,7 +643,9 @@ hipError_t launch_ffn_phased(const FfnProblem& p0, const void* const* k1n, const
       while (npb > 64 && (long long)L * ((p0.d_ff + npb - 1) / npb) < 600) npb -= 64;
     }
     npb = max(64, min(1024, npb / 64 * 64));
-    while ((p0.d_ff + npb - 1) / npb > kMaxNBC) npb += 64;
+    // partial rows: the scratch holds part_rows of them, shared by the L layers of this set
+    const int nbc_cap = max(1, min(kMostNBC, part_rows / L));
+    while ((p0.d_ff + npb - 1) / npb > nbc_cap) npb += 64;
     if (npb > 1024) return hipErrorInvalidValue;
     P.RPB = rpb;
     P.NBA = (p0.d_ff + rpb - 1) / rpb;
@@ -658,7 +678,7 @@ hipError_t launch_ffn_phased(const FfnProblem& p0, const void* const* k1n, const
     }
     if (err != hipSuccess) return err;
     if (!(phases & 4)) continue;
-    hipLaunchKernelGGL(reduce_layers_kernel, dim3((p0.d_model + 255) / 256, L), dim3(256), 0, st, P);
+    hipLaunchKernelGGL(reduce_layers_kernel, dim3((p0.d_model + kWave - 1) / kWave, L), dim3(256), 0, st, P);
     if (P.count || P.idx || P.ucount || P.uidx)
       hipLaunchKernelGGL(select_layers_kernel, dim3(L), dim3(1024), 0, st, P);
     err = hipGetLastError();

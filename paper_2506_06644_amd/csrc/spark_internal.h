@@ -71,14 +71,17 @@ struct FfnTuning {
 
 // Phase-by-phase batch-1 path: predictor sweep, gather, reduce as ordinary launches over up
 // to `layer_cap` (<= kPhasedMaxLayers) layers at a time (longer stacks are chained).  `scratch`
-// holds phased_scratch_bytes(d_model, d_ff, layer_cap) bytes, 256-byte aligned, and needs no
-// initialisation.
+// is 256-byte aligned, needs no initialisation and has room for `part_rows` partial output rows
+// (>= layer_cap) behind the scores and block statistics: phased_scratch_bytes gives the size with 64
+// partial rows per layer of the cap, phased_part_rows the rows (at most 128 per layer) that a scratch
+// of a given size holds.
 constexpr int kPhasedMaxLayers = 64;
 size_t phased_scratch_bytes(int d_model, int d_ff, int layer_cap);
+int phased_part_rows(size_t scratch_bytes, int d_model, int d_ff, int layer_cap);
 bool phased_supported(const FfnProblem& p);
 hipError_t launch_ffn_phased(const FfnProblem& p0, const void* const* k1n, const void* const* k2n,
                              const void* const* vn, int n_layers, int dense, const FfnTuning& tune, void* scratch,
-                             int layer_cap, hipStream_t st);
+                             int layer_cap, int part_rows, hipStream_t st);
 
 // Phase-by-phase path for batches of 2..64 tokens on the matrix cores (bf16 weights and
 // tokens), up to kBatchMaxLayers layers per set of launches.

@@ -139,13 +139,18 @@ def test_prefill_and_8bit_weights_reject_bad_arguments_before_launch():
     assert prefill(_layer(), n_tokens=0) == 0                 # nothing to do
     assert binding.ffn_prefill_workspace_bytes(256, 1024, 16) >= binding.ffn_workspace_bytes(256, 1024, 16)
     assert binding.ffn_prefill_workspace_bytes(256, 1024, 16) >= binding.ffn_workspace_bytes(256, 1024, 1)
-    # 8-bit weight codes: one token per call, rows of whole 16-byte chunks
+    # 8-bit weight codes: rows of whole 16-byte chunks, tokens cannot be codes, the dense comparison takes one token
     f8 = binding.FP8_E4M3
-    assert _decode(_layer(wd=f8), batch=2) == 4
     assert _decode(_layer(wd=f8, r=136, d_model=328), ldq=328) == 5
-    assert prefill(_layer(wd=f8), chunk=4) == 4
-    assert _decode(_layer(wd=f8), qd=f8) == 4                 # tokens cannot be codes
-    assert _decode(_layer(wd=binding.INT8), batch=2) == 4 and _decode(_layer(wd=binding.INT8), qd=binding.INT8) == 4
+    assert _decode(_layer(wd=f8), qd=f8) == 4
+    assert _decode(_layer(wd=binding.INT8), qd=binding.INT8) == 4
+    for wd in (f8, binding.INT8):
+        layer = _layer(wd=wd)
+        ws_bytes = binding.ffn_workspace_bytes(256, 1024, 2)
+        assert lib.spark_ffn_dense_decode_layers(ctypes.byref(layer), 1, vp(0x4000), binding.BF16, 2, 256, vp(0x5000),
+                                                 vp(0x10000), ws_bytes, None) == 4
+        assert lib.spark_ffn_dense_decode(ctypes.byref(layer), vp(0x4000), binding.BF16, 1, 256, vp(0x5000),
+                                          vp(0x10000), ws_bytes, None) == 4
 
 
 def test_stat_topk_needs_no_workspace_and_copy_validates():

@@ -40,15 +40,15 @@ def _quantised_stack(shape, n_layers, seed, kind="fp8"):
 
 
 def _run(shape, packed, q, via_layers, dense=False, gelu=binding.GELU_ERF, kind="fp8"):
-    L = len(packed)
+    L, B = len(packed), q.shape[0]
     layers = [binding.make_layer_fp8(p[0], p[1], p[2], shape.d_model, shape.d_ff, shape.r, shape.k, gelu, KINDS[kind][0])
               for p in packed]
     qd = q.to(DEV)
-    ws = binding.make_workspace(shape.d_model, shape.d_ff, 1, DEV)
-    y = torch.full((L, 1, shape.d_model), float("nan"), device=DEV)
-    theta = torch.zeros(L, 1, device=DEV)
-    cnt = torch.zeros(L, 1, dtype=torch.int32, device=DEV)
-    idx = torch.full((L, 1, shape.d_ff), -1, dtype=torch.int32, device=DEV)
+    ws = binding.make_workspace(shape.d_model, shape.d_ff, B, DEV)
+    y = torch.full((L, B, shape.d_model), float("nan"), device=DEV)
+    theta = torch.zeros(L, B, device=DEV)
+    cnt = torch.zeros(L, B, dtype=torch.int32, device=DEV)
+    idx = torch.full((L, B, shape.d_ff), -1, dtype=torch.int32, device=DEV)
     ucnt = torch.zeros(L, dtype=torch.int32, device=DEV)
     uidx = torch.full((L, shape.d_ff), -1, dtype=torch.int32, device=DEV)
     if dense:
@@ -98,6 +98,50 @@ def test_dense_evaluation_and_tanh_gelu(kind):
     check_ffn_against_oracle(sh, deq, q, out, TOL_BF16_TIGHT, gelu=oracle.GELU_TANH, what="fp8 tanh")
 
 
+@pytest.mark.parametrize("kind", ["fp8", "int8"])
+@pytest.mark.parametrize("shape,batch", [(synth.TINY, 2), (synth.TINY, 16), (synth.FFNShape("odd", 1040, 1000, 272, 77), 5),
+                                         (synth.GEMMA2_2B, 4), (synth.TINY, 64)])
+def test_batches_take_the_general_kernels(shape, batch, kind):
+    """More than one token with 8-bit weight rows: every token against the oracle on the dequantised
+    weights, the union list against the oracle's, and y[b] equal to the one-token result."""
+    packed, deq = _quantised_stack(shape, 2, 340, kind)
+    for qdtype in (torch.bfloat16, torch.float32):
+        q = synth.tokens(shape, batch, 341 + batch, qdtype)
+        for via_layers in (False, True):
+            out = _run(shape, packed, q, via_layers, kind=kind)
+            check_ffn_against_oracle(shape, deq, q, out, TOL_BF16_TIGHT, what=f"{kind} B={batch} {qdtype}")
+        solo = _run(shape, packed, q[1:2], True, kind=kind)
+        assert np.array_equal(solo["idx"][:, 0], out["idx"][:, 1])
+        assert np.linalg.norm(solo["y"][:, 0] - out["y"][:, 1]) <= 1e-6 * np.linalg.norm(solo["y"][:, 0])
+
+
+@pytest.mark.parametrize("kind", ["fp8", "int8"])
+def test_prefill_in_chunks(kind):
+    """A prompt through a layer with 8-bit weights in chunks of 4 (last chunk shorter): every token and
+    every chunk's union against the oracle."""
+    sh = synth.TINY
+    packed, deq = _quantised_stack(sh, 1, 350, kind)
+    layer = binding.make_layer_fp8(*packed[0], sh.d_model, sh.d_ff, sh.r, sh.k, code_dtype=KINDS[kind][0])
+    T, chunk = 11, 4
+    q = synth.tokens(sh, T, 351, torch.bfloat16)
+    ws = binding.make_prefill_workspace(sh.d_model, sh.d_ff, chunk, DEV)
+    nch = (T + chunk - 1) // chunk
+    y = torch.full((T, sh.d_model), float("nan"), device=DEV)
+    theta = torch.zeros(T, device=DEV)
+    cnt = torch.zeros(T, dtype=torch.int32, device=DEV)
+    idx = torch.full((T, sh.d_ff), -1, dtype=torch.int32, device=DEV)
+    ucnt = torch.zeros(nch, dtype=torch.int32, device=DEV)
+    uidx = torch.full((nch, sh.d_ff), -1, dtype=torch.int32, device=DEV)
+    binding.spark_ffn_prefill(layer, q.to(DEV), chunk, y, ws, theta, cnt, idx, ucnt, uidx)
+    torch.cuda.synchronize()
+    for c in range(nch):
+        t0, t1 = c * chunk, min(T, (c + 1) * chunk)
+        sub = dict(y=y[None, t0:t1].cpu().numpy(), theta=theta[None, t0:t1].cpu().numpy(),
+                   count=cnt[None, t0:t1].cpu().numpy(), idx=idx[None, t0:t1].cpu().numpy(),
+                   ucount=ucnt[c:c + 1].cpu().numpy(), uidx=uidx[c:c + 1].cpu().numpy())
+        check_ffn_against_oracle(sh, deq, q[t0:t1], sub, TOL_BF16_TIGHT, what=f"{kind} prefill chunk {c}")
+
+
 def test_prefill_token_by_token_and_unsupported_uses():
     sh = synth.TINY
     packed, deq = _quantised_stack(sh, 1, 330)
@@ -111,9 +155,8 @@ def test_prefill_token_by_token_and_unsupported_uses():
     for t in range(5):
         o = oracle.spark_ffn(*(synth.to_oracle(a) for a in deq[0]), synth.to_oracle(q)[t], sh.k, skip_inactive=True)
         assert np.linalg.norm(y[t].cpu().numpy() - o.y) <= TOL_BF16_TIGHT * np.linalg.norm(o.y)
-    # more than one token per call, and the single-layer dense call, are not offered for 8-bit weights
-    for call in (lambda: binding.spark_ffn_decode(layer, qd[:2], y[:2], ws),
-                 lambda: binding.spark_ffn_prefill(layer, qd, 4, y, ws),
+    # the dense comparison calls take one token, and only through the layers entry point
+    for call in (lambda: binding.spark_ffn_dense_decode_layers([layer], qd[:2], y[None, :2], ws),
                  lambda: binding.spark_ffn_dense_decode(layer, qd[:1], y[:1], ws)):
         with pytest.raises(binding.SparkError) as e:
             call()
