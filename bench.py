@@ -455,6 +455,21 @@ def prefill_bench(torch, binding, synth, dev, np):
             "tflops_executed_by_tiles": flops_tiles / per / 1e12, "mfma_frac_executed": flops_tiles / per / 1e12 / 2500.0,
             "weight_bytes_fetched_per_call": weight_bytes, "weight_fetch_gbs": weight_bytes / per / 1e9})
         del ws
+    # comparison point, library GEMMs (not this library's code): the same 4096 tokens through the same
+    # layer evaluated densely as three bf16 matrix products (scores and gate products for every neuron,
+    # then all of V) - what a matrix-core GPU does with a long prompt when it ignores the sparsity
+    k1t, k2t, vt = w[0].t().contiguous(), w[1].t().contiguous(), w[2]
+
+    def dense_gemms():
+        s_ = q[:, :sh.r] @ k1t
+        g_ = q[:, sh.r:] @ k2t
+        return (torch.nn.functional.gelu(s_.float()).to(torch.bfloat16) * g_) @ vt
+
+    d_s, _ = time_region(dense_gemms, 10, 3, torch)
+    out["dense_library_gemms"] = {"us_per_call": d_s / 10 * 1e6, "tokens_per_s": T / (d_s / 10),
+                                  "tflops": 2.0 * T * sh.d_ff * 2 * sh.d_model / (d_s / 10) / 1e12,
+                                  "note": "torch matmuls on bf16, dense layer without the top-k: a reference for what the "
+                                          "matrix cores deliver on a long prompt, not a result of this library"}
     last = out["by_chunk"][-1]
     out.update({k: last[k] for k in ("us_per_chunk", "tokens_per_s", "mfma_frac_executed")})
     out["active_count_mean"] = float(m.mean())
