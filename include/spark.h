@@ -347,10 +347,11 @@ typedef struct {
                                        16 x the tiles per workgroup of the predict step              */
   int32_t neurons_per_gather_block; /* one token: neurons per workgroup of the gather; batches: 16 x
                                        the tiles per workgroup of the k2 step                        */
-  int32_t variant;                  /* one token: 1 = the 8-wave gather variant; batches: row slices
-                                       of the V step, plus 100 to keep the k-split kernels for every
-                                       batch size, plus 200 to take the streamed kernels (at most 16
-                                       tokens) however small the launch                              */
+  int32_t variant;                  /* one token: 1 = the 8-wave gather variant; batches: 100 x kernel
+                                       family + row slices of the V step, families 1 = k-split kernels
+                                       for every batch size, 2 = streamed kernels (at most 16 tokens)
+                                       however small the launch, 3 = automatic without the whole-row
+                                       kernels, 4 = whole-row kernels wherever they are compiled     */
 } spark_ffn_tuning;
 
 /* spark_ffn_decode_layers with pinned choices (`tuning` is a host pointer, NULL = automatic). */

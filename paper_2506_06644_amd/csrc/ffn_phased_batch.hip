@@ -57,7 +57,6 @@ struct BatchParams {
   float* ST;                   // [L][d_ff][BP] the same, neuron-major (read by k2: one 64-byte piece per row and token block)
   float* thetas;               // [L][B]
   unsigned long long* tmask;   // [L][B][kMaxWords]  mask of every token
-  unsigned long long* umask;   // [L][kMaxWords]  union of the tokens' masks
   int32_t* urow;               // [L][d_ff]       union rank -> neuron
   int32_t* utotal;             // [L]             union size
   uint16_t* up;                // [kPlanes][L][ldu / 8][B][8]  bf16 planes of u (u = sum of the planes): union ranks in
@@ -401,10 +400,15 @@ __global__ __launch_bounds__(kSelThreads) void select_batch_kernel(const BatchPa
 }
 
 // One workgroup per layer: the union of the tokens' masks, word by word (plain stores and
-// loads: no atomics, and nothing to clear beforehand).
+// loads: no atomics, and nothing to clear beforehand), then the union's size and the neuron of
+// every union rank in ascending order (prefix sums of the words' bit counts; a thread lists the
+// bits of one 16-bit quarter of a word), which is what the k2 workgroups start from.
 __global__ __launch_bounds__(4 * kMaxWords) void union_batch_kernel(const BatchParams P) {
   __shared__ unsigned long long part[4][kMaxWords];
+  __shared__ int wprefix[kMaxWords + 1];
+  __shared__ int wave_sum[kMaxWords / kWave];
   const int l = blockIdx.x, w = threadIdx.x % kMaxWords, q = threadIdx.x / kMaxWords;  // q: every 4th token
+  const int lane = threadIdx.x & (kWave - 1);
   const bool live = w < (P.d_ff + 63) / 64;
   const unsigned long long* tm = P.tmask + (size_t)l * P.B * kMaxWords + w;
   unsigned long long m = 0ull;
@@ -414,61 +418,53 @@ __global__ __launch_bounds__(4 * kMaxWords) void union_batch_kernel(const BatchP
   }
   part[q][w] = m;
   __syncthreads();
-  if (q == 0 && live) P.umask[(size_t)l * kMaxWords + w] = part[0][w] | part[1][w] | part[2][w] | part[3][w];
-}
-
-// -------------------------------------------------------------------------------------- k2
-// Shared opening of the k2 kernels: prefix sums of the union mask's words, the union size, and
-// the neuron of every union rank the workgroup handles (ranks past the end repeat the last
-// one), in LDS and, for the real ranks, in urow / uidx.  Returns the union size; workgroups
-// with no tile to do get -1.
-template <int THREADS>
-__device__ __forceinline__ int k2_ranks_to_rows(const BatchParams& P, int l, int tile0, int* wprefix, int* rowidx) {
-  const int tid = threadIdx.x, lane = tid & (kWave - 1);
-  const int wave = __builtin_amdgcn_readfirstlane(tid / kWave);
-  const int nwords = (P.d_ff + 63) / 64;
-  const unsigned long long* um = P.umask + (size_t)l * kMaxWords;
-  if (wave == 0) {
-    int running = 0;
-    for (int base = 0; base < nwords; base += kWave) {
-      const int c = base + lane < nwords ? __popcll(um[base + lane]) : 0;
-      int inc = c;
+  const unsigned long long word = part[0][w] | part[1][w] | part[2][w] | part[3][w];
+  int inc = 0;
+  if (q == 0) {  // the first kMaxWords threads: one word each, inclusive prefix sums inside each wave
+    inc = __popcll(word);
 #pragma unroll
-      for (int o = 1; o < kWave; o <<= 1) {
-        const int t = __shfl_up(inc, o, kWave);
-        if (lane >= o) inc += t;
-      }
-      if (base + lane < nwords) wprefix[base + lane + 1] = running + inc;
-      running += __shfl(inc, kWave - 1, kWave);
+    for (int o = 1; o < kWave; o <<= 1) {
+      const int t = __shfl_up(inc, o, kWave);
+      if (lane >= o) inc += t;
     }
-    if (lane == 0) wprefix[0] = 0;
+    if (lane == kWave - 1) wave_sum[w / kWave] = inc;
   }
   __syncthreads();
-  const int m_total = wprefix[nwords];
-  const int tiles_total = (m_total + 15) / 16;
-  if (blockIdx.x == 0 && tid == 0) {
+  if (q == 0) {
+    int before = 0;
+#pragma unroll
+    for (int i = 0; i < kMaxWords / kWave; ++i) before += i < w / kWave ? wave_sum[i] : 0;
+    wprefix[w + 1] = before + inc;
+    if (w == 0) wprefix[0] = 0;
+  }
+  __syncthreads();
+  const int m_total = wprefix[kMaxWords];
+  if (threadIdx.x == 0) {
     P.utotal[l] = m_total;
     if (P.ucount) P.ucount[l] = m_total;
   }
-  if (tile0 >= tiles_total) return -1;
-  for (int i = tid; i < P.TPW2 * 16 + 16; i += THREADS) {
-    const int rho = tile0 * 16 + i;
-    const int rc = min(rho, m_total - 1);
-    int lo = 0, hi = nwords - 1;  // last word with wprefix[word] <= rc
-    while (lo < hi) {
-      const int mid = (lo + hi + 1) >> 1;
-      if (wprefix[mid] <= rc) lo = mid;
-      else hi = mid - 1;
-    }
-    unsigned long long bits = um[lo];
-    for (int k = rc - wprefix[lo]; k > 0; --k) bits &= bits - 1;
-    const int j = lo * 64 + __builtin_ctzll(bits);
-    rowidx[i] = j;
-    if (rho < m_total && i < P.TPW2 * 16) {
-      P.urow[(size_t)l * P.d_ff + rho] = j;
-      if (P.uidx) P.uidx[(size_t)l * P.d_ff + rho] = j;
-    }
+  unsigned bits = (unsigned)(word >> (16 * q)) & 0xffffu;
+  int at = wprefix[w] + __popcll(word & ((1ull << (16 * q)) - 1ull));
+  while (bits) {
+    const int j = w * 64 + 16 * q + __builtin_ctz(bits);
+    bits &= bits - 1;
+    P.urow[(size_t)l * P.d_ff + at] = j;
+    if (P.uidx) P.uidx[(size_t)l * P.d_ff + at] = j;
+    ++at;
   }
+}
+
+// -------------------------------------------------------------------------------------- k2
+// Shared opening of the k2 kernels: the union size and, in LDS, the neuron of every union rank
+// the workgroup handles (ranks past the end repeat the last one).  Returns the union size;
+// workgroups with no tile to do get -1.
+template <int THREADS>
+__device__ __forceinline__ int k2_ranks_to_rows(const BatchParams& P, int l, int tile0, int* rowidx) {
+  const int m_total = P.utotal[l];
+  const int tiles_total = (m_total + 15) / 16;
+  if (tile0 >= tiles_total) return -1;
+  const int32_t* urow = P.urow + (size_t)l * P.d_ff;
+  for (int i = threadIdx.x; i < P.TPW2 * 16 + 16; i += THREADS) rowidx[i] = urow[min(tile0 * 16 + i, m_total - 1)];
   __syncthreads();
   return m_total;
 }
@@ -508,13 +504,12 @@ __device__ __forceinline__ void k2_zero_tail(const BatchParams& P, uint16_t* up,
 template <int NB, int SPW, int NLW>
 __global__ __launch_bounds__(kRowThreads) void k2_batch_kernel(const BatchParams P) {
   extern __shared__ __align__(16) float red_raw[];
-  __shared__ int wprefix[kMaxWords + 1];
   __shared__ int rowidx[32 * 16 + 16];
   const int tid = threadIdx.x, lane = tid & (kWave - 1);
   const int ri = lane & 15, kg = lane >> 4;
   const int l = blockIdx.y;
   const int tile0 = blockIdx.x * P.TPW2;
-  const int m_total = k2_ranks_to_rows<kRowThreads>(P, l, tile0, wprefix, rowidx);
+  const int m_total = k2_ranks_to_rows<kRowThreads>(P, l, tile0, rowidx);
   if (m_total < 0) return;
   const int tiles_total = (m_total + 15) / 16;
   const int rank_end = (m_total + 31) / 32 * 32;  // the v phase reads ranks below this
@@ -649,14 +644,13 @@ __global__ __launch_bounds__(kStreamThreads, 4) void predict_stream_kernel(const
 template <int GS, int NG, int NT>
 __global__ __launch_bounds__(kStreamThreads, 4) void k2_stream_kernel(const BatchParams P) {
   extern __shared__ __align__(16) u32x4 qsh[];
-  __shared__ int wprefix[kMaxWords + 1];
   __shared__ int rowidx[kStreamWaves * NT * 16 + 16];
   const int lane = threadIdx.x & (kWave - 1);
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
   const int ri = lane & 15, kg = lane >> 4;
   const int l = blockIdx.y;
   const int tile0 = blockIdx.x * P.TPW2;  // the launch sets TPW2 = 4 NT
-  const int m_total = k2_ranks_to_rows<kStreamThreads>(P, l, tile0, wprefix, rowidx);
+  const int m_total = k2_ranks_to_rows<kStreamThreads>(P, l, tile0, rowidx);
   if (m_total < 0) return;
   const int tiles_total = (m_total + 15) / 16;
   const int rank_end = (m_total + 31) / 32 * 32;  // the v phase reads ranks below this
@@ -682,6 +676,182 @@ __global__ __launch_bounds__(kStreamThreads, 4) void k2_stream_kernel(const Batc
     if (b < P.B && rho < rank_end) k2_store_u(P, up, rho, b, m_total, th, acc[i], score[i]);
   }
   if (tile0 + kStreamWaves * NT >= tiles_total) k2_zero_tail<kStreamThreads>(P, up, (tile0 + kStreamWaves * NT) * 16, rank_end);
+}
+
+// ------------------------------------------------------- rows x tokens, whole rows (<= 16 tokens)
+// The streamed kernels above read a row in 64-byte pieces (the shape the 16x16x32 operand asks
+// for), which the memory system serves at some 85 % of what whole rows reach.  Here a wave
+// takes FOUR CONSECUTIVE ROWS per step and reads them whole: lane (block = lane / 4, i = lane % 4)
+// loads the 16-byte chunks block + 16 c, c < CH, of row i, so one load instruction covers 256
+// contiguous bytes of each of four rows (K = 128 CH).  The products run on the 4x4x4 matrix
+// instruction, whose 16 independent blocks are exactly this layout: block b multiplies rows
+// i < 4 by tokens j < 4 over four k values, A[i][k] in lane 4 b + i, B[k][j] in lane 4 b + j,
+// D[i][j] in lane 4 b + j, register i.  A chunk (8 k values) feeds two instructions per group of
+// four tokens; the token operands sit in LDS in lane order.  After the row's last chunk the 16
+// blocks hold partial sums over disjoint k ranges: they are added across lanes, halving the
+// number of live values at each stage, so that lane (b, j) ends with the sum for row b % 4 and
+// token 4 (b / 4) + j, which goes to LDS; the workgroup stores everything after its last step
+// (no store between the loads: they share the loads' counter).  Two steps are in flight per wave.
+constexpr int kR4Threads = 256;
+typedef short s16x4_t __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ f32x4 mfma_4x4x4(uint32_t a0, uint32_t a1, uint32_t b0, uint32_t b1, f32x4 c) {
+  return __builtin_amdgcn_mfma_f32_4x4x4bf16_1k(__builtin_bit_cast(s16x4_t, u32x2{a0, a1}),
+                                                __builtin_bit_cast(s16x4_t, u32x2{b0, b1}), c, 0, 0, 0);
+}
+// Halves of the wavefront (rows of 16 lanes) trade places: after the call and the addition the
+// lanes whose bit 5 (bit 4) is clear hold `lo` summed over that bit, the others hold `hi`.
+__device__ __forceinline__ float fold_bit5(float lo, float hi) {
+  const u32x2 r = __builtin_amdgcn_permlane32_swap(__float_as_uint(lo), __float_as_uint(hi), false, false);
+  return __uint_as_float(r[0]) + __uint_as_float(r[1]);
+}
+__device__ __forceinline__ float fold_bit4(float lo, float hi) {
+  const u32x2 r = __builtin_amdgcn_permlane16_swap(__float_as_uint(lo), __float_as_uint(hi), false, false);
+  return __uint_as_float(r[0]) + __uint_as_float(r[1]);
+}
+template <int NG>
+__device__ __forceinline__ float blocks_to_lanes(const f32x4 (&acc)[NG], int lane) {
+  float v[16];
+#pragma unroll
+  for (int n = 0; n < 16; ++n) v[n] = n / 4 < NG ? acc[n / 4 < NG ? n / 4 : 0][n % 4] : 0.f;
+  float w8[8], w4[4];
+#pragma unroll
+  for (int n = 0; n < 8; ++n) w8[n] = fold_bit5(v[n], v[n + 8]);
+#pragma unroll
+  for (int n = 0; n < 4; ++n) w4[n] = fold_bit4(w8[n], w8[n + 4]);
+#pragma unroll
+  for (int n = 0; n < 4; ++n) {  // the four blocks of a row of 16 lanes: rotations by 4 and 8
+    w4[n] = dpp_add<0x124, 0xf>(w4[n]);
+    w4[n] = dpp_add<0x128, 0xf>(w4[n]);
+  }
+  const int sel = (lane >> 2) & 3;
+  return sel == 0 ? w4[0] : sel == 1 ? w4[1] : sel == 2 ? w4[2] : w4[3];
+}
+
+constexpr int r4_pitch(int NS) { return NS * 16 + 4; }  // floats between tokens of the result tile in LDS
+// row_of(local row) gives the matrix row of the workgroup's local row (any valid row for rows
+// that do not count); rows from `nrows` on are not read when a whole step lies past them.
+template <int NG, int CH, int NS, typename RowOf>
+__device__ __forceinline__ void rows4_sweep(const bf16_t* __restrict__ w, uint32_t w_bytes, int K,
+                                            const bf16_t* __restrict__ q, int64_t ldq, int qoff, int B, int nrows,
+                                            u32x4* qsh, RowOf row_of, float* out) {
+  const int tid = threadIdx.x, lane = tid & (kWave - 1);
+  const int wave = __builtin_amdgcn_readfirstlane(tid / kWave);
+  const int blk = lane >> 2, i4 = lane & 3;
+  // token operands in lane order: entry (c NG + g) 64 + lane = chunk blk + 16 c of token 4 g + i4
+  auto stage_tokens = [&]() {
+    for (int e = tid; e < CH * NG * kWave; e += kR4Threads) {
+      const int ln = e & (kWave - 1), cg = e >> 6, g = cg % NG, c = cg / NG;
+      const int t = 4 * g + (ln & 3), ch = (ln >> 2) + 16 * c;
+      u32x4 v{0u, 0u, 0u, 0u};
+      if (t < B) v = ld16(q + (int64_t)t * ldq + qoff + ch * 8);
+      qsh[e] = v;
+    }
+    __syncthreads();
+  };
+  auto load_step = [&](int s, u32x4(&a)[CH]) {
+    const int lr = s * 16 + wave * 4;  // steps past the rows: a descriptor without records
+    const __amdgpu_buffer_rsrc_t rs =
+        __builtin_amdgcn_make_buffer_rsrc(const_cast<bf16_t*>(w), 0, lr < nrows ? (int)w_bytes : 0, 0x00020000);
+    const uint32_t off = (uint32_t)row_of(lr + i4) * (uint32_t)K * 2u + (uint32_t)blk * 16u;
+#pragma unroll
+    for (int c = 0; c < CH; ++c) a[c] = __builtin_amdgcn_raw_buffer_load_b128(rs, (int)(off + (uint32_t)c * 256u), 0, kAuxNontemporal);
+  };
+  auto multiply = [&](const u32x4(&a)[CH], int s) {
+    f32x4 acc[NG];
+#pragma unroll
+    for (int g = 0; g < NG; ++g) acc[g] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int c = 0; c < CH; ++c)
+#pragma unroll
+      for (int g = 0; g < NG; ++g) {
+        const u32x4 t = qsh[(c * NG + g) * kWave + lane];
+        acc[g] = mfma_4x4x4(a[c][0], a[c][1], t[0], t[1], acc[g]);
+        acc[g] = mfma_4x4x4(a[c][2], a[c][3], t[2], t[3], acc[g]);
+      }
+    const float val = blocks_to_lanes<NG>(acc, lane);
+    if ((blk >> 2) < NG) out[(4 * (blk >> 2) + i4) * r4_pitch(NS) + s * 16 + wave * 4 + (blk & 3)] = val;
+  };
+  u32x4 a0[CH], a1[CH];
+  if constexpr (NS > 4) stage_tokens();
+  load_step(0, a0);
+  load_step(1, a1);
+  __builtin_amdgcn_sched_barrier(0);
+  if constexpr (NS <= 4) stage_tokens();
+#pragma unroll
+  for (int s = 0; s < NS; s += 2) {
+    multiply(a0, s);
+    __builtin_amdgcn_sched_barrier(0);
+    if (s + 2 < NS) load_step(s + 2, a0);
+    __builtin_amdgcn_sched_barrier(0);
+    multiply(a1, s + 1);
+    __builtin_amdgcn_sched_barrier(0);
+    if (s + 3 < NS) load_step(s + 3, a1);
+    __builtin_amdgcn_sched_barrier(0);
+  }
+  __syncthreads();
+}
+
+template <int NG, int CH, int NS>
+__global__ __launch_bounds__(kR4Threads) void predict_rows4_kernel(const BatchParams P) {
+  extern __shared__ __align__(16) u32x4 qsh[];
+  constexpr int RW = NS * 16, PITCH = r4_pitch(NS);
+  __shared__ __align__(16) float s_sh[4 * NG * PITCH];
+  const int l = blockIdx.y;
+  const int row0 = blockIdx.x * RW, nrows = min(RW, P.d_ff - row0);
+  if (nrows <= 0) return;
+  rows4_sweep<NG, CH, NS>(static_cast<const bf16_t*>(P.k1n[l]), (uint32_t)P.d_ff * (uint32_t)P.r * 2u, P.r,
+                          P.q + (size_t)l * P.qslot, P.ldq, 0, P.B, nrows, qsh,
+                          [&](int lr) { return min(row0 + lr, P.d_ff - 1); }, s_sh);
+  float* S = P.S + (size_t)l * P.B * P.d_ff;
+  for (int idx = threadIdx.x; idx < P.B * RW; idx += kR4Threads) {
+    const int t = idx / RW, rr = idx % RW;
+    if (rr < nrows) S[(size_t)t * P.d_ff + row0 + rr] = s_sh[t * PITCH + rr];
+  }
+  if (P.ST == nullptr) return;  // (the whole-row k2 kernel reads the token-major scores)
+  float* ST = P.ST + (size_t)l * P.d_ff * P.BP;
+  for (int idx = threadIdx.x; idx < RW * P.BP; idx += kR4Threads) {  // tokens past the batch: zeros (whole lines)
+    const int rr = idx / P.BP, t = idx % P.BP;
+    if (rr < nrows) ST[(size_t)(row0 + rr) * P.BP + t] = t < P.B ? s_sh[t * PITCH + rr] : 0.f;
+  }
+}
+
+template <int NG, int CH, int NS>
+__global__ __launch_bounds__(kR4Threads) void k2_rows4_kernel(const BatchParams P) {
+  extern __shared__ __align__(16) u32x4 qsh[];
+  constexpr int RW = NS * 16, PITCH = r4_pitch(NS), IT = NS / 4;
+  static_assert(NS % 4 == 0, "a pass of the closing loop covers 64 ranks");
+  __shared__ int rowidx[RW + 16];
+  __shared__ __align__(16) float g_sh[4 * NG * PITCH];
+  const int tid = threadIdx.x;
+  const int l = blockIdx.y;
+  const int tile0 = blockIdx.x * P.TPW2;  // the launch sets TPW2 = NS
+  const int m_total = k2_ranks_to_rows<kR4Threads>(P, l, tile0, rowidx);
+  if (m_total < 0) return;
+  const int tiles_total = (m_total + 15) / 16;
+  const int rank_end = (m_total + 31) / 32 * 32;  // the v phase reads ranks below this
+  const int rank0 = tile0 * 16;
+  // closing work item m of a thread: token b, ranks rank0 + 4 rq ..+3; its scores are asked for
+  // ahead of the weight rows, from the token-major array (the union's rows ascend, so the four
+  // of an item, and the items of a token, lie close together in the token's row of scores)
+  const int b = tid & 15;
+  const float* Sb = P.S + ((size_t)l * P.B + min(b, P.B - 1)) * P.d_ff;
+  f32x4 score[IT];
+#pragma unroll
+  for (int m = 0; m < IT; ++m)
+#pragma unroll
+    for (int e = 0; e < 4; ++e) score[m][e] = Sb[rowidx[((tid >> 4) + 16 * m) * 4 + e]];
+  const float th = P.thetas[(size_t)l * P.B + min(b, P.B - 1)];
+  rows4_sweep<NG, CH, NS>(static_cast<const bf16_t*>(P.k2n[l]), (uint32_t)P.d_ff * (uint32_t)(P.d_model - P.r) * 2u,
+                          P.d_model - P.r, P.q + (size_t)l * P.qslot, P.ldq, P.r, P.B, m_total - rank0, qsh,
+                          [&](int lr) { return rowidx[lr]; }, g_sh);
+  uint16_t* up = P.up + (size_t)l * P.B * P.ldu;
+#pragma unroll
+  for (int m = 0; m < IT; ++m) {
+    const int rq = (tid >> 4) + 16 * m, rho = rank0 + 4 * rq;
+    if (b < P.B && rho < rank_end)
+      k2_store_u(P, up, rho, b, m_total, th, *reinterpret_cast<const f32x4*>(&g_sh[b * PITCH + 4 * rq]), score[m]);
+  }
+  if (tile0 + NS >= tiles_total) k2_zero_tail<kR4Threads>(P, up, (tile0 + NS) * 16, rank_end);
 }
 
 // --------------------------------------------------------------------------------------- v
@@ -842,7 +1012,7 @@ int v_slabs(int d_model, int nb) { return ((d_model + 63) / 64 + v_waves(d_model
 int part_rows(int d_model) { return kBatchMaxLayers + (768 + v_slabs(d_model, 4) - 1) / v_slabs(d_model, 4); }
 
 struct BatchLayout {
-  size_t S, ST, thetas, tmask, umask, urow, utotal, up, plane, part, total;
+  size_t S, ST, thetas, tmask, urow, utotal, up, plane, part, total;
   int ldu;
 };
 
@@ -855,7 +1025,6 @@ BatchLayout batch_layout(int d_model, int d_ff, int B) {
   s.ST = o;     o += align256(L * (size_t)((B + 15) / 16 * 16) * (size_t)d_ff * 4);
   s.thetas = o; o += align256(L * B * 4);
   s.tmask = o;  o += align256(L * B * kMaxWords * 8);
-  s.umask = o;  o += align256(L * kMaxWords * 8);
   s.urow = o;   o += align256(L * (size_t)d_ff * 4);
   s.utotal = o; o += align256(L * 4);
   s.plane = align256(L * B * (size_t)s.ldu * 2) / 2;
@@ -944,6 +1113,50 @@ hipError_t launch_stream_split(const BatchParams& P, int mode, int gs, int ng, i
   return hipErrorInvalidValue;
 }
 
+
+// Whole-row kernels (at most 16 tokens): rows of K = 128 CH elements for the compiled CH.
+int rows4_chunks(int K) {
+  if (K % 128 != 0) return 0;
+  const int ch = K / 128;
+  return (ch == 4 || ch == 8 || ch == 10 || ch == 12 || ch == 16) ? ch : 0;
+}
+template <int NG, int CH, int NS>
+hipError_t launch_rows4(const BatchParams& P, int mode, int tiles, hipStream_t st) {
+  const size_t dyn = (size_t)CH * NG * kWave * 16;
+  const void* kern = mode == 0 ? reinterpret_cast<const void*>(predict_rows4_kernel<NG, CH, NS>)
+                               : reinterpret_cast<const void*>(k2_rows4_kernel<NG, CH, NS>);
+  const hipError_t e = hipFuncSetAttribute(kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)dyn);
+  if (e != hipSuccess) return e;
+  const dim3 grid((tiles + NS - 1) / NS, P.n_layers);
+  if (mode == 0) hipLaunchKernelGGL((predict_rows4_kernel<NG, CH, NS>), grid, dim3(kR4Threads), dyn, st, P);
+  else hipLaunchKernelGGL((k2_rows4_kernel<NG, CH, NS>), grid, dim3(kR4Threads), dyn, st, P);
+  return hipGetLastError();
+}
+template <int NG, int CH>
+hipError_t launch_rows4_ns(const BatchParams& P, int mode, bool brief, int tiles, hipStream_t st) {
+  return brief ? launch_rows4<NG, CH, 4>(P, mode, tiles, st) : launch_rows4<NG, CH, 16>(P, mode, tiles, st);
+}
+template <int NG>
+hipError_t launch_rows4_ch(const BatchParams& P, int mode, int ch, bool brief, int tiles, hipStream_t st) {
+  switch (ch) {
+    case 4: return launch_rows4_ns<NG, 4>(P, mode, brief, tiles, st);
+    case 8: return launch_rows4_ns<NG, 8>(P, mode, brief, tiles, st);
+    case 10: return launch_rows4_ns<NG, 10>(P, mode, brief, tiles, st);
+    case 12: return launch_rows4_ns<NG, 12>(P, mode, brief, tiles, st);
+    case 16: return launch_rows4_ns<NG, 16>(P, mode, brief, tiles, st);
+    default: return hipErrorInvalidValue;
+  }
+}
+hipError_t launch_rows4_ng(const BatchParams& P, int mode, int ch, bool brief, int tiles, hipStream_t st) {
+  switch ((P.B + 3) / 4) {
+    case 1: return launch_rows4_ch<1>(P, mode, ch, brief, tiles, st);
+    case 2: return launch_rows4_ch<2>(P, mode, ch, brief, tiles, st);
+    case 3: return launch_rows4_ch<3>(P, mode, ch, brief, tiles, st);
+    case 4: return launch_rows4_ch<4>(P, mode, ch, brief, tiles, st);
+    default: return hipErrorInvalidValue;
+  }
+}
+
 }  // namespace
 
 size_t phased_batch_scratch_bytes(int d_model, int d_ff, int batch) { return batch_layout(d_model, d_ff, batch).total; }
@@ -961,10 +1174,14 @@ hipError_t launch_ffn_phased_batch(const FfnProblem& p0, const void* const* k1n,
                                    hipStream_t st) {
   const BatchLayout lay = batch_layout(p0.d_model, p0.d_ff, p0.batch);
   // pinned choices (0 = automatic): tiles per workgroup of the predict and k2 steps (the block sizes
-  // divided by 16), row slices of the V step; variant 100 + ks: the k-split kernels for every batch
-  // size, 200 + ks: the streamed kernels wherever they are compiled, however small the launch
+  // divided by 16); variant = 100 x kernel family + row slices of the V step.  Families: 0 automatic,
+  // 1 the k-split kernels for every batch size, 2 the streamed kernels wherever they are compiled,
+  // however small the launch, 3 automatic among the kernels that read rows in MFMA-shaped pieces,
+  // 4 the whole-row kernels wherever they are compiled
   const int t1 = tune.rows_per_predict_block / 16, t2 = tune.neurons_per_gather_block / 16;
-  const int g_batch_stream = tune.variant >= 200 ? 2 : tune.variant >= 100 ? 0 : 1;
+  const int family = tune.variant / 100;
+  const bool rows4_on = family == 0 || family == 4;
+  const int g_batch_stream = family == 1 ? 0 : family == 2 ? 2 : 1;
   const int g_batch_ks = tune.variant % 100;
   const int g_batch_tpw1 = t1 > 0 ? (t1 + 3) / 4 * 4 : 0;
   const int g_batch_tpw2 = t2 > 0 ? min(32, (t2 + 3) / 4 * 4) : 0;
@@ -995,7 +1212,6 @@ hipError_t launch_ffn_phased_batch(const FfnProblem& p0, const void* const* k1n,
     P.BP = (B + 15) / 16 * 16;
     P.thetas = reinterpret_cast<float*>(s + lay.thetas);
     P.tmask = reinterpret_cast<unsigned long long*>(s + lay.tmask);
-    P.umask = reinterpret_cast<unsigned long long*>(s + lay.umask);
     P.urow = reinterpret_cast<int32_t*>(s + lay.urow);
     P.utotal = reinterpret_cast<int32_t*>(s + lay.utotal);
     P.up = reinterpret_cast<uint16_t*>(s + lay.up);
@@ -1045,7 +1261,25 @@ hipError_t launch_ffn_phased_batch(const FfnProblem& p0, const void* const* k1n,
     // whose workgroups have three times the waves)
     const bool stream_ok = nb == 1 && (g_batch_stream == 2 || (g_batch_stream == 1 && (long long)L * ((tiles + 3) / 4) >= 256));
     const int cpl1 = (p0.r / 8 + kWave - 1) / kWave;
-    if (B <= 4 && cpl1 <= 2 && g_batch_stream != 0) {
+    // At most 16 tokens and rows of whole 256-byte multiples: the whole-row kernels, as long as
+    // the tokens' operands (a KB per 128 elements of a row and group of four tokens) leave room
+    // for three workgroups per compute unit; the predictor only where it gains (with at most 8
+    // tokens always, with more only if k2 joins in and nobody needs the neuron-major scores).
+    // Workgroups of 64 rows up to 8 tokens, of 256 above (measured on the 2B, 9B and paper shapes).
+    const int ngrp = (B + 3) / 4;
+    int ch1 = rows4_on && nb == 1 ? rows4_chunks(p0.r) : 0, ch2 = rows4_on && nb == 1 ? rows4_chunks(p0.d_model - p0.r) : 0;
+    if (family != 4) {
+      if (ch2 * ngrp > 40) ch2 = 0;
+      if (ch1 * ngrp > 48 || (ngrp > 2 && ch2 == 0)) ch1 = 0;
+    }
+    const bool r4_short1 = g_batch_tpw1 > 0 ? g_batch_tpw1 < 16 : (few_wgs || ngrp <= 2);
+    const bool r4_short2 = g_batch_tpw2 > 0 ? g_batch_tpw2 < 16 : (few_wgs || ngrp <= 2);
+    if (ch1 > 0) {
+      BatchParams P1 = P;
+      if (ch2 > 0) P1.ST = nullptr;  // nobody reads the neuron-major copy then
+      err = launch_rows4_ng(P1, 0, ch1, r4_short1, tiles, st);
+    }
+    else if (B <= 4 && cpl1 <= 2 && g_batch_stream != 0) {
       // a few tokens: the vector-ALU sweep (whole-row loads)
       const dim3 gt((p0.d_ff + kTokRows - 1) / kTokRows, L);
       if (cpl1 == 1) hipLaunchKernelGGL((predict_tokens_kernel<4, 1>), gt, dim3(256), 0, st, P);
@@ -1059,7 +1293,10 @@ hipError_t launch_ffn_phased_batch(const FfnProblem& p0, const void* const* k1n,
     if (p0.d_ff <= 36 * kSelThreads) hipLaunchKernelGGL((select_batch_kernel<36>), dim3(B, L), dim3(kSelThreads), 0, st, P);
     else hipLaunchKernelGGL((select_batch_kernel<64>), dim3(B, L), dim3(kSelThreads), 0, st, P);
     hipLaunchKernelGGL(union_batch_kernel, dim3(L), dim3(4 * kMaxWords), 0, st, P);
-    if (stream_ok && stream_split(p0.d_model - p0.r, &gs, &ng)) {
+    if (ch2 > 0) {
+      P.TPW2 = r4_short2 ? 4 : 16;
+      err = launch_rows4_ng(P, 1, ch2, r4_short2, tiles, st);
+    } else if (stream_ok && stream_split(p0.d_model - p0.r, &gs, &ng)) {
       P.TPW2 = kStreamWaves * (s2_short ? 1 : 4);
       err = s2_short ? launch_stream_split<1>(P, 1, gs, ng, tiles, st) : launch_stream_split<4>(P, 1, gs, ng, tiles, st);
     } else {

@@ -7,6 +7,9 @@
 namespace spark {
 
 constexpr int kWave = 64;
+// cache-policy operand of the buffer loads: the nontemporal bit (data that is read once and
+// should not displace what the caches hold)
+constexpr int kAuxNontemporal = 2;
 
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));

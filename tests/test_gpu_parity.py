@@ -342,6 +342,28 @@ def test_streamed_kernels_of_one_token_block(d_model, d_ff, r, k, batch):
         check_ffn_against_oracle(sh, weights, q, out, TOL_BF16_TIGHT, what=f"streamed B={batch} L={n_layers}")
 
 
+@pytest.mark.parametrize("d_model,d_ff,r,k", [(1024, 1000, 512, 77), (2304, 600, 1024, 48), (3584, 40, 1536, 5),
+                                              (1024, 2085, 512, 160)])
+@pytest.mark.parametrize("batch", [2, 5, 9, 16])
+def test_whole_row_kernels_of_one_token_block(d_model, d_ff, r, k, batch):
+    """At most 16 tokens, rows of whole 256-byte multiples: a wave reads four consecutive rows whole
+    and multiplies on the 4x4x4 matrix instruction.  Every compiled row length (512 .. 2048), one
+    to four groups of four tokens, ragged numbers of neurons and of union rows, one and several
+    layers, short (64 rows) and long (256 rows) workgroups; against the oracle and against the
+    kernels that read MFMA-shaped pieces."""
+    sh = synth.FFNShape("rows4", d_model, d_ff, r, k)
+    for n_layers, block in ((1, 0), (3, 256), (2, 64)):
+        weights = synth.ffn_stack(sh, n_layers, base_seed=720 + n_layers, dtype=torch.bfloat16)
+        q = synth.tokens(sh, batch, 730 + batch, torch.bfloat16)
+        tune = binding.Tuning(rows_per_predict_block=block, neurons_per_gather_block=block, variant=400)
+        out = run_gpu_ffn(sh, weights, q, via_layers=True, tuning=tune)
+        check_ffn_against_oracle(sh, weights, q, out, TOL_BF16_TIGHT, what=f"whole rows B={batch} L={n_layers}")
+        other = run_gpu_ffn(sh, weights, q, via_layers=True, tuning=binding.Tuning(variant=300))
+        # (a score within rounding of the threshold may fall on either side of it)
+        assert np.max(np.abs(out["ucount"].astype(np.int64) - other["ucount"])) <= 2
+        assert rel_l2(out["y"], other["y"]) < 1e-3
+
+
 @pytest.mark.parametrize("batch", [2, 3, 4])
 @pytest.mark.parametrize("shape", [synth.GEMMA2_2B, synth.FFNShape("few", 1024, 1000, 520, 77)])
 def test_few_token_predictor(shape, batch):
@@ -350,7 +372,7 @@ def test_few_token_predictor(shape, batch):
     whose neuron count is ragged; against the oracle, and against the matrix-core kernels."""
     weights = synth.ffn_stack(shape, 2, base_seed=800, dtype=torch.bfloat16)
     q = synth.tokens(shape, batch, 810 + batch, torch.bfloat16)
-    out = run_gpu_ffn(shape, weights, q, via_layers=True)
+    out = run_gpu_ffn(shape, weights, q, via_layers=True, tuning=binding.Tuning(variant=300))
     check_ffn_against_oracle(shape, weights, q, out, TOL_BF16_TIGHT, what=f"few tokens B={batch}")
     other = run_gpu_ffn(shape, weights, q, via_layers=True, tuning=binding.Tuning(variant=100))
     assert np.array_equal(out["count"], other["count"]) and np.array_equal(out["idx"], other["idx"])
