@@ -37,7 +37,11 @@ typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
 
 constexpr int kRowWavesAll = 12;  // waves of a predict / k2 workgroup: NLW loaders (k split) + the rest emit
 constexpr int kVPitch = 160;     // bytes between row positions of a staged V tile (conflict-free transposed reads)
-constexpr int kPlanes = 3;       // bf16 planes of u: 3 x 8 significant bits carry an fp32 value
+constexpr int kMaxPlanes = 3;    // bf16 planes of u: 3 x 8 significant bits carry an fp32 value
+// Planes a call uses: all three with one token block; two (16 significant bits, a relative
+// error of 2^-17 per activation, far inside the bf16-weight tolerance) with more, where the
+// V step's matrix work per byte is highest and the third plane costs a tenth of the call.
+constexpr int planes_for(int nb) { return nb == 1 ? 3 : 2; }
 constexpr int kMaxWords = 256;   // 64-bit union mask words per layer: d_ff <= 16384
 
 struct BatchParams {
@@ -59,12 +63,13 @@ struct BatchParams {
   unsigned long long* tmask;   // [L][B][kMaxWords]  mask of every token
   int32_t* urow;               // [L][d_ff]       union rank -> neuron
   int32_t* utotal;             // [L]             union size
-  uint16_t* up;                // [kPlanes][L][ldu / 8][B][8]  bf16 planes of u (u = sum of the planes): union ranks in
+  uint16_t* up;                // [planes][L][ldu / 8][B][8]  bf16 planes of u (u = sum of the planes): union ranks in
                                // blocks of 8, so that the 8 consecutive ranks of one token the v phase feeds to a lane
                                // are 16 contiguous bytes and a group's tokens are contiguous too
   size_t plane;                // elements between planes
   float* part;                 // [L][KS][B][d_model]
   int n_layers, B, BP, d_model, d_ff, r, gelu, ldu;  // BP = B rounded up to 16
+  int planes;  // bf16 planes of u in use
   float z;
   int TPW1;  // predict tiles per workgroup (even)
   int TPW2;  // k2 tiles per workgroup (even, <= 32)
@@ -480,7 +485,8 @@ __device__ __forceinline__ void k2_store_u(const BatchParams& P, uint16_t* up, i
     rest[e] = (rho + e < m_total && a > 0.f) ? gelu(a, P.gelu) * g[e] : 0.f;
   }
 #pragma unroll
-  for (int pl = 0; pl < kPlanes; ++pl) {
+  for (int pl = 0; pl < kMaxPlanes; ++pl) {
+    if (pl >= P.planes) break;
     const uint32_t w01 = pack_bf16x2_rne(rest[0], rest[1]), w23 = pack_bf16x2_rne(rest[2], rest[3]);
     rest[0] -= bf16_lo(w01);
     rest[1] -= bf16_hi(w01);
@@ -496,8 +502,7 @@ template <int THREADS>
 __device__ __forceinline__ void k2_zero_tail(const BatchParams& P, uint16_t* up, int from, int to) {
   for (int i = threadIdx.x; i < (to - from) * P.B; i += THREADS) {
     const int b = i / (to - from), rho = from + i % (to - from);
-#pragma unroll
-    for (int pl = 0; pl < kPlanes; ++pl) up[pl * P.plane + ((size_t)(rho >> 3) * P.B + b) * 8 + (rho & 7)] = 0;
+    for (int pl = 0; pl < P.planes; ++pl) up[pl * P.plane + ((size_t)(rho >> 3) * P.B + b) * 8 + (rho & 7)] = 0;
   }
 }
 
@@ -866,6 +871,7 @@ __global__ __launch_bounds__(kR4Threads) void k2_rows4_kernel(const BatchParams 
 constexpr int kVMinWaves = 4, kVMaxWaves = 8;
 template <int NB>
 __global__ __launch_bounds__(kVMaxWaves * kWave, (NB >= 3 ? 3 : 4)) void v_batch_kernel(const BatchParams P) {
+  constexpr int kPlanes = planes_for(NB);
   constexpr int UCH = kPlanes * NB * kWave;                            // 16-byte chunks of u per group
   constexpr int MINW = NB >= 3 ? 6 : kVMinWaves;                        // fewest waves the launch uses
   constexpr int UPT = (UCH + MINW * kWave - 1) / (MINW * kWave);        // most chunks per thread
@@ -1028,7 +1034,7 @@ BatchLayout batch_layout(int d_model, int d_ff, int B) {
   s.urow = o;   o += align256(L * (size_t)d_ff * 4);
   s.utotal = o; o += align256(L * 4);
   s.plane = align256(L * B * (size_t)s.ldu * 2) / 2;
-  s.up = o;     o += kPlanes * s.plane * 2;
+  s.up = o;     o += kMaxPlanes * s.plane * 2;
   s.part = o;   o += align256((size_t)part_rows(d_model) * B * (size_t)d_model * 4);
   s.total = o;
   return s;
@@ -1224,6 +1230,7 @@ hipError_t launch_ffn_phased_batch(const FfnProblem& p0, const void* const* k1n,
     P.r = p0.r;
     P.gelu = p0.gelu;
     P.ldu = lay.ldu;
+    P.planes = planes_for(nb);
     P.z = p0.z;
     const int tiles = (p0.d_ff + 15) / 16;
     int tpw1 = 16;  // multiples of 4 (the deepest tile pipeline)
@@ -1305,14 +1312,14 @@ hipError_t launch_ffn_phased_batch(const FfnProblem& p0, const void* const* k1n,
     if (err != hipSuccess) return err;
     const dim3 gv(slabs, ksl, L);
     const int nwv = v_waves(p0.d_model, nb);
-    const size_t vdyn = (size_t)nwv * 32 * kVPitch + (size_t)2 * kPlanes * nb * kWave * 16;
+    const size_t vdyn = (size_t)nwv * 32 * kVPitch + (size_t)2 * planes_for(nb) * nb * kWave * 16;
     const void* vk = nb == 1 ? reinterpret_cast<const void*>(v_batch_kernel<1>)
                      : nb == 2 ? reinterpret_cast<const void*>(v_batch_kernel<2>)
                      : nb == 3 ? reinterpret_cast<const void*>(v_batch_kernel<3>)
                                : reinterpret_cast<const void*>(v_batch_kernel<4>);
     // (the attribute is set to the most this variant can ask for, the same value on every call)
     err = hipFuncSetAttribute(vk, hipFuncAttributeMaxDynamicSharedMemorySize,
-                              (int)((size_t)kVMaxWaves * 32 * kVPitch + (size_t)2 * kPlanes * nb * kWave * 16));
+                              (int)((size_t)kVMaxWaves * 32 * kVPitch + (size_t)2 * planes_for(nb) * nb * kWave * 16));
     if (err != hipSuccess) return err;
     switch (nb) {
       case 1: hipLaunchKernelGGL((v_batch_kernel<1>), gv, dim3(nwv * kWave), vdyn, st, P); break;
