@@ -870,7 +870,10 @@ __global__ __launch_bounds__(kR4Threads) void k2_rows4_kernel(const BatchParams 
 // group; the next group's rows and activations are in flight during the MFMAs.
 constexpr int kVMinWaves = 4, kVMaxWaves = 8;
 template <int NB>
-__global__ __launch_bounds__(kVMaxWaves * kWave, (NB >= 3 ? 3 : 4)) void v_batch_kernel(const BatchParams P) {
+__global__ __launch_bounds__(kVMaxWaves * kWave, (NB == 4 ? 2 : NB == 3 ? 3 : 4)) void v_batch_kernel(const BatchParams P) {
+  // (with four token blocks a wave keeps two groups in flight: measured 5 % on the call there,
+  // nothing or a loss with fewer, where more workgroups share a compute unit)
+  constexpr bool DEEP = NB == 4;
   constexpr int kPlanes = planes_for(NB);
   constexpr int UCH = kPlanes * NB * kWave;                            // 16-byte chunks of u per group
   constexpr int MINW = NB >= 3 ? 6 : kVMinWaves;                        // fewest waves the launch uses
@@ -932,6 +935,64 @@ __global__ __launch_bounds__(kVMaxWaves * kWave, (NB >= 3 ? 3 : 4)) void v_batch
     const int c = tid + i * nthreads;
     u_pad[i] = ((c >> 6) % NB) * 16 + (c & 15) >= P.B;
   }
+  if constexpr (DEEP) {
+   if (g0 < g1) {
+    // Two groups are in flight per wave (two register sets, alternating in an unrolled pair of
+    // steps).  A step parks its group in LDS, requests the group two ahead into the registers
+    // it has just emptied (rows, then activations, then the row indices of the group four
+    // ahead: loads return in order, so each is asked for after everything that is needed
+    // before it), and multiplies after the barrier.  Groups past the slice's last are the last
+    // one fetched again; their multiply is skipped.
+    const int last = g1 - 1;
+    auto step = [&](int g, u32x4(&v)[4], u32x4(&ur)[UPT], int& jn) {
+      u32x4* ub = ush + ((g - g0) & 1) * UCH;
+      if (active) {
+#pragma unroll
+        for (int t = 0; t < 4; ++t) *reinterpret_cast<u32x4*>(mine + (4 * lr + t) * kVPitch + lc * 16) = v[t];
+      }
+#pragma unroll
+      for (int i = 0; i < UPT; ++i)
+        if (tid + i * nthreads < UCH) ub[tid + i * nthreads] = u_pad[i] ? u32x4{0u, 0u, 0u, 0u} : ur[i];
+      load_rows(jn, v);
+      load_u(min(g + 2, last), ur);
+      jn = load_idx(min(g + 4, last));
+      lds_barrier();
+      if (active && g <= last) {
+        u32x4 af[NB][kPlanes];
+#pragma unroll
+        for (int nb = 0; nb < NB; ++nb)
+#pragma unroll
+          for (int pl = 0; pl < kPlanes; ++pl) af[nb][pl] = ub[(pl * NB + nb) * kWave + lane];
+#pragma unroll
+        for (int ct = 0; ct < 4; ++ct) {
+          u32x4 bv;
+#pragma unroll
+          for (int e = 0; e < 8; e += 2) {
+            const uint32_t x0 = *reinterpret_cast<const uint16_t*>(mine + (4 * e + kg) * kVPitch + (ct * 16 + ri) * 2);
+            const uint32_t x1 = *reinterpret_cast<const uint16_t*>(mine + (4 * (e + 1) + kg) * kVPitch + (ct * 16 + ri) * 2);
+            bv[e >> 1] = x0 | (x1 << 16);
+          }
+#pragma unroll
+          for (int nb = 0; nb < NB; ++nb)
+#pragma unroll
+            for (int pl = kPlanes - 1; pl >= 0; --pl) acc[ct][nb] = mfma_bf16(af[nb][pl], bv, acc[ct][nb]);
+        }
+      }
+    };
+    u32x4 v0[4], v1[4], ur0[UPT], ur1[UPT];
+    int jn0 = load_idx(g0), jn1 = load_idx(min(g0 + 1, last));
+    load_rows(jn0, v0);
+    load_u(g0, ur0);
+    load_rows(jn1, v1);
+    load_u(min(g0 + 1, last), ur1);
+    jn0 = load_idx(min(g0 + 2, last));
+    jn1 = load_idx(min(g0 + 3, last));
+    for (int g = g0; g < g1; g += 2) {
+      step(g, v0, ur0, jn0);
+      step(g + 1, v1, ur1, jn1);
+    }
+   }
+  } else
   if (g0 < g1) {
     u32x4 v0[4], ur[UPT];
     int jn = load_idx(g0);
@@ -1245,7 +1306,7 @@ hipError_t launch_ffn_phased_batch(const FfnProblem& p0, const void* const* k1n,
     // Row slices: a workgroup's time is its share of the rows plus a fixed part (start-up and
     // its partial sums, about 2 % of a whole column slab), and the launch takes as many rounds
     // as its workgroups need of the chip's resident slots; take the cheapest count.
-    const int v_slots = 256 * max(1, 4 * (nb >= 3 ? 3 : 4) / v_waves(p0.d_model, nb));
+    const int v_slots = 256 * max(1, 4 * (nb == 4 ? 2 : nb == 3 ? 3 : 4) / v_waves(p0.d_model, nb));
     int ksl = 1;
     double cost_best = 1e30;
     for (int c = 1; c <= 16 && L * c <= part_rows(p0.d_model); ++c) {
