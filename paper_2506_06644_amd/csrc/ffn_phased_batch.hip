@@ -223,6 +223,129 @@ __device__ __forceinline__ void rows_times_tokens(const bf16_t* __restrict__ w, 
   }
 }
 
+// ------------------------------------------------- rows x tokens, tiles staged in LDS (> 16 tokens)
+// The k-split kernels above read a tile of 16 rows in 64- and 128-byte pieces, one piece per
+// row and instruction, which the memory system serves well below what whole rows reach.  Here
+// the COMPUTE waves (two per token block: wave (nb, h) multiplies half h of every row by the
+// tokens of block nb, whose operands it keeps in registers) first bring each tile into LDS with
+// whole-row nontemporal loads: a wave fetches 16 / NCW consecutive rows, 256 or 512 contiguous
+// bytes of each per instruction, two tiles ahead, and parks a tile in LDS one step before it is
+// multiplied.  Every compute wave then reads its half of all 16 rows from LDS as the A operand.
+// The two halves' sums meet in LDS, where the EMIT waves (the rest of the 12) add them and
+// store, exactly as above.  One LDS-only barrier per tile.  LDS: two tiles of 16 x (2 K + 16)
+// bytes (the 16 bytes spread the rows over the banks) and two buffers of partial sums.
+template <int CJ>
+constexpr int staged_pitch() { return CJ * 512 + 16; }  // bytes between rows of a tile in LDS (K = 256 CJ)
+template <int NB, int CJ>
+constexpr size_t staged_lds_bytes() { return (size_t)2 * 16 * staged_pitch<CJ>() + (size_t)2 * 2 * NB * 4 * kWave * sizeof(float); }
+template <int NB, int CJ, bool HAS_SIDE, typename RowOf, typename Pre, typename Emit>
+__device__ __forceinline__ void rows_times_tokens_staged(const bf16_t* __restrict__ w, uint32_t w_bytes,
+                                                         const bf16_t* __restrict__ q, int64_t ldq, int qoff, int B,
+                                                         int tile0, int ntiles, int tile_end, unsigned char* lds,
+                                                         RowOf row_of, Pre pre, Emit emit) {
+  constexpr int K = 256 * CJ, PITCH = staged_pitch<CJ>(), TILE = 16 * PITCH;
+  constexpr int NCW = 2 * NB, kEmitWaves = kRowWavesAll - NCW;
+  constexpr int NBE = (NB + kEmitWaves - 1) / kEmitWaves;
+  constexpr int HS = 4 * CJ;            // k steps (of 32) per half row
+  constexpr int RPWV = 16 / NCW;        // rows a compute wave stages per tile
+  constexpr int LPR = kWave / RPWV;     // lanes per staged row
+  constexpr int NLD = K / 8 / LPR;      // 16-byte loads per lane and tile
+  static_assert(16 % NCW == 0 && NCW < kRowWavesAll, "two or four token blocks");
+  float(*red)[2][NB * 4][kWave] = reinterpret_cast<float(*)[2][NB * 4][kWave]>(lds + 2 * TILE);
+  const int lane = threadIdx.x & (kWave - 1);
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
+  const int kg = lane >> 4, ri = lane & 15;
+  if (wave >= NCW) {
+    // ------------------------------------------------------------------ emit wave
+    const int ew = wave - NCW;
+    float side[2][NBE][4];
+    auto prefetch = [&](int t, float(&sv)[NBE][4]) {
+      if constexpr (HAS_SIDE) {
+#pragma unroll
+        for (int k = 0; k < NBE; ++k)
+#pragma unroll
+          for (int e = 0; e < 4; ++e) sv[k][e] = pre(t, min(ew + kEmitWaves * k, NB - 1), e);
+      }
+    };
+    auto emit_tile = [&](int i, const float(&sv)[NBE][4]) {
+      const int buf = i & 1;
+      lds_barrier();
+#pragma unroll
+      for (int k = 0; k < NBE; ++k) {
+        const int nb = ew + kEmitWaves * k;
+        if (nb < NB) {
+          f32x4 v;
+#pragma unroll
+          for (int e = 0; e < 4; ++e) v[e] = red[buf][0][nb * 4 + e][lane] + red[buf][1][nb * 4 + e][lane];
+          emit(tile0 + i, nb, v, f32x4{sv[k][0], sv[k][1], sv[k][2], sv[k][3]});
+        }
+      }
+    };
+    prefetch(tile0, side[0]);
+    prefetch(tile0 + 1, side[1]);
+    lds_barrier();  // (the compute waves' opening barrier: the first tile is in LDS)
+    for (int i = 0; i < ntiles; i += 2) {  // ntiles is even
+      emit_tile(i, side[0]);
+      prefetch(tile0 + i + 2, side[0]);
+      emit_tile(i + 1, side[1]);
+      prefetch(tile0 + i + 3, side[1]);
+    }
+    return;
+  }
+  // ------------------------------------------------------------------- compute wave
+  const int nbw = wave >> 1, h = wave & 1;
+  u32x4 qf[HS];
+#pragma unroll
+  for (int s = 0; s < HS; ++s) {
+    const int b = nbw * 16 + ri;
+    qf[s] = ld16(q + (int64_t)(b < B ? b : 0) * ldq + qoff + ((h * HS + s) * 4 + kg) * 8);
+    if (b >= B) qf[s] = u32x4{0u, 0u, 0u, 0u};
+  }
+  const int srow = wave * RPWV + lane % RPWV, piece = lane / RPWV;  // the row of the tile this lane stages
+  auto load_stage = [&](int t, u32x4(&st)[NLD]) {  // tiles past tile_end: a descriptor without records
+    const __amdgpu_buffer_rsrc_t rs =
+        __builtin_amdgcn_make_buffer_rsrc(const_cast<bf16_t*>(w), 0, t < tile_end ? (int)w_bytes : 0, 0x00020000);
+    const uint32_t off = (uint32_t)row_of(t, srow) * (uint32_t)(K * 2) + (uint32_t)piece * 16u;
+#pragma unroll
+    for (int j = 0; j < NLD; ++j) st[j] = __builtin_amdgcn_raw_buffer_load_b128(rs, (int)(off + (uint32_t)(j * LPR * 16)), 0, kAuxNontemporal);
+  };
+  auto park = [&](const u32x4(&st)[NLD], int slot) {
+    unsigned char* dst = lds + slot * TILE + srow * PITCH + piece * 16;
+#pragma unroll
+    for (int j = 0; j < NLD; ++j) *reinterpret_cast<u32x4*>(dst + j * LPR * 16) = st[j];
+  };
+  auto multiply = [&](int slot, int buf) {
+    const unsigned char* src = lds + slot * TILE + ri * PITCH + (h * HS * 4 + kg) * 16;
+    f32x4 acc{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int s = 0; s < HS; ++s) acc = mfma_bf16(*reinterpret_cast<const u32x4*>(src + s * 64), qf[s], acc);
+#pragma unroll
+    for (int e = 0; e < 4; ++e) red[buf][h][nbw * 4 + e][lane] = acc[e];
+  };
+  u32x4 st0[NLD], st1[NLD];
+  load_stage(tile0, st0);
+  load_stage(tile0 + 1, st1);
+  __builtin_amdgcn_sched_barrier(0);
+  park(st0, 0);
+  load_stage(tile0 + 2, st0);
+  __builtin_amdgcn_sched_barrier(0);
+  lds_barrier();
+  for (int i = 0; i < ntiles; i += 2) {  // ntiles is even
+    park(st1, 1);
+    __builtin_amdgcn_sched_barrier(0);
+    load_stage(tile0 + i + 3, st1);
+    __builtin_amdgcn_sched_barrier(0);
+    multiply(0, 0);
+    lds_barrier();
+    park(st0, 0);
+    __builtin_amdgcn_sched_barrier(0);
+    load_stage(tile0 + i + 4, st0);
+    __builtin_amdgcn_sched_barrier(0);
+    multiply(1, 1);
+    lds_barrier();
+  }
+}
+
 // --------------------------------------------------------------------------------- predict
 template <int NB, int SPW, int NLW>
 __global__ __launch_bounds__(kRowThreads) void predict_batch_kernel(const BatchParams P) {
@@ -252,6 +375,41 @@ __global__ __launch_bounds__(kRowThreads) void predict_batch_kernel(const BatchP
           }
         }
         if (b < P.BP) {  // tokens past the batch have v = 0: whole lines are written
+#pragma unroll
+          for (int e = 0; e < 4; ++e)
+            if (j + e < P.d_ff) ST[(size_t)(j + e) * P.BP + b] = v[e];
+        }
+      });
+}
+
+template <int NB, int CJ>
+__global__ __launch_bounds__(kRowThreads) void predict_staged_kernel(const BatchParams P) {
+  extern __shared__ __align__(16) unsigned char staged_lds[];
+  const int lane = threadIdx.x & (kWave - 1);
+  const int ri = lane & 15, kg = lane >> 4;
+  const int l = blockIdx.y;
+  const int tiles_total = (P.d_ff + 15) / 16;
+  const int tile0 = blockIdx.x * P.TPW1;
+  if (tile0 >= tiles_total) return;
+  float* S = P.S + (size_t)l * P.B * P.d_ff;
+  float* ST = P.ST ? P.ST + (size_t)l * P.d_ff * P.BP : nullptr;  // (written only if a k2 kernel reads it)
+  rows_times_tokens_staged<NB, CJ, false>(
+      static_cast<const bf16_t*>(P.k1n[l]), (uint32_t)P.d_ff * (uint32_t)P.r * 2u, P.q + (size_t)l * P.qslot, P.ldq, 0, P.B, tile0,
+      P.TPW1, min(tile0 + P.TPW1, tiles_total), staged_lds,
+      [&](int t, int i) { return min(t * 16 + i, P.d_ff - 1); }, [](int, int, int) { return 0.f; },
+      [&](int t, int nb, f32x4 v, f32x4) {
+        const int b = nb * 16 + ri, j = t * 16 + 4 * kg;
+        if (t >= tiles_total) return;
+        if (b < P.B) {
+          if ((P.d_ff & 3) == 0) {  // the four neurons of a lane are inside the layer together, or none is
+            if (j < P.d_ff) *reinterpret_cast<f32x4*>(S + (size_t)b * P.d_ff + j) = v;
+          } else {
+#pragma unroll
+            for (int e = 0; e < 4; ++e)
+              if (j + e < P.d_ff) S[(size_t)b * P.d_ff + j + e] = v[e];
+          }
+        }
+        if (ST != nullptr && b < P.BP) {  // tokens past the batch have v = 0: whole lines are written
 #pragma unroll
           for (int e = 0; e < 4; ++e)
             if (j + e < P.d_ff) ST[(size_t)(j + e) * P.BP + b] = v[e];
@@ -530,6 +688,40 @@ __global__ __launch_bounds__(kRowThreads) void k2_batch_kernel(const BatchParams
       [&](int t, int nb, int e) {  // the score the (row, token) pair will need
         const int b = min(nb * 16 + ri, P.B - 1);
         return ST[(size_t)rowidx[min((t - tile0) * 16 + 4 * kg + e, P.TPW2 * 16 + 15)] * P.BP + b];
+      },
+      [&](int t, int nb, f32x4 g, f32x4 score) {
+        const int b = nb * 16 + ri;
+        const int rho = t * 16 + 4 * kg;  // first of the lane's four ranks (inside one block of 8)
+        if (b >= P.B || rho >= rank_end) return;
+        k2_store_u(P, up, rho, b, m_total, th[nb], g, score);
+      });
+  if (tile0 + P.TPW2 >= tiles_total) k2_zero_tail<kRowThreads>(P, up, (tile0 + P.TPW2) * 16, rank_end);
+}
+
+template <int NB, int CJ>
+__global__ __launch_bounds__(kRowThreads) void k2_staged_kernel(const BatchParams P) {
+  extern __shared__ __align__(16) unsigned char staged_lds[];
+  __shared__ int rowidx[32 * 16 + 16];
+  const int tid = threadIdx.x, lane = tid & (kWave - 1);
+  const int ri = lane & 15, kg = lane >> 4;
+  const int l = blockIdx.y;
+  const int tile0 = blockIdx.x * P.TPW2;
+  const int m_total = k2_ranks_to_rows<kRowThreads>(P, l, tile0, rowidx);
+  if (m_total < 0) return;
+  const int tiles_total = (m_total + 15) / 16;
+  const int rank_end = (m_total + 31) / 32 * 32;  // the v phase reads ranks below this
+  const float* S = P.S + (size_t)l * P.B * P.d_ff;
+  float th[NB];
+#pragma unroll
+  for (int nb = 0; nb < NB; ++nb) th[nb] = P.thetas[(size_t)l * P.B + min(nb * 16 + ri, P.B - 1)];
+  uint16_t* up = P.up + (size_t)l * P.B * P.ldu;
+  rows_times_tokens_staged<NB, CJ, true>(
+      static_cast<const bf16_t*>(P.k2n[l]), (uint32_t)P.d_ff * (uint32_t)(P.d_model - P.r) * 2u, P.q + (size_t)l * P.qslot, P.ldq,
+      P.r, P.B, tile0, P.TPW2, min(tile0 + P.TPW2, tiles_total), staged_lds,
+      [&](int t, int i) { return rowidx[min((t - tile0) * 16 + i, P.TPW2 * 16 + 15)]; },
+      [&](int t, int nb, int e) {  // the score the (row, token) pair will need, from the token-major array
+        const int b = min(nb * 16 + ri, P.B - 1);
+        return S[(size_t)b * P.d_ff + rowidx[min((t - tile0) * 16 + 4 * kg + e, P.TPW2 * 16 + 15)]];
       },
       [&](int t, int nb, f32x4 g, f32x4 score) {
         const int b = nb * 16 + ri;
@@ -1146,6 +1338,37 @@ hipError_t launch_rows_nb(const BatchParams& P, int mode, int nb, int K, dim3 gr
   }
 }
 
+// Staged kernels (more than 16 tokens): rows of K = 256 CJ elements for the compiled CJ (a compute
+// wave keeps 4 CJ token operands in registers; with two token blocks it stages four rows per
+// tile, and the registers are enough up to CJ = 4).
+int staged_cj(int K, int nb) { return (K % 256 == 0 && K / 256 >= 2 && K / 256 <= (nb == 2 ? 4 : 6)) ? K / 256 : 0; }
+template <int NB, int CJ>
+hipError_t launch_staged(const BatchParams& P, int mode, dim3 grid, hipStream_t st) {
+  const size_t dyn = staged_lds_bytes<NB, CJ>();
+  const void* kern = mode == 0 ? reinterpret_cast<const void*>(predict_staged_kernel<NB, CJ>)
+                               : reinterpret_cast<const void*>(k2_staged_kernel<NB, CJ>);
+  const hipError_t e = hipFuncSetAttribute(kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)dyn);
+  if (e != hipSuccess) return e;
+  if (mode == 0) hipLaunchKernelGGL((predict_staged_kernel<NB, CJ>), grid, dim3(kRowThreads), dyn, st, P);
+  else hipLaunchKernelGGL((k2_staged_kernel<NB, CJ>), grid, dim3(kRowThreads), dyn, st, P);
+  return hipGetLastError();
+}
+template <int NB>
+hipError_t launch_staged_cj(const BatchParams& P, int mode, int cj, dim3 grid, hipStream_t st) {
+  switch (cj) {
+    case 2: return launch_staged<NB, 2>(P, mode, grid, st);
+    case 3: return launch_staged<NB, 3>(P, mode, grid, st);
+    case 4: return launch_staged<NB, 4>(P, mode, grid, st);
+    case 5: if constexpr (NB == 4) return launch_staged<NB, 5>(P, mode, grid, st); else return hipErrorInvalidValue;
+    case 6: if constexpr (NB == 4) return launch_staged<NB, 6>(P, mode, grid, st); else return hipErrorInvalidValue;
+    default: return hipErrorInvalidValue;
+  }
+}
+// (three token blocks run as four: the fourth block's operands are zeros)
+hipError_t launch_staged_nb(const BatchParams& P, int mode, int nb, int cj, dim3 grid, hipStream_t st) {
+  return nb == 2 ? launch_staged_cj<2>(P, mode, cj, grid, st) : launch_staged_cj<4>(P, mode, cj, grid, st);
+}
+
 // Streamed kernels (at most 16 tokens): k steps per group and groups per row for a row of K
 // elements, from the compiled combinations.
 bool stream_split(int K, int* gs, int* ng) {
@@ -1329,6 +1552,8 @@ hipError_t launch_ffn_phased_batch(const FfnProblem& p0, const void* const* k1n,
     // whose workgroups have three times the waves)
     const bool stream_ok = nb == 1 && (g_batch_stream == 2 || (g_batch_stream == 1 && (long long)L * ((tiles + 3) / 4) >= 256));
     const int cpl1 = (p0.r / 8 + kWave - 1) / kWave;
+    // more than 16 tokens: the LDS-staged kernels where a row's length is among the compiled ones
+    const int cj1 = nb >= 2 && family != 1 ? staged_cj(p0.r, nb) : 0, cj2 = nb >= 2 && family != 1 ? staged_cj(p0.d_model - p0.r, nb) : 0;
     // At most 16 tokens and rows of whole 256-byte multiples: the whole-row kernels, as long as
     // the tokens' operands (a KB per 128 elements of a row and group of four tokens) leave room
     // for three workgroups per compute unit; the predictor only where it gains (with at most 8
@@ -1355,7 +1580,11 @@ hipError_t launch_ffn_phased_batch(const FfnProblem& p0, const void* const* k1n,
       err = hipGetLastError();
     } else if (stream_ok && stream_split(p0.r, &gs, &ng))
       err = s1_short ? launch_stream_split<1>(P, 0, gs, ng, tiles, st) : launch_stream_split<4>(P, 0, gs, ng, tiles, st);
-    else
+    else if (cj1 > 0) {
+      BatchParams P1 = P;
+      if (cj2 > 0) P1.ST = nullptr;  // the staged k2 kernel reads the token-major scores
+      err = launch_staged_nb(P1, 0, nb, cj1, dim3((tiles + tpw1 - 1) / tpw1, L), st);
+    } else
       err = launch_rows_nb(P, 0, nb, p0.r, dim3((tiles + tpw1 - 1) / tpw1, L), st);
     if (err != hipSuccess) return err;
     if (p0.d_ff <= 36 * kSelThreads) hipLaunchKernelGGL((select_batch_kernel<36>), dim3(B, L), dim3(kSelThreads), 0, st, P);
@@ -1367,6 +1596,8 @@ hipError_t launch_ffn_phased_batch(const FfnProblem& p0, const void* const* k1n,
     } else if (stream_ok && stream_split(p0.d_model - p0.r, &gs, &ng)) {
       P.TPW2 = kStreamWaves * (s2_short ? 1 : 4);
       err = s2_short ? launch_stream_split<1>(P, 1, gs, ng, tiles, st) : launch_stream_split<4>(P, 1, gs, ng, tiles, st);
+    } else if (cj2 > 0) {
+      err = launch_staged_nb(P, 1, nb, cj2, dim3((tiles + tpw2 - 1) / tpw2, L), st);
     } else {
       err = launch_rows_nb(P, 1, nb, p0.d_model - p0.r, dim3((tiles + tpw2 - 1) / tpw2, L), st);
     }

@@ -342,6 +342,26 @@ def test_streamed_kernels_of_one_token_block(d_model, d_ff, r, k, batch):
         check_ffn_against_oracle(sh, weights, q, out, TOL_BF16_TIGHT, what=f"streamed B={batch} L={n_layers}")
 
 
+@pytest.mark.parametrize("d_model,d_ff,r,k", [(1280, 1000, 512, 77), (2304, 600, 1024, 48), (3072, 200, 1536, 20),
+                                              (1536, 2085, 768, 160)])
+@pytest.mark.parametrize("batch", [17, 32, 40, 64])
+def test_staged_kernels_of_several_token_blocks(d_model, d_ff, r, k, batch):
+    """More than 16 tokens, rows of whole 512-byte multiples: tiles of 16 rows are brought into LDS
+    by whole-row loads and multiplied from there.  Every compiled row length (512 .. 1536), two,
+    three and four token blocks (three run as four), ragged numbers of neurons and of union tiles,
+    short and long workgroups; against the oracle and against the k-split kernels."""
+    sh = synth.FFNShape("staged", d_model, d_ff, r, k)
+    for n_layers, block in ((1, 0), (3, 32), (2, 256)):
+        weights = synth.ffn_stack(sh, n_layers, base_seed=740 + n_layers, dtype=torch.bfloat16)
+        q = synth.tokens(sh, batch, 750 + batch, torch.bfloat16)
+        tune = binding.Tuning(rows_per_predict_block=block, neurons_per_gather_block=block)
+        out = run_gpu_ffn(sh, weights, q, via_layers=True, tuning=tune)
+        check_ffn_against_oracle(sh, weights, q, out, TOL_BF16_TIGHT, what=f"staged B={batch} L={n_layers}")
+        other = run_gpu_ffn(sh, weights, q, via_layers=True, tuning=binding.Tuning(variant=100))
+        assert np.max(np.abs(out["ucount"].astype(np.int64) - other["ucount"])) <= 2
+        assert rel_l2(out["y"], other["y"]) < 1e-3
+
+
 @pytest.mark.parametrize("d_model,d_ff,r,k", [(1024, 1000, 512, 77), (2304, 600, 1024, 48), (3584, 40, 1536, 5),
                                               (1024, 2085, 512, 160)])
 @pytest.mark.parametrize("batch", [2, 5, 9, 16])
