@@ -74,6 +74,7 @@ struct BatchParams {
   int TPW1;  // predict tiles per workgroup (even)
   int TPW2;  // k2 tiles per workgroup (even, <= 32)
   int KS;    // row slices of the v phase
+  int VSLABS;  // column slabs of the v phase
 };
 
 __device__ __forceinline__ u32x4 ld16(const void* p) { return *reinterpret_cast<const u32x4*>(p); }
@@ -1077,8 +1078,16 @@ __global__ __launch_bounds__(kVMaxWaves * kWave, (NB == 4 ? 2 : NB == 3 ? 3 : 4)
   unsigned char* mine = lds + (size_t)wave * 32 * kVPitch;
   u32x4* ush = reinterpret_cast<u32x4*>(lds + (size_t)nwv * 32 * kVPitch);  // [2][UCH]
   const int ri = lane & 15, kg = lane >> 4;
-  const int l = blockIdx.z, ks = blockIdx.y;
-  const int col_own = (blockIdx.x * nwv + wave) * 64;
+  // Workgroup -> (column slab, row slice, layer).  The slabs of one (slice, layer) read the same
+  // activations; workgroups are dealt to the eight dies in turn, each with an L2 of its own, so
+  // the launch order is folded: die d takes the d-th eighth of the (layer, slice, slab) list,
+  // slab fastest, and the slabs that share activations meet in one L2 at about the same time
+  // (dealt in launch order they sat on different dies and each fetched its own copy).
+  const int total = P.VSLABS * P.KS * P.n_layers, per_die = (total + 7) / 8;
+  const int m = (int)(blockIdx.x & 7u) * per_die + (int)(blockIdx.x >> 3);
+  if (m >= total) return;
+  const int slab = m % P.VSLABS, ks = (m / P.VSLABS) % P.KS, l = m / (P.VSLABS * P.KS);
+  const int col_own = (slab * nwv + wave) * 64;
   // a wave past the last column still helps with u and the barriers; its row loads go to the
   // last strip (unconditional loads keep the number in flight a compile-time constant)
   const bool active = col_own < P.d_model;
@@ -1602,7 +1611,8 @@ hipError_t launch_ffn_phased_batch(const FfnProblem& p0, const void* const* k1n,
       err = launch_rows_nb(P, 1, nb, p0.d_model - p0.r, dim3((tiles + tpw2 - 1) / tpw2, L), st);
     }
     if (err != hipSuccess) return err;
-    const dim3 gv(slabs, ksl, L);
+    P.VSLABS = slabs;
+    const dim3 gv((unsigned)(((long long)slabs * ksl * L + 7) / 8 * 8));  // (a whole number of rounds over the dies)
     const int nwv = v_waves(p0.d_model, nb);
     const size_t vdyn = (size_t)nwv * 32 * kVPitch + (size_t)2 * planes_for(nb) * nb * kWave * 16;
     const void* vk = nb == 1 ? reinterpret_cast<const void*>(v_batch_kernel<1>)
