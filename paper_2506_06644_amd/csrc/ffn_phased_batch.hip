@@ -926,20 +926,47 @@ __device__ __forceinline__ float blocks_to_lanes(const f32x4 (&acc)[NG], int lan
 }
 
 constexpr int r4_pitch(int NS) { return NS * 16 + 4; }  // floats between tokens of the result tile in LDS
+
+// 8-bit weight codes (WK = 1: OCP E4M3, 2: signed integers): the 16 codes of one 16-byte piece
+// widened to bf16, which holds both kinds exactly (an E4M3 value has 4 significant bits, an
+// integer up to 127 has 7), as 8 words in element order.  The row's scale is applied to the
+// finished dot product by the caller.
+template <int WK>
+__device__ __forceinline__ void codes_to_bf16(u32x4 a, uint32_t (&o)[8]) {
+  typedef float f32x2_v __attribute__((ext_vector_type(2)));
+#pragma unroll
+  for (int d = 0; d < 4; ++d) {
+    float f[4];
+    if constexpr (WK == 1) {
+      const f32x2_v lo = __builtin_amdgcn_cvt_pk_f32_fp8((int)a[d], false), hi = __builtin_amdgcn_cvt_pk_f32_fp8((int)a[d], true);
+      f[0] = lo[0]; f[1] = lo[1]; f[2] = hi[0]; f[3] = hi[1];
+    } else {
+#pragma unroll
+      for (int e = 0; e < 4; ++e) f[e] = (float)(int)(int8_t)(a[d] >> (8 * e));
+    }
+    // (the upper halves of two floats side by side: truncation is exact here)
+    o[2 * d] = __builtin_amdgcn_perm(__float_as_uint(f[1]), __float_as_uint(f[0]), 0x07060302u);
+    o[2 * d + 1] = __builtin_amdgcn_perm(__float_as_uint(f[3]), __float_as_uint(f[2]), 0x07060302u);
+  }
+}
+
 // row_of(local row) gives the matrix row of the workgroup's local row (any valid row for rows
 // that do not count); rows from `nrows` on are not read when a whole step lies past them.
-template <int NG, int CH, int NS, typename RowOf>
-__device__ __forceinline__ void rows4_sweep(const bf16_t* __restrict__ w, uint32_t w_bytes, int K,
+// A row is CH pieces of 256 bytes per block column: 128 CH bf16 elements or 256 CH codes.
+template <int WK, int NG, int CH, int NS, typename RowOf>
+__device__ __forceinline__ void rows4_sweep(const void* __restrict__ w, uint32_t w_bytes,
                                             const bf16_t* __restrict__ q, int64_t ldq, int qoff, int B, int nrows,
                                             u32x4* qsh, RowOf row_of, float* out) {
+  constexpr int TPP = WK ? 2 : 1;  // 16-byte token operands per weight piece (8 or 16 elements of k)
   const int tid = threadIdx.x, lane = tid & (kWave - 1);
   const int wave = __builtin_amdgcn_readfirstlane(tid / kWave);
   const int blk = lane >> 2, i4 = lane & 3;
-  // token operands in lane order: entry (c NG + g) 64 + lane = chunk blk + 16 c of token 4 g + i4
+  // token operands in lane order: entry ((c NG + g) TPP + h) 64 + lane = elements
+  // 8 (TPP (blk + 16 c) + h) .. + 7 of token 4 g + i4
   auto stage_tokens = [&]() {
-    for (int e = tid; e < CH * NG * kWave; e += kR4Threads) {
-      const int ln = e & (kWave - 1), cg = e >> 6, g = cg % NG, c = cg / NG;
-      const int t = 4 * g + (ln & 3), ch = (ln >> 2) + 16 * c;
+    for (int e = tid; e < CH * NG * TPP * kWave; e += kR4Threads) {
+      const int ln = e & (kWave - 1), cgh = e >> 6, h = cgh % TPP, cg = cgh / TPP, g = cg % NG, c = cg / NG;
+      const int t = 4 * g + (ln & 3), ch = TPP * ((ln >> 2) + 16 * c) + h;
       u32x4 v{0u, 0u, 0u, 0u};
       if (t < B) v = ld16(q + (int64_t)t * ldq + qoff + ch * 8);
       qsh[e] = v;
@@ -949,8 +976,8 @@ __device__ __forceinline__ void rows4_sweep(const bf16_t* __restrict__ w, uint32
   auto load_step = [&](int s, u32x4(&a)[CH]) {
     const int lr = s * 16 + wave * 4;  // steps past the rows: a descriptor without records
     const __amdgpu_buffer_rsrc_t rs =
-        __builtin_amdgcn_make_buffer_rsrc(const_cast<bf16_t*>(w), 0, lr < nrows ? (int)w_bytes : 0, 0x00020000);
-    const uint32_t off = (uint32_t)row_of(lr + i4) * (uint32_t)K * 2u + (uint32_t)blk * 16u;
+        __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(w), 0, lr < nrows ? (int)w_bytes : 0, 0x00020000);
+    const uint32_t off = (uint32_t)row_of(lr + i4) * (uint32_t)(CH * 256) + (uint32_t)blk * 16u;
 #pragma unroll
     for (int c = 0; c < CH; ++c) a[c] = __builtin_amdgcn_raw_buffer_load_b128(rs, (int)(off + (uint32_t)c * 256u), 0, kAuxNontemporal);
   };
@@ -959,13 +986,27 @@ __device__ __forceinline__ void rows4_sweep(const bf16_t* __restrict__ w, uint32
 #pragma unroll
     for (int g = 0; g < NG; ++g) acc[g] = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-    for (int c = 0; c < CH; ++c)
+    for (int c = 0; c < CH; ++c) {
+      if constexpr (WK == 0) {
 #pragma unroll
-      for (int g = 0; g < NG; ++g) {
-        const u32x4 t = qsh[(c * NG + g) * kWave + lane];
-        acc[g] = mfma_4x4x4(a[c][0], a[c][1], t[0], t[1], acc[g]);
-        acc[g] = mfma_4x4x4(a[c][2], a[c][3], t[2], t[3], acc[g]);
+        for (int g = 0; g < NG; ++g) {
+          const u32x4 t = qsh[(c * NG + g) * kWave + lane];
+          acc[g] = mfma_4x4x4(a[c][0], a[c][1], t[0], t[1], acc[g]);
+          acc[g] = mfma_4x4x4(a[c][2], a[c][3], t[2], t[3], acc[g]);
+        }
+      } else {
+        uint32_t o[8];
+        codes_to_bf16<WK>(a[c], o);
+#pragma unroll
+        for (int g = 0; g < NG; ++g)
+#pragma unroll
+          for (int h = 0; h < 2; ++h) {
+            const u32x4 t = qsh[((c * NG + g) * 2 + h) * kWave + lane];
+            acc[g] = mfma_4x4x4(o[4 * h], o[4 * h + 1], t[0], t[1], acc[g]);
+            acc[g] = mfma_4x4x4(o[4 * h + 2], o[4 * h + 3], t[2], t[3], acc[g]);
+          }
       }
+    }
     const float val = blocks_to_lanes<NG>(acc, lane);
     if ((blk >> 2) < NG) out[(4 * (blk >> 2) + i4) * r4_pitch(NS) + s * 16 + wave * 4 + (blk & 3)] = val;
   };
@@ -989,7 +1030,14 @@ __device__ __forceinline__ void rows4_sweep(const bf16_t* __restrict__ w, uint32
   __syncthreads();
 }
 
-template <int NG, int CH, int NS>
+// Rows of one weight array in bytes and, for codes, the fp32 scales that follow the last row.
+template <int WK, int CH>
+__device__ __forceinline__ const float* r4_scales(const void* w, int rows) {
+  if constexpr (WK != 0) return reinterpret_cast<const float*>(static_cast<const char*>(w) + (size_t)rows * (CH * 256));
+  else return nullptr;
+}
+
+template <int WK, int NG, int CH, int NS>
 __global__ __launch_bounds__(kR4Threads) void predict_rows4_kernel(const BatchParams P) {
   extern __shared__ __align__(16) u32x4 qsh[];
   constexpr int RW = NS * 16, PITCH = r4_pitch(NS);
@@ -997,23 +1045,31 @@ __global__ __launch_bounds__(kR4Threads) void predict_rows4_kernel(const BatchPa
   const int l = blockIdx.y;
   const int row0 = blockIdx.x * RW, nrows = min(RW, P.d_ff - row0);
   if (nrows <= 0) return;
-  rows4_sweep<NG, CH, NS>(static_cast<const bf16_t*>(P.k1n[l]), (uint32_t)P.d_ff * (uint32_t)P.r * 2u, P.r,
-                          P.q + (size_t)l * P.qslot, P.ldq, 0, P.B, nrows, qsh,
-                          [&](int lr) { return min(row0 + lr, P.d_ff - 1); }, s_sh);
+  rows4_sweep<WK, NG, CH, NS>(P.k1n[l], (uint32_t)P.d_ff * (uint32_t)(CH * 256), P.q + (size_t)l * P.qslot, P.ldq, 0, P.B,
+                              nrows, qsh, [&](int lr) { return min(row0 + lr, P.d_ff - 1); }, s_sh);
+  const float* scales = r4_scales<WK, CH>(P.k1n[l], P.d_ff);
   float* S = P.S + (size_t)l * P.B * P.d_ff;
   for (int idx = threadIdx.x; idx < P.B * RW; idx += kR4Threads) {
     const int t = idx / RW, rr = idx % RW;
-    if (rr < nrows) S[(size_t)t * P.d_ff + row0 + rr] = s_sh[t * PITCH + rr];
+    if (rr < nrows) {
+      float v = s_sh[t * PITCH + rr];
+      if constexpr (WK != 0) v *= scales[row0 + rr];
+      S[(size_t)t * P.d_ff + row0 + rr] = v;
+    }
   }
   if (P.ST == nullptr) return;  // (the whole-row k2 kernel reads the token-major scores)
   float* ST = P.ST + (size_t)l * P.d_ff * P.BP;
   for (int idx = threadIdx.x; idx < RW * P.BP; idx += kR4Threads) {  // tokens past the batch: zeros (whole lines)
     const int rr = idx / P.BP, t = idx % P.BP;
-    if (rr < nrows) ST[(size_t)(row0 + rr) * P.BP + t] = t < P.B ? s_sh[t * PITCH + rr] : 0.f;
+    if (rr < nrows) {
+      float v = t < P.B ? s_sh[t * PITCH + rr] : 0.f;
+      if constexpr (WK != 0) v *= scales[row0 + rr];
+      ST[(size_t)(row0 + rr) * P.BP + t] = v;
+    }
   }
 }
 
-template <int NG, int CH, int NS>
+template <int WK, int NG, int CH, int NS>
 __global__ __launch_bounds__(kR4Threads) void k2_rows4_kernel(const BatchParams P) {
   extern __shared__ __align__(16) u32x4 qsh[];
   constexpr int RW = NS * 16, PITCH = r4_pitch(NS), IT = NS / 4;
@@ -1033,21 +1089,32 @@ __global__ __launch_bounds__(kR4Threads) void k2_rows4_kernel(const BatchParams 
   // of an item, and the items of a token, lie close together in the token's row of scores)
   const int b = tid & 15;
   const float* Sb = P.S + ((size_t)l * P.B + min(b, P.B - 1)) * P.d_ff;
-  f32x4 score[IT];
+  f32x4 score[IT], scale[IT];
+  // (codes: the row's two scales travel as their product, which is all the sum needs:
+  // u_j Vn[j] = GELU(a) (scale_k2 g) (scale_v codes); the V step then multiplies plain codes)
+  const float* k2s = r4_scales<WK, CH>(P.k2n[l], P.d_ff);
+  const float* vs = WK != 0 ? reinterpret_cast<const float*>(static_cast<const char*>(P.vn[l]) + (size_t)P.d_ff * P.d_model) : nullptr;
 #pragma unroll
   for (int m = 0; m < IT; ++m)
 #pragma unroll
-    for (int e = 0; e < 4; ++e) score[m][e] = Sb[rowidx[((tid >> 4) + 16 * m) * 4 + e]];
+    for (int e = 0; e < 4; ++e) {
+      const int j = rowidx[((tid >> 4) + 16 * m) * 4 + e];
+      score[m][e] = Sb[j];
+      if constexpr (WK != 0) scale[m][e] = k2s[j] * vs[j];
+      else scale[m][e] = 1.f;
+    }
   const float th = P.thetas[(size_t)l * P.B + min(b, P.B - 1)];
-  rows4_sweep<NG, CH, NS>(static_cast<const bf16_t*>(P.k2n[l]), (uint32_t)P.d_ff * (uint32_t)(P.d_model - P.r) * 2u,
-                          P.d_model - P.r, P.q + (size_t)l * P.qslot, P.ldq, P.r, P.B, m_total - rank0, qsh,
-                          [&](int lr) { return rowidx[lr]; }, g_sh);
+  rows4_sweep<WK, NG, CH, NS>(P.k2n[l], (uint32_t)P.d_ff * (uint32_t)(CH * 256), P.q + (size_t)l * P.qslot, P.ldq, P.r, P.B,
+                              m_total - rank0, qsh, [&](int lr) { return rowidx[lr]; }, g_sh);
   uint16_t* up = P.up + (size_t)l * P.B * P.ldu;
 #pragma unroll
   for (int m = 0; m < IT; ++m) {
     const int rq = (tid >> 4) + 16 * m, rho = rank0 + 4 * rq;
-    if (b < P.B && rho < rank_end)
-      k2_store_u(P, up, rho, b, m_total, th, *reinterpret_cast<const f32x4*>(&g_sh[b * PITCH + 4 * rq]), score[m]);
+    if (b < P.B && rho < rank_end) {
+      f32x4 g = *reinterpret_cast<const f32x4*>(&g_sh[b * PITCH + 4 * rq]);
+      if constexpr (WK != 0) g *= scale[m];
+      k2_store_u(P, up, rho, b, m_total, th, g, score[m]);
+    }
   }
   if (tile0 + NS >= tiles_total) k2_zero_tail<kR4Threads>(P, up, (tile0 + NS) * 16, rank_end);
 }
@@ -1062,8 +1129,13 @@ __global__ __launch_bounds__(kR4Threads) void k2_rows4_kernel(const BatchParams 
 // workgroup fetches them once per group into LDS, already in lane order.  One barrier per
 // group; the next group's rows and activations are in flight during the MFMAs.
 constexpr int kVMinWaves = 4, kVMaxWaves = 8;
-template <int NB>
+template <int NB, int WK = 0>
 __global__ __launch_bounds__(kVMaxWaves * kWave, (NB == 4 ? 2 : NB == 3 ? 3 : 4)) void v_batch_kernel(const BatchParams P) {
+  // WK != 0: Vn holds 8-bit codes (the rows' scales are already inside u).  A wave's 64 columns
+  // are then 64 bytes of a row: lane = (row lane / 4 of 16, 16-byte piece lane % 4), two loads
+  // per 32-row group; the codes are widened to bf16 when the rows are parked in LDS, and the
+  // rest of the kernel is the same.
+  constexpr int NLV = WK ? 2 : 4;  // row loads per lane and group
   // (with four token blocks a wave keeps two groups in flight: measured 5 % on the call there,
   // nothing or a loss with fewer, where more workgroups share a compute unit)
   constexpr bool DEEP = NB == 4;
@@ -1096,7 +1168,7 @@ __global__ __launch_bounds__(kVMaxWaves * kWave, (NB == 4 ? 2 : NB == 3 ? 3 : 4)
   const int groups_total = (m_total + 31) / 32;
   const int per = (groups_total + P.KS - 1) / P.KS;
   const int g0 = ks * per, g1 = min(g0 + per, groups_total);
-  const bf16_t* vn = static_cast<const bf16_t*>(P.vn[l]);
+  const char* vn = static_cast<const char*>(P.vn[l]);
   const int32_t* urow = P.urow + (size_t)l * P.d_ff;
   const uint16_t* up = P.up + (size_t)l * P.B * P.ldu;
 
@@ -1109,11 +1181,32 @@ __global__ __launch_bounds__(kVMaxWaves * kWave, (NB == 4 ? 2 : NB == 3 ? 3 : 4)
   const int lr = lane >> 3, lc = lane & 7;
   // neuron of rank 32 g + lane % 32 (ranks past the end repeat the last neuron; their u is 0)
   auto load_idx = [&](int g) { return urow[max(0, min(g * 32 + (lane & 31), m_total - 1))]; };
-  auto load_rows = [&](int jn, u32x4(&v)[4]) {
+  auto load_rows = [&](int jn, u32x4(&v)[NLV]) {
 #pragma unroll
-    for (int t = 0; t < 4; ++t) {
-      const int j = __shfl(jn, 8 * t + lr, kWave);
-      v[t] = ld16_stream(vn + (int64_t)j * P.d_model + col0 + lc * 8);
+    for (int t = 0; t < NLV; ++t) {
+      if constexpr (WK == 0) {
+        const int j = __shfl(jn, 8 * t + lr, kWave);
+        v[t] = ld16_stream(vn + ((int64_t)j * P.d_model + col0 + lc * 8) * 2);
+      } else {
+        const int j = __shfl(jn, 16 * t + (lane >> 2), kWave);
+        v[t] = ld16_stream(vn + (int64_t)j * P.d_model + col0 + (lane & 3) * 16);
+      }
+    }
+  };
+  // parks the group's rows in the wave's LDS tile: row 8 t + j at position 4 j + t
+  auto park_rows = [&](const u32x4(&v)[NLV]) {
+#pragma unroll
+    for (int t = 0; t < NLV; ++t) {
+      if constexpr (WK == 0) {
+        *reinterpret_cast<u32x4*>(mine + (4 * lr + t) * kVPitch + lc * 16) = v[t];
+      } else {
+        const int row = 16 * t + (lane >> 2);
+        uint32_t o[8];
+        codes_to_bf16<WK>(v[t], o);
+        unsigned char* dst = mine + (4 * (row & 7) + (row >> 3)) * kVPitch + (lane & 3) * 32;
+        *reinterpret_cast<u32x4*>(dst) = u32x4{o[0], o[1], o[2], o[3]};
+        *reinterpret_cast<u32x4*>(dst + 16) = u32x4{o[4], o[5], o[6], o[7]};
+      }
     }
   };
   auto load_u = [&](int g, u32x4(&a)[UPT]) {
@@ -1145,12 +1238,9 @@ __global__ __launch_bounds__(kVMaxWaves * kWave, (NB == 4 ? 2 : NB == 3 ? 3 : 4)
     // before it), and multiplies after the barrier.  Groups past the slice's last are the last
     // one fetched again; their multiply is skipped.
     const int last = g1 - 1;
-    auto step = [&](int g, u32x4(&v)[4], u32x4(&ur)[UPT], int& jn) {
+    auto step = [&](int g, u32x4(&v)[NLV], u32x4(&ur)[UPT], int& jn) {
       u32x4* ub = ush + ((g - g0) & 1) * UCH;
-      if (active) {
-#pragma unroll
-        for (int t = 0; t < 4; ++t) *reinterpret_cast<u32x4*>(mine + (4 * lr + t) * kVPitch + lc * 16) = v[t];
-      }
+      if (active) park_rows(v);
 #pragma unroll
       for (int i = 0; i < UPT; ++i)
         if (tid + i * nthreads < UCH) ub[tid + i * nthreads] = u_pad[i] ? u32x4{0u, 0u, 0u, 0u} : ur[i];
@@ -1180,7 +1270,7 @@ __global__ __launch_bounds__(kVMaxWaves * kWave, (NB == 4 ? 2 : NB == 3 ? 3 : 4)
         }
       }
     };
-    u32x4 v0[4], v1[4], ur0[UPT], ur1[UPT];
+    u32x4 v0[NLV], v1[NLV], ur0[UPT], ur1[UPT];
     int jn0 = load_idx(g0), jn1 = load_idx(min(g0 + 1, last));
     load_rows(jn0, v0);
     load_u(g0, ur0);
@@ -1195,17 +1285,14 @@ __global__ __launch_bounds__(kVMaxWaves * kWave, (NB == 4 ? 2 : NB == 3 ? 3 : 4)
    }
   } else
   if (g0 < g1) {
-    u32x4 v0[4], ur[UPT];
+    u32x4 v0[NLV], ur[UPT];
     int jn = load_idx(g0);
     load_rows(jn, v0);
     load_u(g0, ur);
     jn = load_idx(min(g0 + 1, g1 - 1));
     for (int g = g0; g < g1; ++g) {
       u32x4* ub = ush + ((g - g0) & 1) * UCH;
-      if (active) {
-#pragma unroll
-        for (int t = 0; t < 4; ++t) *reinterpret_cast<u32x4*>(mine + (4 * lr + t) * kVPitch + lc * 16) = v0[t];
-      }
+      if (active) park_rows(v0);
 #pragma unroll
       for (int i = 0; i < UPT; ++i)
         if (tid + i * nthreads < UCH) ub[tid + i * nthreads] = u_pad[i] ? u32x4{0u, 0u, 0u, 0u} : ur[i];
@@ -1413,47 +1500,66 @@ hipError_t launch_stream_split(const BatchParams& P, int mode, int gs, int ng, i
 }
 
 
-// Whole-row kernels (at most 16 tokens): rows of K = 128 CH elements for the compiled CH.
-int rows4_chunks(int K) {
-  if (K % 128 != 0) return 0;
-  const int ch = K / 128;
+// Whole-row kernels (at most 16 tokens): rows of whole 256-byte multiples, for the compiled counts
+// CH of 256-byte pieces per block column (bf16: K = 128 CH; 8-bit codes: K = 256 CH).
+int rows4_chunks(int K, int wkind) {
+  const int per = wkind ? 256 : 128;
+  if (K % per != 0) return 0;
+  const int ch = K / per;
+  if (wkind) return (ch == 4 || ch == 5 || ch == 6 || ch == 8) ? ch : 0;
   return (ch == 4 || ch == 8 || ch == 10 || ch == 12 || ch == 16) ? ch : 0;
 }
-template <int NG, int CH, int NS>
+template <int WK, int NG, int CH, int NS>
 hipError_t launch_rows4(const BatchParams& P, int mode, int tiles, hipStream_t st) {
-  const size_t dyn = (size_t)CH * NG * kWave * 16;
-  const void* kern = mode == 0 ? reinterpret_cast<const void*>(predict_rows4_kernel<NG, CH, NS>)
-                               : reinterpret_cast<const void*>(k2_rows4_kernel<NG, CH, NS>);
+  const size_t dyn = (size_t)CH * NG * (WK ? 2 : 1) * kWave * 16;
+  const void* kern = mode == 0 ? reinterpret_cast<const void*>(predict_rows4_kernel<WK, NG, CH, NS>)
+                               : reinterpret_cast<const void*>(k2_rows4_kernel<WK, NG, CH, NS>);
   const hipError_t e = hipFuncSetAttribute(kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)dyn);
   if (e != hipSuccess) return e;
   const dim3 grid((tiles + NS - 1) / NS, P.n_layers);
-  if (mode == 0) hipLaunchKernelGGL((predict_rows4_kernel<NG, CH, NS>), grid, dim3(kR4Threads), dyn, st, P);
-  else hipLaunchKernelGGL((k2_rows4_kernel<NG, CH, NS>), grid, dim3(kR4Threads), dyn, st, P);
+  if (mode == 0) hipLaunchKernelGGL((predict_rows4_kernel<WK, NG, CH, NS>), grid, dim3(kR4Threads), dyn, st, P);
+  else hipLaunchKernelGGL((k2_rows4_kernel<WK, NG, CH, NS>), grid, dim3(kR4Threads), dyn, st, P);
   return hipGetLastError();
 }
-template <int NG, int CH>
+template <int WK, int NG, int CH>
 hipError_t launch_rows4_ns(const BatchParams& P, int mode, bool brief, int tiles, hipStream_t st) {
-  return brief ? launch_rows4<NG, CH, 4>(P, mode, tiles, st) : launch_rows4<NG, CH, 16>(P, mode, tiles, st);
+  return brief ? launch_rows4<WK, NG, CH, 4>(P, mode, tiles, st) : launch_rows4<WK, NG, CH, 16>(P, mode, tiles, st);
 }
-template <int NG>
+template <int WK, int NG>
 hipError_t launch_rows4_ch(const BatchParams& P, int mode, int ch, bool brief, int tiles, hipStream_t st) {
-  switch (ch) {
-    case 4: return launch_rows4_ns<NG, 4>(P, mode, brief, tiles, st);
-    case 8: return launch_rows4_ns<NG, 8>(P, mode, brief, tiles, st);
-    case 10: return launch_rows4_ns<NG, 10>(P, mode, brief, tiles, st);
-    case 12: return launch_rows4_ns<NG, 12>(P, mode, brief, tiles, st);
-    case 16: return launch_rows4_ns<NG, 16>(P, mode, brief, tiles, st);
-    default: return hipErrorInvalidValue;
+  if constexpr (WK == 0) {
+    switch (ch) {
+      case 4: return launch_rows4_ns<WK, NG, 4>(P, mode, brief, tiles, st);
+      case 8: return launch_rows4_ns<WK, NG, 8>(P, mode, brief, tiles, st);
+      case 10: return launch_rows4_ns<WK, NG, 10>(P, mode, brief, tiles, st);
+      case 12: return launch_rows4_ns<WK, NG, 12>(P, mode, brief, tiles, st);
+      case 16: return launch_rows4_ns<WK, NG, 16>(P, mode, brief, tiles, st);
+      default: return hipErrorInvalidValue;
+    }
+  } else {
+    switch (ch) {
+      case 4: return launch_rows4_ns<WK, NG, 4>(P, mode, brief, tiles, st);
+      case 5: return launch_rows4_ns<WK, NG, 5>(P, mode, brief, tiles, st);
+      case 6: return launch_rows4_ns<WK, NG, 6>(P, mode, brief, tiles, st);
+      case 8: return launch_rows4_ns<WK, NG, 8>(P, mode, brief, tiles, st);
+      default: return hipErrorInvalidValue;
+    }
   }
 }
+template <int WK>
 hipError_t launch_rows4_ng(const BatchParams& P, int mode, int ch, bool brief, int tiles, hipStream_t st) {
   switch ((P.B + 3) / 4) {
-    case 1: return launch_rows4_ch<1>(P, mode, ch, brief, tiles, st);
-    case 2: return launch_rows4_ch<2>(P, mode, ch, brief, tiles, st);
-    case 3: return launch_rows4_ch<3>(P, mode, ch, brief, tiles, st);
-    case 4: return launch_rows4_ch<4>(P, mode, ch, brief, tiles, st);
+    case 1: return launch_rows4_ch<WK, 1>(P, mode, ch, brief, tiles, st);
+    case 2: return launch_rows4_ch<WK, 2>(P, mode, ch, brief, tiles, st);
+    case 3: return launch_rows4_ch<WK, 3>(P, mode, ch, brief, tiles, st);
+    case 4: return launch_rows4_ch<WK, 4>(P, mode, ch, brief, tiles, st);
     default: return hipErrorInvalidValue;
   }
+}
+hipError_t launch_rows4_wk(const BatchParams& P, int wkind, int mode, int ch, bool brief, int tiles, hipStream_t st) {
+  return wkind == 0 ? launch_rows4_ng<0>(P, mode, ch, brief, tiles, st)
+         : wkind == 1 ? launch_rows4_ng<1>(P, mode, ch, brief, tiles, st)
+                      : launch_rows4_ng<2>(P, mode, ch, brief, tiles, st);
 }
 
 }  // namespace
@@ -1463,6 +1569,12 @@ size_t phased_batch_scratch_bytes(int d_model, int d_ff, int batch) { return bat
 bool phased_batch_supported(const FfnProblem& p) {
   const int r2 = p.d_model - p.r;
   int a = 0, b = 0;
+  if (p.w_fp8) {
+    // 8-bit codes: at most 16 tokens, through the whole-row kernels (rows of whole 256-byte multiples)
+    return p.batch >= 2 && p.batch <= 16 && p.q_bf16 && rows4_chunks(p.r, 1) > 0 && rows4_chunks(r2, 1) > 0 &&
+           p.d_model % 64 == 0 && p.d_ff <= 64 * kMaxWords && p.d_ff >= 16 &&
+           (size_t)p.d_ff * (size_t)p.d_model < ((size_t)1 << 31);
+  }
   return p.batch >= 2 && p.batch <= 64 && p.w_bf16 && p.q_bf16 && p.r % 32 == 0 && r2 % 32 == 0 &&
          p.d_model % 64 == 0 && p.d_ff <= 64 * kMaxWords && p.d_ff >= 16 && split_for(p.r, &a, &b) && split_for(r2, &a, &b) &&
          (size_t)p.d_ff * (size_t)p.d_model * 2 < ((size_t)1 << 31);  // 32-bit buffer offsets
@@ -1569,8 +1681,10 @@ hipError_t launch_ffn_phased_batch(const FfnProblem& p0, const void* const* k1n,
     // tokens always, with more only if k2 joins in and nobody needs the neuron-major scores).
     // Workgroups of 64 rows up to 8 tokens, of 256 above (measured on the 2B, 9B and paper shapes).
     const int ngrp = (B + 3) / 4;
-    int ch1 = rows4_on && nb == 1 ? rows4_chunks(p0.r) : 0, ch2 = rows4_on && nb == 1 ? rows4_chunks(p0.d_model - p0.r) : 0;
-    if (family != 4) {
+    const int wkind = p0.w_fp8;  // 0 bf16, 1 E4M3 codes, 2 integer codes (codes: whole-row kernels only)
+    int ch1 = (rows4_on || wkind) && nb == 1 ? rows4_chunks(p0.r, wkind) : 0, ch2 = (rows4_on || wkind) && nb == 1 ? rows4_chunks(p0.d_model - p0.r, wkind) : 0;
+    if (wkind && (ch1 == 0 || ch2 == 0)) return hipErrorInvalidValue;
+    if (family != 4 && !wkind) {
       if (ch2 * ngrp > 40) ch2 = 0;
       if (ch1 * ngrp > 48 || (ngrp > 2 && ch2 == 0)) ch1 = 0;
     }
@@ -1579,7 +1693,7 @@ hipError_t launch_ffn_phased_batch(const FfnProblem& p0, const void* const* k1n,
     if (ch1 > 0) {
       BatchParams P1 = P;
       if (ch2 > 0) P1.ST = nullptr;  // nobody reads the neuron-major copy then
-      err = launch_rows4_ng(P1, 0, ch1, r4_short1, tiles, st);
+      err = launch_rows4_wk(P1, wkind, 0, ch1, r4_short1, tiles, st);
     }
     else if (B <= 4 && cpl1 <= 2 && g_batch_stream != 0) {
       // a few tokens: the vector-ALU sweep (whole-row loads)
@@ -1601,7 +1715,7 @@ hipError_t launch_ffn_phased_batch(const FfnProblem& p0, const void* const* k1n,
     hipLaunchKernelGGL(union_batch_kernel, dim3(L), dim3(4 * kMaxWords), 0, st, P);
     if (ch2 > 0) {
       P.TPW2 = r4_short2 ? 4 : 16;
-      err = launch_rows4_ng(P, 1, ch2, r4_short2, tiles, st);
+      err = launch_rows4_wk(P, wkind, 1, ch2, r4_short2, tiles, st);
     } else if (stream_ok && stream_split(p0.d_model - p0.r, &gs, &ng)) {
       P.TPW2 = kStreamWaves * (s2_short ? 1 : 4);
       err = s2_short ? launch_stream_split<1>(P, 1, gs, ng, tiles, st) : launch_stream_split<4>(P, 1, gs, ng, tiles, st);
@@ -1623,6 +1737,14 @@ hipError_t launch_ffn_phased_batch(const FfnProblem& p0, const void* const* k1n,
     err = hipFuncSetAttribute(vk, hipFuncAttributeMaxDynamicSharedMemorySize,
                               (int)((size_t)kVMaxWaves * 32 * kVPitch + (size_t)2 * planes_for(nb) * nb * kWave * 16));
     if (err != hipSuccess) return err;
+    if (wkind) {
+      const void* vk8 = wkind == 1 ? reinterpret_cast<const void*>(v_batch_kernel<1, 1>) : reinterpret_cast<const void*>(v_batch_kernel<1, 2>);
+      err = hipFuncSetAttribute(vk8, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                (int)((size_t)kVMaxWaves * 32 * kVPitch + (size_t)2 * planes_for(1) * kWave * 16));
+      if (err != hipSuccess) return err;
+      if (wkind == 1) hipLaunchKernelGGL((v_batch_kernel<1, 1>), gv, dim3(nwv * kWave), vdyn, st, P);
+      else hipLaunchKernelGGL((v_batch_kernel<1, 2>), gv, dim3(nwv * kWave), vdyn, st, P);
+    } else
     switch (nb) {
       case 1: hipLaunchKernelGGL((v_batch_kernel<1>), gv, dim3(nwv * kWave), vdyn, st, P); break;
       case 2: hipLaunchKernelGGL((v_batch_kernel<2>), gv, dim3(nwv * kWave), vdyn, st, P); break;

@@ -102,8 +102,10 @@ def test_dense_evaluation_and_tanh_gelu(kind):
 @pytest.mark.parametrize("shape,batch", [(synth.TINY, 2), (synth.TINY, 16), (synth.FFNShape("odd", 1040, 1000, 272, 77), 5),
                                          (synth.GEMMA2_2B, 4), (synth.TINY, 64)])
 def test_batches_take_the_general_kernels(shape, batch, kind):
-    """More than one token with 8-bit weight rows: every token against the oracle on the dequantised
-    weights, the union list against the oracle's, and y[b] equal to the one-token result."""
+    """More than one token with 8-bit weight rows, on shapes, token types and batch sizes that the
+    whole-row kernels do not take (and the 2B shape with bf16 tokens, which they do): every token against
+    the oracle on the dequantised weights, the union list against the oracle's, and y[b] equal to the
+    one-token result."""
     packed, deq = _quantised_stack(shape, 2, 340, kind)
     for qdtype in (torch.bfloat16, torch.float32):
         q = synth.tokens(shape, batch, 341 + batch, qdtype)
@@ -113,6 +115,53 @@ def test_batches_take_the_general_kernels(shape, batch, kind):
         solo = _run(shape, packed, q[1:2], True, kind=kind)
         assert np.array_equal(solo["idx"][:, 0], out["idx"][:, 1])
         assert np.linalg.norm(solo["y"][:, 0] - out["y"][:, 1]) <= 1e-6 * np.linalg.norm(solo["y"][:, 0])
+
+
+@pytest.mark.parametrize("kind", ["fp8", "int8"])
+@pytest.mark.parametrize("d_model,d_ff,r,k", [(2304, 1000, 1024, 77), (3072, 600, 1536, 48), (3584, 200, 1536, 20),
+                                              (2048, 2085, 1024, 160)])
+@pytest.mark.parametrize("batch", [2, 7, 12, 16])
+def test_batches_on_the_whole_row_kernels(d_model, d_ff, r, k, batch, kind):
+    """Two to sixteen bf16 tokens with rows of whole 256-code multiples: the whole-row matrix-core kernels
+    widen the codes to bf16 in registers (predict, k2) and on the way into LDS (V).  Every compiled row
+    length (1024 .. 2048 codes), one to four groups of four tokens, ragged numbers of neurons, one and
+    several layers; against the oracle on the dequantised weights and against the one-token path."""
+    sh = synth.FFNShape("rows4-8bit", d_model, d_ff, r, k)
+    for n_layers in (1, 3):
+        packed, deq = _quantised_stack(sh, n_layers, 360 + n_layers, kind)
+        q = synth.tokens(sh, batch, 370 + batch, torch.bfloat16)
+        out = _run(sh, packed, q, True, kind=kind)
+        check_ffn_against_oracle(sh, deq, q, out, TOL_BF16_TIGHT, what=f"{kind} whole rows B={batch} L={n_layers}")
+        solo = _run(sh, packed, q[batch - 1:batch], True, kind=kind)
+        assert np.linalg.norm(solo["y"][:, 0] - out["y"][:, batch - 1]) <= 1e-5 * np.linalg.norm(solo["y"][:, 0])
+
+
+@pytest.mark.parametrize("kind", ["fp8", "int8"])
+def test_prefill_in_chunks_on_the_whole_row_kernels(kind):
+    """A prompt through a 2B-shaped layer with 8-bit weights in chunks of 8 (the full chunks share one set
+    of batched launches, the shorter last chunk takes a call of its own): sampled tokens and every
+    chunk's union size against the oracle."""
+    sh = synth.FFNShape("prefill-8bit", 2304, 1000, 1024, 77)
+    packed, deq = _quantised_stack(sh, 1, 380, kind)
+    layer = binding.make_layer_fp8(*packed[0], sh.d_model, sh.d_ff, sh.r, sh.k, code_dtype=KINDS[kind][0])
+    T, chunk = 29, 8
+    q = synth.tokens(sh, T, 381, torch.bfloat16)
+    ws = binding.make_prefill_workspace(sh.d_model, sh.d_ff, chunk, DEV)
+    nch = (T + chunk - 1) // chunk
+    y = torch.full((T, sh.d_model), float("nan"), device=DEV)
+    theta = torch.zeros(T, device=DEV)
+    cnt = torch.zeros(T, dtype=torch.int32, device=DEV)
+    idx = torch.full((T, sh.d_ff), -1, dtype=torch.int32, device=DEV)
+    ucnt = torch.zeros(nch, dtype=torch.int32, device=DEV)
+    uidx = torch.full((nch, sh.d_ff), -1, dtype=torch.int32, device=DEV)
+    binding.spark_ffn_prefill(layer, q.to(DEV), chunk, y, ws, theta, cnt, idx, ucnt, uidx)
+    torch.cuda.synchronize()
+    for c in range(nch):
+        t0, t1 = c * chunk, min(T, (c + 1) * chunk)
+        sub = dict(y=y[None, t0:t1].cpu().numpy(), theta=theta[None, t0:t1].cpu().numpy(),
+                   count=cnt[None, t0:t1].cpu().numpy(), idx=idx[None, t0:t1].cpu().numpy(),
+                   ucount=ucnt[c:c + 1].cpu().numpy(), uidx=uidx[c:c + 1].cpu().numpy())
+        check_ffn_against_oracle(sh, deq, q[t0:t1], sub, TOL_BF16_TIGHT, what=f"{kind} prefill chunk {c}")
 
 
 @pytest.mark.parametrize("kind", ["fp8", "int8"])
