@@ -514,11 +514,28 @@ def fp8_bench(torch, binding, synth, dev, np, kind="fp8"):
     gpu_s, _ = time_region(step, 200, 20, torch)
     per = gpu_s / 200
     nbytes = float(np.sum(sh.d_ff * (sh.r + 4) + m * (2 * sh.d_model - sh.r + 8)))
-    return {"workload": f"gemma2-2b-shape, {L} layers, batch 1, {'E4M3' if kind == 'fp8' else 'signed 8-bit integer'} "
-                        "weight codes with per-row fp32 scales",
-            "us_per_layer": per / L * 1e6, "layers_per_s": L / per, "active_count_mean": float(m.mean()),
-            "algorithmic_bytes_per_layer": nbytes / L, "achieved_gbs": nbytes / per / 1e9,
-            "hbm_frac": nbytes / per / 1e9 / HBM_PEAK_GBS}
+    out = {"workload": f"gemma2-2b-shape, {L} layers, batch 1, {'E4M3' if kind == 'fp8' else 'signed 8-bit integer'} "
+                       "weight codes with per-row fp32 scales",
+           "us_per_layer": per / L * 1e6, "layers_per_s": L / per, "active_count_mean": float(m.mean()),
+           "algorithmic_bytes_per_layer": nbytes / L, "achieved_gbs": nbytes / per / 1e9,
+           "hbm_frac": nbytes / per / 1e9 / HBM_PEAK_GBS, "batches": []}
+    # the same stack with 4, 16 and 64 tokens per call (the batched matrix-core kernels on widened codes);
+    # algorithmic bytes: the predictor rows and, for the union U of the tokens' active sets, the K2n and Vn rows
+    for B in (4, 16, 64):
+        qb = synth.tokens(sh, B, 2001 + B, torch.bfloat16, dev)
+        wsb = binding.make_workspace(sh.d_model, sh.d_ff, B, dev)
+        yb = torch.empty(L, B, sh.d_model, device=dev)
+        ucnt = torch.zeros(L, dtype=torch.int32, device=dev)
+        binding.spark_ffn_decode_layers(layers, qb, yb, wsb, union_count=ucnt)
+        torch.cuda.synchronize()
+        u = ucnt.cpu().numpy().astype(np.float64)
+        gpu_b, _ = time_region(lambda: binding.spark_ffn_decode_layers(layers, qb, yb, wsb), 50, 5, torch)
+        perb = gpu_b / 50
+        nb = float(np.sum(sh.d_ff * (sh.r + 4) + u * (2 * sh.d_model - sh.r + 8)))
+        out["batches"].append({"batch": B, "us_per_layer": perb / L * 1e6, "tokens_per_s": B / perb,
+                               "union_size_mean": float(u.mean()), "algorithmic_bytes_per_layer": nb / L,
+                               "achieved_gbs": nb / perb / 1e9, "hbm_frac": nb / perb / 1e9 / HBM_PEAK_GBS})
+    return out
 
 
 def master_weight_error(torch, binding, synth, dev, shape, q, y0, cnt0, idx0):

@@ -149,10 +149,13 @@ spark_status spark_stat_topk_huber_backward(const void* x, const void* gy, spark
  * row: weight[j][c] = scale[j] * value(code[j][c]).  cols (r, d_model - r, d_model) must be
  * multiples of 16.  One token per call (spark_ffn_decode, spark_ffn_decode_layers,
  * spark_ffn_dense_decode_layers, spark_ffn_prefill with chunk 1) takes the bandwidth-bound
- * phase-by-phase kernels; batches and longer chunks are evaluated by the general kernels (a
- * launch sequence per layer, not tuned); the dense comparison calls take one token only
- * (SPARK_ERR_DTYPE otherwise).  Arithmetic: codes widened exactly to fp32, fp32 products and
- * sums, the row's scale applied to the finished dot product. */
+ * phase-by-phase kernels; 2 to 64 bf16 tokens (and prefill chunks of that size) with r and
+ * d_model - r multiples of 256 (up to 2048 for at most 16 tokens, 1536 for 33 to 64, 1024 for 17
+ * to 32) take the batched matrix-core kernels, which widen the codes to bf16 (exact for both
+ * kinds); every other batch is evaluated by the general kernels (a launch sequence per layer,
+ * not tuned); the dense comparison calls take one token only
+ * (SPARK_ERR_DTYPE otherwise).  Arithmetic: codes widened exactly, fp32 products and sums, the
+ * row's scale applied to the finished dot product. */
 typedef struct {
   int32_t d_model;    /* input / output width                                   */
   int32_t d_ff;       /* number of neurons, >= 2                                */

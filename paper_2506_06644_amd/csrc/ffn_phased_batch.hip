@@ -224,6 +224,29 @@ __device__ __forceinline__ void rows_times_tokens(const bf16_t* __restrict__ w, 
   }
 }
 
+// 8-bit weight codes (WK = 1: OCP E4M3, 2: signed integers): the 16 codes of one 16-byte piece
+// widened to bf16, which holds both kinds exactly (an E4M3 value has 4 significant bits, an
+// integer up to 127 has 7), as 8 words in element order.  The row's scale is applied to the
+// finished dot product by the caller.
+template <int WK>
+__device__ __forceinline__ void codes_to_bf16(u32x4 a, uint32_t (&o)[8]) {
+  typedef float f32x2_v __attribute__((ext_vector_type(2)));
+#pragma unroll
+  for (int d = 0; d < 4; ++d) {
+    float f[4];
+    if constexpr (WK == 1) {
+      const f32x2_v lo = __builtin_amdgcn_cvt_pk_f32_fp8((int)a[d], false), hi = __builtin_amdgcn_cvt_pk_f32_fp8((int)a[d], true);
+      f[0] = lo[0]; f[1] = lo[1]; f[2] = hi[0]; f[3] = hi[1];
+    } else {
+#pragma unroll
+      for (int e = 0; e < 4; ++e) f[e] = (float)(int)(int8_t)(a[d] >> (8 * e));
+    }
+    // (the upper halves of two floats side by side: truncation is exact here)
+    o[2 * d] = __builtin_amdgcn_perm(__float_as_uint(f[1]), __float_as_uint(f[0]), 0x07060302u);
+    o[2 * d + 1] = __builtin_amdgcn_perm(__float_as_uint(f[3]), __float_as_uint(f[2]), 0x07060302u);
+  }
+}
+
 // ------------------------------------------------- rows x tokens, tiles staged in LDS (> 16 tokens)
 // The k-split kernels above read a tile of 16 rows in 64- and 128-byte pieces, one piece per
 // row and instruction, which the memory system serves well below what whole rows reach.  Here
@@ -238,21 +261,29 @@ __device__ __forceinline__ void rows_times_tokens(const bf16_t* __restrict__ w, 
 template <int CJ>
 constexpr int staged_pitch() { return CJ * 512 + 16; }  // bytes between rows of a tile in LDS (K = 256 CJ)
 template <int NB, int CJ>
-constexpr size_t staged_lds_bytes() { return (size_t)2 * 16 * staged_pitch<CJ>() + (size_t)2 * 2 * NB * 4 * kWave * sizeof(float); }
-template <int NB, int CJ, bool HAS_SIDE, typename RowOf, typename Pre, typename Emit>
-__device__ __forceinline__ void rows_times_tokens_staged(const bf16_t* __restrict__ w, uint32_t w_bytes,
+constexpr size_t staged_lds_bytes() {
+  return (size_t)2 * 16 * staged_pitch<CJ>() + (size_t)2 * 2 * NB * 4 * kWave * sizeof(float) + 4 * 16 * sizeof(float);
+}
+// WK != 0: the rows are 8-bit codes (K bytes each); they are widened to bf16 when a tile is parked,
+// so the tile in LDS and the multiplies are the same, and scale_of(row) (the row's scale, fetched
+// with the row by the lane that stages its first piece) reaches the emit waves through LDS.
+template <int WK, int NB, int CJ, bool HAS_SIDE, typename RowOf, typename ScaleOf, typename Pre, typename Emit>
+__device__ __forceinline__ void rows_times_tokens_staged(const void* __restrict__ w, uint32_t w_bytes,
                                                          const bf16_t* __restrict__ q, int64_t ldq, int qoff, int B,
                                                          int tile0, int ntiles, int tile_end, unsigned char* lds,
-                                                         RowOf row_of, Pre pre, Emit emit) {
+                                                         RowOf row_of, ScaleOf scale_of, Pre pre, Emit emit) {
   constexpr int K = 256 * CJ, PITCH = staged_pitch<CJ>(), TILE = 16 * PITCH;
   constexpr int NCW = 2 * NB, kEmitWaves = kRowWavesAll - NCW;
   constexpr int NBE = (NB + kEmitWaves - 1) / kEmitWaves;
   constexpr int HS = 4 * CJ;            // k steps (of 32) per half row
   constexpr int RPWV = 16 / NCW;        // rows a compute wave stages per tile
   constexpr int LPR = kWave / RPWV;     // lanes per staged row
-  constexpr int NLD = K / 8 / LPR;      // 16-byte loads per lane and tile
+  constexpr int ROWB = WK ? K : 2 * K;  // bytes of a row in memory
+  constexpr int NPC = ROWB / 16;        // its 16-byte pieces
+  constexpr int NLD = (NPC + LPR - 1) / LPR;  // 16-byte loads per lane and tile
   static_assert(16 % NCW == 0 && NCW < kRowWavesAll, "two or four token blocks");
   float(*red)[2][NB * 4][kWave] = reinterpret_cast<float(*)[2][NB * 4][kWave]>(lds + 2 * TILE);
+  float(*sc_sh)[16] = reinterpret_cast<float(*)[16]>(lds + 2 * TILE + sizeof(float) * 2 * 2 * NB * 4 * kWave);
   const int lane = threadIdx.x & (kWave - 1);
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
   const int kg = lane >> 4, ri = lane & 15;
@@ -277,7 +308,10 @@ __device__ __forceinline__ void rows_times_tokens_staged(const bf16_t* __restric
         if (nb < NB) {
           f32x4 v;
 #pragma unroll
-          for (int e = 0; e < 4; ++e) v[e] = red[buf][0][nb * 4 + e][lane] + red[buf][1][nb * 4 + e][lane];
+          for (int e = 0; e < 4; ++e) {
+            v[e] = red[buf][0][nb * 4 + e][lane] + red[buf][1][nb * 4 + e][lane];
+            if constexpr (WK != 0) v[e] *= sc_sh[i & 3][4 * kg + e];
+          }
           emit(tile0 + i, nb, v, f32x4{sv[k][0], sv[k][1], sv[k][2], sv[k][3]});
         }
       }
@@ -303,17 +337,39 @@ __device__ __forceinline__ void rows_times_tokens_staged(const bf16_t* __restric
     if (b >= B) qf[s] = u32x4{0u, 0u, 0u, 0u};
   }
   const int srow = wave * RPWV + lane % RPWV, piece = lane / RPWV;  // the row of the tile this lane stages
-  auto load_stage = [&](int t, u32x4(&st)[NLD]) {  // tiles past tile_end: a descriptor without records
+  auto load_stage = [&](int t, u32x4(&st)[NLD], float& sc) {  // tiles past tile_end: a descriptor without records
     const __amdgpu_buffer_rsrc_t rs =
-        __builtin_amdgcn_make_buffer_rsrc(const_cast<bf16_t*>(w), 0, t < tile_end ? (int)w_bytes : 0, 0x00020000);
-    const uint32_t off = (uint32_t)row_of(t, srow) * (uint32_t)(K * 2) + (uint32_t)piece * 16u;
+        __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(w), 0, t < tile_end ? (int)w_bytes : 0, 0x00020000);
+    const int row = row_of(t, srow);
+    const uint32_t off = (uint32_t)row * (uint32_t)ROWB;
 #pragma unroll
-    for (int j = 0; j < NLD; ++j) st[j] = __builtin_amdgcn_raw_buffer_load_b128(rs, (int)(off + (uint32_t)(j * LPR * 16)), 0, kAuxNontemporal);
+    for (int j = 0; j < NLD; ++j)  // (pieces past the row's end: its last piece again, not parked)
+      st[j] = __builtin_amdgcn_raw_buffer_load_b128(rs, (int)(off + (uint32_t)min(piece + j * LPR, NPC - 1) * 16u), 0, kAuxNontemporal);
+    if constexpr (WK != 0) {
+      if (piece == 0) sc = scale_of(row);
+    }
   };
-  auto park = [&](const u32x4(&st)[NLD], int slot) {
-    unsigned char* dst = lds + slot * TILE + srow * PITCH + piece * 16;
+  // (the scales have four slots: a tile's are written a step before its multiply and read by the
+  // emit waves a step after it, while the next tiles are already being parked)
+  auto park = [&](const u32x4(&st)[NLD], float sc, int slot, int i) {
+    unsigned char* dst = lds + slot * TILE + srow * PITCH;
 #pragma unroll
-    for (int j = 0; j < NLD; ++j) *reinterpret_cast<u32x4*>(dst + j * LPR * 16) = st[j];
+    for (int j = 0; j < NLD; ++j) {
+      const int pc = piece + j * LPR;
+      if constexpr (WK == 0) {
+        *reinterpret_cast<u32x4*>(dst + pc * 16) = st[j];
+      } else {
+        if (NPC % LPR == 0 || pc < NPC) {
+          uint32_t o[8];
+          codes_to_bf16<WK>(st[j], o);
+          *reinterpret_cast<u32x4*>(dst + pc * 32) = u32x4{o[0], o[1], o[2], o[3]};
+          *reinterpret_cast<u32x4*>(dst + pc * 32 + 16) = u32x4{o[4], o[5], o[6], o[7]};
+        }
+      }
+    }
+    if constexpr (WK != 0) {
+      if (piece == 0) sc_sh[i & 3][srow] = sc;
+    }
   };
   auto multiply = [&](int slot, int buf) {
     const unsigned char* src = lds + slot * TILE + ri * PITCH + (h * HS * 4 + kg) * 16;
@@ -324,23 +380,24 @@ __device__ __forceinline__ void rows_times_tokens_staged(const bf16_t* __restric
     for (int e = 0; e < 4; ++e) red[buf][h][nbw * 4 + e][lane] = acc[e];
   };
   u32x4 st0[NLD], st1[NLD];
-  load_stage(tile0, st0);
-  load_stage(tile0 + 1, st1);
+  float sc0 = 1.f, sc1 = 1.f;
+  load_stage(tile0, st0, sc0);
+  load_stage(tile0 + 1, st1, sc1);
   __builtin_amdgcn_sched_barrier(0);
-  park(st0, 0);
-  load_stage(tile0 + 2, st0);
+  park(st0, sc0, 0, 0);
+  load_stage(tile0 + 2, st0, sc0);
   __builtin_amdgcn_sched_barrier(0);
   lds_barrier();
   for (int i = 0; i < ntiles; i += 2) {  // ntiles is even
-    park(st1, 1);
+    park(st1, sc1, 1, i + 1);
     __builtin_amdgcn_sched_barrier(0);
-    load_stage(tile0 + i + 3, st1);
+    load_stage(tile0 + i + 3, st1, sc1);
     __builtin_amdgcn_sched_barrier(0);
     multiply(0, 0);
     lds_barrier();
-    park(st0, 0);
+    park(st0, sc0, 0, i + 2);
     __builtin_amdgcn_sched_barrier(0);
-    load_stage(tile0 + i + 4, st0);
+    load_stage(tile0 + i + 4, st0, sc0);
     __builtin_amdgcn_sched_barrier(0);
     multiply(1, 1);
     lds_barrier();
@@ -383,7 +440,7 @@ __global__ __launch_bounds__(kRowThreads) void predict_batch_kernel(const BatchP
       });
 }
 
-template <int NB, int CJ>
+template <int WK, int NB, int CJ>
 __global__ __launch_bounds__(kRowThreads) void predict_staged_kernel(const BatchParams P) {
   extern __shared__ __align__(16) unsigned char staged_lds[];
   const int lane = threadIdx.x & (kWave - 1);
@@ -394,10 +451,12 @@ __global__ __launch_bounds__(kRowThreads) void predict_staged_kernel(const Batch
   if (tile0 >= tiles_total) return;
   float* S = P.S + (size_t)l * P.B * P.d_ff;
   float* ST = P.ST ? P.ST + (size_t)l * P.d_ff * P.BP : nullptr;  // (written only if a k2 kernel reads it)
-  rows_times_tokens_staged<NB, CJ, false>(
-      static_cast<const bf16_t*>(P.k1n[l]), (uint32_t)P.d_ff * (uint32_t)P.r * 2u, P.q + (size_t)l * P.qslot, P.ldq, 0, P.B, tile0,
+  const float* k1s = reinterpret_cast<const float*>(static_cast<const char*>(P.k1n[l]) + (size_t)P.d_ff * P.r);  // (codes only)
+  rows_times_tokens_staged<WK, NB, CJ, false>(
+      P.k1n[l], (uint32_t)P.d_ff * (uint32_t)P.r * (WK ? 1u : 2u), P.q + (size_t)l * P.qslot, P.ldq, 0, P.B, tile0,
       P.TPW1, min(tile0 + P.TPW1, tiles_total), staged_lds,
-      [&](int t, int i) { return min(t * 16 + i, P.d_ff - 1); }, [](int, int, int) { return 0.f; },
+      [&](int t, int i) { return min(t * 16 + i, P.d_ff - 1); }, [&](int row) { return k1s[row]; },
+      [](int, int, int) { return 0.f; },
       [&](int t, int nb, f32x4 v, f32x4) {
         const int b = nb * 16 + ri, j = t * 16 + 4 * kg;
         if (t >= tiles_total) return;
@@ -699,7 +758,7 @@ __global__ __launch_bounds__(kRowThreads) void k2_batch_kernel(const BatchParams
   if (tile0 + P.TPW2 >= tiles_total) k2_zero_tail<kRowThreads>(P, up, (tile0 + P.TPW2) * 16, rank_end);
 }
 
-template <int NB, int CJ>
+template <int WK, int NB, int CJ>
 __global__ __launch_bounds__(kRowThreads) void k2_staged_kernel(const BatchParams P) {
   extern __shared__ __align__(16) unsigned char staged_lds[];
   __shared__ int rowidx[32 * 16 + 16];
@@ -716,10 +775,14 @@ __global__ __launch_bounds__(kRowThreads) void k2_staged_kernel(const BatchParam
 #pragma unroll
   for (int nb = 0; nb < NB; ++nb) th[nb] = P.thetas[(size_t)l * P.B + min(nb * 16 + ri, P.B - 1)];
   uint16_t* up = P.up + (size_t)l * P.B * P.ldu;
-  rows_times_tokens_staged<NB, CJ, true>(
-      static_cast<const bf16_t*>(P.k2n[l]), (uint32_t)P.d_ff * (uint32_t)(P.d_model - P.r) * 2u, P.q + (size_t)l * P.qslot, P.ldq,
+  // (codes: a row's two scales travel as their product; the V step then multiplies plain codes)
+  const float* k2s = reinterpret_cast<const float*>(static_cast<const char*>(P.k2n[l]) + (size_t)P.d_ff * (P.d_model - P.r));
+  const float* vs = reinterpret_cast<const float*>(static_cast<const char*>(P.vn[l]) + (size_t)P.d_ff * P.d_model);
+  rows_times_tokens_staged<WK, NB, CJ, true>(
+      P.k2n[l], (uint32_t)P.d_ff * (uint32_t)(P.d_model - P.r) * (WK ? 1u : 2u), P.q + (size_t)l * P.qslot, P.ldq,
       P.r, P.B, tile0, P.TPW2, min(tile0 + P.TPW2, tiles_total), staged_lds,
       [&](int t, int i) { return rowidx[min((t - tile0) * 16 + i, P.TPW2 * 16 + 15)]; },
+      [&](int row) { return k2s[row] * vs[row]; },
       [&](int t, int nb, int e) {  // the score the (row, token) pair will need, from the token-major array
         const int b = min(nb * 16 + ri, P.B - 1);
         return S[(size_t)b * P.d_ff + rowidx[min((t - tile0) * 16 + 4 * kg + e, P.TPW2 * 16 + 15)]];
@@ -926,29 +989,6 @@ __device__ __forceinline__ float blocks_to_lanes(const f32x4 (&acc)[NG], int lan
 }
 
 constexpr int r4_pitch(int NS) { return NS * 16 + 4; }  // floats between tokens of the result tile in LDS
-
-// 8-bit weight codes (WK = 1: OCP E4M3, 2: signed integers): the 16 codes of one 16-byte piece
-// widened to bf16, which holds both kinds exactly (an E4M3 value has 4 significant bits, an
-// integer up to 127 has 7), as 8 words in element order.  The row's scale is applied to the
-// finished dot product by the caller.
-template <int WK>
-__device__ __forceinline__ void codes_to_bf16(u32x4 a, uint32_t (&o)[8]) {
-  typedef float f32x2_v __attribute__((ext_vector_type(2)));
-#pragma unroll
-  for (int d = 0; d < 4; ++d) {
-    float f[4];
-    if constexpr (WK == 1) {
-      const f32x2_v lo = __builtin_amdgcn_cvt_pk_f32_fp8((int)a[d], false), hi = __builtin_amdgcn_cvt_pk_f32_fp8((int)a[d], true);
-      f[0] = lo[0]; f[1] = lo[1]; f[2] = hi[0]; f[3] = hi[1];
-    } else {
-#pragma unroll
-      for (int e = 0; e < 4; ++e) f[e] = (float)(int)(int8_t)(a[d] >> (8 * e));
-    }
-    // (the upper halves of two floats side by side: truncation is exact here)
-    o[2 * d] = __builtin_amdgcn_perm(__float_as_uint(f[1]), __float_as_uint(f[0]), 0x07060302u);
-    o[2 * d + 1] = __builtin_amdgcn_perm(__float_as_uint(f[3]), __float_as_uint(f[2]), 0x07060302u);
-  }
-}
 
 // row_of(local row) gives the matrix row of the workgroup's local row (any valid row for rows
 // that do not count); rows from `nrows` on are not read when a whole step lies past them.
@@ -1438,31 +1478,37 @@ hipError_t launch_rows_nb(const BatchParams& P, int mode, int nb, int K, dim3 gr
 // wave keeps 4 CJ token operands in registers; with two token blocks it stages four rows per
 // tile, and the registers are enough up to CJ = 4).
 int staged_cj(int K, int nb) { return (K % 256 == 0 && K / 256 >= 2 && K / 256 <= (nb == 2 ? 4 : 6)) ? K / 256 : 0; }
-template <int NB, int CJ>
+template <int WK, int NB, int CJ>
 hipError_t launch_staged(const BatchParams& P, int mode, dim3 grid, hipStream_t st) {
   const size_t dyn = staged_lds_bytes<NB, CJ>();
-  const void* kern = mode == 0 ? reinterpret_cast<const void*>(predict_staged_kernel<NB, CJ>)
-                               : reinterpret_cast<const void*>(k2_staged_kernel<NB, CJ>);
+  const void* kern = mode == 0 ? reinterpret_cast<const void*>(predict_staged_kernel<WK, NB, CJ>)
+                               : reinterpret_cast<const void*>(k2_staged_kernel<WK, NB, CJ>);
   const hipError_t e = hipFuncSetAttribute(kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)dyn);
   if (e != hipSuccess) return e;
-  if (mode == 0) hipLaunchKernelGGL((predict_staged_kernel<NB, CJ>), grid, dim3(kRowThreads), dyn, st, P);
-  else hipLaunchKernelGGL((k2_staged_kernel<NB, CJ>), grid, dim3(kRowThreads), dyn, st, P);
+  if (mode == 0) hipLaunchKernelGGL((predict_staged_kernel<WK, NB, CJ>), grid, dim3(kRowThreads), dyn, st, P);
+  else hipLaunchKernelGGL((k2_staged_kernel<WK, NB, CJ>), grid, dim3(kRowThreads), dyn, st, P);
   return hipGetLastError();
 }
-template <int NB>
+template <int WK, int NB>
 hipError_t launch_staged_cj(const BatchParams& P, int mode, int cj, dim3 grid, hipStream_t st) {
   switch (cj) {
-    case 2: return launch_staged<NB, 2>(P, mode, grid, st);
-    case 3: return launch_staged<NB, 3>(P, mode, grid, st);
-    case 4: return launch_staged<NB, 4>(P, mode, grid, st);
-    case 5: if constexpr (NB == 4) return launch_staged<NB, 5>(P, mode, grid, st); else return hipErrorInvalidValue;
-    case 6: if constexpr (NB == 4) return launch_staged<NB, 6>(P, mode, grid, st); else return hipErrorInvalidValue;
+    case 2: return launch_staged<WK, NB, 2>(P, mode, grid, st);
+    case 3: return launch_staged<WK, NB, 3>(P, mode, grid, st);
+    case 4: return launch_staged<WK, NB, 4>(P, mode, grid, st);
+    case 5: if constexpr (NB == 4) return launch_staged<WK, NB, 5>(P, mode, grid, st); else return hipErrorInvalidValue;
+    case 6: if constexpr (NB == 4) return launch_staged<WK, NB, 6>(P, mode, grid, st); else return hipErrorInvalidValue;
     default: return hipErrorInvalidValue;
   }
 }
 // (three token blocks run as four: the fourth block's operands are zeros)
+template <int WK>
 hipError_t launch_staged_nb(const BatchParams& P, int mode, int nb, int cj, dim3 grid, hipStream_t st) {
-  return nb == 2 ? launch_staged_cj<2>(P, mode, cj, grid, st) : launch_staged_cj<4>(P, mode, cj, grid, st);
+  return nb == 2 ? launch_staged_cj<WK, 2>(P, mode, cj, grid, st) : launch_staged_cj<WK, 4>(P, mode, cj, grid, st);
+}
+hipError_t launch_staged_wk(const BatchParams& P, int wkind, int mode, int nb, int cj, dim3 grid, hipStream_t st) {
+  return wkind == 0 ? launch_staged_nb<0>(P, mode, nb, cj, grid, st)
+         : wkind == 1 ? launch_staged_nb<1>(P, mode, nb, cj, grid, st)
+                      : launch_staged_nb<2>(P, mode, nb, cj, grid, st);
 }
 
 // Streamed kernels (at most 16 tokens): k steps per group and groups per row for a row of K
@@ -1562,6 +1608,15 @@ hipError_t launch_rows4_wk(const BatchParams& P, int wkind, int mode, int ch, bo
                       : launch_rows4_ng<2>(P, mode, ch, brief, tiles, st);
 }
 
+template <int NB, int WK>
+hipError_t launch_v8(const BatchParams& P, dim3 grid, int nwv, size_t dyn, hipStream_t st) {
+  const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(v_batch_kernel<NB, WK>), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                           (int)((size_t)kVMaxWaves * 32 * kVPitch + (size_t)2 * planes_for(NB) * NB * kWave * 16));
+  if (e != hipSuccess) return e;
+  hipLaunchKernelGGL((v_batch_kernel<NB, WK>), grid, dim3(nwv * kWave), dyn, st, P);
+  return hipGetLastError();
+}
+
 }  // namespace
 
 size_t phased_batch_scratch_bytes(int d_model, int d_ff, int batch) { return batch_layout(d_model, d_ff, batch).total; }
@@ -1570,9 +1625,10 @@ bool phased_batch_supported(const FfnProblem& p) {
   const int r2 = p.d_model - p.r;
   int a = 0, b = 0;
   if (p.w_fp8) {
-    // 8-bit codes: at most 16 tokens, through the whole-row kernels (rows of whole 256-byte multiples)
-    return p.batch >= 2 && p.batch <= 16 && p.q_bf16 && rows4_chunks(p.r, 1) > 0 && rows4_chunks(r2, 1) > 0 &&
-           p.d_model % 64 == 0 && p.d_ff <= 64 * kMaxWords && p.d_ff >= 16 &&
+    // 8-bit codes: the whole-row kernels up to 16 tokens, the LDS-staged ones above (rows of whole 256-code multiples)
+    const int nb = (p.batch + 15) / 16;
+    const bool rows_ok = nb == 1 ? rows4_chunks(p.r, 1) > 0 && rows4_chunks(r2, 1) > 0 : staged_cj(p.r, nb) > 0 && staged_cj(r2, nb) > 0;
+    return p.batch >= 2 && p.batch <= 64 && p.q_bf16 && rows_ok && p.d_model % 64 == 0 && p.d_ff <= 64 * kMaxWords && p.d_ff >= 16 &&
            (size_t)p.d_ff * (size_t)p.d_model < ((size_t)1 << 31);
   }
   return p.batch >= 2 && p.batch <= 64 && p.w_bf16 && p.q_bf16 && p.r % 32 == 0 && r2 % 32 == 0 &&
@@ -1673,17 +1729,18 @@ hipError_t launch_ffn_phased_batch(const FfnProblem& p0, const void* const* k1n,
     // whose workgroups have three times the waves)
     const bool stream_ok = nb == 1 && (g_batch_stream == 2 || (g_batch_stream == 1 && (long long)L * ((tiles + 3) / 4) >= 256));
     const int cpl1 = (p0.r / 8 + kWave - 1) / kWave;
+    const int wkind = p0.w_fp8;  // 0 bf16, 1 E4M3 codes, 2 integer codes (codes: whole-row and staged kernels only)
     // more than 16 tokens: the LDS-staged kernels where a row's length is among the compiled ones
-    const int cj1 = nb >= 2 && family != 1 ? staged_cj(p0.r, nb) : 0, cj2 = nb >= 2 && family != 1 ? staged_cj(p0.d_model - p0.r, nb) : 0;
+    const int cj1 = nb >= 2 && (family != 1 || wkind) ? staged_cj(p0.r, nb) : 0, cj2 = nb >= 2 && (family != 1 || wkind) ? staged_cj(p0.d_model - p0.r, nb) : 0;
+    if (wkind && nb >= 2 && (cj1 == 0 || cj2 == 0)) return hipErrorInvalidValue;
     // At most 16 tokens and rows of whole 256-byte multiples: the whole-row kernels, as long as
     // the tokens' operands (a KB per 128 elements of a row and group of four tokens) leave room
     // for three workgroups per compute unit; the predictor only where it gains (with at most 8
     // tokens always, with more only if k2 joins in and nobody needs the neuron-major scores).
     // Workgroups of 64 rows up to 8 tokens, of 256 above (measured on the 2B, 9B and paper shapes).
     const int ngrp = (B + 3) / 4;
-    const int wkind = p0.w_fp8;  // 0 bf16, 1 E4M3 codes, 2 integer codes (codes: whole-row kernels only)
     int ch1 = (rows4_on || wkind) && nb == 1 ? rows4_chunks(p0.r, wkind) : 0, ch2 = (rows4_on || wkind) && nb == 1 ? rows4_chunks(p0.d_model - p0.r, wkind) : 0;
-    if (wkind && (ch1 == 0 || ch2 == 0)) return hipErrorInvalidValue;
+    if (wkind && nb == 1 && (ch1 == 0 || ch2 == 0)) return hipErrorInvalidValue;
     if (family != 4 && !wkind) {
       if (ch2 * ngrp > 40) ch2 = 0;
       if (ch1 * ngrp > 48 || (ngrp > 2 && ch2 == 0)) ch1 = 0;
@@ -1706,7 +1763,7 @@ hipError_t launch_ffn_phased_batch(const FfnProblem& p0, const void* const* k1n,
     else if (cj1 > 0) {
       BatchParams P1 = P;
       if (cj2 > 0) P1.ST = nullptr;  // the staged k2 kernel reads the token-major scores
-      err = launch_staged_nb(P1, 0, nb, cj1, dim3((tiles + tpw1 - 1) / tpw1, L), st);
+      err = launch_staged_wk(P1, wkind, 0, nb, cj1, dim3((tiles + tpw1 - 1) / tpw1, L), st);
     } else
       err = launch_rows_nb(P, 0, nb, p0.r, dim3((tiles + tpw1 - 1) / tpw1, L), st);
     if (err != hipSuccess) return err;
@@ -1720,7 +1777,7 @@ hipError_t launch_ffn_phased_batch(const FfnProblem& p0, const void* const* k1n,
       P.TPW2 = kStreamWaves * (s2_short ? 1 : 4);
       err = s2_short ? launch_stream_split<1>(P, 1, gs, ng, tiles, st) : launch_stream_split<4>(P, 1, gs, ng, tiles, st);
     } else if (cj2 > 0) {
-      err = launch_staged_nb(P, 1, nb, cj2, dim3((tiles + tpw2 - 1) / tpw2, L), st);
+      err = launch_staged_wk(P, wkind, 1, nb, cj2, dim3((tiles + tpw2 - 1) / tpw2, L), st);
     } else {
       err = launch_rows_nb(P, 1, nb, p0.d_model - p0.r, dim3((tiles + tpw2 - 1) / tpw2, L), st);
     }
@@ -1738,12 +1795,11 @@ hipError_t launch_ffn_phased_batch(const FfnProblem& p0, const void* const* k1n,
                               (int)((size_t)kVMaxWaves * 32 * kVPitch + (size_t)2 * planes_for(nb) * nb * kWave * 16));
     if (err != hipSuccess) return err;
     if (wkind) {
-      const void* vk8 = wkind == 1 ? reinterpret_cast<const void*>(v_batch_kernel<1, 1>) : reinterpret_cast<const void*>(v_batch_kernel<1, 2>);
-      err = hipFuncSetAttribute(vk8, hipFuncAttributeMaxDynamicSharedMemorySize,
-                                (int)((size_t)kVMaxWaves * 32 * kVPitch + (size_t)2 * planes_for(1) * kWave * 16));
+      err = wkind == 1 ? (nb == 1 ? launch_v8<1, 1>(P, gv, nwv, vdyn, st) : nb == 2 ? launch_v8<2, 1>(P, gv, nwv, vdyn, st)
+                          : nb == 3 ? launch_v8<3, 1>(P, gv, nwv, vdyn, st) : launch_v8<4, 1>(P, gv, nwv, vdyn, st))
+                       : (nb == 1 ? launch_v8<1, 2>(P, gv, nwv, vdyn, st) : nb == 2 ? launch_v8<2, 2>(P, gv, nwv, vdyn, st)
+                          : nb == 3 ? launch_v8<3, 2>(P, gv, nwv, vdyn, st) : launch_v8<4, 2>(P, gv, nwv, vdyn, st));
       if (err != hipSuccess) return err;
-      if (wkind == 1) hipLaunchKernelGGL((v_batch_kernel<1, 1>), gv, dim3(nwv * kWave), vdyn, st, P);
-      else hipLaunchKernelGGL((v_batch_kernel<1, 2>), gv, dim3(nwv * kWave), vdyn, st, P);
     } else
     switch (nb) {
       case 1: hipLaunchKernelGGL((v_batch_kernel<1>), gv, dim3(nwv * kWave), vdyn, st, P); break;

@@ -137,6 +137,22 @@ def test_batches_on_the_whole_row_kernels(d_model, d_ff, r, k, batch, kind):
 
 
 @pytest.mark.parametrize("kind", ["fp8", "int8"])
+@pytest.mark.parametrize("d_model,d_ff,r,k", [(2048, 600, 1024, 48), (2304, 1000, 1024, 77), (3072, 200, 1536, 20)])
+@pytest.mark.parametrize("batch", [17, 40, 64])
+def test_batches_on_the_staged_kernels(d_model, d_ff, r, k, batch, kind):
+    """Seventeen to sixty-four bf16 tokens: tiles of 16 rows of codes are widened to bf16 on the way into
+    LDS (predict, k2; the rows' scales travel with them) and in the V step.  Two, three and four token
+    blocks, every compiled row length, ragged numbers of neurons (the 2B-like shape with two token blocks
+    is one the staged kernels do not take: it goes through the general ones); against the oracle."""
+    sh = synth.FFNShape("staged-8bit", d_model, d_ff, r, k)
+    for n_layers in (1, 3):
+        packed, deq = _quantised_stack(sh, n_layers, 390 + n_layers, kind)
+        q = synth.tokens(sh, batch, 395 + batch, torch.bfloat16)
+        out = _run(sh, packed, q, True, kind=kind)
+        check_ffn_against_oracle(sh, deq, q, out, TOL_BF16_TIGHT, what=f"{kind} staged B={batch} L={n_layers}")
+
+
+@pytest.mark.parametrize("kind", ["fp8", "int8"])
 def test_prefill_in_chunks_on_the_whole_row_kernels(kind):
     """A prompt through a 2B-shaped layer with 8-bit weights in chunks of 8 (the full chunks share one set
     of batched launches, the shorter last chunk takes a call of its own): sampled tokens and every
