@@ -352,9 +352,8 @@ typedef struct {
                                        the tiles per workgroup of the k2 step                        */
   int32_t variant;                  /* one token: 1 = the 8-wave gather variant; batches: 100 x kernel
                                        family + row slices of the V step, families 1 = k-split kernels
-                                       for every batch size, 2 = streamed kernels (at most 16 tokens)
-                                       however small the launch, 3 = automatic without the whole-row
-                                       kernels, 4 = whole-row kernels wherever they are compiled     */
+                                       for every batch size, 4 = whole-row kernels wherever they are
+                                       compiled, 5 = LDS-staged kernels wherever they are compiled   */
 } spark_ffn_tuning;
 
 /* spark_ffn_decode_layers with pinned choices (`tuning` is a host pointer, NULL = automatic). */

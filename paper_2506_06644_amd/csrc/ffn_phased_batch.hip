@@ -1,28 +1,31 @@
 // Spark-FFN decode (Eq.2 of arXiv 2506.06644) for a batch of 2..64 tokens and a stack of
 // independent layers, phase by phase over the whole stack, on the matrix cores of gfx950
-// (bf16 weights and bf16 tokens; Appendix B's batching: every token has its own threshold and
+// (bf16 or 8-bit weights and bf16 tokens; Appendix B's batching: every token has its own threshold and
 // mask, the union of the masks decides which weight rows are fetched).
 //
-//   predict   S[l][b][j] = K1n_l[j] . q_b[:r]: tiles of 16 neurons x all tokens,
-//             v_mfma_f32_16x16x32_bf16 with the k range split over the 8 waves of a workgroup;
-//             the token fragments stay in registers while the workgroup walks its tiles.
-//             With at most 16 tokens (one token block) the token fragments of every k step fit
-//             in LDS instead, and a wave streams whole tiles by itself (no k split, no partial
-//             sums, no barriers); the same holds for k2.
+//   predict   S[l][b][j] = K1n_l[j] . q_b[:r].  Three kernel families, chosen per call: with at
+//             most 16 tokens a wave reads four rows whole and multiplies on the 4x4x4 matrix
+//             instruction (tokens in LDS); with more, 16-row tiles are staged in LDS by whole-row
+//             loads and multiplied with v_mfma_f32_16x16x32_bf16 by waves that hold the tokens
+//             of one token block and one part of the k range in registers; every other shape
+//             takes the first version's kernels, which split the k range over 8 or 10 loader
+//             waves that read MFMA-shaped pieces.
 //   select    one workgroup per (layer, token): mean and std of the row (two passes over
 //             registers), theta (Eq.11), the token's index list and the token's mask; a small
-//             launch then ORs the tokens' masks of a layer into its union mask.
-//   k2        tiles of 16 union rows: G[m][b] = K2n[U[m]] . q_b[r:] (same MFMA scheme, rows
-//             found by rank in the union mask), u[m][b] = GELU(s_bj - theta_b) * G (0 where
-//             token b does not activate the row), stored token-major as three bf16 planes
-//             (u = p0 + p1 + p2 carries all 24 significant bits of the fp32 value, so the
-//             bf16 MFMA of the next phase loses nothing).
+//             launch then ORs the tokens' masks of a layer and lists the union's neurons.
+//   k2        G[m][b] = K2n[U[m]] . q_b[r:] over the union's rows (the same three families),
+//             u[m][b] = GELU(s_bj - theta_b) * G (0 where token b does not activate the row),
+//             stored token-major as bf16 planes: three (u = p0 + p1 + p2 carries all 24
+//             significant bits of the fp32 value) up to 16 tokens, two above.
 //   v         y[b][c] += sum_m u[m][b] * Vn[U[m]][c]: the contraction runs over rows while Vn
 //             is contiguous along columns, so each wave stages its 32 rows x 64 columns
 //             through LDS and reads them back transposed (8 consecutive rows of one column
 //             per lane), then v_mfma_f32_16x16x32_bf16 with tokens as M and columns as N.
 //             Row slices give partial outputs.
 //   reduce    y = sum of the partial outputs in slice order.
+//
+// 8-bit weight codes (E4M3 or integers with a scale per row) are widened to bf16, which holds
+// them exactly, in registers or on the way into LDS, by the first two families and the v step.
 //
 // bf16 x bf16 products are exact in fp32 and all accumulation is fp32.  Nothing waits on
 // another workgroup inside a launch, and every sum has a fixed order.
@@ -250,19 +253,24 @@ __device__ __forceinline__ void codes_to_bf16(u32x4 a, uint32_t (&o)[8]) {
 // ------------------------------------------------- rows x tokens, tiles staged in LDS (> 16 tokens)
 // The k-split kernels above read a tile of 16 rows in 64- and 128-byte pieces, one piece per
 // row and instruction, which the memory system serves well below what whole rows reach.  Here
-// the COMPUTE waves (two per token block: wave (nb, h) multiplies half h of every row by the
+// the COMPUTE waves (2, 4 or 8 per token block: wave (nb, h) multiplies part h of every row by the
 // tokens of block nb, whose operands it keeps in registers) first bring each tile into LDS with
 // whole-row nontemporal loads: a wave fetches 16 / NCW consecutive rows, 256 or 512 contiguous
 // bytes of each per instruction, two tiles ahead, and parks a tile in LDS one step before it is
-// multiplied.  Every compute wave then reads its half of all 16 rows from LDS as the A operand.
-// The two halves' sums meet in LDS, where the EMIT waves (the rest of the 12) add them and
+// multiplied.  Every compute wave then reads its part of all 16 rows from LDS as the A operand.
+// The parts' sums meet in LDS, where the EMIT waves (2 or 4) add them and
 // store, exactly as above.  One LDS-only barrier per tile.  LDS: two tiles of 16 x (2 K + 16)
 // bytes (the 16 bytes spread the rows over the banks) and two buffers of partial sums.
 template <int CJ>
 constexpr int staged_pitch() { return CJ * 512 + 16; }  // bytes between rows of a tile in LDS (K = 256 CJ)
+// k parts a row is split into among the compute waves of a token block, and the waves of a
+// workgroup: KP NB compute waves (4 or 8: they stage 16 / (KP NB) rows each) plus the emit waves.
+constexpr int staged_parts(int nb, int cj) { return nb == 1 ? (cj <= 5 ? 4 : 8) : nb == 2 ? (cj <= 4 ? 2 : 4) : 2; }
+constexpr int staged_emit_waves(int nb) { return nb >= 4 ? 4 : 2; }
+constexpr int staged_waves(int nb, int cj) { return staged_parts(nb, cj) * nb + staged_emit_waves(nb); }
 template <int NB, int CJ>
 constexpr size_t staged_lds_bytes() {
-  return (size_t)2 * 16 * staged_pitch<CJ>() + (size_t)2 * 2 * NB * 4 * kWave * sizeof(float) + 4 * 16 * sizeof(float);
+  return (size_t)2 * 16 * staged_pitch<CJ>() + (size_t)2 * staged_parts(NB, CJ) * NB * 4 * kWave * sizeof(float) + 4 * 16 * sizeof(float);
 }
 // WK != 0: the rows are 8-bit codes (K bytes each); they are widened to bf16 when a tile is parked,
 // so the tile in LDS and the multiplies are the same, and scale_of(row) (the row's scale, fetched
@@ -273,17 +281,18 @@ __device__ __forceinline__ void rows_times_tokens_staged(const void* __restrict_
                                                          int tile0, int ntiles, int tile_end, unsigned char* lds,
                                                          RowOf row_of, ScaleOf scale_of, Pre pre, Emit emit) {
   constexpr int K = 256 * CJ, PITCH = staged_pitch<CJ>(), TILE = 16 * PITCH;
-  constexpr int NCW = 2 * NB, kEmitWaves = kRowWavesAll - NCW;
+  constexpr int KP = staged_parts(NB, CJ);
+  constexpr int NCW = KP * NB, kEmitWaves = staged_emit_waves(NB);
   constexpr int NBE = (NB + kEmitWaves - 1) / kEmitWaves;
-  constexpr int HS = 4 * CJ;            // k steps (of 32) per half row
+  constexpr int HS = 8 * CJ / KP;       // k steps (of 32) per part of a row
   constexpr int RPWV = 16 / NCW;        // rows a compute wave stages per tile
   constexpr int LPR = kWave / RPWV;     // lanes per staged row
   constexpr int ROWB = WK ? K : 2 * K;  // bytes of a row in memory
   constexpr int NPC = ROWB / 16;        // its 16-byte pieces
   constexpr int NLD = (NPC + LPR - 1) / LPR;  // 16-byte loads per lane and tile
-  static_assert(16 % NCW == 0 && NCW < kRowWavesAll, "two or four token blocks");
-  float(*red)[2][NB * 4][kWave] = reinterpret_cast<float(*)[2][NB * 4][kWave]>(lds + 2 * TILE);
-  float(*sc_sh)[16] = reinterpret_cast<float(*)[16]>(lds + 2 * TILE + sizeof(float) * 2 * 2 * NB * 4 * kWave);
+  static_assert(NCW == 4 || NCW == 8, "the compute waves share the 16 rows of a tile evenly");
+  float(*red)[KP][NB * 4][kWave] = reinterpret_cast<float(*)[KP][NB * 4][kWave]>(lds + 2 * TILE);
+  float(*sc_sh)[16] = reinterpret_cast<float(*)[16]>(lds + 2 * TILE + sizeof(float) * 2 * KP * NB * 4 * kWave);
   const int lane = threadIdx.x & (kWave - 1);
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
   const int kg = lane >> 4, ri = lane & 15;
@@ -309,7 +318,9 @@ __device__ __forceinline__ void rows_times_tokens_staged(const void* __restrict_
           f32x4 v;
 #pragma unroll
           for (int e = 0; e < 4; ++e) {
-            v[e] = red[buf][0][nb * 4 + e][lane] + red[buf][1][nb * 4 + e][lane];
+            v[e] = red[buf][0][nb * 4 + e][lane];
+#pragma unroll
+            for (int part = 1; part < KP; ++part) v[e] += red[buf][part][nb * 4 + e][lane];
             if constexpr (WK != 0) v[e] *= sc_sh[i & 3][4 * kg + e];
           }
           emit(tile0 + i, nb, v, f32x4{sv[k][0], sv[k][1], sv[k][2], sv[k][3]});
@@ -328,7 +339,7 @@ __device__ __forceinline__ void rows_times_tokens_staged(const void* __restrict_
     return;
   }
   // ------------------------------------------------------------------- compute wave
-  const int nbw = wave >> 1, h = wave & 1;
+  const int nbw = wave / KP, h = wave % KP;
   u32x4 qf[HS];
 #pragma unroll
   for (int s = 0; s < HS; ++s) {
@@ -441,7 +452,7 @@ __global__ __launch_bounds__(kRowThreads) void predict_batch_kernel(const BatchP
 }
 
 template <int WK, int NB, int CJ>
-__global__ __launch_bounds__(kRowThreads) void predict_staged_kernel(const BatchParams P) {
+__global__ __launch_bounds__(staged_waves(NB, CJ) * kWave) void predict_staged_kernel(const BatchParams P) {
   extern __shared__ __align__(16) unsigned char staged_lds[];
   const int lane = threadIdx.x & (kWave - 1);
   const int ri = lane & 15, kg = lane >> 4;
@@ -477,14 +488,7 @@ __global__ __launch_bounds__(kRowThreads) void predict_staged_kernel(const Batch
       });
 }
 
-// ------------------------------------------------------------------- predict, a few tokens
-// Up to 4 tokens: the predictor sweep of the one-token path with T dot products per row
-// instead of one (two-element bf16 dot products on the vector ALUs, DPP sums): every load
-// instruction reads a whole kilobyte of one row, which keeps the compute unit's request queue
-// fuller than MFMA-shaped loads do, and four tokens cost the vector ALUs little.  Workgroup =
-// 4 waves = 64 consecutive neurons, 16 at a time (4 rows per wave in flight).  Writes the
-// scores in both layouts the later steps read (token-major S, neuron-major ST with the
-// padding tokens as zeros).
+// ------------------------------------------------------------------------ lane-crossing sums
 typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
 __device__ __forceinline__ float dot2_bf16(uint32_t a, uint32_t b, float c) {
   return __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2_t, a), __builtin_bit_cast(bf16x2_t, b), c, false);
@@ -503,63 +507,6 @@ __device__ __forceinline__ float wave_total(float x) {
   x = dpp_add<0x142, 0xa>(x);
   x = dpp_add<0x143, 0xc>(x);
   return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(x), 63));
-}
-constexpr int kTokRows = 64;  // neurons per workgroup
-template <int T, int CPL1>
-__global__ __launch_bounds__(256) void predict_tokens_kernel(const BatchParams P) {
-  constexpr int R = 4;
-  __shared__ float s_sh[T][kTokRows];
-  const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
-  const int l = blockIdx.y, blk = blockIdx.x;
-  const int nvec1 = P.r / 8;
-  const int row0 = blk * kTokRows, nrows = max(0, min(kTokRows, P.d_ff - row0));
-  const bf16_t* q = P.q + (size_t)l * P.qslot;
-  u32x4 qp[T][CPL1];
-#pragma unroll
-  for (int t = 0; t < T; ++t)
-#pragma unroll
-    for (int c = 0; c < CPL1; ++c) {
-      const int ch = lane + kWave * c;
-      qp[t][c] = ld16(q + (int64_t)min(t, P.B - 1) * P.ldq + (ch < nvec1 ? ch : 0) * 8);
-      if (ch >= nvec1 || t >= P.B) qp[t][c] = u32x4{0u, 0u, 0u, 0u};
-    }
-  const bf16_t* base = static_cast<const bf16_t*>(P.k1n[l]);
-  for (int i = 0; i < kTokRows / 4; i += R) {
-    u32x4 reg[R][CPL1];
-#pragma unroll
-    for (int e = 0; e < R; ++e) {
-      const int lr = i * 4 + wave * R + e;
-      // rows past the end of the layer re-read the block's first row; the value is dropped
-      const bf16_t* row = base + (size_t)(row0 + (lr < nrows ? lr : 0)) * P.r;
-#pragma unroll
-      for (int c = 0; c < CPL1; ++c) reg[e][c] = ld16_stream(row + (size_t)(lane + kWave * c < nvec1 ? lane + kWave * c : 0) * 8);
-    }
-#pragma unroll
-    for (int e = 0; e < R; ++e) {
-      const int lr = i * 4 + wave * R + e;
-#pragma unroll
-      for (int t = 0; t < T; ++t) {
-        float acc = 0.f;
-#pragma unroll
-        for (int c = 0; c < CPL1; ++c)
-#pragma unroll
-          for (int d = 0; d < 4; ++d) acc = dot2_bf16(reg[e][c][d], qp[t][c][d], acc);
-        acc = wave_total(acc);
-        if (lane == 0) s_sh[t][lr] = acc;
-      }
-    }
-  }
-  __syncthreads();
-  float* S = P.S + (size_t)l * P.B * P.d_ff;
-  float* ST = P.ST + (size_t)l * P.d_ff * P.BP;
-  for (int idx = threadIdx.x; idx < P.B * kTokRows; idx += 256) {
-    const int t = idx / kTokRows, rr = idx % kTokRows;
-    if (rr < nrows) S[(size_t)t * P.d_ff + row0 + rr] = s_sh[t][rr];
-  }
-  for (int idx = threadIdx.x; idx < kTokRows * P.BP; idx += 256) {
-    const int rr = idx / P.BP, t = idx % P.BP;
-    if (rr < nrows) ST[(size_t)(row0 + rr) * P.BP + t] = t < T ? s_sh[t][rr] : 0.f;
-  }
 }
 
 // ---------------------------------------------------------------------------------- select
@@ -759,14 +706,15 @@ __global__ __launch_bounds__(kRowThreads) void k2_batch_kernel(const BatchParams
 }
 
 template <int WK, int NB, int CJ>
-__global__ __launch_bounds__(kRowThreads) void k2_staged_kernel(const BatchParams P) {
+__global__ __launch_bounds__(staged_waves(NB, CJ) * kWave) void k2_staged_kernel(const BatchParams P) {
+  constexpr int THREADS = staged_waves(NB, CJ) * kWave;
   extern __shared__ __align__(16) unsigned char staged_lds[];
   __shared__ int rowidx[32 * 16 + 16];
   const int tid = threadIdx.x, lane = tid & (kWave - 1);
   const int ri = lane & 15, kg = lane >> 4;
   const int l = blockIdx.y;
   const int tile0 = blockIdx.x * P.TPW2;
-  const int m_total = k2_ranks_to_rows<kRowThreads>(P, l, tile0, rowidx);
+  const int m_total = k2_ranks_to_rows<THREADS>(P, l, tile0, rowidx);
   if (m_total < 0) return;
   const int tiles_total = (m_total + 15) / 16;
   const int rank_end = (m_total + 31) / 32 * 32;  // the v phase reads ranks below this
@@ -793,154 +741,11 @@ __global__ __launch_bounds__(kRowThreads) void k2_staged_kernel(const BatchParam
         if (b >= P.B || rho >= rank_end) return;
         k2_store_u(P, up, rho, b, m_total, th[nb], g, score);
       });
-  if (tile0 + P.TPW2 >= tiles_total) k2_zero_tail<kRowThreads>(P, up, (tile0 + P.TPW2) * 16, rank_end);
-}
-
-// ------------------------------------------------------------- rows x tokens, streamed (<= 16 tokens)
-// With one token block the token fragments of every k step fit in LDS (32 bytes per k), and a
-// wave can take whole tiles by itself: no k split, no partial sums, no barrier after the
-// opening.  Workgroup = 4 waves, 4 NT consecutive tiles; wave w takes tiles w, w + 4, ...  A
-// tile's k steps come in NG groups of GS steps; two groups are in flight per wave while a third
-// is multiplied, across tile boundaries, in straight-line code (NG, NT are compile-time), so
-// every wait is exact.  The accumulators of a wave's NT tiles stay in registers and everything
-// is stored after the last multiply: a store between the loads would make the wave wait for
-// all of its loads at the next use (stores and loads share one counter on this target).
-constexpr int kStreamWaves = 4, kStreamThreads = kStreamWaves * kWave;
-template <int GS, int NG, int NT, typename RowOf>
-__device__ __forceinline__ void rows_stream(const bf16_t* __restrict__ w, uint32_t w_bytes, int K,
-                                            const bf16_t* __restrict__ q, int64_t ldq, int qoff, int B, int tile0,
-                                            int tile_end, u32x4* qsh, RowOf row_of, f32x4 (&acc)[NT]) {
-  static_assert(NG % 2 == 0, "the two group buffers alternate with the group's parity");
-  const int tid = threadIdx.x, lane = tid & (kWave - 1);
-  const int wave = __builtin_amdgcn_readfirstlane(tid / kWave);
-  const int kg = lane >> 4, ri = lane & 15;
-  // token fragments in the lane order of each k step: chunk (4 step + kg) of token ri sits at
-  // 64 step + lane (tokens past the batch are zero)
-  auto stage_tokens = [&]() {
-    for (int c = tid; c < (K / 8) * 16; c += kStreamThreads) {
-      const int b = c & 15, ch = c >> 4;
-      u32x4 v{0u, 0u, 0u, 0u};
-      if (b < B) v = ld16(q + (int64_t)b * ldq + qoff + ch * 8);
-      qsh[c] = v;
-    }
-    __syncthreads();
-  };
-  auto load_group = [&](int i, int g, u32x4(&a)[GS]) {
-    const int t = tile0 + i * kStreamWaves + wave;  // tiles past tile_end: a descriptor without records
-    const __amdgpu_buffer_rsrc_t rs =
-        __builtin_amdgcn_make_buffer_rsrc(const_cast<bf16_t*>(w), 0, t < tile_end ? (int)w_bytes : 0, 0x00020000);
-    const uint32_t off = (uint32_t)row_of(t, ri) * (uint32_t)K * 2u + (uint32_t)(g * GS * 4 + kg) * 16u;
-#pragma unroll
-    for (int s = 0; s < GS; ++s) a[s] = __builtin_amdgcn_raw_buffer_load_b128(rs, (int)(off + (uint32_t)s * 64u), 0, 0);
-  };
-  auto multiply = [&](const u32x4(&a)[GS], int g, f32x4& c) {
-#pragma unroll
-    for (int s = 0; s < GS; ++s) c = mfma_bf16(a[s], qsh[(g * GS + s) * kWave + lane], c);
-  };
-  // Long workgroups stage the tokens first (loads return in order: behind the first row
-  // requests the staging, and the barrier after it, would wait for those rows); short ones,
-  // which run in several rounds, gain more from having their rows on the way meanwhile.
-  u32x4 a0[GS], a1[GS];
-  if constexpr (NT > 1) stage_tokens();
-  load_group(0, 0, a0);
-  load_group(0, 1, a1);
-  __builtin_amdgcn_sched_barrier(0);
-  if constexpr (NT == 1) stage_tokens();
-#pragma unroll
-  for (int i = 0; i < NT; ++i) {
-    acc[i] = f32x4{0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-    for (int g = 0; g < NG; g += 2) {
-      // (the scheduler is kept from moving the requests: their order is the pipeline)
-      multiply(a0, g, acc[i]);
-      __builtin_amdgcn_sched_barrier(0);
-      if (g + 2 < NG) load_group(i, g + 2, a0);
-      else if (i + 1 < NT) load_group(i + 1, 0, a0);
-      __builtin_amdgcn_sched_barrier(0);
-      multiply(a1, g + 1, acc[i]);
-      __builtin_amdgcn_sched_barrier(0);
-      if (g + 2 < NG) load_group(i, g + 3, a1);
-      else if (i + 1 < NT) load_group(i + 1, 1, a1);
-      __builtin_amdgcn_sched_barrier(0);
-    }
-  }
-}
-
-template <int GS, int NG, int NT>
-__global__ __launch_bounds__(kStreamThreads, 4) void predict_stream_kernel(const BatchParams P) {
-  extern __shared__ __align__(16) u32x4 qsh[];
-  const int lane = threadIdx.x & (kWave - 1);
-  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
-  const int ri = lane & 15, kg = lane >> 4;
-  const int l = blockIdx.y;
-  const int tiles_total = (P.d_ff + 15) / 16;
-  const int tile0 = blockIdx.x * (kStreamWaves * NT);
-  if (tile0 >= tiles_total) return;
-  f32x4 acc[NT];
-  rows_stream<GS, NG, NT>(static_cast<const bf16_t*>(P.k1n[l]), (uint32_t)P.d_ff * (uint32_t)P.r * 2u, P.r,
-                          P.q + (size_t)l * P.qslot, P.ldq, 0, P.B, tile0, min(tile0 + kStreamWaves * NT, tiles_total), qsh,
-                          [&](int t, int i) { return min(t * 16 + i, P.d_ff - 1); }, acc);
-  float* S = P.S + (size_t)l * P.B * P.d_ff;
-  float* ST = P.ST + (size_t)l * P.d_ff * P.BP;
-  const int b = ri;
-#pragma unroll
-  for (int i = 0; i < NT; ++i) {
-    const int t = tile0 + i * kStreamWaves + wave, j = t * 16 + 4 * kg;
-    if (t >= tiles_total) continue;
-    if (b < P.B) {
-      if ((P.d_ff & 3) == 0) {  // the four neurons of a lane are inside the layer together, or none is
-        if (j < P.d_ff) *reinterpret_cast<f32x4*>(S + (size_t)b * P.d_ff + j) = acc[i];
-      } else {
-#pragma unroll
-        for (int e = 0; e < 4; ++e)
-          if (j + e < P.d_ff) S[(size_t)b * P.d_ff + j + e] = acc[i][e];
-      }
-    }
-#pragma unroll
-    for (int e = 0; e < 4; ++e)  // tokens past the batch have 0: whole lines are written (BP = 16 here)
-      if (j + e < P.d_ff) ST[(size_t)(j + e) * P.BP + b] = acc[i][e];
-  }
-}
-
-template <int GS, int NG, int NT>
-__global__ __launch_bounds__(kStreamThreads, 4) void k2_stream_kernel(const BatchParams P) {
-  extern __shared__ __align__(16) u32x4 qsh[];
-  __shared__ int rowidx[kStreamWaves * NT * 16 + 16];
-  const int lane = threadIdx.x & (kWave - 1);
-  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
-  const int ri = lane & 15, kg = lane >> 4;
-  const int l = blockIdx.y;
-  const int tile0 = blockIdx.x * P.TPW2;  // the launch sets TPW2 = 4 NT
-  const int m_total = k2_ranks_to_rows<kStreamThreads>(P, l, tile0, rowidx);
-  if (m_total < 0) return;
-  const int tiles_total = (m_total + 15) / 16;
-  const int rank_end = (m_total + 31) / 32 * 32;  // the v phase reads ranks below this
-  const float* ST = P.ST + (size_t)l * P.d_ff * P.BP;
-  const int b = ri;
-  // the scores the lane's (row, token) pairs will need: requested ahead of the weight rows
-  f32x4 score[NT];
-#pragma unroll
-  for (int i = 0; i < NT; ++i)
-#pragma unroll
-    for (int e = 0; e < 4; ++e)
-      score[i][e] = ST[(size_t)rowidx[(i * kStreamWaves + wave) * 16 + 4 * kg + e] * P.BP + min(b, P.B - 1)];
-  const float th = P.thetas[(size_t)l * P.B + min(b, P.B - 1)];
-  f32x4 acc[NT];
-  rows_stream<GS, NG, NT>(static_cast<const bf16_t*>(P.k2n[l]), (uint32_t)P.d_ff * (uint32_t)(P.d_model - P.r) * 2u,
-                          P.d_model - P.r, P.q + (size_t)l * P.qslot, P.ldq, P.r, P.B, tile0,
-                          min(tile0 + kStreamWaves * NT, tiles_total), qsh,
-                          [&](int t, int i) { return rowidx[(t - tile0) * 16 + i]; }, acc);
-  uint16_t* up = P.up + (size_t)l * P.B * P.ldu;
-#pragma unroll
-  for (int i = 0; i < NT; ++i) {
-    const int rho = (tile0 + i * kStreamWaves + wave) * 16 + 4 * kg;  // first of the lane's four ranks
-    if (b < P.B && rho < rank_end) k2_store_u(P, up, rho, b, m_total, th, acc[i], score[i]);
-  }
-  if (tile0 + kStreamWaves * NT >= tiles_total) k2_zero_tail<kStreamThreads>(P, up, (tile0 + kStreamWaves * NT) * 16, rank_end);
+  if (tile0 + P.TPW2 >= tiles_total) k2_zero_tail<THREADS>(P, up, (tile0 + P.TPW2) * 16, rank_end);
 }
 
 // ------------------------------------------------------- rows x tokens, whole rows (<= 16 tokens)
-// The streamed kernels above read a row in 64-byte pieces (the shape the 16x16x32 operand asks
+// The k-split kernels above read a row in 64-byte pieces (the shape the 16x16x32 operand asks
 // for), which the memory system serves at some 85 % of what whole rows reach.  Here a wave
 // takes FOUR CONSECUTIVE ROWS per step and reads them whole: lane (block = lane / 4, i = lane % 4)
 // loads the 16-byte chunks block + 16 c, c < CH, of row i, so one load instruction covers 256
@@ -1474,10 +1279,14 @@ hipError_t launch_rows_nb(const BatchParams& P, int mode, int nb, int K, dim3 gr
   }
 }
 
-// Staged kernels (more than 16 tokens): rows of K = 256 CJ elements for the compiled CJ (a compute
-// wave keeps 4 CJ token operands in registers; with two token blocks it stages four rows per
-// tile, and the registers are enough up to CJ = 4).
-int staged_cj(int K, int nb) { return (K % 256 == 0 && K / 256 >= 2 && K / 256 <= (nb == 2 ? 4 : 6)) ? K / 256 : 0; }
+// Staged kernels: rows of K = 256 CJ elements for the compiled CJ (a compute wave keeps the token
+// operands of its part of a row in registers: 128 of them would be needed for rows of 2048
+// elements with more than two token blocks).
+int staged_cj(int K, int nb) {
+  if (K % 256 != 0) return 0;
+  const int cj = K / 256;
+  return ((cj >= 2 && cj <= 6) || (cj == 8 && nb <= 2)) ? cj : 0;
+}
 template <int WK, int NB, int CJ>
 hipError_t launch_staged(const BatchParams& P, int mode, dim3 grid, hipStream_t st) {
   const size_t dyn = staged_lds_bytes<NB, CJ>();
@@ -1485,8 +1294,8 @@ hipError_t launch_staged(const BatchParams& P, int mode, dim3 grid, hipStream_t 
                                : reinterpret_cast<const void*>(k2_staged_kernel<WK, NB, CJ>);
   const hipError_t e = hipFuncSetAttribute(kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)dyn);
   if (e != hipSuccess) return e;
-  if (mode == 0) hipLaunchKernelGGL((predict_staged_kernel<WK, NB, CJ>), grid, dim3(kRowThreads), dyn, st, P);
-  else hipLaunchKernelGGL((k2_staged_kernel<WK, NB, CJ>), grid, dim3(kRowThreads), dyn, st, P);
+  if (mode == 0) hipLaunchKernelGGL((predict_staged_kernel<WK, NB, CJ>), grid, dim3(staged_waves(NB, CJ) * kWave), dyn, st, P);
+  else hipLaunchKernelGGL((k2_staged_kernel<WK, NB, CJ>), grid, dim3(staged_waves(NB, CJ) * kWave), dyn, st, P);
   return hipGetLastError();
 }
 template <int WK, int NB>
@@ -1495,56 +1304,24 @@ hipError_t launch_staged_cj(const BatchParams& P, int mode, int cj, dim3 grid, h
     case 2: return launch_staged<WK, NB, 2>(P, mode, grid, st);
     case 3: return launch_staged<WK, NB, 3>(P, mode, grid, st);
     case 4: return launch_staged<WK, NB, 4>(P, mode, grid, st);
-    case 5: if constexpr (NB == 4) return launch_staged<WK, NB, 5>(P, mode, grid, st); else return hipErrorInvalidValue;
-    case 6: if constexpr (NB == 4) return launch_staged<WK, NB, 6>(P, mode, grid, st); else return hipErrorInvalidValue;
+    case 5: return launch_staged<WK, NB, 5>(P, mode, grid, st);
+    case 6: return launch_staged<WK, NB, 6>(P, mode, grid, st);
+    case 8: if constexpr (NB <= 2) return launch_staged<WK, NB, 8>(P, mode, grid, st); else return hipErrorInvalidValue;
     default: return hipErrorInvalidValue;
   }
 }
 // (three token blocks run as four: the fourth block's operands are zeros)
 template <int WK>
 hipError_t launch_staged_nb(const BatchParams& P, int mode, int nb, int cj, dim3 grid, hipStream_t st) {
-  return nb == 2 ? launch_staged_cj<WK, 2>(P, mode, cj, grid, st) : launch_staged_cj<WK, 4>(P, mode, cj, grid, st);
+  return nb == 1 ? launch_staged_cj<WK, 1>(P, mode, cj, grid, st)
+         : nb == 2 ? launch_staged_cj<WK, 2>(P, mode, cj, grid, st)
+                   : launch_staged_cj<WK, 4>(P, mode, cj, grid, st);
 }
 hipError_t launch_staged_wk(const BatchParams& P, int wkind, int mode, int nb, int cj, dim3 grid, hipStream_t st) {
   return wkind == 0 ? launch_staged_nb<0>(P, mode, nb, cj, grid, st)
          : wkind == 1 ? launch_staged_nb<1>(P, mode, nb, cj, grid, st)
                       : launch_staged_nb<2>(P, mode, nb, cj, grid, st);
 }
-
-// Streamed kernels (at most 16 tokens): k steps per group and groups per row for a row of K
-// elements, from the compiled combinations.
-bool stream_split(int K, int* gs, int* ng) {
-  static const int cand[][2] = {{8, 2}, {8, 4}, {8, 6}, {8, 8}, {10, 4}};
-  for (const auto& c : cand)
-    if (c[0] * c[1] * 32 == K) {
-      *gs = c[0];
-      *ng = c[1];
-      return true;
-    }
-  return false;
-}
-template <int GS, int NG, int NT>
-hipError_t launch_stream(const BatchParams& P, int mode, int tiles, hipStream_t st) {
-  const size_t dyn = (size_t)GS * NG * 32 * 32;  // 32 bytes of token fragments per k
-  const void* kern = mode == 0 ? reinterpret_cast<const void*>(predict_stream_kernel<GS, NG, NT>)
-                               : reinterpret_cast<const void*>(k2_stream_kernel<GS, NG, NT>);
-  const hipError_t e = hipFuncSetAttribute(kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)dyn);
-  if (e != hipSuccess) return e;
-  const dim3 grid((tiles + kStreamWaves * NT - 1) / (kStreamWaves * NT), P.n_layers);
-  if (mode == 0) hipLaunchKernelGGL((predict_stream_kernel<GS, NG, NT>), grid, dim3(kStreamThreads), dyn, st, P);
-  else hipLaunchKernelGGL((k2_stream_kernel<GS, NG, NT>), grid, dim3(kStreamThreads), dyn, st, P);
-  return hipGetLastError();
-}
-template <int NT>
-hipError_t launch_stream_split(const BatchParams& P, int mode, int gs, int ng, int tiles, hipStream_t st) {
-  if (gs == 8 && ng == 2) return launch_stream<8, 2, NT>(P, mode, tiles, st);
-  if (gs == 8 && ng == 4) return launch_stream<8, 4, NT>(P, mode, tiles, st);
-  if (gs == 8 && ng == 6) return launch_stream<8, 6, NT>(P, mode, tiles, st);
-  if (gs == 8 && ng == 8) return launch_stream<8, 8, NT>(P, mode, tiles, st);
-  if (gs == 10 && ng == 4) return launch_stream<10, 4, NT>(P, mode, tiles, st);
-  return hipErrorInvalidValue;
-}
-
 
 // Whole-row kernels (at most 16 tokens): rows of whole 256-byte multiples, for the compiled counts
 // CH of 256-byte pieces per block column (bf16: K = 128 CH; 8-bit codes: K = 256 CH).
@@ -1642,13 +1419,10 @@ hipError_t launch_ffn_phased_batch(const FfnProblem& p0, const void* const* k1n,
   const BatchLayout lay = batch_layout(p0.d_model, p0.d_ff, p0.batch);
   // pinned choices (0 = automatic): tiles per workgroup of the predict and k2 steps (the block sizes
   // divided by 16); variant = 100 x kernel family + row slices of the V step.  Families: 0 automatic,
-  // 1 the k-split kernels for every batch size, 2 the streamed kernels wherever they are compiled,
-  // however small the launch, 3 automatic among the kernels that read rows in MFMA-shaped pieces,
-  // 4 the whole-row kernels wherever they are compiled
+  // 1 the k-split kernels for every batch size, 4 the whole-row kernels wherever they are compiled,
+  // 5 the LDS-staged kernels wherever they are compiled
   const int t1 = tune.rows_per_predict_block / 16, t2 = tune.neurons_per_gather_block / 16;
   const int family = tune.variant / 100;
-  const bool rows4_on = family == 0 || family == 4;
-  const int g_batch_stream = family == 1 ? 0 : family == 2 ? 2 : 1;
   const int g_batch_ks = tune.variant % 100;
   const int g_batch_tpw1 = t1 > 0 ? (t1 + 3) / 4 * 4 : 0;
   const int g_batch_tpw2 = t2 > 0 ? min(32, (t2 + 3) / 4 * 4) : 0;
@@ -1719,53 +1493,40 @@ hipError_t launch_ffn_phased_batch(const FfnProblem& p0, const void* const* k1n,
     while (L * ksl > part_rows(p0.d_model)) --ksl;
     P.KS = ksl;
 
-    // one token block: the streamed kernels where a row's length is among the compiled ones;
-    // 16 tiles per workgroup when that still fills the chip, else 4
-    int gs = 0, ng = 0;
+    // Which predict / k2 kernels: the whole-row kernels with at most 16 tokens and rows of whole
+    // 256-byte multiples, as long as the tokens' operands (a KB per 128 elements of a row and group
+    // of four tokens) leave room for three workgroups per compute unit; the LDS-staged kernels with
+    // more tokens, or where the whole-row ones do not fit, for rows of whole 512-byte multiples; the
+    // k-split kernels for everything else.  A pair that both read the token-major scores leaves the
+    // neuron-major copy unwritten.  8-bit codes exist for the first two families only.
     const bool few_wgs = (long long)L * ((tiles + 15) / 16) < 600;
-    // (k2 walks the union only: with few tokens it is small, and short workgroups spread it better)
-    const bool s1_short = g_batch_tpw1 > 0 ? g_batch_tpw1 < 16 : few_wgs, s2_short = g_batch_tpw2 > 0 ? g_batch_tpw2 < 16 : (few_wgs || B <= 4);
-    // (a launch too small to give every compute unit a streamed workgroup keeps the k-split kernels,
-    // whose workgroups have three times the waves)
-    const bool stream_ok = nb == 1 && (g_batch_stream == 2 || (g_batch_stream == 1 && (long long)L * ((tiles + 3) / 4) >= 256));
-    const int cpl1 = (p0.r / 8 + kWave - 1) / kWave;
-    const int wkind = p0.w_fp8;  // 0 bf16, 1 E4M3 codes, 2 integer codes (codes: whole-row and staged kernels only)
-    // more than 16 tokens: the LDS-staged kernels where a row's length is among the compiled ones
-    const int cj1 = nb >= 2 && (family != 1 || wkind) ? staged_cj(p0.r, nb) : 0, cj2 = nb >= 2 && (family != 1 || wkind) ? staged_cj(p0.d_model - p0.r, nb) : 0;
-    if (wkind && nb >= 2 && (cj1 == 0 || cj2 == 0)) return hipErrorInvalidValue;
-    // At most 16 tokens and rows of whole 256-byte multiples: the whole-row kernels, as long as
-    // the tokens' operands (a KB per 128 elements of a row and group of four tokens) leave room
-    // for three workgroups per compute unit; the predictor only where it gains (with at most 8
-    // tokens always, with more only if k2 joins in and nobody needs the neuron-major scores).
-    // Workgroups of 64 rows up to 8 tokens, of 256 above (measured on the 2B, 9B and paper shapes).
+    const int wkind = p0.w_fp8;  // 0 bf16, 1 E4M3 codes, 2 integer codes
     const int ngrp = (B + 3) / 4;
-    int ch1 = (rows4_on || wkind) && nb == 1 ? rows4_chunks(p0.r, wkind) : 0, ch2 = (rows4_on || wkind) && nb == 1 ? rows4_chunks(p0.d_model - p0.r, wkind) : 0;
-    if (wkind && nb == 1 && (ch1 == 0 || ch2 == 0)) return hipErrorInvalidValue;
+    const bool pieces_only = family == 1 && !wkind;
+    int ch1 = nb == 1 && !pieces_only && family != 5 ? rows4_chunks(p0.r, wkind) : 0;
+    int ch2 = nb == 1 && !pieces_only && family != 5 ? rows4_chunks(p0.d_model - p0.r, wkind) : 0;
     if (family != 4 && !wkind) {
       if (ch2 * ngrp > 40) ch2 = 0;
-      if (ch1 * ngrp > 48 || (ngrp > 2 && ch2 == 0)) ch1 = 0;
+      if (ch1 * ngrp > 48) ch1 = 0;
     }
+    if (ch1 == 0 || ch2 == 0) ch1 = ch2 = 0;  // (the two steps change over together)
+    const bool staged_on = !pieces_only && ch1 == 0;
+    const int cj1 = staged_on ? staged_cj(p0.r, nb) : 0, cj2 = staged_on ? staged_cj(p0.d_model - p0.r, nb) : 0;
+    if (wkind && ch1 == 0 && (cj1 == 0 || cj2 == 0)) return hipErrorInvalidValue;
+    // workgroups of 64 rows up to 8 tokens, of 256 above (measured on the 2B, 9B and paper shapes)
     const bool r4_short1 = g_batch_tpw1 > 0 ? g_batch_tpw1 < 16 : (few_wgs || ngrp <= 2);
     const bool r4_short2 = g_batch_tpw2 > 0 ? g_batch_tpw2 < 16 : (few_wgs || ngrp <= 2);
     if (ch1 > 0) {
       BatchParams P1 = P;
-      if (ch2 > 0) P1.ST = nullptr;  // nobody reads the neuron-major copy then
+      P1.ST = nullptr;
       err = launch_rows4_wk(P1, wkind, 0, ch1, r4_short1, tiles, st);
-    }
-    else if (B <= 4 && cpl1 <= 2 && g_batch_stream != 0) {
-      // a few tokens: the vector-ALU sweep (whole-row loads)
-      const dim3 gt((p0.d_ff + kTokRows - 1) / kTokRows, L);
-      if (cpl1 == 1) hipLaunchKernelGGL((predict_tokens_kernel<4, 1>), gt, dim3(256), 0, st, P);
-      else hipLaunchKernelGGL((predict_tokens_kernel<4, 2>), gt, dim3(256), 0, st, P);
-      err = hipGetLastError();
-    } else if (stream_ok && stream_split(p0.r, &gs, &ng))
-      err = s1_short ? launch_stream_split<1>(P, 0, gs, ng, tiles, st) : launch_stream_split<4>(P, 0, gs, ng, tiles, st);
-    else if (cj1 > 0) {
+    } else if (cj1 > 0) {
       BatchParams P1 = P;
-      if (cj2 > 0) P1.ST = nullptr;  // the staged k2 kernel reads the token-major scores
+      if (cj2 > 0) P1.ST = nullptr;
       err = launch_staged_wk(P1, wkind, 0, nb, cj1, dim3((tiles + tpw1 - 1) / tpw1, L), st);
-    } else
+    } else {
       err = launch_rows_nb(P, 0, nb, p0.r, dim3((tiles + tpw1 - 1) / tpw1, L), st);
+    }
     if (err != hipSuccess) return err;
     if (p0.d_ff <= 36 * kSelThreads) hipLaunchKernelGGL((select_batch_kernel<36>), dim3(B, L), dim3(kSelThreads), 0, st, P);
     else hipLaunchKernelGGL((select_batch_kernel<64>), dim3(B, L), dim3(kSelThreads), 0, st, P);
@@ -1773,9 +1534,6 @@ hipError_t launch_ffn_phased_batch(const FfnProblem& p0, const void* const* k1n,
     if (ch2 > 0) {
       P.TPW2 = r4_short2 ? 4 : 16;
       err = launch_rows4_wk(P, wkind, 1, ch2, r4_short2, tiles, st);
-    } else if (stream_ok && stream_split(p0.d_model - p0.r, &gs, &ng)) {
-      P.TPW2 = kStreamWaves * (s2_short ? 1 : 4);
-      err = s2_short ? launch_stream_split<1>(P, 1, gs, ng, tiles, st) : launch_stream_split<4>(P, 1, gs, ng, tiles, st);
     } else if (cj2 > 0) {
       err = launch_staged_wk(P, wkind, 1, nb, cj2, dim3((tiles + tpw2 - 1) / tpw2, L), st);
     } else {

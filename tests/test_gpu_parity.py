@@ -327,21 +327,6 @@ def test_matrix_core_path_with_a_ragged_number_of_neurons(batch):
     check_ffn_against_oracle(sh, weights, q, out, TOL_BF16_TIGHT, what=f"ragged d_ff B={batch}")
 
 
-@pytest.mark.parametrize("d_model,d_ff,r,k", [(1024, 1000, 512, 77), (2304, 600, 1024, 48), (3584, 40, 1536, 5),
-                                              (1024, 2085, 512, 160)])
-@pytest.mark.parametrize("batch", [2, 7, 16])
-def test_streamed_kernels_of_one_token_block(d_model, d_ff, r, k, batch):
-    """At most 16 tokens: a wave takes whole 16-row tiles over the full row length.  Every compiled
-    row length (512, 1024, 1280, 1536, 2048), ragged numbers of neurons and of union tiles, one and
-    several layers; the switch makes small launches take these kernels too."""
-    sh = synth.FFNShape("stream", d_model, d_ff, r, k)
-    for n_layers in (1, 3):
-        weights = synth.ffn_stack(sh, n_layers, base_seed=700 + n_layers, dtype=torch.bfloat16)
-        q = synth.tokens(sh, batch, 710 + batch, torch.bfloat16)
-        out = run_gpu_ffn(sh, weights, q, via_layers=True, tuning=binding.Tuning(variant=200))
-        check_ffn_against_oracle(sh, weights, q, out, TOL_BF16_TIGHT, what=f"streamed B={batch} L={n_layers}")
-
-
 @pytest.mark.parametrize("d_model,d_ff,r,k", [(1280, 1000, 512, 77), (2304, 600, 1024, 48), (3072, 200, 1536, 20),
                                               (1536, 2085, 768, 160)])
 @pytest.mark.parametrize("batch", [17, 32, 40, 64])
@@ -362,6 +347,22 @@ def test_staged_kernels_of_several_token_blocks(d_model, d_ff, r, k, batch):
         assert rel_l2(out["y"], other["y"]) < 1e-3
 
 
+@pytest.mark.parametrize("d_model,d_ff,r,k", [(1280, 1000, 512, 77), (2304, 600, 1024, 48), (3584, 200, 1536, 20),
+                                              (4096, 2085, 2048, 160)])
+@pytest.mark.parametrize("batch", [3, 16, 17, 32])
+def test_staged_kernels_with_four_and_eight_parts_per_row(d_model, d_ff, r, k, batch):
+    """One and two token blocks on the LDS-staged kernels: the rows are split into 4 or 8 parts among
+    the compute waves of a token block (2 or 4 with two blocks), which is what lets rows of 2048
+    elements in; forced through the tuning switch at 16 tokens and below."""
+    sh = synth.FFNShape("staged-parts", d_model, d_ff, r, k)
+    for n_layers, block in ((1, 0), (3, 64)):
+        weights = synth.ffn_stack(sh, n_layers, base_seed=760 + n_layers, dtype=torch.bfloat16)
+        q = synth.tokens(sh, batch, 770 + batch, torch.bfloat16)
+        tune = binding.Tuning(rows_per_predict_block=block, neurons_per_gather_block=block, variant=500)
+        out = run_gpu_ffn(sh, weights, q, via_layers=True, tuning=tune)
+        check_ffn_against_oracle(sh, weights, q, out, TOL_BF16_TIGHT, what=f"staged parts B={batch} L={n_layers}")
+
+
 @pytest.mark.parametrize("d_model,d_ff,r,k", [(1024, 1000, 512, 77), (2304, 600, 1024, 48), (3584, 40, 1536, 5),
                                               (1024, 2085, 512, 160)])
 @pytest.mark.parametrize("batch", [2, 5, 9, 16])
@@ -370,7 +371,7 @@ def test_whole_row_kernels_of_one_token_block(d_model, d_ff, r, k, batch):
     and multiplies on the 4x4x4 matrix instruction.  Every compiled row length (512 .. 2048), one
     to four groups of four tokens, ragged numbers of neurons and of union rows, one and several
     layers, short (64 rows) and long (256 rows) workgroups; against the oracle and against the
-    kernels that read MFMA-shaped pieces."""
+    k-split kernels, which read MFMA-shaped pieces."""
     sh = synth.FFNShape("rows4", d_model, d_ff, r, k)
     for n_layers, block in ((1, 0), (3, 256), (2, 64)):
         weights = synth.ffn_stack(sh, n_layers, base_seed=720 + n_layers, dtype=torch.bfloat16)
@@ -378,7 +379,7 @@ def test_whole_row_kernels_of_one_token_block(d_model, d_ff, r, k, batch):
         tune = binding.Tuning(rows_per_predict_block=block, neurons_per_gather_block=block, variant=400)
         out = run_gpu_ffn(sh, weights, q, via_layers=True, tuning=tune)
         check_ffn_against_oracle(sh, weights, q, out, TOL_BF16_TIGHT, what=f"whole rows B={batch} L={n_layers}")
-        other = run_gpu_ffn(sh, weights, q, via_layers=True, tuning=binding.Tuning(variant=300))
+        other = run_gpu_ffn(sh, weights, q, via_layers=True, tuning=binding.Tuning(variant=100))
         # (a score within rounding of the threshold may fall on either side of it)
         assert np.max(np.abs(out["ucount"].astype(np.int64) - other["ucount"])) <= 2
         assert rel_l2(out["y"], other["y"]) < 1e-3
@@ -386,24 +387,27 @@ def test_whole_row_kernels_of_one_token_block(d_model, d_ff, r, k, batch):
 
 @pytest.mark.parametrize("batch", [2, 3, 4])
 @pytest.mark.parametrize("shape", [synth.GEMMA2_2B, synth.FFNShape("few", 1024, 1000, 520, 77)])
-def test_few_token_predictor(shape, batch):
-    """Two to four tokens take the vector-ALU predictor sweep (whole-row loads, a dot product per
-    token): the 2B shape, and a shape whose predictor rows do not fill the last chunks of a wave and
-    whose neuron count is ragged; against the oracle, and against the matrix-core kernels."""
+def test_few_tokens(shape, batch):
+    """Two to four tokens: the 2B shape (whole-row kernels) and a shape whose rows are not multiples of 32
+    elements (general kernels) against the oracle; the 2B shape also against the k-split kernels."""
     weights = synth.ffn_stack(shape, 2, base_seed=800, dtype=torch.bfloat16)
     q = synth.tokens(shape, batch, 810 + batch, torch.bfloat16)
-    out = run_gpu_ffn(shape, weights, q, via_layers=True, tuning=binding.Tuning(variant=300))
+    out = run_gpu_ffn(shape, weights, q, via_layers=True)
     check_ffn_against_oracle(shape, weights, q, out, TOL_BF16_TIGHT, what=f"few tokens B={batch}")
     other = run_gpu_ffn(shape, weights, q, via_layers=True, tuning=binding.Tuning(variant=100))
     assert np.array_equal(out["count"], other["count"]) and np.array_equal(out["idx"], other["idx"])
     assert rel_l2(out["y"], other["y"]) < 1e-6
 
 
-@pytest.mark.parametrize("batch", [1, 4, 16])
-def test_calls_can_be_captured_in_a_graph_and_replayed(batch):
+@pytest.mark.parametrize("shape,batch", [(synth.TINY, 1), (synth.TINY, 4), (synth.TINY, 16),
+                                         (synth.FFNShape("graph", 1280, 1000, 512, 77), 4),
+                                         (synth.FFNShape("graph", 1280, 1000, 512, 77), 16),
+                                         (synth.FFNShape("graph", 1280, 1000, 512, 77), 40)])
+def test_calls_can_be_captured_in_a_graph_and_replayed(shape, batch):
     """The library allocates nothing and clears nothing with memset nodes, so a call can sit in a HIP
-    graph: three replays, with eager calls on other inputs in between, each give the eager result."""
-    sh = synth.TINY
+    graph: three replays, with eager calls on other inputs in between, each give the eager result.
+    (The second shape takes the whole-row kernels at 4 and 16 tokens and the LDS-staged ones at 40.)"""
+    sh = shape
     dev = torch.device(DEV)
     weights = synth.ffn_stack(sh, 3, base_seed=900, dtype=torch.bfloat16, device=dev)
     layers = [binding.make_layer(w[0], w[1], w[2], sh.k) for w in weights]
