@@ -170,6 +170,79 @@ def stat_topk_rows(x, k: int, fill: int = FILL_ZERO, want_y: bool = True, want_i
     return StatTopKRows(y, theta, std, count, idx)
 
 
+def shard_stats(x_shard):
+    """What one device computes on its shard of the activations (Appendix D.2, global variant): the mean
+    and the (population) variance of its entries, per row.  x_shard[rows, n_s] -> (mean[rows], var[rows])."""
+    x = np.asarray(x_shard, dtype=np.float64)
+    if x.ndim != 2 or x.shape[1] < 1:
+        raise ValueError("shard_stats takes a matrix with at least one column")
+    return x.mean(axis=1), x.var(axis=1)
+
+
+def combine_shard_stats(ns, means, variances):
+    """What every device does with the m (mean, variance) pairs it holds after the exchange (Appendix
+    D.2): the mean and the sample standard deviation (ddof = 1, Eq.11's convention) of the whole vector.
+    ns[m] entries per shard, means[m][rows], variances[m][rows] -> (mean[rows], std[rows]).
+    mean = sum n_s mean_s / N;  sum of squares about it = sum n_s (var_s + (mean_s - mean)^2)."""
+    ns = np.asarray(ns, dtype=np.float64)
+    means = np.asarray(means, dtype=np.float64)
+    variances = np.asarray(variances, dtype=np.float64)
+    if means.shape != variances.shape or means.shape[0] != ns.shape[0]:
+        raise ValueError("one (mean, variance) pair per shard and row")
+    total = ns.sum()
+    if total < 2:
+        raise ValueError("at least two entries in all")
+    mean = (ns[:, None] * means).sum(axis=0) / total
+    ss = (ns[:, None] * (variances + (means - mean[None, :]) ** 2)).sum(axis=0)
+    return mean, np.sqrt(ss / (total - 1.0))
+
+
+def stat_topk_sharded(x, k: int, bounds, fill: int = FILL_ZERO, local: bool = False) -> StatTopKRows:
+    """Statistical top-k of every row of x[rows, N] whose columns are sharded at `bounds` (column
+    offsets 0 = b_0 < b_1 < ... < b_m = N), Appendix D.2.
+    Global (local = False): every shard contributes (mean, variance), the combined statistics give one
+    threshold theta = mean + std Q(1 - k / N) per row, and each shard is soft-thresholded with it: the
+    result is that of the unsharded operator.
+    Local (local = True): each shard runs the operator by itself with k' = k n_s / N (k / m for equal
+    shards; rounded to the nearest integer, at least 1): no exchange, a different result.  theta and
+    std then hold the first shard's values."""
+    x = np.ascontiguousarray(x, dtype=np.float64)
+    rows, n = x.shape
+    bounds = [int(b) for b in bounds]
+    if bounds[0] != 0 or bounds[-1] != n or any(b1 <= b0 for b0, b1 in zip(bounds, bounds[1:])):
+        raise ValueError("bounds must run from 0 to N, increasing")
+    if not 1 <= k <= n - 1:
+        raise ValueError("k out of range")
+    fillv = -np.inf if fill == FILL_NEG_INF else 0.0
+    y = np.empty_like(x)
+    count = np.zeros(rows, np.int64)
+    idx = np.full((rows, n), -1, np.int32)
+    if local:
+        theta0 = std0 = None
+        for b0, b1 in zip(bounds, bounds[1:]):
+            ks = min(max(int(round(k * (b1 - b0) / n)), 1), b1 - b0 - 1)
+            part = stat_topk_rows(x[:, b0:b1], ks, fill)
+            y[:, b0:b1] = part.y
+            for r in range(rows):
+                c = int(part.count[r])
+                idx[r, count[r]:count[r] + c] = part.idx[r, :c] + b0
+                count[r] += c
+            if theta0 is None:
+                theta0, std0 = part.theta, part.std
+        return StatTopKRows(y, theta0, std0, count, idx)
+    ns = [b1 - b0 for b0, b1 in zip(bounds, bounds[1:])]
+    stats = [shard_stats(x[:, b0:b1]) for b0, b1 in zip(bounds, bounds[1:])]
+    mean, std = combine_shard_stats(ns, [s[0] for s in stats], [s[1] for s in stats])
+    theta = mean + std * normal_quantile(1.0 - k / n)
+    for r in range(rows):
+        keep = x[r] > theta[r]
+        y[r] = np.where(keep, x[r] - theta[r], fillv)
+        where = np.nonzero(keep)[0]
+        count[r] = where.size
+        idx[r, :where.size] = where
+    return StatTopKRows(y, theta, std, count, idx)
+
+
 def huber(x: float, delta: float) -> float:
     """Huber loss (Section 3.2, Eq.13) for one number."""
     return float(_load().spark_ref_huber(float(x), float(delta)))

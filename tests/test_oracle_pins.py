@@ -728,3 +728,87 @@ def test_int8_rows_dequantise_exactly(oracle):
     assert np.max(np.abs(deq - w.numpy()) / np.abs(w.numpy()).max(axis=1, keepdims=True)) <= 0.5 / 127 * 1.02
     again = torch.round(torch.from_numpy(deq) / scales[:, None]).to(torch.int8).view(torch.uint8)
     assert torch.equal(again, codes)
+
+
+# ------------------------------------------------ sharded statistical top-k (Appendix D.2)
+SHARDINGS = [[0, 2304, 4608, 6912, 9216], [0, 1000, 6000, 9216], [0, 9215, 9216], [0, 9216]]
+
+
+@pytest.mark.parametrize("bounds", SHARDINGS)
+def test_combined_shard_statistics_are_the_statistics_of_the_whole_row(oracle, bounds):
+    """Means and variances of the shards, combined as every device would after the exchange, against
+    numpy's mean and sample standard deviation of the unsharded rows (shards of very different means)."""
+    rng = np.random.default_rng(17)
+    x = rng.standard_normal((9, 9216)) * rng.uniform(0.1, 30.0, (9, 1)) + rng.uniform(-50.0, 50.0, (9, 1))
+    x[:, :bounds[1]] += 40.0
+    ns = [b1 - b0 for b0, b1 in zip(bounds, bounds[1:])]
+    stats = [oracle.shard_stats(x[:, b0:b1]) for b0, b1 in zip(bounds, bounds[1:])]
+    mean, std = oracle.combine_shard_stats(ns, [s[0] for s in stats], [s[1] for s in stats])
+    assert np.allclose(mean, x.mean(axis=1), rtol=1e-13, atol=1e-12)
+    assert np.allclose(std, x.std(axis=1, ddof=1), rtol=1e-12)
+    for m_, v_ in stats[:1]:
+        assert np.allclose(m_, [statistics.fmean(r) for r in x[:, :bounds[1]]], rtol=1e-13, atol=1e-12)
+
+
+@pytest.mark.parametrize("bounds", SHARDINGS)
+@pytest.mark.parametrize("fill", [0, 1])
+def test_global_sharded_top_k_is_the_unsharded_operator(oracle, bounds, fill):
+    """Appendix D.2: with the exchanged statistics the output is exactly that of the unsharded operator
+    (the C oracle on whole rows): thresholds to rounding, identical sets and values."""
+    rng = np.random.default_rng(18)
+    x = rng.standard_normal((6, 9216)) * 3.0 + 1.5
+    x[:, :bounds[1]] -= 2.0
+    whole = oracle.stat_topk_rows(x, 737, fill)
+    sharded = oracle.stat_topk_sharded(x, 737, bounds, fill)
+    assert np.allclose(sharded.theta, whole.theta, rtol=1e-13, atol=1e-13)
+    assert np.allclose(sharded.std, whole.std, rtol=1e-12)
+    assert np.array_equal(sharded.count, whole.count) and np.array_equal(sharded.idx, whole.idx)
+    both = np.isfinite(whole.y)
+    assert np.array_equal(both, np.isfinite(sharded.y))
+    assert np.allclose(sharded.y[both], whole.y[both], rtol=0, atol=1e-12)
+
+
+def test_local_sharded_top_k_keeps_its_share_on_every_shard(oracle):
+    """Appendix D.2's local variant (k' = k / m on every shard, no exchange): every shard keeps about
+    k / m entries whatever its level, while the global variant keeps almost nothing of a shard that lies
+    three standard deviations below the others; on identically distributed shards the two keep about the
+    same number.  The expected counts come from the normal tail, not from the oracle."""
+    rng = np.random.default_rng(19)
+    n, m, k = 8192, 4, 656
+    bounds = [i * n // m for i in range(m + 1)]
+    x = rng.standard_normal((40, n))
+    loc = oracle.stat_topk_sharded(x, k, bounds, local=True)
+    glo = oracle.stat_topk_sharded(x, k, bounds)
+    assert abs(loc.count.mean() - k) < 0.04 * k and abs(glo.count.mean() - k) < 0.04 * k
+    for r in range(3):   # per shard, the local variant is the plain operator with k / m
+        c0 = 0
+        for b0, b1 in zip(bounds, bounds[1:]):
+            part = oracle.stat_topk_rows(x[r:r + 1, b0:b1], k // m)
+            c = int(part.count[0])
+            assert np.array_equal(loc.idx[r, c0:c0 + c], part.idx[0, :c] + b0)
+            assert np.allclose(loc.y[r, b0:b1], part.y[0])
+            c0 += c
+        assert c0 == loc.count[r]
+    shifted = x.copy()
+    shifted[:, :n // m] -= 3.0
+    loc = oracle.stat_topk_sharded(shifted, k, bounds, local=True)
+    glo = oracle.stat_topk_sharded(shifted, k, bounds)
+    in_first = lambda res: np.mean([(res.idx[r, :res.count[r]] < n // m).sum() for r in range(40)])
+    assert abs(in_first(loc) - k / m) < 0.1 * k / m
+    # global: the mixture has mean -0.75 and variance 1 + 27/16; a first-shard entry passes the threshold
+    # with the normal tail probability of (theta + 3), which is tiny
+    z = scipy.special.ndtri(1 - k / n)
+    theta = -0.75 + math.sqrt(1 + 27 / 16) * z
+    expect = n / m * scipy.stats.norm.sf(theta + 3.0)
+    assert in_first(glo) < max(3.0 * expect, 1.0) and expect < 0.5
+
+
+def test_sharded_top_k_argument_errors(oracle):
+    x = np.zeros((2, 64))
+    for bad in ([1, 64], [0, 32, 32, 64], [0, 63]):
+        with pytest.raises(ValueError):
+            oracle.stat_topk_sharded(x, 5, bad)
+    with pytest.raises(ValueError):
+        oracle.stat_topk_sharded(x, 64, [0, 64])
+    with pytest.raises(ValueError):
+        oracle.combine_shard_stats([1], [[0.0]], [[0.0]])
