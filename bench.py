@@ -273,6 +273,29 @@ def stat_topk_bench(torch, binding, synth, dev, with_cpu, traffic, np):
                                               "kernel": "stat_topk_vjp_cached_kernel",
                                               "bytes_per_launch": bbytes, "launch_us": bavg_s * 1e6}}
         del gy
+        # one device's share of the same rows sharded four ways by columns (Appendix D.2, global variant):
+        # statistics of its shard, the combination of the four shards' statistics, thresholding of its
+        # shard; the shard is read twice and written once
+        m_sh = 4
+        ns = n // m_sh
+        stats = torch.zeros(m_sh, rows, 2, device=dev)
+        for s_ in range(m_sh):
+            binding.spark_stat_topk_shard_stats(x[:, s_ * ns:(s_ + 1) * ns], stats[s_])
+        th = torch.empty(rows, device=dev)
+
+        def shard_share():
+            binding.spark_stat_topk_shard_stats(x[:, :ns], stats[0])
+            binding.spark_stat_topk_combine_stats(stats, [ns] * m_sh, k, th)
+            binding.spark_stat_topk_apply(x[:, :ns], th, binding.FILL_ZERO, y[:, :ns], count)
+
+        sh_s, _ = time_region(shard_share, 20, 3, torch)
+        sbytes = 3.0 * rows * ns * w
+        out[name]["sharded_global"] = {"shards": m_sh, "us_per_device_share": sh_s / 20 * 1e6,
+                                       "algorithmic_bytes": sbytes, "achieved_gbs": sbytes / (sh_s / 20) / 1e9,
+                                       "hbm_frac": sbytes / (sh_s / 20) / 1e9 / HBM_PEAK_GBS,
+                                       "note": "three launches per share (statistics, combination, thresholding); "
+                                               "the exchange of 8 bytes per row and shard is not part of it"}
+        del stats, th
         if with_cpu:
             import oracle
             # the GPU's active sets of the first `sample` rows against exact sort-based top-k of the

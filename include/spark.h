@@ -104,6 +104,43 @@ spark_status spark_stat_topk(const void* x, spark_dtype dt, int64_t rows, int64_
                              int32_t* count, int32_t* idx, int64_t idx_cap, void* hip_stream);
 
 /*
+ * Statistical top-k of rows whose columns are sharded over several devices (Appendix D.2, the
+ * global variant: every device contributes the statistics of its shard, the combined
+ * statistics give one threshold per row, and each device thresholds its own shard with it; the
+ * result is that of the unsharded operator).  One device's share, in three calls; the exchange of
+ * the statistics between the devices (8 bytes per row and shard) is the caller's.  The local
+ * variant of the same appendix (k / m on every shard, no exchange, a different result) is
+ * spark_stat_topk applied to the shard with k' = k / m.
+ *
+ * spark_stat_topk_shard_stats: the statistics of this device's shard.
+ *   x      [rows][n_shard] of `dt`, row pitch ldx elements (>= n_shard), device, 16-byte aligned
+ *   stats  [rows][2] fp32, device: mean and centred sum of squares sum (x - mean)^2 of each row  out
+ * spark_stat_topk_combine_stats: thresholds from the statistics of all shards, combined in shard
+ * order (mean = sum n_s mean_s / N, M2 = sum (M2_s + n_s (mean_s - mean)^2)):
+ *   stats    [n_shards][rows][2] fp32, device (the arrays the shards produced, gathered)
+ *   n_shard  [n_shards] entries per shard, HOST array; 1 <= n_shards <= SPARK_MAX_SHARDS,
+ *            N = sum n_shard >= 2
+ *   k        1 <= k <= N - 1 (the sparsity level of the whole rows)
+ *   theta    [rows] fp32, device: mean + std Q(1 - k / N), std with divisor N - 1 (Eq.11)  out
+ *   mean, std [rows] fp32, device                                                out, optional
+ * spark_stat_topk_apply: soft thresholding of this device's shard with the given thresholds:
+ *   y = x - theta where x > theta, the fill value elsewhere; count / idx as in spark_stat_topk
+ *   (indices inside the shard).  y may alias x exactly.
+ *
+ * Errors as spark_stat_topk (n_shard >= 1 here).  No workspace; asynchronous on hip_stream.
+ */
+#define SPARK_MAX_SHARDS 64
+spark_status spark_stat_topk_shard_stats(const void* x, spark_dtype dt, int64_t rows, int64_t n_shard,
+                                         int64_t ldx, float* stats, void* hip_stream);
+spark_status spark_stat_topk_combine_stats(const float* stats, const int64_t* n_shard, int32_t n_shards,
+                                           int64_t rows, int64_t k, float* theta, float* mean,
+                                           float* std, void* hip_stream);
+spark_status spark_stat_topk_apply(const void* x, spark_dtype dt, int64_t rows, int64_t n_shard,
+                                   int64_t ldx, const float* theta, spark_fill fill, void* y,
+                                   int64_t ldy, int32_t* count, int32_t* idx, int64_t idx_cap,
+                                   void* hip_stream);
+
+/*
  * The continuously differentiable variant of Section 3.2 (Eq.13, Eq.14, Theorem 2):
  *   y = Huber(StatTop_k(x); delta) / delta,  Huber(a; delta) = a^2 / 2 for |a| < delta,
  *                                            delta (|a| - delta / 2) otherwise,

@@ -24,6 +24,7 @@ MAX_BATCH = 64
 EXPORTS = (
     "spark_status_string", "spark_version", "spark_normal_quantile", "spark_stat_topk",
     "spark_stat_topk_huber", "spark_stat_topk_huber_backward",
+    "spark_stat_topk_shard_stats", "spark_stat_topk_combine_stats", "spark_stat_topk_apply",
     "spark_ffn_workspace_bytes", "spark_ffn_decode", "spark_ffn_decode_layers",
     "spark_ffn_dense_decode", "spark_ffn_dense_decode_layers",
     "spark_ffn_prefill_workspace_bytes", "spark_ffn_prefill",
@@ -87,6 +88,12 @@ def load_library():
     lib.spark_stat_topk_huber.argtypes = [vp, c_int, i64, i64, i64, i64, ctypes.c_float, vp, i64, vp, vp]
     lib.spark_stat_topk_huber_backward.restype = c_int
     lib.spark_stat_topk_huber_backward.argtypes = [vp, vp, c_int, i64, i64, i64, i64, i64, ctypes.c_float, vp, i64, vp]
+    lib.spark_stat_topk_shard_stats.restype = c_int
+    lib.spark_stat_topk_shard_stats.argtypes = [vp, c_int, i64, i64, i64, vp, vp]
+    lib.spark_stat_topk_combine_stats.restype = c_int
+    lib.spark_stat_topk_combine_stats.argtypes = [vp, ctypes.POINTER(i64), i32, i64, i64, vp, vp, vp, vp]
+    lib.spark_stat_topk_apply.restype = c_int
+    lib.spark_stat_topk_apply.argtypes = [vp, c_int, i64, i64, i64, vp, c_int, vp, i64, vp, vp, i64, vp]
     lib.spark_ffn_workspace_bytes.restype = sz
     lib.spark_ffn_workspace_bytes.argtypes = [i32, i32, i32]
     lib.spark_ffn_decode.restype = c_int
@@ -183,6 +190,33 @@ def spark_stat_topk_huber_backward(x: torch.Tensor, gy: torch.Tensor, k: int, de
     rc = load_library().spark_stat_topk_huber_backward(_p(x), _p(gy), _dt(x), rows, n, x.stride(0), gy.stride(0),
                                                        int(k), float(delta), _p(gx), gx.stride(0), _stream())
     _check(rc, "spark_stat_topk_huber_backward")
+
+
+def spark_stat_topk_shard_stats(x: torch.Tensor, stats: torch.Tensor):
+    """(mean, centred sum of squares) of every row of the shard ``x[rows, n_shard]`` into ``stats[rows, 2]``."""
+    rows, n = x.shape
+    rc = load_library().spark_stat_topk_shard_stats(_p(x), _dt(x), rows, n, x.stride(0), _p(stats), _stream())
+    _check(rc, "spark_stat_topk_shard_stats")
+
+
+def spark_stat_topk_combine_stats(stats: torch.Tensor, n_shard, k: int, theta: torch.Tensor,
+                                  mean: Optional[torch.Tensor] = None, std: Optional[torch.Tensor] = None):
+    """Thresholds ``theta[rows]`` from the shards' statistics ``stats[n_shards, rows, 2]`` (contiguous)."""
+    m, rows, _ = stats.shape
+    ns = (ctypes.c_int64 * m)(*[int(v) for v in n_shard])
+    rc = load_library().spark_stat_topk_combine_stats(_p(stats), ns, m, rows, int(k), _p(theta), _p(mean), _p(std),
+                                                      _stream())
+    _check(rc, "spark_stat_topk_combine_stats")
+
+
+def spark_stat_topk_apply(x: torch.Tensor, theta: torch.Tensor, fill: int = FILL_ZERO, y: Optional[torch.Tensor] = None,
+                          count: Optional[torch.Tensor] = None, idx: Optional[torch.Tensor] = None):
+    """Soft thresholding of the shard ``x[rows, n_shard]`` with the given per-row thresholds."""
+    rows, n = x.shape
+    idx_cap = 0 if idx is None else idx.shape[1]
+    rc = load_library().spark_stat_topk_apply(_p(x), _dt(x), rows, n, x.stride(0), _p(theta), int(fill), _p(y),
+                                              0 if y is None else y.stride(0), _p(count), _p(idx), idx_cap, _stream())
+    _check(rc, "spark_stat_topk_apply")
 
 
 def make_layer(k1n: torch.Tensor, k2n: torch.Tensor, vn: torch.Tensor, k: int, gelu: int = GELU_ERF) -> _Layer:

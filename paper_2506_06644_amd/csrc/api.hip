@@ -265,6 +265,54 @@ spark_status spark_stat_topk(const void* x, spark_dtype dt, int64_t rows, int64_
   return e == hipSuccess ? SPARK_OK : SPARK_ERR_DEVICE;
 }
 
+spark_status spark_stat_topk_shard_stats(const void* x, spark_dtype dt, int64_t rows, int64_t n_shard, int64_t ldx,
+                                         float* stats, void* hip_stream) {
+  if (!x || !stats) return SPARK_ERR_NULL;
+  if (!dtype_ok(dt)) return SPARK_ERR_DTYPE;
+  if (rows < 0 || rows > 2147483647LL || n_shard < 1 || n_shard > 2147483647LL || ldx < n_shard) return SPARK_ERR_SHAPE;
+  const size_t es = dtype_size(dt);
+  if (!aligned16(x) || (ldx * es) % 16) return SPARK_ERR_ALIGN;
+  const hipError_t e = spark::launch_stat_topk(x, dt == SPARK_BF16, rows, n_shard, ldx, 0.f, 0, 0.f, nullptr, 0, nullptr,
+                                               nullptr, nullptr, 0, nullptr, static_cast<hipStream_t>(hip_stream), nullptr,
+                                               stats);
+  return e == hipSuccess ? SPARK_OK : SPARK_ERR_DEVICE;
+}
+
+spark_status spark_stat_topk_combine_stats(const float* stats, const int64_t* n_shard, int32_t n_shards, int64_t rows,
+                                           int64_t k, float* theta, float* mean, float* std, void* hip_stream) {
+  if (!stats || !n_shard || !theta) return SPARK_ERR_NULL;
+  if (rows < 0 || rows > 2147483647LL || n_shards < 1 || n_shards > SPARK_MAX_SHARDS) return SPARK_ERR_SHAPE;
+  int64_t total = 0;
+  for (int32_t s = 0; s < n_shards; ++s) {
+    if (n_shard[s] < 1 || n_shard[s] > 2147483647LL) return SPARK_ERR_SHAPE;
+    total += n_shard[s];
+  }
+  if (total < 2 || total > 2147483647LL) return SPARK_ERR_SHAPE;
+  if (k < 1 || k > total - 1) return SPARK_ERR_K;
+  const float z = (float)spark_normal_quantile(1.0 - (double)k / (double)total);
+  const hipError_t e = spark::launch_combine_shard_stats(stats, n_shard, n_shards, rows, z, theta, mean, std,
+                                                         static_cast<hipStream_t>(hip_stream));
+  return e == hipSuccess ? SPARK_OK : SPARK_ERR_DEVICE;
+}
+
+spark_status spark_stat_topk_apply(const void* x, spark_dtype dt, int64_t rows, int64_t n_shard, int64_t ldx,
+                                   const float* theta, spark_fill fill, void* y, int64_t ldy, int32_t* count,
+                                   int32_t* idx, int64_t idx_cap, void* hip_stream) {
+  if (!x || !theta) return SPARK_ERR_NULL;
+  if (!dtype_ok(dt)) return SPARK_ERR_DTYPE;
+  if (fill != SPARK_FILL_ZERO && fill != SPARK_FILL_NEG_INF) return SPARK_ERR_DTYPE;
+  if (rows < 0 || rows > 2147483647LL || n_shard < 1 || n_shard > 2147483647LL || ldx < n_shard) return SPARK_ERR_SHAPE;
+  if (y && ldy < n_shard) return SPARK_ERR_SHAPE;
+  if (idx && idx_cap < 0) return SPARK_ERR_SHAPE;
+  const size_t es = dtype_size(dt);
+  if (!aligned16(x) || (ldx * es) % 16) return SPARK_ERR_ALIGN;
+  if (y && (!aligned16(y) || (ldy * es) % 16)) return SPARK_ERR_ALIGN;
+  const hipError_t e = spark::launch_stat_topk(x, dt == SPARK_BF16, rows, n_shard, ldx, 0.f, fill == SPARK_FILL_NEG_INF,
+                                               0.f, y, ldy, nullptr, count, idx, idx_cap, nullptr,
+                                               static_cast<hipStream_t>(hip_stream), theta, nullptr);
+  return e == hipSuccess ? SPARK_OK : SPARK_ERR_DEVICE;
+}
+
 spark_status spark_stat_topk_huber(const void* x, spark_dtype dt, int64_t rows, int64_t n, int64_t ldx, int64_t k,
                                    float delta, void* y, int64_t ldy, float* theta, void* hip_stream) {
   if (!x || !y) return SPARK_ERR_NULL;

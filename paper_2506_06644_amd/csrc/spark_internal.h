@@ -12,7 +12,13 @@ namespace spark {
 // delta > 0: the kept entries are mapped through Huber(.; delta) / delta (0: plain soft threshold)
 hipError_t launch_stat_topk(const void* x, int dt, int64_t rows, int64_t n, int64_t ldx, float z,
                             int fill, float delta, void* y, int64_t ldy, float* theta, int32_t* count,
-                            int32_t* idx, int64_t idx_cap, int32_t* flags, hipStream_t st);
+                            int32_t* idx, int64_t idx_cap, int32_t* flags, hipStream_t st,
+                            const float* theta_in = nullptr, float* stats_out = nullptr);
+// (theta_in: per-row thresholds to apply instead of computing them; stats_out: [rows][2] (mean, centred
+// sum of squares), after which the launch stops)
+// thresholds from the shards' statistics stats[m][rows][2] with ns[m] entries per shard (host array)
+hipError_t launch_combine_shard_stats(const float* stats, const int64_t* ns, int m, int64_t rows, float z, float* theta,
+                                      float* mean_out, float* std_out, hipStream_t st);
 // gx = gy . d(Huber(StatTop_k(x); delta) / delta)/dx, row by row
 hipError_t launch_stat_topk_vjp(const void* x, const void* gy, int dt, int64_t rows, int64_t n, int64_t ldx,
                                 int64_t ldgy, float z, float delta, void* gx, int64_t ldgx, hipStream_t st);

@@ -49,7 +49,7 @@ template <typename T, int THREADS, int ITEMS>
 __global__ __launch_bounds__(THREADS) void stat_topk_cached_kernel(
     const T* x, int64_t ldx, int n, float z, int fill_neg_inf, float delta, T* y, int64_t ldy,
     float* __restrict__ theta_out, int32_t* __restrict__ count_out, int32_t* __restrict__ idx_out,
-    int64_t idx_cap, int32_t* __restrict__ flags) {
+    int64_t idx_cap, int32_t* __restrict__ flags, const float* __restrict__ theta_in, float* __restrict__ stats_out) {
   constexpr int VEC = Vec16<T>::N;
   constexpr int NW = THREADS / kWave;
   __shared__ float red[NW];
@@ -80,24 +80,38 @@ __global__ __launch_bounds__(THREADS) void stat_topk_cached_kernel(
     }
   }
 
-  float s = 0.f;
+  // Sharded use (Appendix D.2): with theta_in the row's threshold is given (the statistics were
+  // combined elsewhere) and only the thresholding runs; with stats_out the kernel leaves the
+  // shard's mean and centred sum of squares and stops.
+  float theta;
+  if (theta_in != nullptr) {
+    theta = theta_in[row];
+  } else {
+    float s = 0.f;
 #pragma unroll
-  for (int i = 0; i < ITEMS; ++i)
+    for (int i = 0; i < ITEMS; ++i)
 #pragma unroll
-    for (int e = 0; e < VEC; ++e) s += (e < nv[i]) ? v[i].get(e) : 0.f;
-  const float mean = block_sum<THREADS>(s, red) / (float)n;
+      for (int e = 0; e < VEC; ++e) s += (e < nv[i]) ? v[i].get(e) : 0.f;
+    const float mean = block_sum<THREADS>(s, red) / (float)n;
 
-  float ss = 0.f;
+    float ss = 0.f;
 #pragma unroll
-  for (int i = 0; i < ITEMS; ++i)
+    for (int i = 0; i < ITEMS; ++i)
 #pragma unroll
-    for (int e = 0; e < VEC; ++e) {
-      const float c = v[i].get(e) - mean;
-      ss += (e < nv[i]) ? c * c : 0.f;
+      for (int e = 0; e < VEC; ++e) {
+        const float c = v[i].get(e) - mean;
+        ss += (e < nv[i]) ? c * c : 0.f;
+      }
+    const float m2 = block_sum<THREADS>(ss, red);
+    if (stats_out != nullptr) {
+      if (tid == 0) {
+        stats_out[2 * row] = mean;
+        stats_out[2 * row + 1] = m2;
+      }
+      return;
     }
-  const float m2 = block_sum<THREADS>(ss, red);
-  const float sd = sqrtf(m2 / (float)(n - 1));
-  const float theta = mean + sd * z;
+    theta = mean + sqrtf(m2 / (float)(n - 1)) * z;
+  }
   const float inv_delta = delta > 0.f ? 1.f / delta : 0.f;
   if (tid == 0 && theta_out) theta_out[row] = theta;
 
@@ -190,7 +204,7 @@ template <typename T, int THREADS>
 __global__ __launch_bounds__(THREADS) void stat_topk_stream_kernel(
     const T* x, int64_t ldx, int n, float z, int fill_neg_inf, float delta, T* y, int64_t ldy,
     float* __restrict__ theta_out, int32_t* __restrict__ count_out, int32_t* __restrict__ idx_out,
-    int64_t idx_cap, int32_t* __restrict__ flags) {
+    int64_t idx_cap, int32_t* __restrict__ flags, const float* __restrict__ theta_in, float* __restrict__ stats_out) {
   constexpr int NW = THREADS / kWave;
   __shared__ float red[NW];
   __shared__ int tab[NW + 1];
@@ -200,16 +214,28 @@ __global__ __launch_bounds__(THREADS) void stat_topk_stream_kernel(
   const int64_t row = blockIdx.x;
   const T* xr = x + row * ldx;
 
-  float s = 0.f;
-  for (int i = tid; i < n; i += THREADS) s += Vec16<T>::load1(xr + i);
-  const float mean = block_sum<THREADS>(s, red) / (float)n;
-  float ss = 0.f;
-  for (int i = tid; i < n; i += THREADS) {
-    const float c = Vec16<T>::load1(xr + i) - mean;
-    ss += c * c;
+  float theta;
+  if (theta_in != nullptr) {
+    theta = theta_in[row];
+  } else {
+    float s = 0.f;
+    for (int i = tid; i < n; i += THREADS) s += Vec16<T>::load1(xr + i);
+    const float mean = block_sum<THREADS>(s, red) / (float)n;
+    float ss = 0.f;
+    for (int i = tid; i < n; i += THREADS) {
+      const float c = Vec16<T>::load1(xr + i) - mean;
+      ss += c * c;
+    }
+    const float m2 = block_sum<THREADS>(ss, red);
+    if (stats_out != nullptr) {
+      if (tid == 0) {
+        stats_out[2 * row] = mean;
+        stats_out[2 * row + 1] = m2;
+      }
+      return;
+    }
+    theta = mean + sqrtf(m2 / (float)(n - 1)) * z;
   }
-  const float m2 = block_sum<THREADS>(ss, red);
-  const float theta = mean + sqrtf(m2 / (float)(n - 1)) * z;
   const float inv_delta = delta > 0.f ? 1.f / delta : 0.f;
   if (tid == 0 && theta_out) theta_out[row] = theta;
   const float fillv = fill_neg_inf ? -__builtin_inff() : 0.f;
@@ -254,14 +280,14 @@ __global__ __launch_bounds__(THREADS) void stat_topk_stream_kernel(
 template <typename T>
 hipError_t launch_stat_topk_t(const T* x, int64_t rows, int64_t n, int64_t ldx, float z, int fill, float delta,
                               T* y, int64_t ldy, float* theta, int32_t* count, int32_t* idx,
-                              int64_t idx_cap, int32_t* flags, hipStream_t st) {
+                              int64_t idx_cap, int32_t* flags, const float* theta_in, float* stats_out, hipStream_t st) {
   if (rows == 0) return hipSuccess;
   constexpr int VEC = Vec16<T>::N;
   const int64_t nvec = (n + VEC - 1) / VEC;
   const dim3 grid((unsigned)rows);
 #define SPARK_LAUNCH_CACHED(THREADS, ITEMS)                                                        \
   hipLaunchKernelGGL((stat_topk_cached_kernel<T, THREADS, ITEMS>), grid, dim3(THREADS), 0, st, x, \
-                     ldx, (int)n, z, fill, delta, y, ldy, theta, count, idx, idx_cap, flags)
+                     ldx, (int)n, z, fill, delta, y, ldy, theta, count, idx, idx_cap, flags, theta_in, stats_out)
   if (nvec <= 256 * 1) SPARK_LAUNCH_CACHED(256, 1);
   else if (nvec <= 256 * 2) SPARK_LAUNCH_CACHED(256, 2);
   else if (nvec <= 256 * 5) SPARK_LAUNCH_CACHED(256, 5);
@@ -273,7 +299,7 @@ hipError_t launch_stat_topk_t(const T* x, int64_t rows, int64_t n, int64_t ldx, 
     if constexpr (sizeof(T) == 4) SPARK_LAUNCH_CACHED(1024, 16);
   } else
     hipLaunchKernelGGL((stat_topk_stream_kernel<T, 1024>), grid, dim3(1024), 0, st, x, ldx, (int)n,
-                       z, fill, delta, y, ldy, theta, count, idx, idx_cap, flags);
+                       z, fill, delta, y, ldy, theta, count, idx, idx_cap, flags, theta_in, stats_out);
 #undef SPARK_LAUNCH_CACHED
   return hipGetLastError();
 }
@@ -453,12 +479,57 @@ hipError_t launch_stat_topk_vjp_t(const T* x, const T* gy, int64_t rows, int64_t
 
 hipError_t launch_stat_topk(const void* x, int dt, int64_t rows, int64_t n, int64_t ldx, float z,
                             int fill, float delta, void* y, int64_t ldy, float* theta, int32_t* count,
-                            int32_t* idx, int64_t idx_cap, int32_t* flags, hipStream_t st) {
+                            int32_t* idx, int64_t idx_cap, int32_t* flags, hipStream_t st,
+                            const float* theta_in, float* stats_out) {
   if (dt == 0)
     return launch_stat_topk_t<float>(static_cast<const float*>(x), rows, n, ldx, z, fill, delta,
-                                     static_cast<float*>(y), ldy, theta, count, idx, idx_cap, flags, st);
+                                     static_cast<float*>(y), ldy, theta, count, idx, idx_cap, flags, theta_in, stats_out, st);
   return launch_stat_topk_t<bf16_t>(static_cast<const bf16_t*>(x), rows, n, ldx, z, fill, delta,
-                                    static_cast<bf16_t*>(y), ldy, theta, count, idx, idx_cap, flags, st);
+                                    static_cast<bf16_t*>(y), ldy, theta, count, idx, idx_cap, flags, theta_in, stats_out, st);
+}
+
+// Appendix D.2, global variant: the thresholds of `rows` rows from the (mean, centred sum of
+// squares) pairs of their m shards, stats[s][row][2], with n_s = ns[s] entries each: the
+// pairwise update of Chan et al. with every shard against the global mean,
+// mean = sum n_s mean_s / N, M2 = sum (M2_s + n_s (mean_s - mean)^2), in shard order;
+// theta = mean + sqrt(M2 / (N - 1)) z.  One thread per row.
+constexpr int kMaxShards = 64;
+struct ShardSizes {
+  float n[kMaxShards];
+};
+__global__ __launch_bounds__(256) void combine_shard_stats_kernel(const float* __restrict__ stats, ShardSizes sizes, int m,
+                                                                  int64_t rows, float n_total, float z,
+                                                                  float* __restrict__ theta, float* __restrict__ mean_out,
+                                                                  float* __restrict__ std_out) {
+  const int64_t row = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (row >= rows) return;
+  float s1 = 0.f;
+  for (int s = 0; s < m; ++s) s1 += sizes.n[s] * stats[((int64_t)s * rows + row) * 2];
+  const float mean = s1 / n_total;
+  float m2 = 0.f;
+  for (int s = 0; s < m; ++s) {
+    const float d = stats[((int64_t)s * rows + row) * 2] - mean;
+    m2 += stats[((int64_t)s * rows + row) * 2 + 1] + sizes.n[s] * d * d;
+  }
+  const float sd = sqrtf(m2 / (n_total - 1.f));
+  theta[row] = mean + sd * z;
+  if (mean_out) mean_out[row] = mean;
+  if (std_out) std_out[row] = sd;
+}
+
+hipError_t launch_combine_shard_stats(const float* stats, const int64_t* ns, int m, int64_t rows, float z, float* theta,
+                                      float* mean_out, float* std_out, hipStream_t st) {
+  if (rows == 0) return hipSuccess;
+  if (m < 1 || m > kMaxShards) return hipErrorInvalidValue;
+  ShardSizes sizes;
+  double total = 0.0;
+  for (int s = 0; s < kMaxShards; ++s) {
+    sizes.n[s] = s < m ? (float)ns[s] : 0.f;
+    total += s < m ? (double)ns[s] : 0.0;
+  }
+  hipLaunchKernelGGL(combine_shard_stats_kernel, dim3((unsigned)((rows + 255) / 256)), dim3(256), 0, st, stats, sizes, m, rows,
+                     (float)total, z, theta, mean_out, std_out);
+  return hipGetLastError();
 }
 
 hipError_t launch_stat_topk_vjp(const void* x, const void* gy, int dt, int64_t rows, int64_t n, int64_t ldx,

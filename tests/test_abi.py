@@ -186,3 +186,33 @@ def test_static_scratch_entry_point_rejects_on_the_host():
     assert call(_layer(k=0)) == 3
     assert call(_layer(d_ff=600000)) == 6                     # scratch need beyond the built-in array
     assert call(_layer(d_model=328, r=136, wd=binding.F32)) in (2, 5)
+
+
+def test_sharded_top_k_entries_reject_bad_arguments_before_launch():
+    lib = binding.load_library()
+    vp = ctypes.c_void_p
+    i64 = ctypes.c_int64
+
+    def stats(x=0x1000, dt=0, rows=4, n=64, ldx=256, out=0x2000):
+        return lib.spark_stat_topk_shard_stats(vp(x), dt, rows, n, ldx, vp(out) if out else None, None)
+
+    def combine(st=0x1000, ns=(64, 64, 128), rows=4, k=20, theta=0x2000):
+        arr = (i64 * max(1, len(ns)))(*ns)
+        return lib.spark_stat_topk_combine_stats(vp(st) if st else None, arr, len(ns), rows, k, vp(theta) if theta else None,
+                                                 None, None, None)
+
+    def apply(x=0x1000, dt=0, rows=4, n=64, ldx=256, theta=0x3000, fill=0, y=0x2000, ldy=256, cap=0):
+        return lib.spark_stat_topk_apply(vp(x), dt, rows, n, ldx, vp(theta) if theta else None, fill, vp(y), ldy, None, None,
+                                         cap, None)
+
+    assert stats(x=0) == 1 and stats(out=0) == 1
+    assert stats(n=0) == 2 and stats(ldx=32) == 2 and stats(rows=-1) == 2
+    assert stats(dt=2) == 4 and stats(x=0x1004) == 5 and stats(dt=1, ldx=260) == 5
+    assert stats(rows=0) == 0 and stats(n=1, rows=0) == 0
+    assert combine(st=0) == 1 and combine(theta=0) == 1
+    assert combine(ns=()) == 2 and combine(ns=(64, 0)) == 2 and combine(ns=(1,)) == 2 and combine(ns=(1,) * 65) == 2
+    assert combine(k=0) == 3 and combine(k=256) == 3
+    assert combine(rows=0) == 0
+    assert apply(x=0) == 1 and apply(theta=0) == 1
+    assert apply(n=0) == 2 and apply(ldy=32) == 2 and apply(dt=3) == 4 and apply(fill=2) == 4
+    assert apply(x=0x1008) == 5 and apply(rows=0) == 0
