@@ -187,9 +187,9 @@ spark_status spark_stat_topk_huber_backward(const void* x, const void* gy, spark
  * multiples of 16.  One token per call (spark_ffn_decode, spark_ffn_decode_layers,
  * spark_ffn_dense_decode_layers, spark_ffn_prefill with chunk 1) takes the bandwidth-bound
  * phase-by-phase kernels; 2 to 64 bf16 tokens (and prefill chunks of that size) with r and
- * d_model - r multiples of 256 (up to 2048 for at most 16 tokens, 1536 for 33 to 64, 1024 for 17
- * to 32) take the batched matrix-core kernels, which widen the codes to bf16 (exact for both
- * kinds); every other batch is evaluated by the general kernels (a launch sequence per layer,
+ * d_model - r multiples of 256 (1024, 1280, 1536 or 2048 for at most 16 tokens; 512 to 1536 above
+ * that, and 2048 for at most 32) take the batched matrix-core kernels, which widen the codes to
+ * bf16 (exact for both kinds); every other batch is evaluated by the general kernels (a launch sequence per layer,
  * not tuned); the dense comparison calls take one token only
  * (SPARK_ERR_DTYPE otherwise).  Arithmetic: codes widened exactly, fp32 products and sums, the
  * row's scale applied to the finished dot product. */

@@ -234,10 +234,11 @@ def test_prefill_token_by_token_and_unsupported_uses():
     assert e.value.code == 5              # SPARK_ERR_ALIGN
 
 
-@pytest.mark.parametrize("kind", ["fp8", "int8"])
-def test_stack_as_benchmarked_52_layers(kind):
-    """The benchmark's launch configuration (52 quantised 2B-shaped layers in one call): y of the
-    first, a middle and the last layer, and every layer's index set, against the oracle."""
+@pytest.mark.parametrize("kind,batch", [("fp8", 1), ("int8", 1), ("fp8", 4), ("int8", 16), ("fp8", 64)])
+def test_stack_as_benchmarked_52_layers(kind, batch):
+    """The benchmark's launch configurations (52 quantised 2B-shaped layers in one call, with 1, 4, 16
+    or 64 tokens): y of the first, a middle and the last layer, and every layer's index sets, against
+    the oracle."""
     sh, L = synth.GEMMA2_2B, 52
     _, quantize, dequantize = KINDS[kind]
     packed, host = [], {}
@@ -251,17 +252,18 @@ def test_stack_as_benchmarked_52_layers(kind):
                 host[(l, i)] = dequantize(codes.cpu().numpy(), scales.cpu().numpy())
         packed.append(arrays)
         del w
-    q = synth.tokens(sh, 1, 2001, torch.bfloat16)
+    q = synth.tokens(sh, batch, 2001, torch.bfloat16)
     out = _run(sh, packed, q, True, kind=kind)
-    qs = synth.to_oracle(q)[0]
+    qs = synth.to_oracle(q)
     pick = [0, 25, 51]
     sub = {k: (v[pick] if v.shape[0] == L else v) for k, v in out.items()}
     deq = [tuple(torch.from_numpy(host[(l, i)]) for i in range(3)) for l in pick]
-    check_ffn_against_oracle(sh, deq, q, sub, TOL_BF16_TIGHT, what=f"{kind} stack")
+    check_ffn_against_oracle(sh, deq, q, sub, TOL_BF16_TIGHT, what=f"{kind} stack, {batch} tokens")
     from parity_util import assert_active_set
     for l in range(L):
-        s = host[(l, 0)].astype(np.float64) @ qs[:sh.r].astype(np.float64)
-        ref = oracle.stat_topk_rows(s[None, :], sh.k)
-        assert abs(out["theta"][l, 0] - ref.theta[0]) <= 1e-5 * ref.std[0] + 1e-6 * abs(ref.theta[0])
-        m = int(out["count"][l, 0])
-        assert_active_set(out["idx"][l, 0, :m], s, ref.theta[0], ref.std[0], f"layer {l}")
+        S = qs[:, :sh.r].astype(np.float64) @ host[(l, 0)].astype(np.float64).T
+        ref = oracle.stat_topk_rows(S, sh.k)
+        for b in range(batch):
+            assert abs(out["theta"][l, b] - ref.theta[b]) <= 1e-5 * ref.std[b] + 1e-6 * abs(ref.theta[b])
+            m = int(out["count"][l, b])
+            assert_active_set(out["idx"][l, b, :m], S[b], ref.theta[b], ref.std[b], f"layer {l} token {b}")
