@@ -45,6 +45,63 @@ __device__ __forceinline__ float huber_over_delta(float a, float delta, float in
 // Its derivative in a (Appendix A.2): a / delta below delta, 1 from there on.
 __device__ __forceinline__ float huber_slope(float a, float delta, float inv_delta) { return a < delta ? a * inv_delta : 1.f; }
 
+// A copy of one held vector that the compiler has to take as a new value.  Every pass over a row
+// held in registers unpacks its bf16 pairs from such a copy (one shift or mask per element, and
+// four moves per vector for the copy): without it the compiler keeps the widened values of one pass
+// alive for the next, which triples the registers of a thread and halves the rows in flight
+// per compute unit.  The copies are made in program order, one vector at a time.
+template <typename V>
+__device__ __forceinline__ V fresh(const V& v) {
+  V t = v;
+  if constexpr (V::N == 8) asm volatile("" : "+v"(t.raw));
+  return t;
+}
+
+// The thresholding pass over a row held in registers (Eq.10, or its Huber form of Section 3.2 with
+// HUBER): writes y where asked and returns the thread's number of active entries; with MASKS it also
+// leaves each vector's mask of active entries (for the index list and the flags).  Entries that
+// are not part of the row hold -inf and are never active.  This pass is where the kernel's
+// arithmetic is, and the three forms keep the plain one (no Huber term, no masks) at 5 or 6
+// instructions per element.
+template <bool HUBER, bool MASKS, typename T, int THREADS, int ITEMS>
+__device__ __forceinline__ int threshold_pass(const Vec16<T> (&v)[ITEMS], const int (&nv)[ITEMS], float theta, float delta,
+                                              float fillv, T* yr, int tid, uint32_t (&act)[ITEMS]) {
+  constexpr int VEC = Vec16<T>::N;
+  const float inv_delta = HUBER ? 1.f / delta : 0.f;
+  int cnt = 0;
+#pragma unroll
+  for (int i = 0; i < ITEMS; ++i) {
+    const int vi = i * THREADS + tid;
+    const Vec16<T> xi = fresh(v[i]);
+    uint32_t m = 0;
+    Vec16<T> o;
+#pragma unroll
+    for (int e = 0; e < VEC; e += 2) {
+      const float x0 = xi.get(e), x1 = xi.get(e + 1);
+      const bool a0 = x0 > theta, a1 = x1 > theta;
+      if (MASKS) m |= (a0 ? (1u << e) : 0u) | (a1 ? (2u << e) : 0u);
+      else cnt += (a0 ? 1 : 0) + (a1 ? 1 : 0);
+      const float d0 = x0 - theta, d1 = x1 - theta;
+      o.set2(e / 2, a0 ? (HUBER ? huber_over_delta(d0, delta, inv_delta) : d0) : fillv,
+             a1 ? (HUBER ? huber_over_delta(d1, delta, inv_delta) : d1) : fillv);
+    }
+    if (MASKS) {
+      act[i] = m;
+      cnt += __popc(m);
+    }
+    if (yr != nullptr && nv[i] != 0) {
+      if (nv[i] == VEC) {
+        __builtin_nontemporal_store(o.raw, reinterpret_cast<decltype(o.raw)*>(yr + (int64_t)vi * VEC));
+      } else {
+#pragma unroll
+        for (int e = 0; e < VEC; ++e)
+          if (e < nv[i]) Vec16<T>::store1(yr + (int64_t)vi * VEC + e, o.get(e));
+      }
+    }
+  }
+  return cnt;
+}
+
 template <typename T, int THREADS, int ITEMS>
 __global__ __launch_bounds__(THREADS) void stat_topk_cached_kernel(
     const T* x, int64_t ldx, int n, float z, int fill_neg_inf, float delta, T* y, int64_t ldy,
@@ -87,21 +144,36 @@ __global__ __launch_bounds__(THREADS) void stat_topk_cached_kernel(
   if (theta_in != nullptr) {
     theta = theta_in[row];
   } else {
+    // entries that are not part of the row were loaded as zeros: they add nothing here
     float s = 0.f;
 #pragma unroll
-    for (int i = 0; i < ITEMS; ++i)
+    for (int i = 0; i < ITEMS; ++i) {
+      const Vec16<T> xi = fresh(v[i]);
 #pragma unroll
-      for (int e = 0; e < VEC; ++e) s += (e < nv[i]) ? v[i].get(e) : 0.f;
+      for (int e = 0; e < VEC; ++e) s += xi.get(e);
+    }
     const float mean = block_sum<THREADS>(s, red) / (float)n;
 
     float ss = 0.f;
 #pragma unroll
-    for (int i = 0; i < ITEMS; ++i)
+    for (int i = 0; i < ITEMS; ++i) {
+      const Vec16<T> xi = fresh(v[i]);
+      float sv = 0.f;
 #pragma unroll
       for (int e = 0; e < VEC; ++e) {
-        const float c = v[i].get(e) - mean;
-        ss += (e < nv[i]) ? c * c : 0.f;
+        const float c = xi.get(e) - mean;
+        sv += c * c;
       }
+      if (nv[i] != VEC) {  // the row's last, partial vector and the vectors past it
+        sv = 0.f;
+#pragma unroll
+        for (int e = 0; e < VEC; ++e) {
+          const float c = xi.get(e) - mean;
+          sv += (e < nv[i]) ? c * c : 0.f;
+        }
+      }
+      ss += sv;
+    }
     const float m2 = block_sum<THREADS>(ss, red);
     if (stats_out != nullptr) {
       if (tid == 0) {
@@ -112,45 +184,24 @@ __global__ __launch_bounds__(THREADS) void stat_topk_cached_kernel(
     }
     theta = mean + sqrtf(m2 / (float)(n - 1)) * z;
   }
-  const float inv_delta = delta > 0.f ? 1.f / delta : 0.f;
   if (tid == 0 && theta_out) theta_out[row] = theta;
 
-  const float fillv = fill_neg_inf ? -__builtin_inff() : 0.f;
-  uint32_t act[ITEMS];
-  int cnt = 0;
+  // entries that are not part of the row become -inf: never active
 #pragma unroll
-  for (int i = 0; i < ITEMS; ++i) {
-    uint32_t m = 0;
+  for (int i = 0; i < ITEMS; ++i)
+    if (nv[i] != VEC) {
 #pragma unroll
-    for (int e = 0; e < VEC; ++e) {
-      const float xv = v[i].get(e);
-      const bool a = (e < nv[i]) && (xv > theta);
-      m |= a ? (1u << e) : 0u;
+      for (int e = 0; e < VEC; ++e)
+        if (e >= nv[i]) v[i].set(e, -__builtin_inff());
     }
-    act[i] = m;
-    cnt += __popc(m);
-  }
 
-  if (y) {
-    T* yr = y + row * ldy;
-#pragma unroll
-    for (int i = 0; i < ITEMS; ++i) {
-      const int vi = i * THREADS + tid;
-      if (nv[i] == 0) continue;
-      Vec16<T> o;
-#pragma unroll
-      for (int e = 0; e < VEC; e += 2)
-        o.set2(e / 2, ((act[i] >> e) & 1u) ? huber_over_delta(v[i].get(e) - theta, delta, inv_delta) : fillv,
-               ((act[i] >> (e + 1)) & 1u) ? huber_over_delta(v[i].get(e + 1) - theta, delta, inv_delta) : fillv);
-      if (nv[i] == VEC) {
-        __builtin_nontemporal_store(o.raw, reinterpret_cast<decltype(o.raw)*>(yr + (int64_t)vi * VEC));
-      } else {
-#pragma unroll
-        for (int e = 0; e < VEC; ++e)
-          if (e < nv[i]) Vec16<T>::store1(yr + (int64_t)vi * VEC + e, o.get(e));
-      }
-    }
-  }
+  const float fillv = fill_neg_inf ? -__builtin_inff() : 0.f;
+  T* yr = y ? y + row * ldy : nullptr;
+  uint32_t act[ITEMS];
+  int cnt;
+  if (delta > 0.f) cnt = threshold_pass<true, true, T, THREADS, ITEMS>(v, nv, theta, delta, fillv, yr, tid, act);
+  else if (flags != nullptr || idx_out != nullptr) cnt = threshold_pass<false, true, T, THREADS, ITEMS>(v, nv, theta, delta, fillv, yr, tid, act);
+  else cnt = threshold_pass<false, false, T, THREADS, ITEMS>(v, nv, theta, delta, fillv, yr, tid, act);
 
   if (flags) {
 #pragma unroll
@@ -305,16 +356,6 @@ hipError_t launch_stat_topk_t(const T* x, int64_t rows, int64_t n, int64_t ldx, 
 }
 
 
-// Between the passes over a row held in registers: the packed vectors are declared changed, so
-// the compiler unpacks bf16 pairs again in the next pass (one shift or mask per element)
-// instead of keeping every widened value alive across the passes, which triples the registers
-// of a thread and halves the rows in flight per compute unit.
-template <typename V, int N>
-__device__ __forceinline__ void forget_unpacked(V (&v)[N]) {
-#pragma unroll
-  for (int i = 0; i < N; ++i) asm volatile("" : "+v"(v[i].raw));
-}
-
 // ------------------------------------------------------------------------------- backward
 // gx = gy . d(Huber(StatTop_k(x); delta) / delta)/dx for one row per workgroup (chain rule
 // through theta = mean + z std, Appendix A.2):
@@ -322,6 +363,57 @@ __device__ __forceinline__ void forget_unpacked(V (&v)[N]) {
 //   gx_j = w_j - G * (1/n + z (x_j - mean) / ((n - 1) std))
 // x and gy are each read once (both rows sit in registers), gx is written once.  A constant
 // row (std = 0) has no active entry: G = 0 and gx = 0.
+// Slope of the Huber form at a = x - theta, zero where the entry is inactive: a / delta clamped to
+// [0, 1] (one multiplication whose result is clamped), which is a / delta below delta and 1 from
+// there on (Appendix A.2); without the Huber term (delta = 0) the step 1[a > 0].
+template <bool HUBER>
+__device__ __forceinline__ float active_slope(float a, float inv_delta) {
+  if (HUBER) return __builtin_amdgcn_fmed3f(a * inv_delta, 0.f, 1.f);
+  return a > 0.f ? 1.f : 0.f;
+}
+
+// The two passes of the backward kernel after theta is known: G = sum of w, then gx.
+template <bool HUBER, typename T, int THREADS, int ITEMS>
+__device__ __forceinline__ void vjp_passes(Vec16<T> (&v)[ITEMS], Vec16<T> (&g)[ITEMS], const int (&nv)[ITEMS], int n, float z,
+                                           float mean, float sd, float theta, float delta, T* or_, int tid, float* red) {
+  constexpr int VEC = Vec16<T>::N;
+  const float inv_delta = HUBER ? 1.f / delta : 0.f;
+  float wsum = 0.f;
+#pragma unroll
+  for (int i = 0; i < ITEMS; ++i) {
+    const Vec16<T> xv = fresh(v[i]), gv = fresh(g[i]);
+#pragma unroll
+    for (int e = 0; e < VEC; ++e) wsum += gv.get(e) * active_slope<HUBER>(xv.get(e) - theta, inv_delta);
+  }
+  const float G = block_sum<THREADS>(wsum, red);
+  const float c0 = G / (float)n, c1 = sd > 0.f ? G * z / ((float)(n - 1) * sd) : 0.f;
+#pragma unroll
+  for (int i = 0; i < ITEMS; ++i) {
+    const int vi = i * THREADS + tid;
+    if (nv[i] == 0) continue;
+    const Vec16<T> xi = fresh(v[i]), gi = fresh(g[i]);
+    Vec16<T> o;
+#pragma unroll
+    for (int e = 0; e < VEC; e += 2) {
+      float r[2];
+#pragma unroll
+      for (int h = 0; h < 2; ++h) {
+        const float xv = xi.get(e + h);
+        const float w = gi.get(e + h) * active_slope<HUBER>(xv - theta, inv_delta);
+        r[h] = w - (c0 + c1 * (xv - mean));
+      }
+      o.set2(e / 2, r[0], r[1]);
+    }
+    if (nv[i] == VEC) {
+      __builtin_nontemporal_store(o.raw, reinterpret_cast<decltype(o.raw)*>(or_ + (int64_t)vi * VEC));
+    } else {
+#pragma unroll
+      for (int e = 0; e < VEC; ++e)
+        if (e < nv[i]) Vec16<T>::store1(or_ + (int64_t)vi * VEC + e, o.get(e));
+    }
+  }
+}
+
 template <typename T, int THREADS, int ITEMS>
 __global__ __launch_bounds__(THREADS) void stat_topk_vjp_cached_kernel(const T* x, int64_t ldx, const T* gy, int64_t ldgy,
                                                                       int n, float z, float delta, T* gx, int64_t ldgx) {
@@ -354,63 +446,42 @@ __global__ __launch_bounds__(THREADS) void stat_topk_vjp_cached_kernel(const T* 
         }
     }
   }
+  // entries that are not part of the row were loaded as zeros, in x and in gy: they add nothing
+  // to the sum of x, and their w below is gy * slope = 0
   float s = 0.f;
 #pragma unroll
-  for (int i = 0; i < ITEMS; ++i)
+  for (int i = 0; i < ITEMS; ++i) {
+    const Vec16<T> xi = fresh(v[i]);
 #pragma unroll
-    for (int e = 0; e < VEC; ++e) s += (e < nv[i]) ? v[i].get(e) : 0.f;
+    for (int e = 0; e < VEC; ++e) s += xi.get(e);
+  }
   const float mean = block_sum<THREADS>(s, red) / (float)n;
-  forget_unpacked(v);
   float ss = 0.f;
 #pragma unroll
-  for (int i = 0; i < ITEMS; ++i)
+  for (int i = 0; i < ITEMS; ++i) {
+    const Vec16<T> xi = fresh(v[i]);
+    float sv = 0.f;
 #pragma unroll
     for (int e = 0; e < VEC; ++e) {
-      const float c = v[i].get(e) - mean;
-      ss += (e < nv[i]) ? c * c : 0.f;
+      const float c = xi.get(e) - mean;
+      sv += c * c;
     }
+    if (nv[i] != VEC) {  // the row's last, partial vector and the vectors past it
+      sv = 0.f;
+#pragma unroll
+      for (int e = 0; e < VEC; ++e) {
+        const float c = xi.get(e) - mean;
+        sv += (e < nv[i]) ? c * c : 0.f;
+      }
+    }
+    ss += sv;
+  }
   const float m2 = block_sum<THREADS>(ss, red);
   const float sd = sqrtf(m2 / (float)(n - 1));
   const float theta = mean + sd * z;
-  const float inv_delta = delta > 0.f ? 1.f / delta : 0.f;
-  forget_unpacked(v);
-  float wsum = 0.f;
-#pragma unroll
-  for (int i = 0; i < ITEMS; ++i)
-#pragma unroll
-    for (int e = 0; e < VEC; ++e) {
-      const float a = v[i].get(e) - theta;
-      wsum += (e < nv[i] && a > 0.f) ? g[i].get(e) * huber_slope(a, delta, inv_delta) : 0.f;
-    }
-  const float G = block_sum<THREADS>(wsum, red);
-  forget_unpacked(v);
-  forget_unpacked(g);
-  const float c0 = G / (float)n, c1 = sd > 0.f ? G * z / ((float)(n - 1) * sd) : 0.f;
   T* or_ = gx + row * ldgx;
-#pragma unroll
-  for (int i = 0; i < ITEMS; ++i) {
-    const int vi = i * THREADS + tid;
-    if (nv[i] == 0) continue;
-    Vec16<T> o;
-#pragma unroll
-    for (int e = 0; e < VEC; e += 2) {
-      float r[2];
-#pragma unroll
-      for (int h = 0; h < 2; ++h) {
-        const float xv = v[i].get(e + h), a = xv - theta;
-        const float w = a > 0.f ? g[i].get(e + h) * huber_slope(a, delta, inv_delta) : 0.f;
-        r[h] = w - (c0 + c1 * (xv - mean));
-      }
-      o.set2(e / 2, r[0], r[1]);
-    }
-    if (nv[i] == VEC) {
-      __builtin_nontemporal_store(o.raw, reinterpret_cast<decltype(o.raw)*>(or_ + (int64_t)vi * VEC));
-    } else {
-#pragma unroll
-      for (int e = 0; e < VEC; ++e)
-        if (e < nv[i]) Vec16<T>::store1(or_ + (int64_t)vi * VEC + e, o.get(e));
-    }
-  }
+  if (delta > 0.f) vjp_passes<true, T, THREADS, ITEMS>(v, g, nv, n, z, mean, sd, theta, delta, or_, tid, red);
+  else vjp_passes<false, T, THREADS, ITEMS>(v, g, nv, n, z, mean, sd, theta, delta, or_, tid, red);
 }
 
 // Rows too long for the register file: x is read three times, gy twice.
