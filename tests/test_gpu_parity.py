@@ -327,6 +327,19 @@ def test_matrix_core_path_with_a_ragged_number_of_neurons(batch):
     check_ffn_against_oracle(sh, weights, q, out, TOL_BF16_TIGHT, what=f"ragged d_ff B={batch}")
 
 
+@pytest.mark.parametrize("d_ff", [16384, 16400])
+@pytest.mark.parametrize("batch", [1, 5, 33])
+def test_most_neurons_the_matrix_core_path_takes_and_one_tile_more(d_ff, batch):
+    """The batched matrix-core path keeps the union mask of a layer in 256 words of 64 bits: 16384
+    neurons are the most it takes, and a layer with one 16-row tile more goes through the general kernels.
+    Batch 1 runs the phase-by-phase kernels at both sizes."""
+    sh = synth.FFNShape("wide", 256, d_ff, 128, round(0.08 * d_ff))
+    weights = synth.ffn_stack(sh, 2, base_seed=911, dtype=torch.bfloat16)
+    q = synth.tokens(sh, batch, 912 + batch, torch.bfloat16)
+    out = run_gpu_ffn(sh, weights, q, via_layers=True)
+    check_ffn_against_oracle(sh, weights, q, out, TOL_BF16_TIGHT, what=f"d_ff={d_ff} B={batch}")
+
+
 @pytest.mark.parametrize("d_model,d_ff,r,k", [(1280, 1000, 512, 77), (2304, 600, 1024, 48), (3072, 200, 1536, 20),
                                               (1536, 2085, 768, 160)])
 @pytest.mark.parametrize("batch", [17, 32, 40, 64])
