@@ -339,8 +339,13 @@ hipError_t launch_stat_topk_t(const T* x, int64_t rows, int64_t n, int64_t ldx, 
 #define SPARK_LAUNCH_CACHED(THREADS, ITEMS)                                                        \
   hipLaunchKernelGGL((stat_topk_cached_kernel<T, THREADS, ITEMS>), grid, dim3(THREADS), 0, st, x, \
                      ldx, (int)n, z, fill, delta, y, ldy, theta, count, idx, idx_cap, flags, theta_in, stats_out)
-  if (nvec <= 256 * 1) SPARK_LAUNCH_CACHED(256, 1);
-  else if (nvec <= 256 * 2) SPARK_LAUNCH_CACHED(256, 2);
+  // rows of up to 576 vectors go to one wavefront each: the two workgroup-wide sums of the statistics
+  // cost a short row more than its loads (a 4.6 KB bf16 row: 23 us for 8192 rows with 256 threads per
+  // row, 15 us with 64)
+  if (nvec <= 64 * 1) SPARK_LAUNCH_CACHED(64, 1);
+  else if (nvec <= 64 * 2) SPARK_LAUNCH_CACHED(64, 2);
+  else if (nvec <= 64 * 5) SPARK_LAUNCH_CACHED(64, 5);
+  else if (nvec <= 64 * 9) SPARK_LAUNCH_CACHED(64, 9);
   else if (nvec <= 256 * 5) SPARK_LAUNCH_CACHED(256, 5);
   else if (nvec <= 256 * 9) SPARK_LAUNCH_CACHED(256, 9);
   else if (nvec <= 256 * 14) SPARK_LAUNCH_CACHED(256, 14);
