@@ -12,9 +12,10 @@
 //
 //   predict   s[h][g][i] = k1c_h[i] . q_hg[:r] for every cached key: a fully coalesced sweep
 //             (a wave instruction covers 64 / LPR consecutive keys, LPR lanes per key); the
-//             `group` query heads that share a cache are served by one pass over it.
-//   gather    one workgroup per (query head): mean / std of the scores (two passes over
-//             registers), theta, the kept keys in ascending order, then for those only the
+//             `group` query heads that share a cache are served by one pass over it.  Every
+//             workgroup also leaves sum, centred sum of squares and maximum of its 256 scores.
+//   gather    one workgroup per (query head): theta from the merged block statistics, then every
+//             wave for itself: the kept keys among the keys it holds and, for those only, the
 //             k2c and vc rows: w = exp(s - max s) * softplus(k2c[i] . q[r:]),
 //             y = sum w vc[i] / sum exp(s - max s), summed in a fixed order.
 //
@@ -29,8 +30,10 @@ namespace {
 constexpr int kKeysPerWave = 64;
 constexpr int kKeysPerBlock = 4 * kKeysPerWave;   // predict: 4 waves
 constexpr int kGatherWavesA = 16;    // gather: waves per workgroup
-constexpr int kChunk = 4096;         // kept keys handled per pass of the gather
+constexpr int kGatherGateCap = 512;  // keys per wave up to which the gate products have room in LDS too
 constexpr int kMaxVPT = kAttnMaxCtx / (kGatherWavesA * kWave);  // scores per thread of the gather
+constexpr int kStatBlocks = kAttnMaxCtx / kKeysPerBlock;         // predictor workgroups per cache at most (64)
+static_assert(kStatBlocks <= kWave, "a lane per block when the gather merges the block statistics");
 
 struct AttnParams {
   const void* k1c[kAttnMaxHeads];
@@ -42,6 +45,7 @@ struct AttnParams {
   int32_t* count;     // [heads][G]         optional
   int32_t* idx;       // [heads][G][n_ctx]  optional
   float* scores;      // [heads][G][n_ctx]
+  float* bstats;      // [heads][G][kStatBlocks][4]: sum, centred sum of squares and maximum of each block of 256 scores
   int n_ctx, d_attn, r, G, q_bf16, keep_all;
   float z;
 };
@@ -65,6 +69,32 @@ __device__ __forceinline__ float group_sum(float v) {
 #pragma unroll
   for (int o = 16; o < LPR; o <<= 1) v += __shfl_xor(v, o, kWave);
   return v;
+}
+
+// Sums and maxima over a wavefront without the LDS crossbar (quad swaps, row mirrors, row
+// broadcasts), returned as a uniform value; the order of the operations is fixed.
+template <int CTRL, int ROW_MASK>
+__device__ __forceinline__ float dpp_other(float x) {  // lanes the row mask leaves out see their own value
+  return __int_as_float(__builtin_amdgcn_update_dpp(__float_as_int(x), __float_as_int(x), CTRL, ROW_MASK, 0xf, false));
+}
+__device__ __forceinline__ float wave_total(float x) {
+  x += dpp_other<0xB1, 0xf>(x);
+  x += dpp_other<0x4E, 0xf>(x);
+  x += dpp_other<0x141, 0xf>(x);
+  x += dpp_other<0x140, 0xf>(x);
+  // (a lane outside the row mask would add its own value: those lanes' results are not used)
+  x += __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(x), 0x142, 0xa, 0xf, false));
+  x += __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(x), 0x143, 0xc, 0xf, false));
+  return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(x), 63));
+}
+__device__ __forceinline__ float wave_maximum(float x) {
+  x = fmaxf(x, dpp_other<0xB1, 0xf>(x));
+  x = fmaxf(x, dpp_other<0x4E, 0xf>(x));
+  x = fmaxf(x, dpp_other<0x141, 0xf>(x));
+  x = fmaxf(x, dpp_other<0x140, 0xf>(x));
+  x = fmaxf(x, dpp_other<0x142, 0xa>(x));
+  x = fmaxf(x, dpp_other<0x143, 0xc>(x));
+  return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(x), 63));
 }
 
 // --------------------------------------------------------------------------------- predict
@@ -125,135 +155,162 @@ __global__ __launch_bounds__(256) void attn_predict_kernel(const AttnParams P) {
   for (int g = 0; g < G; ++g)
     for (int t = tid; t < kKeysPerBlock; t += 256)
       if (key0 + t < P.n_ctx) P.scores[((size_t)h * G + g) * P.n_ctx + key0 + t] = s_sh[g][t];
+  // the block's statistics (Eq.11 needs mean and standard deviation of all scores of a head: the
+  // gather merges the blocks' sums and centred sums of squares): wave g serves head g
+  if (wave < G) {
+    const int valid = min(kKeysPerBlock, P.n_ctx - key0);
+    float x[kKeysPerBlock / kWave];
+    float sum = 0.f, mx = -INFINITY;
+#pragma unroll
+    for (int i = 0; i < kKeysPerBlock / kWave; ++i) {
+      const int t = lane + kWave * i;
+      x[i] = t < valid ? s_sh[wave][t] : 0.f;
+      sum += x[i];
+      if (t < valid) mx = fmaxf(mx, x[i]);
+    }
+    sum = wave_total(sum);
+    mx = wave_maximum(mx);
+    const float mean_b = sum / (float)valid;
+    float sq = 0.f;
+#pragma unroll
+    for (int i = 0; i < kKeysPerBlock / kWave; ++i) {
+      const float d = lane + kWave * i < valid ? x[i] - mean_b : 0.f;
+      sq += d * d;
+    }
+    sq = wave_total(sq);
+    if (lane == 0)
+      *reinterpret_cast<f32x4*>(P.bstats + (((size_t)h * G + wave) * kStatBlocks + blockIdx.x) * 4) = f32x4{sum, sq, mx, 0.f};
+  }
 }
 
 // ---------------------------------------------------------------------------------- gather
-template <int T>
-__device__ __forceinline__ float block_max(float v, float* red) {
-#pragma unroll
-  for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, kWave));
-  const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
-  __syncthreads();
-  if (lane == 0) red[wave] = v;
-  __syncthreads();
-  float t = red[0];
-#pragma unroll
-  for (int w = 1; w < T / kWave; ++w) t = fmaxf(t, red[w]);
-  return t;
+// LDS written by some lanes of a wavefront and read by others of the same wavefront
+__device__ __forceinline__ void wave_lds_fence() {
+  asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+  __builtin_amdgcn_wave_barrier();
 }
 
-// LPR2 / LPRV: lanes per k2c row / vc row (16-byte chunks); a wave step handles 64 / LPRV keys.
+// One workgroup of 16 waves per query head.  The workgroup forms theta and the largest score
+// together (two workgroup-wide reductions); from there on every wave works alone on the kept keys
+// among the keys it holds (key j = tid + T k, so the kept keys, which cluster in time, spread
+// evenly over the waves): it lists them in LDS, multiplies their k2c rows by q[r:]
+// (64 / LPR2 keys per step), forms the weights w = exp(s - max s) * softplus(gate) once per key
+// (one lane per list position: inside the row loops the transcendentals would run for a few
+// keys per instruction), and accumulates w * vc[key] (64 / LPRV keys per step; the first value
+// rows are requested before the weights are formed).  The waves' rows and their sums of
+// exp(s - max s) meet in LDS once, at the end, and are added in wave order.  Only a call that asks
+// for the index list pays for the workgroup-wide ordered compaction.
+// LDS per wave: its keys (2 bytes each), their scores (overwritten by the weights) and, when the
+// context is short enough for it to fit, their gate products; with longer contexts (LEAN) the lane
+// that finishes a gate product forms the weight on the spot.
+// LPR2 / LPRV: lanes per k2c row / vc row (16-byte chunks).
 template <typename WT, int LPR2, int LPRV>
 __global__ __launch_bounds__(kGatherWavesA * kWave) void attn_gather_kernel(const AttnParams P) {
   constexpr int VEC = Vec16<WT>::N;
   constexpr int T = kGatherWavesA * kWave;
-  constexpr int KPS = kWave / LPRV;  // keys per wave step
+  constexpr int KPS = kWave / LPRV;  // keys per wave step, values
+  constexpr int KPG = kWave / LPR2;  // keys per wave step, gates
   static_assert(LPR2 <= LPRV, "the gate half of a key is not longer than the value");
-  __shared__ float red[kGatherWavesA];
+  __shared__ float red_den[kGatherWavesA];
+  __shared__ int red_cnt[kGatherWavesA];
   __shared__ int wcnt[kMaxVPT * kGatherWavesA];
   __shared__ int woff[kMaxVPT * kGatherWavesA + 1];
-  __shared__ float w_sh[kChunk];  // gate products, then weights, by list position within the chunk
   extern __shared__ __align__(16) unsigned char dyn[];
-  float* s_sh = reinterpret_cast<float*>(dyn);                                  // [n_ctx] scores, later [16][d_attn] partial rows
-  uint16_t* list = reinterpret_cast<uint16_t*>(dyn + (size_t)max(P.n_ctx, kGatherWavesA * P.d_attn) * 4);  // [n_ctx] kept keys, ascending
-  const int tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid / kWave;
+  const int tid = threadIdx.x, lane = tid & (kWave - 1);
+  const int wave = __builtin_amdgcn_readfirstlane(tid / kWave);
   const int g = blockIdx.x, h = blockIdx.y, G = P.G, n = P.n_ctx;
+  const int vpt = (n + T - 1) / T;    // scores per thread in use
+  const int cap = vpt * kWave;        // most keys a wave can keep
+  const bool lean = cap > kGatherGateCap;
+  float* rows_sh = reinterpret_cast<float*>(dyn);                                   // [16][d_attn]
+  float* wval = rows_sh + (size_t)kGatherWavesA * P.d_attn + (size_t)wave * cap;     // [cap] of this wave
+  float* wgate = rows_sh + (size_t)kGatherWavesA * P.d_attn + (size_t)kGatherWavesA * cap + (size_t)wave * cap;  // (not LEAN)
+  uint16_t* wkey = reinterpret_cast<uint16_t*>(rows_sh + (size_t)kGatherWavesA * P.d_attn + (size_t)(lean ? 1 : 2) * kGatherWavesA * cap) +
+                   (size_t)wave * cap;
   const size_t hg = (size_t)h * G + g;
   const float* sc = P.scores + hg * n;
 
   float v[kMaxVPT];
-  float sum = 0.f, vmax = -INFINITY;
 #pragma unroll
   for (int k = 0; k < kMaxVPT; ++k) {
     const int j = tid + T * k;
     v[k] = j < n ? sc[j] : 0.f;
-    sum += v[k];
-    if (j < n) {
-      vmax = fmaxf(vmax, v[k]);
-      s_sh[j] = v[k];
+  }
+  // theta and the largest score from the predictor's block statistics: a lane per block, every wave
+  // for itself (no workgroup-wide sum): mean = sum of the sums / n, M2 = sum (M2_b + n_b (mean_b - mean)^2)
+  float theta = -INFINITY, smax;
+  {
+    const int nblk = (n + kKeysPerBlock - 1) / kKeysPerBlock;
+    const f32x4 st = lane < nblk ? *reinterpret_cast<const f32x4*>(P.bstats + (hg * kStatBlocks + lane) * 4) : f32x4{0.f, 0.f, -INFINITY, 0.f};
+    const float nb = lane < nblk ? (float)min(kKeysPerBlock, n - lane * kKeysPerBlock) : 0.f;
+    smax = wave_maximum(st[2]);
+    if (!P.keep_all) {
+      const float mean = wave_total(st[0]) / (float)n;
+      const float d = lane < nblk ? st[0] / nb - mean : 0.f;
+      const float m2 = wave_total(st[1] + nb * d * d);
+      theta = mean + sqrtf(m2 / (float)(n - 1)) * P.z;
     }
   }
-  float theta = -INFINITY;
-  if (!P.keep_all) {
-    const float mean = block_sum<T>(sum, red) / (float)n;
-    float sq = 0.f;
+
+  // this wave's kept keys, in the order (k, lane) = ascending
+  int nw = 0;
+#pragma unroll
+  for (int k = 0; k < kMaxVPT; ++k) {
+    const int j = tid + T * k;
+    const bool keep = j < n && v[k] > theta;
+    const unsigned long long bal = __ballot(keep);
+    if (keep) {
+      const int pos = nw + lanes_below(bal);
+      wkey[pos] = (uint16_t)j;
+      wval[pos] = v[k];
+    }
+    if (P.idx != nullptr && lane == 0) wcnt[k * kGatherWavesA + wave] = __popcll(bal);
+    nw += __popcll(bal);
+  }
+  if (P.idx != nullptr) {
+    // the index list in ascending order over the whole workgroup: one scan over the (k, wave) counts
+    __syncthreads();
+    if (wave == 0) {
+      int run = 0;
+      for (int base = 0; base < kMaxVPT * kGatherWavesA; base += kWave) {
+        const int c = wcnt[base + lane];
+        int inc = c;
+#pragma unroll
+        for (int o = 1; o < kWave; o <<= 1) {
+          const int t = __shfl_up(inc, o, kWave);
+          if (lane >= o) inc += t;
+        }
+        woff[base + lane] = run + inc - c;
+        run += __shfl(inc, kWave - 1, kWave);
+      }
+    }
+    __syncthreads();
 #pragma unroll
     for (int k = 0; k < kMaxVPT; ++k) {
-      const float d = tid + T * k < n ? v[k] - mean : 0.f;
-      sq += d * d;
-    }
-    const float m2 = block_sum<T>(sq, red);
-    theta = mean + sqrtf(m2 / (float)(n - 1)) * P.z;
-  }
-  const float smax = block_max<T>(vmax, red);
-  // ordered compaction of the kept keys: key j = tid + T * k, so the order is k, then wave, then
-  // lane; one scan over the (k, wave) counts gives every wave its offsets
-  unsigned long long bal[kMaxVPT];
-#pragma unroll
-  for (int k = 0; k < kMaxVPT; ++k) {
-    const int j = tid + T * k;
-    bal[k] = __ballot(j < n && v[k] > theta);
-    if (lane == 0) wcnt[k * kGatherWavesA + wave] = __popcll(bal[k]);
-  }
-  __syncthreads();
-  if (wave == 0) {
-    int run = 0;
-    for (int base = 0; base < kMaxVPT * kGatherWavesA; base += kWave) {
-      const int c = wcnt[base + lane];
-      int inc = c;
-#pragma unroll
-      for (int o = 1; o < kWave; o <<= 1) {
-        const int t = __shfl_up(inc, o, kWave);
-        if (lane >= o) inc += t;
-      }
-      woff[base + lane] = run + inc - c;
-      run += __shfl(inc, kWave - 1, kWave);
-    }
-    if (lane == 0) woff[kMaxVPT * kGatherWavesA] = run;
-  }
-  __syncthreads();
-#pragma unroll
-  for (int k = 0; k < kMaxVPT; ++k) {
-    const int j = tid + T * k;
-    if ((bal[k] >> lane) & 1ull) {
-      const int pos = woff[k * kGatherWavesA + wave] + lanes_below(bal[k]);
-      list[pos] = (uint16_t)j;
-      if (P.idx) P.idx[hg * n + pos] = j;
+      const int j = tid + T * k;
+      const bool keep = j < n && v[k] > theta;
+      const unsigned long long bal = __ballot(keep);
+      if (keep) P.idx[hg * n + woff[k * kGatherWavesA + wave] + lanes_below(bal)] = j;
     }
   }
-  const int running = woff[kMaxVPT * kGatherWavesA];
-  const int count = running;
-  if (tid == 0) {
-    if (P.theta) P.theta[hg] = theta;
-    if (P.count) P.count[hg] = count;
-  }
-  __syncthreads();
+  wave_lds_fence();
 
-  // The kept keys in three steps per chunk of kChunk list positions, so that the exponential
-  // and the softplus are evaluated once per key by one thread each (inside the row loops a wave
-  // would evaluate them for only 64 / LPRV keys per instruction, and they would dominate):
-  //   gate     gd[pos] = k2c[key] . q[r:], 64 / LPR2 keys per wave step
-  //   weights  w[pos] = exp(s - max s) * softplus(gd[pos]); the denominator sums exp(s - max s)
-  //   values   acc += w[pos] * vc[key], 64 / LPRV keys per wave step
-  constexpr int KPG = kWave / LPR2;
   const int r2 = P.d_attn - P.r;
   const WT* k2 = static_cast<const WT*>(P.k2c[h]);
   const WT* vv = static_cast<const WT*>(P.vc[h]);
   const int gsub = lane / LPR2, gch = lane % LPR2;
   const int sub = lane / LPRV, ch = lane % LPRV;
-  float q2[VEC];
-  load_q_vec<VEC>(P.q, P.q_bf16, (int64_t)hg * P.d_attn + P.r + (int64_t)gch * VEC, q2);
   float acc[VEC];
 #pragma unroll
   for (int e = 0; e < VEC; ++e) acc[e] = 0.f;
   float den_mine = 0.f;
-  for (int c0 = 0; c0 < count; c0 += kChunk) {
-    const int cn = min(kChunk, count - c0);  // positions of this chunk
+  if (nw > 0) {  // (uniform in the wave)
+    float q2[VEC];
+    load_q_vec<VEC>(P.q, P.q_bf16, (int64_t)hg * P.d_attn + P.r + (int64_t)gch * VEC, q2);
     {
       constexpr int D = 4;
-      const int gstride = kGatherWavesA * KPG;
       auto gfetch = [&](int p, Vec16<WT>& kr) {
-        const int key = list[c0 + min(p, cn - 1)];
+        const int key = wkey[min(p + gsub, nw - 1)];
         kr = load_vec16<WT>(k2 + (size_t)key * r2 + (size_t)gch * VEC);
       };
       auto guse = [&](int p, const Vec16<WT>& kr) {
@@ -261,67 +318,88 @@ __global__ __launch_bounds__(kGatherWavesA * kWave) void attn_gather_kernel(cons
 #pragma unroll
         for (int e = 0; e < VEC; ++e) gd += kr.get(e) * q2[e];
         gd = group_sum<LPR2>(gd);
-        if (gch == 0 && p < cn) w_sh[p] = gd;
+        if (gch == 0 && p + gsub < nw) {
+          if (lean) {
+            const float e0 = expf(wval[p + gsub] - smax);
+            den_mine += e0;
+            wval[p + gsub] = e0 * softplus_f(gd);
+          } else {
+            wgate[p + gsub] = gd;
+          }
+        }
       };
       Vec16<WT> kr[D];
-      const int p0 = wave * KPG + gsub;
 #pragma unroll
-      for (int d = 0; d < D; ++d) gfetch(p0 + d * gstride, kr[d]);
-      for (int p = p0; p - gsub < cn; p += D * gstride) {  // uniform bound
+      for (int d = 0; d < D; ++d) gfetch(d * KPG, kr[d]);
+      for (int p = 0; p < nw; p += D * KPG) {
 #pragma unroll
         for (int d = 0; d < D; ++d) {
-          guse(p + d * gstride, kr[d]);
-          gfetch(p + (d + D) * gstride, kr[d]);
+          guse(p + d * KPG, kr[d]);
+          gfetch(p + (d + D) * KPG, kr[d]);
         }
       }
     }
-    // the first value rows of the chunk are requested before the weights are formed
+    // the first value rows are requested before the weights are formed (requested together with
+    // the gate rows they delay the gate products: 54 -> 57 us per step)
     constexpr int DV = 4;
-    const int vstride = kGatherWavesA * KPS;
     auto vfetch = [&](int p, Vec16<WT>& vr) {
-      const int key = list[c0 + min(p, cn - 1)];
+      const int key = wkey[min(p + sub, nw - 1)];
       vr = load_vec16<WT>(vv + (size_t)key * P.d_attn + (size_t)ch * VEC);
     };
     Vec16<WT> vr[DV];
-    const int v0 = wave * KPS + sub;
 #pragma unroll
-    for (int d = 0; d < DV; ++d) vfetch(v0 + d * vstride, vr[d]);
-    __syncthreads();
-    for (int p = tid; p < cn; p += T) {
-      const float e0 = expf(s_sh[list[c0 + p]] - smax);
-      den_mine += e0;
-      w_sh[p] = e0 * softplus_f(w_sh[p]);
+    for (int d = 0; d < DV; ++d) vfetch(d * KPS, vr[d]);
+    wave_lds_fence();
+    if (!lean) {
+      for (int p = lane; p < nw; p += kWave) {
+        const float e0 = expf(wval[p] - smax);
+        den_mine += e0;
+        wval[p] = e0 * softplus_f(wgate[p]);
+      }
+      wave_lds_fence();
     }
-    __syncthreads();
-    for (int p = v0; p - sub < cn; p += DV * vstride) {  // uniform bound
+    for (int p = 0; p < nw; p += DV * KPS) {
 #pragma unroll
       for (int d = 0; d < DV; ++d) {
-        const int pp = p + d * vstride;
-        const float w = pp < cn ? w_sh[pp] : 0.f;
+        const int pp = p + d * KPS + sub;
+        const float w = pp < nw ? wval[pp] : 0.f;
 #pragma unroll
         for (int e = 0; e < VEC; ++e) acc[e] += w * vr[d].get(e);
-        vfetch(pp + DV * vstride, vr[d]);
+        vfetch(p + (d + DV) * KPS, vr[d]);
       }
     }
-    __syncthreads();  // w_sh is rewritten by the next chunk
   }
-  const float den_total = block_sum<T>(den_mine, red);
-  // the KPS lane groups of a wave, then the waves in order
+  // the lane groups of a wave, then the waves in order
 #pragma unroll
   for (int o = LPRV; o < kWave; o <<= 1) {
 #pragma unroll
     for (int e = 0; e < VEC; ++e) acc[e] += __shfl_xor(acc[e], o, kWave);
   }
-  __syncthreads();  // s_sh is reused for the waves' rows
+  const float den_wave = wave_total(den_mine);
   if (sub == 0) {
 #pragma unroll
-    for (int e = 0; e < VEC; ++e) s_sh[(size_t)wave * P.d_attn + ch * VEC + e] = acc[e];
+    for (int e = 0; e < VEC; ++e) rows_sh[(size_t)wave * P.d_attn + ch * VEC + e] = acc[e];
+  }
+  if (lane == 0) {
+    red_den[wave] = den_wave;
+    red_cnt[wave] = nw;
   }
   __syncthreads();
+  float den_total = 0.f;
+  int count = 0;
+#pragma unroll
+  for (int w = 0; w < kGatherWavesA; ++w) {
+    den_total += red_den[w];
+    count += red_cnt[w];
+  }
+  if (tid == 0) {
+    if (P.theta) P.theta[hg] = theta;
+    if (P.count) P.count[hg] = count;
+  }
   for (int c = tid; c < P.d_attn; c += T) {
     float num = 0.f;
 #pragma unroll
-    for (int w = 0; w < kGatherWavesA; ++w) num += s_sh[(size_t)w * P.d_attn + c];
+    for (int w = 0; w < kGatherWavesA; ++w) num += rows_sh[(size_t)w * P.d_attn + c];
     P.y[hg * P.d_attn + c] = count > 0 ? num / den_total : 0.f;
   }
 }
@@ -351,14 +429,23 @@ hipError_t launch_predict_t(const AttnParams& P, int lpr, dim3 grid, hipStream_t
   }
 }
 
+// Dynamic LDS of the gather: the waves' rows, and per wave its keys (2 bytes), their scores / weights
+// and, up to kGatherGateCap keys per wave, their gate products.
+size_t gather_lds_bytes(int n_ctx, int d_attn) {
+  const int T = kGatherWavesA * kWave;
+  const size_t cap = (size_t)((n_ctx + T - 1) / T) * kWave;
+  return (size_t)kGatherWavesA * d_attn * 4 + (size_t)kGatherWavesA * cap * ((cap > (size_t)kGatherGateCap ? 4 : 8) + 2);
+}
+constexpr size_t kGatherMaxLds = 150 * 1024;
+
 template <typename WT, int LPR2, int LPRV>
 hipError_t launch_gather_k(const AttnParams& P, dim3 grid, size_t dyn, hipStream_t st) {
   const void* kern = reinterpret_cast<const void*>(attn_gather_kernel<WT, LPR2, LPRV>);
-  // the attribute is set to the most any call may ask for (scores of kAttnMaxCtx keys + their list),
-  // the same value every time, so calls from several threads cannot undercut each other
-  const hipError_t e = hipFuncSetAttribute(kern, hipFuncAttributeMaxDynamicSharedMemorySize, kAttnMaxCtx * 6 + 16);
+  // the attribute is set to the most any call may ask for, the same value every time, so calls from
+  // several threads cannot undercut each other
+  const hipError_t e = hipFuncSetAttribute(kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kGatherMaxLds);
   if (e != hipSuccess) return e;
-  if (dyn > (size_t)kAttnMaxCtx * 6 + 16) return hipErrorInvalidValue;
+  if (dyn > kGatherMaxLds) return hipErrorInvalidValue;
   hipLaunchKernelGGL((attn_gather_kernel<WT, LPR2, LPRV>), grid, dim3(kGatherWavesA * kWave), dyn, st, P);
   return hipGetLastError();
 }
@@ -391,9 +478,15 @@ bool attn_supported(const AttnProblem& p) {
          p.n_ctx >= 1 && p.n_ctx <= kAttnMaxCtx && p.group >= 1 && p.group <= 4;
 }
 
-size_t attn_workspace_bytes(int n_heads, int group, int n_ctx) {
+// scores [heads][group][n_ctx], then the block statistics [heads][group][kStatBlocks][4], for the
+// caches of one pair of launches
+size_t attn_scores_bytes(int n_heads, int group, int n_ctx) {
   const size_t per = ((size_t)group * n_ctx * 4 + 255) / 256 * 256;
   return per * (size_t)(n_heads < kAttnMaxHeads ? n_heads : kAttnMaxHeads);
+}
+size_t attn_workspace_bytes(int n_heads, int group, int n_ctx) {
+  return attn_scores_bytes(n_heads, group, n_ctx) +
+         (size_t)(n_heads < kAttnMaxHeads ? n_heads : kAttnMaxHeads) * group * kStatBlocks * 4 * sizeof(float);
 }
 
 hipError_t launch_attn_decode(const AttnProblem& p, const void* const* k1c, const void* const* k2c,
@@ -416,6 +509,7 @@ hipError_t launch_attn_decode(const AttnProblem& p, const void* const* k1c, cons
     P.count = p.count ? p.count + hg0 : nullptr;
     P.idx = p.idx ? p.idx + hg0 * p.n_ctx : nullptr;
     P.scores = static_cast<float*>(workspace);
+    P.bstats = reinterpret_cast<float*>(static_cast<char*>(workspace) + attn_scores_bytes(n_heads, p.group, p.n_ctx));
     P.n_ctx = p.n_ctx;
     P.d_attn = p.d_attn;
     P.r = p.r;
@@ -427,8 +521,7 @@ hipError_t launch_attn_decode(const AttnProblem& p, const void* const* k1c, cons
     if (p.c_bf16) err = p.q_bf16 ? launch_predict_t<bf16_t, true>(P, l1, gp, st) : launch_predict_t<bf16_t, false>(P, l1, gp, st);
     else err = launch_predict_t<float, false>(P, l1, gp, st);
     if (err != hipSuccess) return err;
-    const size_t rows = (size_t)(p.n_ctx > kGatherWavesA * p.d_attn ? p.n_ctx : kGatherWavesA * p.d_attn);
-    const size_t dyn = rows * 4 + (size_t)p.n_ctx * 2 + 16;
+    const size_t dyn = gather_lds_bytes(p.n_ctx, p.d_attn);
     const dim3 gg(p.group, H);
     err = p.c_bf16 ? launch_gather_t<bf16_t>(P, l2, lv, gg, dyn, st) : launch_gather_t<float>(P, l2, lv, gg, dyn, st);
   }
