@@ -83,6 +83,19 @@ def test_paper_attention_shape(n_ctx):
     assert np.all(np.abs(out["count"] - 256) < 6 * 16)
 
 
+@pytest.mark.parametrize("n_ctx,k", [(16384, 256), (12000, 1500), (8192, 3000), (9000, 9000)])
+def test_longest_contexts_and_many_kept_keys(n_ctx, k):
+    """The longest context the step takes (16384 keys), contexts above 8192 keys (where a wave's gate
+    products no longer have room in LDS and the weights are formed as the products finish), hundreds
+    of kept keys per wave, and a context no longer than k (every key is kept)."""
+    H, group, d_attn, r = 2, 2, 64, 32
+    caches = [synth.attn_caches(n_ctx, d_attn, r, 1300 + h, torch.bfloat16) for h in range(H)]
+    q = synth.attn_queries(H, group, d_attn, 1301 + n_ctx, torch.bfloat16)
+    out = run_gpu_attention(caches, q, k, group)
+    n = check_attention(caches, q, k, out, TOL_BF16_TIGHT, f"n_ctx={n_ctx} k={k}")
+    assert n >= H * group - 1
+
+
 def test_more_caches_than_one_launch_holds_and_mixed_query_dtype():
     H, group, d_attn, r, k, n_ctx = 70, 1, 64, 32, 20, 400
     caches = [synth.attn_caches(n_ctx, d_attn, r, 1000 + h, torch.bfloat16) for h in range(H)]
