@@ -4,6 +4,8 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <type_traits>
+
 namespace spark {
 
 constexpr int kWave = 64;
@@ -162,12 +164,23 @@ __device__ __forceinline__ void load_q_vec(const void* q, int q_is_bf16, int64_t
   }
 }
 
-// Butterfly sum over the 64 lanes of a wavefront; every lane ends with the total, and the
-// order of additions is fixed, so the result is reproducible.
+// Sum over the 64 lanes of a wavefront with lane-crossing moves inside the vector unit (quad
+// swaps, the two row mirrors, the two row broadcasts: no trip through the LDS crossbar); the total
+// comes back as a uniform value, so every lane has it, and the order of additions is fixed, so
+// the result is reproducible.
 __device__ __forceinline__ float wave_sum(float v) {
-#pragma unroll
-  for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, kWave);
-  return v;
+  auto step = [](float x, auto ctrl, auto row_mask) {
+    // lanes outside the row mask receive 0 and keep their value
+    return x + __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(x), decltype(ctrl)::value,
+                                                          decltype(row_mask)::value, 0xf, false));
+  };
+  v = step(v, std::integral_constant<int, 0xB1>{}, std::integral_constant<int, 0xf>{});   // quad_perm [1,0,3,2]
+  v = step(v, std::integral_constant<int, 0x4E>{}, std::integral_constant<int, 0xf>{});   // quad_perm [2,3,0,1]
+  v = step(v, std::integral_constant<int, 0x141>{}, std::integral_constant<int, 0xf>{});  // row_half_mirror
+  v = step(v, std::integral_constant<int, 0x140>{}, std::integral_constant<int, 0xf>{});  // row_mirror
+  v = step(v, std::integral_constant<int, 0x142>{}, std::integral_constant<int, 0xa>{});  // row_bcast:15 into rows 1 and 3
+  v = step(v, std::integral_constant<int, 0x143>{}, std::integral_constant<int, 0xc>{});  // row_bcast:31 into rows 2 and 3
+  return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 63));
 }
 
 __device__ __forceinline__ int wave_sum_int(int v) {
