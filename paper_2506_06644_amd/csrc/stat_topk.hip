@@ -1,11 +1,12 @@
 // Row-wise statistical top-k (Eq.9-11 of arXiv 2506.06644) for gfx950.
 //
-// One workgroup owns one row.  The row is read from HBM once into registers (striped
-// 16-byte vectors, fully coalesced), the mean and the centred sum of squares are reduced
-// with wavefront butterflies plus a small LDS combine, theta = mean + std * Q(1 - k/n) is
-// formed, and the soft-thresholded row is written once.  Active indices are compacted in
-// ascending order with wave ballots and an LDS prefix table.  Rows too long for the
-// register file fall back to a kernel that re-reads the row for each pass.
+// One workgroup owns one row (one wavefront for rows of up to 576 16-byte vectors, 4 or 16
+// wavefronts for longer ones).  The row is read from HBM once into registers (striped 16-byte
+// vectors, fully coalesced), the mean and the centred sum of squares are reduced with wavefront
+// sums plus a small LDS combine, theta = mean + std * Q(1 - k/n) is formed, and the
+// soft-thresholded row is written once.  Active indices are compacted in ascending order with
+// wave ballots and an LDS prefix table.  Rows too long for the register file fall back to a
+// kernel that re-reads the row for each pass.
 #include "spark_device.h"
 #include "spark_internal.h"
 
