@@ -108,6 +108,19 @@ struct Vec16<i8_t> {
   }
 };
 
+// A copy of one held vector of a packed type (bf16 pairs, 8-bit codes) that the compiler has to take
+// as a new value.  A pass over vectors held in registers unpacks from such a copy (one shift, mask or
+// conversion per element, and four moves per vector for the copy): without it the compiler keeps
+// the widened values of one pass alive for the next, or widens vectors long before their turn,
+// which multiplies the registers of a thread and lowers the rows in flight per compute unit.  The
+// copies are made in program order, one vector at a time.
+template <typename V>
+__device__ __forceinline__ V fresh(const V& v) {
+  V t = v;
+  if constexpr (V::N >= 8) asm volatile("" : "+v"(t.raw));
+  return t;
+}
+
 template <typename T>
 __device__ __forceinline__ Vec16<T> load_vec16(const T* p) {
   Vec16<T> v;

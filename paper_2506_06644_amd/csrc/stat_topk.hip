@@ -46,18 +46,6 @@ __device__ __forceinline__ float huber_over_delta(float a, float delta, float in
 // Its derivative in a (Appendix A.2): a / delta below delta, 1 from there on.
 __device__ __forceinline__ float huber_slope(float a, float delta, float inv_delta) { return a < delta ? a * inv_delta : 1.f; }
 
-// A copy of one held vector that the compiler has to take as a new value.  Every pass over a row
-// held in registers unpacks its bf16 pairs from such a copy (one shift or mask per element, and
-// four moves per vector for the copy): without it the compiler keeps the widened values of one pass
-// alive for the next, which triples the registers of a thread and halves the rows in flight
-// per compute unit.  The copies are made in program order, one vector at a time.
-template <typename V>
-__device__ __forceinline__ V fresh(const V& v) {
-  V t = v;
-  if constexpr (V::N == 8) asm volatile("" : "+v"(t.raw));
-  return t;
-}
-
 // The thresholding pass over a row held in registers (Eq.10, or its Huber form of Section 3.2 with
 // HUBER): writes y where asked and returns the thread's number of active entries; with MASKS it also
 // leaves each vector's mask of active entries (for the index list and the flags).  Entries that
