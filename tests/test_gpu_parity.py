@@ -67,6 +67,15 @@ def test_stat_topk_matches_oracle(rows, n, k, dtype):
 
 
 @pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
+@pytest.mark.parametrize("n", [256, 260, 516, 1280, 1288, 2304, 2312, 4608, 4616, 10240, 10248])
+def test_stat_topk_row_lengths_around_the_kernel_tiers(n, dtype):
+    """Row lengths at and just past the sizes where the kernel changes its shape (one wavefront per
+    row with 1, 2, 5 or 9 vectors per lane; 256 threads with 5, 9 or 14), with and without a ragged
+    last vector."""
+    _topk_case(6, n, max(1, n // 12), dtype)
+
+
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
 def test_stat_topk_ragged_pitch_neg_inf_and_optional_outputs(dtype):
     _topk_case(6, 1003, 80, dtype, fill=binding.FILL_NEG_INF, ld=1016)
     _topk_case(6, 9216, 737, dtype, with_idx=False)
